@@ -1,0 +1,187 @@
+/*
+ * kvcar.h - C ABI of libkvcar: the decode-time hot path of KV-CAR on one MI355X (gfx950).
+ *
+ * KV-CAR (arxiv 2512.06727) stores, per transformer layer, an autoencoder *latent* of every
+ * token's key vector and value vector instead of the vectors themselves, and lets selected heads
+ * of a layer take the previous layer's keys/values instead of storing their own.  This library
+ * implements the two operations a decode step needs per layer:
+ *
+ *   kvcar_encode_append     encoder after K/V generation + append of one latent row per token to
+ *                           the layer's latent KV cache   (Methodology, "Network Architecture",
+ *                           first paragraph)
+ *   kvcar_decode_attention  decoder applied to every cached latent row at retrieval, followed by
+ *                           scaled-dot-product attention per head   ("Network Architecture",
+ *                           second paragraph; Background, Eq. 1), with inter-layer head reuse
+ *                           ("Network Architecture", third paragraph) resolved while addressing
+ *   kvcar_set_reuse_map     the per-layer boolean map of reused K heads and V heads
+ *
+ * Conventions
+ *   - Pure C.  Every function returns a kvcar_status (0 = OK, negative = error); nothing throws.
+ *   - "dev" pointers are device (HBM) addresses owned by the caller (e.g. PyTorch tensors); they
+ *     must be 16-byte aligned and stay valid until the work enqueued on `stream` has finished.
+ *     "host" pointers are read during the call and not retained.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  No call
+ *     synchronises the device or allocates device memory; kernels are only enqueued.
+ *   - Elements (activations, weights, cache, output) share one dtype; accumulation is fp32.
+ *   - Weight matrices are row-major [in_features, out_features]; biases may be NULL.
+ *   - The library owns only its host-side context.  The context holds no sequence positions:
+ *     positions are explicit arguments, so calls can be replayed.
+ *   - All sequences of a batch have the same length (uniform batch).
+ *   - Layers are 0-indexed.  KVCAR_K = keys, KVCAR_V = values.
+ *
+ * Latent cache layout (library-defined, caller-allocated): for layer N and tensor `which`
+ *   Z[b][t][c],  b < max_batch, t < max_seq, c < r   row-major, r = latent_width of that
+ *   layer-tensor; one row is r * sizeof(dtype) bytes; kvcar_cache_bytes gives the total.
+ */
+#ifndef KVCAR_H
+#define KVCAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kvcar_ctx kvcar_ctx;
+
+typedef enum {
+    KVCAR_OK = 0,
+    KVCAR_ERR_ARG = -1,          /* null / misaligned pointer, index out of range          */
+    KVCAR_ERR_SHAPE = -2,        /* widths inconsistent with the model or the reuse map    */
+    KVCAR_ERR_CAPACITY = -3,     /* batch, position or context beyond max_batch / max_seq  */
+    KVCAR_ERR_REUSE = -4,        /* layer 0 asked to reuse; source layer lacks the head    */
+    KVCAR_ERR_UNSUPPORTED = -5,  /* no kernel for this dtype / width combination           */
+    KVCAR_ERR_STATE = -6,        /* autoencoder or cache of a needed layer not set / bound */
+    KVCAR_ERR_HIP = -7,          /* a HIP runtime call failed                               */
+    KVCAR_ERR_WORKSPACE = -8     /* workspace too small                                     */
+} kvcar_status;
+
+typedef enum { KVCAR_F32 = 0, KVCAR_F16 = 1, KVCAR_BF16 = 2 } kvcar_dtype;
+
+/* Activation between the two fully connected layers of an encoder / decoder.  NONE = the
+ * autoencoder is a single linear map each way. */
+typedef enum { KVCAR_ACT_NONE = 0, KVCAR_ACT_LEAKY_RELU = 1, KVCAR_ACT_GELU = 2 /* erf form */ } kvcar_act;
+
+enum { KVCAR_K = 0, KVCAR_V = 1 };
+
+/* Model shape.  D_kv = n_kv_heads * d_head is the width of one token's key (or value) vector. */
+typedef struct {
+    int n_layers;
+    int n_q_heads;      /* H_q; must be a multiple of n_kv_heads (grouped-query attention)   */
+    int n_kv_heads;     /* H_kv                                                               */
+    int d_head;
+    int max_batch;
+    int max_seq;        /* capacity of every latent cache, in tokens                          */
+    int dtype;          /* kvcar_dtype                                                        */
+    float softmax_scale; /* 0 => 1/sqrt(d_head), the scaling of Eq. 1                         */
+} kvcar_config;
+
+/*
+ * Autoencoder of one layer for K or for V ("Network Architecture": encoder D -> d placed after
+ * K/V generation, mirrored decoder d -> D applied at retrieval; two fully connected layers with
+ * an activation in between, or a single linear map when hidden_width == 0.  A batch-norm between
+ * the layers is folded into w1/b1 by the caller).
+ *
+ *   in_width      width of the encoder input / decoder output.  Either D_kv (the autoencoder
+ *                 covers every head; columns of reused heads are ignored on decode), or
+ *                 n_stored * d_head where the stored heads are the layer's non-reused heads in
+ *                 increasing order (the autoencoder covers only what the layer stores).
+ *   latent_width  r, the row width of this layer-tensor's cache.  0 is allowed only when
+ *                 in_width == 0 (a layer that stores nothing for this tensor).
+ *   enc_w1 [in_width, hidden or latent], enc_b1; enc_w2 [hidden, latent], enc_b2 (hidden > 0)
+ *   dec_w1 [latent, hidden or in_width], dec_b1; dec_w2 [hidden, in_width], dec_b2 (hidden > 0)
+ *   All weight pointers are dev pointers that must outlive every call using the context.
+ */
+typedef struct {
+    int in_width;
+    int hidden_width;
+    int latent_width;
+    int act;            /* kvcar_act; must be NONE iff hidden_width == 0 */
+    float leaky_slope;
+    const void *enc_w1, *enc_b1, *enc_w2, *enc_b2;
+    const void *dec_w1, *dec_b1, *dec_w2, *dec_b2;
+} kvcar_ae_desc;
+
+/* Launch tuning; all zero = library defaults. */
+typedef struct {
+    int n_splits;       /* token-range splits per sequence in decode_attention; 0 = automatic */
+    int force_generic;  /* 1 = use the plain-ALU kernels even where an MFMA kernel exists     */
+    int reserved[6];
+} kvcar_tuning;
+
+/* Create / destroy a context.  ERR_ARG on null pointers, ERR_SHAPE on non-positive sizes or
+ * n_q_heads % n_kv_heads != 0, ERR_UNSUPPORTED on an unknown dtype. */
+int kvcar_create(const kvcar_config *cfg, kvcar_ctx **out);
+int kvcar_destroy(kvcar_ctx *ctx);
+
+/*
+ * Inter-layer head reuse ("Network Architecture", third paragraph): k_reuse[g] != 0 means KV head g
+ * of `layer` takes the keys of head g of the previous layer instead of storing its own; v_reuse
+ * likewise for values.  Both are host arrays of n_kv_heads bytes.  "The previous layer's" tensor
+ * is whatever that layer itself uses, so chains resolve to the nearest earlier layer whose bit is
+ * clear.  Layer 0 cannot reuse: ERR_REUSE.  Changing a layer's map invalidates the autoencoders
+ * set for that layer (set them again).  Default: nothing reused.
+ */
+int kvcar_set_reuse_map(kvcar_ctx *ctx, int layer, const uint8_t *k_reuse, const uint8_t *v_reuse);
+
+/* Layer that supplies head `kv_head` of `layer` for tensor `which` under the current maps. */
+int kvcar_resolve_source(const kvcar_ctx *ctx, int layer, int which, int kv_head, int *src_layer);
+
+/* Set the autoencoder of (layer, which).  ERR_SHAPE if in_width matches neither form above or
+ * widths are inconsistent; ERR_ARG on null / misaligned required pointers. */
+int kvcar_set_autoencoder(kvcar_ctx *ctx, int layer, int which, const kvcar_ae_desc *desc);
+
+/* Bytes of the latent cache of (layer, which): max_batch * max_seq * latent_width * sizeof(dtype)
+ * (Eq. 3 with d_model replaced by what the layer-tensor stores).  Needs the autoencoder set. */
+int kvcar_cache_bytes(const kvcar_ctx *ctx, int layer, int which, size_t *bytes);
+
+/* Bind caller-allocated device memory as the cache of (layer, which).  ERR_CAPACITY if `bytes`
+ * is smaller than kvcar_cache_bytes.  A zero-width cache needs no binding. */
+int kvcar_bind_cache(kvcar_ctx *ctx, int layer, int which, void *dev, size_t bytes);
+
+int kvcar_set_tuning(kvcar_ctx *ctx, const kvcar_tuning *tuning);
+
+/* Workspace (device bytes) that kvcar_decode_attention needs for `batch` sequences of `n_ctx`
+ * cached tokens, maximised over layers under the current maps, autoencoders and tuning. */
+int kvcar_workspace_bytes(const kvcar_ctx *ctx, int batch, int n_ctx, size_t *bytes);
+
+/*
+ * Encode the new tokens' key and value vectors and append the latent rows to the layer's caches.
+ *   k_new, v_new  dev [batch, t_new, D_kv] row-major (full-width vectors; only the columns the
+ *                 layer's autoencoder covers are read)
+ *   rows are written at positions [pos0, pos0 + t_new) of sequences 0..batch-1, rounded once
+ *   (nearest-even) from the fp32 result to the cache dtype.  Other rows are not touched.
+ * ERR_CAPACITY if batch > max_batch or pos0 + t_new > max_seq; ERR_STATE if an autoencoder or a
+ * non-empty cache of this layer is not set / bound.
+ */
+int kvcar_encode_append(kvcar_ctx *ctx, int layer, const void *k_new, const void *v_new,
+                        int batch, int pos0, int t_new, void *stream);
+
+/*
+ * One decode step of attention for `layer` over cached tokens 0..n_ctx-1 of every sequence:
+ * for each query head j (KV head g = j / (H_q/H_kv)), K^_g[t] and V^_g[t] are the decoder outputs
+ * of the latent rows of the layer that supplies head g (reuse map), and
+ *   out[b, j, :] = sum_t softmax_t(scale * q[b,j,:] . K^_g[t]) V^_g[t]            (Eq. 1)
+ *   q    dev [batch, H_q, d_head]      out  dev [batch, H_q, d_head] (rounded once to dtype)
+ * The decoded K^/V^ are never written to memory; with a linear last decoder layer that layer is
+ * applied to the query and to the weighted latent sum instead of to every row (same result up to
+ * rounding order).  `workspace` is dev scratch of at least kvcar_workspace_bytes(batch, n_ctx).
+ * ERR_CAPACITY if batch > max_batch or n_ctx > max_seq or n_ctx < 1; ERR_STATE if a source
+ * layer's autoencoder / cache is missing; ERR_REUSE if a source layer's autoencoder does not
+ * cover a head taken from it; ERR_WORKSPACE if workspace_bytes is too small.
+ */
+int kvcar_decode_attention(kvcar_ctx *ctx, int layer, const void *q, void *out,
+                           int batch, int n_ctx, void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/* Human-readable name of a status code (static string). */
+const char *kvcar_status_string(int status);
+
+/* Text of the last error recorded in this context (valid until the next call on it). */
+const char *kvcar_last_error(const kvcar_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVCAR_H */

@@ -1,0 +1,171 @@
+"""ctypes binding over libkvcar.so (C ABI in include/kvcar.h).
+
+Argument marshalling only: every step of the path runs inside the library's HIP
+kernels.  PyTorch supplies device memory and the stream.  A missing library is an
+error; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libkvcar.so")
+
+OK = 0
+ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_REUSE, ERR_UNSUPPORTED, ERR_STATE, ERR_HIP, ERR_WORKSPACE = range(-1, -9, -1)
+F32, F16, BF16 = 0, 1, 2
+ACT_NONE, ACT_LEAKY_RELU, ACT_GELU = 0, 1, 2
+K, V = 0, 1
+
+DTYPES = {"f32": F32, "f16": F16, "bf16": BF16}
+ACTS = {"none": ACT_NONE, "leaky_relu": ACT_LEAKY_RELU, "gelu": ACT_GELU}
+
+
+class Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("d_head", C.c_int),
+                ("max_batch", C.c_int), ("max_seq", C.c_int), ("dtype", C.c_int), ("softmax_scale", C.c_float)]
+
+
+class AEDesc(C.Structure):
+    _fields_ = [("in_width", C.c_int), ("hidden_width", C.c_int), ("latent_width", C.c_int), ("act", C.c_int),
+                ("leaky_slope", C.c_float),
+                ("enc_w1", C.c_void_p), ("enc_b1", C.c_void_p), ("enc_w2", C.c_void_p), ("enc_b2", C.c_void_p),
+                ("dec_w1", C.c_void_p), ("dec_b1", C.c_void_p), ("dec_w2", C.c_void_p), ("dec_b2", C.c_void_p)]
+
+
+class Tuning(C.Structure):
+    _fields_ = [("n_splits", C.c_int), ("force_generic", C.c_int), ("reserved", C.c_int * 6)]
+
+
+# every symbol include/kvcar.h declares: name -> (restype, argtypes)
+SYMBOLS = {
+    "kvcar_create": (C.c_int, [C.POINTER(Config), C.POINTER(C.c_void_p)]),
+    "kvcar_destroy": (C.c_int, [C.c_void_p]),
+    "kvcar_set_reuse_map": (C.c_int, [C.c_void_p, C.c_int, C.c_char_p, C.c_char_p]),
+    "kvcar_resolve_source": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int)]),
+    "kvcar_set_autoencoder": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(AEDesc)]),
+    "kvcar_cache_bytes": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]),
+    "kvcar_bind_cache": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t]),
+    "kvcar_set_tuning": (C.c_int, [C.c_void_p, C.POINTER(Tuning)]),
+    "kvcar_workspace_bytes": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]),
+    "kvcar_encode_append": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "kvcar_decode_attention": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
+                                         C.c_size_t, C.c_void_p]),
+    "kvcar_status_string": (C.c_char_p, [C.c_int]),
+    "kvcar_last_error": (C.c_char_p, [C.c_void_p]),
+}
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    """Open libkvcar.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_06727_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(l, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = l
+    return _lib
+
+
+class KVCARError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{lib().kvcar_status_string(status).decode()}: {text}")
+        self.status = status
+
+
+def _ptr(t) -> Optional[int]:
+    """Raw address of a tensor (None -> NULL)."""
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream() -> C.c_void_p:
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Context:
+    """Thin owner of a kvcar_ctx.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, n_layers: int, n_q_heads: int, n_kv_heads: int, d_head: int, max_batch: int, max_seq: int,
+                 dtype: str, softmax_scale: float = 0.0):
+        self._h = C.c_void_p()
+        cfg = Config(n_layers, n_q_heads, n_kv_heads, d_head, max_batch, max_seq, DTYPES[dtype], softmax_scale)
+        st = lib().kvcar_create(C.byref(cfg), C.byref(self._h))
+        if st != OK:
+            raise KVCARError(st, "kvcar_create")
+        self.cfg = cfg
+        self._keep = []          # tensors whose memory the context points at
+
+    def close(self):
+        if self._h:
+            lib().kvcar_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != OK:
+            raise KVCARError(st, lib().kvcar_last_error(self._h).decode())
+
+    def set_reuse_map(self, layer: int, k_reuse: Sequence[bool], v_reuse: Sequence[bool]):
+        kb = bytes(1 if x else 0 for x in k_reuse)
+        vb = bytes(1 if x else 0 for x in v_reuse)
+        self._check(lib().kvcar_set_reuse_map(self._h, layer, kb, vb))
+
+    def resolve_source(self, layer: int, which: int, kv_head: int) -> int:
+        out = C.c_int(-1)
+        self._check(lib().kvcar_resolve_source(self._h, layer, which, kv_head, C.byref(out)))
+        return out.value
+
+    def set_autoencoder(self, layer: int, which: int, in_width: int, hidden_width: int, latent_width: int, act: str,
+                        enc, dec, leaky_slope: float = 0.01):
+        """enc / dec: lists of (weight tensor, bias tensor or None) on the device."""
+        d = AEDesc()
+        d.in_width, d.hidden_width, d.latent_width, d.act, d.leaky_slope = in_width, hidden_width, latent_width, ACTS[act], leaky_slope
+        names = [("enc_w1", "enc_b1"), ("enc_w2", "enc_b2")]
+        for (wn, bn), (w, b) in zip(names, enc):
+            setattr(d, wn, _ptr(w)); setattr(d, bn, _ptr(b))
+        names = [("dec_w1", "dec_b1"), ("dec_w2", "dec_b2")]
+        for (wn, bn), (w, b) in zip(names, dec):
+            setattr(d, wn, _ptr(w)); setattr(d, bn, _ptr(b))
+        self._keep.append((enc, dec))
+        self._check(lib().kvcar_set_autoencoder(self._h, layer, which, C.byref(d)))
+
+    def cache_bytes(self, layer: int, which: int) -> int:
+        n = C.c_size_t(0)
+        self._check(lib().kvcar_cache_bytes(self._h, layer, which, C.byref(n)))
+        return n.value
+
+    def bind_cache(self, layer: int, which: int, tensor):
+        self._keep.append(tensor)
+        nbytes = 0 if tensor is None else tensor.numel() * tensor.element_size()
+        self._check(lib().kvcar_bind_cache(self._h, layer, which, _ptr(tensor), nbytes))
+
+    def set_tuning(self, n_splits: int = 0, force_generic: bool = False):
+        t = Tuning(n_splits, 1 if force_generic else 0)
+        self._check(lib().kvcar_set_tuning(self._h, C.byref(t)))
+
+    def workspace_bytes(self, batch: int, n_ctx: int) -> int:
+        n = C.c_size_t(0)
+        self._check(lib().kvcar_workspace_bytes(self._h, batch, n_ctx, C.byref(n)))
+        return n.value
+
+    def encode_append(self, layer: int, k_new, v_new, batch: int, pos0: int, t_new: int):
+        self._check(lib().kvcar_encode_append(self._h, layer, _ptr(k_new), _ptr(v_new), batch, pos0, t_new, _stream()))
+
+    def decode_attention(self, layer: int, q, out, batch: int, n_ctx: int, workspace):
+        nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self._check(lib().kvcar_decode_attention(self._h, layer, _ptr(q), _ptr(out), batch, n_ctx, _ptr(workspace),
+                                                 nbytes, _stream()))

@@ -1,0 +1,53 @@
+// Device-side helpers: element types, conversions, activations (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvcar_internal.hpp"
+
+namespace kvcar {
+
+struct F32 { using type = float; };
+struct F16 { using type = _Float16; };
+struct BF16 { using type = uint16_t; };   // raw bf16 bits
+
+template <typename E> struct Elem;
+
+template <> struct Elem<F32> {
+    using T = float;
+    static __device__ __forceinline__ float load(const void* p, size_t i) { return static_cast<const float*>(p)[i]; }
+    static __device__ __forceinline__ void store(void* p, size_t i, float v) { static_cast<float*>(p)[i] = v; }
+};
+
+template <> struct Elem<F16> {
+    using T = _Float16;
+    static __device__ __forceinline__ float load(const void* p, size_t i) { return (float)static_cast<const _Float16*>(p)[i]; }
+    // fp32 -> fp16 conversion rounds to nearest even
+    static __device__ __forceinline__ void store(void* p, size_t i, float v) { static_cast<_Float16*>(p)[i] = (_Float16)v; }
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// fp32 -> bf16, round to nearest even (NaN kept quiet).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <> struct Elem<BF16> {
+    using T = uint16_t;
+    static __device__ __forceinline__ float load(const void* p, size_t i) { return bf16_bits_to_f32(static_cast<const uint16_t*>(p)[i]); }
+    static __device__ __forceinline__ void store(void* p, size_t i, float v) { static_cast<uint16_t*>(p)[i] = f32_to_bf16_bits(v); }
+};
+
+// Activation between the two fully connected layers of an encoder / decoder.
+__device__ __forceinline__ float apply_act(float x, int act, float slope) {
+    if (act == KVCAR_ACT_LEAKY_RELU) return x >= 0.f ? x : slope * x;
+    if (act == KVCAR_ACT_GELU) return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
+    return x;
+}
+
+}  // namespace kvcar

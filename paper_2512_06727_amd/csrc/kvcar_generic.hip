@@ -1,0 +1,311 @@
+// Plain-ALU kernels of libkvcar: encode+append, absorbed-query prologue, attention over the latent
+// cache (any dtype, linear or two-layer decoders), split merge + last-decoder-layer epilogue.
+// They are the only kernels for fp32 and for shapes the MFMA kernels do not cover.
+//
+// Decoder handling ("Network Architecture": the decoder expands every cached row at every step):
+// the decoder's last layer is linear, x^ = h W + b, so for a query head with columns C of KV head g
+//   q . x^[C]            = (W[:,C] q) . h + const      -> the constant cancels in the softmax
+//   sum_t p_t x^_t[C]    = (sum_t p_t h_t) W[:,C] + b[C]
+// where h is the latent row itself (linear decoder) or act(z W1 + b1) (two-layer decoder).  The
+// kernels therefore attend over rows h_t and apply W once per head before and after.
+#include "kvcar_device.hpp"
+
+namespace kvcar {
+
+// ---------------------------------------------------------------------------------------------
+// encode + append:  z = x[cols] W1 + b1            (linear encoder)
+//                   z = act(x[cols] W1 + b1) W2 + b2 (two fully connected layers)
+// One workgroup handles kTok tokens of one tensor (K or V).
+// ---------------------------------------------------------------------------------------------
+constexpr int kEncTok = 8;
+
+template <typename E>
+__global__ __launch_bounds__(256) void encode_generic_kernel(EncodeParams p) {
+    extern __shared__ float smem[];
+    const EncodeSide& s = p.s[blockIdx.y];
+    if (s.r == 0) return;
+    const int n_tok = p.batch * p.t_new;
+    const int tok0 = blockIdx.x * kEncTok;
+    const int nt = min(kEncTok, n_tok - tok0);
+    float* xs = smem;                              // [kEncTok][in_width]
+    float* hs = smem + kEncTok * s.in_width;       // [kEncTok][hidden]
+    const int tid = threadIdx.x;
+
+    for (int i = tid; i < nt * s.in_width; i += 256) {
+        const int t = i / s.in_width, c = i % s.in_width;
+        const int src_col = (int)s.heads[c / p.d_head] * p.d_head + c % p.d_head;
+        xs[t * s.in_width + c] = Elem<E>::load(s.x, (size_t)(tok0 + t) * p.d_kv + src_col);
+    }
+    __syncthreads();
+
+    const float* in = xs;
+    int in_w = s.in_width;
+    if (s.hidden > 0) {
+        for (int i = tid; i < nt * s.hidden; i += 256) {
+            const int t = i / s.hidden, c = i % s.hidden;
+            float a = s.b1 ? Elem<E>::load(s.b1, c) : 0.f;
+            for (int k = 0; k < s.in_width; ++k) a = fmaf(xs[t * s.in_width + k], Elem<E>::load(s.w1, (size_t)k * s.hidden + c), a);
+            hs[t * s.hidden + c] = apply_act(a, s.act, s.slope);
+        }
+        __syncthreads();
+        in = hs;
+        in_w = s.hidden;
+    }
+    const void* w = s.hidden > 0 ? s.w2 : s.w1;
+    const void* bias = s.hidden > 0 ? s.b2 : s.b1;
+    for (int i = tid; i < nt * s.r; i += 256) {
+        const int t = i / s.r, c = i % s.r;
+        float a = bias ? Elem<E>::load(bias, c) : 0.f;
+        for (int k = 0; k < in_w; ++k) a = fmaf(in[t * in_w + k], Elem<E>::load(w, (size_t)k * s.r + c), a);
+        const int tok = tok0 + t;
+        const int b = tok / p.t_new, tt = tok % p.t_new;
+        Elem<E>::store(s.z, ((size_t)b * p.max_seq + p.pos0 + tt) * s.r + c, a);
+    }
+}
+
+hipError_t launch_encode_generic(const EncodeParams& p, int dtype, hipStream_t stream) {
+    const int n_tok = p.batch * p.t_new;
+    dim3 grid((n_tok + kEncTok - 1) / kEncTok, 2);
+    size_t lds = 0;
+    for (int i = 0; i < 2; ++i) {
+        size_t need = (size_t)kEncTok * (p.s[i].in_width + p.s[i].hidden) * sizeof(float);
+        lds = need > lds ? need : lds;
+    }
+    if (dtype == KVCAR_F32) hipLaunchKernelGGL(encode_generic_kernel<F32>, grid, dim3(256), lds, stream, p);
+    else if (dtype == KVCAR_F16) hipLaunchKernelGGL(encode_generic_kernel<F16>, grid, dim3(256), lds, stream, p);
+    else hipLaunchKernelGGL(encode_generic_kernel<BF16>, grid, dim3(256), lds, stream, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// absorbed queries:  qt[b][group][slot][c] = scale*log2(e) * sum_k Wl_K[c, col(slot)+k] q[b, head(slot), k]
+// stored as fp32 (plain-ALU attention) or in the 16-bit dtype (MFMA attention).  Padding slots = 0.
+// ---------------------------------------------------------------------------------------------
+template <typename E, bool kF32Out>
+__global__ __launch_bounds__(256) void qtilde_kernel(AttendParams p) {
+    extern __shared__ float smem[];
+    const GroupDesc& g = p.g[blockIdx.y];
+    const int b = blockIdx.x;
+    const int dh = p.d_head;
+    float* qs = smem;                                   // [n_slots][d_head]
+    for (int i = threadIdx.x; i < g.n_slots * dh; i += 256) {
+        const int s = i / dh, k = i % dh;
+        qs[i] = Elem<E>::load(p.q, ((size_t)b * p.n_q_heads + g.q_head[s]) * dh + k);
+    }
+    __syncthreads();
+    const int c_w = g.k.c;
+    const size_t base = (size_t)b * p.qt_stride + g.qt_off;
+    for (int i = threadIdx.x; i < g.slots_pad * c_w; i += 256) {
+        const int s = i / c_w, c = i % c_w;
+        float a = 0.f;
+        if (s < g.n_slots) {
+            const size_t wrow = (size_t)c * g.k.in_width + g.k_col[s];
+            for (int k = 0; k < dh; ++k) a = fmaf(Elem<E>::load(g.k.wl, wrow + k), qs[s * dh + k], a);
+            a *= p.scale_log2e;
+        }
+        if (kF32Out) static_cast<float*>(p.qt)[base + i] = a;
+        else Elem<E>::store(p.qt, base + i, a);
+    }
+}
+
+hipError_t launch_qtilde(const AttendParams& p, int dtype, bool qt_f32, hipStream_t stream) {
+    dim3 grid(p.batch, p.n_groups);
+    size_t lds = (size_t)kMaxSlots * p.d_head * sizeof(float);
+    if (dtype == KVCAR_F32) hipLaunchKernelGGL((qtilde_kernel<F32, true>), grid, dim3(256), lds, stream, p);
+    else if (dtype == KVCAR_F16) {
+        if (qt_f32) hipLaunchKernelGGL((qtilde_kernel<F16, true>), grid, dim3(256), lds, stream, p);
+        else hipLaunchKernelGGL((qtilde_kernel<F16, false>), grid, dim3(256), lds, stream, p);
+    } else {
+        if (qt_f32) hipLaunchKernelGGL((qtilde_kernel<BF16, true>), grid, dim3(256), lds, stream, p);
+        else hipLaunchKernelGGL((qtilde_kernel<BF16, false>), grid, dim3(256), lds, stream, p);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// plain-ALU attention over rows h_t, one workgroup per (split, sequence, group).
+// Partial written per (b, split, group): for each slot  [m, l, o[0..cv)]  with scores in log2 units.
+// ---------------------------------------------------------------------------------------------
+template <typename E>
+__device__ void load_rows(const SideDesc& sd, float* rows, float* zrow, int b, int t0, int nt, int max_seq) {
+    // rows [kGenericTile][c+1]; rows of tokens >= nt are zero
+    const int tid = threadIdx.x;
+    const int ld = sd.c + 1;
+    if (sd.w1 == nullptr) {
+        for (int i = tid; i < kGenericTile * sd.c; i += 256) {
+            const int t = i / sd.c, c = i % sd.c;
+            rows[t * ld + c] = t < nt ? Elem<E>::load(sd.z, ((size_t)b * max_seq + t0 + t) * sd.r + c) : 0.f;
+        }
+        return;
+    }
+    for (int i = tid; i < kGenericTile * sd.r; i += 256) {
+        const int t = i / sd.r, c = i % sd.r;
+        zrow[i] = t < nt ? Elem<E>::load(sd.z, ((size_t)b * max_seq + t0 + t) * sd.r + c) : 0.f;
+    }
+    __syncthreads();
+    for (int i = tid; i < kGenericTile * sd.c; i += 256) {
+        const int t = i / sd.c, c = i % sd.c;
+        float a = sd.b1 ? Elem<E>::load(sd.b1, c) : 0.f;
+        for (int k = 0; k < sd.r; ++k) a = fmaf(zrow[t * sd.r + k], Elem<E>::load(sd.w1, (size_t)k * sd.c + c), a);
+        rows[t * ld + c] = t < nt ? apply_act(a, sd.act, sd.slope) : 0.f;
+    }
+    __syncthreads();   // zrow is reused by the next call
+}
+
+size_t attend_generic_lds_bytes(const GroupDesc& g) {
+    size_t zr = 0;
+    if (g.k.w1) zr = g.k.r;
+    if (g.v.w1 && (size_t)g.v.r > zr) zr = g.v.r;
+    size_t f = (size_t)g.n_slots * g.k.c + (size_t)kGenericTile * (g.k.c + 1) + (size_t)kGenericTile * (g.v.c + 1) +
+               (size_t)kGenericTile * zr + (size_t)g.n_slots * kGenericTile + 3 * (size_t)g.n_slots;
+    return f * sizeof(float);
+}
+
+template <typename E>
+__global__ __launch_bounds__(256) void attend_generic_kernel(AttendParams p) {
+    extern __shared__ float smem[];
+    const GroupDesc& g = p.g[blockIdx.z];
+    const int split = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int ns = g.n_slots, ck = g.k.c, cv = g.v.c;
+    int zr = 0;
+    if (g.k.w1) zr = g.k.r;
+    if (g.v.w1 && g.v.r > zr) zr = g.v.r;
+
+    float* qt = smem;                                   // [ns][ck]
+    float* rk = qt + ns * ck;                           // [tile][ck+1]
+    float* rv = rk + kGenericTile * (ck + 1);           // [tile][cv+1]
+    float* zrow = rv + kGenericTile * (cv + 1);         // [tile][zr]
+    float* sc = zrow + kGenericTile * zr;               // [ns][tile]
+    float* m_s = sc + ns * kGenericTile;                // [ns]
+    float* l_s = m_s + ns;
+    float* a_s = l_s + ns;
+
+    const float* qsrc = static_cast<const float*>(p.qt) + (size_t)b * p.qt_stride + g.qt_off;
+    for (int i = tid; i < ns * ck; i += 256) qt[i] = qsrc[i];
+    if (tid < ns) { m_s[tid] = -INFINITY; l_s[tid] = 0.f; }
+
+    float acc[kGenericAcc];
+#pragma unroll
+    for (int i = 0; i < kGenericAcc; ++i) acc[i] = 0.f;
+    const int n_out = ns * cv;
+
+    // contiguous token range of this split, in whole tiles
+    const int tiles = (p.n_ctx + kGenericTile - 1) / kGenericTile;
+    const int tiles_per = (tiles + p.n_splits - 1) / p.n_splits;
+    const int tile0 = split * tiles_per;
+    const int tile1 = min(tiles, tile0 + tiles_per);
+    __syncthreads();
+
+    for (int tile = tile0; tile < tile1; ++tile) {
+        const int t0 = tile * kGenericTile;
+        const int nt = min(kGenericTile, p.n_ctx - t0);
+        load_rows<E>(g.k, rk, zrow, b, t0, nt, p.max_seq);
+        load_rows<E>(g.v, rv, zrow, b, t0, nt, p.max_seq);
+        __syncthreads();
+        for (int i = tid; i < ns * kGenericTile; i += 256) {
+            const int s = i / kGenericTile, t = i % kGenericTile;
+            float a = 0.f;
+            for (int c = 0; c < ck; ++c) a = fmaf(qt[s * ck + c], rk[t * (ck + 1) + c], a);
+            sc[i] = t < nt ? a : -INFINITY;
+        }
+        __syncthreads();
+        if (tid < ns) {
+            float mx = m_s[tid];
+            for (int t = 0; t < kGenericTile; ++t) mx = fmaxf(mx, sc[tid * kGenericTile + t]);
+            const float alpha = exp2f(m_s[tid] - mx);     // m = -inf on the first tile gives 0
+            float sum = 0.f;
+            for (int t = 0; t < kGenericTile; ++t) {
+                const float e = exp2f(sc[tid * kGenericTile + t] - mx);
+                sc[tid * kGenericTile + t] = e;
+                sum += e;
+            }
+            l_s[tid] = l_s[tid] * alpha + sum;
+            m_s[tid] = mx;
+            a_s[tid] = alpha;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kGenericAcc; ++i) {
+            const int o = tid + i * 256;
+            if (o < n_out) {
+                const int s = o / cv, c = o % cv;
+                float a = acc[i] * a_s[s];
+                for (int t = 0; t < kGenericTile; ++t) a = fmaf(sc[s * kGenericTile + t], rv[t * (cv + 1) + c], a);
+                acc[i] = a;
+            }
+        }
+        __syncthreads();
+    }
+
+    float* part = p.part + ((size_t)b * p.n_splits + split) * p.part_stride + g.part_off;
+    if (tid < ns) { part[tid * (cv + 2)] = m_s[tid]; part[tid * (cv + 2) + 1] = l_s[tid]; }
+#pragma unroll
+    for (int i = 0; i < kGenericAcc; ++i) {
+        const int o = tid + i * 256;
+        if (o < n_out) { const int s = o / cv, c = o % cv; part[s * (cv + 2) + 2 + c] = acc[i]; }
+    }
+}
+
+hipError_t launch_attend_generic(const AttendParams& p, int dtype, hipStream_t stream) {
+    size_t lds = 0;
+    for (int i = 0; i < p.n_groups; ++i) { size_t n = attend_generic_lds_bytes(p.g[i]); lds = n > lds ? n : lds; }
+    dim3 grid(p.n_splits, p.batch, p.n_groups);
+    if (dtype == KVCAR_F32) hipLaunchKernelGGL(attend_generic_kernel<F32>, grid, dim3(256), lds, stream, p);
+    else if (dtype == KVCAR_F16) hipLaunchKernelGGL(attend_generic_kernel<F16>, grid, dim3(256), lds, stream, p);
+    else hipLaunchKernelGGL(attend_generic_kernel<BF16>, grid, dim3(256), lds, stream, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// split merge + epilogue: one workgroup per (sequence, group, slot)
+//   M = max_i m_i,  L = sum_i l_i 2^(m_i-M),  o_lat = sum_i o_i 2^(m_i-M) / L
+//   out[b, head, k] = sum_c o_lat[c] Wl_V[c, col+k] + bl_V[col+k]   rounded once to dtype
+// ---------------------------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(64) void combine_kernel(AttendParams p) {
+    __shared__ float olat[kMaxRow];
+    __shared__ float wsplit[64];
+    const GroupDesc& g = p.g[blockIdx.z];
+    const int b = blockIdx.x, s = blockIdx.y;
+    if (s >= g.n_slots) return;
+    const int cv = g.v.c;
+    const int tid = threadIdx.x;
+    const float* base = p.part + (size_t)b * p.n_splits * p.part_stride + g.part_off + (size_t)s * (cv + 2);
+    float M = -INFINITY;
+    for (int i = 0; i < p.n_splits; ++i) M = fmaxf(M, base[(size_t)i * p.part_stride]);
+    float L = 0.f;
+    for (int i = 0; i < p.n_splits; ++i) {
+        const float m_i = base[(size_t)i * p.part_stride];
+        L += base[(size_t)i * p.part_stride + 1] * (m_i == -INFINITY ? 0.f : exp2f(m_i - M));
+    }
+    const float inv = 1.f / L;
+    for (int c = tid; c < cv; c += 64) {
+        float a = 0.f;
+        for (int i = 0; i < p.n_splits; ++i) {
+            const float m_i = base[(size_t)i * p.part_stride];
+            if (m_i != -INFINITY) a = fmaf(base[(size_t)i * p.part_stride + 2 + c], exp2f(m_i - M), a);
+        }
+        olat[c] = a * inv;
+    }
+    __syncthreads();
+    (void)wsplit;
+    const int col = g.v_col[s];
+    for (int k = tid; k < p.d_head; k += 64) {
+        float a = g.v.bl ? Elem<E>::load(g.v.bl, col + k) : 0.f;
+        for (int c = 0; c < cv; ++c) a = fmaf(olat[c], Elem<E>::load(g.v.wl, (size_t)c * g.v.in_width + col + k), a);
+        Elem<E>::store(p.out, ((size_t)b * p.n_q_heads + g.q_head[s]) * p.d_head + k, a);
+    }
+}
+
+hipError_t launch_combine(const AttendParams& p, int dtype, hipStream_t stream) {
+    int max_slots = 0;
+    for (int i = 0; i < p.n_groups; ++i) max_slots = p.g[i].n_slots > max_slots ? p.g[i].n_slots : max_slots;
+    dim3 grid(p.batch, max_slots, p.n_groups);
+    if (dtype == KVCAR_F32) hipLaunchKernelGGL(combine_kernel<F32>, grid, dim3(64), 0, stream, p);
+    else if (dtype == KVCAR_F16) hipLaunchKernelGGL(combine_kernel<F16>, grid, dim3(64), 0, stream, p);
+    else hipLaunchKernelGGL(combine_kernel<BF16>, grid, dim3(64), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace kvcar

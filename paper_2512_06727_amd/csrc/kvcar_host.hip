@@ -1,0 +1,428 @@
+// Host side of libkvcar: context, validation, reuse-source resolution, launch planning, C ABI.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "kvcar_internal.hpp"
+
+using namespace kvcar;
+
+namespace {
+
+struct AEState {
+    bool set = false;
+    kvcar_ae_desc d{};
+    std::vector<int> heads;        // KV heads covered, in column order
+};
+
+size_t dtype_size(int dt) { return dt == KVCAR_F32 ? 4 : 2; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+struct kvcar_ctx {
+    kvcar_config cfg{};
+    float scale = 0.f;
+    std::vector<uint8_t> reuse;            // [layer][which][kv head]
+    std::vector<AEState> ae;               // [layer][which]
+    std::vector<void*> cache;              // [layer][which]
+    std::vector<size_t> cache_bytes;
+    kvcar_tuning tun{};
+    int n_cu = 256;
+    std::string err;
+
+    uint8_t& reuse_at(int layer, int which, int g) { return reuse[((size_t)layer * 2 + which) * cfg.n_kv_heads + g]; }
+    uint8_t reuse_at(int layer, int which, int g) const { return reuse[((size_t)layer * 2 + which) * cfg.n_kv_heads + g]; }
+    AEState& ae_at(int layer, int which) { return ae[(size_t)layer * 2 + which]; }
+    const AEState& ae_at(int layer, int which) const { return ae[(size_t)layer * 2 + which]; }
+};
+
+namespace {
+
+int fail(const kvcar_ctx* ctx, int code, const char* fmt, ...) {
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        const_cast<kvcar_ctx*>(ctx)->err = buf;
+    }
+    return code;
+}
+
+// Nearest layer M <= layer whose reuse bit for (which, g) is clear: the layer whose cache holds
+// the head ("Network Architecture": heads of layer N reuse those of layer N-1; chains follow
+// through to the layer that stores the head).
+int resolve(const kvcar_ctx* ctx, int layer, int which, int g) {
+    int m = layer;
+    while (m > 0 && ctx->reuse_at(m, which, g)) --m;
+    return m;
+}
+
+struct Plan {
+    std::vector<GroupDesc> groups;
+    bool mfma = false;
+    int n_splits = 1;
+    int qt_stride = 0;        // elements per sequence
+    int part_stride = 0;      // floats per (sequence, split)
+    size_t qt_bytes = 0, part_bytes = 0, total_bytes = 0;
+};
+
+int fill_side(const kvcar_ctx* ctx, int layer, int src, int which, SideDesc& sd) {
+    const AEState& a = ctx->ae_at(src, which);
+    if (!a.set) return fail(ctx, KVCAR_ERR_STATE, "layer %d needs the %s autoencoder of layer %d, which is not set", layer, which ? "V" : "K", src);
+    void* z = ctx->cache[(size_t)src * 2 + which];
+    if (a.d.latent_width > 0 && z == nullptr)
+        return fail(ctx, KVCAR_ERR_STATE, "layer %d needs the %s cache of layer %d, which is not bound", layer, which ? "V" : "K", src);
+    sd.z = z;
+    sd.r = a.d.latent_width;
+    sd.in_width = a.d.in_width;
+    sd.act = a.d.act;
+    sd.slope = a.d.leaky_slope;
+    if (a.d.hidden_width > 0) {
+        sd.w1 = a.d.dec_w1; sd.b1 = a.d.dec_b1; sd.wl = a.d.dec_w2; sd.bl = a.d.dec_b2; sd.c = a.d.hidden_width;
+    } else {
+        sd.w1 = nullptr; sd.b1 = nullptr; sd.wl = a.d.dec_w1; sd.bl = a.d.dec_b1; sd.c = a.d.latent_width;
+    }
+    return KVCAR_OK;
+}
+
+int head_column(const kvcar_ctx* ctx, int src, int which, int g) {
+    const AEState& a = ctx->ae_at(src, which);
+    for (size_t i = 0; i < a.heads.size(); ++i)
+        if (a.heads[i] == g) return (int)i * ctx->cfg.d_head;
+    return -1;
+}
+
+constexpr size_t kLdsBudget = 150 * 1024;
+
+int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan) {
+    const kvcar_config& c = ctx->cfg;
+    const int gq = c.n_q_heads / c.n_kv_heads;
+    std::map<std::pair<int, int>, std::vector<int>> by_src;     // (K source, V source) -> KV heads
+    for (int g = 0; g < c.n_kv_heads; ++g) by_src[{resolve(ctx, layer, KVCAR_K, g), resolve(ctx, layer, KVCAR_V, g)}].push_back(g);
+
+    plan.groups.clear();
+    bool mfma_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && attend_mfma_available();
+    for (auto& kv : by_src) {
+        GroupDesc base{};
+        int rc = fill_side(ctx, layer, kv.first.first, KVCAR_K, base.k);
+        if (rc) return rc;
+        rc = fill_side(ctx, layer, kv.first.second, KVCAR_V, base.v);
+        if (rc) return rc;
+        if (base.k.c > kMaxRow || base.v.c > kMaxRow || base.k.r > kMaxRow || base.v.r > kMaxRow)
+            return fail(ctx, KVCAR_ERR_UNSUPPORTED, "row width above %d", kMaxRow);
+        if (base.k.w1 || base.v.w1 || base.k.r % 32 || base.v.r % 32 || base.k.r > 384 || base.v.r > 384 || c.d_head % 8) mfma_ok = false;
+        // query heads of this (K source, V source) pair, in increasing order
+        std::vector<int> heads;
+        for (int g : kv.second)
+            for (int i = 0; i < gq; ++i) heads.push_back(g * gq + i);
+        // slot capacity of one plain-ALU workgroup: accumulators and LDS
+        int cap = std::min(kMaxSlots, kGenericAcc * 256 / std::max(1, base.v.c));
+        while (cap > 0) {
+            GroupDesc t = base; t.n_slots = cap;
+            if (attend_generic_lds_bytes(t) <= kLdsBudget) break;
+            --cap;
+        }
+        if (cap < 1) return fail(ctx, KVCAR_ERR_UNSUPPORTED, "rows too wide for the attention kernel");
+        for (size_t h0 = 0; h0 < heads.size(); h0 += cap) {
+            GroupDesc gd = base;
+            gd.n_slots = (int)std::min<size_t>(cap, heads.size() - h0);
+            gd.slots_pad = (gd.n_slots + 15) / 16 * 16;
+            for (int s = 0; s < gd.n_slots; ++s) {
+                const int j = heads[h0 + s], g = j / gq;
+                const int kc = head_column(ctx, kv.first.first, KVCAR_K, g);
+                const int vc = head_column(ctx, kv.first.second, KVCAR_V, g);
+                if (kc < 0 || vc < 0)
+                    return fail(ctx, KVCAR_ERR_REUSE, "layer %d takes head %d from a layer whose autoencoder does not cover it", layer, g);
+                gd.q_head[s] = (short)j; gd.k_col[s] = (short)kc; gd.v_col[s] = (short)vc;
+            }
+            plan.groups.push_back(gd);
+        }
+    }
+    plan.mfma = mfma_ok;
+    int qt = 0, part = 0;
+    for (auto& gd : plan.groups) {
+        gd.qt_off = qt; gd.part_off = part;
+        qt += gd.slots_pad * gd.k.c;
+        part += gd.slots_pad * (gd.v.c + 2);
+    }
+    plan.qt_stride = qt;
+    plan.part_stride = part;
+
+    // token-range splits: enough workgroups to fill the chip, never less than one tile per split
+    const int n_groups = (int)plan.groups.size();
+    int splits = ctx->tun.n_splits;
+    if (splits <= 0) {
+        const int target = plan.mfma ? ctx->n_cu * 4 : ctx->n_cu * 2;
+        splits = (target + batch * n_groups - 1) / (batch * n_groups);
+    }
+    const int tile = plan.mfma ? 128 : kGenericTile;
+    const int max_splits = std::max(1, (n_ctx + tile - 1) / tile);
+    splits = std::max(1, std::min(splits, std::min(max_splits, 256)));
+    plan.n_splits = splits;
+    plan.qt_bytes = align_up((size_t)batch * qt * (plan.mfma ? 2 : 4), 256);
+    plan.part_bytes = align_up((size_t)batch * splits * part * sizeof(float), 256);
+    plan.total_bytes = plan.qt_bytes + plan.part_bytes;
+    return KVCAR_OK;
+}
+
+int check_layer(const kvcar_ctx* ctx, int layer) {
+    if (!ctx) return KVCAR_ERR_ARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, KVCAR_ERR_ARG, "layer %d out of range", layer);
+    return KVCAR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kvcar_create(const kvcar_config* cfg, kvcar_ctx** out) {
+    if (!cfg || !out) return KVCAR_ERR_ARG;
+    *out = nullptr;
+    if (cfg->n_layers <= 0 || cfg->n_q_heads <= 0 || cfg->n_kv_heads <= 0 || cfg->d_head <= 0 || cfg->max_batch <= 0 ||
+        cfg->max_seq <= 0 || cfg->n_q_heads % cfg->n_kv_heads != 0)
+        return KVCAR_ERR_SHAPE;
+    if (cfg->n_kv_heads > kMaxKvHeads) return KVCAR_ERR_UNSUPPORTED;
+    if (cfg->dtype != KVCAR_F32 && cfg->dtype != KVCAR_F16 && cfg->dtype != KVCAR_BF16) return KVCAR_ERR_UNSUPPORTED;
+    kvcar_ctx* ctx = new (std::nothrow) kvcar_ctx();
+    if (!ctx) return KVCAR_ERR_ARG;
+    ctx->cfg = *cfg;
+    ctx->scale = cfg->softmax_scale != 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->d_head);
+    ctx->reuse.assign((size_t)cfg->n_layers * 2 * cfg->n_kv_heads, 0);
+    ctx->ae.assign((size_t)cfg->n_layers * 2, AEState());
+    ctx->cache.assign((size_t)cfg->n_layers * 2, nullptr);
+    ctx->cache_bytes.assign((size_t)cfg->n_layers * 2, 0);
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+        ctx->n_cu = prop.multiProcessorCount;
+    else
+        (void)hipGetLastError();   // no device here: host-side calls still work
+    *out = ctx;
+    return KVCAR_OK;
+}
+
+int kvcar_destroy(kvcar_ctx* ctx) {
+    delete ctx;
+    return KVCAR_OK;
+}
+
+int kvcar_set_reuse_map(kvcar_ctx* ctx, int layer, const uint8_t* k_reuse, const uint8_t* v_reuse) {
+    int rc = check_layer(ctx, layer);
+    if (rc) return rc;
+    if (!k_reuse || !v_reuse) return fail(ctx, KVCAR_ERR_ARG, "null reuse mask");
+    const int h = ctx->cfg.n_kv_heads;
+    if (layer == 0)
+        for (int g = 0; g < h; ++g)
+            if (k_reuse[g] || v_reuse[g]) return fail(ctx, KVCAR_ERR_REUSE, "layer 0 has no previous layer to reuse");
+    bool changed = false;
+    for (int g = 0; g < h; ++g) {
+        const uint8_t kb = k_reuse[g] ? 1 : 0, vb = v_reuse[g] ? 1 : 0;
+        changed |= ctx->reuse_at(layer, KVCAR_K, g) != kb || ctx->reuse_at(layer, KVCAR_V, g) != vb;
+        ctx->reuse_at(layer, KVCAR_K, g) = kb;
+        ctx->reuse_at(layer, KVCAR_V, g) = vb;
+    }
+    if (changed) {   // the stored head set changed: autoencoders of this layer must be set again
+        ctx->ae_at(layer, KVCAR_K) = AEState();
+        ctx->ae_at(layer, KVCAR_V) = AEState();
+    }
+    return KVCAR_OK;
+}
+
+int kvcar_resolve_source(const kvcar_ctx* ctx, int layer, int which, int kv_head, int* src_layer) {
+    int rc = check_layer(ctx, layer);
+    if (rc) return rc;
+    if (!src_layer || (which != KVCAR_K && which != KVCAR_V) || kv_head < 0 || kv_head >= ctx->cfg.n_kv_heads)
+        return fail(ctx, KVCAR_ERR_ARG, "bad argument to kvcar_resolve_source");
+    *src_layer = resolve(ctx, layer, which, kv_head);
+    return KVCAR_OK;
+}
+
+int kvcar_set_autoencoder(kvcar_ctx* ctx, int layer, int which, const kvcar_ae_desc* d) {
+    int rc = check_layer(ctx, layer);
+    if (rc) return rc;
+    if (!d || (which != KVCAR_K && which != KVCAR_V)) return fail(ctx, KVCAR_ERR_ARG, "bad argument to kvcar_set_autoencoder");
+    const kvcar_config& c = ctx->cfg;
+    std::vector<int> stored;
+    for (int g = 0; g < c.n_kv_heads; ++g)
+        if (!ctx->reuse_at(layer, which, g)) stored.push_back(g);
+    AEState st;
+    st.d = *d;
+    if (d->in_width == c.n_kv_heads * c.d_head) {
+        for (int g = 0; g < c.n_kv_heads; ++g) st.heads.push_back(g);
+    } else if (d->in_width == (int)stored.size() * c.d_head) {
+        st.heads = stored;
+    } else {
+        return fail(ctx, KVCAR_ERR_SHAPE, "in_width %d is neither D_kv=%d nor stored_heads*d_head=%d", d->in_width,
+                    c.n_kv_heads * c.d_head, (int)stored.size() * c.d_head);
+    }
+    if (d->in_width == 0) {
+        if (d->latent_width != 0) return fail(ctx, KVCAR_ERR_SHAPE, "latent_width must be 0 when in_width is 0");
+    } else {
+        if (d->latent_width <= 0 || d->hidden_width < 0) return fail(ctx, KVCAR_ERR_SHAPE, "non-positive widths");
+        if ((d->hidden_width > 0) != (d->act != KVCAR_ACT_NONE))
+            return fail(ctx, KVCAR_ERR_SHAPE, "activation requires hidden_width > 0 and vice versa");
+        if (d->act != KVCAR_ACT_NONE && d->act != KVCAR_ACT_LEAKY_RELU && d->act != KVCAR_ACT_GELU)
+            return fail(ctx, KVCAR_ERR_UNSUPPORTED, "unknown activation %d", d->act);
+        if (d->latent_width > kMaxRow || d->hidden_width > kMaxRow)
+            return fail(ctx, KVCAR_ERR_UNSUPPORTED, "widths above %d are not supported", kMaxRow);
+        if ((size_t)d->latent_width * dtype_size(c.dtype) % 16 != 0)
+            return fail(ctx, KVCAR_ERR_UNSUPPORTED, "latent rows must be a multiple of 16 bytes");
+        const void* req[4] = {d->enc_w1, d->dec_w1, d->hidden_width ? d->enc_w2 : d->enc_w1, d->hidden_width ? d->dec_w2 : d->dec_w1};
+        for (const void* p : req)
+            if (!p) return fail(ctx, KVCAR_ERR_ARG, "null weight pointer");
+        const void* all[8] = {d->enc_w1, d->enc_b1, d->enc_w2, d->enc_b2, d->dec_w1, d->dec_b1, d->dec_w2, d->dec_b2};
+        for (const void* p : all)
+            if (p && !aligned16(p)) return fail(ctx, KVCAR_ERR_ARG, "weight pointer not 16-byte aligned");
+    }
+    st.set = true;
+    // a new width invalidates a bound cache that is now too small
+    const size_t need = (size_t)c.max_batch * c.max_seq * d->latent_width * dtype_size(c.dtype);
+    if (ctx->cache_bytes[(size_t)layer * 2 + which] < need) {
+        ctx->cache[(size_t)layer * 2 + which] = nullptr;
+        ctx->cache_bytes[(size_t)layer * 2 + which] = 0;
+    }
+    ctx->ae_at(layer, which) = st;
+    return KVCAR_OK;
+}
+
+int kvcar_cache_bytes(const kvcar_ctx* ctx, int layer, int which, size_t* bytes) {
+    int rc = check_layer(ctx, layer);
+    if (rc) return rc;
+    if (!bytes || (which != KVCAR_K && which != KVCAR_V)) return fail(ctx, KVCAR_ERR_ARG, "bad argument to kvcar_cache_bytes");
+    const AEState& a = ctx->ae_at(layer, which);
+    if (!a.set) return fail(ctx, KVCAR_ERR_STATE, "autoencoder of layer %d not set", layer);
+    *bytes = (size_t)ctx->cfg.max_batch * ctx->cfg.max_seq * a.d.latent_width * dtype_size(ctx->cfg.dtype);
+    return KVCAR_OK;
+}
+
+int kvcar_bind_cache(kvcar_ctx* ctx, int layer, int which, void* dev, size_t bytes) {
+    size_t need = 0;
+    int rc = kvcar_cache_bytes(ctx, layer, which, &need);
+    if (rc) return rc;
+    if (need == 0) { ctx->cache[(size_t)layer * 2 + which] = nullptr; ctx->cache_bytes[(size_t)layer * 2 + which] = 0; return KVCAR_OK; }
+    if (!dev || !aligned16(dev)) return fail(ctx, KVCAR_ERR_ARG, "cache pointer null or not 16-byte aligned");
+    if (bytes < need) return fail(ctx, KVCAR_ERR_CAPACITY, "cache of %zu bytes is smaller than the %zu needed", bytes, need);
+    ctx->cache[(size_t)layer * 2 + which] = dev;
+    ctx->cache_bytes[(size_t)layer * 2 + which] = bytes;
+    return KVCAR_OK;
+}
+
+int kvcar_set_tuning(kvcar_ctx* ctx, const kvcar_tuning* t) {
+    if (!ctx || !t) return KVCAR_ERR_ARG;
+    if (t->n_splits < 0) return fail(ctx, KVCAR_ERR_ARG, "negative n_splits");
+    ctx->tun = *t;
+    return KVCAR_OK;
+}
+
+int kvcar_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_ctx, size_t* bytes) {
+    if (!ctx || !bytes) return KVCAR_ERR_ARG;
+    if (batch < 1 || batch > ctx->cfg.max_batch || n_ctx < 1 || n_ctx > ctx->cfg.max_seq)
+        return fail(ctx, KVCAR_ERR_CAPACITY, "batch %d / n_ctx %d outside [1,%d] / [1,%d]", batch, n_ctx, ctx->cfg.max_batch, ctx->cfg.max_seq);
+    size_t mx = 0;
+    for (int layer = 0; layer < ctx->cfg.n_layers; ++layer) {
+        Plan plan;
+        int rc = build_plan(ctx, layer, batch, n_ctx, plan);
+        if (rc) return rc;
+        mx = std::max(mx, plan.total_bytes);
+    }
+    *bytes = mx;
+    return KVCAR_OK;
+}
+
+int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, int pos0, int t_new, void* stream) {
+    int rc = check_layer(ctx, layer);
+    if (rc) return rc;
+    const kvcar_config& c = ctx->cfg;
+    if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return fail(ctx, KVCAR_ERR_ARG, "k_new / v_new null or misaligned");
+    if (batch < 1 || t_new < 1 || pos0 < 0) return fail(ctx, KVCAR_ERR_ARG, "batch, t_new must be >= 1 and pos0 >= 0");
+    if (batch > c.max_batch || (long long)pos0 + t_new > c.max_seq)
+        return fail(ctx, KVCAR_ERR_CAPACITY, "append of %d tokens at %d for batch %d exceeds max_seq %d / max_batch %d", t_new, pos0, batch, c.max_seq, c.max_batch);
+    EncodeParams p{};
+    p.batch = batch; p.t_new = t_new; p.pos0 = pos0; p.max_seq = c.max_seq; p.d_kv = c.n_kv_heads * c.d_head; p.d_head = c.d_head;
+    const void* xs[2] = {k_new, v_new};
+    bool any = false;
+    for (int which = 0; which < 2; ++which) {
+        const AEState& a = ctx->ae_at(layer, which);
+        if (!a.set) return fail(ctx, KVCAR_ERR_STATE, "autoencoder of layer %d (%s) not set", layer, which ? "V" : "K");
+        EncodeSide& s = p.s[which];
+        s.x = xs[which];
+        s.r = a.d.latent_width;
+        if (s.r == 0) continue;
+        s.z = ctx->cache[(size_t)layer * 2 + which];
+        if (!s.z) return fail(ctx, KVCAR_ERR_STATE, "cache of layer %d (%s) not bound", layer, which ? "V" : "K");
+        s.w1 = a.d.enc_w1; s.b1 = a.d.enc_b1; s.w2 = a.d.enc_w2; s.b2 = a.d.enc_b2;
+        s.in_width = a.d.in_width; s.hidden = a.d.hidden_width; s.act = a.d.act; s.slope = a.d.leaky_slope;
+        s.n_heads = (int)a.heads.size();
+        for (size_t i = 0; i < a.heads.size(); ++i) s.heads[i] = (unsigned char)a.heads[i];
+        any = true;
+    }
+    if (!any) return KVCAR_OK;   // the layer stores nothing
+    hipError_t e = launch_encode_generic(p, c.dtype, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "encode launch failed: %s", hipGetErrorString(e));
+    return KVCAR_OK;
+}
+
+int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    int rc = check_layer(ctx, layer);
+    if (rc) return rc;
+    const kvcar_config& c = ctx->cfg;
+    if (!q || !out || !aligned16(q) || !aligned16(out)) return fail(ctx, KVCAR_ERR_ARG, "q / out null or misaligned");
+    if (batch < 1 || batch > c.max_batch || n_ctx < 1 || n_ctx > c.max_seq)
+        return fail(ctx, KVCAR_ERR_CAPACITY, "batch %d / n_ctx %d outside [1,%d] / [1,%d]", batch, n_ctx, c.max_batch, c.max_seq);
+    Plan plan;
+    rc = build_plan(ctx, layer, batch, n_ctx, plan);
+    if (rc) return rc;
+    if (!workspace || !aligned16(workspace)) return fail(ctx, KVCAR_ERR_ARG, "workspace null or misaligned");
+    if (workspace_bytes < plan.total_bytes)
+        return fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, plan.total_bytes);
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    for (size_t g0 = 0; g0 < plan.groups.size(); g0 += kMaxGroups) {
+        AttendParams p{};
+        p.n_groups = (int)std::min<size_t>(kMaxGroups, plan.groups.size() - g0);
+        for (int i = 0; i < p.n_groups; ++i) p.g[i] = plan.groups[g0 + i];
+        p.q = q; p.out = out;
+        p.qt = workspace;
+        p.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.qt_bytes);
+        p.batch = batch; p.n_ctx = n_ctx; p.n_splits = plan.n_splits;
+        p.n_q_heads = c.n_q_heads; p.d_head = c.d_head; p.max_seq = c.max_seq;
+        p.qt_stride = plan.qt_stride; p.part_stride = plan.part_stride;
+        p.scale_log2e = ctx->scale * kLog2e;
+        hipError_t e = launch_qtilde(p, c.dtype, !plan.mfma, st);
+        if (e == hipSuccess) e = plan.mfma ? launch_attend_mfma(p, c.dtype, st) : launch_attend_generic(p, c.dtype, st);
+        if (e == hipSuccess) e = launch_combine(p, c.dtype, st);
+        if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
+    }
+    return KVCAR_OK;
+}
+
+const char* kvcar_status_string(int s) {
+    switch (s) {
+        case KVCAR_OK: return "KVCAR_OK";
+        case KVCAR_ERR_ARG: return "KVCAR_ERR_ARG";
+        case KVCAR_ERR_SHAPE: return "KVCAR_ERR_SHAPE";
+        case KVCAR_ERR_CAPACITY: return "KVCAR_ERR_CAPACITY";
+        case KVCAR_ERR_REUSE: return "KVCAR_ERR_REUSE";
+        case KVCAR_ERR_UNSUPPORTED: return "KVCAR_ERR_UNSUPPORTED";
+        case KVCAR_ERR_STATE: return "KVCAR_ERR_STATE";
+        case KVCAR_ERR_HIP: return "KVCAR_ERR_HIP";
+        case KVCAR_ERR_WORKSPACE: return "KVCAR_ERR_WORKSPACE";
+        default: return "KVCAR_ERR_UNKNOWN";
+    }
+}
+
+const char* kvcar_last_error(const kvcar_ctx* ctx) { return ctx ? ctx->err.c_str() : ""; }
+
+}  // extern "C"

@@ -1,0 +1,86 @@
+// Internal declarations shared by the host code and the kernels of libkvcar (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvcar.h"
+
+namespace kvcar {
+
+constexpr int kMaxSlots = 32;       // query heads served by one group
+constexpr int kMaxGroups = 8;       // groups per attention launch
+constexpr int kMaxKvHeads = 64;     // bound on n_kv_heads (head lists live in kernel arguments)
+constexpr int kGenericTile = 16;    // tokens per tile of the plain-ALU attention kernel
+constexpr int kGenericAcc = 48;     // accumulators per thread of the plain-ALU attention kernel
+constexpr int kMaxRow = 384;        // widest latent / hidden row any kernel handles
+constexpr float kLog2e = 1.4426950408889634f;
+
+// One side (keys or values) of a group: where its rows come from and how they are decoded.
+struct SideDesc {
+    const void* z;        // source layer's latent cache [max_batch, max_seq, r]
+    const void* w1;       // first decoder layer [r, c] (two-layer decoder only, else null)
+    const void* b1;       // its bias or null
+    const void* wl;       // last decoder layer [c, in_width]
+    const void* bl;       // its bias or null
+    int r;                // latent row width
+    int c;                // contraction width: r (linear decoder) or hidden width
+    int in_width;         // row stride of wl
+    int act;              // kvcar_act between the two layers
+    float slope;
+};
+
+// A group: query heads of one layer that read the same (K source layer, V source layer).
+struct GroupDesc {
+    SideDesc k, v;
+    int n_slots;                   // query heads in the group (<= kMaxSlots)
+    int slots_pad;                 // n_slots rounded up to 16
+    int qt_off;                    // element offset of the group's absorbed queries, per sequence
+    int part_off;                  // float offset of the group's partials, per (sequence, split)
+    short q_head[kMaxSlots];       // query head of each slot
+    short k_col[kMaxSlots];        // first column of the slot's KV head in k.wl
+    short v_col[kMaxSlots];        // same for v.wl
+};
+
+struct AttendParams {
+    GroupDesc g[kMaxGroups];
+    const void* q;        // [batch, H_q, d_head]
+    void* out;            // [batch, H_q, d_head]
+    void* qt;             // workspace: absorbed queries
+    float* part;          // workspace: split partials
+    int n_groups;
+    int batch, n_ctx, n_splits;
+    int n_q_heads, d_head;
+    int max_seq;
+    int qt_stride;        // absorbed-query elements per sequence (all groups)
+    int part_stride;      // partial floats per (sequence, split) (all groups)
+    float scale_log2e;    // softmax scale * log2(e)
+};
+
+struct EncodeSide {
+    const void* x;        // [batch, t_new, d_kv]
+    void* z;              // cache [max_batch, max_seq, r]
+    const void* w1; const void* b1;   // [in, hidden or r]
+    const void* w2; const void* b2;   // [hidden, r] or null
+    int in_width, hidden, r, act, n_heads;
+    float slope;
+    unsigned char heads[kMaxKvHeads]; // KV heads whose columns form the encoder input
+};
+
+struct EncodeParams {
+    EncodeSide s[2];
+    int batch, t_new, pos0, max_seq, d_kv, d_head;
+};
+
+// Launchers (defined next to their kernels). All enqueue on `stream` and return hipGetLastError().
+hipError_t launch_encode_generic(const EncodeParams& p, int dtype, hipStream_t stream);
+hipError_t launch_qtilde(const AttendParams& p, int dtype, bool qt_f32, hipStream_t stream);
+hipError_t launch_attend_generic(const AttendParams& p, int dtype, hipStream_t stream);
+hipError_t launch_combine(const AttendParams& p, int dtype, hipStream_t stream);
+size_t attend_generic_lds_bytes(const GroupDesc& g);
+
+// MFMA path (16-bit dtypes, linear decoders, widths that are multiples of 32).
+bool attend_mfma_available();
+hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stream);
+
+}  // namespace kvcar

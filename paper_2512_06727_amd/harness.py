@@ -1,0 +1,85 @@
+"""Plumbing between a synthetic workload and the library: allocates caches, weights and
+workspace as PyTorch tensors on the GPU and drives the C ABI.  No arithmetic of the method
+lives here."""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding, synth
+
+
+class Session:
+    def __init__(self, w: synth.Workload, reuse: Optional[np.ndarray] = None, with_bias: bool = False,
+                 device: str = "cuda:0", n_splits: int = 0, force_generic: bool = False, poison: bool = False,
+                 max_batch: Optional[int] = None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: libkvcar has no CPU path")
+        self.w = w
+        self.dev = torch.device(device)
+        self.tdt = synth.TORCH_DTYPE[w.dtype]
+        self.reuse = synth.reuse_map(w) if reuse is None else reuse
+        self.ctx = binding.Context(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, max_batch or w.batch, w.max_seq, w.dtype)
+        self.ctx.set_tuning(n_splits=n_splits, force_generic=force_generic)
+        self.ae: List[List[synth.AEWeights]] = []
+        self.caches: List[List[Optional[torch.Tensor]]] = []
+        for layer in range(w.n_layers):
+            self.ctx.set_reuse_map(layer, self.reuse[layer, 0], self.reuse[layer, 1])
+        for layer in range(w.n_layers):
+            row, crow = [], []
+            for which in (0, 1):
+                ae = synth.autoencoder(w, layer, which, self.reuse, with_bias)
+                up = lambda pairs: [(wt.to(self.dev, self.tdt).contiguous(), None if b is None else b.to(self.dev, self.tdt).contiguous())
+                                    for wt, b in pairs]
+                enc, dec = up(ae.enc), up(ae.dec)
+                self.ctx.set_autoencoder(layer, which, ae.width, ae.hidden if ae.width else 0, ae.latent,
+                                         ae.act if ae.width else "none", enc, dec, ae.slope)
+                nbytes = self.ctx.cache_bytes(layer, which)
+                cache = None
+                if nbytes:
+                    n = nbytes // synth.DTYPE_BYTES[w.dtype]
+                    cache = torch.empty(n, dtype=self.tdt, device=self.dev)
+                    if poison:
+                        cache.fill_(float("nan"))
+                    self.ctx.bind_cache(layer, which, cache)
+                row.append(ae)
+                crow.append(cache)
+            self.ae.append(row)
+            self.caches.append(crow)
+        self.workspace = None
+        self._ws_key = None
+
+    # ------------------------------------------------------------------
+    def cache_view(self, layer: int, which: int) -> Optional[torch.Tensor]:
+        """[max_batch, max_seq, r] view of a latent cache (the documented layout)."""
+        c = self.caches[layer][which]
+        return None if c is None else c.view(self.ctx.cfg.max_batch, self.w.max_seq, self.ae[layer][which].latent)
+
+    def ensure_workspace(self, batch: int, n_ctx: int):
+        need = self.ctx.workspace_bytes(batch, n_ctx)
+        if self.workspace is None or self.workspace.numel() < need:
+            self.workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=self.dev)
+
+    def encode_append(self, layer: int, k_new: torch.Tensor, v_new: torch.Tensor, pos0: int):
+        b, t, _ = k_new.shape
+        self.ctx.encode_append(layer, k_new, v_new, b, pos0, t)
+
+    def prefill(self, t0: int, t1: int, chunk: int = 512, layers=None):
+        """Encode+append synthetic K/V for positions [t0, t1) of every sequence."""
+        w = self.w
+        for layer in (range(w.n_layers) if layers is None else layers):
+            for c0 in range(t0, t1, chunk):
+                c1 = min(t1, c0 + chunk)
+                k = synth.kv_tokens(w, layer, 0, 0, w.batch, c0, c1, device=self.dev).to(self.tdt)
+                v = synth.kv_tokens(w, layer, 1, 0, w.batch, c0, c1, device=self.dev).to(self.tdt)
+                self.encode_append(layer, k, v, c0)
+
+    def decode_attention(self, layer: int, q: torch.Tensor, n_ctx: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        b = q.shape[0]
+        self.ensure_workspace(b, n_ctx)
+        if out is None:
+            out = torch.empty_like(q)
+        self.ctx.decode_attention(layer, q, out, b, n_ctx, self.workspace)
+        return out

@@ -28,3 +28,91 @@ def oracle_prefill(orc, w, layer, t0, t1, b0=0, b1=None):
     v = synth.kv_tokens(w, layer, 1, b0, b1, t0, t1).double().numpy()
     assert b0 == 0
     orc.encode_append(layer, k, v, t0)
+
+
+# ---------------------------------------------------------------------------
+# running a workload through the oracle and through the library
+# ---------------------------------------------------------------------------
+ABS_TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}       # max |gpu - oracle|
+REL_TOL = {"f32": 1e-4, "f16": 4e-3, "bf16": 2e-2}       # max |gpu - oracle| / max |oracle|
+
+
+def run_oracle(w, reuse=None, with_bias=False, gain=1.0, layers=None):
+    """Prefill n_cached tokens, then n_steps decode steps (append at pos, attend over
+    pos+1 tokens).  Returns (oracle, outputs[step][layer] as fp64 arrays)."""
+    orc = build_oracle(w, reuse, with_bias)
+    lay = list(range(w.n_layers)) if layers is None else layers
+    for n in range(w.n_layers):
+        oracle_prefill(orc, w, n, 0, w.n_cached)
+    outs = []
+    for step in range(w.n_steps):
+        pos = w.n_cached + step
+        row = {}
+        for n in range(w.n_layers):
+            oracle_prefill(orc, w, n, pos, pos + 1)
+        for n in lay:
+            q = synth.queries(w, n, step, gain=gain).double().numpy()
+            row[n] = orc.decode_attention(n, q, pos + 1)
+        outs.append(row)
+    return orc, outs
+
+
+def run_gpu(w, reuse=None, with_bias=False, gain=1.0, layers=None, **session_kw):
+    import torch
+    from paper_2512_06727_amd.harness import Session
+    ses = Session(w, reuse=reuse, with_bias=with_bias, poison=True, **session_kw)
+    lay = list(range(w.n_layers)) if layers is None else layers
+    ses.prefill(0, w.n_cached, chunk=256)
+    outs = []
+    for step in range(w.n_steps):
+        pos = w.n_cached + step
+        ses.prefill(pos, pos + 1)
+        row = {}
+        for n in lay:
+            q = synth.queries(w, n, step, gain=gain).to(ses.dev, ses.tdt)
+            row[n] = ses.decode_attention(n, q, pos + 1).float().cpu().double().numpy()
+        outs.append(row)
+    torch.cuda.synchronize()
+    return ses, outs
+
+
+def assert_outputs_close(w, got, want, label=""):
+    for step, (grow, wrow) in enumerate(zip(got, want)):
+        for n in wrow:
+            g, o = grow[n], wrow[n]
+            assert np.isfinite(g).all(), f"{label} step {step} layer {n}: non-finite output"
+            err = np.abs(g - o).max()
+            ref = np.abs(o).max()
+            assert err <= ABS_TOL[w.dtype], f"{label} step {step} layer {n}: max abs err {err:.3e}"
+            assert err <= REL_TOL[w.dtype] * ref, f"{label} step {step} layer {n}: err {err:.3e} vs max |ref| {ref:.3e}"
+
+
+def assert_cache_close(w, ses, orc, n_rows):
+    """GPU latent caches vs the oracle's: same rows written, values equal up to one
+    unit in the last place of the cache dtype on a small fraction of elements
+    (fp32 accumulation order differs from the oracle's fp64 sum)."""
+    import torch
+    for layer in range(w.n_layers):
+        for which in (0, 1):
+            view = ses.cache_view(layer, which)
+            zo = orc.Z[(layer, which)]
+            if view is None:
+                assert zo.shape[-1] == 0
+                continue
+            zg = view.float().cpu().double().numpy()[:, :n_rows]
+            zo = zo[:, :n_rows]
+            assert zg.shape == zo.shape
+            assert np.isfinite(zg).all()
+            if w.dtype == "f32":
+                np.testing.assert_allclose(zg, zo, rtol=2e-5, atol=1e-6)
+            else:
+                ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(zo), 1e-30))) - (7 if w.dtype == "bf16" else 10))
+                diff = np.abs(zg - zo)
+                # values that nearly cancel carry the fp32 accumulation error of the whole sum
+                floor = 2e-6 * np.abs(zo).max()
+                assert (diff <= ulp * 1.0001 + floor).all(), f"layer {layer} which {which}: more than one ulp apart"
+                assert (diff > 0).mean() < 0.02, f"layer {layer} which {which}: {(diff > 0).mean():.4f} of elements differ"
+            # rows never appended keep the poison
+            rest = view[:, n_rows:]
+            if rest.numel():
+                assert torch.isnan(rest.float()).all()

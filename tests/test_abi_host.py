@@ -1,0 +1,155 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header
+declares, and its host logic (validation, reuse resolution, sizes) behaves as documented.
+No kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2512_06727_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "kvcar.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvcar_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert "kvcar_encode_append" in names and "kvcar_decode_attention" in names and "kvcar_set_reuse_map" in names
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.SYMBOLS) == names          # the binding marshals exactly the declared calls
+
+
+def make(n_layers=3, hq=8, hkv=4, dh=64, mb=2, ms=64, dtype="bf16"):
+    return B.Context(n_layers, hq, hkv, dh, mb, ms, dtype)
+
+
+FAKE = 0x7f0000001000          # 16-byte aligned fake device addresses: never dereferenced on the host
+
+
+def desc(in_w, hid, lat, act=B.ACT_NONE, ptrs=True):
+    d = B.AEDesc()
+    d.in_width, d.hidden_width, d.latent_width, d.act, d.leaky_slope = in_w, hid, lat, act, 0.01
+    if ptrs:
+        d.enc_w1 = d.dec_w1 = FAKE
+        if hid:
+            d.enc_w2 = d.dec_w2 = FAKE
+    return d
+
+
+def test_create_validation():
+    h = C.c_void_p()
+    bad = B.Config(2, 7, 4, 64, 1, 8, B.BF16, 0.0)            # 7 % 4 != 0
+    assert B.lib().kvcar_create(C.byref(bad), C.byref(h)) == B.ERR_SHAPE
+    bad = B.Config(2, 8, 4, 64, 1, 8, 9, 0.0)
+    assert B.lib().kvcar_create(C.byref(bad), C.byref(h)) == B.ERR_UNSUPPORTED
+    assert B.lib().kvcar_create(None, C.byref(h)) == B.ERR_ARG
+    assert B.lib().kvcar_status_string(B.ERR_REUSE) == b"KVCAR_ERR_REUSE"
+
+
+def test_reuse_resolution_matches_hand_table():
+    ctx = make(n_layers=4)
+    with pytest.raises(B.KVCARError) as e:
+        ctx.set_reuse_map(0, [1, 0, 0, 0], [0, 0, 0, 0])
+    assert e.value.status == B.ERR_REUSE
+    ctx.set_reuse_map(1, [0, 1, 0, 0], [0, 0, 0, 1])
+    ctx.set_reuse_map(2, [0, 1, 1, 0], [0, 0, 0, 0])
+    ctx.set_reuse_map(3, [1, 1, 0, 0], [0, 0, 0, 1])
+    want_k = {0: [0, 0, 0, 0], 1: [1, 0, 1, 1], 2: [2, 0, 1, 2], 3: [2, 0, 3, 3]}
+    want_v = {0: [0, 0, 0, 0], 1: [1, 1, 1, 0], 2: [2, 2, 2, 2], 3: [3, 3, 3, 2]}
+    for layer in range(4):
+        assert [ctx.resolve_source(layer, B.K, g) for g in range(4)] == want_k[layer]
+        assert [ctx.resolve_source(layer, B.V, g) for g in range(4)] == want_v[layer]
+
+
+def test_autoencoder_shape_rules_and_cache_bytes():
+    ctx = make()
+    st = B.lib().kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(desc(256, 0, 128)))
+    assert st == B.OK
+    assert ctx.cache_bytes(0, B.K) == 2 * 64 * 128 * 2                       # max_batch*max_seq*r*P
+    assert B.lib().kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(desc(200, 0, 128))) == B.ERR_SHAPE
+    assert B.lib().kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(desc(256, 64, 128))) == B.ERR_SHAPE   # hidden without act
+    assert B.lib().kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(desc(256, 0, 128, B.ACT_GELU))) == B.ERR_SHAPE
+    assert B.lib().kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(desc(256, 0, 128, ptrs=False))) == B.ERR_ARG
+    d = desc(256, 0, 128); d.enc_w1 = FAKE + 2
+    assert B.lib().kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(d)) == B.ERR_ARG                     # misaligned
+    # a layer with one reused head may cover all heads (256) or only its three stored heads (192)
+    ctx.set_reuse_map(1, [0, 1, 0, 0], [0, 1, 0, 0])
+    assert B.lib().kvcar_set_autoencoder(ctx._h, 1, B.K, C.byref(desc(192, 0, 96))) == B.OK
+    assert ctx.cache_bytes(1, B.K) == 2 * 64 * 96 * 2
+    assert B.lib().kvcar_set_autoencoder(ctx._h, 1, B.K, C.byref(desc(256, 0, 128))) == B.OK
+    assert B.lib().kvcar_set_autoencoder(ctx._h, 1, B.K, C.byref(desc(128, 0, 64))) == B.ERR_SHAPE
+    # changing the map drops the layer's autoencoders
+    ctx.set_reuse_map(1, [0, 0, 0, 0], [0, 0, 0, 0])
+    n = C.c_size_t()
+    assert B.lib().kvcar_cache_bytes(ctx._h, 1, B.K, C.byref(n)) == B.ERR_STATE
+    # a layer that stores nothing
+    ctx.set_reuse_map(2, [1, 1, 1, 1], [1, 1, 1, 1])
+    assert B.lib().kvcar_set_autoencoder(ctx._h, 2, B.K, C.byref(desc(0, 0, 0, ptrs=False))) == B.OK
+    assert ctx.cache_bytes(2, B.K) == 0
+
+
+def test_bind_and_capacity_errors_before_any_launch():
+    ctx = make(n_layers=2)
+    lib = B.lib()
+    for which in (B.K, B.V):
+        assert lib.kvcar_set_autoencoder(ctx._h, 0, which, C.byref(desc(256, 0, 128))) == B.OK
+    need = ctx.cache_bytes(0, B.K)
+    assert lib.kvcar_bind_cache(ctx._h, 0, B.K, FAKE, need - 1) == B.ERR_CAPACITY
+    assert lib.kvcar_bind_cache(ctx._h, 0, B.K, FAKE + 4, need) == B.ERR_ARG
+    assert lib.kvcar_bind_cache(ctx._h, 0, B.K, None, need) == B.ERR_ARG
+    # encode_append: state, capacity and argument errors are reported before anything is enqueued
+    assert lib.kvcar_encode_append(ctx._h, 0, FAKE, FAKE, 1, 0, 1, None) == B.ERR_STATE          # caches not bound
+    assert lib.kvcar_bind_cache(ctx._h, 0, B.K, FAKE, need) == B.OK
+    assert lib.kvcar_bind_cache(ctx._h, 0, B.V, FAKE, need) == B.OK
+    assert lib.kvcar_encode_append(ctx._h, 0, FAKE, FAKE, 3, 0, 1, None) == B.ERR_CAPACITY       # batch > max_batch
+    assert lib.kvcar_encode_append(ctx._h, 0, FAKE, FAKE, 1, 60, 5, None) == B.ERR_CAPACITY      # past max_seq
+    assert lib.kvcar_encode_append(ctx._h, 0, None, FAKE, 1, 0, 1, None) == B.ERR_ARG
+    assert lib.kvcar_encode_append(ctx._h, 5, FAKE, FAKE, 1, 0, 1, None) == B.ERR_ARG
+    assert lib.kvcar_encode_append(ctx._h, 1, FAKE, FAKE, 1, 0, 1, None) == B.ERR_STATE          # layer 1 has no autoencoder
+    # decode_attention
+    assert lib.kvcar_decode_attention(ctx._h, 0, FAKE, FAKE, 1, 65, FAKE, 1 << 30, None) == B.ERR_CAPACITY
+    assert lib.kvcar_decode_attention(ctx._h, 0, FAKE, FAKE, 1, 0, FAKE, 1 << 30, None) == B.ERR_CAPACITY
+    assert lib.kvcar_decode_attention(ctx._h, 0, FAKE, FAKE, 1, 8, FAKE, 16, None) == B.ERR_WORKSPACE
+    assert lib.kvcar_decode_attention(ctx._h, 0, FAKE, None, 1, 8, FAKE, 1 << 30, None) == B.ERR_ARG
+    assert lib.kvcar_decode_attention(ctx._h, 1, FAKE, FAKE, 1, 8, FAKE, 1 << 30, None) == B.ERR_STATE
+    assert b"not set" in lib.kvcar_last_error(ctx._h)
+
+
+def test_source_layer_must_cover_the_head():
+    """Layer 1 reuses head 2 of layer 0, but layer 0's autoencoder... covers it; a layer-1
+    autoencoder in the stored-heads form does not cover head 2, so layer 2 reusing head 2
+    resolves past layer 1 to layer 0."""
+    ctx = make(n_layers=3)
+    lib = B.lib()
+    ctx.set_reuse_map(1, [0, 0, 1, 0], [0, 0, 1, 0])
+    ctx.set_reuse_map(2, [0, 0, 1, 0], [0, 0, 1, 0])
+    assert ctx.resolve_source(2, B.K, 2) == 0
+    for layer, (inw, lat) in enumerate([(256, 128), (192, 96), (192, 96)]):
+        for which in (B.K, B.V):
+            assert lib.kvcar_set_autoencoder(ctx._h, layer, which, C.byref(desc(inw, 0, lat))) == B.OK
+            assert lib.kvcar_bind_cache(ctx._h, layer, which, FAKE, ctx.cache_bytes(layer, which)) == B.OK
+    n = C.c_size_t()
+    assert lib.kvcar_workspace_bytes(ctx._h, 2, 64, C.byref(n)) == B.OK and n.value > 0
+    assert lib.kvcar_workspace_bytes(ctx._h, 3, 64, C.byref(n)) == B.ERR_CAPACITY
+
+
+def test_workspace_grows_with_splits():
+    ctx = make(n_layers=1, mb=4, ms=4096)
+    lib = B.lib()
+    for which in (B.K, B.V):
+        assert lib.kvcar_set_autoencoder(ctx._h, 0, which, C.byref(desc(256, 0, 128))) == B.OK
+        assert lib.kvcar_bind_cache(ctx._h, 0, which, FAKE, ctx.cache_bytes(0, which)) == B.OK
+    ctx.set_tuning(n_splits=1)
+    a = ctx.workspace_bytes(4, 4096)
+    ctx.set_tuning(n_splits=8)
+    b = ctx.workspace_bytes(4, 4096)
+    assert b > a > 0

@@ -1,0 +1,61 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs, element by element.  Sizes span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_06727_amd import synth
+from tests.helpers import (ABS_TOL, assert_cache_close, assert_outputs_close, run_gpu, run_oracle)
+
+pytestmark = pytest.mark.gpu
+
+C = synth.CONFIGS
+
+CASES = {
+    # the small configuration exactly as specified (fp32, one layer, 128 cached tokens)
+    "c0-exact": (C[0], {}),
+    # GPT-2 shape, fp16, reuse in odd layers, fewer layers / sequences / tokens
+    "c1-small": (C[1].scaled(n_layers=4, batch=2, n_cached=203, n_steps=2), {}),
+    # TinyLlama shape, bf16, grouped-query heads, one reused KV head per layer >= 2 (chains appear)
+    "c2-small": (C[2].scaled(n_layers=5, batch=3, n_cached=301, n_steps=2), {}),
+    # two-layer GELU autoencoder
+    "c3-small": (C[3].scaled(n_layers=2, batch=2, n_cached=77, n_steps=2), {}),
+    # Bernoulli(0.3) map: layers storing 0..4 heads, mixed sources, chains
+    "c4-small": (C[4].scaled(n_layers=8, batch=2, n_cached=333, n_steps=2), {}),
+    # full-width latents in every layer (reuse saves no capacity; decoder columns of reused heads ignored)
+    "c4-small-p2": (C[4].scaled(n_layers=6, batch=2, n_cached=150, n_steps=1, policy="P2"), {}),
+    # biases everywhere and the paper's LeakyReLU between the two layers
+    "leaky-bias": (C[2].scaled(n_layers=3, batch=2, n_cached=90, n_steps=1, hidden=160, act="leaky_relu", dtype="f16"),
+                   {"with_bias": True}),
+    "linear-bias-f32": (C[0].scaled(n_layers=2, batch=2, n_cached=50, n_steps=2, reuse="odd:5"), {"with_bias": True}),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("gain", [1.0, 50.0])
+def test_parity(name, gain):
+    w, kw = CASES[name]
+    if gain != 1.0 and w.dtype == "f32" and name != "c0-exact":
+        pytest.skip("sharp case covered by c0")
+    print(f"case {name} gain {gain} {w}", flush=True)
+    orc, want = run_oracle(w, gain=gain, **kw)
+    ses, got = run_gpu(w, gain=gain, **kw)
+    assert_cache_close(w, ses, orc, w.n_cached + w.n_steps)
+    assert_outputs_close(w, got, want, name)
+
+
+@pytest.mark.parametrize("n_splits", [1, 2, 7])
+def test_split_counts_agree_with_oracle(n_splits):
+    w = C[2].scaled(n_layers=3, batch=2, n_cached=257, n_steps=1)
+    _, want = run_oracle(w, gain=20.0)
+    _, got = run_gpu(w, gain=20.0, n_splits=n_splits)
+    assert_outputs_close(w, got, want, f"splits={n_splits}")
+
+
+def test_single_token_context_and_partial_batch():
+    """n_ctx = 1 (softmax over one token = that token's decoded value) and a batch
+    smaller than max_batch."""
+    w = C[2].scaled(n_layers=2, batch=2, n_cached=0, n_steps=2, reuse="none")
+    _, want = run_oracle(w)
+    _, got = run_gpu(w, max_batch=5)
+    assert_outputs_close(w, got, want, "n_ctx=1")
