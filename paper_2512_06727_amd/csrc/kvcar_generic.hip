@@ -124,7 +124,7 @@ hipError_t launch_qtilde(const AttendParams& p, int dtype, bool qt_f32, hipStrea
 
 // ---------------------------------------------------------------------------------------------
 // plain-ALU attention over rows h_t, one workgroup per (split, sequence, group).
-// Partial written per (b, split, group): for each slot  [m, l, o[0..cv)]  with scores in log2 units.
+// Partial written per (b, split, group): for each slot  [m, l, -, -, o[0..cv)]  with scores in log2 units.
 // ---------------------------------------------------------------------------------------------
 template <typename E>
 __device__ void load_rows(const SideDesc& sd, float* rows, float* zrow, int b, int t0, int nt, int max_seq) {
@@ -239,11 +239,11 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(AttendParams p) {
     }
 
     float* part = p.part + ((size_t)b * p.n_splits + split) * p.part_stride + g.part_off;
-    if (tid < ns) { part[tid * (cv + 2)] = m_s[tid]; part[tid * (cv + 2) + 1] = l_s[tid]; }
+    if (tid < ns) { part[tid * (cv + 4)] = m_s[tid]; part[tid * (cv + 4) + 1] = l_s[tid]; }
 #pragma unroll
     for (int i = 0; i < kGenericAcc; ++i) {
         const int o = tid + i * 256;
-        if (o < n_out) { const int s = o / cv, c = o % cv; part[s * (cv + 2) + 2 + c] = acc[i]; }
+        if (o < n_out) { const int s = o / cv, c = o % cv; part[s * (cv + 4) + 4 + c] = acc[i]; }
     }
 }
 
@@ -265,13 +265,12 @@ hipError_t launch_attend_generic(const AttendParams& p, int dtype, hipStream_t s
 template <typename E>
 __global__ __launch_bounds__(64) void combine_kernel(AttendParams p) {
     __shared__ float olat[kMaxRow];
-    __shared__ float wsplit[64];
     const GroupDesc& g = p.g[blockIdx.z];
     const int b = blockIdx.x, s = blockIdx.y;
     if (s >= g.n_slots) return;
     const int cv = g.v.c;
     const int tid = threadIdx.x;
-    const float* base = p.part + (size_t)b * p.n_splits * p.part_stride + g.part_off + (size_t)s * (cv + 2);
+    const float* base = p.part + (size_t)b * p.n_splits * p.part_stride + g.part_off + (size_t)s * (cv + 4);
     float M = -INFINITY;
     for (int i = 0; i < p.n_splits; ++i) M = fmaxf(M, base[(size_t)i * p.part_stride]);
     float L = 0.f;
@@ -284,12 +283,11 @@ __global__ __launch_bounds__(64) void combine_kernel(AttendParams p) {
         float a = 0.f;
         for (int i = 0; i < p.n_splits; ++i) {
             const float m_i = base[(size_t)i * p.part_stride];
-            if (m_i != -INFINITY) a = fmaf(base[(size_t)i * p.part_stride + 2 + c], exp2f(m_i - M), a);
+            if (m_i != -INFINITY) a = fmaf(base[(size_t)i * p.part_stride + 4 + c], exp2f(m_i - M), a);
         }
         olat[c] = a * inv;
     }
     __syncthreads();
-    (void)wsplit;
     const int col = g.v_col[s];
     for (int k = tid; k < p.d_head; k += 64) {
         float a = g.v.bl ? Elem<E>::load(g.v.bl, col + k) : 0.f;

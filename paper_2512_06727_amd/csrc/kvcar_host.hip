@@ -112,7 +112,11 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     for (int g = 0; g < c.n_kv_heads; ++g) by_src[{resolve(ctx, layer, KVCAR_K, g), resolve(ctx, layer, KVCAR_V, g)}].push_back(g);
 
     plan.groups.clear();
-    bool mfma_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && attend_mfma_available();
+    // MFMA kernels: 16-bit dtype, linear decoders, latent widths that are multiples of 32
+    bool mfma_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && attend_mfma_available() && c.d_head % 8 == 0;
+    int r_all = 0;
+    struct Base { GroupDesc gd; std::vector<int> heads; int src_k, src_v; };
+    std::vector<Base> bases;
     for (auto& kv : by_src) {
         GroupDesc base{};
         int rc = fill_side(ctx, layer, kv.first.first, KVCAR_K, base.k);
@@ -121,30 +125,44 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
         if (rc) return rc;
         if (base.k.c > kMaxRow || base.v.c > kMaxRow || base.k.r > kMaxRow || base.v.r > kMaxRow)
             return fail(ctx, KVCAR_ERR_UNSUPPORTED, "row width above %d", kMaxRow);
-        if (base.k.w1 || base.v.w1 || base.k.r % 32 || base.v.r % 32 || base.k.r > 384 || base.v.r > 384 || c.d_head % 8) mfma_ok = false;
+        if (base.k.w1 || base.v.w1 || base.k.r % 32 || base.v.r % 32 || base.k.r > 384 || base.v.r > 384) mfma_ok = false;
+        r_all = std::max(r_all, std::max(base.k.r, base.v.r));
         // query heads of this (K source, V source) pair, in increasing order
         std::vector<int> heads;
         for (int g : kv.second)
             for (int i = 0; i < gq; ++i) heads.push_back(g * gq + i);
-        // slot capacity of one plain-ALU workgroup: accumulators and LDS
-        int cap = std::min(kMaxSlots, kGenericAcc * 256 / std::max(1, base.v.c));
-        while (cap > 0) {
-            GroupDesc t = base; t.n_slots = cap;
-            if (attend_generic_lds_bytes(t) <= kLdsBudget) break;
-            --cap;
+        for (int j : heads) {
+            const int g = j / gq;
+            if (head_column(ctx, kv.first.first, KVCAR_K, g) < 0 || head_column(ctx, kv.first.second, KVCAR_V, g) < 0)
+                return fail(ctx, KVCAR_ERR_REUSE, "layer %d takes head %d from a layer whose autoencoder does not cover it", layer, g);
         }
-        if (cap < 1) return fail(ctx, KVCAR_ERR_UNSUPPORTED, "rows too wide for the attention kernel");
+        bases.push_back(Base{base, heads, kv.first.first, kv.first.second});
+    }
+    for (auto& bh : bases) {
+        const GroupDesc& base = bh.gd;
+        const std::vector<int>& heads = bh.heads;
+        int cap;
+        if (mfma_ok) {
+            cap = r_all <= 128 ? 32 : 16;      // head blocks one wave can keep accumulators for
+        } else {
+            // slot capacity of one plain-ALU workgroup: accumulators and LDS
+            cap = std::min(kMaxSlots, kGenericAcc * 256 / std::max(1, base.v.c));
+            while (cap > 0) {
+                GroupDesc t = base; t.n_slots = cap;
+                if (attend_generic_lds_bytes(t) <= kLdsBudget) break;
+                --cap;
+            }
+            if (cap < 1) return fail(ctx, KVCAR_ERR_UNSUPPORTED, "rows too wide for the attention kernel");
+        }
         for (size_t h0 = 0; h0 < heads.size(); h0 += cap) {
             GroupDesc gd = base;
             gd.n_slots = (int)std::min<size_t>(cap, heads.size() - h0);
             gd.slots_pad = (gd.n_slots + 15) / 16 * 16;
             for (int s = 0; s < gd.n_slots; ++s) {
                 const int j = heads[h0 + s], g = j / gq;
-                const int kc = head_column(ctx, kv.first.first, KVCAR_K, g);
-                const int vc = head_column(ctx, kv.first.second, KVCAR_V, g);
-                if (kc < 0 || vc < 0)
-                    return fail(ctx, KVCAR_ERR_REUSE, "layer %d takes head %d from a layer whose autoencoder does not cover it", layer, g);
-                gd.q_head[s] = (short)j; gd.k_col[s] = (short)kc; gd.v_col[s] = (short)vc;
+                gd.q_head[s] = (short)j;
+                gd.k_col[s] = (short)head_column(ctx, bh.src_k, KVCAR_K, g);
+                gd.v_col[s] = (short)head_column(ctx, bh.src_v, KVCAR_V, g);
             }
             plan.groups.push_back(gd);
         }
@@ -154,7 +172,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     for (auto& gd : plan.groups) {
         gd.qt_off = qt; gd.part_off = part;
         qt += gd.slots_pad * gd.k.c;
-        part += gd.slots_pad * (gd.v.c + 2);
+        part += gd.slots_pad * (gd.v.c + 4);
     }
     plan.qt_stride = qt;
     plan.part_stride = part;
@@ -166,7 +184,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
         const int target = plan.mfma ? ctx->n_cu * 4 : ctx->n_cu * 2;
         splits = (target + batch * n_groups - 1) / (batch * n_groups);
     }
-    const int tile = plan.mfma ? 128 : kGenericTile;
+    const int tile = plan.mfma ? 128 : kGenericTile;   // tokens per workgroup iteration
     const int max_splits = std::max(1, (n_ctx + tile - 1) / tile);
     splits = std::max(1, std::min(splits, std::min(max_splits, 256)));
     plan.n_splits = splits;

@@ -59,3 +59,12 @@ def test_single_token_context_and_partial_batch():
     _, want = run_oracle(w)
     _, got = run_gpu(w, max_batch=5)
     assert_outputs_close(w, got, want, "n_ctx=1")
+
+
+@pytest.mark.parametrize("name", ["c1-small", "c2-small", "c4-small"])
+def test_plain_alu_kernels_on_16bit_linear(name):
+    """The same cases through the plain-ALU kernels (the MFMA kernels are the default)."""
+    w, kw = CASES[name]
+    _, want = run_oracle(w, gain=20.0, **kw)
+    _, got = run_gpu(w, gain=20.0, force_generic=True, **kw)
+    assert_outputs_close(w, got, want, name + "-generic")
