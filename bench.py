@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV-CAR decode hot path on one MI355X.
+
+A "step" is one decode step of the whole path over one batch: for every layer,
+kvcar_encode_append of the new token's K/V followed by kvcar_decode_attention over the latent
+cache (reuse map applied).  The default workload is the TinyLlama-shaped long-context
+configuration (batch 256, 8192 cached tokens, 22 layers, bf16, linear autoencoder r=128,
+Bernoulli(0.3) head-reuse map).  Inputs are synthetic and resident in HBM before timing starts.
+
+Prints ONE JSON line: tokens/s of the whole job, the HBM roofline of the dominant kernel (the
+MFMA attention kernel, timed live with HIP events recorded around it on its stream in a second
+pass over the same steps) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+
+
+def sources(reuse, layer, which):
+    """Per KV head, the layer whose cache supplies it (nearest earlier layer whose bit is clear)."""
+    out = []
+    for g in range(reuse.shape[2]):
+        m = layer
+        while m > 0 and reuse[m, which, g]:
+            m -= 1
+        out.append(m)
+    return out
+
+
+def algorithmic_latent_bytes(w, reuse, widths, batch, n_ctx, elem):
+    """Bytes of latent rows one decode step must read, per layer: every distinct source
+    layer's K rows and V rows once (P * B * n_ctx * sum of source widths)."""
+    per_layer = []
+    for layer in range(w.n_layers):
+        tot = 0
+        for which in (0, 1):
+            tot += sum(widths[m][which] for m in set(sources(reuse, layer, which)))
+        per_layer.append(elem * batch * n_ctx * tot)
+    return per_layer
+
+
+def cpu_baseline(w, reuse, budget_s: float):
+    """The CPU oracle timed on (layer, sequence) units of the same workload: full-length
+    context, one sequence at a time.  Returns tokens/s extrapolated to the whole job."""
+    import numpy as np
+    import torch
+    from threadpoolctl import threadpool_info
+    from oracle import kvcar_oracle as O
+    from paper_2512_06727_amd import synth
+
+    wo = w.scaled(batch=1)
+    orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, 1, w.max_seq, w.dtype)
+    for layer in range(w.n_layers):
+        orc.set_reuse_map(layer, reuse[layer, 0], reuse[layer, 1])
+    cv = lambda pairs: [(a.double().numpy(), None if b is None else b.double().numpy()) for a, b in pairs]
+    for layer in range(w.n_layers):
+        for which in (0, 1):
+            ae = synth.autoencoder(w, layer, which, reuse)
+            orc.set_autoencoder(layer, which, O.Autoencoder(ae.heads, cv(ae.enc), cv(ae.dec), act=ae.act, slope=ae.slope))
+    # untimed: fill the sequence's caches (prefill is not part of the timed decode step)
+    n_ctx = w.n_cached + 1
+    order = [0, w.n_layers - 1] + list(range(1, w.n_layers - 1))
+    filled = set()
+    t_used, units = 0.0, 0
+    for layer in order:
+        need = {layer} | set(sources(reuse, layer, 0)) | set(sources(reuse, layer, 1))
+        for m in sorted(need - filled):
+            k = synth.kv_tokens(wo, m, 0, 0, 1, 0, w.n_cached).double().numpy()
+            v = synth.kv_tokens(wo, m, 1, 0, 1, 0, w.n_cached).double().numpy()
+            orc.encode_append(m, k, v, 0)
+            filled.add(m)
+        k1 = synth.kv_tokens(wo, layer, 0, 0, 1, w.n_cached, n_ctx).double().numpy()
+        v1 = synth.kv_tokens(wo, layer, 1, 0, 1, w.n_cached, n_ctx).double().numpy()
+        q = synth.queries(wo, layer, 0).double().numpy()
+        t0 = time.perf_counter()
+        orc.encode_append(layer, k1, v1, w.n_cached)          # timed: one decode step of one (layer, sequence)
+        orc.decode_attention(layer, q, n_ctx)
+        t_used += time.perf_counter() - t0
+        units += 1
+        if t_used > budget_s:
+            break
+    per_unit = t_used / units
+    step_s = per_unit * w.n_layers * w.batch                  # extrapolated to all layers and sequences
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [torch.get_num_threads(), 1])
+    return {"value": w.batch / step_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{units} (layer, sequence) units of one decode step at n_ctx={n_ctx}, "
+                      f"{per_unit * 1e3:.1f} ms each, extrapolated to {w.n_layers} layers x {w.batch} sequences"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=16)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", type=int, default=4, help="index into the configuration list (default: long-context TinyLlama)")
+    ap.add_argument("--batch", type=int, default=0, help="override the batch (for quick runs)")
+    ap.add_argument("--cached", type=int, default=0, help="override the cached tokens (for quick runs)")
+    ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--policy", default="", help="P1 (latent shrinks with stored heads) or P2 (full width)")
+    ap.add_argument("--no-reuse", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle leg; 0 skips it")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one process, one MI355X, no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2512_06727_amd import binding, synth
+    from paper_2512_06727_amd.harness import Session
+
+    binding.lib()
+    base = synth.CONFIGS[args.workload]
+    total_steps = args.steps + args.warmup
+    w = base.scaled(n_steps=total_steps)
+    if args.batch:
+        w = w.scaled(batch=args.batch)
+    if args.cached:
+        w = w.scaled(n_cached=args.cached)
+    if args.policy:
+        w = w.scaled(policy=args.policy)
+    if args.no_reuse:
+        w = w.scaled(reuse="none")
+    reuse = synth.reuse_map(w)
+    elem = synth.DTYPE_BYTES[w.dtype]
+
+    ses = Session(w, reuse=reuse, n_splits=args.splits)
+    dev, tdt = ses.dev, ses.tdt
+    widths = [[ses.ae[n][which].latent for which in (0, 1)] for n in range(w.n_layers)]
+    t_fill = time.perf_counter()
+    ses.prefill(0, w.n_cached, chunk=max(1, (1 << 25) // (w.batch * w.d_kv)))
+    torch.cuda.synchronize()
+    t_fill = time.perf_counter() - t_fill
+
+    # inputs of every step, resident in HBM before timing
+    qs, ks, vs = [], [], []
+    for step in range(total_steps):
+        pos = w.n_cached + step
+        qs.append([synth.queries(w, n, step, device=dev).to(tdt) for n in range(w.n_layers)])
+        ks.append([synth.kv_tokens(w, n, 0, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)])
+        vs.append([synth.kv_tokens(w, n, 1, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)])
+    outs = [torch.empty_like(qs[0][n]) for n in range(w.n_layers)]
+    ses.ensure_workspace(w.batch, w.max_seq)
+    ctx, ws = ses.ctx, ses.workspace
+
+    def step_fn(step):
+        pos = w.n_cached + step
+        for n in range(w.n_layers):
+            ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
+            ctx.decode_attention(n, qs[step][n], outs[n], w.batch, pos + 1, ws)
+
+    for step in range(args.warmup):
+        step_fn(step)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for step in range(args.warmup, total_steps):
+        step_fn(step)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    tokens_per_s = w.batch * args.steps / elapsed
+
+    # second pass over the same steps with HIP events around the attention kernel
+    ctx.profile_enable(True)
+    for step in range(args.warmup, total_steps):
+        step_fn(step)
+    attend_ms, n_launch = ctx.profile_read()
+    ctx.profile_enable(False)
+    alg = 0
+    for step in range(args.warmup, total_steps):
+        alg += sum(algorithmic_latent_bytes(w, reuse, widths, w.batch, w.n_cached + step + 1, elem))
+    achieved = alg / (attend_ms * 1e-3) / 1e9
+    plan = ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "attend_mfma_traffic.json.txt")
+    if os.path.exists(tpath) and args.workload == 4 and not (args.batch or args.cached or args.no_reuse or args.policy):
+        try:
+            traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    # capacity: how many cached tokens (batch x context) fit in 288 GB, compressed vs not
+    hbm = 288e9
+    full_tok = 2 * elem * w.n_layers * w.d_kv
+    lat_tok = elem * sum(sum(r) for r in widths)
+    result = {
+        "metric": "decode-attn tokens/s over latent KV cache",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "cached_tokens": w.n_cached, "layers": w.n_layers,
+                   "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_head": w.d_head, "latent": w.latent,
+                   "reuse": w.reuse, "policy": w.policy, "reused_head_fraction": float(reuse[1:].mean()) if w.n_layers > 1 else 0.0,
+                   "splits": plan.n_splits, "mfma": bool(plan.uses_mfma), "prefill_s": t_fill},
+        "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if plan.uses_mfma else "attend_generic_kernel",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "algorithmic_bytes_per_launch": alg / max(1, n_launch),
+                     "avg_launch_ms": attend_ms / max(1, n_launch), "launches": n_launch,
+                     "whole_step_GBs": alg / args.steps / (ms_per_step * 1e-3) / 1e9},
+        "capacity_tokens_288GB": {"uncompressed": int(hbm // full_tok), "latent": int(hbm // lat_tok),
+                                  "bytes_per_token_uncompressed": full_tok, "bytes_per_token_latent": lat_tok},
+    }
+    if args.cpu_seconds > 0:
+        result["cpu_baseline"] = cpu_baseline(w, reuse, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

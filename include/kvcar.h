@@ -175,6 +175,31 @@ int kvcar_decode_attention(kvcar_ctx *ctx, int layer, const void *q, void *out,
                            int batch, int n_ctx, void *workspace, size_t workspace_bytes,
                            void *stream);
 
+/*
+ * What kvcar_decode_attention would launch for (layer, batch, n_ctx) under the current maps,
+ * autoencoders and tuning.  A "group" is the set of query heads of the layer that read the same
+ * (K source layer, V source layer); each distinct source's latent rows are streamed once per group.
+ */
+typedef struct {
+    int uses_mfma;          /* 1 = MFMA kernels, 0 = plain-ALU kernels                          */
+    int n_groups;
+    int n_splits;           /* token-range splits per sequence                                  */
+    int n_launches;         /* attention-kernel launches (groups are batched 8 per launch)      */
+    size_t workspace_bytes;
+    size_t latent_bytes;    /* bytes of latent rows the attention kernel reads for this call    */
+} kvcar_plan_info;
+int kvcar_describe_plan(const kvcar_ctx *ctx, int layer, int batch, int n_ctx, kvcar_plan_info *out);
+
+/*
+ * Optional timing of the attention kernel (the kernel that streams the latent cache).  While
+ * enabled, kvcar_decode_attention records a HIP event before and after that kernel on the caller's
+ * stream.  kvcar_profile_read waits for the recorded events (this is the only call that blocks on
+ * the device), returns the summed kernel time in milliseconds and the number of launches since the
+ * last reset, and resets the counters.
+ */
+int kvcar_profile_enable(kvcar_ctx *ctx, int enable);
+int kvcar_profile_read(kvcar_ctx *ctx, double *attend_ms, long *n_launches);
+
 /* Human-readable name of a status code (static string). */
 const char *kvcar_status_string(int status);
 

@@ -39,6 +39,11 @@ class Tuning(C.Structure):
     _fields_ = [("n_splits", C.c_int), ("force_generic", C.c_int), ("reserved", C.c_int * 6)]
 
 
+class PlanInfo(C.Structure):
+    _fields_ = [("uses_mfma", C.c_int), ("n_groups", C.c_int), ("n_splits", C.c_int), ("n_launches", C.c_int),
+                ("workspace_bytes", C.c_size_t), ("latent_bytes", C.c_size_t)]
+
+
 # every symbol include/kvcar.h declares: name -> (restype, argtypes)
 SYMBOLS = {
     "kvcar_create": (C.c_int, [C.POINTER(Config), C.POINTER(C.c_void_p)]),
@@ -53,6 +58,9 @@ SYMBOLS = {
     "kvcar_encode_append": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "kvcar_decode_attention": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
                                          C.c_size_t, C.c_void_p]),
+    "kvcar_describe_plan": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(PlanInfo)]),
+    "kvcar_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
+    "kvcar_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_long)]),
     "kvcar_status_string": (C.c_char_p, [C.c_int]),
     "kvcar_last_error": (C.c_char_p, [C.c_void_p]),
 }
@@ -161,6 +169,20 @@ class Context:
         n = C.c_size_t(0)
         self._check(lib().kvcar_workspace_bytes(self._h, batch, n_ctx, C.byref(n)))
         return n.value
+
+    def describe_plan(self, layer: int, batch: int, n_ctx: int) -> PlanInfo:
+        info = PlanInfo()
+        self._check(lib().kvcar_describe_plan(self._h, layer, batch, n_ctx, C.byref(info)))
+        return info
+
+    def profile_enable(self, enable: bool):
+        self._check(lib().kvcar_profile_enable(self._h, 1 if enable else 0))
+
+    def profile_read(self):
+        """(summed attention-kernel milliseconds, launches) since the last read; blocks on the events."""
+        ms, n = C.c_double(0.0), C.c_long(0)
+        self._check(lib().kvcar_profile_read(self._h, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     def encode_append(self, layer: int, k_new, v_new, batch: int, pos0: int, t_new: int):
         self._check(lib().kvcar_encode_append(self._h, layer, _ptr(k_new), _ptr(v_new), batch, pos0, t_new, _stream()))

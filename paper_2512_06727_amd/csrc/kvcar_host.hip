@@ -38,6 +38,9 @@ struct kvcar_ctx {
     kvcar_tuning tun{};
     int n_cu = 256;
     std::string err;
+    bool profiling = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_pool;   // events created so far
+    size_t ev_used = 0;                                        // pairs recorded since the last read
 
     uint8_t& reuse_at(int layer, int which, int g) { return reuse[((size_t)layer * 2 + which) * cfg.n_kv_heads + g]; }
     uint8_t reuse_at(int layer, int which, int g) const { return reuse[((size_t)layer * 2 + which) * cfg.n_kv_heads + g]; }
@@ -231,6 +234,8 @@ int kvcar_create(const kvcar_config* cfg, kvcar_ctx** out) {
 }
 
 int kvcar_destroy(kvcar_ctx* ctx) {
+    if (ctx)
+        for (auto& e : ctx->ev_pool) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
     delete ctx;
     return KVCAR_OK;
 }
@@ -419,10 +424,63 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
         p.qt_stride = plan.qt_stride; p.part_stride = plan.part_stride;
         p.scale_log2e = ctx->scale * kLog2e;
         hipError_t e = launch_qtilde(p, c.dtype, !plan.mfma, st);
+        std::pair<hipEvent_t, hipEvent_t>* ev = nullptr;
+        if (e == hipSuccess && ctx->profiling) {
+            if (ctx->ev_used == ctx->ev_pool.size()) {
+                hipEvent_t a, b2;
+                e = hipEventCreate(&a);
+                if (e == hipSuccess) e = hipEventCreate(&b2);
+                if (e == hipSuccess) ctx->ev_pool.emplace_back(a, b2);
+            }
+            if (e == hipSuccess) { ev = &ctx->ev_pool[ctx->ev_used++]; e = hipEventRecord(ev->first, st); }
+        }
         if (e == hipSuccess) e = plan.mfma ? launch_attend_mfma(p, c.dtype, st) : launch_attend_generic(p, c.dtype, st);
+        if (e == hipSuccess && ev) e = hipEventRecord(ev->second, st);
         if (e == hipSuccess) e = launch_combine(p, c.dtype, st);
         if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
     }
+    return KVCAR_OK;
+}
+
+int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, kvcar_plan_info* out) {
+    int rc = check_layer(ctx, layer);
+    if (rc) return rc;
+    if (!out) return fail(ctx, KVCAR_ERR_ARG, "null output");
+    if (batch < 1 || batch > ctx->cfg.max_batch || n_ctx < 1 || n_ctx > ctx->cfg.max_seq)
+        return fail(ctx, KVCAR_ERR_CAPACITY, "batch %d / n_ctx %d outside [1,%d] / [1,%d]", batch, n_ctx, ctx->cfg.max_batch, ctx->cfg.max_seq);
+    Plan plan;
+    rc = build_plan(ctx, layer, batch, n_ctx, plan);
+    if (rc) return rc;
+    out->uses_mfma = plan.mfma ? 1 : 0;
+    out->n_groups = (int)plan.groups.size();
+    out->n_splits = plan.n_splits;
+    out->n_launches = (int)((plan.groups.size() + kMaxGroups - 1) / kMaxGroups);
+    out->workspace_bytes = plan.total_bytes;
+    size_t lat = 0;
+    for (auto& g : plan.groups) lat += (size_t)(g.k.r + g.v.r);
+    out->latent_bytes = lat * dtype_size(ctx->cfg.dtype) * batch * n_ctx;
+    return KVCAR_OK;
+}
+
+int kvcar_profile_enable(kvcar_ctx* ctx, int enable) {
+    if (!ctx) return KVCAR_ERR_ARG;
+    ctx->profiling = enable != 0;
+    return KVCAR_OK;
+}
+
+int kvcar_profile_read(kvcar_ctx* ctx, double* attend_ms, long* n_launches) {
+    if (!ctx || !attend_ms || !n_launches) return KVCAR_ERR_ARG;
+    double total = 0.0;
+    for (size_t i = 0; i < ctx->ev_used; ++i) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(ctx->ev_pool[i].second);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ctx->ev_pool[i].first, ctx->ev_pool[i].second);
+        if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "event read failed: %s", hipGetErrorString(e));
+        total += ms;
+    }
+    *attend_ms = total;
+    *n_launches = (long)ctx->ev_used;
+    ctx->ev_used = 0;
     return KVCAR_OK;
 }
 
