@@ -107,7 +107,9 @@ typedef struct {
 typedef struct {
     int n_splits;       /* token-range splits per sequence in decode_attention; 0 = automatic */
     int force_generic;  /* 1 = use the plain-ALU kernels even where an MFMA kernel exists     */
-    int reserved[6];
+    int tile_order;     /* MFMA attention: 0 = library default, 1 = each split owns a contiguous
+                           token range, 2 = 128-token tiles dealt round-robin over the splits    */
+    int reserved[5];
 } kvcar_tuning;
 
 /* Create / destroy a context.  ERR_ARG on null pointers, ERR_SHAPE on non-positive sizes or

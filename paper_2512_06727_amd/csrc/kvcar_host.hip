@@ -343,7 +343,7 @@ int kvcar_bind_cache(kvcar_ctx* ctx, int layer, int which, void* dev, size_t byt
 
 int kvcar_set_tuning(kvcar_ctx* ctx, const kvcar_tuning* t) {
     if (!ctx || !t) return KVCAR_ERR_ARG;
-    if (t->n_splits < 0) return fail(ctx, KVCAR_ERR_ARG, "negative n_splits");
+    if (t->n_splits < 0 || t->tile_order < 0 || t->tile_order > 2) return fail(ctx, KVCAR_ERR_ARG, "bad tuning value");
     ctx->tun = *t;
     return KVCAR_OK;
 }
@@ -423,6 +423,7 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
         p.n_q_heads = c.n_q_heads; p.d_head = c.d_head; p.max_seq = c.max_seq;
         p.qt_stride = plan.qt_stride; p.part_stride = plan.part_stride;
         p.scale_log2e = ctx->scale * kLog2e;
+        p.tile_order = ctx->tun.tile_order == 2 ? 1 : 0;
         hipError_t e = launch_qtilde(p, c.dtype, !plan.mfma, st);
         std::pair<hipEvent_t, hipEvent_t>* ev = nullptr;
         if (e == hipSuccess && ctx->profiling) {

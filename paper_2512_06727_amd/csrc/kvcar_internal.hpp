@@ -55,6 +55,7 @@ struct AttendParams {
     int qt_stride;        // absorbed-query elements per sequence (all groups)
     int part_stride;      // partial floats per (sequence, split) (all groups)
     float scale_log2e;    // softmax scale * log2(e)
+    int tile_order;       // MFMA kernel: 0 = contiguous token range per split, 1 = tiles dealt round-robin
 };
 
 struct EncodeSide {
