@@ -80,6 +80,10 @@ hipError_t launch_attend_generic(const AttendParams& p, int dtype, hipStream_t s
 hipError_t launch_combine(const AttendParams& p, int dtype, hipStream_t stream);
 size_t attend_generic_lds_bytes(const GroupDesc& g);
 
+// MFMA encoder (16-bit dtypes, widths that are multiples of 32).
+bool encode_mfma_supported(const EncodeParams& p, int dtype);
+hipError_t launch_encode_mfma(const EncodeParams& p, int dtype, hipStream_t stream);
+
 // MFMA path (16-bit dtypes, linear decoders, widths that are multiples of 32).
 bool attend_mfma_available();
 hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stream);
