@@ -106,9 +106,15 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the batch (for quick runs)")
     ap.add_argument("--cached", type=int, default=0, help="override the cached tokens (for quick runs)")
     ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--tile-order", type=int, default=0, help="0 library default, 1 contiguous token range per split, 2 tiles dealt round-robin")
     ap.add_argument("--policy", default="", help="P1 (latent shrinks with stored heads) or P2 (full width)")
     ap.add_argument("--no-reuse", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle leg; 0 skips it")
+    ap.add_argument("--fill", default="encode", choices=["encode", "random"],
+                    help="encode: caches filled by kvcar_encode_append of seeded K/V (default); random: torch.randn latents and "
+                         "inputs (profiling runs only: same traffic, far fewer helper kernels)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one process, one MI355X, no collectives); run with --gpus 1", file=sys.stderr)
@@ -134,11 +140,18 @@ def main():
     reuse = synth.reuse_map(w)
     elem = synth.DTYPE_BYTES[w.dtype]
 
-    ses = Session(w, reuse=reuse, n_splits=args.splits)
+    ses = Session(w, reuse=reuse, n_splits=args.splits, tile_order=args.tile_order)
     dev, tdt = ses.dev, ses.tdt
     widths = [[ses.ae[n][which].latent for which in (0, 1)] for n in range(w.n_layers)]
     t_fill = time.perf_counter()
-    ses.prefill(0, w.n_cached, chunk=max(1, (1 << 25) // (w.batch * w.d_kv)))
+    if args.fill == "encode":
+        ses.prefill(0, w.n_cached, chunk=max(1, (1 << 25) // (w.batch * w.d_kv)))
+    else:
+        torch.manual_seed(w.seed)
+        for row in ses.caches:
+            for c in row:
+                if c is not None:
+                    c.normal_(0.0, 0.32)
     torch.cuda.synchronize()
     t_fill = time.perf_counter() - t_fill
 
@@ -146,9 +159,14 @@ def main():
     qs, ks, vs = [], [], []
     for step in range(total_steps):
         pos = w.n_cached + step
-        qs.append([synth.queries(w, n, step, device=dev).to(tdt) for n in range(w.n_layers)])
-        ks.append([synth.kv_tokens(w, n, 0, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)])
-        vs.append([synth.kv_tokens(w, n, 1, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)])
+        if args.fill == "encode":
+            qs.append([synth.queries(w, n, step, device=dev).to(tdt) for n in range(w.n_layers)])
+            ks.append([synth.kv_tokens(w, n, 0, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)])
+            vs.append([synth.kv_tokens(w, n, 1, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)])
+        else:
+            qs.append([torch.randn(w.batch, w.n_q_heads, w.d_head, device=dev).to(tdt) for n in range(w.n_layers)])
+            ks.append([torch.randn(w.batch, 1, w.d_kv, device=dev).to(tdt) for n in range(w.n_layers)])
+            vs.append([torch.randn(w.batch, 1, w.d_kv, device=dev).to(tdt) for n in range(w.n_layers)])
     outs = [torch.empty_like(qs[0][n]) for n in range(w.n_layers)]
     ses.ensure_workspace(w.batch, w.max_seq)
     ctx, ws = ses.ctx, ses.workspace
@@ -189,6 +207,14 @@ def main():
         except Exception:
             traffic = None
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)          # reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
+
     # capacity: how many cached tokens (batch x context) fit in 288 GB, compressed vs not
     hbm = 288e9
     full_tok = 2 * elem * w.n_layers * w.d_kv
@@ -205,7 +231,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": w.dtype,
-        "data": "synthetic",
+        "data": "synthetic" if args.fill == "encode" else "synthetic (random latents, profiling fill)",
         "config": {"workload": w.name, "batch": w.batch, "cached_tokens": w.n_cached, "layers": w.n_layers,
                    "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_head": w.d_head, "latent": w.latent,
                    "reuse": w.reuse, "policy": w.policy, "reused_head_fraction": float(reuse[1:].mean()) if w.n_layers > 1 else 0.0,

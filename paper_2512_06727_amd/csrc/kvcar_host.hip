@@ -184,7 +184,8 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     const int n_groups = (int)plan.groups.size();
     int splits = ctx->tun.n_splits;
     if (splits <= 0) {
-        const int target = plan.mfma ? ctx->n_cu * 4 : ctx->n_cu * 2;
+        // the MFMA kernel runs best with about one long-lived workgroup per compute unit
+        const int target = plan.mfma ? ctx->n_cu : ctx->n_cu * 2;
         splits = (target + batch * n_groups - 1) / (batch * n_groups);
     }
     const int tile = plan.mfma ? 128 : kGenericTile;   // tokens per workgroup iteration
@@ -426,7 +427,8 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
         p.qt_stride = plan.qt_stride; p.part_stride = plan.part_stride;
         p.scale_log2e = ctx->scale * kLog2e;
         p.tile_order = ctx->tun.tile_order == 2 ? 1 : 0;
-        hipError_t e = launch_qtilde(p, c.dtype, !plan.mfma, st);
+        const bool proj = plan.mfma && proj_mfma_supported(p, c.dtype);
+        hipError_t e = proj ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma, st);
         std::pair<hipEvent_t, hipEvent_t>* ev = nullptr;
         if (e == hipSuccess && ctx->profiling) {
             if (ctx->ev_used == ctx->ev_pool.size()) {
@@ -439,7 +441,7 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
         }
         if (e == hipSuccess) e = plan.mfma ? launch_attend_mfma(p, c.dtype, st) : launch_attend_generic(p, c.dtype, st);
         if (e == hipSuccess && ev) e = hipEventRecord(ev->second, st);
-        if (e == hipSuccess) e = launch_combine(p, c.dtype, st);
+        if (e == hipSuccess) e = proj ? launch_combine_mfma(p, c.dtype, st) : launch_combine(p, c.dtype, st);
         if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
     }
     return KVCAR_OK;

@@ -84,6 +84,11 @@ size_t attend_generic_lds_bytes(const GroupDesc& g);
 bool encode_mfma_supported(const EncodeParams& p, int dtype);
 hipError_t launch_encode_mfma(const EncodeParams& p, int dtype, hipStream_t stream);
 
+// MFMA versions of the absorbed-query prologue and the merge + output epilogue.
+bool proj_mfma_supported(const AttendParams& p, int dtype);
+hipError_t launch_qtilde_mfma(const AttendParams& p, int dtype, hipStream_t stream);
+hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t stream);
+
 // MFMA path (16-bit dtypes, linear decoders, widths that are multiples of 32).
 bool attend_mfma_available();
 hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stream);

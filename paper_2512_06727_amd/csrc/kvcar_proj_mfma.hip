@@ -1,0 +1,285 @@
+// MFMA kernels for the two small projections around the attention kernel (gfx950, 16-bit dtypes):
+//
+//   absorbed queries   qt[(b,slot), c]  = scale*log2(e) * sum_k q[(b,slot), k] * Wl_K[c, col+k]
+//   output epilogue    out[(b,slot), k] = sum_c o[(b,slot), c] * Wl_V[c, col+k] + bl_V[col+k]
+//                      with o = the split partials merged and normalised
+//
+// i.e. the last (linear) decoder layer applied to the query instead of to every cached key row,
+// and to the softmax-weighted latent sum instead of to every cached value row ("Network
+// Architecture", 2nd paragraph, restated by linearity).  Query heads that share a KV head share the
+// 64-column slice of the decoder matrix, so rows (sequence, head) are batched per KV head into
+// 16-row MFMA blocks: [B*heads, d_head] x [d_head, r] and [B*heads, r] x [r, d_head].
+#include "kvcar_device.hpp"
+
+namespace kvcar {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
+
+template <typename E> struct PMma;
+template <> struct PMma<BF16> {
+    static __device__ __forceinline__ f32x4_t mfma(u32x4_t a, u32x4_t b, f32x4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint16_t to16(float v) { return f32_to_bf16_bits(v); }
+    static __device__ __forceinline__ float from16(uint16_t b) { return bf16_bits_to_f32(b); }
+};
+template <> struct PMma<F16> {
+    static __device__ __forceinline__ f32x4_t mfma(u32x4_t a, u32x4_t b, f32x4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint16_t to16(float v) { _Float16 h = (_Float16)v; return __builtin_bit_cast(uint16_t, h); }
+    static __device__ __forceinline__ float from16(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+};
+
+// Slots of a group that share a KV head are consecutive and share a column offset.  Finds the
+// `which`-th such run of `col`; returns false if there are fewer runs.
+__device__ __forceinline__ bool find_segment(const short* col, int n_slots, int which, int& s0, int& len) {
+    int seg = -1, start = 0;
+    for (int s = 0; s <= n_slots; ++s) {
+        if (s == n_slots || (s > 0 && col[s] != col[s - 1])) {
+            if (s > 0) {
+                ++seg;
+                if (seg == which) { s0 = start; len = s - start; return true; }
+            }
+            start = s;
+        }
+    }
+    return false;
+}
+
+// ---------------------------------------------------------------------------------------------
+// absorbed queries.  grid = (row blocks of 64, segment, group); a wave owns 16 rows (sequence, head).
+// Both MFMA operands come straight from global memory: a lane needs 8 consecutive k of one query
+// row (A) and 8 consecutive k of one decoder-matrix row (B), both contiguous.
+// Segment index == number of segments is the zero-fill of the group's padding slots.
+// ---------------------------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(256) void qtilde_mfma_kernel(AttendParams p) {
+    const GroupDesc& g = p.g[blockIdx.z];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, lg = lane >> 4;
+    const int rk = g.k.r;
+    int s0 = 0, len = 0;
+    if (!find_segment(g.k_col, g.n_slots, blockIdx.y, s0, len)) {
+        int dummy0, dummy1;
+        const bool is_pad_pass = (blockIdx.y == 0) ? false : find_segment(g.k_col, g.n_slots, blockIdx.y - 1, dummy0, dummy1);
+        if (!is_pad_pass || g.slots_pad == g.n_slots) return;
+        // zero the padding slots of every sequence (rows of qt the attention kernel loads but ignores)
+        const int pad = g.slots_pad - g.n_slots;
+        const int chunks = pad * rk / 8;                          // 16-byte chunks per sequence
+        const int total = p.batch * chunks;
+        for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+            const int b = i / chunks, c = i - b * chunks;
+            char* dst = static_cast<char*>(p.qt) + ((size_t)b * p.qt_stride + g.qt_off + (size_t)g.n_slots * rk) * 2 + (size_t)c * 16;
+            *reinterpret_cast<u32x4_t*>(dst) = u32x4_t{0u, 0u, 0u, 0u};
+        }
+        return;
+    }
+    const int rows = p.batch * len;
+    const int row0 = (blockIdx.x * 4 + wave) * 16;
+    if (row0 >= rows) return;
+    const int col = g.k_col[s0];
+    const int dh = p.d_head;
+
+    // A operand: query rows
+    const int arow = row0 + l16;
+    const int ab = arow / len, ai = arow - ab * len;
+    const bool a_ok = arow < rows;
+    const char* qrow = static_cast<const char*>(p.q) + ((size_t)(a_ok ? ab : 0) * p.n_q_heads + g.q_head[s0 + (a_ok ? ai : 0)]) * dh * 2;
+    // result rows of this lane
+    size_t orow[4];
+    bool ook[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int r = row0 + 4 * lg + v;
+        ook[v] = r < rows;
+        const int b = r / len, i = r - b * len;
+        orow[v] = (size_t)b * p.qt_stride + g.qt_off + (size_t)(s0 + i) * rk;
+    }
+    uint16_t* qt = static_cast<uint16_t*>(p.qt);
+    const char* wl = static_cast<const char*>(g.k.wl);
+    for (int nb = 0; nb < (rk >> 4); ++nb) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        const char* wrow = wl + ((size_t)(nb * 16 + l16) * g.k.in_width + col) * 2;
+        for (int k0 = 0; k0 < dh; k0 += 32) {
+            u32x4_t a = {0u, 0u, 0u, 0u};
+            if (a_ok) a = *reinterpret_cast<const u32x4_t*>(qrow + (k0 + 8 * lg) * 2);
+            const u32x4_t bw = *reinterpret_cast<const u32x4_t*>(wrow + (k0 + 8 * lg) * 2);
+            acc = PMma<E>::mfma(a, bw, acc);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (ook[v]) qt[orow[v] + nb * 16 + l16] = PMma<E>::to16(acc[v] * p.scale_log2e);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// split merge + output epilogue.  grid = (row blocks of 64, segment, group).  The decoder-matrix
+// slice [r, d_head] of the segment's KV head is staged in LDS once per workgroup and read with the
+// transposing load (a lane needs 8 consecutive c of one output column).  The merged latent sums are
+// fed as a hi + lo pair of 16-bit values so that the product is accurate to ~2^-17.
+// ---------------------------------------------------------------------------------------------
+constexpr int kCombMaxSplits = 64;
+
+template <typename E, int NBO>
+__global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const GroupDesc& g = p.g[blockIdx.z];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, lg = lane >> 4;
+    int s0 = 0, len = 0;
+    if (!find_segment(g.v_col, g.n_slots, blockIdx.y, s0, len)) return;
+    const int rows = p.batch * len;
+    if (blockIdx.x * 64 >= rows) return;
+    const int rv = g.v.r, dh = p.d_head;
+    const int col = g.v_col[s0];
+    const int stride_w = 2 * dh + 32;
+
+    // stage Wl_V[:, col .. col+d_head) : rv rows of d_head elements
+    {
+        const int cpr = dh >> 3;
+        const int total = rv * cpr;
+        const char* src = static_cast<const char*>(g.v.wl);
+        for (int f = threadIdx.x; f < total; f += 256) {
+            const int row = f / cpr, ch = f - row * cpr;
+            *reinterpret_cast<u32x4_t*>(lds + row * stride_w + ch * 16) =
+                *reinterpret_cast<const u32x4_t*>(src + ((size_t)row * g.v.in_width + col) * 2 + ch * 16);
+        }
+    }
+    __syncthreads();
+
+    const int row0 = (blockIdx.x * 4 + wave) * 16;
+    if (row0 >= rows) return;
+    // A operand row of this lane: merge weights of its splits
+    const int arow = row0 + l16;
+    const bool a_ok = arow < rows;
+    const int ab = a_ok ? arow / len : 0, ai = a_ok ? arow - ab * len : 0;
+    const int pstride = rv + 4;
+    const float* prow = p.part + (size_t)ab * p.n_splits * p.part_stride + g.part_off + (size_t)(s0 + ai) * pstride;
+    float M = -INFINITY;
+    for (int i = 0; i < p.n_splits; ++i) M = fmaxf(M, prow[(size_t)i * p.part_stride]);
+    float L = 0.f;
+    for (int i = 0; i < p.n_splits; ++i) {
+        const float m_i = prow[(size_t)i * p.part_stride];
+        if (m_i != -INFINITY) L += prow[(size_t)i * p.part_stride + 1] * exp2f(m_i - M);
+    }
+    const float inv = 1.f / L;
+
+    f32x4_t acc[NBO];
+#pragma unroll
+    for (int nb = 0; nb < NBO; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const int nbo = dh >> 4;
+    for (int k0 = 0; k0 < rv; k0 += 32) {
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = 0.f;
+        if (a_ok) {
+            for (int i = 0; i < p.n_splits; ++i) {
+                const float m_i = prow[(size_t)i * p.part_stride];
+                if (m_i == -INFINITY) continue;
+                const float wgt = exp2f(m_i - M) * inv;
+                const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(prow + (size_t)i * p.part_stride + 4 + k0 + 8 * lg);
+                const f32x4_t x1 = *reinterpret_cast<const f32x4_t*>(prow + (size_t)i * p.part_stride + 8 + k0 + 8 * lg);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { o[e] = fmaf(x0[e], wgt, o[e]); o[4 + e] = fmaf(x1[e], wgt, o[4 + e]); }
+            }
+        }
+        unsigned hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint16_t h0 = PMma<E>::to16(o[2 * e]), h1 = PMma<E>::to16(o[2 * e + 1]);
+            const uint16_t l0 = PMma<E>::to16(o[2 * e] - PMma<E>::from16(h0)), l1 = PMma<E>::to16(o[2 * e + 1] - PMma<E>::from16(h1));
+            hi[e] = (unsigned)h0 | ((unsigned)h1 << 16);
+            lo[e] = (unsigned)l0 | ((unsigned)l1 << 16);
+        }
+        const u32x4_t ah = {hi[0], hi[1], hi[2], hi[3]}, al = {lo[0], lo[1], lo[2], lo[3]};
+        const char* wrow = lds + (k0 + 8 * lg + (l16 >> 2)) * stride_w + (l16 & 3) * 8;
+#pragma unroll
+        for (int nb = 0; nb < NBO; ++nb) {
+            if (nb < nbo) {
+                const s16x4_t t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(wrow + nb * 32));
+                const s16x4_t t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(wrow + nb * 32 + 4 * stride_w));
+                const u32x2_t a0 = __builtin_bit_cast(u32x2_t, t0), a1 = __builtin_bit_cast(u32x2_t, t1);
+                const u32x4_t bw = {a0[0], a0[1], a1[0], a1[1]};
+                acc[nb] = PMma<E>::mfma(ah, bw, acc[nb]);
+                acc[nb] = PMma<E>::mfma(al, bw, acc[nb]);
+            }
+        }
+    }
+    // epilogue: bias, one rounding, store; this lane holds output column 16*nb + l16 of rows 4*lg + v
+    uint16_t* out = static_cast<uint16_t*>(p.out);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int r = row0 + 4 * lg + v;
+        if (r >= rows) continue;
+        const int b = r / len, i = r - b * len;
+        const size_t base = ((size_t)b * p.n_q_heads + g.q_head[s0 + i]) * dh;
+#pragma unroll
+        for (int nb = 0; nb < NBO; ++nb) {
+            if (nb < nbo) {
+                const int k = nb * 16 + l16;
+                const float bias = g.v.bl ? Elem<E>::load(g.v.bl, col + k) : 0.f;
+                out[base + k] = PMma<E>::to16(acc[nb][v] + bias);
+            }
+        }
+    }
+}
+
+// d_head a multiple of 32 (k-steps of the query product, column blocks of the output), up to 128;
+// latent widths multiples of 32.
+bool proj_mfma_supported(const AttendParams& p, int dtype) {
+    if (dtype == KVCAR_F32 || p.d_head % 32 || p.d_head > 128 || p.n_splits > kCombMaxSplits) return false;
+    for (int i = 0; i < p.n_groups; ++i)
+        if (p.g[i].k.w1 || p.g[i].v.w1 || p.g[i].k.r % 32 || p.g[i].v.r % 32) return false;
+    return true;
+}
+
+static int max_segments(const AttendParams& p, bool use_k, int& max_len) {
+    int mx = 0;
+    max_len = 1;
+    for (int i = 0; i < p.n_groups; ++i) {
+        const short* col = use_k ? p.g[i].k_col : p.g[i].v_col;
+        int segs = 0, run = 0;
+        for (int s = 0; s < p.g[i].n_slots; ++s) {
+            if (s == 0 || col[s] != col[s - 1]) { ++segs; run = 0; }
+            ++run;
+            max_len = run > max_len ? run : max_len;
+        }
+        mx = segs > mx ? segs : mx;
+    }
+    return mx;
+}
+
+hipError_t launch_qtilde_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
+    int max_len;
+    const int segs = max_segments(p, true, max_len);
+    dim3 grid((p.batch * max_len + 63) / 64, segs + 1, p.n_groups);     // +1: zero-fill of padding slots
+    if (dtype == KVCAR_BF16) hipLaunchKernelGGL(qtilde_mfma_kernel<BF16>, grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL(qtilde_mfma_kernel<F16>, grid, dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
+    static bool attr[2] = {false, false};
+    int max_len, rmax = 0;
+    const int segs = max_segments(p, false, max_len);
+    for (int i = 0; i < p.n_groups; ++i) rmax = p.g[i].v.r > rmax ? p.g[i].v.r : rmax;
+    const size_t lds = (size_t)rmax * (2 * p.d_head + 32) + 1024;
+    dim3 grid((p.batch * max_len + 63) / 64, segs, p.n_groups);
+    const int e = dtype == KVCAR_BF16 ? 0 : 1;
+    auto kern = e == 0 ? combine_mfma_kernel<BF16, 8> : combine_mfma_kernel<F16, 8>;
+    if (!attr[e]) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (err != hipSuccess) return err;
+        attr[e] = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace kvcar
