@@ -1,0 +1,180 @@
+"""Bit-exact GPU checks: latent-cache indexing of encode+append and reuse-aware addressing of
+decode attention.  Inputs are chosen so that every arithmetic step is exact in the cache dtype:
+the library's bytes must equal the oracle's byte for byte."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvcar_oracle as O
+from paper_2512_06727_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+TDT = synth.TORCH_DTYPE
+
+
+def selection_autoencoder(heads, d_head, latent, stride):
+    """Encoder that copies input column stride*c into latent column c, decoder that puts it
+    back; all other decoder outputs are zero.  Every product is x*1 or x*0: exact."""
+    width = len(heads) * d_head
+    enc = np.zeros((width, latent), np.float32)
+    dec = np.zeros((latent, width), np.float32)
+    for c in range(latent):
+        enc[stride * c, c] = 1.0
+        dec[c, stride * c] = 1.0
+    return enc, dec
+
+
+class Rig:
+    """A library context and an oracle configured identically from explicit weights."""
+
+    def __init__(self, n_layers, hq, hkv, dh, batch, max_seq, dtype, reuse, latent_per_head, stride, **tuning):
+        self.dev = torch.device("cuda:0")
+        self.dtype, self.tdt = dtype, TDT[dtype]
+        self.shape = (n_layers, hq, hkv, dh, batch, max_seq)
+        self.ctx = binding.Context(n_layers, hq, hkv, dh, batch, max_seq, dtype)
+        self.ctx.set_tuning(**tuning)
+        self.orc = O.KVCAROracle(n_layers, hq, hkv, dh, batch, max_seq, dtype)
+        self.caches, self.latent = {}, {}
+        for n in range(n_layers):
+            self.ctx.set_reuse_map(n, reuse[n, 0], reuse[n, 1])
+            self.orc.set_reuse_map(n, reuse[n, 0], reuse[n, 1])
+        for n in range(n_layers):
+            for which in (0, 1):
+                heads = [g for g in range(hkv) if not reuse[n, which, g]]
+                lat = latent_per_head * len(heads)
+                self.latent[(n, which)] = lat
+                enc, dec = selection_autoencoder(heads, dh, lat, stride)
+                self.orc.set_autoencoder(n, which, O.Autoencoder(heads, [(enc, None)], [(dec, None)]))
+                te = torch.from_numpy(enc).to(self.dev, self.tdt)
+                td = torch.from_numpy(dec).to(self.dev, self.tdt)
+                self.ctx.set_autoencoder(n, which, len(heads) * dh, 0, lat, "none", [(te, None)], [(td, None)])
+                nbytes = self.ctx.cache_bytes(n, which)
+                if nbytes:
+                    c = torch.full((nbytes // 2,), 0x7F7F, dtype=torch.int16, device=self.dev) if dtype != "f32" else \
+                        torch.full((nbytes // 4,), 0x7F7F7F7F, dtype=torch.int32, device=self.dev)
+                    self.caches[(n, which)] = c
+                    self.ctx.bind_cache(n, which, c)
+
+    def append(self, layer, k, v, pos0):
+        """k, v: float64 numpy [b, t, D_kv] of exactly representable values."""
+        b, t, _ = k.shape
+        self.orc.encode_append(layer, k, v, pos0)
+        tk = torch.from_numpy(k).to(self.dev, self.tdt).contiguous()
+        tv = torch.from_numpy(v).to(self.dev, self.tdt).contiguous()
+        self.ctx.encode_append(layer, tk, tv, b, pos0, t)
+
+    def cache_bits(self, layer, which):
+        n_layers, hq, hkv, dh, batch, max_seq = self.shape
+        c = self.caches[(layer, which)].cpu().numpy()
+        c = c.view(np.uint16) if self.dtype != "f32" else c.view(np.uint32)
+        return c.reshape(batch, max_seq, self.latent[(layer, which)])
+
+
+def ids(layer, which, b, t, cols):
+    """Small integers in [-125, 125]: exact in bf16, fp16 and fp32."""
+    return ((layer * 37 + which * 101 + b * 53 + t * 29 + cols * 7) % 251 - 125).astype(np.float64)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("force_generic", [False, True])
+def test_cache_bytes_after_scripted_appends(dtype, force_generic):
+    """Bulk prefill, single-token appends, a bulk append at an offset for a sub-batch and an
+    overwrite: afterwards the raw cache bytes equal the oracle's, and rows never written keep
+    the sentinel pattern."""
+    hkv, dh, hq, B, L = 4, 64, 32, 5, 300
+    reuse = np.zeros((3, 2, hkv), dtype=bool)
+    reuse[1, :, 2] = True                    # layer 1 stores heads 0,1,3: latent 96
+    reuse[2, 0, 0] = reuse[2, 0, 3] = True   # layer 2 stores K heads 1,2 (latent 64) and all V heads
+    rig = Rig(3, hq, hkv, dh, B, L, dtype, reuse, latent_per_head=32, stride=2, force_generic=force_generic)
+    cols = np.arange(hkv * dh)
+
+    def kv(layer, b0, b1, t0, t1):
+        out = []
+        for which in (0, 1):
+            x = np.zeros((b1 - b0, t1 - t0, hkv * dh))
+            for b in range(b0, b1):
+                for t in range(t0, t1):
+                    x[b - b0, t - t0] = ids(layer, which, b, t, cols)
+            out.append(x)
+        return out
+
+    written = np.zeros((3, B, L), dtype=bool)
+    for layer in range(3):
+        k, v = kv(layer, 0, B, 0, 131); rig.append(layer, k, v, 0); written[layer, :, :131] = True        # bulk, ragged size
+        for t in (131, 132, 133):                                                                          # decode-style appends
+            k, v = kv(layer, 0, B, t, t + 1); rig.append(layer, k, v, t); written[layer, :, t] = True
+        k, v = kv(layer, 0, 3, 200, 267); rig.append(layer, k, v, 200); written[layer, :3, 200:267] = True  # sub-batch at an offset
+        k, v = kv(layer, 0, 2, 299, 300); rig.append(layer, k, v, 299); written[layer, :2, 299] = True      # last row of the cache
+        k, v = kv(layer, 0, B, 7, 9); rig.append(layer, k, v, 7)                                            # overwrite, same values
+    torch.cuda.synchronize()
+    sentinel = 0x7F7F if dtype != "f32" else 0x7F7F7F7F
+    for layer in range(3):
+        for which in (0, 1):
+            got = rig.cache_bits(layer, which)
+            want = O.dtype_bits(np.nan_to_num(rig.orc.Z[(layer, which)]), dtype)
+            w = written[layer]
+            np.testing.assert_array_equal(got[w], want[w])
+            assert (got[~w] == sentinel).all()
+            # and the stored values are the ids of the selected columns of the stored heads
+            heads = rig.orc.ae[(layer, which)].heads
+            src_cols = np.concatenate([g * dh + np.arange(dh) for g in heads])[::2]
+            np.testing.assert_array_equal(rig.orc.Z[(layer, which)][1, 5], ids(layer, which, 1, 5, src_cols))
+
+
+@pytest.mark.parametrize("dtype,force_generic,n_splits", [("bf16", False, 0), ("bf16", False, 3), ("f16", False, 2),
+                                                           ("bf16", True, 2), ("f32", False, 0)])
+def test_reuse_addressing_is_exact(dtype, force_generic, n_splits):
+    """V carries an integer id per (layer, head, token, column); keys are +-1 sign vectors and the
+    query is a large multiple of one token's key, so the softmax is exactly one-hot on that token.
+    The output must then be exactly the id vector of (source layer, KV head, chosen token)."""
+    hkv, dh, hq, B, L = 4, 64, 32, 3, 333
+    n_layers = 4
+    reuse = np.zeros((n_layers, 2, hkv), dtype=bool)
+    reuse[1, :, 1] = True
+    reuse[2, :, 1] = True                     # chain: layer 2 -> layer 1 -> layer 0
+    reuse[2, 0, 3] = True                     # K only
+    reuse[3, :, 0] = True
+    reuse[3, 1, 1] = True                     # V only: layer 3's V head 1 -> chain to layer 0, its K head 1 is its own
+    rig = Rig(n_layers, hq, hkv, dh, B, L, dtype, reuse, latent_per_head=32, stride=2, force_generic=force_generic,
+              n_splits=n_splits)
+    rng = np.random.default_rng(7)
+    even = np.arange(0, hkv * dh, 2)
+    signs = rng.choice([-1.0, 1.0], size=(n_layers, B, L, hkv * dh))
+    for layer in range(n_layers):
+        k = np.zeros((B, L, hkv * dh)); v = np.zeros((B, L, hkv * dh))
+        k[:, :, even] = signs[layer][:, :, even]
+        for b in range(B):
+            for t in range(L):
+                v[b, t, even] = ids(layer, 1, b, t, even)
+        rig.append(layer, k, v, 0)
+    src = lambda layer, which, g: O.resolve_source(reuse, layer, which, g)
+    gq = hq // hkv
+    for layer in range(n_layers):
+        tstar = rng.integers(0, L, size=(B, hq))
+        q = np.zeros((B, hq, dh))
+        for b in range(B):
+            for j in range(hq):
+                g = j // gq
+                khat = np.zeros(dh); khat[::2] = signs[src(layer, 0, g)][b, tstar[b, j], g * dh:(g + 1) * dh:2]
+                q[b, j] = 256.0 * khat
+                # the chosen token must win by a margin that zeroes every other weight in any precision
+                others = signs[src(layer, 0, g)][b, :, g * dh:(g + 1) * dh:2] @ khat[::2]
+                others[tstar[b, j]] = -1e9
+                assert 0.125 * 1.4426 * 256.0 * (32 - others.max()) > 200
+        want = rig.orc.decode_attention(layer, q, L)
+        expect = np.zeros_like(want)
+        for b in range(B):
+            for j in range(hq):
+                g = j // gq
+                expect[b, j, ::2] = ids(src(layer, 1, g), 1, b, tstar[b, j], np.arange(g * dh, (g + 1) * dh, 2))
+        np.testing.assert_array_equal(O.round_to_dtype(want, dtype), expect)        # the oracle addresses correctly
+        tq = torch.from_numpy(q).to(rig.dev, rig.tdt)
+        out = torch.empty_like(tq)
+        ws = torch.empty(rig.ctx.workspace_bytes(B, L), dtype=torch.uint8, device=rig.dev)
+        rig.ctx.decode_attention(layer, tq, out, B, L, ws)
+        got = out.float().cpu().double().numpy()
+        np.testing.assert_array_equal(got, expect)                                  # and so does the library, exactly
+        for which in (0, 1):
+            for g in range(hkv):
+                assert rig.ctx.resolve_source(layer, which, g) == src(layer, which, g)

@@ -1,0 +1,92 @@
+"""Parity at the full sizes of the configurations, in the launch configuration bench.py times:
+the GPU runs the whole workload, the oracle recomputes sampled (layer, sequence) units one by one
+from the same seeded inputs (any slice of the synthetic K/V can be regenerated on its own)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvcar_oracle as O
+from paper_2512_06727_amd import synth
+from paper_2512_06727_amd.harness import Session
+from tests.helpers import ABS_TOL, REL_TOL, oracle_ae
+
+pytestmark = pytest.mark.gpu
+
+
+def sources(reuse, layer, which):
+    return [O.resolve_source(reuse, layer, which, g) for g in range(reuse.shape[2])]
+
+
+def oracle_unit(w, reuse, layer, b, n_cached, q_row):
+    """Attention output of one (layer, sequence) at the first decode step, from scratch."""
+    orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, 1, w.max_seq, w.dtype)
+    for n in range(w.n_layers):
+        orc.set_reuse_map(n, reuse[n, 0], reuse[n, 1])
+    need = {layer} | set(sources(reuse, layer, 0)) | set(sources(reuse, layer, 1))
+    for n in sorted(need):
+        for which in (0, 1):
+            orc.set_autoencoder(n, which, oracle_ae(synth.autoencoder(w, n, which, reuse)))
+        k = synth.kv_tokens(w, n, 0, b, b + 1, 0, n_cached + 1).double().numpy()
+        v = synth.kv_tokens(w, n, 1, b, b + 1, 0, n_cached + 1).double().numpy()
+        orc.encode_append(n, k, v, 0)
+    return orc.decode_attention(layer, q_row[None], n_cached + 1)[0], orc
+
+
+def run_fullsize(w, layers, seqs, gain, check_cache=True):
+    reuse = synth.reuse_map(w)
+    ses = Session(w, reuse=reuse)
+    need = set()
+    for n in layers:
+        need |= {n} | set(sources(reuse, n, 0)) | set(sources(reuse, n, 1))
+    need = sorted(need)
+    ses.prefill(0, w.n_cached, chunk=max(1, (1 << 24) // (w.batch * w.d_kv)), layers=need)
+    ses.prefill(w.n_cached, w.n_cached + 1, layers=need)            # the decode step's own token
+    for n in layers:
+        q = synth.queries(w, n, 0, gain=gain)
+        out = ses.decode_attention(n, q.to(ses.dev, ses.tdt), w.n_cached + 1).float().cpu().double().numpy()
+        plan = ses.ctx.describe_plan(n, w.batch, w.n_cached + 1)
+        print(f"layer {n}: mfma={plan.uses_mfma} groups={plan.n_groups} splits={plan.n_splits}", flush=True)
+        for b in seqs:
+            want, orc = oracle_unit(w, reuse, n, b, w.n_cached, q[b].double().numpy())
+            err = np.abs(out[b] - want).max()
+            ref = np.abs(want).max()
+            assert err <= ABS_TOL[w.dtype], (n, b, err)
+            assert err <= REL_TOL[w.dtype] * ref, (n, b, err, ref)
+            if check_cache:
+                for which in (0, 1):
+                    view = ses.cache_view(n, which)
+                    if view is None:
+                        continue
+                    zg = view[b, : w.n_cached + 1].float().cpu().double().numpy()
+                    zo = orc.Z[(n, which)][0, : w.n_cached + 1]
+                    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(zo), 1e-30))) - (7 if w.dtype == "bf16" else 10))
+                    assert (np.abs(zg - zo) <= 1.0001 * ulp + 2e-6 * np.abs(zo).max()).all()
+    return ses
+
+
+def test_long_context_tinyllama_full_size():
+    """batch 256 x 8192 cached tokens, 22 layers, Bernoulli(0.3) reuse: the benchmark's workload."""
+    w = synth.CONFIGS[4].scaled(n_steps=1)
+    reuse = synth.reuse_map(w)
+    n_src = [len(set(sources(reuse, n, 0))) for n in range(w.n_layers)]
+    deepest = int(np.argmax([n - min(sources(reuse, n, 0)) for n in range(w.n_layers)]))
+    layers = sorted({0, w.n_layers - 1, int(np.argmax(n_src)), deepest})
+    ses = run_fullsize(w, layers, seqs=[0, 101, 255], gain=30.0)
+    assert ses.ctx.describe_plan(0, w.batch, w.n_cached + 1).uses_mfma == 1
+
+
+def test_tinyllama_full_size():
+    w = synth.CONFIGS[2].scaled(n_steps=1)
+    run_fullsize(w, layers=[0, 2, 11, 21], seqs=[0, 17, 31], gain=30.0)
+
+
+def test_gpt2_fp16_full_size():
+    w = synth.CONFIGS[1].scaled(n_steps=1)
+    run_fullsize(w, layers=[0, 1, 6, 11], seqs=[0, 7], gain=10.0)
+
+
+def test_mlp_prefill_full_size():
+    """batch 16 x 4096-token prefill through the two-layer GELU encoder, then attention with the
+    two-layer decoder."""
+    w = synth.CONFIGS[3].scaled(n_steps=1)
+    run_fullsize(w, layers=[0, 21], seqs=[0, 15], gain=8.0)

@@ -1,0 +1,82 @@
+"""Properties of the attention kernels that hold at any size, checked on caches filled directly
+with synthetic latent rows (the cache layout is part of the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvcar_oracle as O
+from paper_2512_06727_amd import synth
+from paper_2512_06727_amd.harness import Session
+from tests.helpers import ABS_TOL, REL_TOL, build_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def fill(ses, orc, w, n_rows, perm=None):
+    """Same synthetic latent rows into the GPU caches and the oracle's (optionally permuted in time)."""
+    for n in range(w.n_layers):
+        for which in (0, 1):
+            view = ses.cache_view(n, which)
+            if view is None:
+                continue
+            r = view.shape[-1]
+            z = synth.latent_rows(w, n, which, r, 0, w.batch, 0, n_rows)
+            if perm is not None:
+                z = z[:, perm]
+            view[:, :n_rows] = z.to(ses.dev, ses.tdt)
+            if orc is not None:
+                orc.Z[(n, which)][:, :n_rows] = z.double().numpy()
+
+
+def close(w, got, want):
+    err = np.abs(got - want).max()
+    assert err <= ABS_TOL[w.dtype] and err <= REL_TOL[w.dtype] * np.abs(want).max(), err
+
+
+@pytest.mark.parametrize("cfg,n_rows", [(2, 1000), (1, 515), (4, 777)])
+def test_attention_alone_on_direct_cache_fill(cfg, n_rows):
+    w = synth.CONFIGS[cfg].scaled(n_layers=4, batch=3, n_cached=n_rows, n_steps=1)
+    ses, orc = Session(w), build_oracle(w)
+    fill(ses, orc, w, n_rows)
+    for n in range(w.n_layers):
+        q = synth.queries(w, n, 0, gain=25.0)
+        got = ses.decode_attention(n, q.to(ses.dev, ses.tdt), n_rows).float().cpu().double().numpy()
+        close(w, got, orc.decode_attention(n, q.double().numpy(), n_rows))
+
+
+def test_token_permutation_invariance():
+    """Attention does not depend on the order of the cached tokens; a permuted cache sends tokens to
+    different tiles, waves and splits, so this exercises the online-softmax merge."""
+    w = synth.CONFIGS[2].scaled(n_layers=2, batch=2, n_cached=900, n_steps=1, reuse="none")
+    perm = torch.from_numpy(np.random.default_rng(3).permutation(900))
+    outs = []
+    for p in (None, perm):
+        ses = Session(w, n_splits=5)
+        fill(ses, None, w, 900, p)
+        q = synth.queries(w, 1, 0, gain=25.0).to(ses.dev, ses.tdt)
+        outs.append(ses.decode_attention(1, q, 900).float().cpu().double().numpy())
+    assert np.abs(outs[0] - outs[1]).max() <= 4 * 2.0 ** -8 * np.abs(outs[0]).max()
+
+
+def test_zero_query_gives_mean_of_decoded_values():
+    w = synth.CONFIGS[2].scaled(n_layers=1, batch=2, n_cached=600, n_steps=1, reuse="none")
+    ses, orc = Session(w), build_oracle(w)
+    fill(ses, orc, w, 600)
+    q = torch.zeros(2, w.n_q_heads, w.d_head)
+    got = ses.decode_attention(0, q.to(ses.dev, ses.tdt), 600).float().cpu().double().numpy()
+    ae = orc.ae[(0, 1)]
+    mean_v = (orc.Z[(0, 1)][:, :600].mean(1) @ ae.dec[0][0]).reshape(2, w.n_kv_heads, 1, w.d_head)
+    want = np.broadcast_to(mean_v, (2, w.n_kv_heads, w.n_q_heads // w.n_kv_heads, w.d_head)).reshape(2, w.n_q_heads, w.d_head)
+    close(w, got, want)
+
+
+def test_plain_alu_and_mfma_kernels_agree():
+    w = synth.CONFIGS[4].scaled(n_layers=5, batch=2, n_cached=700, n_steps=1)
+    outs = []
+    for generic in (False, True):
+        ses = Session(w, force_generic=generic)
+        assert ses.ctx.describe_plan(4, 2, 700).uses_mfma == (0 if generic else 1)
+        fill(ses, None, w, 700)
+        q = synth.queries(w, 4, 0, gain=25.0).to(ses.dev, ses.tdt)
+        outs.append(ses.decode_attention(4, q, 700).float().cpu().double().numpy())
+    assert np.abs(outs[0] - outs[1]).max() <= REL_TOL[w.dtype] * np.abs(outs[1]).max()
