@@ -200,12 +200,12 @@ def main():
     achieved = alg / (attend_ms * 1e-3) / 1e9
     plan = ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "attend_mfma_traffic.json.txt")
+    # HBM bytes per launch from the committed rocprofv3 counter summary of this same workload
+    tpath = os.path.join(ROOT, "profiles", "attend_mfma_long_context_pmc.md")
     if os.path.exists(tpath) and args.workload == 4 and not (args.batch or args.cached or args.no_reuse or args.policy):
-        try:
-            traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
-        except Exception:
-            traffic = None
+        import re
+        m = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tpath).read())
+        traffic = float(m.group(1)) if m else None
 
     if args.calibrate_copy:
         src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
