@@ -53,7 +53,7 @@ __device__ __forceinline__ bool find_segment(const short* col, int n_slots, int 
 }
 
 // ---------------------------------------------------------------------------------------------
-// absorbed queries.  grid = (row blocks of 64, segment, group); a wave owns 16 rows (sequence, head).
+// absorbed queries.  grid = (16-row blocks, segment, group); rows are (sequence, head) pairs.
 // Both MFMA operands come straight from global memory: a lane needs 8 consecutive k of one query
 // row (A) and 8 consecutive k of one decoder-matrix row (B), both contiguous.
 // Segment index == number of segments is the zero-fill of the group's padding slots.
@@ -81,16 +81,22 @@ __global__ __launch_bounds__(256) void qtilde_mfma_kernel(AttendParams p) {
         return;
     }
     const int rows = p.batch * len;
-    const int row0 = (blockIdx.x * 4 + wave) * 16;
+    const int row0 = blockIdx.x * 16;                 // the four waves share the rows and deal out the column blocks
     if (row0 >= rows) return;
     const int col = g.k_col[s0];
     const int dh = p.d_head;
 
-    // A operand: query rows
+    // A operand: query rows (d_head <= 128: at most four k-steps, loaded once)
     const int arow = row0 + l16;
     const int ab = arow / len, ai = arow - ab * len;
     const bool a_ok = arow < rows;
     const char* qrow = static_cast<const char*>(p.q) + ((size_t)(a_ok ? ab : 0) * p.n_q_heads + g.q_head[s0 + (a_ok ? ai : 0)]) * dh * 2;
+    u32x4_t a[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        a[ks] = u32x4_t{0u, 0u, 0u, 0u};
+        if (a_ok && ks * 32 < dh) a[ks] = *reinterpret_cast<const u32x4_t*>(qrow + (ks * 32 + 8 * lg) * 2);
+    }
     // result rows of this lane
     size_t orow[4];
     bool ook[4];
@@ -103,15 +109,16 @@ __global__ __launch_bounds__(256) void qtilde_mfma_kernel(AttendParams p) {
     }
     uint16_t* qt = static_cast<uint16_t*>(p.qt);
     const char* wl = static_cast<const char*>(g.k.wl);
-    for (int nb = 0; nb < (rk >> 4); ++nb) {
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int nb = wave; nb < (rk >> 4); nb += 4) {
         const char* wrow = wl + ((size_t)(nb * 16 + l16) * g.k.in_width + col) * 2;
-        for (int k0 = 0; k0 < dh; k0 += 32) {
-            u32x4_t a = {0u, 0u, 0u, 0u};
-            if (a_ok) a = *reinterpret_cast<const u32x4_t*>(qrow + (k0 + 8 * lg) * 2);
-            const u32x4_t bw = *reinterpret_cast<const u32x4_t*>(wrow + (k0 + 8 * lg) * 2);
-            acc = PMma<E>::mfma(a, bw, acc);
-        }
+        u32x4_t bw[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            if (ks * 32 < dh) bw[ks] = *reinterpret_cast<const u32x4_t*>(wrow + (ks * 32 + 8 * lg) * 2);
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            if (ks * 32 < dh) acc = PMma<E>::mfma(a[ks], bw[ks], acc);
 #pragma unroll
         for (int v = 0; v < 4; ++v)
             if (ook[v]) qt[orow[v] + nb * 16 + l16] = PMma<E>::to16(acc[v] * p.scale_log2e);
@@ -119,15 +126,18 @@ __global__ __launch_bounds__(256) void qtilde_mfma_kernel(AttendParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// split merge + output epilogue.  grid = (row blocks of 64, segment, group).  The decoder-matrix
-// slice [r, d_head] of the segment's KV head is staged in LDS once per workgroup and read with the
-// transposing load (a lane needs 8 consecutive c of one output column).  The merged latent sums are
-// fed as a hi + lo pair of 16-bit values so that the product is accurate to ~2^-17.
+// split merge + output epilogue.  grid = (row blocks, segment, group); a workgroup owns 16*NW rows
+// (sequence, head) of one KV head.
+//   phase 0  the decoder-matrix slice [r, d_head] of the KV head is staged in LDS (read later with
+//            the transposing load: a lane needs 8 consecutive c of one output column)
+//   phase 1  all threads merge the split partials of the workgroup's rows into LDS:
+//            o = sum_i o_i 2^(m_i-M) / sum_i l_i 2^(m_i-M)
+//   phase 2  out = o . W with MFMA, o fed as a hi + lo pair of 16-bit values (accurate to ~2^-17)
 // ---------------------------------------------------------------------------------------------
-constexpr int kCombMaxSplits = 64;
+constexpr int kCombMaxSplits = 32;
 
 template <typename E, int NBO>
-__global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p) {
+__global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int rows_per_wg) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const GroupDesc& g = p.g[blockIdx.z];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -135,60 +145,80 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p) {
     int s0 = 0, len = 0;
     if (!find_segment(g.v_col, g.n_slots, blockIdx.y, s0, len)) return;
     const int rows = p.batch * len;
-    if (blockIdx.x * 64 >= rows) return;
+    const int wg_row0 = blockIdx.x * rows_per_wg;
+    if (wg_row0 >= rows) return;
     const int rv = g.v.r, dh = p.d_head;
     const int col = g.v_col[s0];
     const int stride_w = 2 * dh + 32;
+    const int pstride = rv + 4;
+    const int ns = p.n_splits;
 
-    // stage Wl_V[:, col .. col+d_head) : rv rows of d_head elements
-    {
+    char* wbuf = lds;                                                   // [rv][stride_w]
+    float* om = reinterpret_cast<float*>(lds + (size_t)rv * stride_w + 1024);   // [rows_per_wg][rv + 4]
+    float* wts = om + (size_t)rows_per_wg * pstride;                    // [rows_per_wg][ns]
+
+    {   // phase 0
         const int cpr = dh >> 3;
         const int total = rv * cpr;
         const char* src = static_cast<const char*>(g.v.wl);
         for (int f = threadIdx.x; f < total; f += 256) {
             const int row = f / cpr, ch = f - row * cpr;
-            *reinterpret_cast<u32x4_t*>(lds + row * stride_w + ch * 16) =
+            *reinterpret_cast<u32x4_t*>(wbuf + row * stride_w + ch * 16) =
                 *reinterpret_cast<const u32x4_t*>(src + ((size_t)row * g.v.in_width + col) * 2 + ch * 16);
+        }
+    }
+    // phase 1a: per-row merge weights
+    for (int r = threadIdx.x; r < rows_per_wg; r += 256) {
+        const int row = wg_row0 + r;
+        if (row < rows) {
+            const int b = row / len, i = row - b * len;
+            const float* prow = p.part + (size_t)b * ns * p.part_stride + g.part_off + (size_t)(s0 + i) * pstride;
+            float M = -INFINITY;
+            for (int k = 0; k < ns; ++k) M = fmaxf(M, prow[(size_t)k * p.part_stride]);
+            float L = 0.f;
+            for (int k = 0; k < ns; ++k) {
+                const float m_k = prow[(size_t)k * p.part_stride];
+                const float e = m_k == -INFINITY ? 0.f : exp2f(m_k - M);
+                wts[r * ns + k] = e;
+                L += prow[(size_t)k * p.part_stride + 1] * e;
+            }
+            const float inv = 1.f / L;
+            for (int k = 0; k < ns; ++k) wts[r * ns + k] *= inv;
+        }
+    }
+    __syncthreads();
+    // phase 1b: merged, normalised latent sums
+    {
+        const int c4n = rv >> 2;
+        for (int idx = threadIdx.x; idx < rows_per_wg * c4n; idx += 256) {
+            const int r = idx / c4n, c4 = idx - r * c4n;
+            const int row = wg_row0 + r;
+            f32x4_t a = {0.f, 0.f, 0.f, 0.f};
+            if (row < rows) {
+                const int b = row / len, i = row - b * len;
+                const float* prow = p.part + (size_t)b * ns * p.part_stride + g.part_off + (size_t)(s0 + i) * pstride + 4 + 4 * c4;
+                for (int k = 0; k < ns; ++k) {
+                    const float w = wts[r * ns + k];
+                    if (w != 0.f) a += *reinterpret_cast<const f32x4_t*>(prow + (size_t)k * p.part_stride) * w;
+                }
+            }
+            *reinterpret_cast<f32x4_t*>(om + (size_t)r * pstride + 4 * c4) = a;
         }
     }
     __syncthreads();
 
-    const int row0 = (blockIdx.x * 4 + wave) * 16;
-    if (row0 >= rows) return;
-    // A operand row of this lane: merge weights of its splits
-    const int arow = row0 + l16;
-    const bool a_ok = arow < rows;
-    const int ab = a_ok ? arow / len : 0, ai = a_ok ? arow - ab * len : 0;
-    const int pstride = rv + 4;
-    const float* prow = p.part + (size_t)ab * p.n_splits * p.part_stride + g.part_off + (size_t)(s0 + ai) * pstride;
-    float M = -INFINITY;
-    for (int i = 0; i < p.n_splits; ++i) M = fmaxf(M, prow[(size_t)i * p.part_stride]);
-    float L = 0.f;
-    for (int i = 0; i < p.n_splits; ++i) {
-        const float m_i = prow[(size_t)i * p.part_stride];
-        if (m_i != -INFINITY) L += prow[(size_t)i * p.part_stride + 1] * exp2f(m_i - M);
-    }
-    const float inv = 1.f / L;
-
+    // phase 2
+    const int row0 = wave * 16;                       // within the workgroup
+    if (row0 >= rows_per_wg || wg_row0 + row0 >= rows) return;
     f32x4_t acc[NBO];
 #pragma unroll
     for (int nb = 0; nb < NBO; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const int nbo = dh >> 4;
+    const float* arow = om + (size_t)(row0 + l16) * pstride;
     for (int k0 = 0; k0 < rv; k0 += 32) {
-        float o[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = 0.f;
-        if (a_ok) {
-            for (int i = 0; i < p.n_splits; ++i) {
-                const float m_i = prow[(size_t)i * p.part_stride];
-                if (m_i == -INFINITY) continue;
-                const float wgt = exp2f(m_i - M) * inv;
-                const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(prow + (size_t)i * p.part_stride + 4 + k0 + 8 * lg);
-                const f32x4_t x1 = *reinterpret_cast<const f32x4_t*>(prow + (size_t)i * p.part_stride + 8 + k0 + 8 * lg);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { o[e] = fmaf(x0[e], wgt, o[e]); o[4 + e] = fmaf(x1[e], wgt, o[4 + e]); }
-            }
-        }
+        const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(arow + k0 + 8 * lg);
+        const f32x4_t x1 = *reinterpret_cast<const f32x4_t*>(arow + k0 + 8 * lg + 4);
+        const float o[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
         unsigned hi[4], lo[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -198,7 +228,7 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p) {
             lo[e] = (unsigned)l0 | ((unsigned)l1 << 16);
         }
         const u32x4_t ah = {hi[0], hi[1], hi[2], hi[3]}, al = {lo[0], lo[1], lo[2], lo[3]};
-        const char* wrow = lds + (k0 + 8 * lg + (l16 >> 2)) * stride_w + (l16 & 3) * 8;
+        const char* wrow = wbuf + (k0 + 8 * lg + (l16 >> 2)) * stride_w + (l16 & 3) * 8;
 #pragma unroll
         for (int nb = 0; nb < NBO; ++nb) {
             if (nb < nbo) {
@@ -215,7 +245,7 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p) {
     uint16_t* out = static_cast<uint16_t*>(p.out);
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        const int r = row0 + 4 * lg + v;
+        const int r = wg_row0 + row0 + 4 * lg + v;
         if (r >= rows) continue;
         const int b = r / len, i = r - b * len;
         const size_t base = ((size_t)b * p.n_q_heads + g.q_head[s0 + i]) * dh;
@@ -258,7 +288,7 @@ static int max_segments(const AttendParams& p, bool use_k, int& max_len) {
 hipError_t launch_qtilde_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
     int max_len;
     const int segs = max_segments(p, true, max_len);
-    dim3 grid((p.batch * max_len + 63) / 64, segs + 1, p.n_groups);     // +1: zero-fill of padding slots
+    dim3 grid((p.batch * max_len + 15) / 16, segs + 1, p.n_groups);     // +1: zero-fill of padding slots
     if (dtype == KVCAR_BF16) hipLaunchKernelGGL(qtilde_mfma_kernel<BF16>, grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL(qtilde_mfma_kernel<F16>, grid, dim3(256), 0, stream, p);
     return hipGetLastError();
@@ -269,8 +299,9 @@ hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t str
     int max_len, rmax = 0;
     const int segs = max_segments(p, false, max_len);
     for (int i = 0; i < p.n_groups; ++i) rmax = p.g[i].v.r > rmax ? p.g[i].v.r : rmax;
-    const size_t lds = (size_t)rmax * (2 * p.d_head + 32) + 1024;
-    dim3 grid((p.batch * max_len + 63) / 64, segs, p.n_groups);
+    const int rows_per_wg = rmax <= 128 ? 64 : 16;
+    const size_t lds = (size_t)rmax * (2 * p.d_head + 32) + 1024 + (size_t)rows_per_wg * (rmax + 4 + p.n_splits) * sizeof(float);
+    dim3 grid((p.batch * max_len + rows_per_wg - 1) / rows_per_wg, segs, p.n_groups);
     const int e = dtype == KVCAR_BF16 ? 0 : 1;
     auto kern = e == 0 ? combine_mfma_kernel<BF16, 8> : combine_mfma_kernel<F16, 8>;
     if (!attr[e]) {
@@ -278,7 +309,7 @@ hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t str
         if (err != hipSuccess) return err;
         attr[e] = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p, rows_per_wg);
     return hipGetLastError();
 }
 
