@@ -109,6 +109,7 @@ def main():
     ap.add_argument("--tile-order", type=int, default=0, help="0 library default, 1 contiguous token range per split, 2 tiles dealt round-robin")
     ap.add_argument("--policy", default="", help="P1 (latent shrinks with stored heads) or P2 (full width)")
     ap.add_argument("--no-reuse", action="store_true")
+    ap.add_argument("--act", default="", help="override the activation of a two-layer autoencoder (gelu | leaky_relu)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle leg; 0 skips it")
     ap.add_argument("--fill", default="encode", choices=["encode", "random"],
                     help="encode: caches filled by kvcar_encode_append of seeded K/V (default); random: torch.randn latents and "
@@ -137,6 +138,8 @@ def main():
         w = w.scaled(policy=args.policy)
     if args.no_reuse:
         w = w.scaled(reuse="none")
+    if args.act:
+        w = w.scaled(act=args.act)
     reuse = synth.reuse_map(w)
     elem = synth.DTYPE_BYTES[w.dtype]
 

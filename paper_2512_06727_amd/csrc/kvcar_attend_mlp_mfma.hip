@@ -1,0 +1,399 @@
+// MFMA attention over the latent cache for TWO-LAYER decoders (gfx950, 16-bit dtypes).
+//
+// The decoder of the paper is FC -> activation -> FC ("Network Architecture", 2nd paragraph).  Its last
+// layer is linear and is absorbed into the query and the output exactly as for a linear decoder, so the
+// kernel attends over the hidden rows h_t = act(z_t W1 + b1), which it rebuilds from the latent rows on
+// the fly, per tile, never writing them to memory:
+//
+//   H_K^T[c, t] = W1K^T . Z_K^T     (MFMA)  -> +b1, act -> is the A operand of   S^T[t, head] = H_K . Qt^T
+//   H_V [t, c]  = Z_V . W1V         (MFMA)  -> +b1, act -> is the A operand of   O^T[c, head] += H_V^T . P^T
+//
+// (the result layout of each first product is the operand layout the second one needs, so the hidden
+// activations never leave registers).  All products use v_mfma_f32_32x32x16 (on this chip it sustains
+// twice the flop rate of the 16x16x32 form, and this kernel is bound by matrix + vector issue): tokens,
+// heads and hidden columns are handled in blocks of 32.  The four waves of a workgroup share a 32-token tile and split the
+// hidden width: each keeps its quarter of W1K and W1V resident in registers as MFMA operands.  Scores
+// are a contraction over the whole hidden width, so the per-wave partial scores are summed through LDS;
+// every wave then runs the same online softmax and accumulates its quarter of O^T.
+#include "kvcar_device.hpp"
+
+namespace kvcar {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
+
+template <typename E> struct MMma;
+template <> struct MMma<BF16> {
+    static __device__ __forceinline__ f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ unsigned pack2(float lo, float hi) {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+        bf16x2_t v = {(__bf16)lo, (__bf16)hi};
+        return __builtin_bit_cast(unsigned, v);
+    }
+};
+template <> struct MMma<F16> {
+    static __device__ __forceinline__ f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ unsigned pack2(float lo, float hi) {
+        typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+        f16x2_t v = {(_Float16)lo, (_Float16)hi};
+        return __builtin_bit_cast(unsigned, v);
+    }
+};
+
+// GELU(x) = x * Phi(x) with Phi(x) = 0.5 + x R(x^2), R a degree-8 polynomial fitted on |x| <= 4 (least
+// squares on Chebyshev nodes, weighted by x); beyond that Phi is held at its value at +-4.  |Phi error|
+// <= 3.1e-5, i.e. |GELU error| <= 3.1e-5 |x|: two orders below the 16-bit rounding applied right after.
+// No transcendental instruction: 8 FMAs, a clamp and three multiplies.
+__device__ __forceinline__ float fast_gelu(float x) {
+    const float xc = __builtin_amdgcn_fmed3f(x, -4.0f, 4.0f);
+    const float s = xc * xc;
+    float r = 7.804710350223232e-11f;
+    r = fmaf(r, s, -6.827684195798156e-09f);
+    r = fmaf(r, s, 2.666981799848145e-07f);
+    r = fmaf(r, s, -6.222018782864325e-06f);
+    r = fmaf(r, s, 9.829134069150314e-05f);
+    r = fmaf(r, s, -0.0011309664696455002f);
+    r = fmaf(r, s, 0.009869969449937344f);
+    r = fmaf(r, s, -0.06640204787254333f);
+    r = fmaf(r, s, 0.39891988039016724f);
+    return x * fmaf(xc, r, 0.5f);
+}
+
+template <int ACT>
+__device__ __forceinline__ float fast_act(float x, float slope) {
+    if (ACT == KVCAR_ACT_LEAKY_RELU) return x >= 0.f ? x : slope * x;
+    if (ACT == KVCAR_ACT_GELU) return fast_gelu(x);
+    return x;
+}
+
+constexpr int kMlpTile = 32;      // tokens per workgroup iteration
+
+// 32x32 result layout: register v of lane (l32, h) holds row 8*(v/4) + 4*h + v%4 of column l32.  As an
+// operand of the next product, k-step s (16 of the 32 rows) is registers 8s..8s+7 of the lane.
+template <typename E, int ACT>
+__device__ __forceinline__ void act_pack(const f32x16_t& t, const float (&bias)[16], float slope, u32x4_t (&out)[2]) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        unsigned w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            w[e] = MMma<E>::pack2(fast_act<ACT>(t[8 * s + 2 * e] + bias[8 * s + 2 * e], slope),
+                                  fast_act<ACT>(t[8 * s + 2 * e + 1] + bias[8 * s + 2 * e + 1], slope));
+        out[s] = u32x4_t{w[0], w[1], w[2], w[3]};
+    }
+}
+
+template <typename E, int R, int C, int ACT>
+__global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p) {
+    constexpr int CW = C / 4;          // hidden columns per wave
+    constexpr int MB = CW / 32;        // 32-column blocks per wave
+    constexpr int KS = R / 16;         // k-steps over the latent width
+    constexpr int STRIDE = 2 * R + 16; // LDS row stride of a latent tile
+    constexpr int NLD = (kMlpTile * R / 8) / 256 > 0 ? (kMlpTile * R / 8) / 256 : 1;   // 16-byte chunks per thread per tile
+    static_assert(CW % 32 == 0 && R % 16 == 0, "shape");
+
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    char* tile_k = lds;
+    char* tile_v = lds + kMlpTile * STRIDE;
+    float* sbuf = reinterpret_cast<float*>(lds + 2 * kMlpTile * STRIDE);    // [wave][64 lanes][16]
+
+    const GroupDesc& g = p.g[blockIdx.z];
+    const int split = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int l16 = lane & 15;
+    const int cw0 = wave * CW;
+    const float slope = g.k.slope;
+
+    // ---- resident operands ----------------------------------------------------------------------
+    // W1K^T as A operand (row = hidden column, k = 8 consecutive latent indices) and W1V as B operand
+    // (column = hidden column, same k): both are "8 consecutive rows of one column" of the row-major
+    // [R, C] matrix.  The matrix goes through LDS once (coalesced 16-byte loads) and the transposing load
+    // hands every lane its column: 16 lanes supply a 4-row x 16-column patch, lane i gets column i.
+    u32x4_t wk[MB][KS], wv[MB][KS];
+    {
+        constexpr int WSTRIDE = 2 * C + 32;
+        typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            const char* w1 = static_cast<const char*>(which == 0 ? g.k.w1 : g.v.w1);
+            __syncthreads();
+            for (int f = tid; f < R * (C / 8); f += 256) {
+                const int row = f / (C / 8), ch = f % (C / 8);
+                *reinterpret_cast<u32x4_t*>(lds + row * WSTRIDE + ch * 16) = *reinterpret_cast<const u32x4_t*>(w1 + (size_t)f * 16);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const char* src = lds + (16 * ks + 8 * h + (l16 >> 2)) * WSTRIDE + (cw0 + 32 * mb + 16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
+                    const s16x4_t t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(src));
+                    const s16x4_t t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(src + 4 * WSTRIDE));
+                    const u32x2_t a0 = __builtin_bit_cast(u32x2_t, t0), a1 = __builtin_bit_cast(u32x2_t, t1);
+                    const u32x4_t v = {a0[0], a0[1], a1[0], a1[1]};
+                    if (which == 0) wk[mb][ks] = v; else wv[mb][ks] = v;
+                }
+        }
+        __syncthreads();          // the staging area becomes the tile and score buffers
+    }
+    // first-layer biases in the two result layouts (rows of H_K^T, column of H_V)
+    float bk[MB][16], bv[MB][16];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const float bcol = g.v.b1 ? Elem<E>::load(g.v.b1, cw0 + 32 * mb + l32) : 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            bk[mb][v] = g.k.b1 ? Elem<E>::load(g.k.b1, cw0 + 32 * mb + 8 * (v >> 2) + 4 * h + (v & 3)) : 0.f;
+            bv[mb][v] = bcol;
+        }
+    }
+    // absorbed queries of this wave's hidden slice as B operand (column = head l32; padding heads are
+    // zero rows of qt): k-slots of lane half h in k-step s of block mb are the hidden columns
+    // 16s + 4h + j and 16s + 8 + 4h + j, which is what the H_K^T result layout delivers
+    u32x4_t qb[MB][2];
+    {
+        const char* qt = static_cast<const char*>(p.qt) + ((size_t)b * p.qt_stride + g.qt_off) * 2;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (l32 < g.slots_pad) {
+                    const char* row = qt + ((size_t)l32 * C + cw0 + 32 * mb + 16 * s + 4 * h) * 2;
+                    const u32x2_t x0 = *reinterpret_cast<const u32x2_t*>(row);
+                    const u32x2_t x1 = *reinterpret_cast<const u32x2_t*>(row + 16);
+                    v = u32x4_t{x0[0], x0[1], x1[0], x1[1]};
+                }
+                qb[mb][s] = v;
+            }
+    }
+
+    f32x16_t acc[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int tiles = (p.n_ctx + kMlpTile - 1) / kMlpTile;
+    const int per_split = (tiles + p.n_splits - 1) / p.n_splits;
+    const int j0 = split * per_split;
+    const int j1 = min(tiles, j0 + per_split);
+    const char* zk = static_cast<const char*>(g.k.z) + (size_t)b * p.max_seq * R * 2;
+    const char* zv = static_cast<const char*>(g.v.z) + (size_t)b * p.max_seq * R * 2;
+
+    // tile chunks of this thread: chunk f = i*256 + tid of the contiguous [32, R] tile
+    u32x4_t stk[NLD], stv[NLD];
+    auto issue = [&](int j) {
+        const int t0 = j * kMlpTile;
+        const int valid = max(0, min(kMlpTile, p.n_ctx - t0)) * (R / 8);
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int f = i * 256 + tid;
+            u32x4_t a = {0u, 0u, 0u, 0u}, c2 = {0u, 0u, 0u, 0u};
+            if (f < valid) {
+                a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(zk + (size_t)t0 * R * 2 + (size_t)f * 16));
+                c2 = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(zv + (size_t)t0 * R * 2 + (size_t)f * 16));
+            }
+            stk[i] = a; stv[i] = c2;
+        }
+    };
+    if (j0 < j1) issue(j0);
+
+    for (int j = j0; j < j1; ++j) {
+        const int nv = min(kMlpTile, p.n_ctx - j * kMlpTile);
+        // ---- park the tile (all threads), prefetch the next ---------------------------------------
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int f = i * 256 + tid;
+            if (f < kMlpTile * (R / 8)) {
+                const int row = f / (R / 8), ch = f % (R / 8);
+                *reinterpret_cast<u32x4_t*>(tile_k + row * STRIDE + ch * 16) = stk[i];
+                *reinterpret_cast<u32x4_t*>(tile_v + row * STRIDE + ch * 16) = stv[i];
+            }
+        }
+        if (j + 1 < j1) issue(j + 1);
+        __syncthreads();
+
+        // ---- H_K^T for this wave's hidden slice, then partial scores ------------------------------
+        // One wave per SIMD: matrix and vector instructions only overlap if they alternate in program
+        // order, so the MFMA chain of the next block is placed under the activations of the previous one.
+        f32x16_t sT;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sT[v] = 0.f;
+        {
+            u32x4_t zb[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) zb[ks] = *reinterpret_cast<const u32x4_t*>(tile_k + l32 * STRIDE + (2 * ks + h) * 16);
+            f32x16_t hk[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) hk[mb][v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) hk[0] = MMma<E>::mfma(wk[0][ks], zb[ks], hk[0]);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                if (mb + 1 < MB) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) hk[mb + 1] = MMma<E>::mfma(wk[mb + 1][ks], zb[ks], hk[mb + 1]);
+                }
+                u32x4_t ha[2];
+                act_pack<E, ACT>(hk[mb], bk[mb], slope, ha);       // lane: token l32, hidden rows of block mb
+                if (mb + 1 < MB) {
+#pragma unroll
+                    for (int i = 0; i < KS; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x002, 24, 0);    // then vector work
+                    }
+                }
+#pragma unroll
+                for (int s = 0; s < 2; ++s) sT = MMma<E>::mfma(ha[s], qb[mb][s], sT);
+            }
+        }
+        // ---- sum the partial scores of the four waves ---------------------------------------------
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<f32x4_t*>(sbuf + ((size_t)wave * 64 + lane) * 16 + 4 * q) = f32x4_t{sT[4 * q], sT[4 * q + 1], sT[4 * q + 2], sT[4 * q + 3]};
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            f32x4_t s4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) s4 += *reinterpret_cast<const f32x4_t*>(sbuf + ((size_t)w * 64 + lane) * 16 + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sT[4 * q + e] = s4[e];
+        }
+        if (nv < kMlpTile) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (8 * (v >> 2) + 4 * h + (v & 3) >= nv) sT[v] = -INFINITY;
+        }
+
+        // ---- online softmax (identical in every wave); lane holds head l32, 16 of the 32 tokens ------
+        u32x4_t pb[2];
+        {
+            float mx = sT[0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sT[v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            const bool rescale = m_new != m_run;
+            m_run = m_new;
+            float e[16], sum = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { e[v] = __builtin_amdgcn_exp2f(sT[v] - m_new); sum += e[v]; }
+            l_run = l_run * alpha + sum;
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                pb[s] = u32x4_t{MMma<E>::pack2(e[8 * s], e[8 * s + 1]), MMma<E>::pack2(e[8 * s + 2], e[8 * s + 3]),
+                                MMma<E>::pack2(e[8 * s + 4], e[8 * s + 5]), MMma<E>::pack2(e[8 * s + 6], e[8 * s + 7])};
+            if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) acc[mb] *= alpha;
+            }
+        }
+
+        // ---- H_V for this wave's hidden slice, then O^T += H_V^T . P^T ------------------------------
+        {
+            u32x4_t za[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) za[ks] = *reinterpret_cast<const u32x4_t*>(tile_v + l32 * STRIDE + (2 * ks + h) * 16);
+            f32x16_t hv[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) hv[mb][v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) hv[0] = MMma<E>::mfma(za[ks], wv[0][ks], hv[0]);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                if (mb + 1 < MB) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) hv[mb + 1] = MMma<E>::mfma(za[ks], wv[mb + 1][ks], hv[mb + 1]);
+                }
+                u32x4_t va[2];
+                act_pack<E, ACT>(hv[mb], bv[mb], slope, va);       // lane: hidden column l32 of block mb, 16 tokens
+                if (mb + 1 < MB) {
+#pragma unroll
+                    for (int i = 0; i < KS; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 24, 0);
+                    }
+                }
+#pragma unroll
+                for (int s = 0; s < 2; ++s) acc[mb] = MMma<E>::mfma(va[s], pb[s], acc[mb]);
+            }
+        }
+        __syncthreads();          // tile and score buffers are rewritten by the next iteration
+    }
+
+    // ---- partial: every wave owns its hidden slice; m and l are the same in all four ------------------
+    l_run += __shfl_xor(l_run, 32);
+    float* part = p.part + ((size_t)b * p.n_splits + split) * p.part_stride + g.part_off;
+    constexpr int PSTRIDE = C + 4;
+    if (l32 < g.slots_pad) {
+        if (wave == 0 && h == 0) { part[(size_t)l32 * PSTRIDE] = m_run; part[(size_t)l32 * PSTRIDE + 1] = l_run; }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                *reinterpret_cast<f32x4_t*>(part + (size_t)l32 * PSTRIDE + 4 + cw0 + 32 * mb + 8 * a + 4 * h) =
+                    f32x4_t{acc[mb][4 * a], acc[mb][4 * a + 1], acc[mb][4 * a + 2], acc[mb][4 * a + 3]};
+    }
+}
+
+template <typename E, int R, int C>
+static hipError_t launch_mlp(const AttendParams& p, int act, hipStream_t stream) {
+    const size_t loop_lds = 2 * (size_t)kMlpTile * (2 * R + 16) + (size_t)4 * 64 * 16 * sizeof(float);
+    const size_t stage_lds = (size_t)R * (2 * C + 32);            // first-layer weights pass through LDS at start
+    const size_t lds = loop_lds > stage_lds ? loop_lds : stage_lds;
+    dim3 grid(p.n_splits, p.batch, p.n_groups);
+    static bool attr[2] = {false, false};
+    auto kg = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_GELU>;
+    auto kl = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_LEAKY_RELU>;
+    const int ai = act == KVCAR_ACT_GELU ? 0 : 1;
+    if (!attr[ai]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ai == 0 ? kg : kl), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr[ai] = true;
+    }
+    if (ai == 0) hipLaunchKernelGGL(kg, grid, dim3(256), lds, stream, p);
+    else hipLaunchKernelGGL(kl, grid, dim3(256), lds, stream, p);
+    return hipGetLastError();
+}
+
+// Shapes with a resident-weight instance: every group has the same (latent, hidden) widths for K and V,
+// (128, 256) or (64, 128), the same activation, and at most 32 heads.
+bool attend_mlp_mfma_supported(const AttendParams& p, int dtype) {
+    if (dtype == KVCAR_F32 || p.n_groups < 1) return false;
+    const GroupDesc& g0 = p.g[0];
+    for (int i = 0; i < p.n_groups; ++i) {
+        const GroupDesc& g = p.g[i];
+        if (!g.k.w1 || !g.v.w1) return false;
+        if (g.k.r != g0.k.r || g.v.r != g0.k.r || g.k.c != g0.k.c || g.v.c != g0.k.c) return false;
+        if (g.k.act != g0.k.act || g.v.act != g0.k.act || g.k.slope != g0.k.slope || g.v.slope != g0.k.slope) return false;
+        if (g.slots_pad > 32) return false;
+    }
+    if (g0.k.act != KVCAR_ACT_GELU && g0.k.act != KVCAR_ACT_LEAKY_RELU) return false;
+    return (g0.k.r == 128 && g0.k.c == 256) || (g0.k.r == 64 && g0.k.c == 128);
+}
+
+hipError_t launch_attend_mlp_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
+    const int act = p.g[0].k.act;
+    const bool big = p.g[0].k.r == 128;
+    if (dtype == KVCAR_BF16) return big ? launch_mlp<BF16, 128, 256>(p, act, stream) : launch_mlp<BF16, 64, 128>(p, act, stream);
+    return big ? launch_mlp<F16, 128, 256>(p, act, stream) : launch_mlp<F16, 64, 128>(p, act, stream);
+}
+
+}  // namespace kvcar

@@ -73,7 +73,8 @@ int resolve(const kvcar_ctx* ctx, int layer, int which, int g) {
 
 struct Plan {
     std::vector<GroupDesc> groups;
-    bool mfma = false;
+    bool mfma = false;        // an MFMA attention kernel (linear or two-layer decoder) is used
+    bool mlp = false;         // ... the two-layer one
     int n_splits = 1;
     int qt_stride = 0;        // elements per sequence
     int part_stride = 0;      // floats per (sequence, split)
@@ -117,6 +118,10 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     plan.groups.clear();
     // MFMA kernels: 16-bit dtype, linear decoders, latent widths that are multiples of 32
     bool mfma_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && attend_mfma_available() && c.d_head % 8 == 0;
+    // ... or two-layer decoders of one of the shapes with a resident-weight kernel, the same for K and V
+    bool mlp_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && c.d_head % 32 == 0 && c.d_head <= 128;
+    int mlp_r = -1, mlp_c = -1, mlp_act = -1;
+    float mlp_slope = 0.f;
     int r_all = 0;
     struct Base { GroupDesc gd; std::vector<int> heads; int src_k, src_v; };
     std::vector<Base> bases;
@@ -129,6 +134,11 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
         if (base.k.c > kMaxRow || base.v.c > kMaxRow || base.k.r > kMaxRow || base.v.r > kMaxRow)
             return fail(ctx, KVCAR_ERR_UNSUPPORTED, "row width above %d", kMaxRow);
         if (base.k.w1 || base.v.w1 || base.k.r % 32 || base.v.r % 32 || base.k.r > 384 || base.v.r > 384) mfma_ok = false;
+        for (const SideDesc* sd : {&base.k, &base.v}) {
+            if (!sd->w1) { mlp_ok = false; continue; }
+            if (mlp_r < 0) { mlp_r = sd->r; mlp_c = sd->c; mlp_act = sd->act; mlp_slope = sd->slope; }
+            if (sd->r != mlp_r || sd->c != mlp_c || sd->act != mlp_act || sd->slope != mlp_slope) mlp_ok = false;
+        }
         r_all = std::max(r_all, std::max(base.k.r, base.v.r));
         // query heads of this (K source, V source) pair, in increasing order
         std::vector<int> heads;
@@ -141,12 +151,15 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
         }
         bases.push_back(Base{base, heads, kv.first.first, kv.first.second});
     }
+    if (mlp_ok) mlp_ok = ((mlp_r == 128 && mlp_c == 256) || (mlp_r == 64 && mlp_c == 128)) &&
+                         (mlp_act == KVCAR_ACT_GELU || mlp_act == KVCAR_ACT_LEAKY_RELU);
+    if (mlp_ok) mfma_ok = true;
     for (auto& bh : bases) {
         const GroupDesc& base = bh.gd;
         const std::vector<int>& heads = bh.heads;
         int cap;
         if (mfma_ok) {
-            cap = r_all <= 128 ? 32 : 16;      // head blocks one wave can keep accumulators for
+            cap = (mlp_ok || r_all <= 128) ? 32 : 16;      // head blocks one wave can keep accumulators for
         } else {
             // slot capacity of one plain-ALU workgroup: accumulators and LDS
             cap = std::min(kMaxSlots, kGenericAcc * 256 / std::max(1, base.v.c));
@@ -171,6 +184,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
         }
     }
     plan.mfma = mfma_ok;
+    plan.mlp = mlp_ok;
     int qt = 0, part = 0;
     for (auto& gd : plan.groups) {
         gd.qt_off = qt; gd.part_off = part;
@@ -188,7 +202,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
         const int target = plan.mfma ? ctx->n_cu : ctx->n_cu * 2;
         splits = (target + batch * n_groups - 1) / (batch * n_groups);
     }
-    const int tile = plan.mfma ? 128 : kGenericTile;   // tokens per workgroup iteration
+    const int tile = plan.mlp ? 32 : plan.mfma ? 128 : kGenericTile;   // tokens per workgroup iteration
     const int max_splits = std::max(1, (n_ctx + tile - 1) / tile);
     splits = std::max(1, std::min(splits, std::min(max_splits, 256)));
     plan.n_splits = splits;
@@ -439,7 +453,9 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
             }
             if (e == hipSuccess) { ev = &ctx->ev_pool[ctx->ev_used++]; e = hipEventRecord(ev->first, st); }
         }
-        if (e == hipSuccess) e = plan.mfma ? launch_attend_mfma(p, c.dtype, st) : launch_attend_generic(p, c.dtype, st);
+        if (e == hipSuccess)
+            e = plan.mlp ? launch_attend_mlp_mfma(p, c.dtype, st)
+                         : plan.mfma ? launch_attend_mfma(p, c.dtype, st) : launch_attend_generic(p, c.dtype, st);
         if (e == hipSuccess && ev) e = hipEventRecord(ev->second, st);
         if (e == hipSuccess) e = proj ? launch_combine_mfma(p, c.dtype, st) : launch_combine(p, c.dtype, st);
         if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));

@@ -89,6 +89,10 @@ bool proj_mfma_supported(const AttendParams& p, int dtype);
 hipError_t launch_qtilde_mfma(const AttendParams& p, int dtype, hipStream_t stream);
 hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t stream);
 
+// MFMA attention for two-layer decoders (resident first-layer weights).
+bool attend_mlp_mfma_supported(const AttendParams& p, int dtype);
+hipError_t launch_attend_mlp_mfma(const AttendParams& p, int dtype, hipStream_t stream);
+
 // MFMA path (16-bit dtypes, linear decoders, widths that are multiples of 32).
 bool attend_mfma_available();
 hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stream);

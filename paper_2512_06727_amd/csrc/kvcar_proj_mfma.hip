@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void qtilde_mfma_kernel(AttendParams p) {
     const GroupDesc& g = p.g[blockIdx.z];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, lg = lane >> 4;
-    const int rk = g.k.r;
+    const int rk = g.k.c;            // contraction width of the score product: latent (linear decoder) or hidden width
     int s0 = 0, len = 0;
     if (!find_segment(g.k_col, g.n_slots, blockIdx.y, s0, len)) {
         int dummy0, dummy1;
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
     const int rows = p.batch * len;
     const int wg_row0 = blockIdx.x * rows_per_wg;
     if (wg_row0 >= rows) return;
-    const int rv = g.v.r, dh = p.d_head;
+    const int rv = g.v.c, dh = p.d_head;      // rows of the last decoder layer: latent or hidden width
     const int col = g.v_col[s0];
     const int stride_w = 2 * dh + 32;
     const int pstride = rv + 4;
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
 bool proj_mfma_supported(const AttendParams& p, int dtype) {
     if (dtype == KVCAR_F32 || p.d_head % 32 || p.d_head > 128 || p.n_splits > kCombMaxSplits) return false;
     for (int i = 0; i < p.n_groups; ++i)
-        if (p.g[i].k.w1 || p.g[i].v.w1 || p.g[i].k.r % 32 || p.g[i].v.r % 32) return false;
+        if (p.g[i].k.c % 32 || p.g[i].v.c % 32) return false;
     return true;
 }
 
@@ -298,7 +298,7 @@ hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t str
     static bool attr[2] = {false, false};
     int max_len, rmax = 0;
     const int segs = max_segments(p, false, max_len);
-    for (int i = 0; i < p.n_groups; ++i) rmax = p.g[i].v.r > rmax ? p.g[i].v.r : rmax;
+    for (int i = 0; i < p.n_groups; ++i) rmax = p.g[i].v.c > rmax ? p.g[i].v.c : rmax;
     const int rows_per_wg = rmax <= 128 ? 64 : 16;
     const size_t lds = (size_t)rmax * (2 * p.d_head + 32) + 1024 + (size_t)rows_per_wg * (rmax + 4 + p.n_splits) * sizeof(float);
     dim3 grid((p.batch * max_len + rows_per_wg - 1) / rows_per_wg, segs, p.n_groups);

@@ -27,6 +27,11 @@ CASES = {
     # biases everywhere and the paper's LeakyReLU between the two layers
     "leaky-bias": (C[2].scaled(n_layers=3, batch=2, n_cached=90, n_steps=1, hidden=160, act="leaky_relu", dtype="f16"),
                    {"with_bias": True}),
+    # two-layer decoders on the MFMA path: LeakyReLU (the paper's activation) with biases and a reuse chain under
+    # the full-width policy, and the narrower fp16 instance
+    "mlp-leaky-p2": (C[3].scaled(n_layers=4, batch=2, n_cached=100, n_steps=2, act="leaky_relu", reuse="from2:1", policy="P2"),
+                     {"with_bias": True}),
+    "mlp-f16-narrow": (C[3].scaled(n_layers=2, batch=3, n_cached=70, n_steps=1, dtype="f16", latent=64, hidden=128), {}),
     "linear-bias-f32": (C[0].scaled(n_layers=2, batch=2, n_cached=50, n_steps=2, reuse="odd:5"), {"with_bias": True}),
 }
 
@@ -68,3 +73,13 @@ def test_plain_alu_kernels_on_16bit_linear(name):
     _, want = run_oracle(w, gain=20.0, **kw)
     _, got = run_gpu(w, gain=20.0, force_generic=True, **kw)
     assert_outputs_close(w, got, want, name + "-generic")
+
+
+def test_two_layer_decoder_uses_the_mfma_kernels():
+    from paper_2512_06727_amd.harness import Session
+    for name in ("c3-small", "mlp-leaky-p2", "mlp-f16-narrow"):
+        w, kw = CASES[name]
+        ses = Session(w, **{k: v for k, v in kw.items() if k == "with_bias"})
+        assert ses.ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached + 1).uses_mfma == 1, name
+    w, kw = CASES["leaky-bias"]            # hidden width 160: no resident-weight instance, plain-ALU kernels
+    assert Session(w, with_bias=True).ctx.describe_plan(0, w.batch, w.n_cached + 1).uses_mfma == 0
