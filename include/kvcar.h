@@ -109,7 +109,8 @@ typedef struct {
     int force_generic;  /* 1 = use the plain-ALU kernels even where an MFMA kernel exists     */
     int tile_order;     /* MFMA attention: 0 = library default, 1 = each split owns a contiguous
                            token range, 2 = 128-token tiles dealt round-robin over the splits    */
-    int reserved[5];
+    int no_fuse;        /* 1 = always run prologue / attention / epilogue as separate kernels     */
+    int reserved[4];
 } kvcar_tuning;
 
 /* Create / destroy a context.  ERR_ARG on null pointers, ERR_SHAPE on non-positive sizes or
@@ -187,6 +188,7 @@ typedef struct {
     int n_groups;
     int n_splits;           /* token-range splits per sequence                                  */
     int n_launches;         /* attention-kernel launches (groups are batched 8 per launch)      */
+    int fused;              /* 1 = prologue and epilogue run inside the attention kernel        */
     size_t workspace_bytes;
     size_t latent_bytes;    /* bytes of latent rows the attention kernel reads for this call    */
 } kvcar_plan_info;

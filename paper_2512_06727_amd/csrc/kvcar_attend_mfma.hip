@@ -42,6 +42,9 @@ template <> struct Mma<BF16> {
         bf16x2_t v = {(__bf16)lo, (__bf16)hi};          // round to nearest even
         return __builtin_bit_cast(unsigned, v);
     }
+    static __device__ __forceinline__ float unpack_lo(unsigned w) { return __uint_as_float(w << 16); }
+    static __device__ __forceinline__ float unpack_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
+    static __device__ __forceinline__ uint16_t to16(float v) { return f32_to_bf16_bits(v); }
 };
 template <> struct Mma<F16> {
     static __device__ __forceinline__ f32x4_t mfma(u32x4_t a, u32x4_t b, f32x4_t c) {
@@ -52,6 +55,9 @@ template <> struct Mma<F16> {
         f16x2_t v = {(_Float16)lo, (_Float16)hi};
         return __builtin_bit_cast(unsigned, v);
     }
+    static __device__ __forceinline__ float unpack_lo(unsigned w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu)); }
+    static __device__ __forceinline__ float unpack_hi(unsigned w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
+    static __device__ __forceinline__ uint16_t to16(float v) { _Float16 h = (_Float16)v; return __builtin_bit_cast(uint16_t, h); }
 };
 
 constexpr int kWaveTile = 32;     // tokens per wave per iteration
@@ -74,13 +80,13 @@ template <int R, int NHB_> struct DimsExact {
     static constexpr int RMAX = R, NHB = NHB_;
     static constexpr bool kExact = true;
     static constexpr int rk = R, rv = R, nhb = NHB_;
-    __device__ explicit DimsExact(const GroupDesc&) {}
+    __device__ DimsExact(int, int, int) {}
 };
 template <int RMAX_, int NHB_> struct DimsAny {
     static constexpr int RMAX = RMAX_, NHB = NHB_;
     static constexpr bool kExact = false;
     int rk, rv, nhb;
-    __device__ explicit DimsAny(const GroupDesc& g) : rk(g.k.r), rv(g.v.r), nhb(g.slots_pad >> 4) {}
+    __device__ DimsAny(int rk_, int rv_, int nhb_) : rk(rk_), rv(rv_), nhb(nhb_) {}
 };
 
 template <int RMAX> struct Geo {
@@ -123,15 +129,37 @@ __device__ __forceinline__ void park_tile(const u32x4_t (&st)[NL], char* region,
         }
 }
 
-template <typename E, typename D>
-__device__ __forceinline__ void attend_body(const AttendParams& p, const GroupDesc& g, char* lds_raw, size_t wave_lds) {
+// The kernel reads its argument block through the kernel-argument segment pointer (constant address
+// space): run-time indexed reads of the by-value argument would otherwise make the compiler copy the
+// whole block into per-lane scratch memory.  The block is the kernel's only explicit argument, so it
+// sits at offset 0 of the segment.
+typedef const __attribute__((address_space(4))) AttendParams* KArgs;
+typedef const __attribute__((address_space(4))) GroupDesc* KGroup;
+typedef const __attribute__((address_space(4))) short* KShorts;
+
+// Entry `base + idx` of a small table that lives in the kernel arguments, for a lane-dependent idx in
+// [0, 16): done with 16 uniform reads and selects, because indexing the argument block with a
+// lane-dependent index would make the compiler copy the whole block to scratch memory.
+__device__ __forceinline__ int lane_lookup16(KShorts table, int base, int limit, int idx, int otherwise) {
+    int r = otherwise;
+#pragma unroll
+    for (int s = 0; s < 16; ++s)
+        if (base + s < limit && idx == s) r = table[base + s];
+    return r;
+}
+
+// kFused (single split, exact shapes only): the absorbed queries are computed in the prologue and the
+// last decoder layer of V is applied in the epilogue, so the whole decode attention of a layer is this
+// one kernel and neither the absorbed queries nor the partials travel through memory.
+template <typename E, typename D, bool kFused>
+__device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, size_t wave_lds) {
     constexpr int RMAX = D::RMAX, NHB = D::NHB;
     using G = Geo<RMAX>;
     constexpr int KS = RMAX / 32;      // k-steps of the score product
     constexpr int MB = RMAX / 16;      // 16-column blocks of the latent accumulator
     constexpr int NL = RMAX / 16;      // 128-bit loads per lane per tile
 
-    const D d(g);
+    const D d(g->k.r, g->v.r, g->slots_pad >> 4);
     const int split = blockIdx.x, b = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, lg = lane >> 4;
@@ -148,8 +176,50 @@ __device__ __forceinline__ void attend_body(const AttendParams& p, const GroupDe
 
     // absorbed queries of this sequence and group, resident as MFMA B operands
     u32x4_t qb[NHB][KS];
-    {
-        const char* qt = static_cast<const char*>(p.qt) + ((size_t)b * p.qt_stride + g.qt_off) * 2;
+    if constexpr (kFused) {
+        // Qt^T[c, head] = scale*log2e * sum_k Wl_K[c, col(head)+k] q[head, k], by MFMA straight from global
+        // memory: A = rows of the decoder matrix, B = the queries of one KV head's heads (other heads of
+        // the 16-block masked to zero; blocks that span two KV heads take two passes).  Row rho of result
+        // tile (s, hh) is latent index 32s + 8(rho/4) + 4hh + rho%4, so that the result registers of tiles
+        // (s,0) and (s,1) are exactly the B operand of score k-step s.
+        const int dh = p->d_head;
+        const char* wl = static_cast<const char*>(g->k.wl);
+        const int slot_l = l16;
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb) {
+            f32x4_t t[KS][2];
+#pragma unroll
+            for (int s2 = 0; s2 < KS; ++s2) { t[s2][0] = f32x4_t{0.f, 0.f, 0.f, 0.f}; t[s2][1] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
+            const int my_col = lane_lookup16(g->k_col, nb * 16, g->n_slots, slot_l, -1);
+            const int my_head = lane_lookup16(g->q_head, nb * 16, g->n_slots, slot_l, 0);
+            const char* qrow = static_cast<const char*>(p->q) + ((size_t)b * p->n_q_heads + my_head) * dh * 2;
+            int prev_col = -1;
+            for (int sl = nb * 16; sl < min(g->n_slots, nb * 16 + 16); ++sl) {
+                const int col = g->k_col[sl];
+                if (col == prev_col) continue;
+                prev_col = col;
+                for (int k0 = 0; k0 < dh; k0 += 32) {
+                    u32x4_t bq = {0u, 0u, 0u, 0u};
+                    if (my_col == col) bq = *reinterpret_cast<const u32x4_t*>(qrow + (k0 + 8 * lg) * 2);
+#pragma unroll
+                    for (int s2 = 0; s2 < KS; ++s2)
+#pragma unroll
+                        for (int hh = 0; hh < 2; ++hh) {
+                            const int c = 32 * s2 + 8 * (l16 >> 2) + 4 * hh + (l16 & 3);
+                            const u32x4_t aw = *reinterpret_cast<const u32x4_t*>(wl + ((size_t)c * g->k.in_width + col + k0 + 8 * lg) * 2);
+                            t[s2][hh] = Mma<E>::mfma(aw, bq, t[s2][hh]);
+                        }
+                }
+            }
+#pragma unroll
+            for (int s2 = 0; s2 < KS; ++s2) {
+                const float sc = p->scale_log2e;
+                qb[nb][s2] = u32x4_t{Mma<E>::pack2(t[s2][0][0] * sc, t[s2][0][1] * sc), Mma<E>::pack2(t[s2][0][2] * sc, t[s2][0][3] * sc),
+                                     Mma<E>::pack2(t[s2][1][0] * sc, t[s2][1][1] * sc), Mma<E>::pack2(t[s2][1][2] * sc, t[s2][1][3] * sc)};
+            }
+        }
+    } else {
+        const char* qt = static_cast<const char*>(p->qt) + ((size_t)b * p->qt_stride + g->qt_off) * 2;
 #pragma unroll
         for (int nb = 0; nb < NHB; ++nb)
 #pragma unroll
@@ -172,26 +242,26 @@ __device__ __forceinline__ void attend_body(const AttendParams& p, const GroupDe
     // Workgroup tiles (4 wave tiles = 128 tokens each) of this split.  tile_order 0: a contiguous
     // token range per split; 1: tiles dealt round-robin over the splits, so that workgroups running
     // at the same time read neighbouring addresses.
-    const int wg_tiles = (p.n_ctx + kWaveTile * kWaves - 1) / (kWaveTile * kWaves);
+    const int wg_tiles = (p->n_ctx + kWaveTile * kWaves - 1) / (kWaveTile * kWaves);
     int j0, j1, jstep;
-    if (p.tile_order == 0) {
-        const int per_split = (wg_tiles + p.n_splits - 1) / p.n_splits;
+    if (p->tile_order == 0) {
+        const int per_split = (wg_tiles + p->n_splits - 1) / p->n_splits;
         j0 = split * per_split;
         j1 = min(wg_tiles, j0 + per_split);
         jstep = 1;
     } else {
-        j0 = split; j1 = wg_tiles; jstep = p.n_splits;
+        j0 = split; j1 = wg_tiles; jstep = p->n_splits;
     }
 
-    const char* zk = static_cast<const char*>(g.k.z) + (size_t)b * p.max_seq * rk * 2;
-    const char* zv = static_cast<const char*>(g.v.z) + (size_t)b * p.max_seq * rv * 2;
+    const char* zk = static_cast<const char*>(g->k.z) + (size_t)b * p->max_seq * rk * 2;
+    const char* zv = static_cast<const char*>(g->v.z) + (size_t)b * p->max_seq * rv * 2;
 
     // kPrefetch: both tiles of the next iteration are in flight while this one computes.
     // Otherwise (wide rows) a tile is loaded right before it is parked and K, V take turns.
     u32x4_t stk[NL], stv[G::kPrefetch ? NL : 1];
     auto issue = [&](int j) {
         const int t0 = (j * kWaves + wave) * kWaveTile;
-        const int nv = max(0, min(kWaveTile, p.n_ctx - t0));
+        const int nv = max(0, min(kWaveTile, p->n_ctx - t0));
         load_tile<NL>(stk, zk + (size_t)t0 * rk * 2, nlk, nv * cprk, nv == kWaveTile, lane);
         if constexpr (G::kPrefetch) load_tile<NL>(stv, zv + (size_t)t0 * rv * 2, nlv, nv * cprv, nv == kWaveTile, lane);
     };
@@ -199,7 +269,7 @@ __device__ __forceinline__ void attend_body(const AttendParams& p, const GroupDe
 
     for (int j = j0; j < j1; j += jstep) {
         const int t0 = (j * kWaves + wave) * kWaveTile;
-        const int nv = min(kWaveTile, p.n_ctx - t0);
+        const int nv = min(kWaveTile, p->n_ctx - t0);
         if (nv <= 0) break;          // wave tile past the context: only in the last workgroup tile, the last one visited
 
         if constexpr (!G::kPrefetch) issue(j);
@@ -332,7 +402,85 @@ __device__ __forceinline__ void attend_body(const AttendParams& p, const GroupDe
         l_all[nb] = L;
     }
     __syncthreads();
-    float* part = p.part + ((size_t)b * p.n_splits + split) * p.part_stride + g.part_off;
+    if constexpr (kFused) {
+        // ---- epilogue: out[head, :] = (O[head, :] / L) . Wl_V[:, col(head) ..] + bias -------------------
+        // normalised latent sums -> LDS [slot][rv + 4] fp32; per KV head its [rv, d_head] slice of the
+        // decoder matrix is staged in LDS and read with the transposing load; wave w owns output column
+        // blocks w, w+4, ...; the latent sums are fed as a hi + lo pair of 16-bit values.
+        const int dh = p->d_head;
+        const int ostride = rv + 4;
+        float* olat = accs + (size_t)kWaves * NHB * MB * 64 * 4;
+        char* wst = reinterpret_cast<char*>(olat + (size_t)NHB * 16 * ostride);
+        const int stride_w = 2 * dh + 32;
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb) {
+            const float inv = 1.f / l_all[nb];
+            for (int mb = wave; mb < mblocks; mb += kWaves) {
+                f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) sacc += *reinterpret_cast<const f32x4_t*>(accs + ((size_t)((w * NHB + nb) * MB + mb) * 64 + lane) * 4);
+                *reinterpret_cast<f32x4_t*>(olat + (size_t)(nb * 16 + l16) * ostride + 16 * mb + 4 * lg) = sacc * inv;
+            }
+        }
+        uint16_t* out = static_cast<uint16_t*>(p->out);
+        const char* wlv = static_cast<const char*>(g->v.wl);
+        int seg0 = 0;
+        while (seg0 < g->n_slots) {                       // uniform loop over the KV-head runs of the group
+            const int col = g->v_col[seg0];
+            int seg1 = seg0 + 1;
+            while (seg1 < g->n_slots && g->v_col[seg1] == col) ++seg1;
+            __syncthreads();                             // olat complete / previous slice consumed
+            const int cpr = dh >> 3;
+            for (int f = threadIdx.x; f < rv * cpr; f += 256) {
+                const int row = f / cpr, ch = f - row * cpr;
+                *reinterpret_cast<u32x4_t*>(wst + row * stride_w + ch * 16) =
+                    *reinterpret_cast<const u32x4_t*>(wlv + ((size_t)row * g->v.in_width + col) * 2 + ch * 16);
+            }
+            __syncthreads();
+            for (int nb = seg0 >> 4; nb <= (seg1 - 1) >> 4; ++nb) {
+                int heads4[4];                          // query heads of this lane's four result rows
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    heads4[v] = 0;
+#pragma unroll
+                    for (int lgx = 0; lgx < 4; ++lgx)
+                        if (lg == lgx && nb * 16 + 4 * lgx + v < g->n_slots) heads4[v] = g->q_head[nb * 16 + 4 * lgx + v];
+                }
+                for (int nbo = wave; nbo < (dh >> 4); nbo += kWaves) {
+                    f32x4_t o = {0.f, 0.f, 0.f, 0.f};
+                    for (int k0 = 0; k0 < rv; k0 += 32) {
+                        const float* arow = olat + (size_t)(nb * 16 + l16) * ostride + k0 + 8 * lg;
+                        const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(arow);
+                        const f32x4_t x1 = *reinterpret_cast<const f32x4_t*>(arow + 4);
+                        const float xv[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+                        unsigned hi[4], lo[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            hi[e] = Mma<E>::pack2(xv[2 * e], xv[2 * e + 1]);
+                            lo[e] = Mma<E>::pack2(xv[2 * e] - Mma<E>::unpack_lo(hi[e]), xv[2 * e + 1] - Mma<E>::unpack_hi(hi[e]));
+                        }
+                        const char* wrow = wst + (k0 + 8 * lg + (l16 >> 2)) * stride_w + (l16 & 3) * 8 + nbo * 32;
+                        const s16x4_t t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(wrow));
+                        const s16x4_t t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(wrow + 4 * stride_w));
+                        const u32x2_t a0 = __builtin_bit_cast(u32x2_t, t0), a1 = __builtin_bit_cast(u32x2_t, t1);
+                        const u32x4_t bw = {a0[0], a0[1], a1[0], a1[1]};
+                        o = Mma<E>::mfma(u32x4_t{hi[0], hi[1], hi[2], hi[3]}, bw, o);
+                        o = Mma<E>::mfma(u32x4_t{lo[0], lo[1], lo[2], lo[3]}, bw, o);
+                    }
+                    const int kcol = nbo * 16 + l16;
+                    const float bias = g->v.bl ? Elem<E>::load(g->v.bl, col + kcol) : 0.f;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int slot = nb * 16 + 4 * lg + v;
+                        if (slot >= seg0 && slot < seg1)
+                            out[((size_t)b * p->n_q_heads + heads4[v]) * dh + kcol] = Mma<E>::to16(o[v] + bias);
+                    }
+                }
+            }
+            seg0 = seg1;
+        }
+    } else {
+    float* part = p->part + ((size_t)b * p->n_splits + split) * p->part_stride + g->part_off;
     const int pstride = rv + 4;
 #pragma unroll
     for (int nb = 0; nb < NHB; ++nb) {
@@ -347,6 +495,7 @@ __device__ __forceinline__ void attend_body(const AttendParams& p, const GroupDe
             *reinterpret_cast<f32x4_t*>(part + (size_t)slot * pstride + 4 + 16 * mb + 4 * lg) = s;
         }
     }
+    }
 }
 
 constexpr size_t mfma_lds_bytes(int rmax, int nhb) {
@@ -357,43 +506,60 @@ constexpr size_t mfma_lds_bytes(int rmax, int nhb) {
 
 // Latent widths up to 128 (TinyLlama-class KV widths): up to two 16-head blocks per group.
 template <typename E>
-__global__ __launch_bounds__(256, 2) void attend_mfma_r128_kernel(AttendParams p) {
+__global__ __launch_bounds__(256, 2) void attend_mfma_r128_kernel(AttendParams p_by_value) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    const GroupDesc& g = p.g[blockIdx.z];
+    (void)p_by_value;
+    KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    KGroup g = &p->g[blockIdx.z];
     constexpr size_t wl = Geo<128>::kWaveLds;
-    const int nhb = g.slots_pad >> 4;
-    if (g.k.r == g.v.r) {
-        const int key = g.k.r * 4 + nhb;
+    const int nhb = g->slots_pad >> 4;
+    if (g->k.r == g->v.r) {
+        const int key = g->k.r * 4 + nhb;
+        if (p->fused) {                       // the host only asks for this with exact shapes in every group
+            switch (key) {
+                case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, true>(p, g, lds_raw, wl); return;
+                case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, true>(p, g, lds_raw, wl); return;
+                case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, true>(p, g, lds_raw, wl); return;
+                case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, true>(p, g, lds_raw, wl); return;
+                case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, true>(p, g, lds_raw, wl); return;
+                case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, true>(p, g, lds_raw, wl); return;
+                case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, true>(p, g, lds_raw, wl); return;
+                case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, true>(p, g, lds_raw, wl); return;
+                default: return;
+            }
+        }
         switch (key) {
-            case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>>(p, g, lds_raw, wl); return;
-            case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>>(p, g, lds_raw, wl); return;
-            case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>>(p, g, lds_raw, wl); return;
-            case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>>(p, g, lds_raw, wl); return;
-            case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>>(p, g, lds_raw, wl); return;
-            case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>>(p, g, lds_raw, wl); return;
-            case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>>(p, g, lds_raw, wl); return;
-            case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>>(p, g, lds_raw, wl); return;
+            case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, false>(p, g, lds_raw, wl); return;
+            case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, false>(p, g, lds_raw, wl); return;
+            case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, false>(p, g, lds_raw, wl); return;
+            case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, false>(p, g, lds_raw, wl); return;
+            case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, false>(p, g, lds_raw, wl); return;
+            case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, false>(p, g, lds_raw, wl); return;
+            case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, false>(p, g, lds_raw, wl); return;
+            case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, false>(p, g, lds_raw, wl); return;
             default: break;
         }
     }
-    attend_body<E, DimsAny<128, 2>>(p, g, lds_raw, wl);
+    attend_body<E, DimsAny<128, 2>, false>(p, g, lds_raw, wl);
 }
 
 // Latent widths up to 384 (GPT-2-class KV widths): one 16-head block per group.
 template <typename E>
-__global__ __launch_bounds__(256, 1) void attend_mfma_r384_kernel(AttendParams p) {
+__global__ __launch_bounds__(256, 1) void attend_mfma_r384_kernel(AttendParams p_by_value) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    const GroupDesc& g = p.g[blockIdx.z];
+    (void)p_by_value;
+    KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    KGroup g = &p->g[blockIdx.z];
     constexpr size_t wl = Geo<384>::kWaveLds;
-    if (g.k.r == g.v.r && g.k.r == 384) { attend_body<E, DimsExact<384, 1>>(p, g, lds_raw, wl); return; }
-    if (g.k.r == g.v.r && g.k.r == 288) { attend_body<E, DimsExact<288, 1>>(p, g, lds_raw, wl); return; }
-    attend_body<E, DimsAny<384, 1>>(p, g, lds_raw, wl);
+    if (g->k.r == g->v.r && g->k.r == 384) { attend_body<E, DimsExact<384, 1>, false>(p, g, lds_raw, wl); return; }
+    if (g->k.r == g->v.r && g->k.r == 288) { attend_body<E, DimsExact<288, 1>, false>(p, g, lds_raw, wl); return; }
+    attend_body<E, DimsAny<384, 1>, false>(p, g, lds_raw, wl);
 }
 
 template <typename K>
 static hipError_t launch_one(K kern, size_t lds, const AttendParams& p, hipStream_t stream, bool& attr_set) {
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -414,7 +580,9 @@ hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stre
     }
     const int e = dtype == KVCAR_BF16 ? 0 : 1;
     if (rmax <= 128 && nhb <= 2) {
-        constexpr size_t lds = mfma_lds_bytes(128, 2);
+        // fused: + normalised latent sums [32][132] fp32 + one decoder-matrix slice [128][2*d_head+32]
+        const size_t lds = p.fused ? mfma_lds_bytes(128, 2) + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32) + 256
+                                   : mfma_lds_bytes(128, 2);
         return e == 0 ? launch_one(attend_mfma_r128_kernel<BF16>, lds, p, stream, set128[0])
                       : launch_one(attend_mfma_r128_kernel<F16>, lds, p, stream, set128[1]);
     }

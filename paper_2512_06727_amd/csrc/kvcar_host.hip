@@ -75,6 +75,7 @@ struct Plan {
     std::vector<GroupDesc> groups;
     bool mfma = false;        // an MFMA attention kernel (linear or two-layer decoder) is used
     bool mlp = false;         // ... the two-layer one
+    bool fused = false;       // one kernel does prologue, attention and epilogue (single split, exact shapes)
     int n_splits = 1;
     int qt_stride = 0;        // elements per sequence
     int part_stride = 0;      // floats per (sequence, split)
@@ -206,6 +207,12 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     const int max_splits = std::max(1, (n_ctx + tile - 1) / tile);
     splits = std::max(1, std::min(splits, std::min(max_splits, 256)));
     plan.n_splits = splits;
+    plan.fused = false;
+    if (plan.mfma && !plan.mlp && splits == 1 && !ctx->tun.no_fuse && r_all <= 128 && c.d_head % 32 == 0 && c.d_head <= 128) {
+        plan.fused = true;
+        for (auto& gd : plan.groups)
+            if (gd.k.r != gd.v.r || gd.k.r % 32 || gd.k.r < 32 || gd.slots_pad > 32) plan.fused = false;
+    }
     plan.qt_bytes = align_up((size_t)batch * qt * (plan.mfma ? 2 : 4), 256);
     plan.part_bytes = align_up((size_t)batch * splits * part * sizeof(float), 256);
     plan.total_bytes = plan.qt_bytes + plan.part_bytes;
@@ -441,8 +448,10 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
         p.qt_stride = plan.qt_stride; p.part_stride = plan.part_stride;
         p.scale_log2e = ctx->scale * kLog2e;
         p.tile_order = ctx->tun.tile_order == 2 ? 1 : 0;
+        p.fused = plan.fused ? 1 : 0;
         const bool proj = plan.mfma && proj_mfma_supported(p, c.dtype);
-        hipError_t e = proj ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma, st);
+        hipError_t e = hipSuccess;
+        if (!plan.fused) e = proj ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma, st);
         std::pair<hipEvent_t, hipEvent_t>* ev = nullptr;
         if (e == hipSuccess && ctx->profiling) {
             if (ctx->ev_used == ctx->ev_pool.size()) {
@@ -457,7 +466,7 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
             e = plan.mlp ? launch_attend_mlp_mfma(p, c.dtype, st)
                          : plan.mfma ? launch_attend_mfma(p, c.dtype, st) : launch_attend_generic(p, c.dtype, st);
         if (e == hipSuccess && ev) e = hipEventRecord(ev->second, st);
-        if (e == hipSuccess) e = proj ? launch_combine_mfma(p, c.dtype, st) : launch_combine(p, c.dtype, st);
+        if (e == hipSuccess && !plan.fused) e = proj ? launch_combine_mfma(p, c.dtype, st) : launch_combine(p, c.dtype, st);
         if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
     }
     return KVCAR_OK;
@@ -476,6 +485,7 @@ int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, k
     out->n_groups = (int)plan.groups.size();
     out->n_splits = plan.n_splits;
     out->n_launches = (int)((plan.groups.size() + kMaxGroups - 1) / kMaxGroups);
+    out->fused = plan.fused ? 1 : 0;
     out->workspace_bytes = plan.total_bytes;
     size_t lat = 0;
     for (auto& g : plan.groups) lat += (size_t)(g.k.r + g.v.r);

@@ -167,24 +167,35 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
                 *reinterpret_cast<const u32x4_t*>(src + ((size_t)row * g.v.in_width + col) * 2 + ch * 16);
         }
     }
-    // phase 1a: per-row merge weights
-    for (int r = threadIdx.x; r < rows_per_wg; r += 256) {
+    // phase 1a: per-row merge weights.  All (row, split) pairs fetch their m and l at once (a serial
+    // loop over the splits would pay one memory latency per split), then one thread per row reduces.
+    float* ml = wts + (size_t)rows_per_wg * ns;                         // [rows_per_wg][ns][2]
+    for (int idx = threadIdx.x; idx < rows_per_wg * ns; idx += 256) {
+        const int r = idx / ns, k = idx - r * ns;
         const int row = wg_row0 + r;
+        float m_k = -INFINITY, l_k = 0.f;
         if (row < rows) {
             const int b = row / len, i = row - b * len;
-            const float* prow = p.part + (size_t)b * ns * p.part_stride + g.part_off + (size_t)(s0 + i) * pstride;
-            float M = -INFINITY;
-            for (int k = 0; k < ns; ++k) M = fmaxf(M, prow[(size_t)k * p.part_stride]);
-            float L = 0.f;
-            for (int k = 0; k < ns; ++k) {
-                const float m_k = prow[(size_t)k * p.part_stride];
-                const float e = m_k == -INFINITY ? 0.f : exp2f(m_k - M);
-                wts[r * ns + k] = e;
-                L += prow[(size_t)k * p.part_stride + 1] * e;
-            }
-            const float inv = 1.f / L;
-            for (int k = 0; k < ns; ++k) wts[r * ns + k] *= inv;
+            const float* prow = p.part + ((size_t)b * ns + k) * p.part_stride + g.part_off + (size_t)(s0 + i) * pstride;
+            m_k = prow[0];
+            l_k = prow[1];
         }
+        ml[2 * idx] = m_k;
+        ml[2 * idx + 1] = l_k;
+    }
+    __syncthreads();
+    for (int r = threadIdx.x; r < rows_per_wg; r += 256) {
+        float M = -INFINITY;
+        for (int k = 0; k < ns; ++k) M = fmaxf(M, ml[2 * (r * ns + k)]);
+        float L = 0.f;
+        for (int k = 0; k < ns; ++k) {
+            const float m_k = ml[2 * (r * ns + k)];
+            const float e = m_k == -INFINITY ? 0.f : exp2f(m_k - M);
+            wts[r * ns + k] = e;
+            L += ml[2 * (r * ns + k) + 1] * e;
+        }
+        const float inv = L > 0.f ? 1.f / L : 0.f;
+        for (int k = 0; k < ns; ++k) wts[r * ns + k] *= inv;
     }
     __syncthreads();
     // phase 1b: merged, normalised latent sums
@@ -300,7 +311,7 @@ hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t str
     const int segs = max_segments(p, false, max_len);
     for (int i = 0; i < p.n_groups; ++i) rmax = p.g[i].v.c > rmax ? p.g[i].v.c : rmax;
     const int rows_per_wg = rmax <= 128 ? 64 : 16;
-    const size_t lds = (size_t)rmax * (2 * p.d_head + 32) + 1024 + (size_t)rows_per_wg * (rmax + 4 + p.n_splits) * sizeof(float);
+    const size_t lds = (size_t)rmax * (2 * p.d_head + 32) + 1024 + (size_t)rows_per_wg * (rmax + 4 + 3 * p.n_splits) * sizeof(float);
     dim3 grid((p.batch * max_len + rows_per_wg - 1) / rows_per_wg, segs, p.n_groups);
     const int e = dtype == KVCAR_BF16 ? 0 : 1;
     auto kern = e == 0 ? combine_mfma_kernel<BF16, 8> : combine_mfma_kernel<F16, 8>;

@@ -13,7 +13,7 @@ from . import binding, synth
 
 class Session:
     def __init__(self, w: synth.Workload, reuse: Optional[np.ndarray] = None, with_bias: bool = False,
-                 device: str = "cuda:0", n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, poison: bool = False,
+                 device: str = "cuda:0", n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, no_fuse: bool = False, poison: bool = False,
                  max_batch: Optional[int] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: libkvcar has no CPU path")
@@ -22,7 +22,7 @@ class Session:
         self.tdt = synth.TORCH_DTYPE[w.dtype]
         self.reuse = synth.reuse_map(w) if reuse is None else reuse
         self.ctx = binding.Context(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, max_batch or w.batch, w.max_seq, w.dtype)
-        self.ctx.set_tuning(n_splits=n_splits, force_generic=force_generic, tile_order=tile_order)
+        self.ctx.set_tuning(n_splits=n_splits, force_generic=force_generic, tile_order=tile_order, no_fuse=no_fuse)
         self.ae: List[List[synth.AEWeights]] = []
         self.caches: List[List[Optional[torch.Tensor]]] = []
         for layer in range(w.n_layers):

@@ -123,7 +123,8 @@ def test_cache_bytes_after_scripted_appends(dtype, force_generic):
 
 
 @pytest.mark.parametrize("dtype,force_generic,n_splits", [("bf16", False, 0), ("bf16", False, 3), ("f16", False, 2),
-                                                           ("bf16", True, 2), ("f32", False, 0)])
+                                                           ("bf16", True, 2), ("f32", False, 0),
+                                                           ("bf16", False, 1), ("f16", False, 1)])   # one split: fused kernel
 def test_reuse_addressing_is_exact(dtype, force_generic, n_splits):
     """V carries an integer id per (layer, head, token, column); keys are +-1 sign vectors and the
     query is a large multiple of one token's key, so the softmax is exactly one-hot on that token.

@@ -83,3 +83,16 @@ def test_two_layer_decoder_uses_the_mfma_kernels():
         assert ses.ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached + 1).uses_mfma == 1, name
     w, kw = CASES["leaky-bias"]            # hidden width 160: no resident-weight instance, plain-ALU kernels
     assert Session(w, with_bias=True).ctx.describe_plan(0, w.batch, w.n_cached + 1).uses_mfma == 0
+
+
+@pytest.mark.parametrize("name", ["c2-small", "c4-small", "c4-small-p2"])
+def test_fused_single_split_kernel(name):
+    """With one split the absorbed queries and the output epilogue run inside the attention kernel;
+    the same cases with the three separate kernels must give the same answer as the oracle."""
+    from paper_2512_06727_amd.harness import Session
+    w, kw = CASES[name]
+    _, want = run_oracle(w, gain=20.0, **kw)
+    for no_fuse in (False, True):
+        ses, got = run_gpu(w, gain=20.0, n_splits=1, no_fuse=no_fuse, **kw)
+        assert ses.ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached + 1).fused == (0 if no_fuse else 1)
+        assert_outputs_close(w, got, want, f"{name} no_fuse={no_fuse}")
