@@ -174,71 +174,6 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     char* lds_k = my_lds;
     char* lds_v = G::kPrefetch ? my_lds + kWaveTile * stride_k : my_lds;
 
-    // absorbed queries of this sequence and group, resident as MFMA B operands
-    u32x4_t qb[NHB][KS];
-    if constexpr (kFused) {
-        // Qt^T[c, head] = scale*log2e * sum_k Wl_K[c, col(head)+k] q[head, k], by MFMA straight from global
-        // memory: A = rows of the decoder matrix, B = the queries of one KV head's heads (other heads of
-        // the 16-block masked to zero; blocks that span two KV heads take two passes).  Row rho of result
-        // tile (s, hh) is latent index 32s + 8(rho/4) + 4hh + rho%4, so that the result registers of tiles
-        // (s,0) and (s,1) are exactly the B operand of score k-step s.
-        const int dh = p->d_head;
-        const char* wl = static_cast<const char*>(g->k.wl);
-        const int slot_l = l16;
-#pragma unroll
-        for (int nb = 0; nb < NHB; ++nb) {
-            f32x4_t t[KS][2];
-#pragma unroll
-            for (int s2 = 0; s2 < KS; ++s2) { t[s2][0] = f32x4_t{0.f, 0.f, 0.f, 0.f}; t[s2][1] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
-            const int my_col = lane_lookup16(g->k_col, nb * 16, g->n_slots, slot_l, -1);
-            const int my_head = lane_lookup16(g->q_head, nb * 16, g->n_slots, slot_l, 0);
-            const char* qrow = static_cast<const char*>(p->q) + ((size_t)b * p->n_q_heads + my_head) * dh * 2;
-            int prev_col = -1;
-            for (int sl = nb * 16; sl < min(g->n_slots, nb * 16 + 16); ++sl) {
-                const int col = g->k_col[sl];
-                if (col == prev_col) continue;
-                prev_col = col;
-                for (int k0 = 0; k0 < dh; k0 += 32) {
-                    u32x4_t bq = {0u, 0u, 0u, 0u};
-                    if (my_col == col) bq = *reinterpret_cast<const u32x4_t*>(qrow + (k0 + 8 * lg) * 2);
-#pragma unroll
-                    for (int s2 = 0; s2 < KS; ++s2)
-#pragma unroll
-                        for (int hh = 0; hh < 2; ++hh) {
-                            const int c = 32 * s2 + 8 * (l16 >> 2) + 4 * hh + (l16 & 3);
-                            const u32x4_t aw = *reinterpret_cast<const u32x4_t*>(wl + ((size_t)c * g->k.in_width + col + k0 + 8 * lg) * 2);
-                            t[s2][hh] = Mma<E>::mfma(aw, bq, t[s2][hh]);
-                        }
-                }
-            }
-#pragma unroll
-            for (int s2 = 0; s2 < KS; ++s2) {
-                const float sc = p->scale_log2e;
-                qb[nb][s2] = u32x4_t{Mma<E>::pack2(t[s2][0][0] * sc, t[s2][0][1] * sc), Mma<E>::pack2(t[s2][0][2] * sc, t[s2][0][3] * sc),
-                                     Mma<E>::pack2(t[s2][1][0] * sc, t[s2][1][1] * sc), Mma<E>::pack2(t[s2][1][2] * sc, t[s2][1][3] * sc)};
-            }
-        }
-    } else {
-        const char* qt = static_cast<const char*>(p->qt) + ((size_t)b * p->qt_stride + g->qt_off) * 2;
-#pragma unroll
-        for (int nb = 0; nb < NHB; ++nb)
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                u32x4_t v = {0u, 0u, 0u, 0u};
-                if (nb < nhb && s < ksteps) v = *reinterpret_cast<const u32x4_t*>(qt + ((size_t)(nb * 16 + l16) * rk + 8 * (4 * s + lg)) * 2);
-                qb[nb][s] = v;
-            }
-    }
-
-    f32x4_t acc[NHB][MB];
-#pragma unroll
-    for (int nb = 0; nb < NHB; ++nb)
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    float m_run[NHB], l_run[NHB];
-#pragma unroll
-    for (int nb = 0; nb < NHB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; }
-
     // Workgroup tiles (4 wave tiles = 128 tokens each) of this split.  tile_order 0: a contiguous
     // token range per split; 1: tiles dealt round-robin over the splits, so that workgroups running
     // at the same time read neighbouring addresses.
@@ -265,7 +200,85 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         load_tile<NL>(stk, zk + (size_t)t0 * rk * 2, nlk, nv * cprk, nv == kWaveTile, lane);
         if constexpr (G::kPrefetch) load_tile<NL>(stv, zv + (size_t)t0 * rv * 2, nlv, nv * cprv, nv == kWaveTile, lane);
     };
-    if (G::kPrefetch && j0 < j1) issue(j0);
+    if (G::kPrefetch && j0 < j1) issue(j0);        // first tile in flight while the queries are prepared
+
+    // absorbed queries of this sequence and group, resident as MFMA B operands
+    u32x4_t qb[NHB][KS];
+    if constexpr (kFused) {
+        // Qt^T[c, head] = scale*log2e * sum_k Wl_K[c, col(head)+k] q[head, k], by MFMA straight from global
+        // memory: A = rows of the decoder matrix, B = the queries of one KV head's heads (other heads of
+        // the 16-block masked to zero; a block spans at most two KV heads: two passes).  Row rho of result
+        // tile (s, hh) is latent index 32s + 8(rho/4) + 4hh + rho%4, so that the result registers of tiles
+        // (s,0) and (s,1) are exactly the B operand of score k-step s.  Wave w computes k-step s = w for
+        // all heads (its loads are independent and fly together) and the waves swap through LDS.
+        const int dh = p->d_head;
+        const char* wl = static_cast<const char*>(g->k.wl);
+        u32x4_t* qlds = reinterpret_cast<u32x4_t*>(lds_raw + kWaves * wave_lds);      // [NHB][KS][64], past the staging regions
+        if (wave < KS) {
+            const int s2 = wave;
+#pragma unroll
+            for (int nb = 0; nb < NHB; ++nb) {
+                const int my_col = lane_lookup16(g->k_col, nb * 16, g->n_slots, l16, -1);
+                const int my_head = lane_lookup16(g->q_head, nb * 16, g->n_slots, l16, 0);
+                const char* qrow = static_cast<const char*>(p->q) + ((size_t)b * p->n_q_heads + my_head) * dh * 2;
+                // the (at most two) KV heads of this 16-head block
+                const int blk_end = min(g->n_slots, nb * 16 + 16);
+                const int col_a = nb * 16 < g->n_slots ? g->k_col[nb * 16] : -1;
+                int col_b = -1;
+                for (int sl = nb * 16 + 1; sl < blk_end; ++sl)
+                    if (g->k_col[sl] != col_a) { col_b = g->k_col[sl]; break; }
+                f32x4_t t[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
+                for (int k0 = 0; k0 < dh; k0 += 32) {
+                    u32x4_t bq[2], aw[2][2];
+                    const u32x4_t qv = my_col >= 0 ? *reinterpret_cast<const u32x4_t*>(qrow + (k0 + 8 * lg) * 2) : u32x4_t{0u, 0u, 0u, 0u};
+                    bq[0] = my_col == col_a ? qv : u32x4_t{0u, 0u, 0u, 0u};
+                    bq[1] = my_col == col_b ? qv : u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+                    for (int sg = 0; sg < 2; ++sg)
+#pragma unroll
+                        for (int hh = 0; hh < 2; ++hh) {
+                            const int c = 32 * s2 + 8 * (l16 >> 2) + 4 * hh + (l16 & 3);
+                            const int col = sg == 0 ? col_a : col_b;
+                            aw[sg][hh] = u32x4_t{0u, 0u, 0u, 0u};
+                            if (col >= 0) aw[sg][hh] = *reinterpret_cast<const u32x4_t*>(wl + ((size_t)c * g->k.in_width + col + k0 + 8 * lg) * 2);
+                        }
+#pragma unroll
+                    for (int sg = 0; sg < 2; ++sg)
+#pragma unroll
+                        for (int hh = 0; hh < 2; ++hh) t[hh] = Mma<E>::mfma(aw[sg][hh], bq[sg], t[hh]);
+                }
+                const float sc = p->scale_log2e;
+                qlds[(nb * KS + s2) * 64 + lane] =
+                    u32x4_t{Mma<E>::pack2(t[0][0] * sc, t[0][1] * sc), Mma<E>::pack2(t[0][2] * sc, t[0][3] * sc),
+                            Mma<E>::pack2(t[1][0] * sc, t[1][1] * sc), Mma<E>::pack2(t[1][2] * sc, t[1][3] * sc)};
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+            for (int s2 = 0; s2 < KS; ++s2) qb[nb][s2] = qlds[(nb * KS + s2) * 64 + lane];
+    } else {
+        const char* qt = static_cast<const char*>(p->qt) + ((size_t)b * p->qt_stride + g->qt_off) * 2;
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (nb < nhb && s < ksteps) v = *reinterpret_cast<const u32x4_t*>(qt + ((size_t)(nb * 16 + l16) * rk + 8 * (4 * s + lg)) * 2);
+                qb[nb][s] = v;
+            }
+    }
+
+    f32x4_t acc[NHB][MB];
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m_run[NHB], l_run[NHB];
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; }
+
 
     for (int j = j0; j < j1; j += jstep) {
         const int t0 = (j * kWaves + wave) * kWaveTile;
@@ -381,7 +394,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         }
     }
     __syncthreads();
-    float m_all[NHB], l_all[NHB];
+    float m_all[NHB], l_all[NHB], f_own[NHB];
 #pragma unroll
     for (int nb = 0; nb < NHB; ++nb) {
         float M = -INFINITY;
@@ -393,51 +406,84 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             const float mw = red[w * NHB * 16 + nb * 16 + l16];
             L += mw == -INFINITY ? 0.f : red[kWaves * NHB * 16 + w * NHB * 16 + nb * 16 + l16] * exp2f(mw - M);
         }
-        const float f = m_run[nb] == -INFINITY ? 0.f : exp2f(m_run[nb] - M);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-            if (mb < mblocks && nb < nhb)
-                *reinterpret_cast<f32x4_t*>(accs + ((size_t)((wave * NHB + nb) * MB + mb) * 64 + lane) * 4) = acc[nb][mb] * f;
+        f_own[nb] = m_run[nb] == -INFINITY ? 0.f : exp2f(m_run[nb] - M);
         m_all[nb] = M;
         l_all[nb] = L;
     }
-    __syncthreads();
     if constexpr (kFused) {
         // ---- epilogue: out[head, :] = (O[head, :] / L) . Wl_V[:, col(head) ..] + bias -------------------
-        // normalised latent sums -> LDS [slot][rv + 4] fp32; per KV head its [rv, d_head] slice of the
-        // decoder matrix is staged in LDS and read with the transposing load; wave w owns output column
-        // blocks w, w+4, ...; the latent sums are fed as a hi + lo pair of 16-bit values.
+        // The slices [rv, d_head] of the decoder matrix (one per KV head of the group, at most four) are
+        // fetched into registers now, so that their latency hides under the merge.  The four waves then
+        // add their scaled accumulators one after the other (fixed order: deterministic) into the
+        // normalised latent sums olat[slot][rv + 4] in LDS.  Per KV head: slice -> LDS, transposing loads
+        // as B operand, latent sums as hi + lo 16-bit A operands; wave w owns output column blocks w, w+4..
+        constexpr int kMaxSeg = 4, kCpt = 4;               // slices, 16-byte chunks per thread and slice
         const int dh = p->d_head;
         const int ostride = rv + 4;
-        float* olat = accs + (size_t)kWaves * NHB * MB * 64 * 4;
+        float* olat = red + 2 * kWaves * NHB * 16;
         char* wst = reinterpret_cast<char*>(olat + (size_t)NHB * 16 * ostride);
         const int stride_w = 2 * dh + 32;
+        const int cpr = dh >> 3;
+        const char* wlv = static_cast<const char*>(g->v.wl);
+        int seg_lo[kMaxSeg], seg_hi[kMaxSeg], seg_col[kMaxSeg], nseg = 0;
+        {
+            int s0 = 0;
 #pragma unroll
-        for (int nb = 0; nb < NHB; ++nb) {
-            const float inv = 1.f / l_all[nb];
-            for (int mb = wave; mb < mblocks; mb += kWaves) {
-                f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int w = 0; w < kWaves; ++w) sacc += *reinterpret_cast<const f32x4_t*>(accs + ((size_t)((w * NHB + nb) * MB + mb) * 64 + lane) * 4);
-                *reinterpret_cast<f32x4_t*>(olat + (size_t)(nb * 16 + l16) * ostride + 16 * mb + 4 * lg) = sacc * inv;
+            for (int sg = 0; sg < kMaxSeg; ++sg) {
+                seg_lo[sg] = seg_hi[sg] = 0; seg_col[sg] = 0;
+                if (s0 < g->n_slots) {
+                    const int col = g->v_col[s0];
+                    int s1 = s0 + 1;
+                    while (s1 < g->n_slots && g->v_col[s1] == col) ++s1;
+                    seg_lo[sg] = s0; seg_hi[sg] = s1; seg_col[sg] = col; nseg = sg + 1;
+                    s0 = s1;
+                }
             }
         }
-        uint16_t* out = static_cast<uint16_t*>(p->out);
-        const char* wlv = static_cast<const char*>(g->v.wl);
-        int seg0 = 0;
-        while (seg0 < g->n_slots) {                       // uniform loop over the KV-head runs of the group
-            const int col = g->v_col[seg0];
-            int seg1 = seg0 + 1;
-            while (seg1 < g->n_slots && g->v_col[seg1] == col) ++seg1;
-            __syncthreads();                             // olat complete / previous slice consumed
-            const int cpr = dh >> 3;
-            for (int f = threadIdx.x; f < rv * cpr; f += 256) {
-                const int row = f / cpr, ch = f - row * cpr;
-                *reinterpret_cast<u32x4_t*>(wst + row * stride_w + ch * 16) =
-                    *reinterpret_cast<const u32x4_t*>(wlv + ((size_t)row * g->v.in_width + col) * 2 + ch * 16);
+        u32x4_t wreg[kMaxSeg][kCpt];
+#pragma unroll
+        for (int sg = 0; sg < kMaxSeg; ++sg)
+#pragma unroll
+            for (int i = 0; i < kCpt; ++i) {
+                const int f = i * 256 + threadIdx.x;
+                if (sg < nseg && f < rv * cpr) {
+                    const int row = f / cpr, ch = f - row * cpr;
+                    wreg[sg][i] = *reinterpret_cast<const u32x4_t*>(wlv + ((size_t)row * g->v.in_width + seg_col[sg]) * 2 + ch * 16);
+                }
+            }
+        // sequential, ordered accumulation of the four waves' scaled latent sums
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            if (wave == w) {
+#pragma unroll
+                for (int nb = 0; nb < NHB; ++nb) {
+                    const float sc = f_own[nb] / l_all[nb];
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        float* dst = olat + (size_t)(nb * 16 + l16) * ostride + 16 * mb + 4 * lg;
+                        f32x4_t v = acc[nb][mb] * sc;
+                        if (w > 0) v += *reinterpret_cast<const f32x4_t*>(dst);
+                        *reinterpret_cast<f32x4_t*>(dst) = v;
+                    }
+                }
             }
             __syncthreads();
-            for (int nb = seg0 >> 4; nb <= (seg1 - 1) >> 4; ++nb) {
+        }
+        uint16_t* out = static_cast<uint16_t*>(p->out);
+#pragma unroll
+        for (int sg = 0; sg < kMaxSeg; ++sg) {
+            if (sg >= nseg) break;
+#pragma unroll
+            for (int i = 0; i < kCpt; ++i) {
+                const int f = i * 256 + threadIdx.x;
+                if (f < rv * cpr) {
+                    const int row = f / cpr, ch = f - row * cpr;
+                    *reinterpret_cast<u32x4_t*>(wst + row * stride_w + ch * 16) = wreg[sg][i];
+                }
+            }
+            __syncthreads();
+            const int col = seg_col[sg];
+            for (int nb = seg_lo[sg] >> 4; nb <= (seg_hi[sg] - 1) >> 4; ++nb) {
                 int heads4[4];                          // query heads of this lane's four result rows
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
@@ -472,14 +518,21 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int slot = nb * 16 + 4 * lg + v;
-                        if (slot >= seg0 && slot < seg1)
+                        if (slot >= seg_lo[sg] && slot < seg_hi[sg])
                             out[((size_t)b * p->n_q_heads + heads4[v]) * dh + kcol] = Mma<E>::to16(o[v] + bias);
                     }
                 }
             }
-            seg0 = seg1;
+            __syncthreads();                             // the slice buffer is rewritten for the next KV head
         }
     } else {
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            if (mb < mblocks && nb < nhb)
+                *reinterpret_cast<f32x4_t*>(accs + ((size_t)((wave * NHB + nb) * MB + mb) * 64 + lane) * 4) = acc[nb][mb] * f_own[nb];
+    __syncthreads();
     float* part = p->part + ((size_t)b * p->n_splits + split) * p->part_stride + g->part_off;
     const int pstride = rv + 4;
 #pragma unroll
@@ -581,8 +634,10 @@ hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stre
     const int e = dtype == KVCAR_BF16 ? 0 : 1;
     if (rmax <= 128 && nhb <= 2) {
         // fused: + normalised latent sums [32][132] fp32 + one decoder-matrix slice [128][2*d_head+32]
-        const size_t lds = p.fused ? mfma_lds_bytes(128, 2) + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32) + 256
-                                   : mfma_lds_bytes(128, 2);
+        // fused epilogue: exchange area + latent sums [32][132] fp32 + one decoder slice [128][2*d_head+32]
+        const size_t epi = 1024 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);
+        const size_t stage = mfma_lds_bytes(128, 2) + (p.fused ? 2 * 4 * 64 * 16 : 0);   // + swapped query operands
+        const size_t lds = epi > stage ? epi : stage;
         return e == 0 ? launch_one(attend_mfma_r128_kernel<BF16>, lds, p, stream, set128[0])
                       : launch_one(attend_mfma_r128_kernel<F16>, lds, p, stream, set128[1]);
     }

@@ -210,8 +210,22 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     plan.fused = false;
     if (plan.mfma && !plan.mlp && splits == 1 && !ctx->tun.no_fuse && r_all <= 128 && c.d_head % 32 == 0 && c.d_head <= 128) {
         plan.fused = true;
-        for (auto& gd : plan.groups)
+        for (auto& gd : plan.groups) {
             if (gd.k.r != gd.v.r || gd.k.r % 32 || gd.k.r < 32 || gd.slots_pad > 32) plan.fused = false;
+            int segs = 0;                                   // KV heads of the group: at most four decoder slices
+            for (int sl = 0; sl < gd.n_slots; ++sl)
+                if (sl == 0 || gd.v_col[sl] != gd.v_col[sl - 1]) ++segs;
+            if (segs > 4 || gd.v.r * (c.d_head / 8) > 4 * 256) plan.fused = false;   // ... of at most 1024 16-byte chunks
+            for (int b0 = 0; b0 < gd.n_slots; b0 += 16) {   // a 16-head block may span at most two KV heads (K side)
+                int kinds = 0;
+                for (int sl = b0; sl < std::min(gd.n_slots, b0 + 16); ++sl) {
+                    bool seen = false;
+                    for (int t = b0; t < sl; ++t) seen |= gd.k_col[t] == gd.k_col[sl];
+                    if (!seen) ++kinds;
+                }
+                if (kinds > 2) plan.fused = false;
+            }
+        }
     }
     plan.qt_bytes = align_up((size_t)batch * qt * (plan.mfma ? 2 : 4), 256);
     plan.part_bytes = align_up((size_t)batch * splits * part * sizeof(float), 256);
