@@ -50,4 +50,33 @@ __device__ __forceinline__ float apply_act(float x, int act, float slope) {
     return x;
 }
 
+// erf by the rational-times-Gaussian form (Abramowitz & Stegun 7.1.26, |error| <= 1.5e-7): for GELU in
+// kernels whose result is rounded to 16 bits afterwards.
+__device__ __forceinline__ float erf_rational(float x) {
+    const float ax = fabsf(x);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * ax * ax);
+    return copysignf(fmaf(-p * t, e, 1.0f), x);
+}
+
+// Pins a value in a register as the compiler sees it.  A value that is split into a 16-bit hi part and
+// the remainder lo = x - hi must round to hi ONCE: when x is the product of two registers the compiler
+// may fold the multiply into the conversion (one rounding of the exact product) at one use and convert
+// the fp32 product (two roundings) at another, and near a rounding tie hi + lo is then off by a whole
+// unit in hi's last place.  Passing x through here first makes every use see the same fp32 value.
+__device__ __forceinline__ float pinned(float x) {
+    asm("" : "+v"(x));
+    return x;
+}
+
+__device__ __forceinline__ float apply_act_fast(float x, int act, float slope) {
+    if (act == KVCAR_ACT_LEAKY_RELU) return x >= 0.f ? x : slope * x;
+    if (act == KVCAR_ACT_GELU) return 0.5f * x * (1.f + erf_rational(x * 0.70710678118654752f));
+    return x;
+}
+
 }  // namespace kvcar

@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
                 const float bias = s.b1 ? Elem<E>::load(s.b1, col) : 0.f;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const float h = apply_act(acc1[nb][v] + bias, s.act, s.slope);
+                    const float h = pinned(apply_act(acc1[nb][v] + bias, s.act, s.slope));
                     const uint16_t hi = EncMma<E>::to16(h);
                     const uint16_t lo = EncMma<E>::to16(h - EncMma<E>::from16(hi));
                     const int row = 4 * lg + v;

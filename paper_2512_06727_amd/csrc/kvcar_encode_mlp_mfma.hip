@@ -1,0 +1,288 @@
+// MFMA encode + append for TWO-LAYER encoders (gfx950, 16-bit dtypes): z = act(x[cols] W1 + b1) W2 + b2
+// ("Network Architecture", 2nd paragraph: the encoder is two fully connected layers with an activation
+// in between), for prefill (many tokens) and decode steps alike.
+//
+// A wave owns 32 tokens and walks the hidden width in blocks of 32 columns:
+//   H^T[hidden blk, token] = W1^T . X^T   v_mfma_f32_32x32x16 (A = a column slice of W1 read from LDS with
+//                                          the transposing load, B = the token rows, resident in registers)
+//   -> + b1, activation, split into a hi + lo pair of 16-bit values: the result layout IS the A-operand
+//      layout of the second product, so the hidden activations never leave registers
+//   Z[token, r] += H[token, hidden blk] . W2[hidden blk, :]   (B = a row slice of W2, transposing load)
+// The two weight slices of the next hidden block are fetched into registers while the current block
+// computes and written to the other half of a double LDS buffer: one barrier per hidden block.
+// The latent is rounded once, from the fp32 accumulator, to the cache dtype and appended.
+#include "kvcar_device.hpp"
+
+namespace kvcar {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
+
+template <typename E> struct EMma;
+template <> struct EMma<BF16> {
+    static __device__ __forceinline__ f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ unsigned pack2(float lo, float hi) {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+        bf16x2_t v = {(__bf16)lo, (__bf16)hi};
+        return __builtin_bit_cast(unsigned, v);
+    }
+    static __device__ __forceinline__ float unpack_lo(unsigned w) { return __uint_as_float(w << 16); }
+    static __device__ __forceinline__ float unpack_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
+    static __device__ __forceinline__ uint16_t to16(float v) { return f32_to_bf16_bits(v); }
+};
+template <> struct EMma<F16> {
+    static __device__ __forceinline__ f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ unsigned pack2(float lo, float hi) {
+        typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+        f16x2_t v = {(_Float16)lo, (_Float16)hi};
+        return __builtin_bit_cast(unsigned, v);
+    }
+    static __device__ __forceinline__ float unpack_lo(unsigned w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu)); }
+    static __device__ __forceinline__ float unpack_hi(unsigned w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
+    static __device__ __forceinline__ uint16_t to16(float v) { _Float16 h = (_Float16)v; return __builtin_bit_cast(uint16_t, h); }
+};
+
+__device__ __forceinline__ u32x4_t tr_pair(const char* p, int second_offset) {
+    const s16x4_t t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
+    const s16x4_t t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p + second_offset));
+    const u32x2_t a0 = __builtin_bit_cast(u32x2_t, t0), a1 = __builtin_bit_cast(u32x2_t, t1);
+    return u32x4_t{a0[0], a0[1], a1[0], a1[1]};
+}
+
+constexpr int kEmTokens = 128;       // tokens per workgroup (4 waves x 32)
+constexpr int kW1Stride = 64 + 32;   // LDS row stride of a [in, 32] slice of W1 (bytes)
+
+// KX: k-steps over the input width (in_width == 16 KX exactly); NBZ: 32-column blocks of the latent
+// (r == 32 NBZ exactly); GELU: the activation is GELU, else leaky ReLU with the side's slope (the identity
+// is slope 1). Exact compile-time shapes keep the whole hidden-block body one straight-line block: with
+// run-time guards every transposing load sat in a block of its own and paid its LDS latency serially.
+template <typename E, int KX, int NBZ, bool GELU>
+__global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p, int side0) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const EncodeSide& s = p.s[blockIdx.y + side0];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
+    const int n_tok = p.batch * p.t_new;
+    const int tok = blockIdx.x * kEmTokens + wave * 32 + l32;       // the token column (B operand) of this lane
+    const bool tok_ok = tok < n_tok;
+    constexpr int in_w = 16 * KX, r = 32 * NBZ;
+    constexpr int w2_stride = 2 * r + 32;
+    constexpr int w2_off = in_w * kW1Stride;
+    constexpr int buf_bytes = w2_off + 32 * w2_stride;
+    const int hid = s.hidden;
+    const int n_mb = hid >> 5;
+    const float slope = s.act == KVCAR_ACT_LEAKY_RELU ? s.slope : 1.f;
+
+    // token rows, resident: k-step ks holds input columns 16ks + 8h .. +7 of this lane's token
+    u32x4_t xr[KX];
+    {
+        const char* xrow = static_cast<const char*>(s.x) + (size_t)(tok_ok ? tok : 0) * p.d_kv * 2;
+#pragma unroll
+        for (int ks = 0; ks < KX; ++ks) {
+            const int kk = 16 * ks + 8 * h;
+            const int src_col = (int)s.heads[kk / p.d_head] * p.d_head + kk % p.d_head;
+            u32x4_t v = *reinterpret_cast<const u32x4_t*>(xrow + src_col * 2);
+            if (!tok_ok) v = u32x4_t{0u, 0u, 0u, 0u};
+            xr[ks] = v;
+        }
+    }
+
+    // weight slices of hidden block mb: W1[:, 32mb .. +32] (in_w rows of 64 bytes) and W2[32mb .. +32, :]
+    // (32 rows of 2r bytes); 16-byte chunk f of the pair belongs to thread f % 256
+    constexpr int c1 = in_w * 4, c2 = 32 * (r >> 3), cpr = r >> 3;
+    constexpr int n_pre = (c1 + c2 + 255) / 256;
+    u32x4_t pre[n_pre];
+    auto fetch = [&](int mb) {
+#pragma unroll
+        for (int i = 0; i < n_pre; ++i) {
+            const int f = i * 256 + tid;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (f < c1) {
+                const int row = f >> 2, ch = f & 3;
+                v = *reinterpret_cast<const u32x4_t*>(static_cast<const char*>(s.w1) + ((size_t)row * hid + 32 * mb) * 2 + ch * 16);
+            } else if (f < c1 + c2) {
+                const int g2 = f - c1;
+                const int row = g2 / cpr, ch = g2 - row * cpr;
+                v = *reinterpret_cast<const u32x4_t*>(static_cast<const char*>(s.w2) + ((size_t)(32 * mb + row) * r) * 2 + ch * 16);
+            }
+            pre[i] = v;
+        }
+    };
+    auto park = [&](char* buf) {
+#pragma unroll
+        for (int i = 0; i < n_pre; ++i) {
+            const int f = i * 256 + tid;
+            if (f < c1) {
+                const int row = f >> 2, ch = f & 3;
+                *reinterpret_cast<u32x4_t*>(buf + row * kW1Stride + ch * 16) = pre[i];
+            } else if (f < c1 + c2) {
+                const int g2 = f - c1;
+                const int row = g2 / cpr, ch = g2 - row * cpr;
+                *reinterpret_cast<u32x4_t*>(buf + w2_off + row * w2_stride + ch * 16) = pre[i];
+            }
+        }
+    };
+
+    f32x16_t accz[NBZ];
+#pragma unroll
+    for (int nb = 0; nb < NBZ; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accz[nb][v] = 0.f;
+
+    // first-layer bias -> LDS (fp32), read from there inside the loop: a global load in the loop body
+    // would queue behind the weight prefetch and serialise its latency into every block
+    float* b1s = reinterpret_cast<float*>(lds + 2 * buf_bytes);
+    for (int i = tid; i < hid; i += 256) b1s[i] = s.b1 ? Elem<E>::load(s.b1, i) : 0.f;
+
+    fetch(0);
+    for (int mb = 0; mb < n_mb; ++mb) {
+        char* buf = lds + (mb & 1) * buf_bytes;
+        park(buf);
+        if (mb + 1 < n_mb) fetch(mb + 1);
+        __syncthreads();          // slice mb visible; every wave is past block mb-1, whose buffer the next park reuses
+
+        // bias of this lane's hidden rows 32mb + 8a + 4h + j: four 16-byte reads
+        f32x4_t bq[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) bq[a] = *reinterpret_cast<const f32x4_t*>(b1s + 32 * mb + 8 * a + 4 * h);
+
+        // ---- H^T[hidden blk, token] ------------------------------------------------------------
+        f32x16_t ht;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ht[v] = 0.f;
+        const char* w1row = buf + (8 * h + (l16 >> 2)) * kW1Stride + (16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KX; ++ks)
+            ht = EMma<E>::mfma(tr_pair(w1row + 16 * ks * kW1Stride, 4 * kW1Stride), xr[ks], ht);
+        // lane: token l32, hidden rows 32mb + 8a + 4h + j  (register v = 4a + j)
+        u32x4_t hi[2], lo[2];
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            unsigned wh[4], wl[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float a[2];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int v = 8 * s2 + 2 * e + q;
+                    const float x = ht[v] + bq[v >> 2][v & 3];
+                    if constexpr (GELU) a[q] = pinned(0.5f * x * (1.f + erf_rational(x * 0.70710678118654752f)));
+                    else a[q] = pinned(x >= 0.f ? x : slope * x);
+                }
+                wh[e] = EMma<E>::pack2(a[0], a[1]);
+                wl[e] = EMma<E>::pack2(a[0] - EMma<E>::unpack_lo(wh[e]), a[1] - EMma<E>::unpack_hi(wh[e]));
+            }
+            hi[s2] = u32x4_t{wh[0], wh[1], wh[2], wh[3]};
+            lo[s2] = u32x4_t{wl[0], wl[1], wl[2], wl[3]};
+        }
+        // ---- Z[token, :] += H[token, hidden blk] . W2[hidden blk, :] ------------------------------
+        // k-slots of lane half h in k-step s2 are hidden rows 16 s2 + 4h + j and 16 s2 + 8 + 4h + j
+        const char* w2base = buf + w2_off + (4 * h + (l16 >> 2)) * w2_stride + (16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int nb = 0; nb < NBZ; ++nb) {
+                const u32x4_t bw = tr_pair(w2base + 16 * s2 * w2_stride + nb * 64, 8 * w2_stride);
+                accz[nb] = EMma<E>::mfma(hi[s2], bw, accz[nb]);
+                accz[nb] = EMma<E>::mfma(lo[s2], bw, accz[nb]);
+            }
+    }
+
+    // ---- latent rows: bias, one rounding to the cache dtype, append --------------------------------
+    // lane holds latent column 32nb + l32 of tokens 8a + 4h + j
+    uint16_t* z = static_cast<uint16_t*>(s.z);
+    const int tbase = blockIdx.x * kEmTokens + wave * 32;
+    float b2v[NBZ];
+#pragma unroll
+    for (int nb = 0; nb < NBZ; ++nb) b2v[nb] = s.b2 ? Elem<E>::load(s.b2, 32 * nb + l32) : 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int t = tbase + 8 * (v >> 2) + 4 * h + (v & 3);
+        if (t >= n_tok) continue;
+        const int b = t / p.t_new, tt = t - b * p.t_new;
+        const size_t row_off = ((size_t)b * p.max_seq + p.pos0 + tt) * r;
+#pragma unroll
+        for (int nb = 0; nb < NBZ; ++nb) z[row_off + 32 * nb + l32] = EMma<E>::to16(accz[nb][v] + b2v[nb]);
+    }
+}
+
+namespace {
+
+struct EmShape { int kx, nbz; };
+constexpr EmShape kEmShapes[] = {{4, 1}, {8, 2}, {12, 3}, {16, 4}, {16, 2}, {8, 1}};
+
+bool em_side_ok(const EncodeSide& s) {
+    if (s.hidden <= 0 || s.hidden % 32 || s.hidden > 1024) return false;
+    if (s.act != KVCAR_ACT_GELU && s.act != KVCAR_ACT_LEAKY_RELU && s.act != KVCAR_ACT_NONE) return false;
+    for (const EmShape& e : kEmShapes)
+        if (s.in_width == 16 * e.kx && s.r == 32 * e.nbz) return true;
+    return false;
+}
+
+template <typename E, int KX, int NBZ>
+hipError_t em_launch_shape(const EncodeParams& p, int side0, int n_sides, bool gelu, hipStream_t stream) {
+    const int n_tok = p.batch * p.t_new;
+    dim3 grid((n_tok + kEmTokens - 1) / kEmTokens, n_sides);
+    constexpr size_t lds = 2 * (size_t)(16 * KX * kW1Stride + 32 * (64 * NBZ + 32)) + 4 * 1024;     // + first-layer bias
+    auto kern = gelu ? encode_mlp_mfma_kernel<E, KX, NBZ, true> : encode_mlp_mfma_kernel<E, KX, NBZ, false>;
+    static bool attr[2] = {false, false};
+    if (lds > 64 * 1024 && !attr[gelu]) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        attr[gelu] = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p, side0);
+    return hipGetLastError();
+}
+
+template <typename E>
+hipError_t em_launch(const EncodeParams& p, int side0, int n_sides, hipStream_t stream) {
+    const EncodeSide& s = p.s[side0];
+    const bool gelu = s.act == KVCAR_ACT_GELU;
+    const int kx = s.in_width / 16, nbz = s.r / 32;
+    if (kx == 4 && nbz == 1) return em_launch_shape<E, 4, 1>(p, side0, n_sides, gelu, stream);
+    if (kx == 8 && nbz == 2) return em_launch_shape<E, 8, 2>(p, side0, n_sides, gelu, stream);
+    if (kx == 12 && nbz == 3) return em_launch_shape<E, 12, 3>(p, side0, n_sides, gelu, stream);
+    if (kx == 16 && nbz == 4) return em_launch_shape<E, 16, 4>(p, side0, n_sides, gelu, stream);
+    if (kx == 16 && nbz == 2) return em_launch_shape<E, 16, 2>(p, side0, n_sides, gelu, stream);
+    if (kx == 8 && nbz == 1) return em_launch_shape<E, 8, 1>(p, side0, n_sides, gelu, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+// 16-bit dtype, every stored tensor two-layer with one of the compiled (input width, latent) shapes,
+// 8-column chunks inside one head, hidden width a multiple of 32 up to 1024.
+bool encode_mlp_mfma_supported(const EncodeParams& p, int dtype) {
+    if (dtype == KVCAR_F32 || p.d_head % 8) return false;
+    bool any = false;
+    for (int i = 0; i < 2; ++i) {
+        const EncodeSide& s = p.s[i];
+        if (s.r == 0) continue;
+        if (!em_side_ok(s)) return false;
+        any = true;
+    }
+    return any;
+}
+
+// One launch covers both tensors when they share shape and activation; otherwise one launch per tensor.
+hipError_t launch_encode_mlp_mfma(const EncodeParams& p, int dtype, hipStream_t stream) {
+    const EncodeSide &k = p.s[0], &v = p.s[1];
+    auto go = [&](int side0, int n) { return dtype == KVCAR_BF16 ? em_launch<BF16>(p, side0, n, stream) : em_launch<F16>(p, side0, n, stream); };
+    if (k.r && v.r && k.in_width == v.in_width && k.r == v.r && (k.act == KVCAR_ACT_GELU) == (v.act == KVCAR_ACT_GELU)) return go(0, 2);
+    hipError_t err = hipSuccess;
+    if (k.r) err = go(0, 1);
+    if (err == hipSuccess && v.r) err = go(1, 1);
+    return err;
+}
+
+}  // namespace kvcar

@@ -427,9 +427,11 @@ int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void
         any = true;
     }
     if (!any) return KVCAR_OK;   // the layer stores nothing
-    const bool mfma = !ctx->tun.force_generic && encode_mfma_supported(p, c.dtype);
-    hipError_t e = mfma ? launch_encode_mfma(p, c.dtype, static_cast<hipStream_t>(stream))
-                        : launch_encode_generic(p, c.dtype, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (!ctx->tun.force_generic && encode_mlp_mfma_supported(p, c.dtype)) e = launch_encode_mlp_mfma(p, c.dtype, st);
+    else if (!ctx->tun.force_generic && encode_mfma_supported(p, c.dtype)) e = launch_encode_mfma(p, c.dtype, st);
+    else e = launch_encode_generic(p, c.dtype, st);
     if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "encode launch failed: %s", hipGetErrorString(e));
     return KVCAR_OK;
 }

@@ -85,6 +85,10 @@ size_t attend_generic_lds_bytes(const GroupDesc& g);
 bool encode_mfma_supported(const EncodeParams& p, int dtype);
 hipError_t launch_encode_mfma(const EncodeParams& p, int dtype, hipStream_t stream);
 
+// MFMA encoder for two-layer encoders (32-token waves, hidden activations kept in registers).
+bool encode_mlp_mfma_supported(const EncodeParams& p, int dtype);
+hipError_t launch_encode_mlp_mfma(const EncodeParams& p, int dtype, hipStream_t stream);
+
 // MFMA versions of the absorbed-query prologue and the merge + output epilogue.
 bool proj_mfma_supported(const AttendParams& p, int dtype);
 hipError_t launch_qtilde_mfma(const AttendParams& p, int dtype, hipStream_t stream);

@@ -208,9 +208,15 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
             if (row < rows) {
                 const int b = row / len, i = row - b * len;
                 const float* prow = p.part + (size_t)b * ns * p.part_stride + g.part_off + (size_t)(s0 + i) * pstride + 4 + 4 * c4;
-                for (int k = 0; k < ns; ++k) {
-                    const float w = wts[r * ns + k];
-                    if (w != 0.f) a += *reinterpret_cast<const f32x4_t*>(prow + (size_t)k * p.part_stride) * w;
+                // four partials in flight at a time (a load inside a one-at-a-time loop pays its latency each turn)
+                for (int k = 0; k < ns; k += 4) {
+                    f32x4_t x[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        x[u] = k + u < ns ? *reinterpret_cast<const f32x4_t*>(prow + (size_t)(k + u) * p.part_stride) : f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (k + u < ns) a += x[u] * wts[r * ns + k + u];
                 }
             }
             *reinterpret_cast<f32x4_t*>(om + (size_t)r * pstride + 4 * c4) = a;
