@@ -114,6 +114,7 @@ def main():
     ap.add_argument("--fill", default="encode", choices=["encode", "random"],
                     help="encode: caches filled by kvcar_encode_append of seeded K/V (default); random: torch.randn latents and "
                          "inputs (profiling runs only: same traffic, far fewer helper kernels)")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -191,6 +192,28 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     tokens_per_s = w.batch * args.steps / elapsed
 
+    # the same step as a HIP graph: captured once at the last step's positions, replayed `steps` times
+    graph_ms = None
+    if not args.no_graph:
+        last = total_steps - 1
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step_fn(last)                                  # every kernel has run once on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step_fn(last)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        del graph
+
     # second pass over the same steps with HIP events around the attention kernel
     ctx.profile_enable(True)
     for step in range(args.warmup, total_steps):
@@ -209,6 +232,13 @@ def main():
         import re
         m = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tpath).read())
         traffic = float(m.group(1)) if m else None
+
+    # what a kernel that only reads reaches on this GPU: sweeps over a 4 GiB buffer (long enough that the
+    # ramp-up and tail of a launch do not count)
+    probe = torch.zeros(1 << 32, dtype=torch.uint8, device=dev)
+    n_probe = probe.numel()
+    read_ceiling = binding.probe_read_bandwidth(probe, repeats=4)
+    del probe
 
     if args.calibrate_copy:
         src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
@@ -243,7 +273,11 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg / max(1, n_launch),
                      "avg_launch_ms": attend_ms / max(1, n_launch), "launches": n_launch,
-                     "whole_step_GBs": alg / args.steps / (ms_per_step * 1e-3) / 1e9},
+                     "whole_step_GBs": alg / args.steps / (ms_per_step * 1e-3) / 1e9,
+                     "read_ceiling_GBs": read_ceiling, "frac_of_read_ceiling": achieved / read_ceiling,
+                     "read_ceiling_bytes": n_probe},
+        "graph_replay": None if graph_ms is None else {"ms_per_step": graph_ms, "tokens_per_s": w.batch / (graph_ms * 1e-3),
+                                                       "note": "one captured step (all layers) replayed at fixed positions"},
         "capacity_tokens_288GB": {"uncompressed": int(hbm // full_tok), "latent": int(hbm // lat_tok),
                                   "bytes_per_token_uncompressed": full_tok, "bytes_per_token_latent": lat_tok},
     }

@@ -204,6 +204,17 @@ int kvcar_describe_plan(const kvcar_ctx *ctx, int layer, int batch, int n_ctx, k
 int kvcar_profile_enable(kvcar_ctx *ctx, int enable);
 int kvcar_profile_read(kvcar_ctx *ctx, double *attend_ms, long *n_launches);
 
+/*
+ * Read-only streaming ceiling of the device: a kernel with no arithmetic reads `bytes` bytes of
+ * `dev_buf` (device memory, 16-byte aligned, bytes a multiple of 16) `repeats` times with 16-byte
+ * non-temporal loads, one grid-stride sweep per repeat, timed with HIP events on `stream`, for a
+ * few launch shapes.  Writes the best achieved GB/s (1e9 bytes per second) to *gb_per_s.  This is the bandwidth a kernel
+ * that only reads can reach on this GPU: the attention kernel's rate is reported against it as
+ * well as against the published peak.  Blocks until the kernels have finished.  The buffer is
+ * not modified.  KVCAR_ERR_ARG for null / misaligned arguments, KVCAR_ERR_HIP if a HIP call fails.
+ */
+int kvcar_probe_read_bandwidth(const void *dev_buf, size_t bytes, int repeats, void *stream, double *gb_per_s);
+
 /* Human-readable name of a status code (static string). */
 const char *kvcar_status_string(int status);
 

@@ -61,6 +61,7 @@ SYMBOLS = {
     "kvcar_describe_plan": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(PlanInfo)]),
     "kvcar_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "kvcar_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_long)]),
+    "kvcar_probe_read_bandwidth": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.POINTER(C.c_double)]),
     "kvcar_status_string": (C.c_char_p, [C.c_int]),
     "kvcar_last_error": (C.c_char_p, [C.c_void_p]),
 }
@@ -97,6 +98,15 @@ def _ptr(t) -> Optional[int]:
 def _stream() -> C.c_void_p:
     import torch
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def probe_read_bandwidth(buf, repeats: int = 8) -> float:
+    """GB/s of a read-only sweep over the tensor `buf` (kvcar_probe_read_bandwidth)."""
+    out = C.c_double(0.0)
+    st = lib().kvcar_probe_read_bandwidth(_ptr(buf), buf.numel() * buf.element_size(), repeats, _stream(), C.byref(out))
+    if st != 0:
+        raise KVCARError(st, "kvcar_probe_read_bandwidth")
+    return out.value
 
 
 class Context:

@@ -306,4 +306,24 @@ hipError_t launch_combine(const AttendParams& p, int dtype, hipStream_t stream) 
     return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Read-only streaming probe: every lane folds 16-byte non-temporal loads into a checksum; one
+// word per workgroup is written so that the loads cannot be dropped.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) unsigned probe_u32x4_t;
+
+__global__ __launch_bounds__(512) void stream_read_kernel(const probe_u32x4_t* __restrict__ src, size_t n16, unsigned* __restrict__ sink) {
+    probe_u32x4_t acc = {0u, 0u, 0u, 0u};
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    const unsigned x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+    if (x == 0x9e3779b9u && sink) sink[blockIdx.x] = x;     // practically never true: keeps the loads alive
+}
+
+hipError_t launch_stream_read(const void* src, size_t bytes, int n_blocks, int block, unsigned* sink, hipStream_t stream) {
+    hipLaunchKernelGGL(stream_read_kernel, dim3(n_blocks), dim3(block), 0, stream, static_cast<const probe_u32x4_t*>(src), bytes / 16, sink);
+    return hipGetLastError();
+}
+
 }  // namespace kvcar

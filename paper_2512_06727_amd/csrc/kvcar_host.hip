@@ -531,6 +531,38 @@ int kvcar_profile_read(kvcar_ctx* ctx, double* attend_ms, long* n_launches) {
     return KVCAR_OK;
 }
 
+int kvcar_probe_read_bandwidth(const void* dev_buf, size_t bytes, int repeats, void* stream, double* gb_per_s) {
+    if (!dev_buf || !gb_per_s || bytes < 16 || bytes % 16 || repeats < 1 || (reinterpret_cast<uintptr_t>(dev_buf) & 15)) return KVCAR_ERR_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return KVCAR_ERR_HIP;
+    if (n_cu <= 0) n_cu = 256;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return KVCAR_ERR_HIP;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return KVCAR_ERR_HIP; }
+    // the best of a few launch shapes (workgroups per compute unit x lanes per workgroup)
+    static const int shapes[][2] = {{4, 256}, {8, 256}, {16, 256}, {32, 256}, {4, 512}, {8, 512}, {16, 512}};
+    double best = 0.0;
+    hipError_t e = hipSuccess;
+    for (const auto& sh : shapes) {
+        const int n_blocks = sh[0] * n_cu;
+        e = kvcar::launch_stream_read(dev_buf, bytes, n_blocks, sh[1], nullptr, st);          // untimed first pass
+        if (e == hipSuccess) e = hipEventRecord(e0, st);
+        for (int i = 0; i < repeats && e == hipSuccess; ++i) e = kvcar::launch_stream_read(dev_buf, bytes, n_blocks, sh[1], nullptr, st);
+        if (e == hipSuccess) e = hipEventRecord(e1, st);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) break;
+        if (ms > 0.f) best = std::max(best, (double)bytes * repeats / (ms * 1e-3) / 1e9);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess || best <= 0.0) return KVCAR_ERR_HIP;
+    *gb_per_s = best;
+    return KVCAR_OK;
+}
+
 const char* kvcar_status_string(int s) {
     switch (s) {
         case KVCAR_OK: return "KVCAR_OK";
