@@ -22,11 +22,19 @@ All arithmetic is float64.  The only rounding that belongs to the method is the
 one at the store (the cache holds P-byte elements, Eq. 3); it is done as
 fp64 -> fp32 -> cache dtype, round-to-nearest-even.
 
+Optional int8 latents (Methodology, "Quantization", Eq. "quant"): step 2 then
+quantises each latent row to int8 codes with a per-row scale and zero point, and
+step 4 dequantises the row before the decoder.  The quantiser's decisions (min,
+max, scale, zero point, codes) are integer-valued results of floating point, so
+they are taken in fp32, one IEEE operation at a time, as the kernels take them.
+
 Pins (tests/test_oracle_*.py): pure-Python brute force on tiny shapes, a library
 SDPA on the decoded K/V, r = D with an orthogonal autoencoder == uncompressed
 attention, all-false reuse map == per-layer attention, softmax rows sum to 1,
 q = 0 closed form, peaked q, chained reuse vs explicit copies, rounding vs hand
-cases and a library cast, GELU vs erf.  The numerical values a *trained*
+cases and a library cast, GELU vs erf; the quantiser vs a hand-worked row, exact
+rational arithmetic, an arithmetic progression (codes -128..127), the half-step
+error bound, and invariance under positive dyadic scaling and shifts.  The numerical values a *trained*
 autoencoder would produce are "parity unpinned": the paper ships no weights.
 """
 from __future__ import annotations
@@ -137,6 +145,43 @@ class Autoencoder:
 
 
 # --------------------------------------------------------------------------
+# int8 quantisation of latent rows ("Quantization", Eq. "quant")
+# --------------------------------------------------------------------------
+def quantize_rows(z: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Eq. "quant" applied to each row (last axis) of z:
+
+        scale     = 255 / (max(x) - min(x))
+        zeropoint = -round(scale * min(x)) - 128
+        Xquant    = round(scale * x + zeropoint)
+
+    Returns (codes int8 [..., r], scale fp32 [...], zeropoint int32 [...]).
+    Readings where the paper is silent: x is one token's latent row; round is
+    round-half-to-even; codes saturate to [-128, 127] (the two roundings can
+    push max(x) to 128); a constant row uses |x| in place of the zero range
+    (then it is reproduced exactly), an all-zero row uses 1.  Every operation is
+    a single fp32 operation (the input is rounded to fp32 first)."""
+    f32 = np.float32
+    x = np.asarray(z, dtype=np.float64).astype(f32)
+    mx = x.max(axis=-1)
+    mn = x.min(axis=-1)
+    rng = (mx - mn).astype(f32)
+    rng = np.where(rng == 0, np.abs(mx), rng).astype(f32)
+    rng = np.where(rng == 0, f32(1), rng).astype(f32)
+    scale = (f32(255) / rng).astype(f32)
+    zp = (-np.rint((scale * mn).astype(f32)) - f32(128)).astype(f32)
+    t = (scale[..., None] * x).astype(f32)
+    q = np.rint((t + zp[..., None]).astype(f32))
+    codes = np.clip(q, -128, 127).astype(np.int8)
+    return codes, scale, zp.astype(np.int64).clip(-2**31, 2**31 - 1).astype(np.int32)
+
+
+def dequantize_rows(codes: np.ndarray, scale: np.ndarray, zeropoint: np.ndarray) -> np.ndarray:
+    """Eq. "quant", last line: Xdequant = (Xquant - zeropoint) / scale, in fp64."""
+    c = np.asarray(codes, dtype=np.float64)
+    return (c - np.asarray(zeropoint, np.float64)[..., None]) / np.asarray(scale, np.float64)[..., None]
+
+
+# --------------------------------------------------------------------------
 # head reuse (step 3)
 # --------------------------------------------------------------------------
 def resolve_source(reuse: np.ndarray, layer: int, which: int, head: int) -> int:
@@ -160,7 +205,8 @@ def resolve_source(reuse: np.ndarray, layer: int, which: int, head: int) -> int:
 # --------------------------------------------------------------------------
 class KVCAROracle:
     def __init__(self, n_layers: int, n_q_heads: int, n_kv_heads: int, d_head: int,
-                 max_batch: int, max_seq: int, dtype: str, softmax_scale: Optional[float] = None):
+                 max_batch: int, max_seq: int, dtype: str, softmax_scale: Optional[float] = None,
+                 latent_format: str = "dtype"):
         assert n_q_heads % n_kv_heads == 0
         self.n_layers, self.hq, self.hkv, self.dh = n_layers, n_q_heads, n_kv_heads, d_head
         self.max_batch, self.max_seq, self.dtype = max_batch, max_seq, dtype
@@ -168,6 +214,12 @@ class KVCAROracle:
         self.reuse = np.zeros((n_layers, 2, n_kv_heads), dtype=bool)
         self.ae: Dict[Tuple[int, int], Autoencoder] = {}
         self.Z: Dict[Tuple[int, int], np.ndarray] = {}   # latent caches, values already rounded
+        # "int8": rows are stored as codes + (scale, zeropoint) per row; Z then holds their dequantised values
+        assert latent_format in ("dtype", "int8")
+        self.latent_format = latent_format
+        self.Q: Dict[Tuple[int, int], np.ndarray] = {}         # int8 codes [B, L, r]
+        self.Qscale: Dict[Tuple[int, int], np.ndarray] = {}    # fp32 [B, L]
+        self.Qzero: Dict[Tuple[int, int], np.ndarray] = {}     # int32 [B, L]
 
     # -- configuration ------------------------------------------------------
     def set_reuse_map(self, layer: int, k_reuse, v_reuse) -> None:
@@ -182,6 +234,10 @@ class KVCAROracle:
         assert ae.width == len(ae.heads) * self.dh
         self.ae[(layer, which)] = ae
         self.Z[(layer, which)] = np.full((self.max_batch, self.max_seq, ae.latent), np.nan)
+        if self.latent_format == "int8":
+            self.Q[(layer, which)] = np.zeros((self.max_batch, self.max_seq, ae.latent), np.int8)
+            self.Qscale[(layer, which)] = np.zeros((self.max_batch, self.max_seq), np.float32)
+            self.Qzero[(layer, which)] = np.zeros((self.max_batch, self.max_seq), np.int32)
 
     # -- steps 1+2 ----------------------------------------------------------
     def encode_append(self, layer: int, k_new: np.ndarray, v_new: np.ndarray, pos0: int) -> None:
@@ -195,7 +251,14 @@ class KVCAROracle:
             assert b <= self.max_batch and pos0 + t <= self.max_seq
             cols = np.concatenate([np.arange(g * self.dh, (g + 1) * self.dh) for g in ae.heads])
             z = ae.encode(x[:, :, cols])
-            self.Z[(layer, which)][:b, pos0:pos0 + t, :] = round_to_dtype(z, self.dtype)
+            if self.latent_format == "int8":
+                codes, scale, zp = quantize_rows(z)
+                self.Q[(layer, which)][:b, pos0:pos0 + t, :] = codes
+                self.Qscale[(layer, which)][:b, pos0:pos0 + t] = scale
+                self.Qzero[(layer, which)][:b, pos0:pos0 + t] = zp
+                self.Z[(layer, which)][:b, pos0:pos0 + t, :] = dequantize_rows(codes, scale, zp)
+            else:
+                self.Z[(layer, which)][:b, pos0:pos0 + t, :] = round_to_dtype(z, self.dtype)
 
     # -- steps 3+4 ----------------------------------------------------------
     def decoded_head(self, layer: int, which: int, head: int, b: int, n_ctx: int,
@@ -251,6 +314,13 @@ def latent_cache_bytes(bytes_per_elem: int, latent_widths: np.ndarray, seq_len: 
     """Eq. 3 with each layer's K and V width replaced by what that layer stores:
     latent_widths[N][which] elements per token."""
     return int(bytes_per_elem * int(np.asarray(latent_widths).sum()) * seq_len * batch)
+
+
+def quantized_latent_cache_bytes(latent_widths: np.ndarray, seq_len: int, batch: int) -> int:
+    """int8 latents: one byte per latent element plus, per stored row, the fp32 scale and
+    the int32 zero point that the dequantisation of Eq. "quant" needs (8 bytes)."""
+    w = np.asarray(latent_widths)
+    return int((int(w.sum()) + 8 * int((w > 0).sum())) * seq_len * batch)
 
 
 def savings_autoencoder(n_compressed_layers: int, n_layers: int, ratio: float) -> float:
