@@ -32,6 +32,18 @@
  * Latent cache layout (library-defined, caller-allocated): for layer N and tensor `which`
  *   Z[b][t][c],  b < max_batch, t < max_seq, c < r   row-major, r = latent_width of that
  *   layer-tensor; one row is r * sizeof(dtype) bytes; kvcar_cache_bytes gives the total.
+ *
+ * int8 latents (kvcar_config.latent_format = KVCAR_LATENT_INT8; Methodology, "Quantization",
+ * Eq. "quant"): kvcar_encode_append quantises every latent row after the encoder,
+ *   scale = 255 / (max(x) - min(x)),  zeropoint = -round(scale * min(x)) - 128,
+ *   code  = round(scale * x + zeropoint)   saturated to [-128, 127],
+ * over the r elements x of the row (fp32 encoder output, round = half to even, every operation
+ * one fp32 operation; a row of equal values uses |x| as its range, or 1 if x = 0), and
+ * kvcar_decode_attention dequantises, x^ = (code - zeropoint) / scale, before the decoder.
+ * The cache of (layer, which) is then one buffer holding
+ *   codes  int8  Z8[b][t][c]            at byte offset 0, followed at the next multiple of 256 by
+ *   meta   M[b][t] = { float scale; int32 zeropoint; }   8 bytes per row;
+ * r must be a multiple of 16.  Activations, weights and outputs keep the configured dtype.
  */
 #ifndef KVCAR_H
 #define KVCAR_H
@@ -59,6 +71,10 @@ typedef enum {
 
 typedef enum { KVCAR_F32 = 0, KVCAR_F16 = 1, KVCAR_BF16 = 2 } kvcar_dtype;
 
+/* How latent rows are held in the cache: in the model dtype, or as int8 codes with a scale and
+ * a zero point per row ("Quantization", Eq. "quant"). */
+typedef enum { KVCAR_LATENT_DTYPE = 0, KVCAR_LATENT_INT8 = 1 } kvcar_latent_format;
+
 /* Activation between the two fully connected layers of an encoder / decoder.  NONE = the
  * autoencoder is a single linear map each way. */
 typedef enum { KVCAR_ACT_NONE = 0, KVCAR_ACT_LEAKY_RELU = 1, KVCAR_ACT_GELU = 2 /* erf form */ } kvcar_act;
@@ -75,6 +91,7 @@ typedef struct {
     int max_seq;        /* capacity of every latent cache, in tokens                          */
     int dtype;          /* kvcar_dtype                                                        */
     float softmax_scale; /* 0 => 1/sqrt(d_head), the scaling of Eq. 1                         */
+    int latent_format;  /* kvcar_latent_format; 0 = rows in `dtype`                           */
 } kvcar_config;
 
 /*
@@ -114,7 +131,7 @@ typedef struct {
 } kvcar_tuning;
 
 /* Create / destroy a context.  ERR_ARG on null pointers, ERR_SHAPE on non-positive sizes or
- * n_q_heads % n_kv_heads != 0, ERR_UNSUPPORTED on an unknown dtype. */
+ * n_q_heads % n_kv_heads != 0, ERR_UNSUPPORTED on an unknown dtype or latent format. */
 int kvcar_create(const kvcar_config *cfg, kvcar_ctx **out);
 int kvcar_destroy(kvcar_ctx *ctx);
 
@@ -136,7 +153,9 @@ int kvcar_resolve_source(const kvcar_ctx *ctx, int layer, int which, int kv_head
 int kvcar_set_autoencoder(kvcar_ctx *ctx, int layer, int which, const kvcar_ae_desc *desc);
 
 /* Bytes of the latent cache of (layer, which): max_batch * max_seq * latent_width * sizeof(dtype)
- * (Eq. 3 with d_model replaced by what the layer-tensor stores).  Needs the autoencoder set. */
+ * (Eq. 3 with d_model replaced by what the layer-tensor stores); with int8 latents the codes
+ * (one byte per element, padded to a multiple of 256 bytes) plus 8 bytes of scale and zero point
+ * per row.  Needs the autoencoder set. */
 int kvcar_cache_bytes(const kvcar_ctx *ctx, int layer, int which, size_t *bytes);
 
 /* Bind caller-allocated device memory as the cache of (layer, which).  ERR_CAPACITY if `bytes`

@@ -158,7 +158,7 @@ def quantize_rows(z: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     Readings where the paper is silent: x is one token's latent row; round is
     round-half-to-even; codes saturate to [-128, 127] (the two roundings can
     push max(x) to 128); a constant row uses |x| in place of the zero range
-    (then it is reproduced exactly), an all-zero row uses 1.  Every operation is
+    (then it is reproduced up to the rounding of the scale), an all-zero row uses 1.  Every operation is
     a single fp32 operation (the input is rounded to fp32 first)."""
     f32 = np.float32
     x = np.asarray(z, dtype=np.float64).astype(f32)

@@ -21,11 +21,13 @@ K, V = 0, 1
 
 DTYPES = {"f32": F32, "f16": F16, "bf16": BF16}
 ACTS = {"none": ACT_NONE, "leaky_relu": ACT_LEAKY_RELU, "gelu": ACT_GELU}
+LATENT_FORMATS = {"dtype": 0, "int8": 1}
 
 
 class Config(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("d_head", C.c_int),
-                ("max_batch", C.c_int), ("max_seq", C.c_int), ("dtype", C.c_int), ("softmax_scale", C.c_float)]
+                ("max_batch", C.c_int), ("max_seq", C.c_int), ("dtype", C.c_int), ("softmax_scale", C.c_float),
+                ("latent_format", C.c_int)]
 
 
 class AEDesc(C.Structure):
@@ -113,9 +115,10 @@ class Context:
     """Thin owner of a kvcar_ctx.  Methods mirror the C entry points one to one."""
 
     def __init__(self, n_layers: int, n_q_heads: int, n_kv_heads: int, d_head: int, max_batch: int, max_seq: int,
-                 dtype: str, softmax_scale: float = 0.0):
+                 dtype: str, softmax_scale: float = 0.0, latent_format: str = "dtype"):
         self._h = C.c_void_p()
-        cfg = Config(n_layers, n_q_heads, n_kv_heads, d_head, max_batch, max_seq, DTYPES[dtype], softmax_scale)
+        cfg = Config(n_layers, n_q_heads, n_kv_heads, d_head, max_batch, max_seq, DTYPES[dtype], softmax_scale,
+                     LATENT_FORMATS[latent_format])
         st = lib().kvcar_create(C.byref(cfg), C.byref(self._h))
         if st != OK:
             raise KVCARError(st, "kvcar_create")

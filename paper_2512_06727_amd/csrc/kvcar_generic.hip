@@ -29,6 +29,7 @@ __global__ __launch_bounds__(256) void encode_generic_kernel(EncodeParams p) {
     const int nt = min(kEncTok, n_tok - tok0);
     float* xs = smem;                              // [kEncTok][in_width]
     float* hs = smem + kEncTok * s.in_width;       // [kEncTok][hidden]
+    float* zs = hs + kEncTok * s.hidden;           // [kEncTok][r] (int8 latents only)
     const int tid = threadIdx.x;
 
     for (int i = tid; i < nt * s.in_width; i += 256) {
@@ -57,10 +58,42 @@ __global__ __launch_bounds__(256) void encode_generic_kernel(EncodeParams p) {
         const int t = i / s.r, c = i % s.r;
         float a = bias ? Elem<E>::load(bias, c) : 0.f;
         for (int k = 0; k < in_w; ++k) a = fmaf(in[t * in_w + k], Elem<E>::load(w, (size_t)k * s.r + c), a);
+        if (s.meta) { zs[t * s.r + c] = a; continue; }
         const int tok = tok0 + t;
         const int b = tok / p.t_new, tt = tok % p.t_new;
         Elem<E>::store(s.z, ((size_t)b * p.max_seq + p.pos0 + tt) * s.r + c, a);
     }
+    if (s.meta == nullptr) return;
+
+    // ---- int8 latents ("Quantization", Eq. "quant"): 32 lanes per token row -------------------------
+    //   scale = 255 / (max - min);  zeropoint = -round(scale * min) - 128;  code = round(scale * x + zeropoint)
+    // Every operation is one fp32 operation (products are pinned so that none is fused into the
+    // following add); a row of equal values uses |x| as its range, an all-zero row 1.
+    __syncthreads();
+    const int t = tid >> 5, j = tid & 31;
+    if (t >= nt) return;
+    const float* zr = zs + t * s.r;
+    float mn = INFINITY, mx = -INFINITY;
+    for (int c = j; c < s.r; c += 32) { mn = fminf(mn, zr[c]); mx = fmaxf(mx, zr[c]); }
+#pragma unroll
+    for (int off = 16; off > 0; off >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, off));
+        mx = fmaxf(mx, __shfl_xor(mx, off));
+    }
+    float rng = mx - mn;
+    if (rng == 0.f) rng = fabsf(mx);
+    if (rng == 0.f) rng = 1.f;
+    const float scale = 255.f / rng;                       // correctly rounded fp32 division
+    const float zp = -rintf(pinned(scale * mn)) - 128.f;
+    const int tok = tok0 + t;
+    const int b = tok / p.t_new, tt = tok % p.t_new;
+    const size_t row = (size_t)b * p.max_seq + p.pos0 + tt;
+    signed char* codes = static_cast<signed char*>(s.z) + row * s.r;
+    for (int c = j; c < s.r; c += 32) {
+        const float q = rintf(pinned(scale * zr[c]) + zp);
+        codes[c] = (signed char)(int)fminf(fmaxf(q, -128.f), 127.f);
+    }
+    if (j == 0) static_cast<RowMeta*>(s.meta)[row] = RowMeta{scale, (int)fminf(fmaxf(zp, -2147483648.f), 2147483520.f)};
 }
 
 hipError_t launch_encode_generic(const EncodeParams& p, int dtype, hipStream_t stream) {
@@ -68,7 +101,7 @@ hipError_t launch_encode_generic(const EncodeParams& p, int dtype, hipStream_t s
     dim3 grid((n_tok + kEncTok - 1) / kEncTok, 2);
     size_t lds = 0;
     for (int i = 0; i < 2; ++i) {
-        size_t need = (size_t)kEncTok * (p.s[i].in_width + p.s[i].hidden) * sizeof(float);
+        size_t need = (size_t)kEncTok * (p.s[i].in_width + p.s[i].hidden + (p.s[i].meta ? p.s[i].r : 0)) * sizeof(float);
         lds = need > lds ? need : lds;
     }
     if (dtype == KVCAR_F32) hipLaunchKernelGGL(encode_generic_kernel<F32>, grid, dim3(256), lds, stream, p);
@@ -126,6 +159,16 @@ hipError_t launch_qtilde(const AttendParams& p, int dtype, bool qt_f32, hipStrea
 // plain-ALU attention over rows h_t, one workgroup per (split, sequence, group).
 // Partial written per (b, split, group): for each slot  [m, l, -, -, o[0..cv)]  with scores in log2 units.
 // ---------------------------------------------------------------------------------------------
+// Element c of cached latent row `row`: the stored value, or for int8 latents the dequantised
+// code, (code - zeropoint) / scale ("Quantization", Eq. "quant", last line).
+template <typename E>
+__device__ __forceinline__ float latent_at(const SideDesc& sd, size_t row, int c) {
+    if (sd.meta == nullptr) return Elem<E>::load(sd.z, row * sd.r + c);
+    const RowMeta m = static_cast<const RowMeta*>(sd.meta)[row];
+    const int code = static_cast<const signed char*>(sd.z)[row * sd.r + c];
+    return (float)(code - m.zeropoint) / m.scale;
+}
+
 template <typename E>
 __device__ void load_rows(const SideDesc& sd, float* rows, float* zrow, int b, int t0, int nt, int max_seq) {
     // rows [kGenericTile][c+1]; rows of tokens >= nt are zero
@@ -134,13 +177,13 @@ __device__ void load_rows(const SideDesc& sd, float* rows, float* zrow, int b, i
     if (sd.w1 == nullptr) {
         for (int i = tid; i < kGenericTile * sd.c; i += 256) {
             const int t = i / sd.c, c = i % sd.c;
-            rows[t * ld + c] = t < nt ? Elem<E>::load(sd.z, ((size_t)b * max_seq + t0 + t) * sd.r + c) : 0.f;
+            rows[t * ld + c] = t < nt ? latent_at<E>(sd, (size_t)b * max_seq + t0 + t, c) : 0.f;
         }
         return;
     }
     for (int i = tid; i < kGenericTile * sd.r; i += 256) {
         const int t = i / sd.r, c = i % sd.r;
-        zrow[i] = t < nt ? Elem<E>::load(sd.z, ((size_t)b * max_seq + t0 + t) * sd.r + c) : 0.f;
+        zrow[i] = t < nt ? latent_at<E>(sd, (size_t)b * max_seq + t0 + t, c) : 0.f;
     }
     __syncthreads();
     for (int i = tid; i < kGenericTile * sd.c; i += 256) {

@@ -42,6 +42,15 @@ struct kvcar_ctx {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_pool;   // events created so far
     size_t ev_used = 0;                                        // pairs recorded since the last read
 
+    bool int8() const { return cfg.latent_format == KVCAR_LATENT_INT8; }
+    size_t row_elem_bytes() const { return int8() ? 1 : dtype_size(cfg.dtype); }
+    // int8 latents: byte offset of the row metadata inside a cache buffer of row width r
+    size_t meta_offset(int r) const { return align_up((size_t)cfg.max_batch * cfg.max_seq * r, 256); }
+    size_t cache_need(int r) const {
+        if (r == 0) return 0;
+        if (int8()) return meta_offset(r) + (size_t)cfg.max_batch * cfg.max_seq * sizeof(RowMeta);
+        return (size_t)cfg.max_batch * cfg.max_seq * r * dtype_size(cfg.dtype);
+    }
     uint8_t& reuse_at(int layer, int which, int g) { return reuse[((size_t)layer * 2 + which) * cfg.n_kv_heads + g]; }
     uint8_t reuse_at(int layer, int which, int g) const { return reuse[((size_t)layer * 2 + which) * cfg.n_kv_heads + g]; }
     AEState& ae_at(int layer, int which) { return ae[(size_t)layer * 2 + which]; }
@@ -89,6 +98,7 @@ int fill_side(const kvcar_ctx* ctx, int layer, int src, int which, SideDesc& sd)
     if (a.d.latent_width > 0 && z == nullptr)
         return fail(ctx, KVCAR_ERR_STATE, "layer %d needs the %s cache of layer %d, which is not bound", layer, which ? "V" : "K", src);
     sd.z = z;
+    sd.meta = (ctx->int8() && z) ? static_cast<const char*>(z) + ctx->meta_offset(a.d.latent_width) : nullptr;
     sd.r = a.d.latent_width;
     sd.in_width = a.d.in_width;
     sd.act = a.d.act;
@@ -118,9 +128,9 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
 
     plan.groups.clear();
     // MFMA kernels: 16-bit dtype, linear decoders, latent widths that are multiples of 32
-    bool mfma_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && attend_mfma_available() && c.d_head % 8 == 0;
+    bool mfma_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && attend_mfma_available() && c.d_head % 8 == 0 && !ctx->int8();
     // ... or two-layer decoders of one of the shapes with a resident-weight kernel, the same for K and V
-    bool mlp_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && c.d_head % 32 == 0 && c.d_head <= 128;
+    bool mlp_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && c.d_head % 32 == 0 && c.d_head <= 128 && !ctx->int8();
     int mlp_r = -1, mlp_c = -1, mlp_act = -1;
     float mlp_slope = 0.f;
     int r_all = 0;
@@ -251,6 +261,7 @@ int kvcar_create(const kvcar_config* cfg, kvcar_ctx** out) {
         return KVCAR_ERR_SHAPE;
     if (cfg->n_kv_heads > kMaxKvHeads) return KVCAR_ERR_UNSUPPORTED;
     if (cfg->dtype != KVCAR_F32 && cfg->dtype != KVCAR_F16 && cfg->dtype != KVCAR_BF16) return KVCAR_ERR_UNSUPPORTED;
+    if (cfg->latent_format != KVCAR_LATENT_DTYPE && cfg->latent_format != KVCAR_LATENT_INT8) return KVCAR_ERR_UNSUPPORTED;
     kvcar_ctx* ctx = new (std::nothrow) kvcar_ctx();
     if (!ctx) return KVCAR_ERR_ARG;
     ctx->cfg = *cfg;
@@ -335,7 +346,7 @@ int kvcar_set_autoencoder(kvcar_ctx* ctx, int layer, int which, const kvcar_ae_d
             return fail(ctx, KVCAR_ERR_UNSUPPORTED, "unknown activation %d", d->act);
         if (d->latent_width > kMaxRow || d->hidden_width > kMaxRow)
             return fail(ctx, KVCAR_ERR_UNSUPPORTED, "widths above %d are not supported", kMaxRow);
-        if ((size_t)d->latent_width * dtype_size(c.dtype) % 16 != 0)
+        if ((size_t)d->latent_width * ctx->row_elem_bytes() % 16 != 0)
             return fail(ctx, KVCAR_ERR_UNSUPPORTED, "latent rows must be a multiple of 16 bytes");
         const void* req[4] = {d->enc_w1, d->dec_w1, d->hidden_width ? d->enc_w2 : d->enc_w1, d->hidden_width ? d->dec_w2 : d->dec_w1};
         for (const void* p : req)
@@ -346,8 +357,9 @@ int kvcar_set_autoencoder(kvcar_ctx* ctx, int layer, int which, const kvcar_ae_d
     }
     st.set = true;
     // a new width invalidates a bound cache that is now too small
-    const size_t need = (size_t)c.max_batch * c.max_seq * d->latent_width * dtype_size(c.dtype);
-    if (ctx->cache_bytes[(size_t)layer * 2 + which] < need) {
+    const size_t need = ctx->cache_need(d->latent_width);
+    const bool width_changed = ctx->ae_at(layer, which).set && ctx->ae_at(layer, which).d.latent_width != d->latent_width;
+    if (ctx->cache_bytes[(size_t)layer * 2 + which] < need || (ctx->int8() && width_changed)) {   // int8: the metadata offset moved
         ctx->cache[(size_t)layer * 2 + which] = nullptr;
         ctx->cache_bytes[(size_t)layer * 2 + which] = 0;
     }
@@ -361,7 +373,7 @@ int kvcar_cache_bytes(const kvcar_ctx* ctx, int layer, int which, size_t* bytes)
     if (!bytes || (which != KVCAR_K && which != KVCAR_V)) return fail(ctx, KVCAR_ERR_ARG, "bad argument to kvcar_cache_bytes");
     const AEState& a = ctx->ae_at(layer, which);
     if (!a.set) return fail(ctx, KVCAR_ERR_STATE, "autoencoder of layer %d not set", layer);
-    *bytes = (size_t)ctx->cfg.max_batch * ctx->cfg.max_seq * a.d.latent_width * dtype_size(ctx->cfg.dtype);
+    *bytes = ctx->cache_need(a.d.latent_width);
     return KVCAR_OK;
 }
 
@@ -420,6 +432,7 @@ int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void
         if (s.r == 0) continue;
         s.z = ctx->cache[(size_t)layer * 2 + which];
         if (!s.z) return fail(ctx, KVCAR_ERR_STATE, "cache of layer %d (%s) not bound", layer, which ? "V" : "K");
+        s.meta = ctx->int8() ? static_cast<char*>(s.z) + ctx->meta_offset(s.r) : nullptr;
         s.w1 = a.d.enc_w1; s.b1 = a.d.enc_b1; s.w2 = a.d.enc_w2; s.b2 = a.d.enc_b2;
         s.in_width = a.d.in_width; s.hidden = a.d.hidden_width; s.act = a.d.act; s.slope = a.d.leaky_slope;
         s.n_heads = (int)a.heads.size();
@@ -429,8 +442,9 @@ int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void
     if (!any) return KVCAR_OK;   // the layer stores nothing
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (!ctx->tun.force_generic && encode_mlp_mfma_supported(p, c.dtype)) e = launch_encode_mlp_mfma(p, c.dtype, st);
-    else if (!ctx->tun.force_generic && encode_mfma_supported(p, c.dtype)) e = launch_encode_mfma(p, c.dtype, st);
+    const bool mfma_enc = !ctx->tun.force_generic && !ctx->int8();
+    if (mfma_enc && encode_mlp_mfma_supported(p, c.dtype)) e = launch_encode_mlp_mfma(p, c.dtype, st);
+    else if (mfma_enc && encode_mfma_supported(p, c.dtype)) e = launch_encode_mfma(p, c.dtype, st);
     else e = launch_encode_generic(p, c.dtype, st);
     if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "encode launch failed: %s", hipGetErrorString(e));
     return KVCAR_OK;
@@ -505,7 +519,8 @@ int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, k
     out->workspace_bytes = plan.total_bytes;
     size_t lat = 0;
     for (auto& g : plan.groups) lat += (size_t)(g.k.r + g.v.r);
-    out->latent_bytes = lat * dtype_size(ctx->cfg.dtype) * batch * n_ctx;
+    out->latent_bytes = lat * ctx->row_elem_bytes() * batch * n_ctx;
+    if (ctx->int8()) out->latent_bytes += plan.groups.size() * 2 * sizeof(RowMeta) * (size_t)batch * n_ctx;
     return KVCAR_OK;
 }
 

@@ -16,9 +16,16 @@ constexpr int kGenericAcc = 48;     // accumulators per thread of the plain-ALU 
 constexpr int kMaxRow = 384;        // widest latent / hidden row any kernel handles
 constexpr float kLog2e = 1.4426950408889634f;
 
+// Scale and zero point of one int8 latent row.
+struct RowMeta {
+    float scale;
+    int zeropoint;
+};
+
 // One side (keys or values) of a group: where its rows come from and how they are decoded.
 struct SideDesc {
     const void* z;        // source layer's latent cache [max_batch, max_seq, r]
+    const void* meta;     // int8 latents: {float scale; int zeropoint} per row [max_batch, max_seq]; else null
     const void* w1;       // first decoder layer [r, c] (two-layer decoder only, else null)
     const void* b1;       // its bias or null
     const void* wl;       // last decoder layer [c, in_width]
@@ -62,6 +69,7 @@ struct AttendParams {
 struct EncodeSide {
     const void* x;        // [batch, t_new, d_kv]
     void* z;              // cache [max_batch, max_seq, r]
+    void* meta;           // int8 latents: {float scale; int zeropoint} per row; else null
     const void* w1; const void* b1;   // [in, hidden or r]
     const void* w2; const void* b2;   // [hidden, r] or null
     int in_width, hidden, r, act, n_heads;

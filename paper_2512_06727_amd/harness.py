@@ -14,14 +14,16 @@ from . import binding, synth
 class Session:
     def __init__(self, w: synth.Workload, reuse: Optional[np.ndarray] = None, with_bias: bool = False,
                  device: str = "cuda:0", n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, no_fuse: bool = False, poison: bool = False,
-                 max_batch: Optional[int] = None):
+                 max_batch: Optional[int] = None, latent_format: str = "dtype"):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: libkvcar has no CPU path")
         self.w = w
         self.dev = torch.device(device)
         self.tdt = synth.TORCH_DTYPE[w.dtype]
         self.reuse = synth.reuse_map(w) if reuse is None else reuse
-        self.ctx = binding.Context(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, max_batch or w.batch, w.max_seq, w.dtype)
+        self.latent_format = latent_format
+        self.ctx = binding.Context(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, max_batch or w.batch, w.max_seq, w.dtype,
+                                   latent_format=latent_format)
         self.ctx.set_tuning(n_splits=n_splits, force_generic=force_generic, tile_order=tile_order, no_fuse=no_fuse)
         self.ae: List[List[synth.AEWeights]] = []
         self.caches: List[List[Optional[torch.Tensor]]] = []
@@ -38,7 +40,12 @@ class Session:
                                          ae.act if ae.width else "none", enc, dec, ae.slope)
                 nbytes = self.ctx.cache_bytes(layer, which)
                 cache = None
-                if nbytes:
+                if nbytes and latent_format == "int8":
+                    cache = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+                    if poison:
+                        cache.fill_(0x7F)
+                    self.ctx.bind_cache(layer, which, cache)
+                elif nbytes:
                     n = nbytes // synth.DTYPE_BYTES[w.dtype]
                     cache = torch.empty(n, dtype=self.tdt, device=self.dev)
                     if poison:
@@ -55,7 +62,24 @@ class Session:
     def cache_view(self, layer: int, which: int) -> Optional[torch.Tensor]:
         """[max_batch, max_seq, r] view of a latent cache (the documented layout)."""
         c = self.caches[layer][which]
-        return None if c is None else c.view(self.ctx.cfg.max_batch, self.w.max_seq, self.ae[layer][which].latent)
+        if c is None:
+            return None
+        if self.latent_format == "int8":
+            raise RuntimeError("int8 latents: use quantized_view")
+        return c.view(self.ctx.cfg.max_batch, self.w.max_seq, self.ae[layer][which].latent)
+
+    def quantized_view(self, layer: int, which: int):
+        """int8 latents: (codes int8 [max_batch, max_seq, r], scale fp32 [max_batch, max_seq],
+        zeropoint int32 [max_batch, max_seq]) views of one cache buffer (the documented layout)."""
+        c = self.caches[layer][which]
+        if c is None:
+            return None
+        mb, ms, r = self.ctx.cfg.max_batch, self.w.max_seq, self.ae[layer][which].latent
+        n = mb * ms * r
+        off = (n + 255) // 256 * 256
+        codes = c[:n].view(torch.int8).view(mb, ms, r)
+        meta = c[off:off + mb * ms * 8]
+        return codes, meta.view(torch.float32).view(mb, ms, 2)[..., 0], meta.view(torch.int32).view(mb, ms, 2)[..., 1]
 
     def ensure_workspace(self, batch: int, n_ctx: int):
         need = self.ctx.workspace_bytes(batch, n_ctx)

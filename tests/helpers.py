@@ -11,9 +11,9 @@ def oracle_ae(ae: synth.AEWeights) -> O.Autoencoder:
     return O.Autoencoder(ae.heads, cv(ae.enc), cv(ae.dec), act=ae.act, slope=ae.slope)
 
 
-def build_oracle(w: synth.Workload, reuse=None, with_bias=False, layers=None):
+def build_oracle(w: synth.Workload, reuse=None, with_bias=False, layers=None, latent_format="dtype"):
     reuse = synth.reuse_map(w) if reuse is None else reuse
-    orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, w.batch, w.max_seq, w.dtype)
+    orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, w.batch, w.max_seq, w.dtype, latent_format=latent_format)
     for layer in range(w.n_layers):
         orc.set_reuse_map(layer, reuse[layer, 0], reuse[layer, 1])
     for layer in (range(w.n_layers) if layers is None else layers):
@@ -37,10 +37,10 @@ ABS_TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}       # max |gpu - oracle|
 REL_TOL = {"f32": 1e-4, "f16": 4e-3, "bf16": 2e-2}       # max |gpu - oracle| / max |oracle|
 
 
-def run_oracle(w, reuse=None, with_bias=False, gain=1.0, layers=None):
+def run_oracle(w, reuse=None, with_bias=False, gain=1.0, layers=None, latent_format="dtype"):
     """Prefill n_cached tokens, then n_steps decode steps (append at pos, attend over
     pos+1 tokens).  Returns (oracle, outputs[step][layer] as fp64 arrays)."""
-    orc = build_oracle(w, reuse, with_bias)
+    orc = build_oracle(w, reuse, with_bias, latent_format=latent_format)
     lay = list(range(w.n_layers)) if layers is None else layers
     for n in range(w.n_layers):
         oracle_prefill(orc, w, n, 0, w.n_cached)
@@ -116,3 +116,29 @@ def assert_cache_close(w, ses, orc, n_rows):
             rest = view[:, n_rows:]
             if rest.numel():
                 assert torch.isnan(rest.float()).all()
+
+
+def assert_quantized_cache_close(w, ses, orc, n_rows):
+    """int8 latents, GPU vs oracle.  Codes, scales and zero points are decisions taken in fp32 on
+    both sides from latent rows that differ only by the rounding order of the encoder's sums
+    (fp32 on the GPU, fp64 rounded to fp32 in the oracle): scales agree to a few fp32 units,
+    zero points and codes are equal except where such a difference moves a value across a
+    rounding boundary, and then by one."""
+    for layer in range(w.n_layers):
+        for which in (0, 1):
+            view = ses.quantized_view(layer, which)
+            if view is None:
+                assert orc.Z[(layer, which)].shape[-1] == 0
+                continue
+            codes, scale, zp = (v.cpu().numpy()[:, :n_rows] for v in view)
+            oc, osc, oz = orc.Q[(layer, which)][:, :n_rows], orc.Qscale[(layer, which)][:, :n_rows], orc.Qzero[(layer, which)][:, :n_rows]
+            np.testing.assert_allclose(scale, osc, rtol=2e-5)
+            dz = np.abs(zp.astype(np.int64) - oz.astype(np.int64))
+            assert dz.max() <= 1 and (dz > 0).mean() < 0.01, f"layer {layer} which {which}: zero points differ"
+            dc = np.abs(codes.astype(np.int32) - oc.astype(np.int32))
+            assert dc.max() <= 1, f"layer {layer} which {which}: codes more than one apart"
+            assert (dc > 0).mean() < 0.01, f"layer {layer} which {which}: {(dc > 0).mean():.4f} of codes differ"
+            # rows never appended keep the poison bytes
+            rest = ses.quantized_view(layer, which)[0][:, n_rows:]
+            if rest.numel():
+                assert (rest == 0x7F).all()

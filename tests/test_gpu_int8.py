@@ -1,0 +1,109 @@
+"""int8 latents (Methodology, "Quantization", Eq. "quant") on the GPU against the oracle: outputs of
+decode attention to the floating-point tolerance, codes / scales / zero points as integer decisions
+(equal, or one apart where the encoder's rounding order moves a value across a boundary), and
+bit-exact on inputs whose encoder sums are exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvcar_oracle as O
+from paper_2512_06727_amd import binding, synth
+from helpers import assert_outputs_close, assert_quantized_cache_close, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+C = synth.CONFIGS
+CASES = {
+    "c0-f32": (C[0], {}),
+    "c1-small-f16": (C[1].scaled(n_layers=4, batch=2, n_cached=150, n_steps=2), {}),
+    "c2-small-bf16": (C[2].scaled(n_layers=4, batch=3, n_cached=200, n_steps=2), {}),
+    "c4-small-bf16": (C[4].scaled(n_layers=5, batch=2, n_cached=300, n_steps=2), {}),
+    "c3-small-mlp": (C[3].scaled(n_layers=2, batch=2, n_cached=90, n_steps=1), {}),
+    "leaky-bias-f16": (C[3].scaled(n_layers=2, batch=2, n_cached=40, n_steps=1, dtype="f16", act="leaky_relu", hidden=160), {"with_bias": True}),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("gain", [1.0, 50.0])
+def test_int8_parity(name, gain):
+    w, kw = CASES[name]
+    orc, want = run_oracle(w, gain=gain, latent_format="int8", **kw)
+    ses, got = run_gpu(w, gain=gain, latent_format="int8", **kw)
+    assert_outputs_close(w, got, want, label=name)
+    assert_quantized_cache_close(w, ses, orc, w.n_cached + w.n_steps)
+
+
+@pytest.mark.parametrize("n_splits", [1, 3, 7])
+def test_int8_split_counts(n_splits):
+    w, kw = CASES["c2-small-bf16"]
+    orc, want = run_oracle(w, latent_format="int8", **kw)
+    ses, got = run_gpu(w, latent_format="int8", n_splits=n_splits, **kw)
+    assert_outputs_close(w, got, want, label=f"splits={n_splits}")
+
+
+def test_int8_cache_is_smaller_and_laid_out_as_documented():
+    w = C[2].scaled(n_layers=2, batch=2, n_cached=10, n_steps=1, reuse="none")
+    from paper_2512_06727_amd.harness import Session
+    s16, s8 = Session(w), Session(w, latent_format="int8")
+    rows = w.batch * w.max_seq
+    assert s16.ctx.cache_bytes(0, 0) == rows * w.latent * 2
+    assert s8.ctx.cache_bytes(0, 0) == (rows * w.latent + 255) // 256 * 256 + rows * 8
+    lat = np.full((w.n_layers, 2), w.latent)
+    # the accounting of the oracle, up to the padding between codes and row metadata
+    total = sum(s8.ctx.cache_bytes(n, k) for n in range(w.n_layers) for k in (0, 1))
+    assert 0 <= total - O.quantized_latent_cache_bytes(lat, w.max_seq, w.batch) < 256 * 2 * w.n_layers
+
+
+def selection_autoencoder(width, latent, stride):
+    enc = np.zeros((width, latent), np.float32)
+    dec = np.zeros((latent, width), np.float32)
+    for c in range(latent):
+        enc[stride * c, c] = 1.0
+        dec[c, stride * c] = 1.0
+    return enc, dec
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_int8_bit_exact_on_exact_inputs(dtype):
+    """The encoder copies input columns (every product is x*1 or x*0), inputs are small integers:
+    the latent rows are identical on both sides, so codes, scales and zero points must be equal
+    bit for bit, ties included (rows of range 255 * 2^k put many values on .5 boundaries)."""
+    hkv, dh, hq, B, L = 2, 64, 4, 3, 70
+    lat, stride = 64, 2
+    dev, tdt = torch.device("cuda:0"), synth.TORCH_DTYPE[dtype]
+    ctx = binding.Context(1, hq, hkv, dh, B, L, dtype, latent_format="int8")
+    orc = O.KVCAROracle(1, hq, hkv, dh, B, L, dtype, latent_format="int8")
+    enc, dec = selection_autoencoder(hkv * dh, lat, stride)
+    caches = []
+    for which in (0, 1):
+        orc.set_autoencoder(0, which, O.Autoencoder(list(range(hkv)), [(enc, None)], [(dec, None)]))
+        te, td = torch.from_numpy(enc).to(dev, tdt), torch.from_numpy(dec).to(dev, tdt)
+        ctx.set_autoencoder(0, which, hkv * dh, 0, lat, "none", [(te, None)], [(td, None)])
+        c = torch.full((ctx.cache_bytes(0, which),), 0x7F, dtype=torch.uint8, device=dev)
+        ctx.bind_cache(0, which, c)
+        caches.append(c)
+    rng = np.random.default_rng(2)
+    k = rng.integers(-60, 61, size=(B, L, hkv * dh)).astype(np.float64)
+    v = rng.integers(-100, 101, size=(B, L, hkv * dh)).astype(np.float64) / 4.0
+    # rows with range exactly 255 / 2: scale 2, quarter values land on .5 boundaries
+    v[:, ::3, 0], v[:, ::3, stride] = -60.0, 67.5
+    k[:, 5] = 7.0                       # a constant row
+    k[:, 6] = 0.0                       # a zero row
+    orc.encode_append(0, k, v, 0)
+    ctx.encode_append(0, torch.from_numpy(k).to(dev, tdt), torch.from_numpy(v).to(dev, tdt), B, 0, L)
+    torch.cuda.synchronize()
+    n = B * L * lat
+    off = (n + 255) // 256 * 256
+    for which in (0, 1):
+        raw = caches[which].cpu().numpy()
+        codes = raw[:n].view(np.int8).reshape(B, L, lat)
+        meta = raw[off:off + B * L * 8]
+        scale = meta.view(np.float32).reshape(B, L, 2)[..., 0]
+        zp = meta.view(np.int32).reshape(B, L, 2)[..., 1]
+        np.testing.assert_array_equal(codes, orc.Q[(0, which)])
+        np.testing.assert_array_equal(scale.view(np.uint32), orc.Qscale[(0, which)].view(np.uint32))
+        np.testing.assert_array_equal(zp, orc.Qzero[(0, which)])
+        assert (raw[n:off] == 0x7F).all()            # the padding between codes and metadata is not touched
+    # constant rows dequantise to themselves up to the rounding of the scale, zero rows exactly
+    np.testing.assert_allclose(orc.Z[(0, 0)][:, 5], 7.0, rtol=1e-7)
+    np.testing.assert_array_equal(orc.Z[(0, 0)][:, 6], 0.0)
