@@ -37,15 +37,16 @@ def sources(reuse, layer, which):
     return out
 
 
-def algorithmic_latent_bytes(w, reuse, widths, batch, n_ctx, elem):
+def algorithmic_latent_bytes(w, reuse, widths, batch, n_ctx, elem, row_meta=0):
     """Bytes of latent rows one decode step must read, per layer: every distinct source
-    layer's K rows and V rows once (P * B * n_ctx * sum of source widths)."""
+    layer's K rows and V rows once (P * B * n_ctx * sum of source widths; int8 latents: one byte
+    per element plus the 8 bytes of scale and zero point per row)."""
     per_layer = []
     for layer in range(w.n_layers):
         tot = 0
         for which in (0, 1):
-            tot += sum(widths[m][which] for m in set(sources(reuse, layer, which)))
-        per_layer.append(elem * batch * n_ctx * tot)
+            tot += sum(widths[m][which] * elem + row_meta for m in set(sources(reuse, layer, which)) if widths[m][which])
+        per_layer.append(batch * n_ctx * tot)
     return per_layer
 
 
@@ -114,6 +115,8 @@ def main():
     ap.add_argument("--fill", default="encode", choices=["encode", "random"],
                     help="encode: caches filled by kvcar_encode_append of seeded K/V (default); random: torch.randn latents and "
                          "inputs (profiling runs only: same traffic, far fewer helper kernels)")
+    ap.add_argument("--latent", default="dtype", choices=["dtype", "int8"],
+                    help="latent rows in the model dtype (default, the headline) or as int8 codes with a scale and zero point per row")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (counter calibration under rocprofv3 --pmc)")
@@ -144,7 +147,8 @@ def main():
     reuse = synth.reuse_map(w)
     elem = synth.DTYPE_BYTES[w.dtype]
 
-    ses = Session(w, reuse=reuse, n_splits=args.splits, tile_order=args.tile_order)
+    ses = Session(w, reuse=reuse, n_splits=args.splits, tile_order=args.tile_order, latent_format=args.latent)
+    lat_elem, row_meta = (1, 8) if args.latent == "int8" else (elem, 0)
     dev, tdt = ses.dev, ses.tdt
     widths = [[ses.ae[n][which].latent for which in (0, 1)] for n in range(w.n_layers)]
     t_fill = time.perf_counter()
@@ -152,9 +156,16 @@ def main():
         ses.prefill(0, w.n_cached, chunk=max(1, (1 << 25) // (w.batch * w.d_kv)))
     else:
         torch.manual_seed(w.seed)
-        for row in ses.caches:
-            for c in row:
-                if c is not None:
+        for n, row in enumerate(ses.caches):
+            for which, c in enumerate(row):
+                if c is None:
+                    continue
+                if args.latent == "int8":
+                    codes, scale, zp = ses.quantized_view(n, which)
+                    codes.view(torch.uint8).random_(0, 256)
+                    scale.fill_(127.5)
+                    zp.random_(-8, 9)
+                else:
                     c.normal_(0.0, 0.32)
     torch.cuda.synchronize()
     t_fill = time.perf_counter() - t_fill
@@ -222,13 +233,13 @@ def main():
     ctx.profile_enable(False)
     alg = 0
     for step in range(args.warmup, total_steps):
-        alg += sum(algorithmic_latent_bytes(w, reuse, widths, w.batch, w.n_cached + step + 1, elem))
+        alg += sum(algorithmic_latent_bytes(w, reuse, widths, w.batch, w.n_cached + step + 1, lat_elem, row_meta))
     achieved = alg / (attend_ms * 1e-3) / 1e9
     plan = ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq)
     traffic = None
     # HBM bytes per launch from the committed rocprofv3 counter summary of this same workload
     tpath = os.path.join(ROOT, "profiles", "attend_mfma_long_context_pmc.md")
-    if os.path.exists(tpath) and args.workload == 4 and not (args.batch or args.cached or args.no_reuse or args.policy):
+    if os.path.exists(tpath) and args.workload == 4 and args.latent == "dtype" and not (args.batch or args.cached or args.no_reuse or args.policy):
         import re
         m = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tpath).read())
         traffic = float(m.group(1)) if m else None
@@ -251,7 +262,7 @@ def main():
     # capacity: how many cached tokens (batch x context) fit in 288 GB, compressed vs not
     hbm = 288e9
     full_tok = 2 * elem * w.n_layers * w.d_kv
-    lat_tok = elem * sum(sum(r) for r in widths)
+    lat_tok = sum(r * lat_elem + (row_meta if r else 0) for pair in widths for r in pair)
     result = {
         "metric": "decode-attn tokens/s over latent KV cache",
         "value": tokens_per_s,
@@ -266,7 +277,7 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic" if args.fill == "encode" else "synthetic (random latents, profiling fill)",
         "config": {"workload": w.name, "batch": w.batch, "cached_tokens": w.n_cached, "layers": w.n_layers,
-                   "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_head": w.d_head, "latent": w.latent,
+                   "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_head": w.d_head, "latent": w.latent, "latent_format": args.latent,
                    "reuse": w.reuse, "policy": w.policy, "reused_head_fraction": float(reuse[1:].mean()) if w.n_layers > 1 else 0.0,
                    "splits": plan.n_splits, "mfma": bool(plan.uses_mfma), "prefill_s": t_fill},
         "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if plan.uses_mfma else "attend_generic_kernel",

@@ -1,0 +1,76 @@
+// MFMA attention over int8 latent rows ("Quantization", Eq. "quant"; gfx950, 16-bit model dtypes, linear
+// decoders, latent width 32 / 64 / 96 / 128 equal for K and V).  Same loop as the 16-bit kernel
+// (kvcar_attend_mfma_body.hpp): the code bytes become fp16 operands on their way into LDS and the
+// per-row scale and zero point are applied to the scores and folded into the probabilities.
+#include "kvcar_attend_mfma_body.hpp"
+
+namespace kvcar {
+
+constexpr size_t kI8WaveLds = Geo<128>::kWaveLds + 512;      // + 1/scale, off/scale, 256/scale of the tile's rows
+
+template <typename E>
+__global__ __launch_bounds__(256, 2) void attend_i8_mfma_r128_kernel(AttendParams p_by_value) {
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    (void)p_by_value;
+    KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    KGroup g = &p->g[blockIdx.z];
+    const int key = g->k.r * 4 + (g->slots_pad >> 4);
+    if (p->fused) {
+        switch (key) {
+            case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+            default: return;
+        }
+    }
+    switch (key) {
+        case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+        case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+        case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+        case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+        case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+        case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+        case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+        case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+        default: return;
+    }
+}
+
+// Every group: int8 rows with metadata, linear decoders, K and V latent widths equal and one of 32 / 64 / 96 / 128,
+// at most 32 query heads.
+bool attend_i8_mfma_supported(const AttendParams& p, int dtype) {
+    if (dtype == KVCAR_F32) return false;
+    for (int i = 0; i < p.n_groups; ++i) {
+        const GroupDesc& g = p.g[i];
+        if (!g.k.meta || !g.v.meta || g.k.w1 || g.v.w1) return false;
+        if (g.k.r != g.v.r || g.k.r % 32 || g.k.r < 32 || g.k.r > 128 || g.slots_pad > 32) return false;
+    }
+    return true;
+}
+
+hipError_t launch_attend_i8_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
+    static bool attr[2] = {false, false};
+    if (!attend_i8_mfma_supported(p, dtype)) return hipErrorNotSupported;
+    const size_t epi = 1024 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);
+    const size_t merge = mfma_lds_bytes(128, 2);
+    size_t lds = kWaves * kI8WaveLds + (p.fused ? 2 * 4 * 64 * 16 : 0);
+    lds = lds > merge ? lds : merge;
+    lds = lds > epi ? lds : epi;
+    const int e = dtype == KVCAR_BF16 ? 0 : 1;
+    auto kern = e == 0 ? attend_i8_mfma_r128_kernel<BF16> : attend_i8_mfma_r128_kernel<F16>;
+    if (!attr[e]) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (err != hipSuccess) return err;
+        attr[e] = true;
+    }
+    dim3 grid(p.n_splits, p.batch, p.n_groups);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace kvcar

@@ -1,0 +1,712 @@
+// MFMA attention over the latent cache for gfx950 (16-bit dtypes, linear decoders).
+//
+// One workgroup = 4 independent wavefronts serving ALL query heads of a group for one sequence and
+// one token split: the autoencoder latent mixes heads, so every head needs the whole latent row and
+// the row is read from HBM once for all of them.  Per 32-token tile a wave
+//   1. streams the K and V latent rows with fully coalesced 128-bit loads (next tile prefetched in
+//      registers), parks them in its private LDS region (padded rows, no bank conflicts),
+//   2. S^T[token, head] = Z_K . Qt^T      v_mfma_f32_16x16x32 (A = latent rows from LDS, B = absorbed
+//                                          queries resident in registers)
+//   3. online softmax in base 2: the MFMA result layout gives a lane 8 tokens of ONE head, so the
+//      max / sum reductions are in-lane plus two cross-lane steps
+//   4. O^T[latent col, head] += Z_V^T . P^T  with P^T taken straight from the softmax registers
+//      (the S^T result layout IS the B-operand layout) and Z_V^T read from LDS with the gfx950
+//      transposing load ds_read_b64_tr_b16.
+// No barrier is needed in the loop; the four waves merge their (m, l, O) once at the end and write
+// one partial per (sequence, split, group).  Attention itself is Eq. 1 of the paper; the decoder is
+// applied to the query before (prologue kernel) and to the weighted latent sum after (combine
+// kernel), which equals decoding every cached row first ("Network Architecture", 2nd paragraph).
+//
+// The loop body is compiled once per exact shape (latent width R for both K and V, 16-head blocks)
+// so that every LDS address is lane base + immediate and no width test survives in the loop; a
+// workgroup picks its instance from its group's widths.  Other width mixes take an instance with
+// run-time widths.
+#pragma once
+
+#include <type_traits>
+
+#include "kvcar_device.hpp"
+
+namespace kvcar {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
+
+template <typename E> struct Mma;
+template <> struct Mma<BF16> {
+    static __device__ __forceinline__ f32x4_t mfma(u32x4_t a, u32x4_t b, f32x4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ unsigned pack2(float lo, float hi) {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+        bf16x2_t v = {(__bf16)lo, (__bf16)hi};          // round to nearest even
+        return __builtin_bit_cast(unsigned, v);
+    }
+    static __device__ __forceinline__ float unpack_lo(unsigned w) { return __uint_as_float(w << 16); }
+    static __device__ __forceinline__ float unpack_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
+    static __device__ __forceinline__ uint16_t to16(float v) { return f32_to_bf16_bits(v); }
+};
+template <> struct Mma<F16> {
+    static __device__ __forceinline__ f32x4_t mfma(u32x4_t a, u32x4_t b, f32x4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ unsigned pack2(float lo, float hi) {
+        typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+        f16x2_t v = {(_Float16)lo, (_Float16)hi};
+        return __builtin_bit_cast(unsigned, v);
+    }
+    static __device__ __forceinline__ float unpack_lo(unsigned w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu)); }
+    static __device__ __forceinline__ float unpack_hi(unsigned w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
+    static __device__ __forceinline__ uint16_t to16(float v) { _Float16 h = (_Float16)v; return __builtin_bit_cast(uint16_t, h); }
+};
+
+constexpr int kWaveTile = 32;     // tokens per wave per iteration
+constexpr int kWaves = 4;
+
+#ifndef KVCAR_NT_LOADS
+#define KVCAR_NT_LOADS 1
+#endif
+
+__device__ __forceinline__ u32x4_t ld_global_16(const char* p) {
+#if KVCAR_NT_LOADS
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+#else
+    return *reinterpret_cast<const u32x4_t*>(p);
+#endif
+}
+
+// Shapes of one loop instance.  Exact: everything is a compile-time constant.
+template <int R, int NHB_> struct DimsExact {
+    static constexpr int RMAX = R, NHB = NHB_;
+    static constexpr bool kExact = true;
+    static constexpr int rk = R, rv = R, nhb = NHB_;
+    __device__ DimsExact(int, int, int) {}
+};
+template <int RMAX_, int NHB_> struct DimsAny {
+    static constexpr int RMAX = RMAX_, NHB = NHB_;
+    static constexpr bool kExact = false;
+    int rk, rv, nhb;
+    __device__ DimsAny(int rk_, int rv_, int nhb_) : rk(rk_), rv(rv_), nhb(nhb_) {}
+};
+
+template <int RMAX> struct Geo {
+    static constexpr bool kPrefetch = RMAX <= 128;            // next tile's K and V rows held in registers
+    static constexpr int kRegionK = kWaveTile * (2 * RMAX + 16);
+    static constexpr int kRegionV = kWaveTile * (2 * RMAX + 32);
+    static constexpr int kWaveLds = kPrefetch ? kRegionK + kRegionV : kRegionV;   // wide rows: K, V take turns
+};
+
+// This lane's share of a [kWaveTile x r] tile whose rows are contiguous in memory: 16-byte chunk
+// f = i*64 + lane.  Full tiles need no test; on the ragged last tile chunks of rows >= n_valid read 0.
+template <int NL>
+__device__ __forceinline__ void load_tile(u32x4_t (&st)[NL], const char* tile, int n_loads, int valid_chunks, bool full, int lane) {
+    if (full) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            if (i < n_loads) st[i] = ld_global_16(tile + lane * 16 + i * 1024);
+    } else {
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            if (i < n_loads) {
+                const int f = i * 64 + lane;
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (f < valid_chunks) v = ld_global_16(tile + f * 16);
+                st[i] = v;
+            }
+    }
+}
+
+// Park the tile in LDS: chunk f -> row f / cpr, chunk-in-row f % cpr, padded row stride.
+template <int NL>
+__device__ __forceinline__ void park_tile(const u32x4_t (&st)[NL], char* region, int n_loads, int cpr, int stride, int lane) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+        if (i < n_loads) {
+            const unsigned f = i * 64 + lane;
+            const unsigned row = f / (unsigned)cpr;
+            const unsigned ch = f - row * cpr;
+            *reinterpret_cast<u32x4_t*>(region + row * stride + ch * 16) = st[i];
+        }
+}
+
+// The kernel reads its argument block through the kernel-argument segment pointer (constant address
+// space): run-time indexed reads of the by-value argument would otherwise make the compiler copy the
+// whole block into per-lane scratch memory.  The block is the kernel's only explicit argument, so it
+// sits at offset 0 of the segment.
+typedef const __attribute__((address_space(4))) AttendParams* KArgs;
+typedef const __attribute__((address_space(4))) GroupDesc* KGroup;
+typedef const __attribute__((address_space(4))) short* KShorts;
+
+// Entry `base + idx` of a small table that lives in the kernel arguments, for a lane-dependent idx in
+// [0, 16): done with 16 uniform reads and selects, because indexing the argument block with a
+// lane-dependent index would make the compiler copy the whole block to scratch memory.
+__device__ __forceinline__ int lane_lookup16(KShorts table, int base, int limit, int idx, int otherwise) {
+    int r = otherwise;
+#pragma unroll
+    for (int s = 0; s < 16; ++s)
+        if (base + s < limit && idx == s) r = table[base + s];
+    return r;
+}
+
+// int8 latents ("Quantization", Eq. "quant"): a row is r codes plus {scale, zeropoint}.  A code byte
+// c is turned into the fp16 number 1024 + (c + 128) by one byte permute (0x64 in the high byte makes
+// the mantissa count in units of one), so the products below run on v_mfma_f32_16x16x32_f16 whatever
+// the model dtype is; the constant 1152 and the zero point are taken out afterwards:
+//   x^_tc = (u_tc - off_t) / scale_t,   u_tc = 1152 + code_tc,  off_t = 1152 + zeropoint_t
+//   score = (1/scale_t) (sum_c qt_c u_tc - off_t sum_c qt_c)
+//   sum_t p_t x^_tc = sum_t P_t u_tc - sum_t P_t off_t,   P_t = p_t / scale_t
+// where sum_t P_t off_t comes out of the same MFMA from three extra columns of the V tile (off_t
+// split as 4096 h2 + 64 h1 + h0, each exact in fp16), which sit in the padding of the LDS rows.
+constexpr float kI8Offset = 1152.f;       // 1024 (fp16 exponent trick) + 128 (codes are signed)
+constexpr float kI8PScale = 256.f;        // keeps P_t = p_t / scale_t in fp16's normal range
+
+// 16 code bytes -> 16 fp16 numbers 1024 + (code + 128), as two 16-byte halves
+__device__ __forceinline__ void i8_chunk_to_f16(const u32x4_t c, u32x4_t& lo, u32x4_t& hi) {
+    unsigned h[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const unsigned x = c[i] ^ 0x80808080u;
+        // selector bytes 0..3 pick bytes of the second operand, 4..7 of the first
+        h[2 * i] = __builtin_amdgcn_perm(0x64646464u, x, 0x04010400u);
+        h[2 * i + 1] = __builtin_amdgcn_perm(0x64646464u, x, 0x04030402u);
+    }
+    lo = u32x4_t{h[0], h[1], h[2], h[3]};
+    hi = u32x4_t{h[4], h[5], h[6], h[7]};
+}
+
+// Park an int8 tile: 16-byte chunk f holds 16 codes of row f / cpr8 -> 32 bytes of fp16 in the padded row
+template <int NL>
+__device__ __forceinline__ void park_tile_i8(const u32x4_t (&st)[NL], char* region, int n_loads, int cpr8, int stride, int lane) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+        if (i < n_loads) {
+            const unsigned f = i * 64 + lane;
+            const unsigned row = f / (unsigned)cpr8;
+            const unsigned ch = f - row * cpr8;
+            u32x4_t lo, hi;
+            i8_chunk_to_f16(st[i], lo, hi);
+            *reinterpret_cast<u32x4_t*>(region + row * stride + ch * 32) = lo;
+            *reinterpret_cast<u32x4_t*>(region + row * stride + ch * 32 + 16) = hi;
+        }
+}
+
+// kFused (single split, exact shapes only): the absorbed queries are computed in the prologue and the
+// last decoder layer of V is applied in the epilogue, so the whole decode attention of a layer is this
+// one kernel and neither the absorbed queries nor the partials travel through memory.
+template <typename E, typename D, bool kFused, bool kI8 = false>
+__device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, size_t wave_lds) {
+    constexpr int RMAX = D::RMAX, NHB = D::NHB;
+    using G = Geo<RMAX>;
+    using ML = typename std::conditional<kI8, F16, E>::type;    // element type of the products in the loop
+    static_assert(!kI8 || (D::kExact && G::kPrefetch), "int8 latents: exact shapes up to 128 only");
+    constexpr int KS = RMAX / 32;      // k-steps of the score product
+    constexpr int MB = RMAX / 16;      // 16-column blocks of the latent accumulator
+    constexpr int NL = kI8 ? RMAX / 32 : RMAX / 16;      // 128-bit loads per lane per tile
+    constexpr int EB = kI8 ? 1 : 2;    // bytes per cached latent element
+
+    const D d(g->k.r, g->v.r, g->slots_pad >> 4);
+    const int split = blockIdx.x, b = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, lg = lane >> 4;
+
+    const int rk = d.rk, rv = d.rv, nhb = d.nhb;
+    const int ksteps = rk >> 5, mblocks = rv >> 4;
+    const int nlk = kI8 ? rk >> 5 : rk >> 4, nlv = kI8 ? rv >> 5 : rv >> 4;     // loads per lane per tile
+    const int cprk = kI8 ? rk >> 4 : rk >> 3, cprv = kI8 ? rv >> 4 : rv >> 3;   // 16-byte chunks per cached row
+    const int stride_k = 2 * rk + 16, stride_v = 2 * rv + 32;
+
+    char* my_lds = lds_raw + wave * wave_lds;
+    char* lds_k = my_lds;
+    char* lds_v = G::kPrefetch ? my_lds + kWaveTile * stride_k : my_lds;
+
+    // Workgroup tiles (4 wave tiles = 128 tokens each) of this split.  tile_order 0: a contiguous
+    // token range per split; 1: tiles dealt round-robin over the splits, so that workgroups running
+    // at the same time read neighbouring addresses.
+    const int wg_tiles = (p->n_ctx + kWaveTile * kWaves - 1) / (kWaveTile * kWaves);
+    int j0, j1, jstep;
+    if (p->tile_order == 0) {
+        const int per_split = (wg_tiles + p->n_splits - 1) / p->n_splits;
+        j0 = split * per_split;
+        j1 = min(wg_tiles, j0 + per_split);
+        jstep = 1;
+    } else {
+        j0 = split; j1 = wg_tiles; jstep = p->n_splits;
+    }
+
+    const char* zk = static_cast<const char*>(g->k.z) + (size_t)b * p->max_seq * rk * EB;
+    const char* zv = static_cast<const char*>(g->v.z) + (size_t)b * p->max_seq * rv * EB;
+    // int8: {scale, zeropoint} of this sequence's rows; lanes 0..31 take the K rows of a tile, 32..63 the V rows
+    const RowMeta* mrow = nullptr;
+    float* mlds = nullptr;               // per wave: ak[32] (1/scale_K), bk[32] (off_K/scale_K), av[32] (256/scale_V)
+    if constexpr (kI8) {
+        mrow = static_cast<const RowMeta*>(lane < 32 ? g->k.meta : g->v.meta) + (size_t)b * p->max_seq;
+        mlds = reinterpret_cast<float*>(my_lds + kWaveTile * stride_k + kWaveTile * stride_v);
+    }
+    u32x2_t stm = {0u, 0u};
+
+    // kPrefetch: both tiles of the next iteration are in flight while this one computes.
+    // Otherwise (wide rows) a tile is loaded right before it is parked and K, V take turns.
+    u32x4_t stk[NL], stv[G::kPrefetch ? NL : 1];
+    auto issue = [&](int j) {
+        const int t0 = (j * kWaves + wave) * kWaveTile;
+        const int nv = max(0, min(kWaveTile, p->n_ctx - t0));
+        load_tile<NL>(stk, zk + (size_t)t0 * rk * EB, nlk, nv * cprk, nv == kWaveTile, lane);
+        if constexpr (G::kPrefetch) load_tile<NL>(stv, zv + (size_t)t0 * rv * EB, nlv, nv * cprv, nv == kWaveTile, lane);
+        if constexpr (kI8) {
+            const int tok = t0 + (lane & 31);
+            stm = u32x2_t{0x3f800000u, 0u};                       // rows past the context: scale 1, zero point 0
+            if (tok < p->n_ctx) stm = *reinterpret_cast<const u32x2_t*>(mrow + tok);
+        }
+    };
+    if (G::kPrefetch && j0 < j1) issue(j0);        // first tile in flight while the queries are prepared
+
+    // absorbed queries of this sequence and group, resident as MFMA B operands
+    u32x4_t qb[NHB][KS];
+    if constexpr (kFused) {
+        // Qt^T[c, head] = scale*log2e * sum_k Wl_K[c, col(head)+k] q[head, k], by MFMA straight from global
+        // memory: A = rows of the decoder matrix, B = the queries of one KV head's heads (other heads of
+        // the 16-block masked to zero; a block spans at most two KV heads: two passes).  Row rho of result
+        // tile (s, hh) is latent index 32s + 8(rho/4) + 4hh + rho%4, so that the result registers of tiles
+        // (s,0) and (s,1) are exactly the B operand of score k-step s.  Wave w computes k-step s = w for
+        // all heads (its loads are independent and fly together) and the waves swap through LDS.
+        const int dh = p->d_head;
+        const char* wl = static_cast<const char*>(g->k.wl);
+        u32x4_t* qlds = reinterpret_cast<u32x4_t*>(lds_raw + kWaves * wave_lds);      // [NHB][KS][64], past the staging regions
+        if (wave < KS) {
+            const int s2 = wave;
+#pragma unroll
+            for (int nb = 0; nb < NHB; ++nb) {
+                const int my_col = lane_lookup16(g->k_col, nb * 16, g->n_slots, l16, -1);
+                const int my_head = lane_lookup16(g->q_head, nb * 16, g->n_slots, l16, 0);
+                const char* qrow = static_cast<const char*>(p->q) + ((size_t)b * p->n_q_heads + my_head) * dh * 2;
+                // the (at most two) KV heads of this 16-head block
+                const int blk_end = min(g->n_slots, nb * 16 + 16);
+                const int col_a = nb * 16 < g->n_slots ? g->k_col[nb * 16] : -1;
+                int col_b = -1;
+                for (int sl = nb * 16 + 1; sl < blk_end; ++sl)
+                    if (g->k_col[sl] != col_a) { col_b = g->k_col[sl]; break; }
+                f32x4_t t[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
+                for (int k0 = 0; k0 < dh; k0 += 32) {
+                    u32x4_t bq[2], aw[2][2];
+                    const u32x4_t qv = my_col >= 0 ? *reinterpret_cast<const u32x4_t*>(qrow + (k0 + 8 * lg) * 2) : u32x4_t{0u, 0u, 0u, 0u};
+                    bq[0] = my_col == col_a ? qv : u32x4_t{0u, 0u, 0u, 0u};
+                    bq[1] = my_col == col_b ? qv : u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+                    for (int sg = 0; sg < 2; ++sg)
+#pragma unroll
+                        for (int hh = 0; hh < 2; ++hh) {
+                            const int c = 32 * s2 + 8 * (l16 >> 2) + 4 * hh + (l16 & 3);
+                            const int col = sg == 0 ? col_a : col_b;
+                            aw[sg][hh] = u32x4_t{0u, 0u, 0u, 0u};
+                            if (col >= 0) aw[sg][hh] = *reinterpret_cast<const u32x4_t*>(wl + ((size_t)c * g->k.in_width + col + k0 + 8 * lg) * 2);
+                        }
+#pragma unroll
+                    for (int sg = 0; sg < 2; ++sg)
+#pragma unroll
+                        for (int hh = 0; hh < 2; ++hh) t[hh] = Mma<E>::mfma(aw[sg][hh], bq[sg], t[hh]);
+                }
+                const float sc = p->scale_log2e;
+                qlds[(nb * KS + s2) * 64 + lane] =
+                    u32x4_t{Mma<ML>::pack2(t[0][0] * sc, t[0][1] * sc), Mma<ML>::pack2(t[0][2] * sc, t[0][3] * sc),
+                            Mma<ML>::pack2(t[1][0] * sc, t[1][1] * sc), Mma<ML>::pack2(t[1][2] * sc, t[1][3] * sc)};
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+            for (int s2 = 0; s2 < KS; ++s2) qb[nb][s2] = qlds[(nb * KS + s2) * 64 + lane];
+    } else if constexpr (kI8) {
+        // the prologue kernel leaves the absorbed queries in fp32; they enter the products as fp16
+        const float* qt = static_cast<const float*>(p->qt) + (size_t)b * p->qt_stride + g->qt_off;
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const float* src = qt + (size_t)(nb * 16 + l16) * rk + 8 * (4 * s + lg);
+                const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(src), x1 = *reinterpret_cast<const f32x4_t*>(src + 4);
+                qb[nb][s] = u32x4_t{Mma<F16>::pack2(x0[0], x0[1]), Mma<F16>::pack2(x0[2], x0[3]), Mma<F16>::pack2(x1[0], x1[1]), Mma<F16>::pack2(x1[2], x1[3])};
+            }
+    } else {
+        const char* qt = static_cast<const char*>(p->qt) + ((size_t)b * p->qt_stride + g->qt_off) * 2;
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (nb < nhb && s < ksteps) v = *reinterpret_cast<const u32x4_t*>(qt + ((size_t)(nb * 16 + l16) * rk + 8 * (4 * s + lg)) * 2);
+                qb[nb][s] = v;
+            }
+    }
+    // int8: Qsum[nb] = sum over the latent index of this lane's head's absorbed query, as rounded to fp16
+    float qsum[NHB];
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb) qsum[nb] = 0.f;
+    if constexpr (kI8) {
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb) {
+            float a = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a += Mma<F16>::unpack_lo(qb[nb][s][e]) + Mma<F16>::unpack_hi(qb[nb][s][e]);
+            a += __shfl_xor(a, 16);
+            a += __shfl_xor(a, 32);
+            qsum[nb] = a;
+        }
+    }
+
+    f32x4_t acc[NHB][MB];
+    f32x4_t accx[NHB];                 // int8: rows 0..2 accumulate sum_t P_t (h2, h1, h0)_t
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb) {
+        accx[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+    float m_run[NHB], l_run[NHB];
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; }
+
+
+    for (int j = j0; j < j1; j += jstep) {
+        const int t0 = (j * kWaves + wave) * kWaveTile;
+        const int nv = min(kWaveTile, p->n_ctx - t0);
+        if (nv <= 0) break;          // wave tile past the context: only in the last workgroup tile, the last one visited
+
+        if constexpr (!G::kPrefetch) issue(j);
+        if constexpr (kI8) {
+            park_tile_i8<NL>(stk, lds_k, nlk, cprk, stride_k, lane);
+            park_tile_i8<NL>(stv, lds_v, nlv, cprv, stride_v, lane);
+            const float inv = __builtin_amdgcn_rcpf(__uint_as_float(stm[0]));
+            const float off = kI8Offset + (float)(int)stm[1];
+            if (lane < 32) {
+                mlds[lane] = inv;
+                mlds[32 + lane] = inv * off;
+            } else {
+                mlds[32 + lane] = fminf(inv * kI8PScale, 60000.f);
+                // off = 4096 h2 + 64 h1 + h0 with |h1|, |h0| <= 32 and h2 exact in fp16 up to 2048
+                const float h2 = fminf(fmaxf(rintf(off * (1.f / 4096.f)), -2048.f), 2048.f);
+                const float r1 = off - 4096.f * h2;
+                const float h1 = rintf(r1 * (1.f / 64.f));
+                const float h0 = r1 - 64.f * h1;
+                *reinterpret_cast<u32x2_t*>(lds_v + (lane - 32) * stride_v + 2 * rv) = u32x2_t{Mma<F16>::pack2(h2, h1), Mma<F16>::pack2(h0, 0.f)};
+            }
+            if (j + jstep < j1) issue(j + jstep);
+        } else {
+        park_tile<NL>(stk, lds_k, nlk, cprk, stride_k, lane);
+        if constexpr (G::kPrefetch) {
+            park_tile<NL>(stv, lds_v, nlv, cprv, stride_v, lane);
+            if (j + jstep < j1) issue(j + jstep);
+        }
+        }
+
+        // ---- scores: S^T[token, head] ------------------------------------------------------
+        f32x4_t sT[2][NHB];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int nb = 0; nb < NHB; ++nb) sT[a][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        const char* krow = lds_k + l16 * stride_k + lg * 16;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            if (s < ksteps) {
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    const u32x4_t ka = *reinterpret_cast<const u32x4_t*>(krow + a * 16 * stride_k + s * 64);
+#pragma unroll
+                    for (int nb = 0; nb < NHB; ++nb)
+                        if (nb < nhb) sT[a][nb] = Mma<ML>::mfma(ka, qb[nb][s], sT[a][nb]);
+                }
+            }
+        }
+        if constexpr (!G::kPrefetch) {
+            // K and V share the staging registers and the LDS region: V rows replace K rows
+            // (LDS operations of one wave complete in order, so the score reads are done)
+            load_tile<NL>(stk, zv + (size_t)t0 * rv * 2, nlv, nv * cprv, nv == kWaveTile, lane);
+            park_tile<NL>(stk, lds_v, nlv, cprv, stride_v, lane);
+        }
+        f32x4_t av4[2];                   // int8: 256 / scale_V of this lane's eight tokens
+        if constexpr (kI8) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                const f32x4_t ak4 = *reinterpret_cast<const f32x4_t*>(mlds + 16 * a + 4 * lg);
+                const f32x4_t bk4 = *reinterpret_cast<const f32x4_t*>(mlds + 32 + 16 * a + 4 * lg);
+                av4[a] = *reinterpret_cast<const f32x4_t*>(mlds + 64 + 16 * a + 4 * lg);
+#pragma unroll
+                for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) sT[a][nb][v] = fmaf(ak4[v], sT[a][nb][v], -bk4[v] * qsum[nb]);
+            }
+        }
+        if (nv < kWaveTile) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (16 * a + 4 * lg + v >= nv) sT[a][nb][v] = -INFINITY;
+        }
+
+        // ---- online softmax (base 2) and P^T as B operand -------------------------------------
+        u32x4_t pb[NHB];
+        float alpha[NHB];
+        bool rescale = false;
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb) {
+            float mx = fmaxf(fmaxf(fmaxf(sT[0][nb][0], sT[0][nb][1]), fmaxf(sT[0][nb][2], sT[0][nb][3])),
+                             fmaxf(fmaxf(sT[1][nb][0], sT[1][nb][1]), fmaxf(sT[1][nb][2], sT[1][nb][3])));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[nb], mx);
+            alpha[nb] = __builtin_amdgcn_exp2f(m_run[nb] - m_new);     // m_run = -inf on the first tile gives 0
+            rescale |= m_new != m_run[nb];
+            m_run[nb] = m_new;
+            float e[8];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                e[v] = __builtin_amdgcn_exp2f(sT[0][nb][v] - m_new);
+                e[4 + v] = __builtin_amdgcn_exp2f(sT[1][nb][v] - m_new);
+            }
+            l_run[nb] = l_run[nb] * alpha[nb] + ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+            if constexpr (kI8) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) { e[v] *= av4[0][v]; e[4 + v] *= av4[1][v]; }
+            }
+            pb[nb] = u32x4_t{Mma<ML>::pack2(e[0], e[1]), Mma<ML>::pack2(e[2], e[3]), Mma<ML>::pack2(e[4], e[5]), Mma<ML>::pack2(e[6], e[7])};
+        }
+        // the running maxima settle after a few tiles; rescale the accumulators only when one moved
+        if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
+#pragma unroll
+            for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    if (nb < nhb && mb < mblocks) acc[nb][mb] *= alpha[nb];
+            if constexpr (kI8) {
+#pragma unroll
+                for (int nb = 0; nb < NHB; ++nb) accx[nb] *= alpha[nb];
+            }
+        }
+
+        // ---- O^T[latent col, head] += Z_V^T . P^T --------------------------------------------
+        // 16 lanes of a block supply the addresses of a 4-token x 16-column patch; the transposing
+        // load hands lane i its column i for the 4 tokens
+        const char* vrow = lds_v + (4 * lg + (l16 >> 2)) * stride_v + (l16 & 3) * 8;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            if (mb < mblocks) {
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(vrow + mb * 32));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(vrow + mb * 32 + 16 * stride_v));
+                const u32x2_t lo2 = __builtin_bit_cast(u32x2_t, lo), hi2 = __builtin_bit_cast(u32x2_t, hi);
+                const u32x4_t va = {lo2[0], lo2[1], hi2[0], hi2[1]};
+#pragma unroll
+                for (int nb = 0; nb < NHB; ++nb)
+                    if (nb < nhb) acc[nb][mb] = Mma<ML>::mfma(va, pb[nb], acc[nb][mb]);
+            }
+        }
+        if constexpr (kI8) {             // the three off_t columns in the padding of the V rows
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(vrow + MB * 32));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(vrow + MB * 32 + 16 * stride_v));
+            const u32x2_t lo2 = __builtin_bit_cast(u32x2_t, lo), hi2 = __builtin_bit_cast(u32x2_t, hi);
+            const u32x4_t va = {lo2[0], lo2[1], hi2[0], hi2[1]};
+#pragma unroll
+            for (int nb = 0; nb < NHB; ++nb) accx[nb] = Mma<ML>::mfma(va, pb[nb], accx[nb]);
+        }
+    }
+    if constexpr (kI8) {
+        // sum_t P_t x^_t = (sum_t P_t u_t - sum_t P_t off_t) / 256; the second sum sits in rows 0..2 of accx,
+        // i.e. in the lanes of quarter 0, column = head
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb) {
+            const float corr = __shfl(4096.f * accx[nb][0] + 64.f * accx[nb][1] + accx[nb][2], l16);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = (acc[nb][mb] - corr) * (1.f / kI8PScale);
+        }
+    }
+
+    // ---- merge the four waves and write one partial --------------------------------------------
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb) {
+        l_run[nb] += __shfl_xor(l_run[nb], 16);
+        l_run[nb] += __shfl_xor(l_run[nb], 32);
+    }
+    __syncthreads();                                   // every wave is done with its staging region
+    float* red = reinterpret_cast<float*>(lds_raw);    // [wave][NHB*16] m, then l
+    float* accs = reinterpret_cast<float*>(lds_raw) + 2 * kWaves * NHB * 16;   // [wave][NHB][MB][64][4]
+    if (lane < 16) {
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb) {
+            red[wave * NHB * 16 + nb * 16 + lane] = m_run[nb];
+            red[kWaves * NHB * 16 + wave * NHB * 16 + nb * 16 + lane] = l_run[nb];
+        }
+    }
+    __syncthreads();
+    float m_all[NHB], l_all[NHB], f_own[NHB];
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, red[w * NHB * 16 + nb * 16 + l16]);
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float mw = red[w * NHB * 16 + nb * 16 + l16];
+            L += mw == -INFINITY ? 0.f : red[kWaves * NHB * 16 + w * NHB * 16 + nb * 16 + l16] * exp2f(mw - M);
+        }
+        f_own[nb] = m_run[nb] == -INFINITY ? 0.f : exp2f(m_run[nb] - M);
+        m_all[nb] = M;
+        l_all[nb] = L;
+    }
+    if constexpr (kFused) {
+        // ---- epilogue: out[head, :] = (O[head, :] / L) . Wl_V[:, col(head) ..] + bias -------------------
+        // The slices [rv, d_head] of the decoder matrix (one per KV head of the group, at most four) are
+        // fetched into registers now, so that their latency hides under the merge.  The four waves then
+        // add their scaled accumulators one after the other (fixed order: deterministic) into the
+        // normalised latent sums olat[slot][rv + 4] in LDS.  Per KV head: slice -> LDS, transposing loads
+        // as B operand, latent sums as hi + lo 16-bit A operands; wave w owns output column blocks w, w+4..
+        constexpr int kMaxSeg = 4, kCpt = 4;               // slices, 16-byte chunks per thread and slice
+        const int dh = p->d_head;
+        const int ostride = rv + 4;
+        float* olat = red + 2 * kWaves * NHB * 16;
+        char* wst = reinterpret_cast<char*>(olat + (size_t)NHB * 16 * ostride);
+        const int stride_w = 2 * dh + 32;
+        const int cpr = dh >> 3;
+        const char* wlv = static_cast<const char*>(g->v.wl);
+        int seg_lo[kMaxSeg], seg_hi[kMaxSeg], seg_col[kMaxSeg], nseg = 0;
+        {
+            int s0 = 0;
+#pragma unroll
+            for (int sg = 0; sg < kMaxSeg; ++sg) {
+                seg_lo[sg] = seg_hi[sg] = 0; seg_col[sg] = 0;
+                if (s0 < g->n_slots) {
+                    const int col = g->v_col[s0];
+                    int s1 = s0 + 1;
+                    while (s1 < g->n_slots && g->v_col[s1] == col) ++s1;
+                    seg_lo[sg] = s0; seg_hi[sg] = s1; seg_col[sg] = col; nseg = sg + 1;
+                    s0 = s1;
+                }
+            }
+        }
+        u32x4_t wreg[kMaxSeg][kCpt];
+#pragma unroll
+        for (int sg = 0; sg < kMaxSeg; ++sg)
+#pragma unroll
+            for (int i = 0; i < kCpt; ++i) {
+                const int f = i * 256 + threadIdx.x;
+                if (sg < nseg && f < rv * cpr) {
+                    const int row = f / cpr, ch = f - row * cpr;
+                    wreg[sg][i] = *reinterpret_cast<const u32x4_t*>(wlv + ((size_t)row * g->v.in_width + seg_col[sg]) * 2 + ch * 16);
+                }
+            }
+        // sequential, ordered accumulation of the four waves' scaled latent sums
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            if (wave == w) {
+#pragma unroll
+                for (int nb = 0; nb < NHB; ++nb) {
+                    const float sc = f_own[nb] / l_all[nb];
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        float* dst = olat + (size_t)(nb * 16 + l16) * ostride + 16 * mb + 4 * lg;
+                        f32x4_t v = acc[nb][mb] * sc;
+                        if (w > 0) v += *reinterpret_cast<const f32x4_t*>(dst);
+                        *reinterpret_cast<f32x4_t*>(dst) = v;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        uint16_t* out = static_cast<uint16_t*>(p->out);
+#pragma unroll
+        for (int sg = 0; sg < kMaxSeg; ++sg) {
+            if (sg >= nseg) break;
+#pragma unroll
+            for (int i = 0; i < kCpt; ++i) {
+                const int f = i * 256 + threadIdx.x;
+                if (f < rv * cpr) {
+                    const int row = f / cpr, ch = f - row * cpr;
+                    *reinterpret_cast<u32x4_t*>(wst + row * stride_w + ch * 16) = wreg[sg][i];
+                }
+            }
+            __syncthreads();
+            const int col = seg_col[sg];
+            for (int nb = seg_lo[sg] >> 4; nb <= (seg_hi[sg] - 1) >> 4; ++nb) {
+                int heads4[4];                          // query heads of this lane's four result rows
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    heads4[v] = 0;
+#pragma unroll
+                    for (int lgx = 0; lgx < 4; ++lgx)
+                        if (lg == lgx && nb * 16 + 4 * lgx + v < g->n_slots) heads4[v] = g->q_head[nb * 16 + 4 * lgx + v];
+                }
+                for (int nbo = wave; nbo < (dh >> 4); nbo += kWaves) {
+                    f32x4_t o = {0.f, 0.f, 0.f, 0.f};
+                    for (int k0 = 0; k0 < rv; k0 += 32) {
+                        const float* arow = olat + (size_t)(nb * 16 + l16) * ostride + k0 + 8 * lg;
+                        const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(arow);
+                        const f32x4_t x1 = *reinterpret_cast<const f32x4_t*>(arow + 4);
+                        const float xv[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+                        unsigned hi[4], lo[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            hi[e] = Mma<E>::pack2(xv[2 * e], xv[2 * e + 1]);
+                            lo[e] = Mma<E>::pack2(xv[2 * e] - Mma<E>::unpack_lo(hi[e]), xv[2 * e + 1] - Mma<E>::unpack_hi(hi[e]));
+                        }
+                        const char* wrow = wst + (k0 + 8 * lg + (l16 >> 2)) * stride_w + (l16 & 3) * 8 + nbo * 32;
+                        const s16x4_t t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(wrow));
+                        const s16x4_t t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(wrow + 4 * stride_w));
+                        const u32x2_t a0 = __builtin_bit_cast(u32x2_t, t0), a1 = __builtin_bit_cast(u32x2_t, t1);
+                        const u32x4_t bw = {a0[0], a0[1], a1[0], a1[1]};
+                        o = Mma<E>::mfma(u32x4_t{hi[0], hi[1], hi[2], hi[3]}, bw, o);
+                        o = Mma<E>::mfma(u32x4_t{lo[0], lo[1], lo[2], lo[3]}, bw, o);
+                    }
+                    const int kcol = nbo * 16 + l16;
+                    const float bias = g->v.bl ? Elem<E>::load(g->v.bl, col + kcol) : 0.f;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int slot = nb * 16 + 4 * lg + v;
+                        if (slot >= seg_lo[sg] && slot < seg_hi[sg])
+                            out[((size_t)b * p->n_q_heads + heads4[v]) * dh + kcol] = Mma<E>::to16(o[v] + bias);
+                    }
+                }
+            }
+            __syncthreads();                             // the slice buffer is rewritten for the next KV head
+        }
+    } else {
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            if (mb < mblocks && nb < nhb)
+                *reinterpret_cast<f32x4_t*>(accs + ((size_t)((wave * NHB + nb) * MB + mb) * 64 + lane) * 4) = acc[nb][mb] * f_own[nb];
+    __syncthreads();
+    float* part = p->part + ((size_t)b * p->n_splits + split) * p->part_stride + g->part_off;
+    const int pstride = rv + 4;
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb) {
+        if (nb >= nhb) continue;
+        const int slot = nb * 16 + l16;
+        if (wave == 0 && lane < 16) { part[(size_t)slot * pstride] = m_all[nb]; part[(size_t)slot * pstride + 1] = l_all[nb]; }
+        // 16-column blocks are shared out over the four waves
+        for (int mb = wave; mb < mblocks; mb += kWaves) {
+            f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) s += *reinterpret_cast<const f32x4_t*>(accs + ((size_t)((w * NHB + nb) * MB + mb) * 64 + lane) * 4);
+            *reinterpret_cast<f32x4_t*>(part + (size_t)slot * pstride + 4 + 16 * mb + 4 * lg) = s;
+        }
+    }
+    }
+}
+
+constexpr size_t mfma_lds_bytes(int rmax, int nhb) {
+    size_t stage = (size_t)kWaves * (rmax <= 128 ? kWaveTile * (2 * rmax + 16) + kWaveTile * (2 * rmax + 32) : kWaveTile * (2 * rmax + 32));
+    size_t merge = (size_t)(2 * kWaves * nhb * 16 + kWaves * nhb * (rmax / 16) * 64 * 4) * sizeof(float);
+    return stage > merge ? stage : merge;
+}
+
+}  // namespace kvcar

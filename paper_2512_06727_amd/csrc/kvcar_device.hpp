@@ -73,6 +73,30 @@ __device__ __forceinline__ float pinned(float x) {
     return x;
 }
 
+// int8 quantisation of one latent row ("Quantization", Eq. "quant"), one fp32 operation per step:
+//   scale = 255 / (max - min);  zeropoint = -round(scale * min) - 128;  code = round(scale * x + zeropoint)
+// round = half to even, codes saturate to [-128, 127]; a row of equal values uses |x| as its range, an
+// all-zero row 1.  Products are pinned so that none is fused into the add that follows.
+struct QuantParams {
+    float scale, zp;       // zp holds the integer zero point as a float
+};
+__device__ __forceinline__ QuantParams quant_params(float mn, float mx) {
+    float rng = mx - mn;
+    if (rng == 0.f) rng = fabsf(mx);
+    if (rng == 0.f) rng = 1.f;
+    QuantParams q;
+    q.scale = 255.f / rng;                                  // correctly rounded fp32 division
+    q.zp = -rintf(pinned(q.scale * mn)) - 128.f;
+    return q;
+}
+__device__ __forceinline__ signed char quant_code(float x, const QuantParams& q) {
+    const float c = rintf(pinned(q.scale * x) + q.zp);
+    return (signed char)(int)fminf(fmaxf(c, -128.f), 127.f);
+}
+__device__ __forceinline__ RowMeta quant_meta(const QuantParams& q) {
+    return RowMeta{q.scale, (int)fminf(fmaxf(q.zp, -2147483648.f), 2147483520.f)};
+}
+
 __device__ __forceinline__ float apply_act_fast(float x, int act, float slope) {
     if (act == KVCAR_ACT_LEAKY_RELU) return x >= 0.f ? x : slope * x;
     if (act == KVCAR_ACT_GELU) return 0.5f * x * (1.f + erf_rational(x * 0.70710678118654752f));

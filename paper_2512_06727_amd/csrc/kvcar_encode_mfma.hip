@@ -170,6 +170,44 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
         const int b = t / p.t_new, tt = t - b * p.t_new;
         row_off[v] = ((size_t)b * p.max_seq + p.pos0 + tt) * s.r;
     }
+    if (s.meta) {
+        // ---- int8 latents: a token's row lies in the 16 lanes of its quarter (columns 16 nb + l16) -------
+        constexpr int NBO = kTwoLayer ? NB2 : NB1;
+        float mn[4], mx[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) { mn[v] = INFINITY; mx[v] = -INFINITY; }
+#pragma unroll
+        for (int nb = 0; nb < NBO; ++nb) {
+            const int col = nb * 16 + l16;
+            if (nb < n_out_blocks && col < s.r) {
+                const float bias = out_bias ? Elem<E>::load(out_bias, col) : 0.f;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    out_acc[nb][v] += bias;
+                    mn[v] = fminf(mn[v], out_acc[nb][v]);
+                    mx[v] = fmaxf(mx[v], out_acc[nb][v]);
+                }
+            }
+        }
+        signed char* z8 = static_cast<signed char*>(s.z);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+#pragma unroll
+            for (int off = 8; off > 0; off >>= 1) {
+                mn[v] = fminf(mn[v], __shfl_xor(mn[v], off));
+                mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], off));
+            }
+            const QuantParams qp = quant_params(mn[v], mx[v]);
+            if (!row_ok[v]) continue;
+#pragma unroll
+            for (int nb = 0; nb < NBO; ++nb) {
+                const int col = nb * 16 + l16;
+                if (nb < n_out_blocks && col < s.r) z8[row_off[v] + col] = quant_code(out_acc[nb][v], qp);
+            }
+            if (l16 == 0) static_cast<RowMeta*>(s.meta)[row_off[v] / s.r] = quant_meta(qp);
+        }
+        return;
+    }
     uint16_t* z = static_cast<uint16_t*>(s.z);
 #pragma unroll
     for (int nb = 0; nb < (kTwoLayer ? NB2 : NB1); ++nb) {

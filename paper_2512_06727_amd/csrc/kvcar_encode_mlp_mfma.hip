@@ -204,6 +204,34 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
     float b2v[NBZ];
 #pragma unroll
     for (int nb = 0; nb < NBZ; ++nb) b2v[nb] = s.b2 ? Elem<E>::load(s.b2, 32 * nb + l32) : 0.f;
+    if (s.meta) {
+        // ---- int8 latents: a token's row lies in the 32 lanes of its half (columns 32 nb + l32) ---------
+        signed char* z8 = static_cast<signed char*>(s.z);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+            for (int nb = 0; nb < NBZ; ++nb) {
+                accz[nb][v] += b2v[nb];
+                mn = fminf(mn, accz[nb][v]);
+                mx = fmaxf(mx, accz[nb][v]);
+            }
+#pragma unroll
+            for (int off = 16; off > 0; off >>= 1) {
+                mn = fminf(mn, __shfl_xor(mn, off));
+                mx = fmaxf(mx, __shfl_xor(mx, off));
+            }
+            const QuantParams qp = quant_params(mn, mx);
+            const int t = tbase + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (t >= n_tok) continue;
+            const int b = t / p.t_new, tt = t - b * p.t_new;
+            const size_t row = (size_t)b * p.max_seq + p.pos0 + tt;
+#pragma unroll
+            for (int nb = 0; nb < NBZ; ++nb) z8[row * r + 32 * nb + l32] = quant_code(accz[nb][v], qp);
+            if (l32 == 0) static_cast<RowMeta*>(s.meta)[row] = quant_meta(qp);
+        }
+        return;
+    }
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int t = tbase + 8 * (v >> 2) + 4 * h + (v & 3);

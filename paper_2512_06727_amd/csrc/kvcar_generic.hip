@@ -66,9 +66,6 @@ __global__ __launch_bounds__(256) void encode_generic_kernel(EncodeParams p) {
     if (s.meta == nullptr) return;
 
     // ---- int8 latents ("Quantization", Eq. "quant"): 32 lanes per token row -------------------------
-    //   scale = 255 / (max - min);  zeropoint = -round(scale * min) - 128;  code = round(scale * x + zeropoint)
-    // Every operation is one fp32 operation (products are pinned so that none is fused into the
-    // following add); a row of equal values uses |x| as its range, an all-zero row 1.
     __syncthreads();
     const int t = tid >> 5, j = tid & 31;
     if (t >= nt) return;
@@ -80,20 +77,13 @@ __global__ __launch_bounds__(256) void encode_generic_kernel(EncodeParams p) {
         mn = fminf(mn, __shfl_xor(mn, off));
         mx = fmaxf(mx, __shfl_xor(mx, off));
     }
-    float rng = mx - mn;
-    if (rng == 0.f) rng = fabsf(mx);
-    if (rng == 0.f) rng = 1.f;
-    const float scale = 255.f / rng;                       // correctly rounded fp32 division
-    const float zp = -rintf(pinned(scale * mn)) - 128.f;
+    const QuantParams qp = quant_params(mn, mx);
     const int tok = tok0 + t;
     const int b = tok / p.t_new, tt = tok % p.t_new;
     const size_t row = (size_t)b * p.max_seq + p.pos0 + tt;
     signed char* codes = static_cast<signed char*>(s.z) + row * s.r;
-    for (int c = j; c < s.r; c += 32) {
-        const float q = rintf(pinned(scale * zr[c]) + zp);
-        codes[c] = (signed char)(int)fminf(fmaxf(q, -128.f), 127.f);
-    }
-    if (j == 0) static_cast<RowMeta*>(s.meta)[row] = RowMeta{scale, (int)fminf(fmaxf(zp, -2147483648.f), 2147483520.f)};
+    for (int c = j; c < s.r; c += 32) codes[c] = quant_code(zr[c], qp);
+    if (j == 0) static_cast<RowMeta*>(s.meta)[row] = quant_meta(qp);
 }
 
 hipError_t launch_encode_generic(const EncodeParams& p, int dtype, hipStream_t stream) {

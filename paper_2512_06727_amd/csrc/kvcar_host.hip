@@ -84,6 +84,7 @@ struct Plan {
     std::vector<GroupDesc> groups;
     bool mfma = false;        // an MFMA attention kernel (linear or two-layer decoder) is used
     bool mlp = false;         // ... the two-layer one
+    bool i8 = false;          // ... the one over int8 latent rows (absorbed queries travel in fp32)
     bool fused = false;       // one kernel does prologue, attention and epilogue (single split, exact shapes)
     int n_splits = 1;
     int qt_stride = 0;        // elements per sequence
@@ -128,7 +129,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
 
     plan.groups.clear();
     // MFMA kernels: 16-bit dtype, linear decoders, latent widths that are multiples of 32
-    bool mfma_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && attend_mfma_available() && c.d_head % 8 == 0 && !ctx->int8();
+    bool mfma_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && attend_mfma_available() && c.d_head % 8 == 0;
     // ... or two-layer decoders of one of the shapes with a resident-weight kernel, the same for K and V
     bool mlp_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && c.d_head % 32 == 0 && c.d_head <= 128 && !ctx->int8();
     int mlp_r = -1, mlp_c = -1, mlp_act = -1;
@@ -145,6 +146,8 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
         if (base.k.c > kMaxRow || base.v.c > kMaxRow || base.k.r > kMaxRow || base.v.r > kMaxRow)
             return fail(ctx, KVCAR_ERR_UNSUPPORTED, "row width above %d", kMaxRow);
         if (base.k.w1 || base.v.w1 || base.k.r % 32 || base.v.r % 32 || base.k.r > 384 || base.v.r > 384) mfma_ok = false;
+        // int8 rows: equal K and V widths up to 128 only
+        if (ctx->int8() && (base.k.r != base.v.r || base.k.r > 128)) mfma_ok = false;
         for (const SideDesc* sd : {&base.k, &base.v}) {
             if (!sd->w1) { mlp_ok = false; continue; }
             if (mlp_r < 0) { mlp_r = sd->r; mlp_c = sd->c; mlp_act = sd->act; mlp_slope = sd->slope; }
@@ -196,6 +199,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     }
     plan.mfma = mfma_ok;
     plan.mlp = mlp_ok;
+    plan.i8 = mfma_ok && ctx->int8();
     int qt = 0, part = 0;
     for (auto& gd : plan.groups) {
         gd.qt_off = qt; gd.part_off = part;
@@ -237,7 +241,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
             }
         }
     }
-    plan.qt_bytes = align_up((size_t)batch * qt * (plan.mfma ? 2 : 4), 256);
+    plan.qt_bytes = align_up((size_t)batch * qt * (plan.mfma && !plan.i8 ? 2 : 4), 256);
     plan.part_bytes = align_up((size_t)batch * splits * part * sizeof(float), 256);
     plan.total_bytes = plan.qt_bytes + plan.part_bytes;
     return KVCAR_OK;
@@ -442,7 +446,7 @@ int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void
     if (!any) return KVCAR_OK;   // the layer stores nothing
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
-    const bool mfma_enc = !ctx->tun.force_generic && !ctx->int8();
+    const bool mfma_enc = !ctx->tun.force_generic;
     if (mfma_enc && encode_mlp_mfma_supported(p, c.dtype)) e = launch_encode_mlp_mfma(p, c.dtype, st);
     else if (mfma_enc && encode_mfma_supported(p, c.dtype)) e = launch_encode_mfma(p, c.dtype, st);
     else e = launch_encode_generic(p, c.dtype, st);
@@ -481,7 +485,7 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
         p.fused = plan.fused ? 1 : 0;
         const bool proj = plan.mfma && proj_mfma_supported(p, c.dtype);
         hipError_t e = hipSuccess;
-        if (!plan.fused) e = proj ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma, st);
+        if (!plan.fused) e = proj && !plan.i8 ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma || plan.i8, st);
         std::pair<hipEvent_t, hipEvent_t>* ev = nullptr;
         if (e == hipSuccess && ctx->profiling) {
             if (ctx->ev_used == ctx->ev_pool.size()) {
@@ -494,6 +498,7 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
         }
         if (e == hipSuccess)
             e = plan.mlp ? launch_attend_mlp_mfma(p, c.dtype, st)
+                         : plan.i8 ? launch_attend_i8_mfma(p, c.dtype, st)
                          : plan.mfma ? launch_attend_mfma(p, c.dtype, st) : launch_attend_generic(p, c.dtype, st);
         if (e == hipSuccess && ev) e = hipEventRecord(ev->second, st);
         if (e == hipSuccess && !plan.fused) e = proj ? launch_combine_mfma(p, c.dtype, st) : launch_combine(p, c.dtype, st);

@@ -110,6 +110,10 @@ hipError_t launch_attend_mlp_mfma(const AttendParams& p, int dtype, hipStream_t 
 bool attend_mfma_available();
 hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stream);
 
+// MFMA attention over int8 latent rows (linear decoders, equal K / V widths of 32..128).
+bool attend_i8_mfma_supported(const AttendParams& p, int dtype);
+hipError_t launch_attend_i8_mfma(const AttendParams& p, int dtype, hipStream_t stream);
+
 hipError_t launch_stream_read(const void* src, size_t bytes, int n_blocks, int block, unsigned* sink, hipStream_t stream);
 
 }  // namespace kvcar

@@ -41,6 +41,21 @@ def test_int8_split_counts(n_splits):
     assert_outputs_close(w, got, want, label=f"splits={n_splits}")
 
 
+@pytest.mark.parametrize("name", ["c2-small-bf16", "c4-small-bf16"])
+@pytest.mark.parametrize("gain", [1.0, 50.0])
+def test_int8_mfma_kernel_is_used_and_agrees_with_plain_alu(name, gain):
+    """16-bit dtypes with linear decoders of width <= 128 take the MFMA kernel over int8 rows (fused
+    when one split is enough, else with the prologue / merge kernels); the plain-ALU kernels must
+    give the same outputs from the same caches."""
+    from paper_2512_06727_amd.harness import Session
+    w, kw = CASES[name]
+    assert Session(w, latent_format="int8").ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached + 1).uses_mfma == 1
+    orc, want = run_oracle(w, gain=gain, latent_format="int8", **kw)
+    for session_kw in ({"n_splits": 1}, {"n_splits": 1, "no_fuse": True}, {"n_splits": 4}, {"force_generic": True}):
+        ses, got = run_gpu(w, gain=gain, latent_format="int8", **session_kw, **kw)
+        assert_outputs_close(w, got, want, label=f"{name} {session_kw}")
+
+
 def test_int8_cache_is_smaller_and_laid_out_as_documented():
     w = C[2].scaled(n_layers=2, batch=2, n_cached=10, n_steps=1, reuse="none")
     from paper_2512_06727_amd.harness import Session
