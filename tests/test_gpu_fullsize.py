@@ -17,9 +17,9 @@ def sources(reuse, layer, which):
     return [O.resolve_source(reuse, layer, which, g) for g in range(reuse.shape[2])]
 
 
-def oracle_unit(w, reuse, layer, b, n_cached, q_row):
+def oracle_unit(w, reuse, layer, b, n_cached, q_row, latent_format="dtype"):
     """Attention output of one (layer, sequence) at the first decode step, from scratch."""
-    orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, 1, w.max_seq, w.dtype)
+    orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, 1, w.max_seq, w.dtype, latent_format=latent_format)
     for n in range(w.n_layers):
         orc.set_reuse_map(n, reuse[n, 0], reuse[n, 1])
     need = {layer} | set(sources(reuse, layer, 0)) | set(sources(reuse, layer, 1))
@@ -32,9 +32,9 @@ def oracle_unit(w, reuse, layer, b, n_cached, q_row):
     return orc.decode_attention(layer, q_row[None], n_cached + 1)[0], orc
 
 
-def run_fullsize(w, layers, seqs, gain, check_cache=True):
+def run_fullsize(w, layers, seqs, gain, check_cache=True, latent_format="dtype"):
     reuse = synth.reuse_map(w)
-    ses = Session(w, reuse=reuse)
+    ses = Session(w, reuse=reuse, latent_format=latent_format)
     need = set()
     for n in layers:
         need |= {n} | set(sources(reuse, n, 0)) | set(sources(reuse, n, 1))
@@ -47,12 +47,22 @@ def run_fullsize(w, layers, seqs, gain, check_cache=True):
         plan = ses.ctx.describe_plan(n, w.batch, w.n_cached + 1)
         print(f"layer {n}: mfma={plan.uses_mfma} groups={plan.n_groups} splits={plan.n_splits}", flush=True)
         for b in seqs:
-            want, orc = oracle_unit(w, reuse, n, b, w.n_cached, q[b].double().numpy())
+            want, orc = oracle_unit(w, reuse, n, b, w.n_cached, q[b].double().numpy(), latent_format)
             err = np.abs(out[b] - want).max()
             ref = np.abs(want).max()
             assert err <= ABS_TOL[w.dtype], (n, b, err)
             assert err <= REL_TOL[w.dtype] * ref, (n, b, err, ref)
-            if check_cache:
+            if check_cache and latent_format == "int8":
+                for which in (0, 1):
+                    view = ses.quantized_view(n, which)
+                    if view is None:
+                        continue
+                    codes, scale, zp = (x[b, : w.n_cached + 1].cpu().numpy() for x in view)
+                    np.testing.assert_allclose(scale, orc.Qscale[(n, which)][0, : w.n_cached + 1], rtol=2e-5)
+                    dz = np.abs(zp.astype(np.int64) - orc.Qzero[(n, which)][0, : w.n_cached + 1])
+                    dc = np.abs(codes.astype(np.int32) - orc.Q[(n, which)][0, : w.n_cached + 1])
+                    assert dz.max() <= 1 and dc.max() <= 1 and (dc > 0).mean() < 0.01
+            elif check_cache:
                 for which in (0, 1):
                     view = ses.cache_view(n, which)
                     if view is None:
@@ -73,6 +83,14 @@ def test_long_context_tinyllama_full_size():
     layers = sorted({0, w.n_layers - 1, int(np.argmax(n_src)), deepest})
     ses = run_fullsize(w, layers, seqs=[0, 101, 255], gain=30.0)
     assert ses.ctx.describe_plan(0, w.batch, w.n_cached + 1).uses_mfma == 1
+
+
+def test_long_context_tinyllama_full_size_int8():
+    """The same workload with int8 latents ("Quantization"): the MFMA kernel over code bytes."""
+    w = synth.CONFIGS[4].scaled(n_steps=1)
+    ses = run_fullsize(w, [0, 9, w.n_layers - 1], seqs=[0, 200], gain=30.0, latent_format="int8")
+    plan = ses.ctx.describe_plan(0, w.batch, w.n_cached + 1)
+    assert plan.uses_mfma == 1 and plan.fused == 1
 
 
 def test_tinyllama_full_size():
