@@ -117,6 +117,7 @@ def main():
                          "inputs (profiling runs only: same traffic, far fewer helper kernels)")
     ap.add_argument("--latent", default="dtype", choices=["dtype", "int8"],
                     help="latent rows in the model dtype (default, the headline) or as int8 codes with a scale and zero point per row")
+    ap.add_argument("--wg-waves", type=int, default=0, help="fused attention kernel: 0 automatic, 4 or 8 waves per workgroup")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (counter calibration under rocprofv3 --pmc)")
@@ -147,7 +148,7 @@ def main():
     reuse = synth.reuse_map(w)
     elem = synth.DTYPE_BYTES[w.dtype]
 
-    ses = Session(w, reuse=reuse, n_splits=args.splits, tile_order=args.tile_order, latent_format=args.latent)
+    ses = Session(w, reuse=reuse, n_splits=args.splits, tile_order=args.tile_order, latent_format=args.latent, wg_waves=args.wg_waves)
     lat_elem, row_meta = (1, 8) if args.latent == "int8" else (elem, 0)
     dev, tdt = ses.dev, ses.tdt
     widths = [[ses.ae[n][which].latent for which in (0, 1)] for n in range(w.n_layers)]

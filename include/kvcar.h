@@ -127,7 +127,9 @@ typedef struct {
     int tile_order;     /* MFMA attention: 0 = library default, 1 = each split owns a contiguous
                            token range, 2 = 128-token tiles dealt round-robin over the splits    */
     int no_fuse;        /* 1 = always run prologue / attention / epilogue as separate kernels     */
-    int reserved[4];
+    int wg_waves;       /* fused attention kernel: 0 = automatic (eight waves per workgroup when the
+                           launch has no more workgroups than compute units, else four), 4 or 8      */
+    int reserved[3];
 } kvcar_tuning;
 
 /* Create / destroy a context.  ERR_ARG on null pointers, ERR_SHAPE on non-positive sizes or

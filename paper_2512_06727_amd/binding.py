@@ -38,7 +38,7 @@ class AEDesc(C.Structure):
 
 
 class Tuning(C.Structure):
-    _fields_ = [("n_splits", C.c_int), ("force_generic", C.c_int), ("tile_order", C.c_int), ("no_fuse", C.c_int), ("reserved", C.c_int * 4)]
+    _fields_ = [("n_splits", C.c_int), ("force_generic", C.c_int), ("tile_order", C.c_int), ("no_fuse", C.c_int), ("wg_waves", C.c_int), ("reserved", C.c_int * 3)]
 
 
 class PlanInfo(C.Structure):
@@ -174,8 +174,9 @@ class Context:
         nbytes = 0 if tensor is None else tensor.numel() * tensor.element_size()
         self._check(lib().kvcar_bind_cache(self._h, layer, which, _ptr(tensor), nbytes))
 
-    def set_tuning(self, n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, no_fuse: bool = False):
-        t = Tuning(n_splits, 1 if force_generic else 0, tile_order, 1 if no_fuse else 0)
+    def set_tuning(self, n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, no_fuse: bool = False,
+                   wg_waves: int = 0):
+        t = Tuning(n_splits, 1 if force_generic else 0, tile_order, 1 if no_fuse else 0, wg_waves)
         self._check(lib().kvcar_set_tuning(self._h, C.byref(t)))
 
     def workspace_bytes(self, batch: int, n_ctx: int) -> int:

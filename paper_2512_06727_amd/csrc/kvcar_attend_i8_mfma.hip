@@ -41,6 +41,26 @@ __global__ __launch_bounds__(256, 2) void attend_i8_mfma_r128_kernel(AttendParam
     }
 }
 
+// Eight waves per workgroup (fused, single split): for launches with no more workgroups than compute units.
+template <typename E>
+__global__ __launch_bounds__(512, 1) void attend_i8_mfma_r128_w8_kernel(AttendParams p_by_value) {
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    (void)p_by_value;
+    KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    KGroup g = &p->g[blockIdx.z];
+    switch (g->k.r * 4 + (g->slots_pad >> 4)) {
+        case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+        case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+        case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+        case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+        case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+        case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+        case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+        case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+        default: return;
+    }
+}
+
 // Every group: int8 rows with metadata, linear decoders, K and V latent widths equal and one of 32 / 64 / 96 / 128,
 // at most 32 query heads.
 bool attend_i8_mfma_supported(const AttendParams& p, int dtype) {
@@ -54,8 +74,22 @@ bool attend_i8_mfma_supported(const AttendParams& p, int dtype) {
 }
 
 hipError_t launch_attend_i8_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
-    static bool attr[2] = {false, false};
+    static bool attr[2] = {false, false}, attr8[2] = {false, false};
     if (!attend_i8_mfma_supported(p, dtype)) return hipErrorNotSupported;
+    if (p.fused == 2) {
+        const size_t epi8 = 2048 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);
+        size_t lds8 = 8 * kI8WaveLds + 2 * 4 * 64 * 16;
+        lds8 = lds8 > epi8 ? lds8 : epi8;
+        const int e8 = dtype == KVCAR_BF16 ? 0 : 1;
+        auto kern8 = e8 == 0 ? attend_i8_mfma_r128_w8_kernel<BF16> : attend_i8_mfma_r128_w8_kernel<F16>;
+        if (!attr8[e8]) {
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern8), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (err != hipSuccess) return err;
+            attr8[e8] = true;
+        }
+        hipLaunchKernelGGL(kern8, dim3(p.n_splits, p.batch, p.n_groups), dim3(512), lds8, stream, p);
+        return hipGetLastError();
+    }
     const size_t epi = 1024 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);
     const size_t merge = mfma_lds_bytes(128, 2);
     size_t lds = kWaves * kI8WaveLds + (p.fused ? 2 * 4 * 64 * 16 : 0);

@@ -43,6 +43,29 @@ __global__ __launch_bounds__(256, 2) void attend_mfma_r128_kernel(AttendParams p
     attend_body<E, DimsAny<128, 2>, false>(p, g, lds_raw, wl);
 }
 
+// Fused single-split variant with eight waves per workgroup, for launches with no more workgroups
+// than compute units: a four-wave workgroup alone on a compute unit leaves one wave per SIMD, which
+// cannot overlap its loads, MFMA and vector work with anything.
+template <typename E>
+__global__ __launch_bounds__(512, 1) void attend_mfma_r128_w8_kernel(AttendParams p_by_value) {
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    (void)p_by_value;
+    KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    KGroup g = &p->g[blockIdx.z];
+    constexpr size_t wl = Geo<128>::kWaveLds;
+    switch (g->k.r * 4 + (g->slots_pad >> 4)) {
+        case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, true, false, 8>(p, g, lds_raw, wl); return;
+        case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, true, false, 8>(p, g, lds_raw, wl); return;
+        case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, true, false, 8>(p, g, lds_raw, wl); return;
+        case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, true, false, 8>(p, g, lds_raw, wl); return;
+        case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, true, false, 8>(p, g, lds_raw, wl); return;
+        case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, true, false, 8>(p, g, lds_raw, wl); return;
+        case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, true, false, 8>(p, g, lds_raw, wl); return;
+        case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, true, false, 8>(p, g, lds_raw, wl); return;
+        default: return;
+    }
+}
+
 // Latent widths up to 384 (GPT-2-class KV widths): one 16-head block per group.
 template <typename E>
 __global__ __launch_bounds__(256, 1) void attend_mfma_r384_kernel(AttendParams p_by_value) {
@@ -57,21 +80,21 @@ __global__ __launch_bounds__(256, 1) void attend_mfma_r384_kernel(AttendParams p
 }
 
 template <typename K>
-static hipError_t launch_one(K kern, size_t lds, const AttendParams& p, hipStream_t stream, bool& attr_set) {
+static hipError_t launch_one(K kern, size_t lds, const AttendParams& p, hipStream_t stream, bool& attr_set, int threads = 256) {
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.n_splits, p.batch, p.n_groups);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
+    hipLaunchKernelGGL(kern, grid, dim3(threads), lds, stream, p);
     return hipGetLastError();
 }
 
 bool attend_mfma_available() { return true; }
 
 hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
-    static bool set128[2] = {false, false}, set384[2] = {false, false};
+    static bool set128[2] = {false, false}, set384[2] = {false, false}, set128w8[2] = {false, false};
     int rmax = 0, nhb = 1;
     for (int i = 0; i < p.n_groups; ++i) {
         rmax = p.g[i].k.r > rmax ? p.g[i].k.r : rmax;
@@ -79,6 +102,15 @@ hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stre
         nhb = p.g[i].slots_pad / 16 > nhb ? p.g[i].slots_pad / 16 : nhb;
     }
     const int e = dtype == KVCAR_BF16 ? 0 : 1;
+    if (rmax <= 128 && nhb <= 2 && p.fused == 2) {
+        // eight waves: staging regions + swapped query operands, or the epilogue's exchange area (m, l of
+        // eight waves) + latent sums + one decoder slice
+        const size_t epi = 2048 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);
+        const size_t stage = 8 * Geo<128>::kWaveLds + 2 * 4 * 64 * 16;
+        const size_t lds = epi > stage ? epi : stage;
+        return e == 0 ? launch_one(attend_mfma_r128_w8_kernel<BF16>, lds, p, stream, set128w8[0], 512)
+                      : launch_one(attend_mfma_r128_w8_kernel<F16>, lds, p, stream, set128w8[1], 512);
+    }
     if (rmax <= 128 && nhb <= 2) {
         // fused: + normalised latent sums [32][132] fp32 + one decoder-matrix slice [128][2*d_head+32]
         // fused epilogue: exchange area + latent sums [32][132] fp32 + one decoder slice [128][2*d_head+32]

@@ -197,7 +197,7 @@ __device__ __forceinline__ void park_tile_i8(const u32x4_t (&st)[NL], char* regi
 // kFused (single split, exact shapes only): the absorbed queries are computed in the prologue and the
 // last decoder layer of V is applied in the epilogue, so the whole decode attention of a layer is this
 // one kernel and neither the absorbed queries nor the partials travel through memory.
-template <typename E, typename D, bool kFused, bool kI8 = false>
+template <typename E, typename D, bool kFused, bool kI8 = false, int NW = kWaves>
 __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, size_t wave_lds) {
     constexpr int RMAX = D::RMAX, NHB = D::NHB;
     using G = Geo<RMAX>;
@@ -226,7 +226,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     // Workgroup tiles (4 wave tiles = 128 tokens each) of this split.  tile_order 0: a contiguous
     // token range per split; 1: tiles dealt round-robin over the splits, so that workgroups running
     // at the same time read neighbouring addresses.
-    const int wg_tiles = (p->n_ctx + kWaveTile * kWaves - 1) / (kWaveTile * kWaves);
+    const int wg_tiles = (p->n_ctx + kWaveTile * NW - 1) / (kWaveTile * NW);
     int j0, j1, jstep;
     if (p->tile_order == 0) {
         const int per_split = (wg_tiles + p->n_splits - 1) / p->n_splits;
@@ -246,23 +246,33 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         mrow = static_cast<const RowMeta*>(lane < 32 ? g->k.meta : g->v.meta) + (size_t)b * p->max_seq;
         mlds = reinterpret_cast<float*>(my_lds + kWaveTile * stride_k + kWaveTile * stride_v);
     }
-    u32x2_t stm = {0u, 0u};
 
-    // kPrefetch: both tiles of the next iteration are in flight while this one computes.
-    // Otherwise (wide rows) a tile is loaded right before it is parked and K, V take turns.
-    u32x4_t stk[NL], stv[G::kPrefetch ? NL : 1];
-    auto issue = [&](int j) {
-        const int t0 = (j * kWaves + wave) * kWaveTile;
+    // kPrefetch: both tiles of the next iteration are in flight while this one computes.  Otherwise (wide
+    // rows) a tile is loaded right before it is parked and K, V take turns.  PF = iterations of look-ahead;
+    // two was measured slower for int8 rows (the second set of staging registers spills).
+    constexpr int PF = 1;
+    struct Stage {
+        u32x4_t k[NL];
+        u32x4_t v[G::kPrefetch ? NL : 1];
+        u32x2_t m;
+    };
+    Stage stage[PF];
+    auto issue = [&](Stage& sg, int j) {
+        const int t0 = (j * NW + wave) * kWaveTile;
         const int nv = max(0, min(kWaveTile, p->n_ctx - t0));
-        load_tile<NL>(stk, zk + (size_t)t0 * rk * EB, nlk, nv * cprk, nv == kWaveTile, lane);
-        if constexpr (G::kPrefetch) load_tile<NL>(stv, zv + (size_t)t0 * rv * EB, nlv, nv * cprv, nv == kWaveTile, lane);
+        load_tile<NL>(sg.k, zk + (size_t)t0 * rk * EB, nlk, nv * cprk, nv == kWaveTile, lane);
+        if constexpr (G::kPrefetch) load_tile<NL>(sg.v, zv + (size_t)t0 * rv * EB, nlv, nv * cprv, nv == kWaveTile, lane);
         if constexpr (kI8) {
             const int tok = t0 + (lane & 31);
-            stm = u32x2_t{0x3f800000u, 0u};                       // rows past the context: scale 1, zero point 0
-            if (tok < p->n_ctx) stm = *reinterpret_cast<const u32x2_t*>(mrow + tok);
+            sg.m = u32x2_t{0x3f800000u, 0u};                      // rows past the context: scale 1, zero point 0
+            if (tok < p->n_ctx) sg.m = *reinterpret_cast<const u32x2_t*>(mrow + tok);
         }
     };
-    if (G::kPrefetch && j0 < j1) issue(j0);        // first tile in flight while the queries are prepared
+    if constexpr (G::kPrefetch) {                  // first tiles in flight while the queries are prepared
+#pragma unroll
+        for (int pf = 0; pf < PF; ++pf)
+            if (j0 + pf * jstep < j1) issue(stage[pf], j0 + pf * jstep);
+    }
 
     // absorbed queries of this sequence and group, resident as MFMA B operands
     u32x4_t qb[NHB][KS];
@@ -275,7 +285,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         // all heads (its loads are independent and fly together) and the waves swap through LDS.
         const int dh = p->d_head;
         const char* wl = static_cast<const char*>(g->k.wl);
-        u32x4_t* qlds = reinterpret_cast<u32x4_t*>(lds_raw + kWaves * wave_lds);      // [NHB][KS][64], past the staging regions
+        u32x4_t* qlds = reinterpret_cast<u32x4_t*>(lds_raw + NW * wave_lds);      // [NHB][KS][64], past the staging regions
         if (wave < KS) {
             const int s2 = wave;
 #pragma unroll
@@ -373,17 +383,17 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     for (int nb = 0; nb < NHB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; }
 
 
-    for (int j = j0; j < j1; j += jstep) {
-        const int t0 = (j * kWaves + wave) * kWaveTile;
+    auto tile = [&](Stage& sg, int j) -> bool {
+        const int t0 = (j * NW + wave) * kWaveTile;
         const int nv = min(kWaveTile, p->n_ctx - t0);
-        if (nv <= 0) break;          // wave tile past the context: only in the last workgroup tile, the last one visited
+        if (nv <= 0) return false;   // wave tile past the context: only in the last workgroup tile, the last one visited
 
-        if constexpr (!G::kPrefetch) issue(j);
+        if constexpr (!G::kPrefetch) issue(sg, j);
         if constexpr (kI8) {
-            park_tile_i8<NL>(stk, lds_k, nlk, cprk, stride_k, lane);
-            park_tile_i8<NL>(stv, lds_v, nlv, cprv, stride_v, lane);
-            const float inv = __builtin_amdgcn_rcpf(__uint_as_float(stm[0]));
-            const float off = kI8Offset + (float)(int)stm[1];
+            park_tile_i8<NL>(sg.k, lds_k, nlk, cprk, stride_k, lane);
+            park_tile_i8<NL>(sg.v, lds_v, nlv, cprv, stride_v, lane);
+            const float inv = __builtin_amdgcn_rcpf(__uint_as_float(sg.m[0]));
+            const float off = kI8Offset + (float)(int)sg.m[1];
             if (lane < 32) {
                 mlds[lane] = inv;
                 mlds[32 + lane] = inv * off;
@@ -396,12 +406,12 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
                 const float h0 = r1 - 64.f * h1;
                 *reinterpret_cast<u32x2_t*>(lds_v + (lane - 32) * stride_v + 2 * rv) = u32x2_t{Mma<F16>::pack2(h2, h1), Mma<F16>::pack2(h0, 0.f)};
             }
-            if (j + jstep < j1) issue(j + jstep);
+            if (j + PF * jstep < j1) issue(sg, j + PF * jstep);
         } else {
-        park_tile<NL>(stk, lds_k, nlk, cprk, stride_k, lane);
+        park_tile<NL>(sg.k, lds_k, nlk, cprk, stride_k, lane);
         if constexpr (G::kPrefetch) {
-            park_tile<NL>(stv, lds_v, nlv, cprv, stride_v, lane);
-            if (j + jstep < j1) issue(j + jstep);
+            park_tile<NL>(sg.v, lds_v, nlv, cprv, stride_v, lane);
+            if (j + PF * jstep < j1) issue(sg, j + PF * jstep);
         }
         }
 
@@ -427,8 +437,8 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         if constexpr (!G::kPrefetch) {
             // K and V share the staging registers and the LDS region: V rows replace K rows
             // (LDS operations of one wave complete in order, so the score reads are done)
-            load_tile<NL>(stk, zv + (size_t)t0 * rv * 2, nlv, nv * cprv, nv == kWaveTile, lane);
-            park_tile<NL>(stk, lds_v, nlv, cprv, stride_v, lane);
+            load_tile<NL>(sg.k, zv + (size_t)t0 * rv * 2, nlv, nv * cprv, nv == kWaveTile, lane);
+            park_tile<NL>(sg.k, lds_v, nlv, cprv, stride_v, lane);
         }
         f32x4_t av4[2];                   // int8: 256 / scale_V of this lane's eight tokens
         if constexpr (kI8) {
@@ -517,6 +527,14 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
 #pragma unroll
             for (int nb = 0; nb < NHB; ++nb) accx[nb] = Mma<ML>::mfma(va, pb[nb], accx[nb]);
         }
+        return true;
+    };
+    for (int j = j0; j < j1; j += PF * jstep) {
+        bool more = true;
+#pragma unroll
+        for (int pf = 0; pf < PF; ++pf)
+            if (more && j + pf * jstep < j1) more = tile(stage[pf], j + pf * jstep);
+        if (!more) break;
     }
     if constexpr (kI8) {
         // sum_t P_t x^_t = (sum_t P_t u_t - sum_t P_t off_t) / 256; the second sum sits in rows 0..2 of accx,
@@ -537,12 +555,12 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     }
     __syncthreads();                                   // every wave is done with its staging region
     float* red = reinterpret_cast<float*>(lds_raw);    // [wave][NHB*16] m, then l
-    float* accs = reinterpret_cast<float*>(lds_raw) + 2 * kWaves * NHB * 16;   // [wave][NHB][MB][64][4]
+    float* accs = reinterpret_cast<float*>(lds_raw) + 2 * NW * NHB * 16;   // [wave][NHB][MB][64][4]
     if (lane < 16) {
 #pragma unroll
         for (int nb = 0; nb < NHB; ++nb) {
             red[wave * NHB * 16 + nb * 16 + lane] = m_run[nb];
-            red[kWaves * NHB * 16 + wave * NHB * 16 + nb * 16 + lane] = l_run[nb];
+            red[NW * NHB * 16 + wave * NHB * 16 + nb * 16 + lane] = l_run[nb];
         }
     }
     __syncthreads();
@@ -551,12 +569,12 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     for (int nb = 0; nb < NHB; ++nb) {
         float M = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, red[w * NHB * 16 + nb * 16 + l16]);
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, red[w * NHB * 16 + nb * 16 + l16]);
         float L = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
+        for (int w = 0; w < NW; ++w) {
             const float mw = red[w * NHB * 16 + nb * 16 + l16];
-            L += mw == -INFINITY ? 0.f : red[kWaves * NHB * 16 + w * NHB * 16 + nb * 16 + l16] * exp2f(mw - M);
+            L += mw == -INFINITY ? 0.f : red[NW * NHB * 16 + w * NHB * 16 + nb * 16 + l16] * exp2f(mw - M);
         }
         f_own[nb] = m_run[nb] == -INFINITY ? 0.f : exp2f(m_run[nb] - M);
         m_all[nb] = M;
@@ -569,10 +587,10 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         // add their scaled accumulators one after the other (fixed order: deterministic) into the
         // normalised latent sums olat[slot][rv + 4] in LDS.  Per KV head: slice -> LDS, transposing loads
         // as B operand, latent sums as hi + lo 16-bit A operands; wave w owns output column blocks w, w+4..
-        constexpr int kMaxSeg = 4, kCpt = 4;               // slices, 16-byte chunks per thread and slice
+        constexpr int kMaxSeg = 4, kCpt = 1024 / (64 * NW);   // slices, 16-byte chunks per thread and slice
         const int dh = p->d_head;
         const int ostride = rv + 4;
-        float* olat = red + 2 * kWaves * NHB * 16;
+        float* olat = red + 2 * NW * NHB * 16;
         char* wst = reinterpret_cast<char*>(olat + (size_t)NHB * 16 * ostride);
         const int stride_w = 2 * dh + 32;
         const int cpr = dh >> 3;
@@ -597,7 +615,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         for (int sg = 0; sg < kMaxSeg; ++sg)
 #pragma unroll
             for (int i = 0; i < kCpt; ++i) {
-                const int f = i * 256 + threadIdx.x;
+                const int f = i * (64 * NW) + threadIdx.x;
                 if (sg < nseg && f < rv * cpr) {
                     const int row = f / cpr, ch = f - row * cpr;
                     wreg[sg][i] = *reinterpret_cast<const u32x4_t*>(wlv + ((size_t)row * g->v.in_width + seg_col[sg]) * 2 + ch * 16);
@@ -605,7 +623,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             }
         // sequential, ordered accumulation of the four waves' scaled latent sums
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
+        for (int w = 0; w < NW; ++w) {
             if (wave == w) {
 #pragma unroll
                 for (int nb = 0; nb < NHB; ++nb) {
@@ -627,7 +645,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             if (sg >= nseg) break;
 #pragma unroll
             for (int i = 0; i < kCpt; ++i) {
-                const int f = i * 256 + threadIdx.x;
+                const int f = i * (64 * NW) + threadIdx.x;
                 if (f < rv * cpr) {
                     const int row = f / cpr, ch = f - row * cpr;
                     *reinterpret_cast<u32x4_t*>(wst + row * stride_w + ch * 16) = wreg[sg][i];
@@ -644,7 +662,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
                     for (int lgx = 0; lgx < 4; ++lgx)
                         if (lg == lgx && nb * 16 + 4 * lgx + v < g->n_slots) heads4[v] = g->q_head[nb * 16 + 4 * lgx + v];
                 }
-                for (int nbo = wave; nbo < (dh >> 4); nbo += kWaves) {
+                for (int nbo = wave; nbo < (dh >> 4); nbo += NW) {
                     f32x4_t o = {0.f, 0.f, 0.f, 0.f};
                     for (int k0 = 0; k0 < rv; k0 += 32) {
                         const float* arow = olat + (size_t)(nb * 16 + l16) * ostride + k0 + 8 * lg;
@@ -693,10 +711,10 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         const int slot = nb * 16 + l16;
         if (wave == 0 && lane < 16) { part[(size_t)slot * pstride] = m_all[nb]; part[(size_t)slot * pstride + 1] = l_all[nb]; }
         // 16-column blocks are shared out over the four waves
-        for (int mb = wave; mb < mblocks; mb += kWaves) {
+        for (int mb = wave; mb < mblocks; mb += NW) {
             f32x4_t s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) s += *reinterpret_cast<const f32x4_t*>(accs + ((size_t)((w * NHB + nb) * MB + mb) * 64 + lane) * 4);
+            for (int w = 0; w < NW; ++w) s += *reinterpret_cast<const f32x4_t*>(accs + ((size_t)((w * NHB + nb) * MB + mb) * 64 + lane) * 4);
             *reinterpret_cast<f32x4_t*>(part + (size_t)slot * pstride + 4 + 16 * mb + 4 * lg) = s;
         }
     }

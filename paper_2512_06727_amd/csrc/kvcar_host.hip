@@ -395,7 +395,8 @@ int kvcar_bind_cache(kvcar_ctx* ctx, int layer, int which, void* dev, size_t byt
 
 int kvcar_set_tuning(kvcar_ctx* ctx, const kvcar_tuning* t) {
     if (!ctx || !t) return KVCAR_ERR_ARG;
-    if (t->n_splits < 0 || t->tile_order < 0 || t->tile_order > 2) return fail(ctx, KVCAR_ERR_ARG, "bad tuning value");
+    if (t->n_splits < 0 || t->tile_order < 0 || t->tile_order > 2 || (t->wg_waves != 0 && t->wg_waves != 4 && t->wg_waves != 8))
+        return fail(ctx, KVCAR_ERR_ARG, "bad tuning value");
     ctx->tun = *t;
     return KVCAR_OK;
 }
@@ -482,7 +483,9 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
         p.qt_stride = plan.qt_stride; p.part_stride = plan.part_stride;
         p.scale_log2e = ctx->scale * kLog2e;
         p.tile_order = ctx->tun.tile_order == 2 ? 1 : 0;
-        p.fused = plan.fused ? 1 : 0;
+        // fused: 1 = four waves per workgroup; 2 = eight, when the launch has no more workgroups than compute units
+        const bool w8 = ctx->tun.wg_waves == 8 || (ctx->tun.wg_waves == 0 && batch * p.n_groups <= ctx->n_cu);
+        p.fused = !plan.fused ? 0 : w8 ? 2 : 1;
         const bool proj = plan.mfma && proj_mfma_supported(p, c.dtype);
         hipError_t e = hipSuccess;
         if (!plan.fused) e = proj && !plan.i8 ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma || plan.i8, st);

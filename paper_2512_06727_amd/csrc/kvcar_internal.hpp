@@ -63,7 +63,8 @@ struct AttendParams {
     int part_stride;      // partial floats per (sequence, split) (all groups)
     float scale_log2e;    // softmax scale * log2(e)
     int tile_order;       // MFMA kernel: 0 = contiguous token range per split, 1 = tiles dealt round-robin
-    int fused;            // MFMA kernel: absorbed queries and output epilogue computed inside (single split)
+    int fused;            // MFMA kernel: absorbed queries and output epilogue computed inside (single split);
+                          // 2 = the eight-wave variant of that kernel
 };
 
 struct EncodeSide {

@@ -51,7 +51,8 @@ def test_int8_mfma_kernel_is_used_and_agrees_with_plain_alu(name, gain):
     w, kw = CASES[name]
     assert Session(w, latent_format="int8").ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached + 1).uses_mfma == 1
     orc, want = run_oracle(w, gain=gain, latent_format="int8", **kw)
-    for session_kw in ({"n_splits": 1}, {"n_splits": 1, "no_fuse": True}, {"n_splits": 4}, {"force_generic": True}):
+    for session_kw in ({"n_splits": 1, "wg_waves": 4}, {"n_splits": 1, "wg_waves": 8}, {"n_splits": 1, "no_fuse": True}, {"n_splits": 4},
+                       {"force_generic": True}):
         ses, got = run_gpu(w, gain=gain, latent_format="int8", **session_kw, **kw)
         assert_outputs_close(w, got, want, label=f"{name} {session_kw}")
 

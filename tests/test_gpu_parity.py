@@ -92,7 +92,7 @@ def test_fused_single_split_kernel(name):
     from paper_2512_06727_amd.harness import Session
     w, kw = CASES[name]
     _, want = run_oracle(w, gain=20.0, **kw)
-    for no_fuse in (False, True):
-        ses, got = run_gpu(w, gain=20.0, n_splits=1, no_fuse=no_fuse, **kw)
+    for no_fuse, wg_waves in ((False, 4), (False, 8), (True, 0)):       # four- and eight-wave workgroups, then unfused
+        ses, got = run_gpu(w, gain=20.0, n_splits=1, no_fuse=no_fuse, wg_waves=wg_waves, **kw)
         assert ses.ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached + 1).fused == (0 if no_fuse else 1)
-        assert_outputs_close(w, got, want, f"{name} no_fuse={no_fuse}")
+        assert_outputs_close(w, got, want, f"{name} no_fuse={no_fuse} wg_waves={wg_waves}")
