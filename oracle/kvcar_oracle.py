@@ -240,25 +240,33 @@ class KVCAROracle:
             self.Qzero[(layer, which)] = np.zeros((self.max_batch, self.max_seq), np.int32)
 
     # -- steps 1+2 ----------------------------------------------------------
-    def encode_append(self, layer: int, k_new: np.ndarray, v_new: np.ndarray, pos0: int) -> None:
-        """k_new, v_new [B, T_new, H_kv*d_head]; rows land at [pos0, pos0+T_new)."""
+    def encode_append(self, layer: int, k_new: np.ndarray, v_new: np.ndarray, pos0) -> None:
+        """k_new, v_new [B, T_new, H_kv*d_head]; rows land at [pos0, pos0+T_new).  pos0 may be a
+        sequence of per-sequence positions (ragged batch)."""
+        if not np.isscalar(pos0):
+            for b, pb in enumerate(pos0):
+                self._encode_append_rows(layer, k_new[b:b + 1], v_new[b:b + 1], int(pb), b)
+            return
+        self._encode_append_rows(layer, k_new, v_new, int(pos0), 0)
+
+    def _encode_append_rows(self, layer: int, k_new: np.ndarray, v_new: np.ndarray, pos0: int, b0: int) -> None:
         for which, x in ((K, k_new), (V, v_new)):
             ae = self.ae[(layer, which)]
             if ae.latent == 0 or not ae.heads:
                 continue
             x = np.asarray(x, np.float64)
             b, t, _ = x.shape
-            assert b <= self.max_batch and pos0 + t <= self.max_seq
+            assert b0 + b <= self.max_batch and pos0 + t <= self.max_seq
             cols = np.concatenate([np.arange(g * self.dh, (g + 1) * self.dh) for g in ae.heads])
             z = ae.encode(x[:, :, cols])
             if self.latent_format == "int8":
                 codes, scale, zp = quantize_rows(z)
-                self.Q[(layer, which)][:b, pos0:pos0 + t, :] = codes
-                self.Qscale[(layer, which)][:b, pos0:pos0 + t] = scale
-                self.Qzero[(layer, which)][:b, pos0:pos0 + t] = zp
-                self.Z[(layer, which)][:b, pos0:pos0 + t, :] = dequantize_rows(codes, scale, zp)
+                self.Q[(layer, which)][b0:b0 + b, pos0:pos0 + t, :] = codes
+                self.Qscale[(layer, which)][b0:b0 + b, pos0:pos0 + t] = scale
+                self.Qzero[(layer, which)][b0:b0 + b, pos0:pos0 + t] = zp
+                self.Z[(layer, which)][b0:b0 + b, pos0:pos0 + t, :] = dequantize_rows(codes, scale, zp)
             else:
-                self.Z[(layer, which)][:b, pos0:pos0 + t, :] = round_to_dtype(z, self.dtype)
+                self.Z[(layer, which)][b0:b0 + b, pos0:pos0 + t, :] = round_to_dtype(z, self.dtype)
 
     # -- steps 3+4 ----------------------------------------------------------
     def decoded_head(self, layer: int, which: int, head: int, b: int, n_ctx: int,
@@ -279,26 +287,46 @@ class KVCAROracle:
         return full[:, i * self.dh:(i + 1) * self.dh]
 
     # -- step 5 -------------------------------------------------------------
-    def decode_attention(self, layer: int, q: np.ndarray, n_ctx: int, return_probs: bool = False):
+    def decode_attention(self, layer: int, q: np.ndarray, n_ctx: int, return_probs: bool = False,
+                         seq_lens: Optional[Sequence[int]] = None,
+                         k_cur: Optional[np.ndarray] = None, v_cur: Optional[np.ndarray] = None):
         """q [B, H_q, d_head] -> out [B, H_q, d_head] (fp64), attending over cached
-        tokens 0..n_ctx-1 of every sequence."""
+        tokens 0..n_ctx-1 of every sequence.
+
+        seq_lens: per-sequence context lengths (ragged batch) instead of the common n_ctx.
+        k_cur, v_cur [B, H_kv*d_head]: the paper's form of the decode step ("Network
+        Architecture", 2nd paragraph): the decoded rows of the cached tokens are
+        concatenated with the current token's exact key and value vectors, so the
+        attention runs over n cached rows plus one row that never went through the
+        autoencoder.  Column block g of k_cur / v_cur is the vector KV head g of this
+        layer uses (for a reused head: the source layer's)."""
         q = np.asarray(q, np.float64)
         bsz = q.shape[0]
         group = self.hq // self.hkv
         out = np.zeros((bsz, self.hq, self.dh))
-        probs = np.zeros((bsz, self.hq, n_ctx)) if return_probs else None
+        assert (k_cur is None) == (v_cur is None)
+        exact = k_cur is not None
+        if exact:
+            k_cur = np.asarray(k_cur, np.float64)
+            v_cur = np.asarray(v_cur, np.float64)
+        probs = np.zeros((bsz, self.hq, n_ctx + (1 if exact else 0))) if return_probs else None
         for b in range(bsz):
             memo: dict = {}
+            n = n_ctx if seq_lens is None else int(seq_lens[b])
+            assert 0 <= n <= n_ctx and (n > 0 or exact)
             for j in range(self.hq):
                 g = j // group
-                k_hat = self.decoded_head(layer, K, g, b, n_ctx, memo)
-                v_hat = self.decoded_head(layer, V, g, b, n_ctx, memo)
+                k_hat = self.decoded_head(layer, K, g, b, n, memo)
+                v_hat = self.decoded_head(layer, V, g, b, n, memo)
+                if exact:
+                    k_hat = np.concatenate([k_hat, k_cur[b, None, g * self.dh:(g + 1) * self.dh]], axis=0)
+                    v_hat = np.concatenate([v_hat, v_cur[b, None, g * self.dh:(g + 1) * self.dh]], axis=0)
                 s = (k_hat @ q[b, j]) * self.scale
                 p = np.exp(s - s.max())
                 p = p / p.sum()
                 out[b, j] = p @ v_hat
                 if return_probs:
-                    probs[b, j] = p
+                    probs[b, j, :p.shape[0]] = p
         return (out, probs) if return_probs else out
 
 
