@@ -117,6 +117,10 @@ def main():
                          "inputs (profiling runs only: same traffic, far fewer helper kernels)")
     ap.add_argument("--latent", default="dtype", choices=["dtype", "int8"],
                     help="latent rows in the model dtype (default, the headline) or as int8 codes with a scale and zero point per row")
+    ap.add_argument("--variant", default="cache", choices=["cache", "exact", "ragged"],
+                    help="cache: append the new token, attend over the cache (default, the headline); exact: attend over the cached "
+                         "rows plus the current token's exact K/V row (kvcar_decode_attention_ex), then append; ragged: per-sequence "
+                         "context lengths drawn uniformly from [n_cached/2, n_cached]")
     ap.add_argument("--wg-waves", type=int, default=0, help="fused attention kernel: 0 automatic, 4 or 8 waves per workgroup")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -187,11 +191,24 @@ def main():
     ses.ensure_workspace(w.batch, w.max_seq)
     ctx, ws = ses.ctx, ses.workspace
 
+    seq_lens = None
+    if args.variant == "ragged":
+        gen = torch.Generator(device="cpu").manual_seed(w.seed)
+        seq_lens = torch.randint(w.n_cached // 2, w.n_cached + 1, (w.batch,), generator=gen, dtype=torch.int32).to(dev)
+
     def step_fn(step):
         pos = w.n_cached + step
         for n in range(w.n_layers):
-            ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
-            ctx.decode_attention(n, qs[step][n], outs[n], w.batch, pos + 1, ws)
+            if args.variant == "exact":
+                kc, vc = ks[step][n].view(w.batch, w.d_kv), vs[step][n].view(w.batch, w.d_kv)
+                ctx.decode_attention_ex(n, qs[step][n], outs[n], w.batch, pos, ws, k_cur=kc, v_cur=vc)
+                ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
+            elif args.variant == "ragged":
+                ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
+                ctx.decode_attention_ex(n, qs[step][n], outs[n], w.batch, pos + 1, ws, seq_lens=seq_lens)
+            else:
+                ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
+                ctx.decode_attention(n, qs[step][n], outs[n], w.batch, pos + 1, ws)
 
     for step in range(args.warmup):
         step_fn(step)
@@ -234,13 +251,17 @@ def main():
     ctx.profile_enable(False)
     alg = 0
     for step in range(args.warmup, total_steps):
-        alg += sum(algorithmic_latent_bytes(w, reuse, widths, w.batch, w.n_cached + step + 1, lat_elem, row_meta))
+        n_rows = w.n_cached + step + (0 if args.variant == "exact" else 1)
+        if seq_lens is not None:                      # ragged: bytes of the rows each sequence really reads
+            alg += sum(algorithmic_latent_bytes(w, reuse, widths, 1, int(seq_lens.sum().item()), lat_elem, row_meta))
+        else:
+            alg += sum(algorithmic_latent_bytes(w, reuse, widths, w.batch, n_rows, lat_elem, row_meta))
     achieved = alg / (attend_ms * 1e-3) / 1e9
     plan = ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq)
     traffic = None
     # HBM bytes per launch from the committed rocprofv3 counter summary of this same workload
     tpath = os.path.join(ROOT, "profiles", "attend_mfma_long_context_pmc.md")
-    if os.path.exists(tpath) and args.workload == 4 and args.latent == "dtype" and not (args.batch or args.cached or args.no_reuse or args.policy):
+    if os.path.exists(tpath) and args.workload == 4 and args.latent == "dtype" and args.variant == "cache" and not (args.batch or args.cached or args.no_reuse or args.policy):
         import re
         m = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tpath).read())
         traffic = float(m.group(1)) if m else None
@@ -278,7 +299,7 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic" if args.fill == "encode" else "synthetic (random latents, profiling fill)",
         "config": {"workload": w.name, "batch": w.batch, "cached_tokens": w.n_cached, "layers": w.n_layers,
-                   "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_head": w.d_head, "latent": w.latent, "latent_format": args.latent,
+                   "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_head": w.d_head, "latent": w.latent, "latent_format": args.latent, "variant": args.variant,
                    "reuse": w.reuse, "policy": w.policy, "reused_head_fraction": float(reuse[1:].mean()) if w.n_layers > 1 else 0.0,
                    "splits": plan.n_splits, "mfma": bool(plan.uses_mfma), "prefill_s": t_fill},
         "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if plan.uses_mfma else "attend_generic_kernel",

@@ -200,6 +200,35 @@ int kvcar_decode_attention(kvcar_ctx *ctx, int layer, const void *q, void *out,
                            void *stream);
 
 /*
+ * Extensions of a decode step.  All pointers may be NULL (then the call equals the plain one).
+ *   seq_lens  dev int32 [batch]: per-sequence context length (ragged batch); sequence b attends over
+ *             its first min(seq_lens[b], n_ctx) cached rows.  n_ctx stays the upper bound the launch
+ *             is sized for.  A length of 0 is allowed only together with k_cur / v_cur.
+ *   k_cur, v_cur  dev [batch, H_kv * d_head] in the model dtype, both or neither: the paper's form of
+ *             the step ("Network Architecture", 2nd paragraph): the decoded rows of the cached tokens
+ *             are concatenated with the current token's exact key and value vectors, so attention
+ *             runs over the cached rows plus this one row, which never passed the autoencoder.
+ *             Column block g holds the vector KV head g of this layer uses (for a reused head: the
+ *             source layer's).  With these, n_ctx = 0 (nothing cached yet) is accepted.
+ */
+typedef struct {
+    const int32_t *seq_lens;
+    const void *k_cur;
+    const void *v_cur;
+} kvcar_step_ext;
+
+/* kvcar_decode_attention with the extensions above.  Same arguments, errors and workspace; ERR_ARG
+ * if only one of k_cur / v_cur is given or a pointer is misaligned. */
+int kvcar_decode_attention_ex(kvcar_ctx *ctx, int layer, const void *q, void *out, int batch, int n_ctx,
+                              const kvcar_step_ext *ext, void *workspace, size_t workspace_bytes, void *stream);
+
+/* kvcar_encode_append for a ragged batch: sequence b's t_new rows land at positions
+ * [positions[b], positions[b] + t_new) (positions: dev int32 [batch]).  The caller guarantees
+ * positions[b] + t_new <= max_seq (device data is not checked). */
+int kvcar_encode_append_at(kvcar_ctx *ctx, int layer, const void *k_new, const void *v_new, int batch,
+                           const int32_t *positions, int t_new, void *stream);
+
+/*
  * What kvcar_decode_attention would launch for (layer, batch, n_ctx) under the current maps,
  * autoencoders and tuning.  A "group" is the set of query heads of the layer that read the same
  * (K source layer, V source layer); each distinct source's latent rows are streamed once per group.

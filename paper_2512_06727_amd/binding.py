@@ -41,6 +41,10 @@ class Tuning(C.Structure):
     _fields_ = [("n_splits", C.c_int), ("force_generic", C.c_int), ("tile_order", C.c_int), ("no_fuse", C.c_int), ("wg_waves", C.c_int), ("reserved", C.c_int * 3)]
 
 
+class StepExt(C.Structure):
+    _fields_ = [("seq_lens", C.c_void_p), ("k_cur", C.c_void_p), ("v_cur", C.c_void_p)]
+
+
 class PlanInfo(C.Structure):
     _fields_ = [("uses_mfma", C.c_int), ("n_groups", C.c_int), ("n_splits", C.c_int), ("n_launches", C.c_int), ("fused", C.c_int),
                 ("workspace_bytes", C.c_size_t), ("latent_bytes", C.c_size_t)]
@@ -60,6 +64,9 @@ SYMBOLS = {
     "kvcar_encode_append": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "kvcar_decode_attention": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
                                          C.c_size_t, C.c_void_p]),
+    "kvcar_decode_attention_ex": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(StepExt), C.c_void_p,
+                                            C.c_size_t, C.c_void_p]),
+    "kvcar_encode_append_at": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]),
     "kvcar_describe_plan": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(PlanInfo)]),
     "kvcar_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "kvcar_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_long)]),
@@ -200,6 +207,18 @@ class Context:
 
     def encode_append(self, layer: int, k_new, v_new, batch: int, pos0: int, t_new: int):
         self._check(lib().kvcar_encode_append(self._h, layer, _ptr(k_new), _ptr(v_new), batch, pos0, t_new, _stream()))
+
+    def encode_append_at(self, layer: int, k_new, v_new, batch: int, positions, t_new: int):
+        """positions: int32 device tensor [batch]."""
+        self._check(lib().kvcar_encode_append_at(self._h, layer, _ptr(k_new), _ptr(v_new), batch, _ptr(positions), t_new, _stream()))
+
+    def decode_attention_ex(self, layer: int, q, out, batch: int, n_ctx: int, workspace, seq_lens=None, k_cur=None, v_cur=None):
+        """seq_lens: int32 device tensor [batch] or None; k_cur, v_cur: [batch, D_kv] tensors or None."""
+        nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        ext = StepExt(None if seq_lens is None else seq_lens.data_ptr(), None if k_cur is None else k_cur.data_ptr(),
+                      None if v_cur is None else v_cur.data_ptr())
+        self._check(lib().kvcar_decode_attention_ex(self._h, layer, _ptr(q), _ptr(out), batch, n_ctx, C.byref(ext), _ptr(workspace),
+                                                    nbytes, _stream()))
 
     def decode_attention(self, layer: int, q, out, batch: int, n_ctx: int, workspace):
         nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()

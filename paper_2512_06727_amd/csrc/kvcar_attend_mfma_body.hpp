@@ -226,7 +226,9 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     // Workgroup tiles (4 wave tiles = 128 tokens each) of this split.  tile_order 0: a contiguous
     // token range per split; 1: tiles dealt round-robin over the splits, so that workgroups running
     // at the same time read neighbouring addresses.
-    const int wg_tiles = (p->n_ctx + kWaveTile * NW - 1) / (kWaveTile * NW);
+    // context length of this sequence (ragged batches pass one per sequence)
+    const int n_ctx = p->seq_lens ? min(p->seq_lens[b], p->n_ctx) : p->n_ctx;
+    const int wg_tiles = (n_ctx + kWaveTile * NW - 1) / (kWaveTile * NW);
     int j0, j1, jstep;
     if (p->tile_order == 0) {
         const int per_split = (wg_tiles + p->n_splits - 1) / p->n_splits;
@@ -259,13 +261,13 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     Stage stage[PF];
     auto issue = [&](Stage& sg, int j) {
         const int t0 = (j * NW + wave) * kWaveTile;
-        const int nv = max(0, min(kWaveTile, p->n_ctx - t0));
+        const int nv = max(0, min(kWaveTile, n_ctx - t0));
         load_tile<NL>(sg.k, zk + (size_t)t0 * rk * EB, nlk, nv * cprk, nv == kWaveTile, lane);
         if constexpr (G::kPrefetch) load_tile<NL>(sg.v, zv + (size_t)t0 * rv * EB, nlv, nv * cprv, nv == kWaveTile, lane);
         if constexpr (kI8) {
             const int tok = t0 + (lane & 31);
             sg.m = u32x2_t{0x3f800000u, 0u};                      // rows past the context: scale 1, zero point 0
-            if (tok < p->n_ctx) sg.m = *reinterpret_cast<const u32x2_t*>(mrow + tok);
+            if (tok < n_ctx) sg.m = *reinterpret_cast<const u32x2_t*>(mrow + tok);
         }
     };
     if constexpr (G::kPrefetch) {                  // first tiles in flight while the queries are prepared
@@ -385,7 +387,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
 
     auto tile = [&](Stage& sg, int j) -> bool {
         const int t0 = (j * NW + wave) * kWaveTile;
-        const int nv = min(kWaveTile, p->n_ctx - t0);
+        const int nv = min(kWaveTile, n_ctx - t0);
         if (nv <= 0) return false;   // wave tile past the context: only in the last workgroup tile, the last one visited
 
         if constexpr (!G::kPrefetch) issue(sg, j);
@@ -627,7 +629,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             if (wave == w) {
 #pragma unroll
                 for (int nb = 0; nb < NHB; ++nb) {
-                    const float sc = f_own[nb] / l_all[nb];
+                    const float sc = l_all[nb] > 0.f ? f_own[nb] / l_all[nb] : 0.f;     // an empty context leaves the bias
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb) {
                         float* dst = olat + (size_t)(nb * 16 + l16) * ostride + 16 * mb + 4 * lg;

@@ -184,7 +184,8 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
         for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    const int tiles = (p.n_ctx + kMlpTile - 1) / kMlpTile;
+    const int n_ctx = p.seq_lens ? min(p.seq_lens[b], p.n_ctx) : p.n_ctx;      // ragged batches: one length per sequence
+    const int tiles = (n_ctx + kMlpTile - 1) / kMlpTile;
     const int per_split = (tiles + p.n_splits - 1) / p.n_splits;
     const int j0 = split * per_split;
     const int j1 = min(tiles, j0 + per_split);
@@ -195,7 +196,7 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
     u32x4_t stk[NLD], stv[NLD];
     auto issue = [&](int j) {
         const int t0 = j * kMlpTile;
-        const int valid = max(0, min(kMlpTile, p.n_ctx - t0)) * (R / 8);
+        const int valid = max(0, min(kMlpTile, n_ctx - t0)) * (R / 8);
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int f = i * 256 + tid;
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
     if (j0 < j1) issue(j0);
 
     for (int j = j0; j < j1; ++j) {
-        const int nv = min(kMlpTile, p.n_ctx - j * kMlpTile);
+        const int nv = min(kMlpTile, n_ctx - j * kMlpTile);
         // ---- park the tile (all threads), prefetch the next ---------------------------------------
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {

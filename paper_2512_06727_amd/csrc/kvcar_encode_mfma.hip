@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
         const int t = tbase + v;
         row_ok[v] = t < n_tok;
         const int b = t / p.t_new, tt = t - b * p.t_new;
-        row_off[v] = ((size_t)b * p.max_seq + p.pos0 + tt) * s.r;
+        row_off[v] = ((size_t)b * p.max_seq + (p.positions && row_ok[v] ? p.positions[b] : p.pos0) + tt) * s.r;
     }
     if (s.meta) {
         // ---- int8 latents: a token's row lies in the 16 lanes of its quarter (columns 16 nb + l16) -------

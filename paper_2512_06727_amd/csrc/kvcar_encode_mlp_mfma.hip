@@ -225,7 +225,7 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
             const int t = tbase + 8 * (v >> 2) + 4 * h + (v & 3);
             if (t >= n_tok) continue;
             const int b = t / p.t_new, tt = t - b * p.t_new;
-            const size_t row = (size_t)b * p.max_seq + p.pos0 + tt;
+            const size_t row = (size_t)b * p.max_seq + (p.positions ? p.positions[b] : p.pos0) + tt;
 #pragma unroll
             for (int nb = 0; nb < NBZ; ++nb) z8[row * r + 32 * nb + l32] = quant_code(accz[nb][v], qp);
             if (l32 == 0) static_cast<RowMeta*>(s.meta)[row] = quant_meta(qp);
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
         const int t = tbase + 8 * (v >> 2) + 4 * h + (v & 3);
         if (t >= n_tok) continue;
         const int b = t / p.t_new, tt = t - b * p.t_new;
-        const size_t row_off = ((size_t)b * p.max_seq + p.pos0 + tt) * r;
+        const size_t row_off = ((size_t)b * p.max_seq + (p.positions ? p.positions[b] : p.pos0) + tt) * r;
 #pragma unroll
         for (int nb = 0; nb < NBZ; ++nb) z[row_off + 32 * nb + l32] = EMma<E>::to16(accz[nb][v] + b2v[nb]);
     }

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void encode_generic_kernel(EncodeParams p) {
         if (s.meta) { zs[t * s.r + c] = a; continue; }
         const int tok = tok0 + t;
         const int b = tok / p.t_new, tt = tok % p.t_new;
-        Elem<E>::store(s.z, ((size_t)b * p.max_seq + p.pos0 + tt) * s.r + c, a);
+        Elem<E>::store(s.z, ((size_t)b * p.max_seq + (p.positions ? p.positions[b] : p.pos0) + tt) * s.r + c, a);
     }
     if (s.meta == nullptr) return;
 
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void encode_generic_kernel(EncodeParams p) {
     const QuantParams qp = quant_params(mn, mx);
     const int tok = tok0 + t;
     const int b = tok / p.t_new, tt = tok % p.t_new;
-    const size_t row = (size_t)b * p.max_seq + p.pos0 + tt;
+    const size_t row = (size_t)b * p.max_seq + (p.positions ? p.positions[b] : p.pos0) + tt;
     signed char* codes = static_cast<signed char*>(s.z) + row * s.r;
     for (int c = j; c < s.r; c += 32) codes[c] = quant_code(zr[c], qp);
     if (j == 0) static_cast<RowMeta*>(s.meta)[row] = quant_meta(qp);
@@ -201,6 +201,7 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(AttendParams p) {
     const int split = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x;
     const int ns = g.n_slots, ck = g.k.c, cv = g.v.c;
+    const int n_ctx = p.seq_lens ? min(p.seq_lens[b], p.n_ctx) : p.n_ctx;
     int zr = 0;
     if (g.k.w1) zr = g.k.r;
     if (g.v.w1 && g.v.r > zr) zr = g.v.r;
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(AttendParams p) {
     const int n_out = ns * cv;
 
     // contiguous token range of this split, in whole tiles
-    const int tiles = (p.n_ctx + kGenericTile - 1) / kGenericTile;
+    const int tiles = (n_ctx + kGenericTile - 1) / kGenericTile;
     const int tiles_per = (tiles + p.n_splits - 1) / p.n_splits;
     const int tile0 = split * tiles_per;
     const int tile1 = min(tiles, tile0 + tiles_per);
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(AttendParams p) {
 
     for (int tile = tile0; tile < tile1; ++tile) {
         const int t0 = tile * kGenericTile;
-        const int nt = min(kGenericTile, p.n_ctx - t0);
+        const int nt = min(kGenericTile, n_ctx - t0);
         load_rows<E>(g.k, rk, zrow, b, t0, nt, p.max_seq);
         load_rows<E>(g.v, rv, zrow, b, t0, nt, p.max_seq);
         __syncthreads();
@@ -294,6 +295,10 @@ hipError_t launch_attend_generic(const AttendParams& p, int dtype, hipStream_t s
 // split merge + epilogue: one workgroup per (sequence, group, slot)
 //   M = max_i m_i,  L = sum_i l_i 2^(m_i-M),  o_lat = sum_i o_i 2^(m_i-M) / L
 //   out[b, head, k] = sum_c o_lat[c] Wl_V[c, col+k] + bl_V[col+k]   rounded once to dtype
+// With the current token's exact row ("Network Architecture", 2nd paragraph: the decoded rows are
+// concatenated with the current key and value vectors) one more softmax term joins the merge:
+//   s = scale q . k_cur[head],  p = 2^(s-M'),  M' = max(M, s),  L' = L 2^(M-M') + p
+//   out = ((L 2^(M-M')) (o_lat W + b) + p v_cur[head]) / L'
 // ---------------------------------------------------------------------------------------------
 template <typename E>
 __global__ __launch_bounds__(64) void combine_kernel(AttendParams p) {
@@ -311,7 +316,26 @@ __global__ __launch_bounds__(64) void combine_kernel(AttendParams p) {
         const float m_i = base[(size_t)i * p.part_stride];
         L += base[(size_t)i * p.part_stride + 1] * (m_i == -INFINITY ? 0.f : exp2f(m_i - M));
     }
-    const float inv = 1.f / L;
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    float w_cached = 1.f, w_cur = 0.f;                 // weights of the cached part and of the exact current row
+    const int kvh = g.q_head[s] / p.gq;
+    if (p.k_cur) {
+        // the bias of the last K decoder layer shifts every cached score of the head by q . b and was left
+        // out of them (it cancels among cached rows): the exact row's score is lowered by it instead
+        float d = 0.f;
+        for (int k = tid; k < p.d_head; k += 64)
+            d = fmaf(Elem<E>::load(p.q, ((size_t)b * p.n_q_heads + g.q_head[s]) * p.d_head + k),
+                     Elem<E>::load(p.k_cur, ((size_t)b * (p.n_q_heads / p.gq) + kvh) * p.d_head + k) -
+                         (g.k.bl ? Elem<E>::load(g.k.bl, g.k_col[s] + k) : 0.f), d);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off);
+        const float s_cur = d * p.scale_log2e;
+        const float M2 = fmaxf(M, s_cur);
+        const float lc = M == -INFINITY ? 0.f : L * exp2f(M - M2);
+        const float pc = exp2f(s_cur - M2);
+        w_cached = lc / (lc + pc);
+        w_cur = pc / (lc + pc);
+    }
     for (int c = tid; c < cv; c += 64) {
         float a = 0.f;
         for (int i = 0; i < p.n_splits; ++i) {
@@ -325,6 +349,7 @@ __global__ __launch_bounds__(64) void combine_kernel(AttendParams p) {
     for (int k = tid; k < p.d_head; k += 64) {
         float a = g.v.bl ? Elem<E>::load(g.v.bl, col + k) : 0.f;
         for (int c = 0; c < cv; ++c) a = fmaf(olat[c], Elem<E>::load(g.v.wl, (size_t)c * g.v.in_width + col + k), a);
+        if (p.v_cur) a = w_cached * a + w_cur * Elem<E>::load(p.v_cur, ((size_t)b * (p.n_q_heads / p.gq) + kvh) * p.d_head + k);
         Elem<E>::store(p.out, ((size_t)b * p.n_q_heads + g.q_head[s]) * p.d_head + k, a);
     }
 }

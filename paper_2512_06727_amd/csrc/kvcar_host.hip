@@ -416,7 +416,12 @@ int kvcar_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_ctx, size_t* by
     return KVCAR_OK;
 }
 
-int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, int pos0, int t_new, void* stream) {
+}  // extern "C"
+
+namespace {
+
+int encode_impl(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, int pos0, const int32_t* positions, int t_new,
+                void* stream) {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     const kvcar_config& c = ctx->cfg;
@@ -426,6 +431,7 @@ int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void
         return fail(ctx, KVCAR_ERR_CAPACITY, "append of %d tokens at %d for batch %d exceeds max_seq %d / max_batch %d", t_new, pos0, batch, c.max_seq, c.max_batch);
     EncodeParams p{};
     p.batch = batch; p.t_new = t_new; p.pos0 = pos0; p.max_seq = c.max_seq; p.d_kv = c.n_kv_heads * c.d_head; p.d_head = c.d_head;
+    p.positions = positions;
     const void* xs[2] = {k_new, v_new};
     bool any = false;
     for (int which = 0; which < 2; ++which) {
@@ -455,17 +461,22 @@ int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void
     return KVCAR_OK;
 }
 
-int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, void* workspace,
-                           size_t workspace_bytes, void* stream) {
+int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, const kvcar_step_ext* ext, void* workspace,
+                size_t workspace_bytes, void* stream) {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     const kvcar_config& c = ctx->cfg;
     if (!q || !out || !aligned16(q) || !aligned16(out)) return fail(ctx, KVCAR_ERR_ARG, "q / out null or misaligned");
-    if (batch < 1 || batch > c.max_batch || n_ctx < 1 || n_ctx > c.max_seq)
-        return fail(ctx, KVCAR_ERR_CAPACITY, "batch %d / n_ctx %d outside [1,%d] / [1,%d]", batch, n_ctx, c.max_batch, c.max_seq);
+    const bool exact = ext && (ext->k_cur || ext->v_cur);
+    if (exact && (!ext->k_cur || !ext->v_cur || !aligned16(ext->k_cur) || !aligned16(ext->v_cur)))
+        return fail(ctx, KVCAR_ERR_ARG, "k_cur and v_cur must both be given, 16-byte aligned");
+    if (ext && ext->seq_lens && (reinterpret_cast<uintptr_t>(ext->seq_lens) & 3u)) return fail(ctx, KVCAR_ERR_ARG, "seq_lens misaligned");
+    if (batch < 1 || batch > c.max_batch || n_ctx < (exact ? 0 : 1) || n_ctx > c.max_seq)
+        return fail(ctx, KVCAR_ERR_CAPACITY, "batch %d / n_ctx %d outside [1,%d] / [%d,%d]", batch, n_ctx, c.max_batch, exact ? 0 : 1, c.max_seq);
     Plan plan;
-    rc = build_plan(ctx, layer, batch, n_ctx, plan);
+    rc = build_plan(ctx, layer, batch, std::max(1, n_ctx), plan);
     if (rc) return rc;
+    if (exact) plan.fused = false;        // the exact current row joins the merge in the epilogue kernel
     if (!workspace || !aligned16(workspace)) return fail(ctx, KVCAR_ERR_ARG, "workspace null or misaligned");
     if (workspace_bytes < plan.total_bytes)
         return fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, plan.total_bytes);
@@ -482,6 +493,10 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
         p.n_q_heads = c.n_q_heads; p.d_head = c.d_head; p.max_seq = c.max_seq;
         p.qt_stride = plan.qt_stride; p.part_stride = plan.part_stride;
         p.scale_log2e = ctx->scale * kLog2e;
+        p.gq = c.n_q_heads / c.n_kv_heads;
+        p.seq_lens = ext ? ext->seq_lens : nullptr;
+        p.k_cur = exact ? ext->k_cur : nullptr;
+        p.v_cur = exact ? ext->v_cur : nullptr;
         p.tile_order = ctx->tun.tile_order == 2 ? 1 : 0;
         // fused: 1 = four waves per workgroup; 2 = eight, when the launch has no more workgroups than compute units
         const bool w8 = ctx->tun.wg_waves == 8 || (ctx->tun.wg_waves == 0 && batch * p.n_groups <= ctx->n_cu);
@@ -508,6 +523,31 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
         if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
     }
     return KVCAR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, int pos0, int t_new, void* stream) {
+    return encode_impl(ctx, layer, k_new, v_new, batch, pos0, nullptr, t_new, stream);
+}
+
+int kvcar_encode_append_at(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, const int32_t* positions, int t_new,
+                           void* stream) {
+    if (!ctx) return KVCAR_ERR_ARG;
+    if (!positions || (reinterpret_cast<uintptr_t>(positions) & 3u)) return fail(ctx, KVCAR_ERR_ARG, "positions null or misaligned");
+    return encode_impl(ctx, layer, k_new, v_new, batch, 0, positions, t_new, stream);
+}
+
+int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    return decode_impl(ctx, layer, q, out, batch, n_ctx, nullptr, workspace, workspace_bytes, stream);
+}
+
+int kvcar_decode_attention_ex(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, const kvcar_step_ext* ext,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+    return decode_impl(ctx, layer, q, out, batch, n_ctx, ext, workspace, workspace_bytes, stream);
 }
 
 int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, kvcar_plan_info* out) {

@@ -65,6 +65,10 @@ struct AttendParams {
     int tile_order;       // MFMA kernel: 0 = contiguous token range per split, 1 = tiles dealt round-robin
     int fused;            // MFMA kernel: absorbed queries and output epilogue computed inside (single split);
                           // 2 = the eight-wave variant of that kernel
+    int gq;               // query heads per KV head
+    const int* seq_lens;  // per-sequence context length [batch] (ragged batch), or null: n_ctx for all
+    const void* k_cur;    // exact key / value row of the current token [batch, H_kv * d_head], attended as one
+    const void* v_cur;    //   more row after the cached ones; or both null
 };
 
 struct EncodeSide {
@@ -81,6 +85,7 @@ struct EncodeSide {
 struct EncodeParams {
     EncodeSide s[2];
     int batch, t_new, pos0, max_seq, d_kv, d_head;
+    const int* positions; // per-sequence first position [batch] (ragged batch), or null: pos0 for all
 };
 
 // Launchers (defined next to their kernels). All enqueue on `stream` and return hipGetLastError().

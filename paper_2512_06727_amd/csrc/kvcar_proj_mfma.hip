@@ -170,6 +170,7 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
     // phase 1a: per-row merge weights.  All (row, split) pairs fetch their m and l at once (a serial
     // loop over the splits would pay one memory latency per split), then one thread per row reduces.
     float* ml = wts + (size_t)rows_per_wg * ns;                         // [rows_per_wg][ns][2]
+    float* ab = ml + 2 * (size_t)rows_per_wg * ns;                      // [rows_per_wg][2]: weights of bias and of the exact current row
     for (int idx = threadIdx.x; idx < rows_per_wg * ns; idx += 256) {
         const int r = idx / ns, k = idx - r * ns;
         const int row = wg_row0 + r;
@@ -184,9 +185,26 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
         ml[2 * idx + 1] = l_k;
     }
     __syncthreads();
+    // With the current token's exact row (k_cur, v_cur) one more softmax term joins the merge:
+    // s = scale q . k_cur[head], weight 2^(s-M); the output is (L (o W + b) + 2^(s-M) v_cur) / (L + 2^(s-M)).
     for (int r = threadIdx.x; r < rows_per_wg; r += 256) {
         float M = -INFINITY;
         for (int k = 0; k < ns; ++k) M = fmaxf(M, ml[2 * (r * ns + k)]);
+        float s_cur = -INFINITY;
+        const int row = wg_row0 + r;
+        if (p.k_cur && row < rows) {
+            const int b = row / len, i = row - b * len;
+            const int head = g.q_head[s0 + i];
+            const size_t qo = ((size_t)b * p.n_q_heads + head) * dh, ko = ((size_t)b * (p.n_q_heads / p.gq) + head / p.gq) * dh;
+            float d = 0.f;
+            // the K decoder's last-layer bias was left out of the cached scores (it cancels among them):
+            // the exact row's score is lowered by q . b instead
+            const int kcol = g.k_col[s0 + i];
+            for (int k = 0; k < dh; ++k)
+                d = fmaf(Elem<E>::load(p.q, qo + k), Elem<E>::load(p.k_cur, ko + k) - (g.k.bl ? Elem<E>::load(g.k.bl, kcol + k) : 0.f), d);
+            s_cur = d * p.scale_log2e;
+            M = fmaxf(M, s_cur);
+        }
         float L = 0.f;
         for (int k = 0; k < ns; ++k) {
             const float m_k = ml[2 * (r * ns + k)];
@@ -194,8 +212,11 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
             wts[r * ns + k] = e;
             L += ml[2 * (r * ns + k) + 1] * e;
         }
-        const float inv = L > 0.f ? 1.f / L : 0.f;
+        const float pc = s_cur == -INFINITY ? 0.f : exp2f(s_cur - M);
+        const float inv = L + pc > 0.f ? 1.f / (L + pc) : 0.f;
         for (int k = 0; k < ns; ++k) wts[r * ns + k] *= inv;
+        ab[2 * r] = p.k_cur ? L * inv : 1.f;
+        ab[2 * r + 1] = pc * inv;
     }
     __syncthreads();
     // phase 1b: merged, normalised latent sums
@@ -262,7 +283,8 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
     uint16_t* out = static_cast<uint16_t*>(p.out);
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        const int r = wg_row0 + row0 + 4 * lg + v;
+        const int rl = row0 + 4 * lg + v;
+        const int r = wg_row0 + rl;
         if (r >= rows) continue;
         const int b = r / len, i = r - b * len;
         const size_t base = ((size_t)b * p.n_q_heads + g.q_head[s0 + i]) * dh;
@@ -271,7 +293,9 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
             if (nb < nbo) {
                 const int k = nb * 16 + l16;
                 const float bias = g.v.bl ? Elem<E>::load(g.v.bl, col + k) : 0.f;
-                out[base + k] = PMma<E>::to16(acc[nb][v] + bias);
+                float y = acc[nb][v] + ab[2 * rl] * bias;
+                if (p.v_cur) y += ab[2 * rl + 1] * Elem<E>::load(p.v_cur, ((size_t)b * (p.n_q_heads / p.gq) + g.q_head[s0 + i] / p.gq) * dh + k);
+                out[base + k] = PMma<E>::to16(y);
             }
         }
     }
@@ -317,7 +341,7 @@ hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t str
     const int segs = max_segments(p, false, max_len);
     for (int i = 0; i < p.n_groups; ++i) rmax = p.g[i].v.c > rmax ? p.g[i].v.c : rmax;
     const int rows_per_wg = rmax <= 128 ? 64 : 16;
-    const size_t lds = (size_t)rmax * (2 * p.d_head + 32) + 1024 + (size_t)rows_per_wg * (rmax + 4 + 3 * p.n_splits) * sizeof(float);
+    const size_t lds = (size_t)rmax * (2 * p.d_head + 32) + 1024 + (size_t)rows_per_wg * (rmax + 4 + 3 * p.n_splits + 2) * sizeof(float);
     dim3 grid((p.batch * max_len + rows_per_wg - 1) / rows_per_wg, segs, p.n_groups);
     const int e = dtype == KVCAR_BF16 ? 0 : 1;
     auto kern = e == 0 ? combine_mfma_kernel<BF16, 8> : combine_mfma_kernel<F16, 8>;
