@@ -98,6 +98,66 @@ def cpu_baseline(w, reuse, budget_s: float):
                       f"{per_unit * 1e3:.1f} ms each, extrapolated to {w.n_layers} layers x {w.batch} sequences"}
 
 
+def bench_l1_distance(args):
+    """Secondary measurement: the reuse-map selection statistic (per-head mean L1 distance between the keys
+    of two adjacent layers) over the tokens of the chosen workload; HBM-bound, both tensors read once."""
+    import numpy as np
+    import torch
+    from oracle import kvcar_oracle as O
+    from paper_2512_06727_amd import binding, synth
+
+    w = synth.CONFIGS[args.workload]
+    if args.batch:
+        w = w.scaled(batch=args.batch)
+    if args.cached:
+        w = w.scaled(n_cached=args.cached)
+    dev, tdt = torch.device("cuda:0"), synth.TORCH_DTYPE[w.dtype]
+    n_tokens = w.batch * w.n_cached
+    chunk = max(1, (1 << 25) // (w.batch * w.d_kv))
+    xs = []
+    for layer in (0, 1):
+        parts = [synth.kv_tokens(w, layer, 0, 0, w.batch, c0, min(w.n_cached, c0 + chunk), device=dev).to(tdt) for c0 in range(0, w.n_cached, chunk)]
+        xs.append(torch.cat(parts, dim=1).reshape(n_tokens, w.d_kv).contiguous())
+    dist = torch.zeros(w.n_kv_heads, dtype=torch.float32, device=dev)
+    need = binding.C.c_size_t(0)
+    binding.lib().kvcar_head_l1_workspace_bytes(n_tokens, w.n_kv_heads, binding.C.byref(need))
+    ws = torch.empty(max(16, need.value), dtype=torch.uint8, device=dev)
+    run = lambda: binding.head_l1_distance(xs[0], xs[1], w.n_kv_heads, w.d_head, dist=dist, workspace=ws)
+    for _ in range(args.warmup):
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    nbytes = 2 * xs[0].numel() * xs[0].element_size()
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    probe = torch.zeros(1 << 32, dtype=torch.uint8, device=dev)
+    ceiling = binding.probe_read_bandwidth(probe, repeats=4)
+    del probe
+    # oracle on a bounded sample, and parity of the sample
+    n_s = min(n_tokens, 1 << 18)
+    a, b = xs[0][:n_s].float().cpu().double().numpy(), xs[1][:n_s].float().cpu().double().numpy()
+    t0 = time.perf_counter()
+    want = O.head_l1_distance(a, b, w.n_kv_heads, w.d_head)
+    t_cpu = time.perf_counter() - t0
+    got = binding.head_l1_distance(xs[0][:n_s], xs[1][:n_s], w.n_kv_heads, w.d_head).cpu().double().numpy()
+    print(json.dumps({
+        "metric": "reuse-selection L1 distance, tokens/s", "value": n_tokens / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "op": "head_l1_distance", "tokens": n_tokens, "kv_heads": w.n_kv_heads, "d_head": w.d_head},
+        "roofline": {"bound": "hbm", "kernel": "head_l1_partial_kernel", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": ms,
+                     "read_ceiling_GBs": ceiling, "frac_of_read_ceiling": gbs / ceiling},
+        "cpu_baseline": {"value": n_s / t_cpu, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                         "sample": f"first {n_s} tokens, {t_cpu:.2f} s; max relative difference GPU vs oracle on the sample {np.abs(got / want - 1).max():.2e}"},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -121,6 +181,8 @@ def main():
                     help="cache: append the new token, attend over the cache (default, the headline); exact: attend over the cached "
                          "rows plus the current token's exact K/V row (kvcar_decode_attention_ex), then append; ragged: per-sequence "
                          "context lengths drawn uniformly from [n_cached/2, n_cached]")
+    ap.add_argument("--op", default="decode", choices=["decode", "l1dist"],
+                    help="decode: the decode step (default, the headline); l1dist: the reuse-map selection statistic over the workload's tokens")
     ap.add_argument("--wg-waves", type=int, default=0, help="fused attention kernel: 0 automatic, 4 or 8 waves per workgroup")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -136,6 +198,8 @@ def main():
     from paper_2512_06727_amd.harness import Session
 
     binding.lib()
+    if args.op == "l1dist":
+        return bench_l1_distance(args)
     base = synth.CONFIGS[args.workload]
     total_steps = args.steps + args.warmup
     w = base.scaled(n_steps=total_steps)

@@ -255,6 +255,25 @@ int kvcar_profile_enable(kvcar_ctx *ctx, int enable);
 int kvcar_profile_read(kvcar_ctx *ctx, double *attend_ms, long *n_launches);
 
 /*
+ * Reuse-map selection statistic (Algorithm 2, steps 1-2; Methodology, the paragraph on key and value
+ * reuse: the L1 norm between heads of adjacent layers, averaged over mini-batches, is what the reuse
+ * threshold is applied to).  For two dev tensors [n_tokens, n_kv_heads * d_head] in `dtype` (the keys,
+ * or the values, of layer N-1 and of layer N for the same tokens):
+ *   dist[g] = mean over tokens t and components k < d_head of | x_cur[t, g, k] - x_prev[t, g, k] |
+ * written to dist (dev fp32 [n_kv_heads]); with accumulate != 0 the result is added to what dist holds,
+ * so that a caller sums mini-batches and divides by their number.  Choosing the threshold and filling
+ * kvcar_set_reuse_map stay with the caller.  The result does not depend on scheduling (fixed reduction
+ * order).  workspace: dev, 16-byte aligned, kvcar_head_l1_workspace_bytes bytes.  Stateless: no context.
+ * ERR_ARG on null / misaligned pointers or n_tokens == 0, ERR_SHAPE if a row is not a multiple of
+ * 16 bytes or d_head is not a multiple of the elements in 16 bytes, ERR_UNSUPPORTED on an unknown
+ * dtype or more than 1024 heads, ERR_WORKSPACE, ERR_HIP.
+ */
+int kvcar_head_l1_workspace_bytes(size_t n_tokens, int n_kv_heads, size_t *bytes);
+int kvcar_head_l1_distance(const void *x_prev, const void *x_cur, int dtype, size_t n_tokens, int n_kv_heads,
+                           int d_head, int accumulate, float *dist, void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/*
  * Read-only streaming ceiling of the device: a kernel with no arithmetic reads `bytes` bytes of
  * `dev_buf` (device memory, 16-byte aligned, bytes a multiple of 16) `repeats` times with 16-byte
  * non-temporal loads, one grid-stride sweep per repeat, timed with HIP events on `stream`, for a

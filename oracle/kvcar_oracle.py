@@ -331,6 +331,19 @@ class KVCAROracle:
 
 
 # --------------------------------------------------------------------------
+# reuse-map selection statistic (Algorithm 2, steps 1-2)
+# --------------------------------------------------------------------------
+def head_l1_distance(x_prev: np.ndarray, x_cur: np.ndarray, n_kv_heads: int, d_head: int) -> np.ndarray:
+    """Mean L1 distance between the same head of adjacent layers over a batch of tokens:
+    x_prev, x_cur [n_tokens, H_kv*d_head] are the keys (or the values) of layer N-1 and
+    layer N; returns [H_kv].  The paper averages this over mini-batches and applies an
+    empirical threshold to pick the heads that reuse the previous layer's tensor."""
+    a = np.asarray(x_prev, np.float64).reshape(-1, n_kv_heads, d_head)
+    b = np.asarray(x_cur, np.float64).reshape(-1, n_kv_heads, d_head)
+    return np.abs(b - a).mean(axis=(0, 2))
+
+
+# --------------------------------------------------------------------------
 # memory accounting (Eq. 3 and the savings columns of Tables 2-4)
 # --------------------------------------------------------------------------
 def kv_cache_bytes(bytes_per_elem: int, n_layers: int, d_model: int, seq_len: int, batch: int) -> int:

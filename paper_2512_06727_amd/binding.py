@@ -70,6 +70,9 @@ SYMBOLS = {
     "kvcar_describe_plan": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(PlanInfo)]),
     "kvcar_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "kvcar_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_long)]),
+    "kvcar_head_l1_workspace_bytes": (C.c_int, [C.c_size_t, C.c_int, C.POINTER(C.c_size_t)]),
+    "kvcar_head_l1_distance": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                         C.c_size_t, C.c_void_p]),
     "kvcar_probe_read_bandwidth": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.POINTER(C.c_double)]),
     "kvcar_status_string": (C.c_char_p, [C.c_int]),
     "kvcar_last_error": (C.c_char_p, [C.c_void_p]),
@@ -107,6 +110,27 @@ def _ptr(t) -> Optional[int]:
 def _stream() -> C.c_void_p:
     import torch
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def head_l1_distance(x_prev, x_cur, n_kv_heads: int, d_head: int, dist=None, accumulate: bool = False, workspace=None):
+    """kvcar_head_l1_distance on two [n_tokens, n_kv_heads * d_head] tensors; returns the fp32 tensor
+    dist [n_kv_heads] (allocated here unless given).  Marshalling only."""
+    import torch
+    n_tokens = x_prev.numel() // (n_kv_heads * d_head)
+    dt = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}[x_prev.dtype]
+    need = C.c_size_t(0)
+    st = lib().kvcar_head_l1_workspace_bytes(n_tokens, n_kv_heads, C.byref(need))
+    if st != 0:
+        raise KVCARError(st, "kvcar_head_l1_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(max(need.value, 16), dtype=torch.uint8, device=x_prev.device)
+    if dist is None:
+        dist = torch.zeros(n_kv_heads, dtype=torch.float32, device=x_prev.device)
+    st = lib().kvcar_head_l1_distance(_ptr(x_prev), _ptr(x_cur), dt, n_tokens, n_kv_heads, d_head, 1 if accumulate else 0, _ptr(dist),
+                                      _ptr(workspace), workspace.numel(), _stream())
+    if st != 0:
+        raise KVCARError(st, "kvcar_head_l1_distance")
+    return dist
 
 
 def probe_read_bandwidth(buf, repeats: int = 8) -> float:

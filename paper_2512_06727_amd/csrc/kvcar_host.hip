@@ -594,6 +594,36 @@ int kvcar_profile_read(kvcar_ctx* ctx, double* attend_ms, long* n_launches) {
     return KVCAR_OK;
 }
 
+static int device_cu_count() {
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    return n_cu;
+}
+
+int kvcar_head_l1_workspace_bytes(size_t n_tokens, int n_kv_heads, size_t* bytes) {
+    if (!bytes || n_tokens == 0 || n_kv_heads < 1) return KVCAR_ERR_ARG;
+    *bytes = (size_t)kvcar::head_l1_workgroups(n_tokens, device_cu_count()) * n_kv_heads * sizeof(float);
+    return KVCAR_OK;
+}
+
+int kvcar_head_l1_distance(const void* x_prev, const void* x_cur, int dtype, size_t n_tokens, int n_kv_heads, int d_head, int accumulate,
+                           float* dist, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!x_prev || !x_cur || !dist || !workspace || n_tokens == 0 || n_kv_heads < 1 || d_head < 1) return KVCAR_ERR_ARG;
+    if (!aligned16(x_prev) || !aligned16(x_cur) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(dist) & 3u)) return KVCAR_ERR_ARG;
+    if (dtype != KVCAR_F32 && dtype != KVCAR_F16 && dtype != KVCAR_BF16) return KVCAR_ERR_UNSUPPORTED;
+    if (n_kv_heads > 1024) return KVCAR_ERR_UNSUPPORTED;
+    const int el = dtype == KVCAR_F32 ? 4 : 8;                 // elements per 16-byte chunk
+    if (d_head % el) return KVCAR_ERR_SHAPE;                   // a chunk must lie inside one head
+    const int n_wg = kvcar::head_l1_workgroups(n_tokens, device_cu_count());
+    if (workspace_bytes < (size_t)n_wg * n_kv_heads * sizeof(float)) return KVCAR_ERR_WORKSPACE;
+    hipError_t e = kvcar::launch_head_l1(x_prev, x_cur, dtype, n_tokens, n_kv_heads, d_head, accumulate, dist, static_cast<float*>(workspace), n_wg,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KVCAR_OK : KVCAR_ERR_HIP;
+}
+
 int kvcar_probe_read_bandwidth(const void* dev_buf, size_t bytes, int repeats, void* stream, double* gb_per_s) {
     if (!dev_buf || !gb_per_s || bytes < 16 || bytes % 16 || repeats < 1 || (reinterpret_cast<uintptr_t>(dev_buf) & 15)) return KVCAR_ERR_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);

@@ -120,6 +120,11 @@ hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stre
 bool attend_i8_mfma_supported(const AttendParams& p, int dtype);
 hipError_t launch_attend_i8_mfma(const AttendParams& p, int dtype, hipStream_t stream);
 
+// Reuse-map selection statistic: per-head mean L1 distance between two [n_tokens, H_kv * d_head] tensors.
+int head_l1_workgroups(size_t n_tokens, int n_cu);
+hipError_t launch_head_l1(const void* prev, const void* cur, int dtype, size_t n_tokens, int n_kv_heads, int d_head, int accumulate, float* dist,
+                          float* partial, int n_wg, hipStream_t stream);
+
 hipError_t launch_stream_read(const void* src, size_t bytes, int n_blocks, int block, unsigned* sink, hipStream_t stream);
 
 }  // namespace kvcar
