@@ -324,8 +324,8 @@ def main():
     plan = ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq)
     traffic = None
     # HBM bytes per launch from the committed rocprofv3 counter summary of this same workload
-    tpath = os.path.join(ROOT, "profiles", "attend_mfma_long_context_pmc.md")
-    if os.path.exists(tpath) and args.workload == 4 and args.latent == "dtype" and args.variant == "cache" and not (args.batch or args.cached or args.no_reuse or args.policy):
+    tpath = os.path.join(ROOT, "profiles", "attend_i8_mfma_long_context_pmc.md" if args.latent == "int8" else "attend_mfma_long_context_pmc.md")
+    if os.path.exists(tpath) and args.workload == 4 and args.variant == "cache" and not (args.batch or args.cached or args.no_reuse or args.policy):
         import re
         m = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tpath).read())
         traffic = float(m.group(1)) if m else None
@@ -366,7 +366,7 @@ def main():
                    "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_head": w.d_head, "latent": w.latent, "latent_format": args.latent, "variant": args.variant,
                    "reuse": w.reuse, "policy": w.policy, "reused_head_fraction": float(reuse[1:].mean()) if w.n_layers > 1 else 0.0,
                    "splits": plan.n_splits, "mfma": bool(plan.uses_mfma), "prefill_s": t_fill},
-        "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if plan.uses_mfma else "attend_generic_kernel",
+        "roofline": {"bound": "hbm", "kernel": ("attend_i8_mfma_r128_kernel" if args.latent == "int8" else "attend_mfma_kernel") if plan.uses_mfma else "attend_generic_kernel",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg / max(1, n_launch),
                      "avg_launch_ms": attend_ms / max(1, n_launch), "launches": n_launch,
