@@ -183,6 +183,7 @@ def main():
                          "context lengths drawn uniformly from [n_cached/2, n_cached]")
     ap.add_argument("--op", default="decode", choices=["decode", "l1dist"],
                     help="decode: the decode step (default, the headline); l1dist: the reuse-map selection statistic over the workload's tokens")
+    ap.add_argument("--no-fuse", action="store_true", help="run prologue / attention / merge as separate kernels")
     ap.add_argument("--wg-waves", type=int, default=0, help="fused attention kernel: 0 automatic, 4 or 8 waves per workgroup")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -216,7 +217,7 @@ def main():
     reuse = synth.reuse_map(w)
     elem = synth.DTYPE_BYTES[w.dtype]
 
-    ses = Session(w, reuse=reuse, n_splits=args.splits, tile_order=args.tile_order, latent_format=args.latent, wg_waves=args.wg_waves)
+    ses = Session(w, reuse=reuse, n_splits=args.splits, tile_order=args.tile_order, latent_format=args.latent, wg_waves=args.wg_waves, no_fuse=args.no_fuse)
     lat_elem, row_meta = (1, 8) if args.latent == "int8" else (elem, 0)
     dev, tdt = ses.dev, ses.tdt
     widths = [[ses.ae[n][which].latent for which in (0, 1)] for n in range(w.n_layers)]
