@@ -1,0 +1,51 @@
+"""A decode step captured as a HIP graph gives the eager result on every replay, with eager work and
+synchronisations of the program's own between the replays (the library records no memset nodes and
+allocates nothing, so its calls may be captured)."""
+import pytest
+import torch
+
+from paper_2512_06727_amd import synth
+from paper_2512_06727_amd.harness import Session
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("fmt,splits", [("dtype", 1), ("dtype", 3), ("int8", 1)])
+def test_graph_replays_match_eager(fmt, splits):
+    w = synth.CONFIGS[4].scaled(n_layers=3, batch=4, n_cached=200, n_steps=4)
+    ses = Session(w, latent_format=fmt, n_splits=splits)
+    ses.prefill(0, w.n_cached, chunk=128)
+    dev, tdt = ses.dev, ses.tdt
+    pos = w.n_cached
+    ks = [synth.kv_tokens(w, n, 0, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)]
+    vs = [synth.kv_tokens(w, n, 1, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)]
+    qs = [synth.queries(w, n, 0, device=dev, gain=10.0).to(tdt) for n in range(w.n_layers)]
+    outs = [torch.empty_like(q) for q in qs]
+    ses.ensure_workspace(w.batch, w.max_seq)
+
+    def step():
+        for n in range(w.n_layers):
+            ses.ctx.encode_append(n, ks[n], vs[n], w.batch, pos, 1)
+            ses.ctx.decode_attention(n, qs[n], outs[n], w.batch, pos + 1, ses.workspace)
+
+    step()                                        # eager reference (and first-call set-up of every kernel)
+    torch.cuda.synchronize()
+    want = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for replay in range(4):
+        for o in outs:
+            o.fill_(float("nan"))                 # eager work between replays: a replay must rewrite every output
+        scratch = torch.randn(1 << 16, device=dev).sum().item()      # and a library reduction with a host sync
+        assert scratch == scratch
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in range(w.n_layers):
+            assert torch.equal(outs[n], want[n]), f"replay {replay}, layer {n}"
