@@ -158,6 +158,83 @@ def bench_l1_distance(args):
     }))
 
 
+def capacity_check(args):
+    """Capacity leg (the analogue of the paper's maximum-sequence-length-before-OOM measurement, Results,
+    "System Evaluation"): allocate latent caches for as many cached tokens as fit in this GPU's free memory
+    (batch of the workload, context grown), fill them, run one decode step over the full context and
+    report what was allocated against what the uncompressed cache would need."""
+    import torch
+    from paper_2512_06727_amd import synth
+    from paper_2512_06727_amd.harness import Session
+
+    base = synth.CONFIGS[args.workload]
+    if args.policy:
+        base = base.scaled(policy=args.policy)
+    if args.no_reuse:
+        base = base.scaled(reuse="none")
+    reuse = synth.reuse_map(base)
+    elem = synth.DTYPE_BYTES[base.dtype]
+    lat_elem, row_meta = (1, 8) if args.latent == "int8" else (elem, 0)
+    probe = Session(base.scaled(batch=1, n_cached=1, n_steps=1), reuse=reuse, latent_format=args.latent)
+    widths = [[probe.ae[n][k].latent for k in (0, 1)] for n in range(base.n_layers)]
+    del probe
+    lat_tok = sum(r * lat_elem + (row_meta if r else 0) for pair in widths for r in pair)
+    full_tok = 2 * elem * base.n_layers * base.d_kv
+    free, total = torch.cuda.mem_get_info()
+    budget = int(free * args.capacity_fraction)
+    max_seq = budget // (lat_tok * base.batch) // 128 * 128
+    w = base.scaled(n_cached=max_seq - 1, n_steps=1)
+    t0 = time.perf_counter()
+    ses = Session(w, reuse=reuse, latent_format=args.latent)
+    for n, row in enumerate(ses.caches):                    # every row holds valid data
+        for which, c in enumerate(row):
+            if c is None:
+                continue
+            if args.latent == "int8":
+                codes, scale, zp = ses.quantized_view(n, which)
+                flat = codes.view(-1).view(torch.uint8)
+                for i in range(0, flat.numel(), 1 << 30):
+                    flat[i:i + (1 << 30)].random_(0, 256)
+                scale.fill_(127.5)
+                zp.zero_()
+            else:
+                for i in range(0, c.numel(), 1 << 29):
+                    c[i:i + (1 << 29)].normal_(0.0, 0.32)
+    torch.cuda.synchronize()
+    t_alloc = time.perf_counter() - t0
+    dev, tdt = ses.dev, ses.tdt
+    pos = w.n_cached
+    q = [torch.randn(w.batch, w.n_q_heads, w.d_head, device=dev).to(tdt) for _ in range(w.n_layers)]
+    k = [torch.randn(w.batch, 1, w.d_kv, device=dev).to(tdt) for _ in range(w.n_layers)]
+    v = [torch.randn(w.batch, 1, w.d_kv, device=dev).to(tdt) for _ in range(w.n_layers)]
+    outs = [torch.empty_like(x) for x in q]
+    ses.ensure_workspace(w.batch, w.max_seq)
+
+    def step():
+        for n in range(w.n_layers):
+            ses.ctx.encode_append(n, k[n], v[n], w.batch, pos, 1)
+            ses.ctx.decode_attention(n, q[n], outs[n], w.batch, pos + 1, ses.workspace)
+
+    step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3
+    finite = all(bool(torch.isfinite(o.float()).all()) for o in outs)
+    cache_bytes = sum(c.numel() * c.element_size() for row in ses.caches for c in row if c is not None)
+    tokens = w.batch * w.max_seq
+    print(json.dumps({
+        "metric": "cached tokens resident in HBM (capacity check)", "value": tokens, "unit": "tokens", "n_gpus": 1,
+        "higher_is_better": True, "dtype": w.dtype, "data": "synthetic (random latents)",
+        "config": {"workload": w.name, "batch": w.batch, "context": w.max_seq, "latent_format": args.latent, "policy": w.policy, "reuse": w.reuse},
+        "device_memory_bytes": total, "free_before_bytes": free, "latent_cache_bytes": cache_bytes,
+        "bytes_per_token_latent": lat_tok, "bytes_per_token_uncompressed": full_tok,
+        "uncompressed_cache_would_need_bytes": tokens * full_tok, "uncompressed_tokens_in_same_bytes": cache_bytes // full_tok,
+        "decode_step_ms_at_full_context": ms, "outputs_finite": finite, "alloc_and_fill_s": t_alloc,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,6 +261,9 @@ def main():
     ap.add_argument("--op", default="decode", choices=["decode", "l1dist"],
                     help="decode: the decode step (default, the headline); l1dist: the reuse-map selection statistic over the workload's tokens")
     ap.add_argument("--no-fuse", action="store_true", help="run prologue / attention / merge as separate kernels")
+    ap.add_argument("--capacity-check", action="store_true",
+                    help="allocate latent caches for as many tokens as fit in free HBM, run one decode step over them, report")
+    ap.add_argument("--capacity-fraction", type=float, default=0.92, help="share of the free device memory the capacity check may take")
     ap.add_argument("--wg-waves", type=int, default=0, help="fused attention kernel: 0 automatic, 4 or 8 waves per workgroup")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -201,6 +281,8 @@ def main():
     binding.lib()
     if args.op == "l1dist":
         return bench_l1_distance(args)
+    if args.capacity_check:
+        return capacity_check(args)
     base = synth.CONFIGS[args.workload]
     total_steps = args.steps + args.warmup
     w = base.scaled(n_steps=total_steps)
