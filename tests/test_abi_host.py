@@ -153,3 +153,62 @@ def test_workspace_grows_with_splits():
     ctx.set_tuning(n_splits=8)
     b = ctx.workspace_bytes(4, 4096)
     assert b > a > 0
+
+
+def test_int8_latent_format_rules_and_cache_bytes():
+    lib = B.lib()
+    h = C.c_void_p()
+    bad = B.Config(2, 8, 4, 64, 1, 8, B.BF16, 0.0, 7)                           # unknown latent format
+    assert lib.kvcar_create(C.byref(bad), C.byref(h)) == B.ERR_UNSUPPORTED
+    ctx = B.Context(2, 8, 4, 64, 2, 64, "bf16", latent_format="int8")
+    assert lib.kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(desc(256, 0, 128))) == B.OK
+    rows = 2 * 64
+    assert ctx.cache_bytes(0, B.K) == rows * 128 + rows * 8                    # codes (already a multiple of 256) + {scale, zeropoint} per row
+    assert lib.kvcar_set_autoencoder(ctx._h, 0, B.V, C.byref(desc(256, 0, 48))) == B.OK
+    assert ctx.cache_bytes(0, B.V) == (rows * 48 + 255) // 256 * 256 + rows * 8
+    assert lib.kvcar_set_autoencoder(ctx._h, 0, B.V, C.byref(desc(256, 0, 24))) == B.ERR_UNSUPPORTED   # rows must be multiples of 16 bytes
+    # the same width is fine with 16-bit rows (48 bytes)
+    ctx16 = make()
+    assert lib.kvcar_set_autoencoder(ctx16._h, 0, B.V, C.byref(desc(256, 0, 24))) == B.OK
+
+
+def test_extended_step_argument_errors():
+    ctx = make(n_layers=1)
+    lib = B.lib()
+    for which in (B.K, B.V):
+        assert lib.kvcar_set_autoencoder(ctx._h, 0, which, C.byref(desc(256, 0, 128))) == B.OK
+        assert lib.kvcar_bind_cache(ctx._h, 0, which, FAKE, ctx.cache_bytes(0, which)) == B.OK
+    ext = B.StepExt(None, FAKE, None)                                            # k_cur without v_cur
+    assert lib.kvcar_decode_attention_ex(ctx._h, 0, FAKE, FAKE, 1, 8, C.byref(ext), FAKE, 1 << 30, None) == B.ERR_ARG
+    ext = B.StepExt(None, FAKE + 2, FAKE)                                        # misaligned
+    assert lib.kvcar_decode_attention_ex(ctx._h, 0, FAKE, FAKE, 1, 8, C.byref(ext), FAKE, 1 << 30, None) == B.ERR_ARG
+    ext = B.StepExt(FAKE + 2, None, None)                                        # seq_lens not 4-byte aligned
+    assert lib.kvcar_decode_attention_ex(ctx._h, 0, FAKE, FAKE, 1, 8, C.byref(ext), FAKE, 1 << 30, None) == B.ERR_ARG
+    # nothing cached yet is accepted only together with the exact current row
+    ext = B.StepExt(None, None, None)
+    assert lib.kvcar_decode_attention_ex(ctx._h, 0, FAKE, FAKE, 1, 0, C.byref(ext), FAKE, 1 << 30, None) == B.ERR_CAPACITY
+    assert lib.kvcar_decode_attention_ex(ctx._h, 0, FAKE, FAKE, 1, 0, None, FAKE, 1 << 30, None) == B.ERR_CAPACITY
+    ext = B.StepExt(None, FAKE, FAKE)
+    assert lib.kvcar_decode_attention_ex(ctx._h, 0, FAKE, FAKE, 1, 0, C.byref(ext), FAKE, 16, None) == B.ERR_WORKSPACE   # accepted up to the workspace check
+    # ragged append: positions are required
+    assert lib.kvcar_encode_append_at(ctx._h, 0, FAKE, FAKE, 1, None, 1, None) == B.ERR_ARG
+    assert lib.kvcar_encode_append_at(ctx._h, 0, FAKE, FAKE, 3, FAKE, 1, None) == B.ERR_CAPACITY
+    assert lib.kvcar_encode_append_at(None, 0, FAKE, FAKE, 1, FAKE, 1, None) == B.ERR_ARG
+
+
+def test_selection_statistic_argument_errors_and_workspace_size():
+    lib = B.lib()
+    n = C.c_size_t()
+    assert lib.kvcar_head_l1_workspace_bytes(1000, 4, C.byref(n)) == B.OK
+    assert n.value > 0 and n.value % (4 * 4) == 0                                # workgroups x heads x 4 bytes
+    assert lib.kvcar_head_l1_workspace_bytes(0, 4, C.byref(n)) == B.ERR_ARG
+    assert lib.kvcar_head_l1_workspace_bytes(10, 4, None) == B.ERR_ARG
+    call = lib.kvcar_head_l1_distance
+    assert call(None, FAKE, B.BF16, 64, 4, 64, 0, FAKE, FAKE, 1 << 20, None) == B.ERR_ARG
+    assert call(FAKE, FAKE, B.BF16, 0, 4, 64, 0, FAKE, FAKE, 1 << 20, None) == B.ERR_ARG
+    assert call(FAKE, FAKE + 8, B.BF16, 64, 4, 64, 0, FAKE, FAKE, 1 << 20, None) == B.ERR_ARG
+    assert call(FAKE, FAKE, 5, 64, 4, 64, 0, FAKE, FAKE, 1 << 20, None) == B.ERR_UNSUPPORTED
+    assert call(FAKE, FAKE, B.BF16, 64, 4, 60, 0, FAKE, FAKE, 1 << 20, None) == B.ERR_SHAPE
+    assert call(FAKE, FAKE, B.F32, 64, 4, 62, 0, FAKE, FAKE, 1 << 20, None) == B.ERR_SHAPE
+    assert call(FAKE, FAKE, B.BF16, 64, 4, 64, 0, FAKE, FAKE, 4, None) == B.ERR_WORKSPACE
+    assert call(FAKE, FAKE, B.BF16, 64, 2000, 64, 0, FAKE, FAKE, 1 << 30, None) == B.ERR_UNSUPPORTED
