@@ -15,6 +15,19 @@ __global__ __launch_bounds__(256, 2) void attend_i8_mfma_r128_kernel(AttendParam
     KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
     KGroup g = &p->g[blockIdx.z];
     const int key = g->k.r * 4 + (g->slots_pad >> 4);
+    if (p->fused == 3) {                      // several splits, absorbed queries computed here
+        switch (key) {
+            case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+            case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+            default: return;
+        }
+    }
     if (p->fused) {
         switch (key) {
             case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, true, true>(p, g, lds_raw, kI8WaveLds); return;

@@ -15,7 +15,7 @@ __global__ __launch_bounds__(256, 2) void attend_mfma_r128_kernel(AttendParams p
     const int nhb = g->slots_pad >> 4;
     if (g->k.r == g->v.r) {
         const int key = g->k.r * 4 + nhb;
-        if (p->fused) {                       // the host only asks for this with exact shapes in every group
+        if (p->fused == 1) {                  // the host only asks for this with exact shapes in every group
             switch (key) {
                 case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, true>(p, g, lds_raw, wl); return;
                 case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, true>(p, g, lds_raw, wl); return;
@@ -25,6 +25,19 @@ __global__ __launch_bounds__(256, 2) void attend_mfma_r128_kernel(AttendParams p
                 case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, true>(p, g, lds_raw, wl); return;
                 case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, true>(p, g, lds_raw, wl); return;
                 case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, true>(p, g, lds_raw, wl); return;
+                default: return;
+            }
+        }
+        if (p->fused == 3) {                  // several splits, absorbed queries computed here
+            switch (key) {
+                case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
+                case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
+                case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
+                case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
+                case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
+                case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
+                case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
+                case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
                 default: return;
             }
         }

@@ -197,7 +197,9 @@ __device__ __forceinline__ void park_tile_i8(const u32x4_t (&st)[NL], char* regi
 // kFused (single split, exact shapes only): the absorbed queries are computed in the prologue and the
 // last decoder layer of V is applied in the epilogue, so the whole decode attention of a layer is this
 // one kernel and neither the absorbed queries nor the partials travel through memory.
-template <typename E, typename D, bool kFused, bool kI8 = false, int NW = kWaves>
+// kPrologue without kFused (several splits): every split's workgroup computes the absorbed queries itself
+// (a few microseconds, in parallel) instead of a prologue kernel running first; partials go to memory.
+template <typename E, typename D, bool kFused, bool kI8 = false, int NW = kWaves, bool kPrologue = kFused>
 __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, size_t wave_lds) {
     constexpr int RMAX = D::RMAX, NHB = D::NHB;
     using G = Geo<RMAX>;
@@ -278,7 +280,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
 
     // absorbed queries of this sequence and group, resident as MFMA B operands
     u32x4_t qb[NHB][KS];
-    if constexpr (kFused) {
+    if constexpr (kPrologue) {
         // Qt^T[c, head] = scale*log2e * sum_k Wl_K[c, col(head)+k] q[head, k], by MFMA straight from global
         // memory: A = rows of the decoder matrix, B = the queries of one KV head's heads (other heads of
         // the 16-block masked to zero; a block spans at most two KV heads: two passes).  Row rho of result

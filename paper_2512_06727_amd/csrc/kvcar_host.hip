@@ -86,6 +86,7 @@ struct Plan {
     bool mlp = false;         // ... the two-layer one
     bool i8 = false;          // ... the one over int8 latent rows (absorbed queries travel in fp32)
     bool fused = false;       // one kernel does prologue, attention and epilogue (single split, exact shapes)
+    bool prologue = false;    // several splits: the attention kernel computes the absorbed queries itself
     int n_splits = 1;
     int qt_stride = 0;        // elements per sequence
     int part_stride = 0;      // floats per (sequence, split)
@@ -222,10 +223,12 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     splits = std::max(1, std::min(splits, std::min(max_splits, 256)));
     plan.n_splits = splits;
     plan.fused = false;
-    if (plan.mfma && !plan.mlp && splits == 1 && !ctx->tun.no_fuse && r_all <= 128 && c.d_head % 32 == 0 && c.d_head <= 128) {
-        plan.fused = true;
+    plan.prologue = false;
+    if (plan.mfma && !plan.mlp && !ctx->tun.no_fuse && r_all <= 128 && c.d_head % 32 == 0 && c.d_head <= 128) {
+        plan.fused = splits == 1;
+        plan.prologue = true;                               // the query side alone: also with several splits
         for (auto& gd : plan.groups) {
-            if (gd.k.r != gd.v.r || gd.k.r % 32 || gd.k.r < 32 || gd.slots_pad > 32) plan.fused = false;
+            if (gd.k.r != gd.v.r || gd.k.r % 32 || gd.k.r < 32 || gd.slots_pad > 32) plan.fused = plan.prologue = false;
             int segs = 0;                                   // KV heads of the group: at most four decoder slices
             for (int sl = 0; sl < gd.n_slots; ++sl)
                 if (sl == 0 || gd.v_col[sl] != gd.v_col[sl - 1]) ++segs;
@@ -237,7 +240,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
                     for (int t = b0; t < sl; ++t) seen |= gd.k_col[t] == gd.k_col[sl];
                     if (!seen) ++kinds;
                 }
-                if (kinds > 2) plan.fused = false;
+                if (kinds > 2) plan.fused = plan.prologue = false;
             }
         }
     }
@@ -500,10 +503,11 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
         p.tile_order = ctx->tun.tile_order == 2 ? 1 : 0;
         // fused: 1 = four waves per workgroup; 2 = eight, when the launch has no more workgroups than compute units
         const bool w8 = ctx->tun.wg_waves == 8 || (ctx->tun.wg_waves == 0 && batch * p.n_groups <= ctx->n_cu);
-        p.fused = !plan.fused ? 0 : w8 ? 2 : 1;
+        p.fused = plan.fused ? (w8 ? 2 : 1) : plan.prologue ? 3 : 0;
         const bool proj = plan.mfma && proj_mfma_supported(p, c.dtype);
         hipError_t e = hipSuccess;
-        if (!plan.fused) e = proj && !plan.i8 ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma || plan.i8, st);
+        if (!plan.fused && !plan.prologue)
+            e = proj && !plan.i8 ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma || plan.i8, st);
         std::pair<hipEvent_t, hipEvent_t>* ev = nullptr;
         if (e == hipSuccess && ctx->profiling) {
             if (ctx->ev_used == ctx->ev_pool.size()) {
