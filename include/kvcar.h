@@ -44,6 +44,9 @@
  *   codes  int8  Z8[b][t][c]            at byte offset 0, followed at the next multiple of 256 by
  *   meta   M[b][t] = { float scale; int32 zeropoint; }   8 bytes per row;
  * r must be a multiple of 16.  Activations, weights and outputs keep the configured dtype.
+ * The matrix-core attention kernel for int8 rows feeds codes, 1/scale and the zero point to fp16
+ * operands: it expects |zeropoint| < 2^23 and max(x) - min(x) < 6e4 in every row (far outside what
+ * latent activations reach; a row of nearly equal large values would violate the first).
  */
 #ifndef KVCAR_H
 #define KVCAR_H

@@ -304,24 +304,33 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
                 for (int sl = nb * 16 + 1; sl < blk_end; ++sl)
                     if (g->k_col[sl] != col_a) { col_b = g->k_col[sl]; break; }
                 f32x4_t t[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
-                for (int k0 = 0; k0 < dh; k0 += 32) {
-                    u32x4_t bq[2], aw[2][2];
-                    const u32x4_t qv = my_col >= 0 ? *reinterpret_cast<const u32x4_t*>(qrow + (k0 + 8 * lg) * 2) : u32x4_t{0u, 0u, 0u, 0u};
-                    bq[0] = my_col == col_a ? qv : u32x4_t{0u, 0u, 0u, 0u};
-                    bq[1] = my_col == col_b ? qv : u32x4_t{0u, 0u, 0u, 0u};
+                // two 32-wide steps of the head dimension per round: all loads of a round are issued before its
+                // products, so a head dimension of 64 costs one memory latency
+                for (int k0 = 0; k0 < dh; k0 += 64) {
+                    u32x4_t bq[2][2], aw[2][2][2];
 #pragma unroll
-                    for (int sg = 0; sg < 2; ++sg)
+                    for (int u = 0; u < 2; ++u) {
+                        const int k = k0 + 32 * u;
+                        const bool on = k < dh;
+                        const u32x4_t qv = (on && my_col >= 0) ? *reinterpret_cast<const u32x4_t*>(qrow + (k + 8 * lg) * 2) : u32x4_t{0u, 0u, 0u, 0u};
+                        bq[u][0] = my_col == col_a ? qv : u32x4_t{0u, 0u, 0u, 0u};
+                        bq[u][1] = my_col == col_b ? qv : u32x4_t{0u, 0u, 0u, 0u};
 #pragma unroll
-                        for (int hh = 0; hh < 2; ++hh) {
-                            const int c = 32 * s2 + 8 * (l16 >> 2) + 4 * hh + (l16 & 3);
-                            const int col = sg == 0 ? col_a : col_b;
-                            aw[sg][hh] = u32x4_t{0u, 0u, 0u, 0u};
-                            if (col >= 0) aw[sg][hh] = *reinterpret_cast<const u32x4_t*>(wl + ((size_t)c * g->k.in_width + col + k0 + 8 * lg) * 2);
-                        }
+                        for (int sg = 0; sg < 2; ++sg)
 #pragma unroll
-                    for (int sg = 0; sg < 2; ++sg)
+                            for (int hh = 0; hh < 2; ++hh) {
+                                const int c = 32 * s2 + 8 * (l16 >> 2) + 4 * hh + (l16 & 3);
+                                const int col = sg == 0 ? col_a : col_b;
+                                aw[u][sg][hh] = u32x4_t{0u, 0u, 0u, 0u};
+                                if (on && col >= 0) aw[u][sg][hh] = *reinterpret_cast<const u32x4_t*>(wl + ((size_t)c * g->k.in_width + col + k + 8 * lg) * 2);
+                            }
+                    }
 #pragma unroll
-                        for (int hh = 0; hh < 2; ++hh) t[hh] = Mma<E>::mfma(aw[sg][hh], bq[sg], t[hh]);
+                    for (int u = 0; u < 2; ++u)
+#pragma unroll
+                        for (int sg = 0; sg < 2; ++sg)
+#pragma unroll
+                            for (int hh = 0; hh < 2; ++hh) t[hh] = Mma<E>::mfma(aw[u][sg][hh], bq[u][sg], t[hh]);
                 }
                 const float sc = p->scale_log2e;
                 qlds[(nb * KS + s2) * 64 + lane] =
