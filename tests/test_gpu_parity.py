@@ -96,3 +96,20 @@ def test_fused_single_split_kernel(name):
         ses, got = run_gpu(w, gain=20.0, n_splits=1, no_fuse=no_fuse, wg_waves=wg_waves, **kw)
         assert ses.ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached + 1).fused == (0 if no_fuse else 1)
         assert_outputs_close(w, got, want, f"{name} no_fuse={no_fuse} wg_waves={wg_waves}")
+
+
+@pytest.mark.parametrize("force_generic", [False, True])
+def test_many_source_layers_need_several_launches(force_generic):
+    """GPT-2 shape, 12 layers, KV head g reused in every layer after layer g: the last layer's heads come from
+    12 different source layers (12 groups: more than one launch carries), with latent widths 384, 352, .. 32."""
+    from paper_2512_06727_amd.harness import Session
+    w = C[1].scaled(n_layers=12, batch=2, n_cached=100, n_steps=1)
+    reuse = np.zeros((12, 2, 12), dtype=bool)
+    for layer in range(12):
+        reuse[layer, :, :layer] = True
+    _, want = run_oracle(w, reuse=reuse, gain=10.0)
+    ses, got = run_gpu(w, reuse=reuse, gain=10.0, force_generic=force_generic)
+    plan = ses.ctx.describe_plan(11, w.batch, w.n_cached + 1)
+    assert plan.n_groups == 12 and plan.n_launches == 2
+    assert [ses.ctx.resolve_source(11, 0, g) for g in range(12)] == list(range(12))
+    assert_outputs_close(w, got, want, label=f"12 sources, force_generic={force_generic}")
