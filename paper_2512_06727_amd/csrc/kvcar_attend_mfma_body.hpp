@@ -294,15 +294,19 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             const int s2 = wave;
 #pragma unroll
             for (int nb = 0; nb < NHB; ++nb) {
-                const int my_col = lane_lookup16(g->k_col, nb * 16, g->n_slots, l16, -1);
-                const int my_head = lane_lookup16(g->q_head, nb * 16, g->n_slots, l16, 0);
+                const int my_slot = nb * 16 + l16;
+                const bool live = my_slot < g->n_slots;
+                const int my_col = live ? (int)g->k_col[my_slot] : -1;
+                const int my_head = live ? (int)g->q_head[my_slot] : 0;
                 const char* qrow = static_cast<const char*>(p->q) + ((size_t)b * p->n_q_heads + my_head) * dh * 2;
-                // the (at most two) KV heads of this 16-head block
-                const int blk_end = min(g->n_slots, nb * 16 + 16);
-                const int col_a = nb * 16 < g->n_slots ? g->k_col[nb * 16] : -1;
-                int col_b = -1;
-                for (int sl = nb * 16 + 1; sl < blk_end; ++sl)
-                    if (g->k_col[sl] != col_a) { col_b = g->k_col[sl]; break; }
+                // the (at most two) KV heads of this 16-head block, from the host's table of runs
+                int col_a = -1, col_b = -1;
+#pragma unroll
+                for (int sg = 0; sg < kMaxSeg; ++sg)
+                    if (sg < g->n_kseg && g->kseg_lo[sg] < nb * 16 + 16 && g->kseg_hi[sg] > nb * 16) {
+                        if (col_a < 0) col_a = g->kseg_col[sg];
+                        else col_b = g->kseg_col[sg];
+                    }
                 f32x4_t t[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
                 // two 32-wide steps of the head dimension per round: all loads of a round are issued before its
                 // products, so a head dimension of 64 costs one memory latency
@@ -596,11 +600,10 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     if constexpr (kFused) {
         // ---- epilogue: out[head, :] = (O[head, :] / L) . Wl_V[:, col(head) ..] + bias -------------------
         // The slices [rv, d_head] of the decoder matrix (one per KV head of the group, at most four) are
-        // fetched into registers now, so that their latency hides under the merge.  The four waves then
-        // add their scaled accumulators one after the other (fixed order: deterministic) into the
-        // normalised latent sums olat[slot][rv + 4] in LDS.  Per KV head: slice -> LDS, transposing loads
-        // as B operand, latent sums as hi + lo 16-bit A operands; wave w owns output column blocks w, w+4..
-        constexpr int kMaxSeg = 4, kCpt = 1024 / (64 * NW);   // slices, 16-byte chunks per thread and slice
+        // fetched into registers now, so that their latency hides under the merge of the waves.  Per KV head:
+        // slice -> LDS, transposing loads as B operand, latent sums as hi + lo 16-bit A operands; wave w owns
+        // output column blocks w, w + NW, ..
+        constexpr int kCpt = 1024 / (64 * NW);                // 16-byte chunks per thread and decoder slice
         const int dh = p->d_head;
         const int ostride = rv + 4;
         float* olat = red + 2 * NW * NHB * 16;
@@ -608,21 +611,10 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         const int stride_w = 2 * dh + 32;
         const int cpr = dh >> 3;
         const char* wlv = static_cast<const char*>(g->v.wl);
-        int seg_lo[kMaxSeg], seg_hi[kMaxSeg], seg_col[kMaxSeg], nseg = 0;
-        {
-            int s0 = 0;
+        int seg_lo[kMaxSeg], seg_hi[kMaxSeg], seg_col[kMaxSeg];
+        const int nseg = g->n_vseg;
 #pragma unroll
-            for (int sg = 0; sg < kMaxSeg; ++sg) {
-                seg_lo[sg] = seg_hi[sg] = 0; seg_col[sg] = 0;
-                if (s0 < g->n_slots) {
-                    const int col = g->v_col[s0];
-                    int s1 = s0 + 1;
-                    while (s1 < g->n_slots && g->v_col[s1] == col) ++s1;
-                    seg_lo[sg] = s0; seg_hi[sg] = s1; seg_col[sg] = col; nseg = sg + 1;
-                    s0 = s1;
-                }
-            }
-        }
+        for (int sg = 0; sg < kMaxSeg; ++sg) { seg_lo[sg] = g->vseg_lo[sg]; seg_hi[sg] = g->vseg_hi[sg]; seg_col[sg] = g->vseg_col[sg]; }
         u32x4_t wreg[kMaxSeg][kCpt];
 #pragma unroll
         for (int sg = 0; sg < kMaxSeg; ++sg)
@@ -634,24 +626,40 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
                     wreg[sg][i] = *reinterpret_cast<const u32x4_t*>(wlv + ((size_t)row * g->v.in_width + seg_col[sg]) * 2 + ch * 16);
                 }
             }
-        // sequential, ordered accumulation of the four waves' scaled latent sums
+        // Merge of the waves' normalised latent sums: every wave parks its scaled accumulators, then each thread
+        // adds the waves' copies of its share in wave order (a fixed order: deterministic) and writes the result
+        // as olat[slot][rv + 4], which overlays the parked copies once every thread has read its inputs.
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            if (wave == w) {
+        for (int nb = 0; nb < NHB; ++nb) {
+            const float sc = l_all[nb] > 0.f ? f_own[nb] / l_all[nb] : 0.f;     // an empty context leaves the bias
 #pragma unroll
-                for (int nb = 0; nb < NHB; ++nb) {
-                    const float sc = l_all[nb] > 0.f ? f_own[nb] / l_all[nb] : 0.f;     // an empty context leaves the bias
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        float* dst = olat + (size_t)(nb * 16 + l16) * ostride + 16 * mb + 4 * lg;
-                        f32x4_t v = acc[nb][mb] * sc;
-                        if (w > 0) v += *reinterpret_cast<const f32x4_t*>(dst);
-                        *reinterpret_cast<f32x4_t*>(dst) = v;
-                    }
-                }
-            }
-            __syncthreads();
+            for (int mb = 0; mb < MB; ++mb)
+                *reinterpret_cast<f32x4_t*>(accs + ((size_t)((wave * NHB + nb) * MB + mb) * 64 + lane) * 4) = acc[nb][mb] * sc;
         }
+        __syncthreads();
+        constexpr int kItems = NHB * MB * 64;                  // float4 items of the merged sums
+        constexpr int kPerThread = (kItems + 64 * NW - 1) / (64 * NW);
+        f32x4_t merged[kPerThread];
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int item = i * (64 * NW) + threadIdx.x;
+            f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+            if (item < kItems) {
+#pragma unroll
+                for (int w = 0; w < NW; ++w) sum += *reinterpret_cast<const f32x4_t*>(accs + ((size_t)w * kItems + item) * 4);
+            }
+            merged[i] = sum;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int item = i * (64 * NW) + threadIdx.x;
+            if (item < kItems) {
+                const int ln = item & 63, blk = item >> 6, mb = blk % MB, nb = blk / MB;
+                *reinterpret_cast<f32x4_t*>(olat + (size_t)(nb * 16 + (ln & 15)) * ostride + 16 * mb + 4 * (ln >> 4)) = merged[i];
+            }
+        }
+        __syncthreads();
         uint16_t* out = static_cast<uint16_t*>(p->out);
 #pragma unroll
         for (int sg = 0; sg < kMaxSeg; ++sg) {
@@ -669,12 +677,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             for (int nb = seg_lo[sg] >> 4; nb <= (seg_hi[sg] - 1) >> 4; ++nb) {
                 int heads4[4];                          // query heads of this lane's four result rows
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    heads4[v] = 0;
-#pragma unroll
-                    for (int lgx = 0; lgx < 4; ++lgx)
-                        if (lg == lgx && nb * 16 + 4 * lgx + v < g->n_slots) heads4[v] = g->q_head[nb * 16 + 4 * lgx + v];
-                }
+                for (int v = 0; v < 4; ++v) heads4[v] = nb * 16 + 4 * lg + v < g->n_slots ? (int)g->q_head[nb * 16 + 4 * lg + v] : 0;
                 for (int nbo = wave; nbo < (dh >> 4); nbo += NW) {
                     f32x4_t o = {0.f, 0.f, 0.f, 0.f};
                     for (int k0 = 0; k0 < rv; k0 += 32) {

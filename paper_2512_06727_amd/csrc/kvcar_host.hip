@@ -195,6 +195,20 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
                 gd.k_col[s] = (short)head_column(ctx, bh.src_k, KVCAR_K, g);
                 gd.v_col[s] = (short)head_column(ctx, bh.src_v, KVCAR_V, g);
             }
+            // runs of equal KV head on either side
+            auto runs = [&](const short* col, short& n, short* lo, short* hi, short* c0) {
+                int cnt = 0;
+                for (int sl = 0; sl < gd.n_slots; ++sl) {
+                    if (sl == 0 || col[sl] != col[sl - 1]) {
+                        if (cnt < kMaxSeg) { lo[cnt] = (short)sl; c0[cnt] = col[sl]; }
+                        ++cnt;
+                    }
+                    if (cnt <= kMaxSeg) hi[cnt - 1] = (short)(sl + 1);
+                }
+                n = (short)(cnt <= kMaxSeg ? cnt : 0);
+            };
+            runs(gd.k_col, gd.n_kseg, gd.kseg_lo, gd.kseg_hi, gd.kseg_col);
+            runs(gd.v_col, gd.n_vseg, gd.vseg_lo, gd.vseg_hi, gd.vseg_col);
             plan.groups.push_back(gd);
         }
     }
@@ -228,7 +242,8 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
         plan.fused = splits == 1;
         plan.prologue = true;                               // the query side alone: also with several splits
         for (auto& gd : plan.groups) {
-            if (gd.k.r != gd.v.r || gd.k.r % 32 || gd.k.r < 32 || gd.slots_pad > 32) plan.fused = plan.prologue = false;
+            if (gd.k.r != gd.v.r || gd.k.r % 32 || gd.k.r < 32 || gd.slots_pad > 32 || gd.n_kseg == 0) plan.fused = plan.prologue = false;
+            if (gd.n_vseg == 0) plan.fused = false;
             int segs = 0;                                   // KV heads of the group: at most four decoder slices
             for (int sl = 0; sl < gd.n_slots; ++sl)
                 if (sl == 0 || gd.v_col[sl] != gd.v_col[sl - 1]) ++segs;

@@ -47,7 +47,14 @@ struct GroupDesc {
     short q_head[kMaxSlots];       // query head of each slot
     short k_col[kMaxSlots];        // first column of the slot's KV head in k.wl
     short v_col[kMaxSlots];        // same for v.wl
+    // Runs of slots with the same KV head (slots are ordered by KV head), worked out on the host so that the
+    // fused kernels read a handful of scalars instead of walking the tables above: [lo, hi) and the column.
+    // n = 0 when there are more than kMaxSeg runs (then no fused kernel is used).
+    short n_kseg, n_vseg;
+    short kseg_lo[4], kseg_hi[4], kseg_col[4];
+    short vseg_lo[4], vseg_hi[4], vseg_col[4];
 };
+constexpr int kMaxSeg = 4;
 
 struct AttendParams {
     GroupDesc g[kMaxGroups];
