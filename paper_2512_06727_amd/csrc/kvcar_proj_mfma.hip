@@ -37,8 +37,16 @@ template <> struct PMma<F16> {
 };
 
 // Slots of a group that share a KV head are consecutive and share a column offset.  Finds the
-// `which`-th such run of `col`; returns false if there are fewer runs.
-__device__ __forceinline__ bool find_segment(const short* col, int n_slots, int which, int& s0, int& len) {
+// `which`-th such run of `col`; returns false if there are fewer runs.  The host's table of runs answers
+// directly when the group has at most kMaxSeg of them; otherwise the column table is walked.
+__device__ __forceinline__ bool find_segment(const short* col, int n_slots, int n_seg, const short* seg_lo, const short* seg_hi, int which, int& s0,
+                                             int& len) {
+    if (n_seg > 0) {
+        if (which >= n_seg) return false;
+        s0 = seg_lo[which];
+        len = seg_hi[which] - s0;
+        return true;
+    }
     int seg = -1, start = 0;
     for (int s = 0; s <= n_slots; ++s) {
         if (s == n_slots || (s > 0 && col[s] != col[s - 1])) {
@@ -65,9 +73,9 @@ __global__ __launch_bounds__(256) void qtilde_mfma_kernel(AttendParams p) {
     const int l16 = lane & 15, lg = lane >> 4;
     const int rk = g.k.c;            // contraction width of the score product: latent (linear decoder) or hidden width
     int s0 = 0, len = 0;
-    if (!find_segment(g.k_col, g.n_slots, blockIdx.y, s0, len)) {
+    if (!find_segment(g.k_col, g.n_slots, g.n_kseg, g.kseg_lo, g.kseg_hi, blockIdx.y, s0, len)) {
         int dummy0, dummy1;
-        const bool is_pad_pass = (blockIdx.y == 0) ? false : find_segment(g.k_col, g.n_slots, blockIdx.y - 1, dummy0, dummy1);
+        const bool is_pad_pass = (blockIdx.y == 0) ? false : find_segment(g.k_col, g.n_slots, g.n_kseg, g.kseg_lo, g.kseg_hi, blockIdx.y - 1, dummy0, dummy1);
         if (!is_pad_pass || g.slots_pad == g.n_slots) return;
         // zero the padding slots of every sequence (rows of qt the attention kernel loads but ignores)
         const int pad = g.slots_pad - g.n_slots;
@@ -143,7 +151,7 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, lg = lane >> 4;
     int s0 = 0, len = 0;
-    if (!find_segment(g.v_col, g.n_slots, blockIdx.y, s0, len)) return;
+    if (!find_segment(g.v_col, g.n_slots, g.n_vseg, g.vseg_lo, g.vseg_hi, blockIdx.y, s0, len)) return;
     const int rows = p.batch * len;
     const int wg_row0 = blockIdx.x * rows_per_wg;
     if (wg_row0 >= rows) return;
