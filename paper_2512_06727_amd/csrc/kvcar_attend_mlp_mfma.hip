@@ -91,13 +91,19 @@ __device__ __forceinline__ void act_pack(const f32x16_t& t, const float (&bias)[
     }
 }
 
-template <typename E, int R, int C, int ACT>
+// kI8: the cache holds int8 codes with a scale and a zero point per row ("Quantization", Eq. "quant").  The
+// rows are dequantised, x^ = (code - zeropoint) / scale, on their way from the staging registers into LDS and
+// rounded there to the model dtype - the precision a 16-bit model holds the dequantised tensor in before
+// the decoder - so everything after the park is the 16-bit path.
+template <typename E, int R, int C, int ACT, bool kI8>
 __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p) {
     constexpr int CW = C / 4;          // hidden columns per wave
     constexpr int MB = CW / 32;        // 32-column blocks per wave
     constexpr int KS = R / 16;         // k-steps over the latent width
     constexpr int STRIDE = 2 * R + 16; // LDS row stride of a latent tile
-    constexpr int NLD = (kMlpTile * R / 8) / 256 > 0 ? (kMlpTile * R / 8) / 256 : 1;   // 16-byte chunks per thread per tile
+    constexpr int EB = kI8 ? 1 : 2;    // bytes per cached latent element
+    constexpr int CPR = R * EB / 16;   // 16-byte chunks per cached row
+    constexpr int NLD = (kMlpTile * CPR) / 256 > 0 ? (kMlpTile * CPR) / 256 : 1;       // 16-byte chunks per thread per tile
     static_assert(CW % 32 == 0 && R % 16 == 0, "shape");
 
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -189,24 +195,48 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
     const int per_split = (tiles + p.n_splits - 1) / p.n_splits;
     const int j0 = split * per_split;
     const int j1 = min(tiles, j0 + per_split);
-    const char* zk = static_cast<const char*>(g.k.z) + (size_t)b * p.max_seq * R * 2;
-    const char* zv = static_cast<const char*>(g.v.z) + (size_t)b * p.max_seq * R * 2;
+    const char* zk = static_cast<const char*>(g.k.z) + (size_t)b * p.max_seq * R * EB;
+    const char* zv = static_cast<const char*>(g.v.z) + (size_t)b * p.max_seq * R * EB;
+    const RowMeta* mk = static_cast<const RowMeta*>(g.k.meta) + (size_t)b * p.max_seq;     // int8 rows only
+    const RowMeta* mv = static_cast<const RowMeta*>(g.v.meta) + (size_t)b * p.max_seq;
 
     // tile chunks of this thread: chunk f = i*256 + tid of the contiguous [32, R] tile
     u32x4_t stk[NLD], stv[NLD];
+    u32x2_t smk[NLD], smv[NLD];        // int8: {scale, zeropoint} of the row each chunk belongs to
     auto issue = [&](int j) {
         const int t0 = j * kMlpTile;
-        const int valid = max(0, min(kMlpTile, n_ctx - t0)) * (R / 8);
+        const int valid = max(0, min(kMlpTile, n_ctx - t0)) * CPR;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int f = i * 256 + tid;
             u32x4_t a = {0u, 0u, 0u, 0u}, c2 = {0u, 0u, 0u, 0u};
+            smk[i] = smv[i] = u32x2_t{0x3f800000u, 0u};
             if (f < valid) {
-                a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(zk + (size_t)t0 * R * 2 + (size_t)f * 16));
-                c2 = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(zv + (size_t)t0 * R * 2 + (size_t)f * 16));
+                a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(zk + (size_t)t0 * R * EB + (size_t)f * 16));
+                c2 = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(zv + (size_t)t0 * R * EB + (size_t)f * 16));
+                if constexpr (kI8) {
+                    smk[i] = *reinterpret_cast<const u32x2_t*>(mk + t0 + f / CPR);
+                    smv[i] = *reinterpret_cast<const u32x2_t*>(mv + t0 + f / CPR);
+                }
             }
             stk[i] = a; stv[i] = c2;
         }
+    };
+    // 16 codes -> 16 dequantised values in the model dtype (two 16-byte halves)
+    auto dequant = [&](const u32x4_t c, const u32x2_t m, u32x4_t& lo, u32x4_t& hi) {
+        const float inv = 1.f / __uint_as_float(m[0]);
+        const float sub = (128.f + (float)(int)m[1]) * inv;         // codes are read as unsigned bytes code + 128
+        unsigned w[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const unsigned x = c[i] ^ 0x80808080u;
+            const float f0 = fmaf((float)(x & 0xffu), inv, -sub), f1 = fmaf((float)((x >> 8) & 0xffu), inv, -sub);
+            const float f2 = fmaf((float)((x >> 16) & 0xffu), inv, -sub), f3 = fmaf((float)(x >> 24), inv, -sub);
+            w[2 * i] = MMma<E>::pack2(f0, f1);
+            w[2 * i + 1] = MMma<E>::pack2(f2, f3);
+        }
+        lo = u32x4_t{w[0], w[1], w[2], w[3]};
+        hi = u32x4_t{w[4], w[5], w[6], w[7]};
     };
     if (j0 < j1) issue(j0);
 
@@ -216,10 +246,20 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int f = i * 256 + tid;
-            if (f < kMlpTile * (R / 8)) {
-                const int row = f / (R / 8), ch = f % (R / 8);
-                *reinterpret_cast<u32x4_t*>(tile_k + row * STRIDE + ch * 16) = stk[i];
-                *reinterpret_cast<u32x4_t*>(tile_v + row * STRIDE + ch * 16) = stv[i];
+            if (f < kMlpTile * CPR) {
+                const int row = f / CPR, ch = f % CPR;
+                if constexpr (kI8) {
+                    u32x4_t lo, hi;
+                    dequant(stk[i], smk[i], lo, hi);
+                    *reinterpret_cast<u32x4_t*>(tile_k + row * STRIDE + ch * 32) = lo;
+                    *reinterpret_cast<u32x4_t*>(tile_k + row * STRIDE + ch * 32 + 16) = hi;
+                    dequant(stv[i], smv[i], lo, hi);
+                    *reinterpret_cast<u32x4_t*>(tile_v + row * STRIDE + ch * 32) = lo;
+                    *reinterpret_cast<u32x4_t*>(tile_v + row * STRIDE + ch * 32 + 16) = hi;
+                } else {
+                    *reinterpret_cast<u32x4_t*>(tile_k + row * STRIDE + ch * 16) = stk[i];
+                    *reinterpret_cast<u32x4_t*>(tile_v + row * STRIDE + ch * 16) = stv[i];
+                }
             }
         }
         if (j + 1 < j1) issue(j + 1);
@@ -354,15 +394,15 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
     }
 }
 
-template <typename E, int R, int C>
+template <typename E, int R, int C, bool kI8>
 static hipError_t launch_mlp(const AttendParams& p, int act, hipStream_t stream) {
     const size_t loop_lds = 2 * (size_t)kMlpTile * (2 * R + 16) + (size_t)4 * 64 * 16 * sizeof(float);
     const size_t stage_lds = (size_t)R * (2 * C + 32);            // first-layer weights pass through LDS at start
     const size_t lds = loop_lds > stage_lds ? loop_lds : stage_lds;
     dim3 grid(p.n_splits, p.batch, p.n_groups);
     static bool attr[2] = {false, false};
-    auto kg = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_GELU>;
-    auto kl = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_LEAKY_RELU>;
+    auto kg = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_GELU, kI8>;
+    auto kl = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_LEAKY_RELU, kI8>;
     const int ai = act == KVCAR_ACT_GELU ? 0 : 1;
     if (!attr[ai]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ai == 0 ? kg : kl), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -393,8 +433,13 @@ bool attend_mlp_mfma_supported(const AttendParams& p, int dtype) {
 hipError_t launch_attend_mlp_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
     const int act = p.g[0].k.act;
     const bool big = p.g[0].k.r == 128;
-    if (dtype == KVCAR_BF16) return big ? launch_mlp<BF16, 128, 256>(p, act, stream) : launch_mlp<BF16, 64, 128>(p, act, stream);
-    return big ? launch_mlp<F16, 128, 256>(p, act, stream) : launch_mlp<F16, 64, 128>(p, act, stream);
+    const bool i8 = p.g[0].k.meta != nullptr;
+    if (dtype == KVCAR_BF16) {
+        if (i8) return big ? launch_mlp<BF16, 128, 256, true>(p, act, stream) : launch_mlp<BF16, 64, 128, true>(p, act, stream);
+        return big ? launch_mlp<BF16, 128, 256, false>(p, act, stream) : launch_mlp<BF16, 64, 128, false>(p, act, stream);
+    }
+    if (i8) return big ? launch_mlp<F16, 128, 256, true>(p, act, stream) : launch_mlp<F16, 64, 128, true>(p, act, stream);
+    return big ? launch_mlp<F16, 128, 256, false>(p, act, stream) : launch_mlp<F16, 64, 128, false>(p, act, stream);
 }
 
 }  // namespace kvcar

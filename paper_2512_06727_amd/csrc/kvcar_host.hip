@@ -132,7 +132,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     // MFMA kernels: 16-bit dtype, linear decoders, latent widths that are multiples of 32
     bool mfma_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && attend_mfma_available() && c.d_head % 8 == 0;
     // ... or two-layer decoders of one of the shapes with a resident-weight kernel, the same for K and V
-    bool mlp_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && c.d_head % 32 == 0 && c.d_head <= 128 && !ctx->int8();
+    bool mlp_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && c.d_head % 32 == 0 && c.d_head <= 128;
     int mlp_r = -1, mlp_c = -1, mlp_act = -1;
     float mlp_slope = 0.f;
     int r_all = 0;
@@ -214,7 +214,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     }
     plan.mfma = mfma_ok;
     plan.mlp = mlp_ok;
-    plan.i8 = mfma_ok && ctx->int8();
+    plan.i8 = mfma_ok && !mlp_ok && ctx->int8();       // linear decoders over int8 rows; the two-layer kernel dequantises while parking
     int qt = 0, part = 0;
     for (auto& gd : plan.groups) {
         gd.qt_off = qt; gd.part_off = part;

@@ -57,6 +57,18 @@ def test_int8_mfma_kernel_is_used_and_agrees_with_plain_alu(name, gain):
         assert_outputs_close(w, got, want, label=f"{name} {session_kw}")
 
 
+def test_int8_two_layer_decoder_takes_the_mfma_kernel():
+    """Two-layer autoencoder over int8 rows (the paper's autoencoder form with its quantisation on top): the
+    matrix-core kernel dequantises while parking the tile; the plain-ALU kernels give the same outputs."""
+    from paper_2512_06727_amd.harness import Session
+    w, kw = CASES["c3-small-mlp"]
+    assert Session(w, latent_format="int8").ctx.describe_plan(0, w.batch, w.n_cached + 1).uses_mfma == 1
+    orc, want = run_oracle(w, gain=8.0, latent_format="int8", **kw)
+    for session_kw in ({}, {"n_splits": 2}, {"force_generic": True}):
+        ses, got = run_gpu(w, gain=8.0, latent_format="int8", **session_kw, **kw)
+        assert_outputs_close(w, got, want, label=f"two-layer int8 {session_kw}")
+
+
 def test_int8_cache_is_smaller_and_laid_out_as_documented():
     w = C[2].scaled(n_layers=2, batch=2, n_cached=10, n_steps=1, reuse="none")
     from paper_2512_06727_amd.harness import Session
