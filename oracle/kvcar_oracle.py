@@ -34,7 +34,8 @@ attention, all-false reuse map == per-layer attention, softmax rows sum to 1,
 q = 0 closed form, peaked q, chained reuse vs explicit copies, rounding vs hand
 cases and a library cast, GELU vs erf; the quantiser vs a hand-worked row, exact
 rational arithmetic, an arithmetic progression (codes -128..127), the half-step
-error bound, and invariance under positive dyadic scaling and shifts.  The numerical values a *trained*
+error bound, and invariance under positive dyadic scaling and shifts; the prefill form vs scalar
+brute force, a library causal SDPA, token-by-token decode steps, and causality.  The numerical values a *trained*
 autoencoder would produce are "parity unpinned": the paper ships no weights.
 """
 from __future__ import annotations
@@ -328,6 +329,36 @@ class KVCAROracle:
                 if return_probs:
                     probs[b, j, :p.shape[0]] = p
         return (out, probs) if return_probs else out
+
+    # -- step 5 for a whole prompt chunk (prefill) ---------------------------
+    def prefill_attention(self, layer: int, q: np.ndarray, pos0: int) -> np.ndarray:
+        """Causal attention of a chunk of T query tokens over the latent cache (Introduction: the
+        prefill phase processes the prompt and produces the keys and values of all its tokens,
+        which are stored - here as latent rows - and read back through the decoder; Eq. 1 per
+        token, each token seeing the rows up to and including its own).
+
+        q [B, T, H_q, d_head]; query token i of a sequence sits at position pos0 + i and its own
+        latent row (like every earlier one) is already in the cache.  Returns [B, T, H_q, d_head]
+        (fp64):  out[b, i, j] = sum_{t <= pos0 + i} softmax_t(scale q[b,i,j] . K^_g[t]) V^_g[t]."""
+        q = np.asarray(q, np.float64)
+        bsz, t_new = q.shape[0], q.shape[1]
+        n = pos0 + t_new
+        assert pos0 >= 0 and n <= self.max_seq
+        group = self.hq // self.hkv
+        out = np.zeros((bsz, t_new, self.hq, self.dh))
+        visible = np.arange(n)[None, :] <= (pos0 + np.arange(t_new))[:, None]      # [T, n]
+        for b in range(bsz):
+            memo: dict = {}
+            for j in range(self.hq):
+                g = j // group
+                k_hat = self.decoded_head(layer, K, g, b, n, memo)
+                v_hat = self.decoded_head(layer, V, g, b, n, memo)
+                s = (q[b, :, j, :] @ k_hat.T) * self.scale
+                s = np.where(visible, s, -np.inf)
+                p = np.exp(s - s.max(axis=1, keepdims=True))
+                p = p / p.sum(axis=1, keepdims=True)
+                out[b, :, j, :] = p @ v_hat
+        return out
 
 
 # --------------------------------------------------------------------------
