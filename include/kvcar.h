@@ -14,6 +14,7 @@
  *                           second paragraph; Background, Eq. 1), with inter-layer head reuse
  *                           ("Network Architecture", third paragraph) resolved while addressing
  *   kvcar_set_reuse_map     the per-layer boolean map of reused K heads and V heads
+ * and, for the prompt, kvcar_prefill_attention (causal attention of a chunk over the same caches).
  *
  * Conventions
  *   - Pure C.  Every function returns a kvcar_status (0 = OK, negative = error); nothing throws.
@@ -232,6 +233,31 @@ int kvcar_encode_append_at(kvcar_ctx *ctx, int layer, const void *k_new, const v
                            const int32_t *positions, int t_new, void *stream);
 
 /*
+ * Prefill attention over the latent cache (Introduction: in the prefill phase the whole prompt is
+ * processed and the keys and values of all its tokens go to the KV cache - here as latent rows;
+ * "Network Architecture", 2nd paragraph: the decoder rebuilds them on retrieval; Eq. 1 per token, each
+ * token attending to the rows up to and including its own).  For a chunk of t_new query tokens per
+ * sequence, token i sitting at position pos0 + i, whose latent rows - like those of all earlier
+ * positions - are already in the caches (kvcar_encode_append):
+ *   out[b, i, j, :] = sum_{t <= pos0 + i} softmax_t(scale * q[b,i,j,:] . K^_g[t]) V^_g[t],   g = j / (H_q/H_kv)
+ *   q    dev [batch, t_new, H_q, d_head]      out  dev [batch, t_new, H_q, d_head] (rounded once to dtype)
+ * K^_g / V^_g as in kvcar_decode_attention (source layer by the reuse map).  This equals t_new decode
+ * steps with n_ctx = pos0 + i + 1 up to rounding.  Unlike a decode step, a prompt chunk is bound by the
+ * matrix units, not by reading the cache, so the decoder is not folded into the query (that would double
+ * the products per score): the rows 0 .. pos0 + t_new - 1 of every KV head are decoded ONCE per call into
+ * `workspace` (rounded to dtype, the precision the model holds its keys and values in) and a causal
+ * attention kernel runs over them.  Nothing outlives the call: the workspace may be reused at once by
+ * the next layer.  kvcar_prefill_workspace_bytes(batch, n_rows) gives its size for n_rows = pos0 + t_new
+ * (2 * batch * n_rows * H_kv * d_head elements).
+ * ERR_CAPACITY if batch > max_batch or pos0 + t_new > max_seq; ERR_ARG if t_new < 1, pos0 < 0 or a
+ * pointer is null / misaligned; ERR_STATE / ERR_REUSE as for a decode step; ERR_WORKSPACE;
+ * ERR_UNSUPPORTED if d_head > 256.
+ */
+int kvcar_prefill_workspace_bytes(const kvcar_ctx *ctx, int batch, int n_rows, size_t *bytes);
+int kvcar_prefill_attention(kvcar_ctx *ctx, int layer, const void *q, void *out, int batch, int pos0, int t_new,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * What kvcar_decode_attention would launch for (layer, batch, n_ctx) under the current maps,
  * autoencoders and tuning.  A "group" is the set of query heads of the layer that read the same
  * (K source layer, V source layer); each distinct source's latent rows are streamed once per group.
@@ -248,9 +274,10 @@ typedef struct {
 int kvcar_describe_plan(const kvcar_ctx *ctx, int layer, int batch, int n_ctx, kvcar_plan_info *out);
 
 /*
- * Optional timing of the attention kernel (the kernel that streams the latent cache).  While
- * enabled, kvcar_decode_attention records a HIP event before and after that kernel on the caller's
- * stream.  kvcar_profile_read waits for the recorded events (this is the only call that blocks on
+ * Optional timing of the attention kernel (the kernel that streams the latent cache; for
+ * kvcar_prefill_attention the causal attention kernel).  While enabled, kvcar_decode_attention and
+ * kvcar_prefill_attention record a HIP event before and after that kernel on the caller's stream.
+ * kvcar_profile_read waits for the recorded events (this is the only call that blocks on
  * the device), returns the summed kernel time in milliseconds and the number of launches since the
  * last reset, and resets the counters.
  */

@@ -67,6 +67,9 @@ SYMBOLS = {
     "kvcar_decode_attention_ex": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(StepExt), C.c_void_p,
                                             C.c_size_t, C.c_void_p]),
     "kvcar_encode_append_at": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]),
+    "kvcar_prefill_workspace_bytes": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]),
+    "kvcar_prefill_attention": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t,
+                                          C.c_void_p]),
     "kvcar_describe_plan": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(PlanInfo)]),
     "kvcar_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "kvcar_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_long)]),
@@ -248,3 +251,13 @@ class Context:
         nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
         self._check(lib().kvcar_decode_attention(self._h, layer, _ptr(q), _ptr(out), batch, n_ctx, _ptr(workspace),
                                                  nbytes, _stream()))
+
+    def prefill_workspace_bytes(self, batch: int, n_rows: int) -> int:
+        n = C.c_size_t(0)
+        self._check(lib().kvcar_prefill_workspace_bytes(self._h, batch, n_rows, C.byref(n)))
+        return n.value
+
+    def prefill_attention(self, layer: int, q, out, batch: int, pos0: int, t_new: int, workspace):
+        """q, out: [batch, t_new, H_q, d_head] device tensors."""
+        nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self._check(lib().kvcar_prefill_attention(self._h, layer, _ptr(q), _ptr(out), batch, pos0, t_new, _ptr(workspace), nbytes, _stream()))

@@ -43,6 +43,16 @@ template <> struct Elem<BF16> {
     static __device__ __forceinline__ void store(void* p, size_t i, float v) { static_cast<uint16_t*>(p)[i] = f32_to_bf16_bits(v); }
 };
 
+// Element c of latent row `row` of a cache side: as stored, or dequantised from its int8 code
+// (x^ = (code - zeropoint) / scale, Eq. "quant").
+template <typename E>
+__device__ __forceinline__ float latent_at(const SideDesc& sd, size_t row, int c) {
+    if (sd.meta == nullptr) return Elem<E>::load(sd.z, row * sd.r + c);
+    const RowMeta m = static_cast<const RowMeta*>(sd.meta)[row];
+    const int code = static_cast<const signed char*>(sd.z)[row * sd.r + c];
+    return (float)(code - m.zeropoint) / m.scale;
+}
+
 // Activation between the two fully connected layers of an encoder / decoder.
 __device__ __forceinline__ float apply_act(float x, int act, float slope) {
     if (act == KVCAR_ACT_LEAKY_RELU) return x >= 0.f ? x : slope * x;

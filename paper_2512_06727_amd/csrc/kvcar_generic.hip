@@ -149,16 +149,6 @@ hipError_t launch_qtilde(const AttendParams& p, int dtype, bool qt_f32, hipStrea
 // plain-ALU attention over rows h_t, one workgroup per (split, sequence, group).
 // Partial written per (b, split, group): for each slot  [m, l, -, -, o[0..cv)]  with scores in log2 units.
 // ---------------------------------------------------------------------------------------------
-// Element c of cached latent row `row`: the stored value, or for int8 latents the dequantised
-// code, (code - zeropoint) / scale ("Quantization", Eq. "quant", last line).
-template <typename E>
-__device__ __forceinline__ float latent_at(const SideDesc& sd, size_t row, int c) {
-    if (sd.meta == nullptr) return Elem<E>::load(sd.z, row * sd.r + c);
-    const RowMeta m = static_cast<const RowMeta*>(sd.meta)[row];
-    const int code = static_cast<const signed char*>(sd.z)[row * sd.r + c];
-    return (float)(code - m.zeropoint) / m.scale;
-}
-
 template <typename E>
 __device__ void load_rows(const SideDesc& sd, float* rows, float* zrow, int b, int t0, int nt, int max_seq) {
     // rows [kGenericTile][c+1]; rows of tokens >= nt are zero

@@ -544,6 +544,95 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
     return KVCAR_OK;
 }
 
+// Sources to decode for prefill attention of `layer`: one entry per (source layer, K or V), listing the KV heads that take it.
+int build_recon(const kvcar_ctx* ctx, int layer, std::vector<ReconEntry>& entries) {
+    const kvcar_config& c = ctx->cfg;
+    entries.clear();
+    for (int which = 0; which < 2; ++which) {
+        std::map<int, std::vector<int>> by_src;
+        for (int g = 0; g < c.n_kv_heads; ++g) by_src[resolve(ctx, layer, which, g)].push_back(g);
+        for (auto& kv : by_src) {
+            SideDesc sd{};
+            int rc = fill_side(ctx, layer, kv.first, which, sd);
+            if (rc) return rc;
+            if (sd.c > kMaxRow || sd.r > kMaxRow) return fail(ctx, KVCAR_ERR_UNSUPPORTED, "row width above %d", kMaxRow);
+            for (size_t h0 = 0; h0 < kv.second.size(); h0 += kMaxReconHeads) {
+                ReconEntry e{};
+                e.d = sd;
+                e.which = which;
+                e.n_heads = (int)std::min<size_t>(kMaxReconHeads, kv.second.size() - h0);
+                for (int i = 0; i < e.n_heads; ++i) {
+                    const int g = kv.second[h0 + i];
+                    const int col = head_column(ctx, kv.first, which, g);
+                    if (col < 0) return fail(ctx, KVCAR_ERR_REUSE, "layer %d takes head %d from a layer whose autoencoder does not cover it", layer, g);
+                    e.head[i] = (short)g;
+                    e.col[i] = (short)col;
+                }
+                entries.push_back(e);
+            }
+        }
+    }
+    return KVCAR_OK;
+}
+
+size_t prefill_need(const kvcar_ctx* ctx, int batch, int n_rows) {
+    const kvcar_config& c = ctx->cfg;
+    return 2 * align_up((size_t)batch * n_rows * c.n_kv_heads * c.d_head * dtype_size(c.dtype), 256);
+}
+
+int prefill_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int pos0, int t_new, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+    int rc = check_layer(ctx, layer);
+    if (rc) return rc;
+    const kvcar_config& c = ctx->cfg;
+    if (!q || !out || !aligned16(q) || !aligned16(out)) return fail(ctx, KVCAR_ERR_ARG, "q / out null or misaligned");
+    if (batch < 1 || t_new < 1 || pos0 < 0) return fail(ctx, KVCAR_ERR_ARG, "batch, t_new must be >= 1 and pos0 >= 0");
+    if (batch > c.max_batch || (long long)pos0 + t_new > c.max_seq)
+        return fail(ctx, KVCAR_ERR_CAPACITY, "chunk of %d tokens at %d for batch %d exceeds max_seq %d / max_batch %d", t_new, pos0, batch, c.max_seq, c.max_batch);
+    if (c.d_head > 256) return fail(ctx, KVCAR_ERR_UNSUPPORTED, "prefill attention handles d_head up to 256");
+    const int n_rows = pos0 + t_new;
+    std::vector<ReconEntry> entries;
+    rc = build_recon(ctx, layer, entries);
+    if (rc) return rc;
+    const size_t need = prefill_need(ctx, batch, n_rows);
+    if (!workspace || !aligned16(workspace)) return fail(ctx, KVCAR_ERR_ARG, "workspace null or misaligned");
+    if (workspace_bytes < need) return fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need);
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    void* khat = workspace;
+    void* vhat = static_cast<char*>(workspace) + need / 2;
+    hipError_t e = hipSuccess;
+    for (size_t e0 = 0; e0 < entries.size() && e == hipSuccess; e0 += kMaxReconEntries) {
+        ReconParams rp{};
+        rp.n_entries = (int)std::min<size_t>(kMaxReconEntries, entries.size() - e0);
+        for (int i = 0; i < rp.n_entries; ++i) rp.e[i] = entries[e0 + i];
+        rp.khat = khat; rp.vhat = vhat;
+        rp.batch = batch; rp.n_rows = n_rows; rp.max_seq = c.max_seq; rp.n_kv_heads = c.n_kv_heads; rp.d_head = c.d_head;
+        e = (!ctx->tun.force_generic && recon_mfma_supported(rp, c.dtype)) ? launch_recon_mfma(rp, c.dtype, st) : launch_recon_generic(rp, c.dtype, st);
+    }
+    PrefillParams pp{};
+    pp.q = q; pp.out = out; pp.khat = khat; pp.vhat = vhat;
+    pp.batch = batch; pp.t_new = t_new; pp.pos0 = pos0; pp.n_rows = n_rows;
+    pp.n_q_heads = c.n_q_heads; pp.n_kv_heads = c.n_kv_heads; pp.d_head = c.d_head;
+    pp.scale_log2e = ctx->scale * kLog2e;
+    std::pair<hipEvent_t, hipEvent_t>* ev = nullptr;
+    if (e == hipSuccess && ctx->profiling) {
+        if (ctx->ev_used == ctx->ev_pool.size()) {
+            hipEvent_t a, b2;
+            e = hipEventCreate(&a);
+            if (e == hipSuccess) e = hipEventCreate(&b2);
+            if (e == hipSuccess) ctx->ev_pool.emplace_back(a, b2);
+        }
+        if (e == hipSuccess) { ev = &ctx->ev_pool[ctx->ev_used++]; e = hipEventRecord(ev->first, st); }
+    }
+    if (e == hipSuccess)
+        e = (!ctx->tun.force_generic && prefill_mfma_supported(pp, c.dtype)) ? launch_prefill_mfma(pp, c.dtype, ctx->n_cu, st)
+                                                                              : launch_prefill_generic(pp, c.dtype, st);
+    if (e == hipSuccess && ev) e = hipEventRecord(ev->second, st);
+    if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "prefill launch failed: %s", hipGetErrorString(e));
+    return KVCAR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -567,6 +656,19 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
 int kvcar_decode_attention_ex(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, const kvcar_step_ext* ext,
                               void* workspace, size_t workspace_bytes, void* stream) {
     return decode_impl(ctx, layer, q, out, batch, n_ctx, ext, workspace, workspace_bytes, stream);
+}
+
+int kvcar_prefill_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_rows, size_t* bytes) {
+    if (!ctx || !bytes) return KVCAR_ERR_ARG;
+    if (batch < 1 || batch > ctx->cfg.max_batch || n_rows < 1 || n_rows > ctx->cfg.max_seq)
+        return fail(ctx, KVCAR_ERR_CAPACITY, "batch %d / n_rows %d outside [1,%d] / [1,%d]", batch, n_rows, ctx->cfg.max_batch, ctx->cfg.max_seq);
+    *bytes = prefill_need(ctx, batch, n_rows);
+    return KVCAR_OK;
+}
+
+int kvcar_prefill_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int pos0, int t_new, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    return prefill_impl(ctx, layer, q, out, batch, pos0, t_new, workspace, workspace_bytes, stream);
 }
 
 int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, kvcar_plan_info* out) {

@@ -132,6 +132,46 @@ int head_l1_workgroups(size_t n_tokens, int n_cu);
 hipError_t launch_head_l1(const void* prev, const void* cur, int dtype, size_t n_tokens, int n_kv_heads, int d_head, int accumulate, float* dist,
                           float* partial, int n_wg, hipStream_t stream);
 
+// ---- prefill attention: decode every needed row once, then causal attention over the decoded rows ----------
+constexpr int kMaxReconHeads = 16;     // KV heads per entry
+constexpr int kMaxReconEntries = 8;    // entries per launch
+
+// One source (layer, K or V) whose cached rows are decoded, with the KV heads of the attending layer that take it.
+struct ReconEntry {
+    SideDesc d;
+    int which;                    // KVCAR_K / KVCAR_V: which of the two decoded tensors the heads go to
+    int n_heads;
+    short head[kMaxReconHeads];   // KV head index in the attending layer
+    short col[kMaxReconHeads];    // first column of that head in d.wl
+};
+
+struct ReconParams {
+    ReconEntry e[kMaxReconEntries];
+    int n_entries;
+    void* khat;                   // decoded keys   [batch, H_kv, n_rows, d_head]
+    void* vhat;                   // decoded values [batch, H_kv, n_rows, d_head]
+    int batch, n_rows, max_seq, n_kv_heads, d_head;
+};
+
+struct PrefillParams {
+    const void* q;                // [batch, t_new, H_q, d_head]
+    void* out;                    // [batch, t_new, H_q, d_head]
+    const void* khat;
+    const void* vhat;
+    int batch, t_new, pos0, n_rows;
+    int n_q_heads, n_kv_heads, d_head;
+    float scale_log2e;            // softmax scale * log2(e)
+};
+
+hipError_t launch_recon_generic(const ReconParams& p, int dtype, hipStream_t stream);
+hipError_t launch_prefill_generic(const PrefillParams& p, int dtype, hipStream_t stream);
+// MFMA versions (16-bit dtypes): decoded rows for linear decoders with latent widths that are multiples of 32;
+// causal attention for d_head = 64 or 128.
+bool recon_mfma_supported(const ReconParams& p, int dtype);
+hipError_t launch_recon_mfma(const ReconParams& p, int dtype, hipStream_t stream);
+bool prefill_mfma_supported(const PrefillParams& p, int dtype);
+hipError_t launch_prefill_mfma(const PrefillParams& p, int dtype, int n_cu, hipStream_t stream);
+
 hipError_t launch_stream_read(const void* src, size_t bytes, int n_blocks, int block, unsigned* sink, hipStream_t stream);
 
 }  // namespace kvcar

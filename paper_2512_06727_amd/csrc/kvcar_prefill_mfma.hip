@@ -1,0 +1,446 @@
+// Prefill attention over the latent cache on the matrix cores (gfx950, 16-bit dtypes).
+//
+// A prompt chunk attends causally over the cached rows of its sequence (Introduction: the prefill phase
+// produces the keys and values of all prompt tokens; they are cached as latent rows and come back through
+// the decoder, "Network Architecture", 2nd paragraph; attention is Eq. 1 per token).  Unlike a decode
+// step this is bound by the matrix units: T x L scores per head against L latent rows read.  Folding the
+// decoder into the query (what the decode kernels do) would make every score a contraction over the
+// latent width r instead of d_head - twice the work for r = 2 d_head - so here the rows are decoded
+// first, ONCE per call, and a causal attention kernel runs over the decoded rows:
+//
+//   recon_mfma_kernel    K^^T[n, t] = W^T[n, c] . Z^T[c, t]   (v_mfma_f32_32x32x16; A = the decoder columns
+//                        of one KV head through LDS and the transposing load, B = latent rows straight
+//                        from global memory, dequantised in registers when they are int8 codes)
+//   prefill_mfma_kernel  per workgroup: 4 waves x 32*QB query tokens of one head; K^ / V^ tiles of 64 rows
+//                        are shared through LDS (double buffered, one barrier per tile)
+//                          S^T[row, q] = K^ . Q^T            A = K^ rows (LDS), B = queries (registers)
+//                          online softmax in base 2: a lane holds 32 rows of ONE query per tile, so the
+//                          reductions are in-lane plus one cross-lane step
+//                          O^T[d, q] += V^^T . P^T           A = V^ through the transposing load, B = P^T
+//                          straight from the softmax registers (the result layout of S^T is the operand
+//                          layout, with the rows of a k-step taken in the order the registers hold them)
+//                        the causal limit only touches the last one or two tiles of a wave.
+#include "kvcar_attend_mfma_body.hpp"
+
+namespace kvcar {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+template <typename E> struct Mma32;
+template <> struct Mma32<BF16> {
+    static __device__ __forceinline__ f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+};
+template <> struct Mma32<F16> {
+    static __device__ __forceinline__ f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    }
+};
+
+// Transposing LDS load: 16 lanes supply the addresses of a 4-row x 16-column patch of 16-bit elements and
+// lane i receives the 4 rows of column i.  Two patches make the 8 k-slots of a lane.
+__device__ __forceinline__ u32x4_t tr_pair32(const char* p, int second_offset) {
+    const s16x4_t t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
+    const s16x4_t t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p + second_offset));
+    const u32x2_t a0 = __builtin_bit_cast(u32x2_t, t0), a1 = __builtin_bit_cast(u32x2_t, t1);
+    return u32x4_t{a0[0], a0[1], a1[0], a1[1]};
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// decoded rows (linear decoder)
+// ---------------------------------------------------------------------------------------------------------
+typedef const __attribute__((address_space(4))) ReconParams* RArgs;
+typedef const __attribute__((address_space(4))) ReconEntry* REntry;
+
+constexpr int kReconChunk = 256;      // tokens per workgroup: two 32-token tiles per wave
+
+// Workgroup = (256-token chunk, sequence, entry).  The wave keeps its latent rows as B operands (lane: token
+// l32, latent columns 16s + 8h .. +7 of k-step s) and walks over the KV heads of the entry; per head the
+// decoder slice [R, d_head] passes through LDS once for the four waves.
+template <typename E, int R, bool kI8>
+__global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
+    constexpr int KS = R / 16;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    RArgs p = (RArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    REntry e = &p->e[blockIdx.z];
+    const int b = blockIdx.y, chunk0 = blockIdx.x * kReconChunk;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
+    const int dh = p->d_head, n_rows = p->n_rows;
+    const int stride_w = 2 * dh + 32, cpr = dh >> 3;
+
+    u32x4_t zb[2][KS];
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+        const int t = chunk0 + wave * 64 + tile * 32 + l32;
+        const bool valid = t < n_rows;
+        const size_t row = (size_t)b * p->max_seq + (valid ? t : 0);
+        if constexpr (kI8) {
+            const RowMeta m = static_cast<const RowMeta*>(e->d.meta)[row];
+            const float inv = 1.f / m.scale;
+            const float sub = (128.f + (float)m.zeropoint) * inv;          // codes are read as unsigned bytes code + 128
+            const char* zr = static_cast<const char*>(e->d.z) + row * R + 8 * h;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const u32x2_t c = *reinterpret_cast<const u32x2_t*>(zr + 16 * s);
+                unsigned w[4];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const unsigned x = c[i] ^ 0x80808080u;
+                    const float f0 = fmaf((float)(x & 0xffu), inv, -sub), f1 = fmaf((float)((x >> 8) & 0xffu), inv, -sub);
+                    const float f2 = fmaf((float)((x >> 16) & 0xffu), inv, -sub), f3 = fmaf((float)(x >> 24), inv, -sub);
+                    w[2 * i] = Mma<E>::pack2(f0, f1);
+                    w[2 * i + 1] = Mma<E>::pack2(f2, f3);
+                }
+                zb[tile][s] = valid ? u32x4_t{w[0], w[1], w[2], w[3]} : u32x4_t{0u, 0u, 0u, 0u};
+            }
+        } else {
+            const char* zr = static_cast<const char*>(e->d.z) + (row * R + 8 * h) * 2;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (valid) v = *reinterpret_cast<const u32x4_t*>(zr + 32 * s);
+                zb[tile][s] = v;
+            }
+        }
+    }
+
+    const char* wl = static_cast<const char*>(e->d.wl);
+    const int in_width = e->d.in_width;
+    char* dst = static_cast<char*>(e->which == KVCAR_K ? p->khat : p->vhat);
+    for (int hi = 0; hi < e->n_heads; ++hi) {
+        const int g = e->head[hi], col = e->col[hi];
+        __syncthreads();                           // the previous slice is no longer read
+        for (int f = tid; f < R * cpr; f += 256) {
+            const int row = f / cpr, ch = f - row * cpr;
+            *reinterpret_cast<u32x4_t*>(lds + row * stride_w + ch * 16) =
+                *reinterpret_cast<const u32x4_t*>(wl + ((size_t)row * in_width + col) * 2 + ch * 16);
+        }
+        __syncthreads();
+        for (int mb = 0; mb < (dh >> 5); ++mb) {
+            // A operand: row = decoder column 32 mb + l32, k-slots = latent indices 16s + 8h .. +7
+            const char* wsrc = lds + (8 * h + (l16 >> 2)) * stride_w + (32 * mb + 16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
+            f32x16_t acc[2];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const u32x4_t wa = tr_pair32(wsrc + 16 * s * stride_w, 4 * stride_w);
+                acc[0] = Mma32<E>::mfma(wa, zb[0][s], acc[0]);
+                acc[1] = Mma32<E>::mfma(wa, zb[1][s], acc[1]);
+            }
+            // this lane: token l32, decoder columns 32 mb + 8a + 4h + j (register 4a + j)
+#pragma unroll
+            for (int tile = 0; tile < 2; ++tile) {
+                const int t = chunk0 + wave * 64 + tile * 32 + l32;
+                if (t >= n_rows) continue;
+                char* orow = dst + ((((size_t)b * p->n_kv_heads + g) * n_rows + t) * dh + 32 * mb + 4 * h) * 2;
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    float bias[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (e->d.bl) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) bias[j] = Elem<E>::load(e->d.bl, col + 32 * mb + 8 * a + 4 * h + j);
+                    }
+                    *reinterpret_cast<u32x2_t*>(orow + 16 * a) =
+                        u32x2_t{Mma<E>::pack2(acc[tile][4 * a] + bias[0], acc[tile][4 * a + 1] + bias[1]),
+                                Mma<E>::pack2(acc[tile][4 * a + 2] + bias[2], acc[tile][4 * a + 3] + bias[3])};
+                }
+            }
+        }
+    }
+}
+
+static bool recon_width_ok(int r) { return r == 32 || r == 64 || r == 96 || r == 128 || r == 192 || r == 256 || r == 384; }
+
+bool recon_mfma_supported(const ReconParams& p, int dtype) {
+    if (dtype == KVCAR_F32 || p.n_entries < 1) return false;
+    if (p.d_head % 32 != 0) return false;
+    for (int i = 0; i < p.n_entries; ++i) {
+        const SideDesc& sd = p.e[i].d;
+        if (sd.w1 != nullptr || !recon_width_ok(sd.r)) return false;
+        if ((size_t)sd.r * (2 * p.d_head + 32) > 150 * 1024) return false;
+        if (sd.in_width % 8 != 0) return false;
+    }
+    return true;
+}
+
+template <typename E, int R, bool kI8>
+static hipError_t launch_recon_one(const ReconParams& p, hipStream_t stream) {
+    const size_t lds = (size_t)R * (2 * p.d_head + 32);
+    auto k = recon_mfma_kernel<E, R, kI8>;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid((p.n_rows + kReconChunk - 1) / kReconChunk, p.batch, p.n_entries);
+    hipLaunchKernelGGL(k, grid, dim3(256), lds, stream, p);
+    return hipGetLastError();
+}
+
+template <typename E, bool kI8>
+static hipError_t launch_recon_width(const ReconParams& p, int r, hipStream_t stream) {
+    switch (r) {
+        case 32: return launch_recon_one<E, 32, kI8>(p, stream);
+        case 64: return launch_recon_one<E, 64, kI8>(p, stream);
+        case 96: return launch_recon_one<E, 96, kI8>(p, stream);
+        case 128: return launch_recon_one<E, 128, kI8>(p, stream);
+        case 192: return launch_recon_one<E, 192, kI8>(p, stream);
+        case 256: return launch_recon_one<E, 256, kI8>(p, stream);
+        case 384: return launch_recon_one<E, 384, kI8>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// Entries of different latent widths go out in launches of their own (the width is a template argument).
+hipError_t launch_recon_mfma(const ReconParams& p, int dtype, hipStream_t stream) {
+    bool done[kMaxReconEntries] = {};
+    for (int i = 0; i < p.n_entries; ++i) {
+        if (done[i]) continue;
+        ReconParams sub = p;
+        sub.n_entries = 0;
+        for (int k = i; k < p.n_entries; ++k)
+            if (!done[k] && p.e[k].d.r == p.e[i].d.r) { sub.e[sub.n_entries++] = p.e[k]; done[k] = true; }
+        const bool i8 = sub.e[0].d.meta != nullptr;
+        const int r = sub.e[0].d.r;
+        hipError_t err;
+        if (dtype == KVCAR_BF16) err = i8 ? launch_recon_width<BF16, true>(sub, r, stream) : launch_recon_width<BF16, false>(sub, r, stream);
+        else err = i8 ? launch_recon_width<F16, true>(sub, r, stream) : launch_recon_width<F16, false>(sub, r, stream);
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// causal attention over the decoded rows
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kKvTile = 64;           // decoded rows per LDS tile
+
+template <int DH> struct PrefillGeo {
+    static constexpr int kStrideK = 2 * DH + 16;                 // an odd number of 16-byte units: 128-bit reads hit every bank once
+    static constexpr int kStrideV = DH == 64 ? 192 : 320;        // 64 or 192 modulo 256: the transposing reads hit every bank once
+    static constexpr int kBuf = kKvTile * (kStrideK + kStrideV);
+};
+
+template <typename E, int DH, int QB>
+__global__ __launch_bounds__(256) void prefill_mfma_kernel(PrefillParams p, int n_qblk, int total_wg, int per_xcd) {
+    using G = PrefillGeo<DH>;
+    constexpr int KS = DH / 16;                 // k-steps of the score product
+    constexpr int DB = DH / 32;                 // 32-column blocks of the output
+    constexpr int TQ = 4 * 32 * QB;             // query tokens per workgroup
+    constexpr int NLD = DH / 32;                // 16-byte chunks per thread per tile and tensor
+    constexpr int CPR = DH / 8;                 // 16-byte chunks per decoded row
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    // Workgroups that share decoded rows - the query heads of one KV head of one sequence - get consecutive
+    // virtual indices, heaviest query blocks first, and the virtual index space is cut into one contiguous
+    // piece per XCD (hardware deals workgroup ids round-robin over the 8 XCDs, each with its own L2).
+    const int vid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (vid >= total_wg) return;
+    const int gq = p.n_q_heads / p.n_kv_heads;
+    const int per_pair = gq * n_qblk;
+    const int pair = vid / per_pair, rem = vid - pair * per_pair;
+    const int qblk = n_qblk - 1 - rem / gq;
+    const int b = pair / p.n_kv_heads, g = pair - b * p.n_kv_heads;
+    const int j = g * gq + rem % gq;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
+    const int i0 = qblk * TQ + wave * 32 * QB;  // first query token of this wave
+    const float c = p.scale_log2e;
+
+    // queries as B operands: lane (token l32 of block qb, half h) holds components 16s + 8h .. +7
+    u32x4_t qB[QB][KS];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int i = i0 + 32 * qb + l32;
+        const char* qrow = static_cast<const char*>(p.q) + ((((size_t)b * p.t_new + min(i, p.t_new - 1)) * p.n_q_heads + j) * DH + 8 * h) * 2;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (i < p.t_new) v = *reinterpret_cast<const u32x4_t*>(qrow + 32 * s);
+            qB[qb][s] = v;
+        }
+    }
+
+    const int wg_last = p.pos0 + min(p.t_new, (qblk + 1) * TQ) - 1;           // last position any query of the workgroup sees
+    const int n_tiles = wg_last / kKvTile + 1;
+    const int wave_tiles = i0 < p.t_new ? (p.pos0 + min(p.t_new, i0 + 32 * QB) - 1) / kKvTile + 1 : 0;
+    const char* kbase = static_cast<const char*>(p.khat) + ((size_t)b * p.n_kv_heads + g) * p.n_rows * DH * 2;
+    const char* vbase = static_cast<const char*>(p.vhat) + ((size_t)b * p.n_kv_heads + g) * p.n_rows * DH * 2;
+
+    u32x4_t stk[NLD], stv[NLD];
+    auto issue = [&](int jt) {
+        const int valid = max(0, min(kKvTile, p.n_rows - jt * kKvTile)) * CPR;
+        const size_t off = (size_t)jt * kKvTile * DH * 2;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int f = i * 256 + tid;
+            u32x4_t a = {0u, 0u, 0u, 0u}, v = {0u, 0u, 0u, 0u};
+            if (f < valid) {
+                a = *reinterpret_cast<const u32x4_t*>(kbase + off + (size_t)f * 16);
+                v = *reinterpret_cast<const u32x4_t*>(vbase + off + (size_t)f * 16);
+            }
+            stk[i] = a; stv[i] = v;
+        }
+    };
+    auto park = [&](int buf) {
+        char* kl = lds + buf * G::kBuf;
+        char* vl = kl + kKvTile * G::kStrideK;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int f = i * 256 + tid;
+            const int row = f / CPR, ch = f % CPR;
+            *reinterpret_cast<u32x4_t*>(kl + row * G::kStrideK + ch * 16) = stk[i];
+            *reinterpret_cast<u32x4_t*>(vl + row * G::kStrideV + ch * 16) = stv[i];
+        }
+    };
+
+    f32x16_t acc[QB][DB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[qb][db][v] = 0.f;
+    float m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+
+    issue(0);
+    park(0);
+    __syncthreads();
+    for (int jt = 0; jt < n_tiles; ++jt) {
+        if (jt + 1 < n_tiles) issue(jt + 1);
+        if (jt < wave_tiles) {
+            const char* kl = lds + (jt & 1) * G::kBuf;
+            const char* vl = kl + kKvTile * G::kStrideK;
+
+            // ---- scores: S^T[row, q]; this lane: query l32 of block qb, rows 32 kvb + 8a + 4h + j (register 4a + j)
+            f32x16_t s[QB][2];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) s[qb][kvb][v] = 0.f;
+            const char* krow = kl + l32 * G::kStrideK + h * 16;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int kvb = 0; kvb < 2; ++kvb) {
+                    const u32x4_t ka = *reinterpret_cast<const u32x4_t*>(krow + 32 * kvb * G::kStrideK + ks * 32);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) s[qb][kvb] = Mma32<E>::mfma(ka, qB[qb][ks], s[qb][kvb]);
+                }
+
+            u32x4_t pb[QB][2][2];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                // ---- the causal limit: only where the tile reaches past the block's first query
+                const int qpos0 = p.pos0 + i0 + 32 * qb;
+                if (jt * kKvTile + kKvTile - 1 > qpos0) {
+                    asm volatile("");                 // keeps this a branch instead of 32 selects on every tile
+                    const int lim = qpos0 + l32 - jt * kKvTile - 4 * h;          // row index in the tile, less the lane's offset, that is still visible
+#pragma unroll
+                    for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            if (32 * kvb + 8 * (v >> 2) + (v & 3) > lim) s[qb][kvb][v] = -INFINITY;
+                }
+                // ---- online softmax in base 2 (the scale rides on the exponent's multiply-add)
+                float mx = s[qb][0][0];
+#pragma unroll
+                for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kvb][v]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run[qb], mx);             // finite: the first tile holds row 0, which every query sees
+                const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c);
+                const bool rescale = m_new != m_run[qb];
+                m_run[qb] = m_new;
+                const float mc = m_new * c;
+                float sum = 0.f;
+#pragma unroll
+                for (int kvb = 0; kvb < 2; ++kvb) {
+                    float e[16];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) { e[v] = __builtin_amdgcn_exp2f(fmaf(s[qb][kvb][v], c, -mc)); sum += e[v]; }
+                    // k-step s2 of this 32-row block: rows 16 s2 + 8(e/4) + 4h + e%4 = registers 8 s2 .. 8 s2 + 7
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2)
+                        pb[qb][kvb][s2] = u32x4_t{Mma<E>::pack2(e[8 * s2], e[8 * s2 + 1]), Mma<E>::pack2(e[8 * s2 + 2], e[8 * s2 + 3]),
+                                                  Mma<E>::pack2(e[8 * s2 + 4], e[8 * s2 + 5]), Mma<E>::pack2(e[8 * s2 + 6], e[8 * s2 + 7])};
+                }
+                l_run[qb] = l_run[qb] * alpha + sum;
+                if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) acc[qb][db] *= alpha;
+                }
+            }
+
+            // ---- O^T[d, q] += V^^T . P^T
+            const char* vrow = vl + (4 * h + (l16 >> 2)) * G::kStrideV + (16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
+#pragma unroll
+            for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const u32x4_t va = tr_pair32(vrow + (32 * kvb + 16 * s2) * G::kStrideV + db * 64, 8 * G::kStrideV);
+#pragma unroll
+                        for (int qb = 0; qb < QB; ++qb) acc[qb][db] = Mma32<E>::mfma(va, pb[qb][kvb][s2], acc[qb][db]);
+                    }
+        }
+        if (jt + 1 < n_tiles) park((jt + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- normalise and store: this lane holds query l32 of block qb, components 32 db + 8a + 4h + j
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int i = i0 + 32 * qb + l32;
+        const float l_all = l_run[qb] + __shfl_xor(l_run[qb], 32);
+        if (i >= p.t_new) continue;
+        const float inv = 1.f / l_all;
+        char* orow = static_cast<char*>(p.out) + ((((size_t)b * p.t_new + i) * p.n_q_heads + j) * DH + 4 * h) * 2;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                *reinterpret_cast<u32x2_t*>(orow + (32 * db + 8 * a) * 2) =
+                    u32x2_t{Mma<E>::pack2(acc[qb][db][4 * a] * inv, acc[qb][db][4 * a + 1] * inv),
+                            Mma<E>::pack2(acc[qb][db][4 * a + 2] * inv, acc[qb][db][4 * a + 3] * inv)};
+    }
+}
+
+bool prefill_mfma_supported(const PrefillParams& p, int dtype) {
+    if (dtype == KVCAR_F32) return false;
+    if (!(p.scale_log2e > 0.f)) return false;          // the running maximum is taken on unscaled scores
+    return p.d_head == 64;
+}
+
+template <typename E, int DH, int QB>
+static hipError_t launch_prefill_one(const PrefillParams& p, hipStream_t stream) {
+    constexpr int TQ = 4 * 32 * QB;
+    const int n_qblk = (p.t_new + TQ - 1) / TQ;
+    const long long total = (long long)p.batch * p.n_q_heads * n_qblk;
+    if (total > (1ll << 30)) return hipErrorInvalidValue;
+    const int per_xcd = (int)((total + 7) / 8);
+    const size_t lds = 2 * (size_t)PrefillGeo<DH>::kBuf;
+    auto k = prefill_mfma_kernel<E, DH, QB>;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(k, dim3(per_xcd * 8), dim3(256), lds, stream, p, n_qblk, (int)total, per_xcd);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill_mfma(const PrefillParams& p, int dtype, int /*n_cu*/, hipStream_t stream) {
+    if (dtype == KVCAR_BF16) return launch_prefill_one<BF16, 64, 2>(p, stream);
+    return launch_prefill_one<F16, 64, 2>(p, stream);
+}
+
+}  // namespace kvcar

@@ -107,3 +107,14 @@ class Session:
             out = torch.empty_like(q)
         self.ctx.decode_attention(layer, q, out, b, n_ctx, self.workspace)
         return out
+
+    def prefill_attention(self, layer: int, q: torch.Tensor, pos0: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """q [batch, t_new, H_q, d_head]: causal attention of the chunk at positions pos0.. over the caches."""
+        b, t = q.shape[0], q.shape[1]
+        need = self.ctx.prefill_workspace_bytes(b, pos0 + t)
+        if getattr(self, "prefill_ws", None) is None or self.prefill_ws.numel() < need:
+            self.prefill_ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        if out is None:
+            out = torch.empty_like(q)
+        self.ctx.prefill_attention(layer, q, out, b, pos0, t, self.prefill_ws)
+        return out

@@ -91,7 +91,7 @@ TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat1
 DTYPE_BYTES = {"f32": 4, "f16": 2, "bf16": 2}
 
 # stream purposes
-_P_WEIGHT, _P_KV, _P_Q, _P_REUSE, _P_BIAS, _P_LATENT = 1, 2, 3, 4, 5, 6
+_P_WEIGHT, _P_KV, _P_Q, _P_REUSE, _P_BIAS, _P_LATENT, _P_PROMPT_Q = 1, 2, 3, 4, 5, 6, 7
 
 
 @dataclasses.dataclass(frozen=True)
@@ -241,6 +241,19 @@ def queries(w: Workload, layer: int, step: int, device="cpu", gain: float = 1.0)
     """q ~ N(0,1) * gain for one decode step: fp32 [batch, H_q, d_head]."""
     key = stream_key(w.seed, _P_Q, layer, step)
     return _round(normal(key, (w.batch, w.n_q_heads, w.d_head), device=device) * gain, w.dtype)
+
+
+def prompt_queries(w: Workload, layer: int, b0: int, b1: int, t0: int, t1: int, device="cpu",
+                   gain: float = 1.0) -> torch.Tensor:
+    """q ~ N(0,1) * gain of the prompt tokens at positions [t0,t1) of sequences [b0,b1):
+    fp32 [b1-b0, t1-t0, H_q, d_head], dtype-representable.  Any slice can be generated on its own."""
+    key = stream_key(w.seed, _P_PROMPT_Q, layer)
+    d = w.n_q_heads * w.d_head
+    b = torch.arange(b0, b1, dtype=torch.int64, device=device).view(-1, 1, 1)
+    t = torch.arange(t0, t1, dtype=torch.int64, device=device).view(1, -1, 1)
+    c = torch.arange(d, dtype=torch.int64, device=device).view(1, 1, -1)
+    idx = (b * w.max_seq + t) * d + c
+    return _round(normal_at(key, idx) * gain, w.dtype).view(b1 - b0, t1 - t0, w.n_q_heads, w.d_head)
 
 
 def latent_rows(w: Workload, layer: int, which: int, latent: int, b0: int, b1: int, t0: int, t1: int,

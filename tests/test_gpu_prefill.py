@@ -1,0 +1,134 @@
+"""GPU parity of prefill attention over the latent cache: kvcar_prefill_attention, through the C ABI,
+against the oracle's prefill form on the same seeded inputs, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_06727_amd import synth
+from tests.helpers import ABS_TOL, REL_TOL, build_oracle, oracle_prefill
+
+pytestmark = pytest.mark.gpu
+
+C = synth.CONFIGS
+
+
+def run_both(w, n_prompt, chunks, layers=None, gain=1.0, with_bias=False, reuse=None, **session_kw):
+    """Fill the caches with n_prompt tokens, then run the prompt's queries through the oracle in one
+    piece and through the library chunk by chunk (chunks = [(pos0, t_new), ..] covering the prompt)."""
+    from paper_2512_06727_amd.harness import Session
+    lay = list(range(w.n_layers)) if layers is None else layers
+    fmt = session_kw.get("latent_format", "dtype")
+    orc = build_oracle(w, reuse=reuse, with_bias=with_bias, latent_format=fmt)
+    for n in range(w.n_layers):
+        oracle_prefill(orc, w, n, 0, n_prompt)
+    ses = Session(w, reuse=reuse, with_bias=with_bias, poison=True, **session_kw)
+    ses.prefill(0, n_prompt, chunk=256)
+    got, want = {}, {}
+    for n in lay:
+        q = synth.prompt_queries(w, n, 0, w.batch, 0, n_prompt, gain=gain)
+        want[n] = orc.prefill_attention(n, q.double().numpy(), 0)
+        outs = []
+        for pos0, t_new in chunks:
+            qc = q[:, pos0:pos0 + t_new].contiguous().to(ses.dev, ses.tdt)
+            outs.append(ses.prefill_attention(n, qc, pos0).float().cpu().double().numpy())
+        got[n] = np.concatenate(outs, axis=1)
+    torch.cuda.synchronize()
+    return got, want
+
+
+def assert_close(w, got, want, label):
+    for n in want:
+        g, o = got[n], want[n]
+        assert g.shape == o.shape
+        assert np.isfinite(g).all(), f"{label} layer {n}: non-finite output"
+        err = np.abs(g - o)
+        # outputs of O(1) (a sharp softmax returns single value rows) carry the rounding of the decoded rows
+        # and of the result to the model dtype: one unit of either in addition to the absolute bound
+        ulp = {"f32": 2.0 ** -22, "f16": 2.0 ** -10, "bf16": 2.0 ** -7}[w.dtype]
+        assert (err <= ABS_TOL[w.dtype] + ulp * np.abs(o)).all(), f"{label} layer {n}: max abs err {err.max():.3e}"
+        assert err.max() <= REL_TOL[w.dtype] * np.abs(o).max(), f"{label} layer {n}: err {err.max():.3e} vs max |ref| {np.abs(o).max():.3e}"
+
+
+CASES = {
+    # fp32, GPT-2 shape: the plain-ALU kernels, one chunk and a ragged split into three
+    "c0-f32": (C[0].scaled(n_cached=150), 150, [(0, 150)], {}),
+    "c0-f32-chunks": (C[0].scaled(n_cached=150, batch=2, n_layers=2, reuse="odd:5"), 150, [(0, 64), (64, 1), (65, 85)], {"with_bias": True}),
+    # TinyLlama shape, bf16, grouped heads, a reused head per layer (chains): matrix-core kernels; 333 tokens =
+    # one full 256-token query block plus a ragged one, and a tail of the decoded-row tiles
+    "c2-bf16": (C[2].scaled(n_layers=4, batch=2, n_cached=333), 333, [(0, 333)], {}),
+    "c2-bf16-chunks": (C[2].scaled(n_layers=3, batch=3, n_cached=700), 700, [(0, 300), (300, 400)], {"with_bias": True}),
+    # Bernoulli(0.3) map under both policies: layers storing 0..4 heads, narrow latents (96, 64, 32)
+    "c4-bf16": (C[4].scaled(n_layers=8, batch=2, n_cached=300), 300, [(0, 300)], {}),
+    "c4-bf16-p2": (C[4].scaled(n_layers=6, batch=2, n_cached=200, policy="P2"), 200, [(0, 200)], {}),
+    # fp16, GPT-2 shape (12 KV heads, latent 384 / 288)
+    "c1-f16": (C[1].scaled(n_layers=4, batch=2, n_cached=260), 260, [(0, 260)], {}),
+    # two-layer GELU / LeakyReLU decoders
+    "c3-mlp": (C[3].scaled(n_layers=2, batch=2, n_cached=140), 140, [(0, 140)], {}),
+    "mlp-leaky": (C[3].scaled(n_layers=3, batch=2, n_cached=100, act="leaky_relu", reuse="from2:1", policy="P2"), 100, [(0, 100)],
+                  {"with_bias": True}),
+    # int8 latent rows
+    "c2-int8": (C[2].scaled(n_layers=3, batch=2, n_cached=280), 280, [(0, 280)], {"latent_format": "int8"}),
+    "c3-mlp-int8": (C[3].scaled(n_layers=2, batch=2, n_cached=90), 90, [(0, 90)], {"latent_format": "int8"}),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("gain", [1.0, 30.0])
+def test_prefill_parity(name, gain):
+    w, n_prompt, chunks, kw = CASES[name]
+    print(f"case {name} gain {gain} {w}", flush=True)
+    got, want = run_both(w, n_prompt, chunks, gain=gain, **kw)
+    assert_close(w, got, want, f"{name} gain={gain}")
+
+
+@pytest.mark.parametrize("name", ["c2-bf16", "c4-bf16", "c1-f16", "c2-int8"])
+def test_prefill_plain_alu_kernels_on_16bit(name):
+    w, n_prompt, chunks, kw = CASES[name]
+    got, want = run_both(w, n_prompt, chunks, gain=10.0, force_generic=True, **kw)
+    assert_close(w, got, want, name + "-generic")
+
+
+def test_prefill_single_token_and_partial_batch():
+    """t_new = 1 at position 0 (the output is the token's own decoded value row) and at a later position
+    (a decode step), with a batch smaller than max_batch."""
+    w = C[2].scaled(n_layers=2, batch=2, n_cached=130, reuse="none")
+    got, want = run_both(w, 130, [(i, 1) for i in range(3)] + [(3, 126), (129, 1)], max_batch=5)
+    assert_close(w, got, want, "single tokens")
+
+
+def test_prefill_agrees_with_decode_steps():
+    """The last token of a chunk through kvcar_prefill_attention and through kvcar_decode_attention."""
+    from paper_2512_06727_amd.harness import Session
+    w = C[2].scaled(n_layers=3, batch=2, n_cached=200)
+    ses = Session(w)
+    ses.prefill(0, 200, chunk=256)
+    for n in range(3):
+        q = synth.prompt_queries(w, n, 0, w.batch, 0, 200, gain=8.0).to(ses.dev, ses.tdt)
+        pre = ses.prefill_attention(n, q, 0).float()
+        for i in (0, 63, 64, 199):
+            dec = ses.decode_attention(n, q[:, i].contiguous(), i + 1).float()
+            assert (pre[:, i] - dec).abs().max().item() <= 2 * ABS_TOL[w.dtype]
+
+
+def test_prefill_argument_errors():
+    from paper_2512_06727_amd import binding
+    from paper_2512_06727_amd.harness import Session
+    w = C[2].scaled(n_layers=1, batch=2, n_cached=64, n_steps=0)
+    ses = Session(w)
+    ses.prefill(0, 64)
+    q = synth.prompt_queries(w, 0, 0, 2, 0, 64).to(ses.dev, ses.tdt)
+    out = torch.empty_like(q)
+    ws = torch.empty(ses.ctx.prefill_workspace_bytes(2, 64), dtype=torch.uint8, device=ses.dev)
+    for args, status in (((0, q, out, 2, 1, 64, ws), binding.ERR_CAPACITY),          # pos0 + t_new > max_seq
+                         ((0, q, out, 3, 0, 64, ws), binding.ERR_CAPACITY),          # batch > max_batch
+                         ((0, q, out, 2, 0, 0, ws), binding.ERR_ARG),
+                         ((0, q, out, 2, -1, 8, ws), binding.ERR_ARG),
+                         ((1, q, out, 2, 0, 64, ws), binding.ERR_ARG),               # layer out of range
+                         ((0, q, out, 2, 0, 64, ws[:1024]), binding.ERR_WORKSPACE),
+                         ((0, None, out, 2, 0, 64, ws), binding.ERR_ARG)):
+        with pytest.raises(binding.KVCARError) as ei:
+            ses.ctx.prefill_attention(*args)
+        assert ei.value.status == status
+    ses.ctx.prefill_attention(0, q, out, 2, 0, 64, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
