@@ -158,6 +158,101 @@ def bench_l1_distance(args):
     }))
 
 
+MFMA_PEAK_TFLOPS = 2500.0    # MI355X published dense bf16 / fp16 matrix rate
+
+
+def bench_prefill(args):
+    """Secondary measurement: the prompt phase.  A step = for every layer, kvcar_encode_append of the whole
+    prompt chunk (T tokens per sequence) followed by kvcar_prefill_attention of the chunk over the latent
+    caches.  Bound by the matrix units: the roofline object is the causal attention kernel against the dense
+    16-bit MFMA peak, with 4 * H_q * d_head flops per (query, visible row) pair."""
+    import numpy as np
+    import torch
+    from oracle import kvcar_oracle as O
+    from paper_2512_06727_amd import synth
+    from paper_2512_06727_amd.harness import Session
+
+    base = synth.CONFIGS[args.workload]
+    w = base.scaled(batch=args.batch or 16, n_cached=args.cached or 4096, n_steps=0)
+    if args.policy:
+        w = w.scaled(policy=args.policy)
+    if args.no_reuse:
+        w = w.scaled(reuse="none")
+    reuse = synth.reuse_map(w)
+    T = w.n_cached
+    ses = Session(w, reuse=reuse, latent_format=args.latent)
+    dev, tdt = ses.dev, ses.tdt
+    chunk = max(1, (1 << 25) // (w.batch * w.d_kv))
+    gen = lambda f: torch.cat([f(c0, min(T, c0 + chunk)) for c0 in range(0, T, chunk)], dim=1).contiguous()
+    ks = [gen(lambda a, b: synth.kv_tokens(w, n, 0, 0, w.batch, a, b, device=dev).to(tdt)) for n in range(w.n_layers)]
+    vs = [gen(lambda a, b: synth.kv_tokens(w, n, 1, 0, w.batch, a, b, device=dev).to(tdt)) for n in range(w.n_layers)]
+    qs = [gen(lambda a, b: synth.prompt_queries(w, n, 0, w.batch, a, b, device=dev).to(tdt)) for n in range(w.n_layers)]
+    out = torch.empty_like(qs[0])
+    ws = torch.empty(ses.ctx.prefill_workspace_bytes(w.batch, T), dtype=torch.uint8, device=dev)
+    ctx = ses.ctx
+
+    def step_fn():
+        for n in range(w.n_layers):
+            ctx.encode_append(n, ks[n], vs[n], w.batch, 0, T)
+            ctx.prefill_attention(n, qs[n], out, w.batch, 0, T, ws)
+
+    for _ in range(args.warmup):
+        step_fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_fn()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    ctx.profile_enable(True)
+    for _ in range(args.steps):
+        step_fn()
+    attend_ms, n_launch = ctx.profile_read()
+    ctx.profile_enable(False)
+    pairs = w.batch * T * (T + 1) // 2                                  # (query, visible row) pairs per layer
+    flops = 4 * w.n_q_heads * w.d_head * pairs                          # per attention launch
+    achieved = flops / (attend_ms / n_launch * 1e-3) / 1e12
+
+    result = {
+        "metric": "prefill tokens/s over latent KV cache (encode + causal attention, all layers)", "value": w.batch * T * args.steps / elapsed,
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "op": "prefill", "batch": w.batch, "prompt_tokens": T, "layers": w.n_layers, "q_heads": w.n_q_heads,
+                   "kv_heads": w.n_kv_heads, "d_head": w.d_head, "latent": w.latent, "hidden": w.hidden, "latent_format": args.latent,
+                   "reuse": w.reuse, "policy": w.policy},
+        "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None, "algorithmic_flops_per_launch": flops,
+                     "avg_launch_ms": attend_ms / n_launch, "launches": n_launch,
+                     "attention_share_of_step": attend_ms / args.steps / ms_per_step},
+    }
+    if args.cpu_seconds > 0:
+        # the oracle on one (layer, sequence) unit of the same prompt (shortened if the budget asks for it)
+        t_s = T if args.cpu_seconds >= 10 else min(T, 1024)
+        wo = w.scaled(batch=1)
+        orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, 1, T, w.dtype, latent_format=args.latent)
+        cv = lambda pairs_: [(a.double().numpy(), None if b is None else b.double().numpy()) for a, b in pairs_]
+        for which in (0, 1):
+            ae = synth.autoencoder(w, 0, which, reuse)
+            orc.set_autoencoder(0, which, O.Autoencoder(ae.heads, cv(ae.enc), cv(ae.dec), act=ae.act, slope=ae.slope))
+        k = synth.kv_tokens(wo, 0, 0, 0, 1, 0, t_s).double().numpy()
+        v = synth.kv_tokens(wo, 0, 1, 0, 1, 0, t_s).double().numpy()
+        q = synth.prompt_queries(wo, 0, 0, 1, 0, t_s).double().numpy()
+        from threadpoolctl import threadpool_info
+        t0 = time.perf_counter()
+        orc.encode_append(0, k, v, 0)
+        want = orc.prefill_attention(0, q, 0)
+        t_cpu = time.perf_counter() - t0
+        got = ses.prefill_attention(0, qs[0][:1, :t_s].contiguous(), 0).float().cpu().double().numpy()
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [torch.get_num_threads(), 1])
+        # cost grows with the square of the prompt: scale the unit to the full prompt before extrapolating
+        unit_s = t_cpu * (T * (T + 1)) / (t_s * (t_s + 1))
+        result["cpu_baseline"] = {"value": w.batch * T / (unit_s * w.n_layers * w.batch), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+                                  "sample": f"layer 0, sequence 0, first {t_s} prompt tokens: {t_cpu:.1f} s, scaled by visible pairs to {T} tokens "
+                                            f"and to {w.n_layers} layers x {w.batch} sequences; max |GPU - oracle| on the sample {np.abs(got - want).max():.2e}"}
+    print(json.dumps(result))
+
+
 def capacity_check(args):
     """Capacity leg (the analogue of the paper's maximum-sequence-length-before-OOM measurement, Results,
     "System Evaluation"): allocate latent caches for as many cached tokens as fit in this GPU's free memory
@@ -258,8 +353,9 @@ def main():
                     help="cache: append the new token, attend over the cache (default, the headline); exact: attend over the cached "
                          "rows plus the current token's exact K/V row (kvcar_decode_attention_ex), then append; ragged: per-sequence "
                          "context lengths drawn uniformly from [n_cached/2, n_cached]")
-    ap.add_argument("--op", default="decode", choices=["decode", "l1dist"],
-                    help="decode: the decode step (default, the headline); l1dist: the reuse-map selection statistic over the workload's tokens")
+    ap.add_argument("--op", default="decode", choices=["decode", "l1dist", "prefill"],
+                    help="decode: the decode step (default, the headline); l1dist: the reuse-map selection statistic over the workload's tokens; "
+                         "prefill: encode + causal attention of a whole prompt (default batch 16 x 4096 tokens of the chosen workload's shape)")
     ap.add_argument("--no-fuse", action="store_true", help="run prologue / attention / merge as separate kernels")
     ap.add_argument("--capacity-check", action="store_true",
                     help="allocate latent caches for as many tokens as fit in free HBM, run one decode step over them, report")
@@ -281,6 +377,8 @@ def main():
     binding.lib()
     if args.op == "l1dist":
         return bench_l1_distance(args)
+    if args.op == "prefill":
+        return bench_prefill(args)
     if args.capacity_check:
         return capacity_check(args)
     base = synth.CONFIGS[args.workload]

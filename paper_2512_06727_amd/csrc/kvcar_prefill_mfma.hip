@@ -224,7 +224,7 @@ template <int DH> struct PrefillGeo {
 };
 
 template <typename E, int DH, int QB>
-__global__ __launch_bounds__(256) void prefill_mfma_kernel(PrefillParams p, int n_qblk, int total_wg, int per_xcd) {
+__global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillParams p, int n_qblk, int total_wg, int per_xcd) {
     using G = PrefillGeo<DH>;
     constexpr int KS = DH / 16;                 // k-steps of the score product
     constexpr int DB = DH / 32;                 // 32-column blocks of the output
@@ -317,81 +317,74 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(PrefillParams p, int 
             const char* kl = lds + (jt & 1) * G::kBuf;
             const char* vl = kl + kKvTile * G::kStrideK;
 
-            // ---- scores: S^T[row, q]; this lane: query l32 of block qb, rows 32 kvb + 8a + 4h + j (register 4a + j)
-            f32x16_t s[QB][2];
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) s[qb][kvb][v] = 0.f;
             const char* krow = kl + l32 * G::kStrideK + h * 16;
+            const char* vrow = vl + (4 * h + (l16 >> 2)) * G::kStrideV + (16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
+            // the tile in two halves of 32 rows: scores, softmax and the output product of a half need half the registers
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
+            for (int kvb = 0; kvb < 2; ++kvb) {
+                // ---- scores: S^T[row, q]; this lane: query l32 of block qb, rows 32 kvb + 8a + 4h + j (register 4a + j)
+                f32x16_t s[QB];
 #pragma unroll
-                for (int kvb = 0; kvb < 2; ++kvb) {
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) s[qb][v] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
                     const u32x4_t ka = *reinterpret_cast<const u32x4_t*>(krow + 32 * kvb * G::kStrideK + ks * 32);
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) s[qb][kvb] = Mma32<E>::mfma(ka, qB[qb][ks], s[qb][kvb]);
+                    for (int qb = 0; qb < QB; ++qb) s[qb] = Mma32<E>::mfma(ka, qB[qb][ks], s[qb]);
                 }
 
-            u32x4_t pb[QB][2][2];
+                u32x4_t pb[QB][2];
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                // ---- the causal limit: only where the tile reaches past the block's first query
-                const int qpos0 = p.pos0 + i0 + 32 * qb;
-                if (jt * kKvTile + kKvTile - 1 > qpos0) {
-                    asm volatile("");                 // keeps this a branch instead of 32 selects on every tile
-                    const int lim = qpos0 + l32 - jt * kKvTile - 4 * h;          // row index in the tile, less the lane's offset, that is still visible
-#pragma unroll
-                    for (int kvb = 0; kvb < 2; ++kvb)
+                for (int qb = 0; qb < QB; ++qb) {
+                    // ---- the causal limit: only where the half reaches past the block's first query
+                    const int qpos0 = p.pos0 + i0 + 32 * qb;
+                    const int row0 = jt * kKvTile + 32 * kvb;
+                    if (row0 + 31 > qpos0) {
+                        asm volatile("");             // keeps this a branch instead of 16 selects on every half
+                        const int lim = qpos0 + l32 - row0 - 4 * h;      // last visible row of the half, less this lane's row offset
 #pragma unroll
                         for (int v = 0; v < 16; ++v)
-                            if (32 * kvb + 8 * (v >> 2) + (v & 3) > lim) s[qb][kvb][v] = -INFINITY;
-                }
-                // ---- online softmax in base 2 (the scale rides on the exponent's multiply-add)
-                float mx = s[qb][0][0];
+                            if (8 * (v >> 2) + (v & 3) > lim) s[qb][v] = -INFINITY;
+                    }
+                    // ---- online softmax in base 2 (the scale rides on the exponent's multiply-add)
+                    float mx = fmaxf(fmaxf(s[qb][0], s[qb][1]), s[qb][2]);
 #pragma unroll
-                for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kvb][v]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run[qb], mx);             // finite: the first tile holds row 0, which every query sees
-                const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c);
-                const bool rescale = m_new != m_run[qb];
-                m_run[qb] = m_new;
-                const float mc = m_new * c;
-                float sum = 0.f;
-#pragma unroll
-                for (int kvb = 0; kvb < 2; ++kvb) {
+                    for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s[qb][v]), s[qb][v + 1]);
+                    mx = fmaxf(mx, s[qb][15]);
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    const float m_new = fmaxf(m_run[qb], mx);         // finite: the first half holds row 0, which every query sees
+                    const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c);
+                    const bool rescale = m_new != m_run[qb];
+                    m_run[qb] = m_new;
+                    const float mc = m_new * c;
                     float e[16];
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) { e[v] = __builtin_amdgcn_exp2f(fmaf(s[qb][kvb][v], c, -mc)); sum += e[v]; }
-                    // k-step s2 of this 32-row block: rows 16 s2 + 8(e/4) + 4h + e%4 = registers 8 s2 .. 8 s2 + 7
+                    for (int v = 0; v < 16; ++v) e[v] = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c, -mc));
+                    l_run[qb] = l_run[qb] * alpha + ((((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]))) +
+                                                     (((e[8] + e[9]) + (e[10] + e[11])) + ((e[12] + e[13]) + (e[14] + e[15]))));
+                    // k-step s2 of the half: rows 16 s2 + 8(e/4) + 4h + e%4 = registers 8 s2 .. 8 s2 + 7
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2)
-                        pb[qb][kvb][s2] = u32x4_t{Mma<E>::pack2(e[8 * s2], e[8 * s2 + 1]), Mma<E>::pack2(e[8 * s2 + 2], e[8 * s2 + 3]),
-                                                  Mma<E>::pack2(e[8 * s2 + 4], e[8 * s2 + 5]), Mma<E>::pack2(e[8 * s2 + 6], e[8 * s2 + 7])};
-                }
-                l_run[qb] = l_run[qb] * alpha + sum;
-                if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
+                        pb[qb][s2] = u32x4_t{Mma<E>::pack2(e[8 * s2], e[8 * s2 + 1]), Mma<E>::pack2(e[8 * s2 + 2], e[8 * s2 + 3]),
+                                             Mma<E>::pack2(e[8 * s2 + 4], e[8 * s2 + 5]), Mma<E>::pack2(e[8 * s2 + 6], e[8 * s2 + 7])};
+                    if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
 #pragma unroll
-                    for (int db = 0; db < DB; ++db) acc[qb][db] *= alpha;
+                        for (int db = 0; db < DB; ++db) acc[qb][db] *= alpha;
+                    }
                 }
-            }
 
-            // ---- O^T[d, q] += V^^T . P^T
-            const char* vrow = vl + (4 * h + (l16 >> 2)) * G::kStrideV + (16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
-#pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb)
+                // ---- O^T[d, q] += V^^T . P^T
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
                     for (int db = 0; db < DB; ++db) {
                         const u32x4_t va = tr_pair32(vrow + (32 * kvb + 16 * s2) * G::kStrideV + db * 64, 8 * G::kStrideV);
 #pragma unroll
-                        for (int qb = 0; qb < QB; ++qb) acc[qb][db] = Mma32<E>::mfma(va, pb[qb][kvb][s2], acc[qb][db]);
+                        for (int qb = 0; qb < QB; ++qb) acc[qb][db] = Mma32<E>::mfma(va, pb[qb][s2], acc[qb][db]);
                     }
+            }
         }
         if (jt + 1 < n_tiles) park((jt + 1) & 1);
         __syncthreads();
