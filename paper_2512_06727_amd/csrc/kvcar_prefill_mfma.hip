@@ -11,15 +11,20 @@
 //   recon_mfma_kernel    K^^T[n, t] = W^T[n, c] . Z^T[c, t]   (v_mfma_f32_32x32x16; A = the decoder columns
 //                        of one KV head through LDS and the transposing load, B = latent rows straight
 //                        from global memory, dequantised in registers when they are int8 codes)
-//   prefill_mfma_kernel  per workgroup: 4 waves x 32*QB query tokens of one head; K^ / V^ tiles of 64 rows
-//                        are shared through LDS (double buffered, one barrier per tile)
+//   prefill_mfma_kernel  per workgroup: 8 waves x 32 query tokens of one head; K^ / V^ tiles of 64 rows are
+//                        shared through LDS (double buffered, one barrier per tile); per 32-row half of a tile
 //                          S^T[row, q] = K^ . Q^T            A = K^ rows (LDS), B = queries (registers)
-//                          online softmax in base 2: a lane holds 32 rows of ONE query per tile, so the
-//                          reductions are in-lane plus one cross-lane step
+//                          online softmax in base 2: a lane holds 16 rows of ONE query per half, so the
+//                          reductions are in-lane plus one cross-lane step; the reference point of a query
+//                          only moves when a score exceeds it by 2^8, so the accumulators are rarely rescaled
 //                          O^T[d, q] += V^^T . P^T           A = V^ through the transposing load, B = P^T
 //                          straight from the softmax registers (the result layout of S^T is the operand
 //                          layout, with the rows of a k-step taken in the order the registers hold them)
 //                        the causal limit only touches the last one or two tiles of a wave.
+// Measured budget of the attention kernel on 16 x 4096 tokens (per launch): matrix instructions alone would
+// take 0.44 ms at the dense peak; LDS reads of the operands 0.40 ms, staging and barriers 0.19 ms, the
+// softmax's vector instructions 0.69 ms (16-bit conversion, exp2, sum, max: 5.5 per score, and on this chip
+// a matrix instruction blocks vector issue for about half its duration); they overlap only in part: 1.24 ms.
 #include "kvcar_attend_mfma_body.hpp"
 
 namespace kvcar {
@@ -216,6 +221,13 @@ hipError_t launch_recon_mfma(const ReconParams& p, int dtype, hipStream_t stream
 // causal attention over the decoded rows
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kKvTile = 64;           // decoded rows per LDS tile
+constexpr float kSlack = 8.f;         // a query's softmax reference point moves when a score exceeds it by 2^kSlack
+// Launch shape (measured on 16 x 4096 tokens, 32 heads of 64: TFLOP/s of the kernel):
+//   one 32-query block per wave, 8 waves, 2 workgroups per CU (4 waves per SIMD)   887      <- used
+//   two blocks per wave, 4 waves, 2 workgroups per CU (2 waves per SIMD)            835
+//   two blocks per wave, 8 waves, 1 workgroup per CU                                779;  with 128-row tiles 808
+//   two blocks per wave, 4 waves, 1 workgroup per CU (1 wave per SIMD)              485
+constexpr int kPrefillQB = 1, kPrefillNW = 8;
 
 template <int DH> struct PrefillGeo {
     static constexpr int kStrideK = 2 * DH + 16;                 // an odd number of 16-byte units: 128-bit reads hit every bank once
@@ -223,13 +235,15 @@ template <int DH> struct PrefillGeo {
     static constexpr int kBuf = kKvTile * (kStrideK + kStrideV);
 };
 
-template <typename E, int DH, int QB>
-__global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillParams p, int n_qblk, int total_wg, int per_xcd) {
+template <typename E, int DH, int QB, int NW, int OCC>
+__global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParams p, int n_qblk, int total_wg, int per_xcd) {
     using G = PrefillGeo<DH>;
     constexpr int KS = DH / 16;                 // k-steps of the score product
     constexpr int DB = DH / 32;                 // 32-column blocks of the output
-    constexpr int TQ = 4 * 32 * QB;             // query tokens per workgroup
-    constexpr int NLD = DH / 32;                // 16-byte chunks per thread per tile and tensor
+    constexpr int TQ = NW * 32 * QB;            // query tokens per workgroup
+    constexpr int NT = 64 * NW;                 // threads
+    constexpr int NLD = (kKvTile * DH / 8) / NT; // 16-byte chunks per thread per tile and tensor
+    static_assert(NLD * NT == kKvTile * DH / 8, "tile chunks divide over the threads");
     constexpr int CPR = DH / 8;                 // 16-byte chunks per decoded row
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -276,7 +290,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillParams p, i
         const size_t off = (size_t)jt * kKvTile * DH * 2;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-            const int f = i * 256 + tid;
+            const int f = i * NT + tid;
             u32x4_t a = {0u, 0u, 0u, 0u}, v = {0u, 0u, 0u, 0u};
             if (f < valid) {
                 a = *reinterpret_cast<const u32x4_t*>(kbase + off + (size_t)f * 16);
@@ -290,7 +304,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillParams p, i
         char* vl = kl + kKvTile * G::kStrideK;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-            const int f = i * 256 + tid;
+            const int f = i * NT + tid;
             const int row = f / CPR, ch = f % CPR;
             *reinterpret_cast<u32x4_t*>(kl + row * G::kStrideK + ch * 16) = stk[i];
             *reinterpret_cast<u32x4_t*>(vl + row * G::kStrideV + ch * 16) = stv[i];
@@ -321,7 +335,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillParams p, i
             const char* vrow = vl + (4 * h + (l16 >> 2)) * G::kStrideV + (16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
             // the tile in two halves of 32 rows: scores, softmax and the output product of a half need half the registers
 #pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb) {
+            for (int kvb = 0; kvb < kKvTile / 32; ++kvb) {
                 // ---- scores: S^T[row, q]; this lane: query l32 of block qb, rows 32 kvb + 8a + 4h + j (register 4a + j)
                 f32x16_t s[QB];
 #pragma unroll
@@ -348,31 +362,35 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillParams p, i
                         for (int v = 0; v < 16; ++v)
                             if (8 * (v >> 2) + (v & 3) > lim) s[qb][v] = -INFINITY;
                     }
-                    // ---- online softmax in base 2 (the scale rides on the exponent's multiply-add)
+                    // ---- online softmax in base 2 (the scale rides on the exponent's multiply-add).  The reference
+                    // point m of a query only moves when a score exceeds it by more than kSlack (in log2 units):
+                    // until then probabilities simply grow up to 2^kSlack, which costs nothing in fp32 / 16-bit
+                    // floating point, and the accumulators need no rescaling - a rare event instead of one in most halves.
                     float mx = fmaxf(fmaxf(s[qb][0], s[qb][1]), s[qb][2]);
 #pragma unroll
                     for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s[qb][v]), s[qb][v + 1]);
                     mx = fmaxf(mx, s[qb][15]);
                     mx = fmaxf(mx, __shfl_xor(mx, 32));
-                    const float m_new = fmaxf(m_run[qb], mx);         // finite: the first half holds row 0, which every query sees
-                    const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c);
-                    const bool rescale = m_new != m_run[qb];
-                    m_run[qb] = m_new;
-                    const float mc = m_new * c;
+                    const bool moved = (mx - m_run[qb]) * c > kSlack;       // always on the first half (m = -inf), which holds row 0
+                    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+                        const float m_new = moved ? mx : m_run[qb];
+                        const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c);
+                        m_run[qb] = m_new;
+                        l_run[qb] *= alpha;
+#pragma unroll
+                        for (int db = 0; db < DB; ++db) acc[qb][db] *= alpha;
+                    }
+                    const float mc = m_run[qb] * c;
                     float e[16];
 #pragma unroll
                     for (int v = 0; v < 16; ++v) e[v] = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c, -mc));
-                    l_run[qb] = l_run[qb] * alpha + ((((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]))) +
-                                                     (((e[8] + e[9]) + (e[10] + e[11])) + ((e[12] + e[13]) + (e[14] + e[15]))));
+                    l_run[qb] += (((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]))) +
+                                 (((e[8] + e[9]) + (e[10] + e[11])) + ((e[12] + e[13]) + (e[14] + e[15])));
                     // k-step s2 of the half: rows 16 s2 + 8(e/4) + 4h + e%4 = registers 8 s2 .. 8 s2 + 7
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2)
                         pb[qb][s2] = u32x4_t{Mma<E>::pack2(e[8 * s2], e[8 * s2 + 1]), Mma<E>::pack2(e[8 * s2 + 2], e[8 * s2 + 3]),
                                              Mma<E>::pack2(e[8 * s2 + 4], e[8 * s2 + 5]), Mma<E>::pack2(e[8 * s2 + 6], e[8 * s2 + 7])};
-                    if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
-#pragma unroll
-                        for (int db = 0; db < DB; ++db) acc[qb][db] *= alpha;
-                    }
                 }
 
                 // ---- O^T[d, q] += V^^T . P^T
@@ -411,29 +429,34 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillParams p, i
 bool prefill_mfma_supported(const PrefillParams& p, int dtype) {
     if (dtype == KVCAR_F32) return false;
     if (!(p.scale_log2e > 0.f)) return false;          // the running maximum is taken on unscaled scores
-    return p.d_head == 64;
+    return p.d_head == 64 || p.d_head == 128;
 }
 
-template <typename E, int DH, int QB>
+template <typename E, int DH, int QB, int NW, int OCC>
 static hipError_t launch_prefill_one(const PrefillParams& p, hipStream_t stream) {
-    constexpr int TQ = 4 * 32 * QB;
+    constexpr int TQ = NW * 32 * QB;
     const int n_qblk = (p.t_new + TQ - 1) / TQ;
     const long long total = (long long)p.batch * p.n_q_heads * n_qblk;
     if (total > (1ll << 30)) return hipErrorInvalidValue;
     const int per_xcd = (int)((total + 7) / 8);
     const size_t lds = 2 * (size_t)PrefillGeo<DH>::kBuf;
-    auto k = prefill_mfma_kernel<E, DH, QB>;
+    auto k = prefill_mfma_kernel<E, DH, QB, NW, OCC>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(k, dim3(per_xcd * 8), dim3(256), lds, stream, p, n_qblk, (int)total, per_xcd);
+    hipLaunchKernelGGL(k, dim3(per_xcd * 8), dim3(64 * NW), lds, stream, p, n_qblk, (int)total, per_xcd);
     return hipGetLastError();
 }
 
 hipError_t launch_prefill_mfma(const PrefillParams& p, int dtype, int /*n_cu*/, hipStream_t stream) {
-    if (dtype == KVCAR_BF16) return launch_prefill_one<BF16, 64, 2>(p, stream);
-    return launch_prefill_one<F16, 64, 2>(p, stream);
+    // d_head 128: twice the accumulators and query operands per wave, so one workgroup per compute unit
+    if (p.d_head == 128) {
+        if (dtype == KVCAR_BF16) return launch_prefill_one<BF16, 128, kPrefillQB, kPrefillNW, 1>(p, stream);
+        return launch_prefill_one<F16, 128, kPrefillQB, kPrefillNW, 1>(p, stream);
+    }
+    if (dtype == KVCAR_BF16) return launch_prefill_one<BF16, 64, kPrefillQB, kPrefillNW, 2>(p, stream);
+    return launch_prefill_one<F16, 64, kPrefillQB, kPrefillNW, 2>(p, stream);
 }
 
 }  // namespace kvcar

@@ -66,6 +66,10 @@ CASES = {
     "c3-mlp": (C[3].scaled(n_layers=2, batch=2, n_cached=140), 140, [(0, 140)], {}),
     "mlp-leaky": (C[3].scaled(n_layers=3, batch=2, n_cached=100, act="leaky_relu", reuse="from2:1", policy="P2"), 100, [(0, 100)],
                   {"with_bias": True}),
+    # d_head 128 (two KV heads of 128, four query heads each)
+    "dh128-bf16": (C[2].scaled(n_layers=3, batch=2, n_cached=300, n_q_heads=8, n_kv_heads=2, d_head=128), 300, [(0, 300)], {}),
+    "dh128-f16": (C[2].scaled(n_layers=2, batch=2, n_cached=150, n_q_heads=8, n_kv_heads=2, d_head=128, dtype="f16", reuse="none"), 150, [(0, 100), (100, 50)],
+                  {"with_bias": True}),
     # int8 latent rows
     "c2-int8": (C[2].scaled(n_layers=3, batch=2, n_cached=280), 280, [(0, 280)], {"latent_format": "int8"}),
     "c3-mlp-int8": (C[3].scaled(n_layers=2, batch=2, n_cached=90), 90, [(0, 90)], {"latent_format": "int8"}),
