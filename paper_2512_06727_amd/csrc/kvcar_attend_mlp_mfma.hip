@@ -48,32 +48,6 @@ template <> struct MMma<F16> {
     }
 };
 
-// GELU(x) = x * Phi(x) with Phi(x) = 0.5 + x R(x^2), R a degree-8 polynomial fitted on |x| <= 4 (least
-// squares on Chebyshev nodes, weighted by x); beyond that Phi is held at its value at +-4.  |Phi error|
-// <= 3.1e-5, i.e. |GELU error| <= 3.1e-5 |x|: two orders below the 16-bit rounding applied right after.
-// No transcendental instruction: 8 FMAs, a clamp and three multiplies.
-__device__ __forceinline__ float fast_gelu(float x) {
-    const float xc = __builtin_amdgcn_fmed3f(x, -4.0f, 4.0f);
-    const float s = xc * xc;
-    float r = 7.804710350223232e-11f;
-    r = fmaf(r, s, -6.827684195798156e-09f);
-    r = fmaf(r, s, 2.666981799848145e-07f);
-    r = fmaf(r, s, -6.222018782864325e-06f);
-    r = fmaf(r, s, 9.829134069150314e-05f);
-    r = fmaf(r, s, -0.0011309664696455002f);
-    r = fmaf(r, s, 0.009869969449937344f);
-    r = fmaf(r, s, -0.06640204787254333f);
-    r = fmaf(r, s, 0.39891988039016724f);
-    return x * fmaf(xc, r, 0.5f);
-}
-
-template <int ACT>
-__device__ __forceinline__ float fast_act(float x, float slope) {
-    if (ACT == KVCAR_ACT_LEAKY_RELU) return x >= 0.f ? x : slope * x;
-    if (ACT == KVCAR_ACT_GELU) return fast_gelu(x);
-    return x;
-}
-
 constexpr int kMlpTile = 32;      // tokens per workgroup iteration
 
 // 32x32 result layout: register v of lane (l32, h) holds row 8*(v/4) + 4*h + v%4 of column l32.  As an

@@ -60,25 +60,15 @@ typedef const __attribute__((address_space(4))) ReconEntry* REntry;
 
 constexpr int kReconChunk = 256;      // tokens per workgroup: two 32-token tiles per wave
 
-// Workgroup = (256-token chunk, sequence, entry).  The wave keeps its latent rows as B operands (lane: token
-// l32, latent columns 16s + 8h .. +7 of k-step s) and walks over the KV heads of the entry; per head the
-// decoder slice [R, d_head] passes through LDS once for the four waves.
+// The wave's latent rows as B operands: tile `tile` (0, 1) of its 64 tokens; lane (token l32, half h) holds latent
+// columns 16s + 8h .. +7 of k-step s, dequantised in registers when the rows are int8 codes; rows past n_rows are zero.
 template <typename E, int R, bool kI8>
-__global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
+__device__ __forceinline__ void recon_load_rows(u32x4_t (&zb)[2][R / 16], REntry e, RArgs p, int b, int tok0, int l32, int h) {
     constexpr int KS = R / 16;
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-    RArgs p = (RArgs)__builtin_amdgcn_kernarg_segment_ptr();
-    REntry e = &p->e[blockIdx.z];
-    const int b = blockIdx.y, chunk0 = blockIdx.x * kReconChunk;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
-    const int dh = p->d_head, n_rows = p->n_rows;
-    const int stride_w = 2 * dh + 32, cpr = dh >> 3;
-
-    u32x4_t zb[2][KS];
+    const int n_rows = p->n_rows;
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
-        const int t = chunk0 + wave * 64 + tile * 32 + l32;
+        const int t = tok0 + tile * 32 + l32;
         const bool valid = t < n_rows;
         const size_t row = (size_t)b * p->max_seq + (valid ? t : 0);
         if constexpr (kI8) {
@@ -110,6 +100,25 @@ __global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
             }
         }
     }
+}
+
+// Workgroup = (256-token chunk, sequence, entry).  The wave keeps its latent rows as B operands (lane: token
+// l32, latent columns 16s + 8h .. +7 of k-step s) and walks over the KV heads of the entry; per head the
+// decoder slice [R, d_head] passes through LDS once for the four waves.
+template <typename E, int R, bool kI8>
+__global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
+    constexpr int KS = R / 16;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    RArgs p = (RArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    REntry e = &p->e[blockIdx.z];
+    const int b = blockIdx.y, chunk0 = blockIdx.x * kReconChunk;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
+    const int dh = p->d_head, n_rows = p->n_rows;
+    const int stride_w = 2 * dh + 32, cpr = dh >> 3;
+
+    u32x4_t zb[2][KS];
+    recon_load_rows<E, R, kI8>(zb, e, p, b, chunk0 + wave * 64, l32, h);
 
     const char* wl = static_cast<const char*>(e->d.wl);
     const int in_width = e->d.in_width;
@@ -157,16 +166,139 @@ __global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
     }
 }
 
+// Two-layer decoder (FC -> activation -> FC): the hidden rows stay in registers between the two products.
+//   H^T[c, t] = W1^T . Z^T   per 32-column block of the hidden width; + b1, activation, rounded to 16 bits:
+//               the result layout (lane: token l32, hidden rows 8a + 4h + j of the block) is the B-operand layout
+//               of the second product with the rows of a k-step taken in register order
+//   X^^T[n, t] = Wl^T[n, c] . H^T[c, t]   per KV head and 32-column block of the head
+// W1 [R, C] stays in LDS for the whole workgroup; the slice [C, d_head] of the last layer passes through LDS per head.
+template <typename E, int R, int C, int ACT, bool kI8>
+__global__ __launch_bounds__(256) void recon_mlp_mfma_kernel(ReconParams) {
+    constexpr int KS = R / 16;          // k-steps of the first product
+    constexpr int CB = C / 32;          // 32-column blocks of the hidden width
+    constexpr int STRIDE1 = 2 * C + 32; // LDS row stride of W1
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    RArgs p = (RArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    REntry e = &p->e[blockIdx.z];
+    const int b = blockIdx.y, chunk0 = blockIdx.x * kReconChunk;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
+    const int dh = p->d_head, n_rows = p->n_rows;
+    const int stride_w = 2 * dh + 32, cpr = dh >> 3;
+    char* w1_lds = lds;
+    char* wl_lds = lds + R * STRIDE1;
+    const float slope = e->d.slope;
+
+    {
+        const char* w1 = static_cast<const char*>(e->d.w1);
+        for (int f = tid; f < R * (C / 8); f += 256) {
+            const int row = f / (C / 8), ch = f % (C / 8);
+            *reinterpret_cast<u32x4_t*>(w1_lds + row * STRIDE1 + ch * 16) = *reinterpret_cast<const u32x4_t*>(w1 + (size_t)f * 16);
+        }
+    }
+    u32x4_t zb[2][KS];
+    recon_load_rows<E, R, kI8>(zb, e, p, b, chunk0 + wave * 64, l32, h);
+    __syncthreads();
+
+    // hidden rows of the wave's two tiles as B operands of the second product: [tile][block][k-step]
+    u32x4_t hb[2][CB][2];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        const char* wsrc = w1_lds + (8 * h + (l16 >> 2)) * STRIDE1 + (32 * cb + 16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
+        f32x16_t acc[2];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const u32x4_t wa = tr_pair32(wsrc + 16 * s * STRIDE1, 4 * STRIDE1);
+            acc[0] = Mma32<E>::mfma(wa, zb[0][s], acc[0]);
+            acc[1] = Mma32<E>::mfma(wa, zb[1][s], acc[1]);
+        }
+        float bias[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) bias[v] = e->d.b1 ? Elem<E>::load(e->d.b1, 32 * cb + 8 * (v >> 2) + 4 * h + (v & 3)) : 0.f;
+#pragma unroll
+        for (int tile = 0; tile < 2; ++tile)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                unsigned w[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    w[q] = Mma<E>::pack2(fast_act<ACT>(acc[tile][8 * s + 2 * q] + bias[8 * s + 2 * q], slope),
+                                         fast_act<ACT>(acc[tile][8 * s + 2 * q + 1] + bias[8 * s + 2 * q + 1], slope));
+                hb[tile][cb][s] = u32x4_t{w[0], w[1], w[2], w[3]};
+            }
+    }
+
+    const char* wl = static_cast<const char*>(e->d.wl);
+    const int in_width = e->d.in_width;
+    char* dst = static_cast<char*>(e->which == KVCAR_K ? p->khat : p->vhat);
+    for (int hi = 0; hi < e->n_heads; ++hi) {
+        const int g = e->head[hi], col = e->col[hi];
+        __syncthreads();                           // the previous slice is no longer read
+        for (int f = tid; f < C * cpr; f += 256) {
+            const int row = f / cpr, ch = f - row * cpr;
+            *reinterpret_cast<u32x4_t*>(wl_lds + row * stride_w + ch * 16) =
+                *reinterpret_cast<const u32x4_t*>(wl + ((size_t)row * in_width + col) * 2 + ch * 16);
+        }
+        __syncthreads();
+        for (int mb = 0; mb < (dh >> 5); ++mb) {
+            // A operand: row = decoder column 32 mb + l32; k-slots of k-step s of block cb = hidden rows
+            // 32 cb + 16 s + 8(e/4) + 4h + e%4
+            const char* wsrc = wl_lds + (4 * h + (l16 >> 2)) * stride_w + (32 * mb + 16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
+            f32x16_t acc[2];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.f;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const u32x4_t wa = tr_pair32(wsrc + (32 * cb + 16 * s) * stride_w, 8 * stride_w);
+                    acc[0] = Mma32<E>::mfma(wa, hb[0][cb][s], acc[0]);
+                    acc[1] = Mma32<E>::mfma(wa, hb[1][cb][s], acc[1]);
+                }
+#pragma unroll
+            for (int tile = 0; tile < 2; ++tile) {
+                const int t = chunk0 + wave * 64 + tile * 32 + l32;
+                if (t >= n_rows) continue;
+                char* orow = dst + ((((size_t)b * p->n_kv_heads + g) * n_rows + t) * dh + 32 * mb + 4 * h) * 2;
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    float bias[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (e->d.bl) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) bias[j] = Elem<E>::load(e->d.bl, col + 32 * mb + 8 * a + 4 * h + j);
+                    }
+                    *reinterpret_cast<u32x2_t*>(orow + 16 * a) =
+                        u32x2_t{Mma<E>::pack2(acc[tile][4 * a] + bias[0], acc[tile][4 * a + 1] + bias[1]),
+                                Mma<E>::pack2(acc[tile][4 * a + 2] + bias[2], acc[tile][4 * a + 3] + bias[3])};
+                }
+            }
+        }
+    }
+}
+
+
 static bool recon_width_ok(int r) { return r == 32 || r == 64 || r == 96 || r == 128 || r == 192 || r == 256 || r == 384; }
+
+// Two-layer decoders: the (latent, hidden) shapes with an instance
+static bool recon_mlp_shape_ok(const SideDesc& sd) {
+    return ((sd.r == 128 && sd.c == 256) || (sd.r == 64 && sd.c == 128)) && (sd.act == KVCAR_ACT_GELU || sd.act == KVCAR_ACT_LEAKY_RELU);
+}
 
 bool recon_mfma_supported(const ReconParams& p, int dtype) {
     if (dtype == KVCAR_F32 || p.n_entries < 1) return false;
     if (p.d_head % 32 != 0) return false;
     for (int i = 0; i < p.n_entries; ++i) {
         const SideDesc& sd = p.e[i].d;
-        if (sd.w1 != nullptr || !recon_width_ok(sd.r)) return false;
-        if ((size_t)sd.r * (2 * p.d_head + 32) > 150 * 1024) return false;
         if (sd.in_width % 8 != 0) return false;
+        if (sd.w1 != nullptr) {
+            if (!recon_mlp_shape_ok(sd)) return false;
+            if ((size_t)sd.r * (2 * sd.c + 32) + (size_t)sd.c * (2 * p.d_head + 32) > 150 * 1024) return false;
+        } else {
+            if (!recon_width_ok(sd.r)) return false;
+            if ((size_t)sd.r * (2 * p.d_head + 32) > 150 * 1024) return false;
+        }
     }
     return true;
 }
@@ -198,20 +330,47 @@ static hipError_t launch_recon_width(const ReconParams& p, int r, hipStream_t st
     }
 }
 
-// Entries of different latent widths go out in launches of their own (the width is a template argument).
+template <typename E, int R, int C, int ACT, bool kI8>
+static hipError_t launch_recon_mlp_one(const ReconParams& p, hipStream_t stream) {
+    const size_t lds = (size_t)R * (2 * C + 32) + (size_t)C * (2 * p.d_head + 32);
+    auto k = recon_mlp_mfma_kernel<E, R, C, ACT, kI8>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    dim3 grid((p.n_rows + kReconChunk - 1) / kReconChunk, p.batch, p.n_entries);
+    hipLaunchKernelGGL(k, grid, dim3(256), lds, stream, p);
+    return hipGetLastError();
+}
+
+template <typename E, bool kI8>
+static hipError_t launch_recon_mlp(const ReconParams& p, const SideDesc& sd, hipStream_t stream) {
+    const bool big = sd.r == 128;
+    if (sd.act == KVCAR_ACT_GELU)
+        return big ? launch_recon_mlp_one<E, 128, 256, KVCAR_ACT_GELU, kI8>(p, stream) : launch_recon_mlp_one<E, 64, 128, KVCAR_ACT_GELU, kI8>(p, stream);
+    return big ? launch_recon_mlp_one<E, 128, 256, KVCAR_ACT_LEAKY_RELU, kI8>(p, stream) : launch_recon_mlp_one<E, 64, 128, KVCAR_ACT_LEAKY_RELU, kI8>(p, stream);
+}
+
+// Entries of different shapes go out in launches of their own (widths and activation are template arguments).
 hipError_t launch_recon_mfma(const ReconParams& p, int dtype, hipStream_t stream) {
     bool done[kMaxReconEntries] = {};
+    auto same = [](const SideDesc& a, const SideDesc& b) {
+        return a.r == b.r && (a.w1 != nullptr) == (b.w1 != nullptr) && (a.w1 == nullptr || (a.c == b.c && a.act == b.act));
+    };
     for (int i = 0; i < p.n_entries; ++i) {
         if (done[i]) continue;
         ReconParams sub = p;
         sub.n_entries = 0;
         for (int k = i; k < p.n_entries; ++k)
-            if (!done[k] && p.e[k].d.r == p.e[i].d.r) { sub.e[sub.n_entries++] = p.e[k]; done[k] = true; }
-        const bool i8 = sub.e[0].d.meta != nullptr;
-        const int r = sub.e[0].d.r;
+            if (!done[k] && same(p.e[k].d, p.e[i].d)) { sub.e[sub.n_entries++] = p.e[k]; done[k] = true; }
+        const SideDesc& sd = sub.e[0].d;
+        const bool i8 = sd.meta != nullptr;
         hipError_t err;
-        if (dtype == KVCAR_BF16) err = i8 ? launch_recon_width<BF16, true>(sub, r, stream) : launch_recon_width<BF16, false>(sub, r, stream);
-        else err = i8 ? launch_recon_width<F16, true>(sub, r, stream) : launch_recon_width<F16, false>(sub, r, stream);
+        if (sd.w1 != nullptr) {
+            if (dtype == KVCAR_BF16) err = i8 ? launch_recon_mlp<BF16, true>(sub, sd, stream) : launch_recon_mlp<BF16, false>(sub, sd, stream);
+            else err = i8 ? launch_recon_mlp<F16, true>(sub, sd, stream) : launch_recon_mlp<F16, false>(sub, sd, stream);
+        } else {
+            if (dtype == KVCAR_BF16) err = i8 ? launch_recon_width<BF16, true>(sub, sd.r, stream) : launch_recon_width<BF16, false>(sub, sd.r, stream);
+            else err = i8 ? launch_recon_width<F16, true>(sub, sd.r, stream) : launch_recon_width<F16, false>(sub, sd.r, stream);
+        }
         if (err != hipSuccess) return err;
     }
     return hipSuccess;
