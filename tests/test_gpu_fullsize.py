@@ -108,3 +108,48 @@ def test_mlp_prefill_full_size():
     two-layer decoder."""
     w = synth.CONFIGS[3].scaled(n_steps=1)
     run_fullsize(w, layers=[0, 21], seqs=[0, 15], gain=8.0)
+
+
+def run_prefill_fullsize(w, layers, seqs, tokens, gain):
+    """kvcar_prefill_attention on the whole prompt (the shape bench.py --op prefill times); the oracle
+    recomputes sampled (sequence, token) rows one by one: token i is a decode step over i + 1 rows."""
+    reuse = synth.reuse_map(w)
+    ses = Session(w, reuse=reuse)
+    T = w.n_cached
+    need = set()
+    for n in layers:
+        need |= {n} | set(sources(reuse, n, 0)) | set(sources(reuse, n, 1))
+    need = sorted(need)
+    ses.prefill(0, T, chunk=max(1, (1 << 24) // (w.batch * w.d_kv)), layers=need)
+    for n in layers:
+        q = synth.prompt_queries(w, n, 0, w.batch, 0, T, gain=gain)
+        out = ses.prefill_attention(n, q.to(ses.dev, ses.tdt), 0).float().cpu().double().numpy()
+        assert np.isfinite(out).all()
+        for b in seqs:
+            orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, 1, w.max_seq, w.dtype)
+            for m in range(w.n_layers):
+                orc.set_reuse_map(m, reuse[m, 0], reuse[m, 1])
+            for m in sorted({n} | set(sources(reuse, n, 0)) | set(sources(reuse, n, 1))):
+                for which in (0, 1):
+                    orc.set_autoencoder(m, which, oracle_ae(synth.autoencoder(w, m, which, reuse)))
+                orc.encode_append(m, synth.kv_tokens(w, m, 0, b, b + 1, 0, T).double().numpy(),
+                                  synth.kv_tokens(w, m, 1, b, b + 1, 0, T).double().numpy(), 0)
+            for i in tokens:
+                want = orc.decode_attention(n, q[b, i].double().numpy()[None], i + 1)[0]
+                err = np.abs(out[b, i] - want)
+                ulp = 2.0 ** -7 if w.dtype == "bf16" else 2.0 ** -10
+                assert (err <= ABS_TOL[w.dtype] + ulp * np.abs(want)).all(), (n, b, i, err.max())
+                assert err.max() <= REL_TOL[w.dtype] * np.abs(want).max(), (n, b, i, err.max(), np.abs(want).max())
+
+
+def test_prefill_tinyllama_full_size():
+    """16 x 4096-token prompts, TinyLlama shape with a reused head per layer: first and last tokens, both sides of
+    tile (64), query-block (32) and workgroup (256) boundaries."""
+    w = synth.CONFIGS[2].scaled(batch=16, n_cached=4096, n_steps=0)
+    run_prefill_fullsize(w, layers=[0, 11, 21], seqs=[0, 15], tokens=[0, 1, 31, 32, 63, 64, 255, 256, 2047, 2048, 4095], gain=30.0)
+
+
+def test_prefill_mlp_full_size():
+    """The same prompt shape through two-layer GELU decoders (the configuration named for prefill)."""
+    w = synth.CONFIGS[3].scaled(n_steps=0)
+    run_prefill_fullsize(w, layers=[0, 21], seqs=[3], tokens=[0, 63, 64, 1000, 4095], gain=8.0)
