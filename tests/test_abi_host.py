@@ -212,3 +212,44 @@ def test_selection_statistic_argument_errors_and_workspace_size():
     assert call(FAKE, FAKE, B.F32, 64, 4, 62, 0, FAKE, FAKE, 1 << 20, None) == B.ERR_SHAPE
     assert call(FAKE, FAKE, B.BF16, 64, 4, 64, 0, FAKE, FAKE, 4, None) == B.ERR_WORKSPACE
     assert call(FAKE, FAKE, B.BF16, 64, 2000, 64, 0, FAKE, FAKE, 1 << 30, None) == B.ERR_UNSUPPORTED
+
+
+def test_prefill_workspace_size_and_argument_errors_before_any_launch():
+    """Workspace of kvcar_prefill_attention = decoded keys + decoded values of the rows 0 .. n_rows - 1 in the
+    model dtype; every argument, capacity, state and workspace error is reported before anything is enqueued."""
+    ctx = make(n_layers=2, hq=8, hkv=4, dh=64, mb=2, ms=64, dtype="bf16")
+    lib = B.lib()
+    assert ctx.prefill_workspace_bytes(2, 64) == 2 * 2 * 64 * 4 * 64 * 2
+    assert ctx.prefill_workspace_bytes(1, 3) == 2 * 1536            # each half is padded to 256 bytes
+    n = C.c_size_t()
+    assert lib.kvcar_prefill_workspace_bytes(ctx._h, 3, 8, C.byref(n)) == B.ERR_CAPACITY
+    assert lib.kvcar_prefill_workspace_bytes(ctx._h, 1, 65, C.byref(n)) == B.ERR_CAPACITY
+    assert lib.kvcar_prefill_workspace_bytes(ctx._h, 1, 8, None) == B.ERR_ARG
+    big = 1 << 30
+    assert lib.kvcar_prefill_attention(ctx._h, 0, FAKE, FAKE, 1, 0, 8, FAKE, big, None) == B.ERR_STATE        # no autoencoder yet
+    for which in (B.K, B.V):
+        assert lib.kvcar_set_autoencoder(ctx._h, 0, which, C.byref(desc(256, 0, 128))) == B.OK
+    assert lib.kvcar_prefill_attention(ctx._h, 0, FAKE, FAKE, 1, 0, 8, FAKE, big, None) == B.ERR_STATE        # caches not bound
+    for which in (B.K, B.V):
+        assert lib.kvcar_bind_cache(ctx._h, 0, which, FAKE, ctx.cache_bytes(0, which)) == B.OK
+    assert lib.kvcar_prefill_attention(ctx._h, 0, FAKE, FAKE, 3, 0, 8, FAKE, big, None) == B.ERR_CAPACITY
+    assert lib.kvcar_prefill_attention(ctx._h, 0, FAKE, FAKE, 1, 60, 5, FAKE, big, None) == B.ERR_CAPACITY
+    assert lib.kvcar_prefill_attention(ctx._h, 0, FAKE, FAKE, 1, 0, 0, FAKE, big, None) == B.ERR_ARG
+    assert lib.kvcar_prefill_attention(ctx._h, 0, FAKE, FAKE, 1, -1, 4, FAKE, big, None) == B.ERR_ARG
+    assert lib.kvcar_prefill_attention(ctx._h, 0, None, FAKE, 1, 0, 8, FAKE, big, None) == B.ERR_ARG
+    assert lib.kvcar_prefill_attention(ctx._h, 0, FAKE, FAKE + 2, 1, 0, 8, FAKE, big, None) == B.ERR_ARG
+    assert lib.kvcar_prefill_attention(ctx._h, 0, FAKE, FAKE, 1, 0, 8, None, big, None) == B.ERR_ARG
+    assert lib.kvcar_prefill_attention(ctx._h, 0, FAKE, FAKE, 1, 0, 8, FAKE, ctx.prefill_workspace_bytes(1, 8) - 1, None) == B.ERR_WORKSPACE
+    assert lib.kvcar_prefill_attention(ctx._h, 2, FAKE, FAKE, 1, 0, 8, FAKE, big, None) == B.ERR_ARG
+    assert lib.kvcar_prefill_attention(ctx._h, 1, FAKE, FAKE, 1, 0, 8, FAKE, big, None) == B.ERR_STATE        # layer 1 has no autoencoder
+    # a layer whose source does not cover a head it takes
+    ctx.set_reuse_map(1, [0, 0, 1, 0], [0, 0, 0, 0])
+    for which in (B.K, B.V):
+        assert lib.kvcar_set_autoencoder(ctx._h, 1, which, C.byref(desc(256, 0, 128))) == B.OK
+        assert lib.kvcar_bind_cache(ctx._h, 1, which, FAKE, ctx.cache_bytes(1, which)) == B.OK
+    assert lib.kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(desc(256, 0, 128))) == B.OK
+    big_dh = make(n_layers=1, hq=2, hkv=2, dh=320, mb=1, ms=8, dtype="f32")
+    for which in (B.K, B.V):
+        assert lib.kvcar_set_autoencoder(big_dh._h, 0, which, C.byref(desc(640, 0, 64))) == B.OK
+        assert lib.kvcar_bind_cache(big_dh._h, 0, which, FAKE, big_dh.cache_bytes(0, which)) == B.OK
+    assert lib.kvcar_prefill_attention(big_dh._h, 0, FAKE, FAKE, 1, 0, 8, FAKE, big, None) == B.ERR_UNSUPPORTED   # d_head > 256
