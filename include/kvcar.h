@@ -245,7 +245,8 @@ int kvcar_encode_append_at(kvcar_ctx *ctx, int layer, const void *k_new, const v
  * steps with n_ctx = pos0 + i + 1 up to rounding.  Unlike a decode step, a prompt chunk is bound by the
  * matrix units, not by reading the cache, so the decoder is not folded into the query (that would double
  * the products per score): the rows 0 .. pos0 + t_new - 1 of every KV head are decoded ONCE per call into
- * `workspace` (rounded to dtype, the precision the model holds its keys and values in) and a causal
+ * `workspace` (rounded to dtype, the precision the model holds its keys and values in; the keys carry the
+ * softmax scale into that one rounding) and a causal
  * attention kernel runs over them.  Nothing outlives the call: the workspace may be reused at once by
  * the next layer.  kvcar_prefill_workspace_bytes(batch, n_rows) gives its size for n_rows = pos0 + t_new
  * (2 * batch * n_rows * H_kv * d_head elements).

@@ -608,13 +608,13 @@ int prefill_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch,
         for (int i = 0; i < rp.n_entries; ++i) rp.e[i] = entries[e0 + i];
         rp.khat = khat; rp.vhat = vhat;
         rp.batch = batch; rp.n_rows = n_rows; rp.max_seq = c.max_seq; rp.n_kv_heads = c.n_kv_heads; rp.d_head = c.d_head;
+        rp.k_scale = ctx->scale * kLog2e;
         e = (!ctx->tun.force_generic && recon_mfma_supported(rp, c.dtype)) ? launch_recon_mfma(rp, c.dtype, st) : launch_recon_generic(rp, c.dtype, st);
     }
     PrefillParams pp{};
     pp.q = q; pp.out = out; pp.khat = khat; pp.vhat = vhat;
     pp.batch = batch; pp.t_new = t_new; pp.pos0 = pos0; pp.n_rows = n_rows;
     pp.n_q_heads = c.n_q_heads; pp.n_kv_heads = c.n_kv_heads; pp.d_head = c.d_head;
-    pp.scale_log2e = ctx->scale * kLog2e;
     std::pair<hipEvent_t, hipEvent_t>* ev = nullptr;
     if (e == hipSuccess && ctx->profiling) {
         if (ctx->ev_used == ctx->ev_pool.size()) {

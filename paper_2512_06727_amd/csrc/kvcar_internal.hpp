@@ -151,16 +151,16 @@ struct ReconParams {
     void* khat;                   // decoded keys   [batch, H_kv, n_rows, d_head]
     void* vhat;                   // decoded values [batch, H_kv, n_rows, d_head]
     int batch, n_rows, max_seq, n_kv_heads, d_head;
+    float k_scale;                // softmax scale * log2(e), multiplied into the decoded keys before their one rounding
 };
 
 struct PrefillParams {
     const void* q;                // [batch, t_new, H_q, d_head]
     void* out;                    // [batch, t_new, H_q, d_head]
-    const void* khat;
+    const void* khat;             // decoded keys, already multiplied by softmax scale * log2(e): scores come out in log2 units
     const void* vhat;
     int batch, t_new, pos0, n_rows;
     int n_q_heads, n_kv_heads, d_head;
-    float scale_log2e;            // softmax scale * log2(e)
 };
 
 hipError_t launch_recon_generic(const ReconParams& p, int dtype, hipStream_t stream);

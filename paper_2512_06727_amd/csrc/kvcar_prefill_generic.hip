@@ -4,7 +4,9 @@
 // the keys and values of all prompt tokens, which go to the cache - as latent rows here - and come back
 // through the decoder, "Network Architecture", 2nd paragraph; attention is Eq. 1 per token).  Two steps:
 //   recon    K^[b, g, t, :] / V^[b, g, t, :] = decoder(latent row t of the layer that supplies head g),
-//            the columns of head g, for t < n_rows; written once, rounded to the model dtype
+//            the columns of head g, for t < n_rows; written once, rounded to the model dtype.  The keys are
+//            multiplied by scale * log2(e) before that one rounding, so scores come out in log2 units and
+//            the scale costs neither an operation per score nor a second rounding
 //   attend   out[b, i, j, :] = sum_{t <= pos0 + i} softmax_t(scale q[b,i,j,:] . K^_g[t]) V^_g[t]
 // These kernels serve fp32 models and shapes the matrix-core kernels do not cover.
 #include "kvcar_device.hpp"
@@ -42,6 +44,7 @@ __global__ __launch_bounds__(256) void recon_generic_kernel(ReconParams p) {
         rows = hid;
     }
     void* dst = e.which == KVCAR_K ? p.khat : p.vhat;
+    const float out_scale = e.which == KVCAR_K ? p.k_scale : 1.f;     // keys carry the softmax scale (log2 units)
     const int dh = p.d_head;
     for (int hi = 0; hi < e.n_heads; ++hi) {
         const int g = e.head[hi], col = e.col[hi];
@@ -50,7 +53,7 @@ __global__ __launch_bounds__(256) void recon_generic_kernel(ReconParams p) {
             if (t >= nt) continue;
             float a = sd.bl ? Elem<E>::load(sd.bl, col + k) : 0.f;
             for (int c = 0; c < sd.c; ++c) a = fmaf(rows[t * sd.c + c], Elem<E>::load(sd.wl, (size_t)c * sd.in_width + col + k), a);
-            Elem<E>::store(dst, (((size_t)b * p.n_kv_heads + g) * p.n_rows + t0 + t) * dh + k, a);
+            Elem<E>::store(dst, (((size_t)b * p.n_kv_heads + g) * p.n_rows + t0 + t) * dh + k, a * out_scale);
         }
     }
 }
@@ -81,7 +84,7 @@ __global__ __launch_bounds__(64) void prefill_generic_kernel(PrefillParams p) {
     const int i = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
     const int dh = p.d_head, g = j / (p.n_q_heads / p.n_kv_heads);
     const size_t qoff = (((size_t)b * p.t_new + i) * p.n_q_heads + j) * dh;
-    for (int k = lane; k < dh; k += 64) qs[k] = Elem<E>::load(p.q, qoff + k) * p.scale_log2e;
+    for (int k = lane; k < dh; k += 64) qs[k] = Elem<E>::load(p.q, qoff + k);
     __syncthreads();
     const size_t row0 = ((size_t)b * p.n_kv_heads + g) * p.n_rows;
     const int n = p.pos0 + i + 1;             // rows this token sees

@@ -43,6 +43,21 @@ template <> struct Mma32<F16> {
     }
 };
 
+// acc + lo + hi for the two 16-bit elements packed in w (v_dot2 with a vector of ones: one instruction per pair).
+template <typename E> struct PairSum;
+template <> struct PairSum<BF16> {
+    static __device__ __forceinline__ float add(float acc, unsigned w) {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w), __builtin_bit_cast(bf16x2_t, 0x3f803f80u), acc, false);
+    }
+};
+template <> struct PairSum<F16> {
+    static __device__ __forceinline__ float add(float acc, unsigned w) {
+        typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, w), __builtin_bit_cast(f16x2_t, 0x3c003c00u), acc, false);
+    }
+};
+
 // Transposing LDS load: 16 lanes supply the addresses of a 4-row x 16-column patch of 16-bit elements and
 // lane i receives the 4 rows of column i.  Two patches make the 8 k-slots of a lane.
 __device__ __forceinline__ u32x4_t tr_pair32(const char* p, int second_offset) {
@@ -123,6 +138,7 @@ __global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
     const char* wl = static_cast<const char*>(e->d.wl);
     const int in_width = e->d.in_width;
     char* dst = static_cast<char*>(e->which == KVCAR_K ? p->khat : p->vhat);
+    const float out_scale = e->which == KVCAR_K ? p->k_scale : 1.f;      // keys carry softmax scale * log2(e) into their one rounding
     for (int hi = 0; hi < e->n_heads; ++hi) {
         const int g = e->head[hi], col = e->col[hi];
         __syncthreads();                           // the previous slice is no longer read
@@ -158,8 +174,8 @@ __global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
                         for (int j = 0; j < 4; ++j) bias[j] = Elem<E>::load(e->d.bl, col + 32 * mb + 8 * a + 4 * h + j);
                     }
                     *reinterpret_cast<u32x2_t*>(orow + 16 * a) =
-                        u32x2_t{Mma<E>::pack2(acc[tile][4 * a] + bias[0], acc[tile][4 * a + 1] + bias[1]),
-                                Mma<E>::pack2(acc[tile][4 * a + 2] + bias[2], acc[tile][4 * a + 3] + bias[3])};
+                        u32x2_t{Mma<E>::pack2((acc[tile][4 * a] + bias[0]) * out_scale, (acc[tile][4 * a + 1] + bias[1]) * out_scale),
+                                Mma<E>::pack2((acc[tile][4 * a + 2] + bias[2]) * out_scale, (acc[tile][4 * a + 3] + bias[3]) * out_scale)};
                 }
             }
         }
@@ -233,6 +249,7 @@ __global__ __launch_bounds__(256) void recon_mlp_mfma_kernel(ReconParams) {
     const char* wl = static_cast<const char*>(e->d.wl);
     const int in_width = e->d.in_width;
     char* dst = static_cast<char*>(e->which == KVCAR_K ? p->khat : p->vhat);
+    const float out_scale = e->which == KVCAR_K ? p->k_scale : 1.f;      // keys carry softmax scale * log2(e) into their one rounding
     for (int hi = 0; hi < e->n_heads; ++hi) {
         const int g = e->head[hi], col = e->col[hi];
         __syncthreads();                           // the previous slice is no longer read
@@ -270,8 +287,8 @@ __global__ __launch_bounds__(256) void recon_mlp_mfma_kernel(ReconParams) {
                         for (int j = 0; j < 4; ++j) bias[j] = Elem<E>::load(e->d.bl, col + 32 * mb + 8 * a + 4 * h + j);
                     }
                     *reinterpret_cast<u32x2_t*>(orow + 16 * a) =
-                        u32x2_t{Mma<E>::pack2(acc[tile][4 * a] + bias[0], acc[tile][4 * a + 1] + bias[1]),
-                                Mma<E>::pack2(acc[tile][4 * a + 2] + bias[2], acc[tile][4 * a + 3] + bias[3])};
+                        u32x2_t{Mma<E>::pack2((acc[tile][4 * a] + bias[0]) * out_scale, (acc[tile][4 * a + 1] + bias[1]) * out_scale),
+                                Mma<E>::pack2((acc[tile][4 * a + 2] + bias[2]) * out_scale, (acc[tile][4 * a + 3] + bias[3]) * out_scale)};
                 }
             }
         }
@@ -421,9 +438,9 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
     const int i0 = qblk * TQ + wave * 32 * QB;  // first query token of this wave
-    const float c = p.scale_log2e;
 
-    // queries as B operands: lane (token l32 of block qb, half h) holds components 16s + 8h .. +7
+    // queries as B operands: lane (token l32 of block qb, half h) holds components 16s + 8h .. +7 (the decoded keys
+    // carry scale * log2(e), so the score product comes out in log2 units)
     u32x4_t qB[QB][KS];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -477,9 +494,16 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[qb][db][v] = 0.f;
-    float m_run[QB], l_run[QB];
+    // -m of every query (m = the reference point of its softmax, log2 units) as the score product's initial
+    // accumulator: the product then delivers score - m and the exponent needs no subtraction
+    f32x16_t negm[QB];
+    float l_run[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+    for (int qb = 0; qb < QB; ++qb) {
+        l_run[qb] = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) negm[qb][v] = 0.f;
+    }
 
     issue(0);
     park(0);
@@ -498,14 +522,10 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
                 // ---- scores: S^T[row, q]; this lane: query l32 of block qb, rows 32 kvb + 8a + 4h + j (register 4a + j)
                 f32x16_t s[QB];
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) s[qb][v] = 0.f;
-#pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     const u32x4_t ka = *reinterpret_cast<const u32x4_t*>(krow + 32 * kvb * G::kStrideK + ks * 32);
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) s[qb] = Mma32<E>::mfma(ka, qB[qb][ks], s[qb]);
+                    for (int qb = 0; qb < QB; ++qb) s[qb] = Mma32<E>::mfma(ka, qB[qb][ks], ks == 0 ? negm[qb] : s[qb]);
                 }
 
                 u32x4_t pb[QB][2];
@@ -521,35 +541,39 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
                         for (int v = 0; v < 16; ++v)
                             if (8 * (v >> 2) + (v & 3) > lim) s[qb][v] = -INFINITY;
                     }
-                    // ---- online softmax in base 2 (the scale rides on the exponent's multiply-add).  The reference
-                    // point m of a query only moves when a score exceeds it by more than kSlack (in log2 units):
-                    // until then probabilities simply grow up to 2^kSlack, which costs nothing in fp32 / 16-bit
-                    // floating point, and the accumulators need no rescaling - a rare event instead of one in most halves.
+                    // ---- online softmax in base 2.  s holds score - m.  The reference point m of a query only moves
+                    // when a score exceeds it by more than kSlack: until then probabilities simply grow up to 2^kSlack,
+                    // which costs nothing in fp32 / 16-bit floating point, and the accumulators need no rescaling - a
+                    // rare event instead of one in most halves.  The very first half sets m (it holds row 0, which
+                    // every query sees, so the maximum is finite).
                     float mx = fmaxf(fmaxf(s[qb][0], s[qb][1]), s[qb][2]);
 #pragma unroll
                     for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s[qb][v]), s[qb][v + 1]);
                     mx = fmaxf(mx, s[qb][15]);
                     mx = fmaxf(mx, __shfl_xor(mx, 32));
-                    const bool moved = (mx - m_run[qb]) * c > kSlack;       // always on the first half (m = -inf), which holds row 0
+                    const bool moved = mx > kSlack || (jt == 0 && kvb == 0);
                     if (__builtin_amdgcn_ballot_w64(moved) != 0) {
-                        const float m_new = moved ? mx : m_run[qb];
-                        const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c);
-                        m_run[qb] = m_new;
+                        const float delta = moved ? mx : 0.f;
+                        const float alpha = __builtin_amdgcn_exp2f(-delta);
                         l_run[qb] *= alpha;
 #pragma unroll
                         for (int db = 0; db < DB; ++db) acc[qb][db] *= alpha;
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) { negm[qb][v] -= delta; s[qb][v] -= delta; }
                     }
-                    const float mc = m_run[qb] * c;
                     float e[16];
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) e[v] = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c, -mc));
-                    l_run[qb] += (((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]))) +
-                                 (((e[8] + e[9]) + (e[10] + e[11])) + ((e[12] + e[13]) + (e[14] + e[15])));
+                    for (int v = 0; v < 16; ++v) e[v] = __builtin_amdgcn_exp2f(s[qb][v]);
                     // k-step s2 of the half: rows 16 s2 + 8(e/4) + 4h + e%4 = registers 8 s2 .. 8 s2 + 7
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2)
                         pb[qb][s2] = u32x4_t{Mma<E>::pack2(e[8 * s2], e[8 * s2 + 1]), Mma<E>::pack2(e[8 * s2 + 2], e[8 * s2 + 3]),
                                              Mma<E>::pack2(e[8 * s2 + 4], e[8 * s2 + 5]), Mma<E>::pack2(e[8 * s2 + 6], e[8 * s2 + 7])};
+                    // the denominator sums the probabilities as rounded for the product (two chains of four pairs)
+                    float la = 0.f, lb = 0.f;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) { la = PairSum<E>::add(la, pb[qb][0][w]); lb = PairSum<E>::add(lb, pb[qb][1][w]); }
+                    l_run[qb] += la + lb;
                 }
 
                 // ---- O^T[d, q] += V^^T . P^T
@@ -587,7 +611,6 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
 
 bool prefill_mfma_supported(const PrefillParams& p, int dtype) {
     if (dtype == KVCAR_F32) return false;
-    if (!(p.scale_log2e > 0.f)) return false;          // the running maximum is taken on unscaled scores
     return p.d_head == 64 || p.d_head == 128;
 }
 
