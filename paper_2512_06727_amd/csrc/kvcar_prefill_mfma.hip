@@ -21,10 +21,11 @@
 //                          straight from the softmax registers (the result layout of S^T is the operand
 //                          layout, with the rows of a k-step taken in the order the registers hold them)
 //                        the causal limit only touches the last one or two tiles of a wave.
-// Measured budget of the attention kernel on 16 x 4096 tokens (per launch): matrix instructions alone would
-// take 0.44 ms at the dense peak; LDS reads of the operands 0.40 ms, staging and barriers 0.19 ms, the
-// softmax's vector instructions 0.69 ms (16-bit conversion, exp2, sum, max: 5.5 per score, and on this chip
-// a matrix instruction blocks vector issue for about half its duration); they overlap only in part: 1.24 ms.
+// Measured budget of the attention kernel on 16 x 4096 tokens (per launch, with parts removed in turn):
+// matrix instructions alone would take 0.44 ms at the dense peak; LDS reads of the operands 0.40 ms, staging
+// and barriers 0.19 ms, the softmax's vector instructions 0.5-0.7 ms (on this chip a matrix instruction blocks
+// vector issue for about half its duration); they overlap only in part: 1.17 ms.  Hence the effort to keep
+// vector work per score down to exp2 + half a conversion + half a dot2 + half a max3.
 #include "kvcar_attend_mfma_body.hpp"
 
 namespace kvcar {
@@ -399,7 +400,7 @@ hipError_t launch_recon_mfma(const ReconParams& p, int dtype, hipStream_t stream
 constexpr int kKvTile = 64;           // decoded rows per LDS tile
 constexpr float kSlack = 8.f;         // a query's softmax reference point moves when a score exceeds it by 2^kSlack
 // Launch shape (measured on 16 x 4096 tokens, 32 heads of 64: TFLOP/s of the kernel):
-//   one 32-query block per wave, 8 waves, 2 workgroups per CU (4 waves per SIMD)   887      <- used
+//   one 32-query block per wave, 8 waves, 2 workgroups per CU (4 waves per SIMD)   887      <- used (944 after later savings)
 //   two blocks per wave, 4 waves, 2 workgroups per CU (2 waves per SIMD)            835
 //   two blocks per wave, 8 waves, 1 workgroup per CU                                779;  with 128-row tiles 808
 //   two blocks per wave, 4 waves, 1 workgroup per CU (1 wave per SIMD)              485
