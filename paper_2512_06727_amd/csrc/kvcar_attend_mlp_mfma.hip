@@ -11,10 +11,10 @@
 // (the result layout of each first product is the operand layout the second one needs, so the hidden
 // activations never leave registers).  All products use v_mfma_f32_32x32x16 (on this chip it sustains
 // twice the flop rate of the 16x16x32 form, and this kernel is bound by matrix + vector issue): tokens,
-// heads and hidden columns are handled in blocks of 32.  The four waves of a workgroup share a 32-token tile and split the
-// hidden width: each keeps its quarter of W1K and W1V resident in registers as MFMA operands.  Scores
+// heads and hidden columns are handled in blocks of 32.  The waves of a workgroup (eight, or four for the narrow shape) share a 32-token tile and split the
+// hidden width: each keeps its share of W1K and W1V resident in registers as MFMA operands.  Scores
 // are a contraction over the whole hidden width, so the per-wave partial scores are summed through LDS;
-// every wave then runs the same online softmax and accumulates its quarter of O^T.
+// every wave then runs the same online softmax and accumulates its share of O^T.
 #include "kvcar_device.hpp"
 
 namespace kvcar {
@@ -69,15 +69,16 @@ __device__ __forceinline__ void act_pack(const f32x16_t& t, const float (&bias)[
 // rows are dequantised, x^ = (code - zeropoint) / scale, on their way from the staging registers into LDS and
 // rounded there to the model dtype - the precision a 16-bit model holds the dequantised tensor in before
 // the decoder - so everything after the park is the 16-bit path.
-template <typename E, int R, int C, int ACT, bool kI8>
-__global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p) {
-    constexpr int CW = C / 4;          // hidden columns per wave
+template <typename E, int R, int C, int ACT, bool kI8, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParams p) {
+    constexpr int NT = 64 * NW;        // threads
+    constexpr int CW = C / NW;         // hidden columns per wave
     constexpr int MB = CW / 32;        // 32-column blocks per wave
     constexpr int KS = R / 16;         // k-steps over the latent width
     constexpr int STRIDE = 2 * R + 16; // LDS row stride of a latent tile
     constexpr int EB = kI8 ? 1 : 2;    // bytes per cached latent element
     constexpr int CPR = R * EB / 16;   // 16-byte chunks per cached row
-    constexpr int NLD = (kMlpTile * CPR) / 256 > 0 ? (kMlpTile * CPR) / 256 : 1;       // 16-byte chunks per thread per tile
+    constexpr int NLD = (kMlpTile * CPR) / NT > 0 ? (kMlpTile * CPR) / NT : 1;         // 16-byte chunks per thread per tile
     static_assert(CW % 32 == 0 && R % 16 == 0, "shape");
 
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
         for (int which = 0; which < 2; ++which) {
             const char* w1 = static_cast<const char*>(which == 0 ? g.k.w1 : g.v.w1);
             __syncthreads();
-            for (int f = tid; f < R * (C / 8); f += 256) {
+            for (int f = tid; f < R * (C / 8); f += NT) {
                 const int row = f / (C / 8), ch = f % (C / 8);
                 *reinterpret_cast<u32x4_t*>(lds + row * WSTRIDE + ch * 16) = *reinterpret_cast<const u32x4_t*>(w1 + (size_t)f * 16);
             }
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
         const int valid = max(0, min(kMlpTile, n_ctx - t0)) * CPR;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-            const int f = i * 256 + tid;
+            const int f = i * NT + tid;
             u32x4_t a = {0u, 0u, 0u, 0u}, c2 = {0u, 0u, 0u, 0u};
             smk[i] = smv[i] = u32x2_t{0x3f800000u, 0u};
             if (f < valid) {
@@ -219,7 +220,7 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
         // ---- park the tile (all threads), prefetch the next ---------------------------------------
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-            const int f = i * 256 + tid;
+            const int f = i * NT + tid;
             if (f < kMlpTile * CPR) {
                 const int row = f / CPR, ch = f % CPR;
                 if constexpr (kI8) {
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
                 for (int s = 0; s < 2; ++s) sT = MMma<E>::mfma(ha[s], qb[mb][s], sT);
             }
         }
-        // ---- sum the partial scores of the four waves ---------------------------------------------
+        // ---- sum the partial scores of the waves ---------------------------------------------
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             *reinterpret_cast<f32x4_t*>(sbuf + ((size_t)wave * 64 + lane) * 16 + 4 * q) = f32x4_t{sT[4 * q], sT[4 * q + 1], sT[4 * q + 2], sT[4 * q + 3]};
@@ -284,7 +285,7 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
         for (int q = 0; q < 4; ++q) {
             f32x4_t s4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int w = 0; w < 4; ++w) s4 += *reinterpret_cast<const f32x4_t*>(sbuf + ((size_t)w * 64 + lane) * 16 + 4 * q);
+            for (int w = 0; w < NW; ++w) s4 += *reinterpret_cast<const f32x4_t*>(sbuf + ((size_t)w * 64 + lane) * 16 + 4 * q);
 #pragma unroll
             for (int e = 0; e < 4; ++e) sT[4 * q + e] = s4[e];
         }
@@ -353,7 +354,7 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
         __syncthreads();          // tile and score buffers are rewritten by the next iteration
     }
 
-    // ---- partial: every wave owns its hidden slice; m and l are the same in all four ------------------
+    // ---- partial: every wave owns its hidden slice; m and l are the same in all of them ------------------
     l_run += __shfl_xor(l_run, 32);
     float* part = p.part + ((size_t)b * p.n_splits + split) * p.part_stride + g.part_off;
     constexpr int PSTRIDE = C + 4;
@@ -368,23 +369,28 @@ __global__ __launch_bounds__(256, 1) void attend_mlp_mfma_kernel(AttendParams p)
     }
 }
 
+// Waves per workgroup: the hidden width is split over them in 32-column blocks; eight for the 256-wide shape
+// (two waves per SIMD: a wave alone issues vector instructions at half the SIMD's rate), four for the 128-wide one.
+template <int C> struct MlpWaves { static constexpr int value = C >= 256 ? 8 : 4; };
+
 template <typename E, int R, int C, bool kI8>
 static hipError_t launch_mlp(const AttendParams& p, int act, hipStream_t stream) {
-    const size_t loop_lds = 2 * (size_t)kMlpTile * (2 * R + 16) + (size_t)4 * 64 * 16 * sizeof(float);
+    constexpr int NW = MlpWaves<C>::value;
+    const size_t loop_lds = 2 * (size_t)kMlpTile * (2 * R + 16) + (size_t)NW * 64 * 16 * sizeof(float);
     const size_t stage_lds = (size_t)R * (2 * C + 32);            // first-layer weights pass through LDS at start
     const size_t lds = loop_lds > stage_lds ? loop_lds : stage_lds;
     dim3 grid(p.n_splits, p.batch, p.n_groups);
     static bool attr[2] = {false, false};
-    auto kg = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_GELU, kI8>;
-    auto kl = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_LEAKY_RELU, kI8>;
+    auto kg = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_GELU, kI8, NW>;
+    auto kl = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_LEAKY_RELU, kI8, NW>;
     const int ai = act == KVCAR_ACT_GELU ? 0 : 1;
     if (!attr[ai]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ai == 0 ? kg : kl), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr[ai] = true;
     }
-    if (ai == 0) hipLaunchKernelGGL(kg, grid, dim3(256), lds, stream, p);
-    else hipLaunchKernelGGL(kl, grid, dim3(256), lds, stream, p);
+    if (ai == 0) hipLaunchKernelGGL(kg, grid, dim3(64 * NW), lds, stream, p);
+    else hipLaunchKernelGGL(kl, grid, dim3(64 * NW), lds, stream, p);
     return hipGetLastError();
 }
 
