@@ -44,16 +44,17 @@ constexpr int kEncTokens = 16 * kEncWaves;        // tokens per workgroup
 constexpr int kWRowBytes = 64 * 1024;             // weight rows staged per chunk
 constexpr int kWBufBytes = kWRowBytes + 1024;     // + slack: column blocks past a narrow matrix are read (and ignored)
 
-// Stage rows [row0, row0 + n_rows) of a row-major [k, n] weight matrix into LDS (padded rows).
-__device__ __forceinline__ void stage_weights(char* buf, const char* w, int n, int row0, int n_rows, int stride) {
-    const int cpr = n >> 3;                               // 16-byte chunks per row
+// Stage rows [row0, row0 + n_rows), columns [col0, col0 + n_cols) of a row-major [k, n] weight matrix into LDS
+// (padded rows of n_cols elements).
+__device__ __forceinline__ void stage_weights(char* buf, const char* w, int n, int row0, int n_rows, int stride, int col0, int n_cols) {
+    const int cpr = n_cols >> 3;                          // 16-byte chunks per staged row
     const unsigned inv = (1u << 20) / cpr + 1;
     const int total = n_rows * cpr;
-    const char* src = w + (size_t)row0 * n * 2;
+    const char* src = w + ((size_t)row0 * n + col0) * 2;
     for (int f = threadIdx.x; f < total; f += 256) {
         const unsigned row = ((unsigned)f * inv) >> 20;
         const unsigned ch = f - row * cpr;
-        *reinterpret_cast<u32x4_t*>(buf + row * stride + ch * 16) = *reinterpret_cast<const u32x4_t*>(src + (size_t)f * 16);
+        *reinterpret_cast<u32x4_t*>(buf + row * stride + ch * 16) = *reinterpret_cast<const u32x4_t*>(src + ((size_t)row * n + ch * 8) * 2);
     }
 }
 
@@ -71,7 +72,10 @@ __device__ __forceinline__ void mma_kstep(f32x4_t (&acc)[NB], u32x4_t a, const c
 
 // NB1: 16-column blocks of the first layer's output (hidden width, or latent width if linear);
 // NB2: of the second layer's output (latent width; unused if linear).
-template <typename E, int NB1, int NB2, bool kTwoLayer>
+// kSplit (linear encoder, rows in the model dtype): the latent columns are dealt over blockIdx.z in windows of
+// 16 * NB1, each workgroup reading only its window of the weight matrix.  A decode step encodes a handful of
+// tokens: without the split one workgroup per tensor streams the whole matrix (590 KB for 768 -> 384) alone.
+template <typename E, int NB1, int NB2, bool kTwoLayer, bool kSplit = false>
 __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const EncodeSide& s = p.s[blockIdx.y];
@@ -85,7 +89,10 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
 
     char* wbuf = lds;
     const int n1 = kTwoLayer ? s.hidden : s.r;
-    const int stride1 = 2 * n1 + 32;
+    const int col0 = kSplit ? (int)blockIdx.z * 16 * NB1 : 0;          // first output column of this workgroup
+    if (kSplit && col0 >= n1) return;
+    const int w1cols = kSplit ? min(16 * NB1, n1 - col0) : n1;         // staged window
+    const int stride1 = 2 * w1cols + 32;
 
     // ---- layer 1: out1[16, n1] = x[cols] W1 ----------------------------------------------------
     f32x4_t acc1[NB1];
@@ -96,7 +103,7 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
         for (int row0 = 0; row0 < s.in_width; row0 += rows_cap) {
             const int n_rows = min(rows_cap, s.in_width - row0);
             __syncthreads();                              // previous chunk fully consumed
-            stage_weights(wbuf, static_cast<const char*>(s.w1), n1, row0, n_rows, stride1);
+            stage_weights(wbuf, static_cast<const char*>(s.w1), n1, row0, n_rows, stride1, col0, w1cols);
             __syncthreads();
             for (int k0 = 0; k0 < n_rows; k0 += 32) {
                 const int kk = row0 + k0 + 8 * lg;        // first of this lane's 8 input columns
@@ -142,7 +149,7 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
         for (int row0 = 0; row0 < s.hidden; row0 += rows_cap) {
             const int n_rows = min(rows_cap, s.hidden - row0);
             __syncthreads();
-            stage_weights(wbuf, static_cast<const char*>(s.w2), s.r, row0, n_rows, stride2);
+            stage_weights(wbuf, static_cast<const char*>(s.w2), s.r, row0, n_rows, stride2, 0, s.r);
             __syncthreads();
             for (int k0 = 0; k0 < n_rows; k0 += 32) {
                 const int off = l16 * stride_h + (row0 + k0 + 8 * lg) * 2;
@@ -211,7 +218,7 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
     uint16_t* z = static_cast<uint16_t*>(s.z);
 #pragma unroll
     for (int nb = 0; nb < (kTwoLayer ? NB2 : NB1); ++nb) {
-        const int col = nb * 16 + l16;
+        const int col = col0 + nb * 16 + l16;
         if (nb < n_out_blocks && col < s.r) {
             const float bias = out_bias ? Elem<E>::load(out_bias, col) : 0.f;
 #pragma unroll
@@ -222,14 +229,14 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
 }
 
 template <typename K>
-static hipError_t launch_enc(K kern, size_t lds, const EncodeParams& p, hipStream_t stream, bool& attr_set) {
+static hipError_t launch_enc(K kern, size_t lds, const EncodeParams& p, hipStream_t stream, bool& attr_set, int col_windows = 1) {
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int n_tok = p.batch * p.t_new;
-    dim3 grid((n_tok + kEncTokens - 1) / kEncTokens, 2);
+    dim3 grid((n_tok + kEncTokens - 1) / kEncTokens, 2, col_windows);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
     return hipGetLastError();
 }
@@ -260,6 +267,12 @@ hipError_t launch_encode_mfma(const EncodeParams& p, int dtype, hipStream_t stre
                   : launch_enc(encode_mfma_kernel<F16, 16, 8, true>, lds, p, stream, set[1]);
     }
     const size_t lds = kWBufBytes;
+    // few tokens (a decode step), rows in the model dtype: 32-column windows over blockIdx.z (int8 rows need the
+    // whole row in one workgroup for their minimum and maximum)
+    const bool i8 = p.s[0].meta != nullptr || p.s[1].meta != nullptr;
+    if (!i8 && (long long)p.batch * p.t_new <= 2048)
+        return bf ? launch_enc(encode_mfma_kernel<BF16, 2, 1, false, true>, lds, p, stream, set[6], (rmax + 31) / 32)
+                  : launch_enc(encode_mfma_kernel<F16, 2, 1, false, true>, lds, p, stream, set[7], (rmax + 31) / 32);
     if (rmax <= 128)
         return bf ? launch_enc(encode_mfma_kernel<BF16, 8, 1, false>, lds, p, stream, set[2])
                   : launch_enc(encode_mfma_kernel<F16, 8, 1, false>, lds, p, stream, set[3]);

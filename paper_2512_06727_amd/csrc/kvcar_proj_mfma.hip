@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void qtilde_mfma_kernel(AttendParams p) {
 // ---------------------------------------------------------------------------------------------
 constexpr int kCombMaxSplits = 32;
 
-template <typename E, int NBO>
+template <typename E, int NBO, int kPf>
 __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int rows_per_wg) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const GroupDesc& g = p.g[blockIdx.z];
@@ -165,6 +165,26 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
     float* om = reinterpret_cast<float*>(lds + (size_t)rv * stride_w + 1024);   // [rows_per_wg][rv + 4]
     float* wts = om + (size_t)rows_per_wg * pstride;                    // [rows_per_wg][ns]
 
+    // Small launches are a chain of memory round trips (decoder slice, (m, l) pairs, latent sums): when a thread
+    // has at most kPf items of phase 1b, their first four splits are requested here, before anything waits on
+    // memory, so that the three share one round trip.
+    const int c4n = rv >> 2;
+    constexpr bool prefetch = kPf > 0;                      // the launcher picks kPf >= items per thread, or 0
+    f32x4_t xp[kPf > 0 ? kPf : 1][4];
+    if constexpr (prefetch) {
+#pragma unroll
+        for (int it = 0; it < kPf; ++it) {
+            const int idx = it * 256 + threadIdx.x;
+            const int r = idx / c4n, c4 = idx - r * c4n;
+            const int row = wg_row0 + r;
+            const bool live = idx < rows_per_wg * c4n && row < rows;
+            const int b = live ? row / len : 0, i = live ? row - b * len : 0;
+            const float* prow = p.part + (size_t)b * ns * p.part_stride + g.part_off + (size_t)(s0 + i) * pstride + 4 + 4 * (live ? c4 : 0);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                xp[it][u] = live && u < ns ? *reinterpret_cast<const f32x4_t*>(prow + (size_t)u * p.part_stride) : f32x4_t{0.f, 0.f, 0.f, 0.f};
+        }
+    }
     {   // phase 0
         const int cpr = dh >> 3;
         const int total = rv * cpr;
@@ -228,8 +248,33 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
     }
     __syncthreads();
     // phase 1b: merged, normalised latent sums
-    {
-        const int c4n = rv >> 2;
+    if constexpr (prefetch) {
+#pragma unroll
+        for (int it = 0; it < kPf; ++it) {
+            const int idx = it * 256 + threadIdx.x;
+            if (idx >= rows_per_wg * c4n) continue;
+            const int r = idx / c4n, c4 = idx - r * c4n;
+            const int row = wg_row0 + r;
+            f32x4_t a = {0.f, 0.f, 0.f, 0.f};
+            if (row < rows) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (u < ns) a += xp[it][u] * wts[r * ns + u];
+                const int b = row / len, i = row - b * len;
+                const float* prow = p.part + (size_t)b * ns * p.part_stride + g.part_off + (size_t)(s0 + i) * pstride + 4 + 4 * c4;
+                for (int k = 4; k < ns; k += 4) {
+                    f32x4_t x[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        x[u] = k + u < ns ? *reinterpret_cast<const f32x4_t*>(prow + (size_t)(k + u) * p.part_stride) : f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (k + u < ns) a += x[u] * wts[r * ns + k + u];
+                }
+            }
+            *reinterpret_cast<f32x4_t*>(om + (size_t)r * pstride + 4 * c4) = a;
+        }
+    } else {
         for (int idx = threadIdx.x; idx < rows_per_wg * c4n; idx += 256) {
             const int r = idx / c4n, c4 = idx - r * c4n;
             const int row = wg_row0 + r;
@@ -344,19 +389,26 @@ hipError_t launch_qtilde_mfma(const AttendParams& p, int dtype, hipStream_t stre
 }
 
 hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
-    static bool attr[2] = {false, false};
     int max_len, rmax = 0;
     const int segs = max_segments(p, false, max_len);
     for (int i = 0; i < p.n_groups; ++i) rmax = p.g[i].v.c > rmax ? p.g[i].v.c : rmax;
-    const int rows_per_wg = rmax <= 128 ? 64 : 16;
+    // 64 rows per workgroup for narrow rows; 16 when the launch is small (more workgroups, and few enough items
+    // per thread for the kernel to request everything at once)
+    const long long rows_all = (long long)p.batch * max_len * segs * p.n_groups;
+    const int rows_per_wg = rmax <= 128 && rows_all > 64 * 64 ? 64 : 16;
     const size_t lds = (size_t)rmax * (2 * p.d_head + 32) + 1024 + (size_t)rows_per_wg * (rmax + 4 + 3 * p.n_splits + 2) * sizeof(float);
     dim3 grid((p.batch * max_len + rows_per_wg - 1) / rows_per_wg, segs, p.n_groups);
-    const int e = dtype == KVCAR_BF16 ? 0 : 1;
-    auto kern = e == 0 ? combine_mfma_kernel<BF16, 8> : combine_mfma_kernel<F16, 8>;
-    if (!attr[e]) {
+    const int items = (rows_per_wg * (rmax >> 2) + 255) / 256;        // phase-1b items per thread
+    const int pf = items <= 2 ? 2 : items <= 6 ? 6 : 0;
+    void (*kern)(AttendParams, int);
+    if (dtype == KVCAR_BF16) kern = pf == 2 ? combine_mfma_kernel<BF16, 8, 2> : pf == 6 ? combine_mfma_kernel<BF16, 8, 6> : combine_mfma_kernel<BF16, 8, 0>;
+    else kern = pf == 2 ? combine_mfma_kernel<F16, 8, 2> : pf == 6 ? combine_mfma_kernel<F16, 8, 6> : combine_mfma_kernel<F16, 8, 0>;
+    const int slot = (dtype == KVCAR_BF16 ? 0 : 3) + (pf == 2 ? 1 : pf == 6 ? 2 : 0);
+    static bool attr[6] = {};
+    if (!attr[slot]) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (err != hipSuccess) return err;
-        attr[e] = true;
+        attr[slot] = true;
     }
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p, rows_per_wg);
     return hipGetLastError();
