@@ -51,10 +51,22 @@ __device__ __forceinline__ void stage_weights(char* buf, const char* w, int n, i
     const unsigned inv = (1u << 20) / cpr + 1;
     const int total = n_rows * cpr;
     const char* src = w + ((size_t)row0 * n + col0) * 2;
-    for (int f = threadIdx.x; f < total; f += 256) {
-        const unsigned row = ((unsigned)f * inv) >> 20;
-        const unsigned ch = f - row * cpr;
-        *reinterpret_cast<u32x4_t*>(buf + row * stride + ch * 16) = *reinterpret_cast<const u32x4_t*>(src + ((size_t)row * n + ch * 8) * 2);
+    // eight chunks per thread in flight: a copy loop that stores each chunk before loading the next pays one
+    // memory round trip per chunk
+    for (int f0 = threadIdx.x; f0 < total; f0 += 8 * 256) {
+        u32x4_t t[8];
+        unsigned dst[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int f = f0 + u * 256;
+            const unsigned row = ((unsigned)f * inv) >> 20;
+            const unsigned ch = f - row * cpr;
+            dst[u] = row * stride + ch * 16;
+            if (f < total) t[u] = *reinterpret_cast<const u32x4_t*>(src + ((size_t)row * n + ch * 8) * 2);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (f0 + u * 256 < total) *reinterpret_cast<u32x4_t*>(buf + dst[u]) = t[u];
     }
 }
 

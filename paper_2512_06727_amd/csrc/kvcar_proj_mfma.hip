@@ -189,10 +189,20 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
         const int cpr = dh >> 3;
         const int total = rv * cpr;
         const char* src = static_cast<const char*>(g.v.wl);
-        for (int f = threadIdx.x; f < total; f += 256) {
-            const int row = f / cpr, ch = f - row * cpr;
-            *reinterpret_cast<u32x4_t*>(wbuf + row * stride_w + ch * 16) =
-                *reinterpret_cast<const u32x4_t*>(src + ((size_t)row * g.v.in_width + col) * 2 + ch * 16);
+        // eight chunks per thread in flight (a load-store-load-store loop pays one round trip per chunk)
+        for (int f0 = threadIdx.x; f0 < total; f0 += 8 * 256) {
+            u32x4_t t[8];
+            int dst[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int f = f0 + u * 256;
+                const int row = f / cpr, ch = f - row * cpr;
+                dst[u] = row * stride_w + ch * 16;
+                if (f < total) t[u] = *reinterpret_cast<const u32x4_t*>(src + ((size_t)row * g.v.in_width + col) * 2 + ch * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (f0 + u * 256 < total) *reinterpret_cast<u32x4_t*>(wbuf + dst[u]) = t[u];
         }
     }
     // phase 1a: per-row merge weights.  All (row, split) pairs fetch their m and l at once (a serial
