@@ -253,6 +253,82 @@ def bench_prefill(args):
     print(json.dumps(result))
 
 
+def bench_per_head(args):
+    """Secondary measurement: the per-head (block-diagonal) autoencoder variant of the workload - one library
+    context per KV head, latent / H_kv columns each (harness.PerHeadSessions).  A reused head then reads only its
+    own rows of the source layer, so the step moves the bytes of the map-free workload while storing what the map
+    leaves.  A step = for every layer and KV head, kvcar_encode_append + kvcar_decode_attention."""
+    import torch
+    from paper_2512_06727_amd import binding, synth
+    from paper_2512_06727_amd.harness import PerHeadSessions
+
+    total_steps = args.steps + args.warmup
+    w = synth.CONFIGS[args.workload].scaled(n_steps=total_steps)
+    if args.batch:
+        w = w.scaled(batch=args.batch)
+    if args.cached:
+        w = w.scaled(n_cached=args.cached)
+    reuse = synth.reuse_map(w)
+    elem = synth.DTYPE_BYTES[w.dtype]
+    ph = PerHeadSessions(w, reuse)
+    t0 = time.perf_counter()
+    ph.prefill(0, w.n_cached, chunk=max(1, (1 << 25) // (w.batch * w.d_head)))
+    torch.cuda.synchronize()
+    t_fill = time.perf_counter() - t0
+    H = w.n_kv_heads
+    qs, ks, vs = [], [], []
+    for step in range(total_steps):
+        pos = w.n_cached + step
+        qs.append([[synth.queries(wg, n, step, device=s.dev).to(s.tdt) for n in range(w.n_layers)] for (wg, _), s in zip(ph.parts, ph.sessions)])
+        ks.append([[synth.kv_tokens(wg, n, 0, 0, w.batch, pos, pos + 1, device=s.dev).to(s.tdt) for n in range(w.n_layers)] for (wg, _), s in zip(ph.parts, ph.sessions)])
+        vs.append([[synth.kv_tokens(wg, n, 1, 0, w.batch, pos, pos + 1, device=s.dev).to(s.tdt) for n in range(w.n_layers)] for (wg, _), s in zip(ph.parts, ph.sessions)])
+    outs = [[torch.empty_like(qs[0][g][n]) for n in range(w.n_layers)] for g in range(H)]
+    for s in ph.sessions:
+        s.ensure_workspace(w.batch, w.max_seq)
+
+    def step_fn(step):
+        pos = w.n_cached + step
+        for n in range(w.n_layers):
+            for g, s in enumerate(ph.sessions):
+                s.ctx.encode_append(n, ks[step][g][n], vs[step][g][n], w.batch, pos, 1)
+                s.ctx.decode_attention(n, qs[step][g][n], outs[g][n], w.batch, pos + 1, s.workspace)
+
+    for step in range(args.warmup):
+        step_fn(step)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for step in range(args.warmup, total_steps):
+        step_fn(step)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    for s in ph.sessions:
+        s.ctx.profile_enable(True)
+    for step in range(args.warmup, total_steps):
+        step_fn(step)
+    attend_ms, n_launch = 0.0, 0
+    for s in ph.sessions:
+        ms, n = s.ctx.profile_read()
+        s.ctx.profile_enable(False)
+        attend_ms += ms
+        n_launch += n
+    r_h = w.latent // H
+    alg = sum(2 * r_h * elem * H * w.batch * (w.n_cached + step + 1) * w.n_layers for step in range(args.warmup, total_steps))
+    achieved = alg / (attend_ms * 1e-3) / 1e9
+    stored = sum(int((~reuse[n, k]).sum()) * r_h * elem for n in range(w.n_layers) for k in (0, 1))
+    print(json.dumps({
+        "metric": "decode-attn tokens/s over latent KV cache, per-head autoencoders", "value": w.batch * args.steps / elapsed, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "variant": "per-head autoencoders (one context per KV head)", "batch": w.batch, "cached_tokens": w.n_cached,
+                   "layers": w.n_layers, "kv_heads": H, "latent_per_head": r_h, "reuse": w.reuse, "reused_head_fraction": float(reuse[1:].mean()),
+                   "prefill_s": t_fill},
+        "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel (latent width 32)", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": alg / max(1, n_launch),
+                     "avg_launch_ms": attend_ms / max(1, n_launch), "launches": n_launch},
+        "bytes_per_token_stored": stored, "bytes_per_token_read_per_step": 2 * r_h * elem * H * w.n_layers,
+    }))
+
+
 def capacity_check(args):
     """Capacity leg (the analogue of the paper's maximum-sequence-length-before-OOM measurement, Results,
     "System Evaluation"): allocate latent caches for as many cached tokens as fit in this GPU's free memory
@@ -356,6 +432,8 @@ def main():
     ap.add_argument("--op", default="decode", choices=["decode", "l1dist", "prefill"],
                     help="decode: the decode step (default, the headline); l1dist: the reuse-map selection statistic over the workload's tokens; "
                          "prefill: encode + causal attention of a whole prompt (default batch 16 x 4096 tokens of the chosen workload's shape)")
+    ap.add_argument("--per-head", action="store_true",
+                    help="the per-head (block-diagonal) autoencoder variant: one context per KV head, reuse adds no cache traffic")
     ap.add_argument("--no-fuse", action="store_true", help="run prologue / attention / merge as separate kernels")
     ap.add_argument("--capacity-check", action="store_true",
                     help="allocate latent caches for as many tokens as fit in free HBM, run one decode step over them, report")
@@ -381,6 +459,8 @@ def main():
         return bench_prefill(args)
     if args.capacity_check:
         return capacity_check(args)
+    if args.per_head:
+        return bench_per_head(args)
     base = synth.CONFIGS[args.workload]
     total_steps = args.steps + args.warmup
     w = base.scaled(n_steps=total_steps)

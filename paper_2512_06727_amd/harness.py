@@ -118,3 +118,33 @@ class Session:
             out = torch.empty_like(q)
         self.ctx.prefill_attention(layer, q, out, b, pos0, t, self.prefill_ws)
         return out
+
+
+def per_head_workloads(w: synth.Workload, reuse: Optional[np.ndarray] = None):
+    """The per-head (block-diagonal) autoencoder variant of a workload: every KV head has its own autoencoder
+    d_head -> latent / H_kv -> d_head and its own latent rows, so the model splits into H_kv independent
+    single-KV-head models.  Returns [(workload of head g, its reuse map [n_layers, 2, 1])]; head g's weights
+    and activations come from seed streams of their own."""
+    reuse = synth.reuse_map(w) if reuse is None else reuse
+    gq = w.n_q_heads // w.n_kv_heads
+    return [(w.scaled(name=f"{w.name}-head{g}", n_q_heads=gq, n_kv_heads=1, latent=w.latent // w.n_kv_heads,
+                      seed=w.seed + 7919 * (g + 1), reuse="none"), reuse[:, :, g:g + 1].copy())
+            for g in range(w.n_kv_heads)]
+
+
+class PerHeadSessions:
+    """One library context per KV head (the per-head autoencoder variant): a head that reuses the previous
+    layer's keys or values reads only that head's rows of the source layer, so reuse adds no cache traffic."""
+
+    def __init__(self, w: synth.Workload, reuse: Optional[np.ndarray] = None, **session_kw):
+        self.w = w
+        self.parts = per_head_workloads(w, reuse)
+        self.sessions = [Session(wg, reuse=rg, **session_kw) for wg, rg in self.parts]
+
+    def prefill(self, t0: int, t1: int, **kw):
+        for s in self.sessions:
+            s.prefill(t0, t1, **kw)
+
+    def decode_attention(self, layer: int, qs, n_ctx: int):
+        """qs: one [batch, H_q / H_kv, d_head] tensor per KV head; returns [batch, H_q, d_head]."""
+        return torch.cat([s.decode_attention(layer, q, n_ctx) for s, q in zip(self.sessions, qs)], dim=1)
