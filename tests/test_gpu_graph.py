@@ -49,3 +49,46 @@ def test_graph_replays_match_eager(fmt, splits):
         torch.cuda.synchronize()
         for n in range(w.n_layers):
             assert torch.equal(outs[n], want[n]), f"replay {replay}, layer {n}"
+
+
+@pytest.mark.parametrize("hidden", [0, 256])
+def test_prefill_graph_replays_match_eager(hidden):
+    """The prompt phase (encode of the chunk + prefill attention, every layer) captured and replayed."""
+    base = synth.CONFIGS[3] if hidden else synth.CONFIGS[2]
+    w = base.scaled(n_layers=3, batch=2, n_cached=300, n_steps=0)
+    ses = Session(w)
+    dev, tdt = ses.dev, ses.tdt
+    T = w.n_cached
+    ks = [synth.kv_tokens(w, n, 0, 0, w.batch, 0, T, device=dev).to(tdt) for n in range(w.n_layers)]
+    vs = [synth.kv_tokens(w, n, 1, 0, w.batch, 0, T, device=dev).to(tdt) for n in range(w.n_layers)]
+    qs = [synth.prompt_queries(w, n, 0, w.batch, 0, T, device=dev, gain=10.0).to(tdt) for n in range(w.n_layers)]
+    outs = [torch.empty_like(q) for q in qs]
+    ws = torch.empty(ses.ctx.prefill_workspace_bytes(w.batch, T), dtype=torch.uint8, device=dev)
+
+    def step():
+        for n in range(w.n_layers):
+            ses.ctx.encode_append(n, ks[n], vs[n], w.batch, 0, T)
+            ses.ctx.prefill_attention(n, qs[n], outs[n], w.batch, 0, T, ws)
+
+    step()
+    torch.cuda.synchronize()
+    want = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for replay in range(3):
+        for o in outs:
+            o.fill_(float("nan"))
+        ws.fill_(0xFF)                            # the decoded rows of the last call are not relied on
+        scratch = torch.randn(1 << 16, device=dev).sum().item()      # a library reduction with a host sync between replays
+        assert scratch == scratch
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in range(w.n_layers):
+            assert torch.equal(outs[n], want[n]), f"replay {replay}, layer {n}"
