@@ -240,6 +240,98 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
     }
 }
 
+// Decode steps with int8 latents (linear encoder, few tokens): a row's minimum and maximum need the whole row, so
+// the columns cannot be dealt over workgroups; instead a workgroup takes 16 tokens and its four waves split the
+// columns (wave w: 16-column blocks w, w + 4, ..), meeting once in LDS for the row extremes.  Four times the
+// workgroups of the general kernel and a quarter of the serial work per wave.
+template <typename E, int NBW>
+__global__ __launch_bounds__(256) void encode_i8_step_kernel(EncodeParams p) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const EncodeSide& s = p.s[blockIdx.y];
+    if (s.r == 0) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, lg = lane >> 4;
+    const int n_tok = p.batch * p.t_new;
+    const int tok = blockIdx.x * 16 + l16;                          // the A-operand row of this lane (the same in every wave)
+    const bool tok_ok = tok < n_tok;
+    const char* xrow = static_cast<const char*>(s.x) + (size_t)(tok_ok ? tok : 0) * p.d_kv * 2;
+    char* wbuf = lds;
+    float* ext = reinterpret_cast<float*>(lds + kWBufBytes);        // [4 waves][16 tokens][min, max]
+    const int stride1 = 2 * s.r + 32;
+
+    f32x4_t acc[NBW];
+#pragma unroll
+    for (int nb = 0; nb < NBW; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const int rows_cap = (kWRowBytes / stride1) & ~31;
+    for (int row0 = 0; row0 < s.in_width; row0 += rows_cap) {
+        const int n_rows = min(rows_cap, s.in_width - row0);
+        __syncthreads();
+        stage_weights(wbuf, static_cast<const char*>(s.w1), s.r, row0, n_rows, stride1, 0, s.r);
+        __syncthreads();
+        for (int k0 = 0; k0 < n_rows; k0 += 32) {
+            const int kk = row0 + k0 + 8 * lg;
+            const int src_col = (int)s.heads[kk / p.d_head] * p.d_head + kk % p.d_head;
+            u32x4_t a = {0u, 0u, 0u, 0u};
+            if (tok_ok) a = *reinterpret_cast<const u32x4_t*>(xrow + src_col * 2);
+            const char* wrow = wbuf + (k0 + 8 * lg + (l16 >> 2)) * stride1 + (l16 & 3) * 8;
+#pragma unroll
+            for (int nb = 0; nb < NBW; ++nb) {
+                const int blk = wave + 4 * nb;                      // reads past the matrix land in the buffer's slack and are ignored
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(wrow + blk * 32));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(wrow + blk * 32 + 4 * stride1));
+                const u32x2_t lo2 = __builtin_bit_cast(u32x2_t, lo), hi2 = __builtin_bit_cast(u32x2_t, hi);
+                acc[nb] = EncMma<E>::mfma(a, u32x4_t{lo2[0], lo2[1], hi2[0], hi2[1]}, acc[nb]);
+            }
+        }
+    }
+    // this lane: column 16 (wave + 4 nb) + l16 of tokens 4 lg + v
+    float mn[4], mx[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) { mn[v] = INFINITY; mx[v] = -INFINITY; }
+#pragma unroll
+    for (int nb = 0; nb < NBW; ++nb) {
+        const int col = 16 * (wave + 4 * nb) + l16;
+        if (col < s.r) {
+            const float bias = s.b1 ? Elem<E>::load(s.b1, col) : 0.f;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                acc[nb][v] += bias;
+                mn[v] = fminf(mn[v], acc[nb][v]);
+                mx[v] = fmaxf(mx[v], acc[nb][v]);
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) {
+            mn[v] = fminf(mn[v], __shfl_xor(mn[v], off));
+            mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], off));
+        }
+        if (l16 == 0) { ext[(wave * 16 + 4 * lg + v) * 2] = mn[v]; ext[(wave * 16 + 4 * lg + v) * 2 + 1] = mx[v]; }
+    }
+    __syncthreads();
+    signed char* z8 = static_cast<signed char*>(s.z);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int tl = 4 * lg + v, t = blockIdx.x * 16 + tl;
+        float lo = ext[tl * 2], hi = ext[tl * 2 + 1];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) { lo = fminf(lo, ext[(w * 16 + tl) * 2]); hi = fmaxf(hi, ext[(w * 16 + tl) * 2 + 1]); }
+        const QuantParams qp = quant_params(lo, hi);
+        if (t >= n_tok) continue;
+        const int b = t / p.t_new, tt = t - b * p.t_new;
+        const size_t row = (size_t)b * p.max_seq + (p.positions ? p.positions[b] : p.pos0) + tt;
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb) {
+            const int col = 16 * (wave + 4 * nb) + l16;
+            if (col < s.r) z8[row * s.r + col] = quant_code(acc[nb][v], qp);
+        }
+        if (wave == 0 && l16 == 0) static_cast<RowMeta*>(s.meta)[row] = quant_meta(qp);
+    }
+}
+
+
 template <typename K>
 static hipError_t launch_enc(K kern, size_t lds, const EncodeParams& p, hipStream_t stream, bool& attr_set, int col_windows = 1) {
     if (!attr_set) {
@@ -282,6 +374,22 @@ hipError_t launch_encode_mfma(const EncodeParams& p, int dtype, hipStream_t stre
     // few tokens (a decode step), rows in the model dtype: 32-column windows over blockIdx.z (int8 rows need the
     // whole row in one workgroup for their minimum and maximum)
     const bool i8 = p.s[0].meta != nullptr || p.s[1].meta != nullptr;
+    if (i8 && (long long)p.batch * p.t_new <= 2048) {
+        const size_t lds8 = kWBufBytes + 4 * 16 * 2 * sizeof(float);
+        const int n_tok = p.batch * p.t_new;
+        dim3 grid((n_tok + 15) / 16, 2);
+        static bool set8[4] = {false, false, false, false};
+        const int slot = (bf ? 0 : 2) + (rmax <= 128 ? 0 : 1);
+        void (*k8)(EncodeParams) = bf ? (rmax <= 128 ? encode_i8_step_kernel<BF16, 2> : encode_i8_step_kernel<BF16, 6>)
+                                      : (rmax <= 128 ? encode_i8_step_kernel<F16, 2> : encode_i8_step_kernel<F16, 6>);
+        if (!set8[slot]) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k8), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            set8[slot] = true;
+        }
+        hipLaunchKernelGGL(k8, grid, dim3(256), lds8, stream, p);
+        return hipGetLastError();
+    }
     if (!i8 && (long long)p.batch * p.t_new <= 2048)
         return bf ? launch_enc(encode_mfma_kernel<BF16, 2, 1, false, true>, lds, p, stream, set[6], (rmax + 31) / 32)
                   : launch_enc(encode_mfma_kernel<F16, 2, 1, false, true>, lds, p, stream, set[7], (rmax + 31) / 32);
