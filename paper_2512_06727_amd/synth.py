@@ -126,7 +126,7 @@ class Workload:
         return dataclasses.replace(self, **kw)
 
 
-# The five configurations of the build's baseline file, in its order.
+# The five benchmark configurations: GPT-2-small and TinyLlama-1.1B shapes at growing batch and context.
 CONFIGS: Tuple[Workload, ...] = (
     Workload("gpt2-1layer-f32", 1, 12, 12, 64, batch=1, n_cached=128, n_steps=1, dtype="f32", latent=384),
     Workload("gpt2-12layer-f16", 12, 12, 12, 64, batch=8, n_cached=1024, n_steps=64, dtype="f16", latent=384,
