@@ -105,3 +105,48 @@ def test_ragged_append_positions_write_the_rows_a_per_sequence_append_writes():
             np.testing.assert_array_equal(a.Z[(0, which)][i, p0], one.Z[(0, which)][0, p0])
             others = [t for t in range(8) if t != p0]
             assert np.isnan(a.Z[(0, which)][i, others]).all()
+
+
+def test_block_diagonal_autoencoders_decompose_by_head():
+    """A model whose autoencoders are block-diagonal over the KV heads is H_kv independent single-head
+    models: the full-model oracle with block-diagonal dense matrices equals per-head oracles side by side
+    (the mapping the per-head variant of the library relies on), also under a reuse map."""
+    hkv, gq, dh, rh, L, n_layers = 3, 2, 4, 2, 6, 3
+    reuse = np.zeros((n_layers, 2, hkv), dtype=bool)
+    reuse[1, :, 1] = True
+    reuse[2, 0, 1] = True          # chain for K, own V again in layer 2
+    reuse[2, :, 2] = True
+    full = O.KVCAROracle(n_layers, hkv * gq, hkv, dh, 1, L, "f32")
+    heads = [O.KVCAROracle(n_layers, gq, 1, dh, 1, L, "f32") for _ in range(hkv)]
+    for n in range(n_layers):
+        full.set_reuse_map(n, reuse[n, 0], reuse[n, 1])
+        for g in range(hkv):
+            heads[g].set_reuse_map(n, reuse[n, 0, g:g + 1], reuse[n, 1, g:g + 1])
+    for n in range(n_layers):
+        for which in (0, 1):
+            stored = [g for g in range(hkv) if not reuse[n, which, g]]
+            enc = {g: (rand(dh, rh), rand(rh)) for g in range(hkv)}
+            dec = {g: (rand(rh, dh), rand(dh)) for g in range(hkv)}
+            for g in range(hkv):
+                if g in stored:
+                    heads[g].set_autoencoder(n, which, O.Autoencoder([0], [enc[g]], [dec[g]]))
+                else:
+                    heads[g].set_autoencoder(n, which, O.Autoencoder([], [(np.zeros((0, 0)), None)], [(np.zeros((0, 0)), None)]))
+            we = np.zeros((len(stored) * dh, len(stored) * rh))
+            wd = np.zeros((len(stored) * rh, len(stored) * dh))
+            for i, g in enumerate(stored):
+                we[i * dh:(i + 1) * dh, i * rh:(i + 1) * rh] = enc[g][0]
+                wd[i * rh:(i + 1) * rh, i * dh:(i + 1) * dh] = dec[g][0]
+            be = np.concatenate([enc[g][1] for g in stored]) if stored else None
+            bd = np.concatenate([dec[g][1] for g in stored]) if stored else None
+            full.set_autoencoder(n, which, O.Autoencoder(stored, [(we, be)], [(wd, bd)]))
+    for n in range(n_layers):
+        k, v = rand(1, L, hkv * dh), rand(1, L, hkv * dh)
+        full.encode_append(n, k, v, 0)
+        for g in range(hkv):
+            heads[g].encode_append(n, k[:, :, g * dh:(g + 1) * dh], v[:, :, g * dh:(g + 1) * dh], 0)
+    for n in range(n_layers):
+        q = rand(1, hkv * gq, dh)
+        want = full.decode_attention(n, q, L)
+        got = np.concatenate([heads[g].decode_attention(n, q[:, g * gq:(g + 1) * gq], L) for g in range(hkv)], axis=1)
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
