@@ -82,9 +82,8 @@ __global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParam
     static_assert(CW % 32 == 0 && R % 16 == 0, "shape");
 
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    char* tile_k = lds;
-    char* tile_v = lds + kMlpTile * STRIDE;
-    float* sbuf = reinterpret_cast<float*>(lds + 2 * kMlpTile * STRIDE);    // [wave][64 lanes][16]
+    // two buffers of a K tile + a V tile (the next tile is parked at the end of the current one), then the score exchange
+    float* sbuf = reinterpret_cast<float*>(lds + 4 * kMlpTile * STRIDE);    // [wave][64 lanes][16]
 
     const GroupDesc& g = p.g[blockIdx.z];
     const int split = blockIdx.x, b = blockIdx.y;
@@ -213,11 +212,9 @@ __global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParam
         lo = u32x4_t{w[0], w[1], w[2], w[3]};
         hi = u32x4_t{w[4], w[5], w[6], w[7]};
     };
-    if (j0 < j1) issue(j0);
-
-    for (int j = j0; j < j1; ++j) {
-        const int nv = min(kMlpTile, n_ctx - j * kMlpTile);
-        // ---- park the tile (all threads), prefetch the next ---------------------------------------
+    auto park = [&](int buf) {
+        char* tile_k = lds + buf * 2 * kMlpTile * STRIDE;
+        char* tile_v = tile_k + kMlpTile * STRIDE;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int f = i * NT + tid;
@@ -237,8 +234,18 @@ __global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParam
                 }
             }
         }
-        if (j + 1 < j1) issue(j + 1);
-        __syncthreads();
+    };
+    if (j0 < j1) {
+        issue(j0);
+        park(0);
+        if (j0 + 1 < j1) issue(j0 + 1);
+    }
+    __syncthreads();
+
+    for (int j = j0; j < j1; ++j) {
+        const int nv = min(kMlpTile, n_ctx - j * kMlpTile);
+        const char* tile_k = lds + ((j - j0) & 1) * 2 * kMlpTile * STRIDE;
+        const char* tile_v = tile_k + kMlpTile * STRIDE;
 
         // ---- H_K^T for this wave's hidden slice, then partial scores ------------------------------
         // One wave per SIMD: matrix and vector instructions only overlap if they alternate in program
@@ -351,7 +358,13 @@ __global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParam
                 for (int s = 0; s < 2; ++s) acc[mb] = MMma<E>::mfma(va[s], pb[s], acc[mb]);
             }
         }
-        __syncthreads();          // tile and score buffers are rewritten by the next iteration
+        // the next tile goes into the other buffer (its loads were issued one tile ago; that buffer was last read
+        // one tile ago, before the previous end-of-tile barrier)
+        if (j + 1 < j1) {
+            park(((j - j0) & 1) ^ 1);
+            if (j + 2 < j1) issue(j + 2);
+        }
+        __syncthreads();          // the score buffer is rewritten by the next iteration, which reads the tile just parked
     }
 
     // ---- partial: every wave owns its hidden slice; m and l are the same in all of them ------------------
@@ -376,7 +389,7 @@ template <int C> struct MlpWaves { static constexpr int value = C >= 256 ? 8 : 4
 template <typename E, int R, int C, bool kI8>
 static hipError_t launch_mlp(const AttendParams& p, int act, hipStream_t stream) {
     constexpr int NW = MlpWaves<C>::value;
-    const size_t loop_lds = 2 * (size_t)kMlpTile * (2 * R + 16) + (size_t)NW * 64 * 16 * sizeof(float);
+    const size_t loop_lds = 4 * (size_t)kMlpTile * (2 * R + 16) + (size_t)NW * 64 * 16 * sizeof(float);
     const size_t stage_lds = (size_t)R * (2 * C + 32);            // first-layer weights pass through LDS at start
     const size_t lds = loop_lds > stage_lds ? loop_lds : stage_lds;
     dim3 grid(p.n_splits, p.batch, p.n_groups);
