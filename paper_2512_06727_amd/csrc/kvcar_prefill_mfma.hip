@@ -415,7 +415,7 @@ template <int DH> struct PrefillGeo {
 };
 
 template <typename E, int DH, int QB, int NW, int OCC>
-__global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParams p, int n_qblk, int total_wg, int per_xcd) {
+__global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParams p, int n_qblk, int per_xcd) {
     using G = PrefillGeo<DH>;
     constexpr int KS = DH / 16;                 // k-steps of the score product
     constexpr int DB = DH / 32;                 // 32-column blocks of the output
@@ -426,17 +426,34 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
     constexpr int CPR = DH / 8;                 // 16-byte chunks per decoded row
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
-    // Workgroups that share decoded rows - the query heads of one KV head of one sequence - get consecutive
-    // virtual indices, heaviest query blocks first, and the virtual index space is cut into one contiguous
-    // piece per XCD (hardware deals workgroup ids round-robin over the 8 XCDs, each with its own L2).
-    const int vid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (vid >= total_wg) return;
+    // Which (sequence, KV head) pair, query block and head this workgroup takes.  Hardware deals workgroup ids
+    // round-robin over the 8 XCDs, each with its own L2; workgroups that share decoded rows - the query heads of
+    // one pair - should meet in one L2, every XCD should get the same work, and heavy (late) query blocks should
+    // start first.  per_xcd > 0: the pairs divide evenly over the XCDs; each XCD takes a contiguous run of pairs,
+    // one pair after the other, heaviest blocks first.  per_xcd == 0: any other shape (e.g. one long prompt): the
+    // (query block, pair) combinations, heaviest blocks first, are dealt round-robin over the XCDs, the heads of a
+    // combination staying together.
     const int gq = p.n_q_heads / p.n_kv_heads;
-    const int per_pair = gq * n_qblk;
-    const int pair = vid / per_pair, rem = vid - pair * per_pair;
-    const int qblk = n_qblk - 1 - rem / gq;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    int pair, qblk, jq;
+    if (per_xcd > 0) {
+        const int vid = xcd * per_xcd + slot;
+        const int per_pair = gq * n_qblk;
+        pair = vid / per_pair;
+        const int rem = vid - pair * per_pair;
+        qblk = n_qblk - 1 - rem / gq;
+        jq = rem % gq;
+    } else {
+        const int n_pairs = p.batch * p.n_kv_heads;
+        const int combo = (slot / gq) * 8 + xcd;
+        if (combo >= n_pairs * n_qblk) return;
+        const int rank = combo / n_pairs;
+        pair = combo - rank * n_pairs;
+        qblk = n_qblk - 1 - rank;
+        jq = slot % gq;
+    }
     const int b = pair / p.n_kv_heads, g = pair - b * p.n_kv_heads;
-    const int j = g * gq + rem % gq;
+    const int j = g * gq + jq;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
@@ -623,14 +640,22 @@ static hipError_t launch_prefill_one(const PrefillParams& p, hipStream_t stream)
     const int n_qblk = (p.t_new + TQ - 1) / TQ;
     const long long total = (long long)p.batch * p.n_q_heads * n_qblk;
     if (total > (1ll << 30)) return hipErrorInvalidValue;
-    const int per_xcd = (int)((total + 7) / 8);
+    const int gq = p.n_q_heads / p.n_kv_heads, n_pairs = p.batch * p.n_kv_heads;
+    int per_xcd = 0, grid;
+    if (n_pairs % 8 == 0) {
+        per_xcd = (int)(total / 8);
+        grid = (int)total;
+    } else {
+        const long long combos = (long long)n_pairs * n_qblk;
+        grid = (int)((combos + 7) / 8 * 8 * gq);
+    }
     const size_t lds = 2 * (size_t)PrefillGeo<DH>::kBuf;
     auto k = prefill_mfma_kernel<E, DH, QB, NW, OCC>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(k, dim3(per_xcd * 8), dim3(64 * NW), lds, stream, p, n_qblk, (int)total, per_xcd);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(64 * NW), lds, stream, p, n_qblk, per_xcd);
     return hipGetLastError();
 }
 
