@@ -598,6 +598,45 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         l_all[nb] = L;
     }
     if constexpr (kFused) {
+        // ---- the current token's exact row, if given ("Network Architecture", 2nd paragraph: the decoded cache
+        // rows are concatenated with the exact key / value of the current token): one more softmax term per head,
+        // s = scale q . (k_cur - b_K) (the cached scores were formed without the K decoder's bias, which cancels
+        // among them), so that  out = (L (o W + b) + 2^(s-M') v_cur) / (L + 2^(s-M')),  M' = max(M, s).
+        // Per lane (head slot nb*16 + l16): inv_l = what the accumulators are divided by, w_bias and w_cur the
+        // weights of the V decoder's bias and of v_cur.
+        const bool exact_row = p->k_cur != nullptr;
+        float inv_l[NHB], w_bias[NHB], w_cur[NHB];
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb) {
+            inv_l[nb] = l_all[nb] > 0.f ? 1.f / l_all[nb] : 0.f;     // an empty context leaves the bias
+            w_bias[nb] = 1.f;
+            w_cur[nb] = 0.f;
+        }
+        if (exact_row) {
+            const int dh = p->d_head, dq = dh >> 2;                 // each quarter of the lanes takes a quarter of the dot product
+#pragma unroll
+            for (int nb = 0; nb < NHB; ++nb) {
+                const int slot = nb * 16 + l16;
+                const int head = lane_lookup16(g->q_head, nb * 16, g->n_slots, l16, 0);
+                const int kcol = lane_lookup16(g->k_col, nb * 16, g->n_slots, l16, 0);
+                const size_t qo = ((size_t)b * p->n_q_heads + head) * dh + lg * dq;
+                const size_t ko = ((size_t)b * (p->n_q_heads / p->gq) + head / p->gq) * dh + lg * dq;
+                float d = 0.f;
+                for (int k = 0; k < dq; ++k)
+                    d = fmaf(Elem<E>::load(p->q, qo + k), Elem<E>::load(p->k_cur, ko + k) - (g->k.bl ? Elem<E>::load(g->k.bl, kcol + lg * dq + k) : 0.f), d);
+                d += __shfl_xor(d, 16);
+                d += __shfl_xor(d, 32);
+                const float s_cur = slot < g->n_slots ? d * p->scale_log2e : -INFINITY;
+                const float M = m_all[nb], M2 = fmaxf(M, s_cur);
+                const float w_cache = M == -INFINITY ? 0.f : exp2f(M - M2);
+                const float pc = s_cur == -INFINITY ? 0.f : exp2f(s_cur - M2);
+                const float L2 = l_all[nb] * w_cache + pc;
+                const float inv = L2 > 0.f ? 1.f / L2 : 0.f;
+                inv_l[nb] = w_cache * inv;
+                w_bias[nb] = l_all[nb] * w_cache * inv;
+                w_cur[nb] = pc * inv;
+            }
+        }
         // ---- epilogue: out[head, :] = (O[head, :] / L) . Wl_V[:, col(head) ..] + bias -------------------
         // The slices [rv, d_head] of the decoder matrix (one per KV head of the group, at most four) are
         // fetched into registers now, so that their latency hides under the merge of the waves.  Per KV head:
@@ -631,12 +670,19 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         // as olat[slot][rv + 4], which overlays the parked copies once every thread has read its inputs.
 #pragma unroll
         for (int nb = 0; nb < NHB; ++nb) {
-            const float sc = l_all[nb] > 0.f ? f_own[nb] / l_all[nb] : 0.f;     // an empty context leaves the bias
+            const float sc = f_own[nb] * inv_l[nb];
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
                 *reinterpret_cast<f32x4_t*>(accs + ((size_t)((wave * NHB + nb) * MB + mb) * 64 + lane) * 4) = acc[nb][mb] * sc;
         }
         __syncthreads();
+        if (exact_row && wave == 0 && lane < 16) {             // the (m, l) exchange area is free now: per-slot weights for the store
+#pragma unroll
+            for (int nb = 0; nb < NHB; ++nb) {
+                red[nb * 16 + lane] = w_bias[nb];
+                red[NHB * 16 + nb * 16 + lane] = w_cur[nb];
+            }
+        }
         constexpr int kItems = NHB * MB * 64;                  // float4 items of the merged sums
         constexpr int kPerThread = (kItems + 64 * NW - 1) / (64 * NW);
         f32x4_t merged[kPerThread];
@@ -704,8 +750,13 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int slot = nb * 16 + 4 * lg + v;
-                        if (slot >= seg_lo[sg] && slot < seg_hi[sg])
-                            out[((size_t)b * p->n_q_heads + heads4[v]) * dh + kcol] = Mma<E>::to16(o[v] + bias);
+                        if (slot >= seg_lo[sg] && slot < seg_hi[sg]) {
+                            float y = o[v] + bias;
+                            if (exact_row)
+                                y = o[v] + red[slot] * bias +
+                                    red[NHB * 16 + slot] * Elem<E>::load(p->v_cur, ((size_t)b * (p->n_q_heads / p->gq) + heads4[v] / p->gq) * dh + kcol);
+                            out[((size_t)b * p->n_q_heads + heads4[v]) * dh + kcol] = Mma<E>::to16(y);
+                        }
                     }
                 }
             }

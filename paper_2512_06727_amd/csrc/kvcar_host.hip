@@ -494,7 +494,6 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
     Plan plan;
     rc = build_plan(ctx, layer, batch, std::max(1, n_ctx), plan);
     if (rc) return rc;
-    if (exact) plan.fused = false;        // the exact current row joins the merge in the epilogue kernel
     if (!workspace || !aligned16(workspace)) return fail(ctx, KVCAR_ERR_ARG, "workspace null or misaligned");
     if (workspace_bytes < plan.total_bytes)
         return fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, plan.total_bytes);

@@ -18,6 +18,10 @@ CASES = {
     "c2-small-bf16": (C[2].scaled(n_layers=4, batch=5, n_cached=300, n_steps=1), {}, {}),
     "c2-small-bf16-1split": (C[2].scaled(n_layers=4, batch=5, n_cached=300, n_steps=1), {}, {"n_splits": 1}),
     "c4-small-bf16": (C[4].scaled(n_layers=5, batch=3, n_cached=260, n_steps=1), {}, {}),
+    # one split: prologue, attention and epilogue in one kernel, which then also takes the exact row
+    "c4-small-bf16-1split": (C[4].scaled(n_layers=8, batch=3, n_cached=260, n_steps=1), {"with_bias": True}, {"n_splits": 1}),
+    "c4-small-bf16-1split-w8": (C[4].scaled(n_layers=5, batch=2, n_cached=300, n_steps=1), {}, {"n_splits": 1, "wg_waves": 8}),
+    "c2-small-int8-1split": (C[2].scaled(n_layers=4, batch=3, n_cached=200, n_steps=1), {"latent_format": "int8"}, {"n_splits": 1}),
     "c3-small-mlp": (C[3].scaled(n_layers=2, batch=3, n_cached=90, n_steps=1), {}, {}),
     "c2-small-int8": (C[2].scaled(n_layers=4, batch=5, n_cached=300, n_steps=1), {"latent_format": "int8"}, {}),
     "bias-f16-generic": (C[3].scaled(n_layers=2, batch=2, n_cached=40, n_steps=1, dtype="f16", act="leaky_relu", hidden=160),
@@ -72,7 +76,7 @@ def test_exact_current_token(name, gain):
         check(w, got, want, f"{name} layer {layer}")
 
 
-@pytest.mark.parametrize("name", ["c0-f32", "c2-small-bf16", "c3-small-mlp", "c2-small-int8"])
+@pytest.mark.parametrize("name", ["c0-f32", "c2-small-bf16", "c2-small-bf16-1split", "c4-small-bf16-1split-w8", "c2-small-int8-1split", "c3-small-mlp", "c2-small-int8"])
 def test_exact_current_token_with_nothing_cached(name):
     """n_ctx = 0: the output is the current value row of each head's KV head (rounded to the dtype)."""
     w, orc, ses = setup(name)
@@ -102,7 +106,7 @@ def test_ragged_context_lengths(name):
         check(w, got, want, f"{name} layer {layer} lens {lens.tolist()}")
 
 
-@pytest.mark.parametrize("name", ["c2-small-bf16", "c2-small-bf16-1split", "c3-small-mlp", "c2-small-int8", "c0-f32"])
+@pytest.mark.parametrize("name", ["c2-small-bf16", "c2-small-bf16-1split", "c4-small-bf16-1split", "c2-small-int8-1split", "c3-small-mlp", "c2-small-int8", "c0-f32"])
 def test_ragged_lengths_with_exact_current_token_and_an_empty_sequence(name):
     w, orc, ses = setup(name)
     lens = np.array([(7 * b * b + 3) % (w.n_cached + 1) for b in range(w.batch)])
@@ -153,3 +157,9 @@ def test_ragged_append_positions(name):
                 assert np.isnan(zg[~written]).all()
                 tol = 1e-6 if w.dtype == "f32" else 2.0 ** -7 if w.dtype == "bf16" else 2.0 ** -10
                 np.testing.assert_allclose(zg[written], zo[written], rtol=tol, atol=2e-6 * np.abs(zo[written]).max())
+
+
+def test_single_split_exact_row_runs_in_the_fused_kernel():
+    w, _, skw = CASES["c4-small-bf16-1split"]
+    ses = Session(w, with_bias=True, **skw)
+    assert ses.ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached).fused == 1
