@@ -133,7 +133,9 @@ typedef struct {
     int no_fuse;        /* 1 = always run prologue / attention / epilogue as separate kernels     */
     int wg_waves;       /* fused attention kernel: 0 = automatic (eight waves per workgroup when the
                            launch has no more workgroups than compute units, else four), 4 or 8      */
-    int reserved[3];
+    int no_bulk_encode; /* 1 = prompt-sized encode calls take the general encoder kernel, not the
+                           streaming one (linear encoders, 8192 tokens or more)                      */
+    int reserved[2];
 } kvcar_tuning;
 
 /* Create / destroy a context.  ERR_ARG on null pointers, ERR_SHAPE on non-positive sizes or
@@ -273,6 +275,20 @@ typedef struct {
     size_t latent_bytes;    /* bytes of latent rows the attention kernel reads for this call    */
 } kvcar_plan_info;
 int kvcar_describe_plan(const kvcar_ctx *ctx, int layer, int batch, int n_ctx, kvcar_plan_info *out);
+
+/*
+ * Which encoder kernel kvcar_encode_append(layer, batch, .., t_new) would take with the current
+ * autoencoders and tuning (host-only, nothing is launched; caches need not be bound).  ERR_ARG / ERR_CAPACITY
+ * / ERR_STATE as for the call itself.
+ */
+enum {
+    KVCAR_ENC_NONE = 0,            /* the layer stores nothing: no launch                                   */
+    KVCAR_ENC_PLAIN = 1,           /* plain-ALU kernel (fp32 models, shapes without an MFMA kernel)          */
+    KVCAR_ENC_MFMA = 2,            /* general MFMA kernel (linear, or two layers of any covered shape)       */
+    KVCAR_ENC_MFMA_TWO_LAYER = 3,  /* two-layer encoder of one of the exact shapes with resident token rows  */
+    KVCAR_ENC_MFMA_STREAM = 4      /* streaming kernel for prompt-sized calls through a linear encoder       */
+};
+int kvcar_describe_encode(const kvcar_ctx *ctx, int layer, int batch, int t_new, int *kernel);
 
 /*
  * Optional timing of the attention kernel (the kernel that streams the latent cache; for

@@ -14,6 +14,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libkvcar.so")
 
 OK = 0
+ENC_NONE, ENC_PLAIN, ENC_MFMA, ENC_MFMA_TWO_LAYER, ENC_MFMA_STREAM = range(5)
 ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_REUSE, ERR_UNSUPPORTED, ERR_STATE, ERR_HIP, ERR_WORKSPACE = range(-1, -9, -1)
 F32, F16, BF16 = 0, 1, 2
 ACT_NONE, ACT_LEAKY_RELU, ACT_GELU = 0, 1, 2
@@ -38,7 +39,7 @@ class AEDesc(C.Structure):
 
 
 class Tuning(C.Structure):
-    _fields_ = [("n_splits", C.c_int), ("force_generic", C.c_int), ("tile_order", C.c_int), ("no_fuse", C.c_int), ("wg_waves", C.c_int), ("reserved", C.c_int * 3)]
+    _fields_ = [("n_splits", C.c_int), ("force_generic", C.c_int), ("tile_order", C.c_int), ("no_fuse", C.c_int), ("wg_waves", C.c_int), ("no_bulk_encode", C.c_int), ("reserved", C.c_int * 2)]
 
 
 class StepExt(C.Structure):
@@ -67,6 +68,7 @@ SYMBOLS = {
     "kvcar_decode_attention_ex": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(StepExt), C.c_void_p,
                                             C.c_size_t, C.c_void_p]),
     "kvcar_encode_append_at": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]),
+    "kvcar_describe_encode": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int)]),
     "kvcar_prefill_workspace_bytes": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]),
     "kvcar_prefill_attention": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t,
                                           C.c_void_p]),
@@ -209,9 +211,15 @@ class Context:
         self._check(lib().kvcar_bind_cache(self._h, layer, which, _ptr(tensor), nbytes))
 
     def set_tuning(self, n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, no_fuse: bool = False,
-                   wg_waves: int = 0):
-        t = Tuning(n_splits, 1 if force_generic else 0, tile_order, 1 if no_fuse else 0, wg_waves)
+                   wg_waves: int = 0, no_bulk_encode: bool = False):
+        t = Tuning(n_splits, 1 if force_generic else 0, tile_order, 1 if no_fuse else 0, wg_waves, 1 if no_bulk_encode else 0)
         self._check(lib().kvcar_set_tuning(self._h, C.byref(t)))
+
+    def describe_encode(self, layer: int, batch: int, t_new: int) -> int:
+        """The encoder kernel an encode_append call of this size takes (one of the ENC_* values)."""
+        k = C.c_int(0)
+        self._check(lib().kvcar_describe_encode(self._h, layer, batch, t_new, C.byref(k)))
+        return k.value
 
     def workspace_bytes(self, batch: int, n_ctx: int) -> int:
         n = C.c_size_t(0)

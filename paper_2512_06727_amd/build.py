@@ -14,7 +14,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libkvcar.so")
 
-SOURCES = ["kvcar_host.hip", "kvcar_generic.hip", "kvcar_attend_mfma.hip", "kvcar_attend_i8_mfma.hip", "kvcar_encode_mfma.hip", "kvcar_proj_mfma.hip", "kvcar_attend_mlp_mfma.hip", "kvcar_encode_mlp_mfma.hip", "kvcar_select.hip", "kvcar_prefill_generic.hip", "kvcar_prefill_mfma.hip"]
+SOURCES = ["kvcar_host.hip", "kvcar_generic.hip", "kvcar_attend_mfma.hip", "kvcar_attend_i8_mfma.hip", "kvcar_encode_mfma.hip", "kvcar_proj_mfma.hip", "kvcar_attend_mlp_mfma.hip", "kvcar_encode_mlp_mfma.hip", "kvcar_encode_bulk_mfma.hip", "kvcar_select.hip", "kvcar_prefill_generic.hip", "kvcar_prefill_mfma.hip"]
 
 # packed-fp32 instructions are disabled for device code on purpose (see the HIP flags below)
 HIP_FLAGS = [

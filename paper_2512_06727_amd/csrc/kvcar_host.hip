@@ -438,6 +438,45 @@ int kvcar_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_ctx, size_t* by
 
 namespace {
 
+// The encoder side of a call: shapes, weights and (when `bound`) the input and cache pointers.  `any` tells
+// whether the layer stores anything.
+int fill_encode_params(const kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, int pos0, const int32_t* positions,
+                       int t_new, bool bound, EncodeParams& p, bool& any) {
+    const kvcar_config& c = ctx->cfg;
+    p = EncodeParams{};
+    p.batch = batch; p.t_new = t_new; p.pos0 = pos0; p.max_seq = c.max_seq; p.d_kv = c.n_kv_heads * c.d_head; p.d_head = c.d_head;
+    p.positions = positions;
+    const void* xs[2] = {k_new, v_new};
+    any = false;
+    for (int which = 0; which < 2; ++which) {
+        const AEState& a = ctx->ae_at(layer, which);
+        if (!a.set) return fail(ctx, KVCAR_ERR_STATE, "autoencoder of layer %d (%s) not set", layer, which ? "V" : "K");
+        EncodeSide& s = p.s[which];
+        s.x = xs[which];
+        s.r = a.d.latent_width;
+        if (s.r == 0) continue;
+        s.z = ctx->cache[(size_t)layer * 2 + which];
+        if (bound && !s.z) return fail(ctx, KVCAR_ERR_STATE, "cache of layer %d (%s) not bound", layer, which ? "V" : "K");
+        s.meta = ctx->int8() && s.z ? static_cast<char*>(s.z) + ctx->meta_offset(s.r) : nullptr;
+        s.w1 = a.d.enc_w1; s.b1 = a.d.enc_b1; s.w2 = a.d.enc_w2; s.b2 = a.d.enc_b2;
+        s.in_width = a.d.in_width; s.hidden = a.d.hidden_width; s.act = a.d.act; s.slope = a.d.leaky_slope;
+        s.n_heads = (int)a.heads.size();
+        for (size_t i = 0; i < a.heads.size(); ++i) s.heads[i] = (unsigned char)a.heads[i];
+        any = true;
+    }
+    return KVCAR_OK;
+}
+
+// Which encoder kernel a call takes (the KVCAR_ENC_* values).
+int encode_kernel_kind(const kvcar_ctx* ctx, const EncodeParams& p) {
+    const int dtype = ctx->cfg.dtype;
+    if (ctx->tun.force_generic) return KVCAR_ENC_PLAIN;
+    if (encode_mlp_mfma_supported(p, dtype)) return KVCAR_ENC_MFMA_TWO_LAYER;
+    if (!ctx->tun.no_bulk_encode && encode_bulk_supported(p, dtype)) return KVCAR_ENC_MFMA_STREAM;
+    if (encode_mfma_supported(p, dtype)) return KVCAR_ENC_MFMA;
+    return KVCAR_ENC_PLAIN;
+}
+
 int encode_impl(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, int pos0, const int32_t* positions, int t_new,
                 void* stream) {
     int rc = check_layer(ctx, layer);
@@ -447,34 +486,19 @@ int encode_impl(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new,
     if (batch < 1 || t_new < 1 || pos0 < 0) return fail(ctx, KVCAR_ERR_ARG, "batch, t_new must be >= 1 and pos0 >= 0");
     if (batch > c.max_batch || (long long)pos0 + t_new > c.max_seq)
         return fail(ctx, KVCAR_ERR_CAPACITY, "append of %d tokens at %d for batch %d exceeds max_seq %d / max_batch %d", t_new, pos0, batch, c.max_seq, c.max_batch);
-    EncodeParams p{};
-    p.batch = batch; p.t_new = t_new; p.pos0 = pos0; p.max_seq = c.max_seq; p.d_kv = c.n_kv_heads * c.d_head; p.d_head = c.d_head;
-    p.positions = positions;
-    const void* xs[2] = {k_new, v_new};
+    EncodeParams p;
     bool any = false;
-    for (int which = 0; which < 2; ++which) {
-        const AEState& a = ctx->ae_at(layer, which);
-        if (!a.set) return fail(ctx, KVCAR_ERR_STATE, "autoencoder of layer %d (%s) not set", layer, which ? "V" : "K");
-        EncodeSide& s = p.s[which];
-        s.x = xs[which];
-        s.r = a.d.latent_width;
-        if (s.r == 0) continue;
-        s.z = ctx->cache[(size_t)layer * 2 + which];
-        if (!s.z) return fail(ctx, KVCAR_ERR_STATE, "cache of layer %d (%s) not bound", layer, which ? "V" : "K");
-        s.meta = ctx->int8() ? static_cast<char*>(s.z) + ctx->meta_offset(s.r) : nullptr;
-        s.w1 = a.d.enc_w1; s.b1 = a.d.enc_b1; s.w2 = a.d.enc_w2; s.b2 = a.d.enc_b2;
-        s.in_width = a.d.in_width; s.hidden = a.d.hidden_width; s.act = a.d.act; s.slope = a.d.leaky_slope;
-        s.n_heads = (int)a.heads.size();
-        for (size_t i = 0; i < a.heads.size(); ++i) s.heads[i] = (unsigned char)a.heads[i];
-        any = true;
-    }
+    rc = fill_encode_params(ctx, layer, k_new, v_new, batch, pos0, positions, t_new, true, p, any);
+    if (rc) return rc;
     if (!any) return KVCAR_OK;   // the layer stores nothing
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
-    const bool mfma_enc = !ctx->tun.force_generic;
-    if (mfma_enc && encode_mlp_mfma_supported(p, c.dtype)) e = launch_encode_mlp_mfma(p, c.dtype, st);
-    else if (mfma_enc && encode_mfma_supported(p, c.dtype)) e = launch_encode_mfma(p, c.dtype, st);
-    else e = launch_encode_generic(p, c.dtype, st);
+    switch (encode_kernel_kind(ctx, p)) {
+        case KVCAR_ENC_MFMA_TWO_LAYER: e = launch_encode_mlp_mfma(p, c.dtype, st); break;
+        case KVCAR_ENC_MFMA_STREAM: e = launch_encode_bulk(p, c.dtype, ctx->n_cu, st); break;
+        case KVCAR_ENC_MFMA: e = launch_encode_mfma(p, c.dtype, st); break;
+        default: e = launch_encode_generic(p, c.dtype, st); break;
+    }
     if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "encode launch failed: %s", hipGetErrorString(e));
     return KVCAR_OK;
 }
@@ -689,6 +713,21 @@ int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, k
     for (auto& g : plan.groups) lat += (size_t)(g.k.r + g.v.r);
     out->latent_bytes = lat * ctx->row_elem_bytes() * batch * n_ctx;
     if (ctx->int8()) out->latent_bytes += plan.groups.size() * 2 * sizeof(RowMeta) * (size_t)batch * n_ctx;
+    return KVCAR_OK;
+}
+
+int kvcar_describe_encode(const kvcar_ctx* ctx, int layer, int batch, int t_new, int* kernel) {
+    int rc = check_layer(ctx, layer);
+    if (rc) return rc;
+    if (!kernel) return fail(ctx, KVCAR_ERR_ARG, "null output");
+    if (batch < 1 || t_new < 1) return fail(ctx, KVCAR_ERR_ARG, "batch, t_new must be >= 1");
+    if (batch > ctx->cfg.max_batch || t_new > ctx->cfg.max_seq)
+        return fail(ctx, KVCAR_ERR_CAPACITY, "batch %d / t_new %d exceed max_batch %d / max_seq %d", batch, t_new, ctx->cfg.max_batch, ctx->cfg.max_seq);
+    EncodeParams p;
+    bool any = false;
+    rc = fill_encode_params(ctx, layer, nullptr, nullptr, batch, 0, nullptr, t_new, false, p, any);
+    if (rc) return rc;
+    *kernel = any ? encode_kernel_kind(ctx, p) : KVCAR_ENC_NONE;
     return KVCAR_OK;
 }
 

@@ -105,6 +105,8 @@ size_t attend_generic_lds_bytes(const GroupDesc& g);
 // MFMA encoder (16-bit dtypes, widths that are multiples of 32).
 bool encode_mfma_supported(const EncodeParams& p, int dtype);
 hipError_t launch_encode_mfma(const EncodeParams& p, int dtype, hipStream_t stream);
+bool encode_bulk_supported(const EncodeParams& p, int dtype);
+hipError_t launch_encode_bulk(const EncodeParams& p, int dtype, int n_cu, hipStream_t stream);
 
 // MFMA encoder for two-layer encoders (32-token waves, hidden activations kept in registers).
 bool encode_mlp_mfma_supported(const EncodeParams& p, int dtype);

@@ -14,7 +14,7 @@ from . import binding, synth
 class Session:
     def __init__(self, w: synth.Workload, reuse: Optional[np.ndarray] = None, with_bias: bool = False,
                  device: str = "cuda:0", n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, no_fuse: bool = False, poison: bool = False,
-                 max_batch: Optional[int] = None, latent_format: str = "dtype", wg_waves: int = 0):
+                 max_batch: Optional[int] = None, latent_format: str = "dtype", wg_waves: int = 0, no_bulk_encode: bool = False):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: libkvcar has no CPU path")
         self.w = w
@@ -24,7 +24,7 @@ class Session:
         self.latent_format = latent_format
         self.ctx = binding.Context(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, max_batch or w.batch, w.max_seq, w.dtype,
                                    latent_format=latent_format)
-        self.ctx.set_tuning(n_splits=n_splits, force_generic=force_generic, tile_order=tile_order, no_fuse=no_fuse, wg_waves=wg_waves)
+        self.ctx.set_tuning(n_splits=n_splits, force_generic=force_generic, tile_order=tile_order, no_fuse=no_fuse, wg_waves=wg_waves, no_bulk_encode=no_bulk_encode)
         self.ae: List[List[synth.AEWeights]] = []
         self.caches: List[List[Optional[torch.Tensor]]] = []
         for layer in range(w.n_layers):

@@ -253,3 +253,38 @@ def test_prefill_workspace_size_and_argument_errors_before_any_launch():
         assert lib.kvcar_set_autoencoder(big_dh._h, 0, which, C.byref(desc(640, 0, 64))) == B.OK
         assert lib.kvcar_bind_cache(big_dh._h, 0, which, FAKE, big_dh.cache_bytes(0, which)) == B.OK
     assert lib.kvcar_prefill_attention(big_dh._h, 0, FAKE, FAKE, 1, 0, 8, FAKE, big, None) == B.ERR_UNSUPPORTED   # d_head > 256
+
+
+def test_encoder_kernel_choice():
+    """kvcar_describe_encode: prompt-sized calls through a linear 16-bit encoder take the streaming kernel."""
+    lib = B.lib()
+    ctx = make(n_layers=4, mb=16, ms=4096)
+    for which in (B.K, B.V):
+        assert lib.kvcar_set_autoencoder(ctx._h, 0, which, C.byref(desc(256, 0, 128))) == B.OK
+        assert lib.kvcar_set_autoencoder(ctx._h, 1, which, C.byref(desc(256, 256, 128, B.ACT_GELU))) == B.OK
+        assert lib.kvcar_set_autoencoder(ctx._h, 2, which, C.byref(desc(256, 0, 256))) == B.OK     # latent too wide to stream
+    assert ctx.describe_encode(0, 16, 1) == B.ENC_MFMA
+    assert ctx.describe_encode(0, 16, 511) == B.ENC_MFMA                 # 8176 tokens
+    assert ctx.describe_encode(0, 16, 512) == B.ENC_MFMA_STREAM          # 8192 tokens
+    assert ctx.describe_encode(0, 16, 4096) == B.ENC_MFMA_STREAM
+    assert ctx.describe_encode(1, 16, 4096) == B.ENC_MFMA_TWO_LAYER
+    assert ctx.describe_encode(2, 16, 4096) == B.ENC_MFMA
+    ctx.set_tuning(no_bulk_encode=True)
+    assert ctx.describe_encode(0, 16, 4096) == B.ENC_MFMA
+    ctx.set_tuning(force_generic=True)
+    assert ctx.describe_encode(0, 16, 4096) == B.ENC_PLAIN
+    ctx.set_tuning()
+    k = C.c_int(-1)
+    assert lib.kvcar_describe_encode(ctx._h, 3, 16, 4096, C.byref(k)) == B.ERR_STATE          # autoencoder not set
+    assert lib.kvcar_describe_encode(ctx._h, 0, 17, 1, C.byref(k)) == B.ERR_CAPACITY
+    assert lib.kvcar_describe_encode(ctx._h, 0, 0, 1, C.byref(k)) == B.ERR_ARG
+    assert lib.kvcar_describe_encode(ctx._h, 0, 1, 1, None) == B.ERR_ARG
+    # a layer that stores nothing (every head reused: its autoencoders have width zero)
+    ctx.set_reuse_map(3, [1, 1, 1, 1], [1, 1, 1, 1])
+    for which in (B.K, B.V):
+        assert lib.kvcar_set_autoencoder(ctx._h, 3, which, C.byref(desc(0, 0, 0, ptrs=False))) == B.OK
+    assert ctx.describe_encode(3, 16, 4096) == B.ENC_NONE
+    f32 = make(dtype="f32", mb=16, ms=4096)
+    for which in (B.K, B.V):
+        assert lib.kvcar_set_autoencoder(f32._h, 0, which, C.byref(desc(256, 0, 128))) == B.OK
+    assert f32.describe_encode(0, 16, 4096) == B.ENC_PLAIN
