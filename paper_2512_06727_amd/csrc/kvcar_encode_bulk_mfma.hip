@@ -43,7 +43,10 @@ constexpr int kBulkWaves = 8;
 constexpr int kBulkRows = 16;                          // tokens per wave tile
 constexpr int kBulkTile = kBulkWaves * kBulkRows;      // tokens per workgroup iteration
 constexpr int kBulkMaxKs = 8;                          // input width up to 256: 16-byte chunks per lane and tile
-constexpr int kBulkAhead = 2;                          // tiles in flight per wave
+#ifndef KVCAR_BULK_AHEAD
+#define KVCAR_BULK_AHEAD 2
+#endif
+constexpr int kBulkAhead = KVCAR_BULK_AHEAD;             // tiles in flight per wave
 constexpr int kBulkMinTokens = 8192;                   // below this the launch cannot fill the chip with whole workgroups
 constexpr size_t kBulkLdsMax = 160 * 1024;
 

@@ -154,6 +154,7 @@ struct ReconParams {
     void* vhat;                   // decoded values [batch, H_kv, n_rows, d_head]
     int batch, n_rows, max_seq, n_kv_heads, d_head;
     float k_scale;                // softmax scale * log2(e), multiplied into the decoded keys before their one rounding
+    int staged;                   // set by the MFMA launcher: rows leave through an LDS staging area as 16-byte chunks
 };
 
 struct PrefillParams {

@@ -68,22 +68,77 @@ __device__ __forceinline__ u32x4_t tr_pair32(const char* p, int second_offset) {
     return u32x4_t{a0[0], a0[1], a1[0], a1[1]};
 }
 
+// [n_rows, cpr 16-byte chunks] of a row-major matrix (row pitch src_pitch bytes) -> padded LDS rows, by the
+// threads of the workgroup with eight chunks per thread in flight: a loop that stores each chunk before it loads
+// the next pays one memory round trip per chunk.
+__device__ __forceinline__ void recon_stage_matrix(char* dst, int dst_stride, const char* src, size_t src_pitch, int n_rows, int cpr, int tid, int n_threads) {
+    const int total = n_rows * cpr;
+    for (int f0 = tid; f0 < total; f0 += 8 * n_threads) {
+        u32x4_t t[8];
+        int off[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int f = f0 + u * n_threads;
+            const int row = f / cpr, ch = f - row * cpr;
+            off[u] = row * dst_stride + ch * 16;
+            if (f < total) t[u] = *reinterpret_cast<const u32x4_t*>(src + (size_t)row * src_pitch + ch * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (f0 + u * n_threads < total) *reinterpret_cast<u32x4_t*>(dst + off[u]) = t[u];
+    }
+}
+
+// The decoded rows of one head leave a wave through LDS.  The result layout gives a lane four 8-byte pieces of one
+// token's row; parked as rows of d_head elements (the wave's 32-token tiles) they go out as whole
+// 16-byte chunks of contiguous memory: a tile's rows of one head are contiguous in K^ / V^.
+constexpr size_t kReconLdsMax = 160 * 1024;
+constexpr int kReconChunk = 256;      // tokens per workgroup: TL 32-token tiles per wave, 8 / TL waves
+__host__ __device__ constexpr int recon_stage_stride(int d_head) { return 2 * d_head + 16; }
+__host__ __device__ constexpr size_t recon_stage_bytes(int d_head) { return (size_t)kReconChunk * recon_stage_stride(d_head); }
+
+template <typename E>
+__device__ __forceinline__ void recon_emit_block(const f32x16_t& acc, const void* bl, int col0, float out_scale, char* stage_row, char* orow) {
+    // this lane: one token, decoder columns col0 + 8a + j (register 4a + j), col0 already holding the lane half's 4h
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        float bias[4] = {0.f, 0.f, 0.f, 0.f};
+        if (bl) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bias[j] = Elem<E>::load(bl, col0 + 8 * a + j);
+        }
+        const u32x2_t w = {Mma<E>::pack2((acc[4 * a] + bias[0]) * out_scale, (acc[4 * a + 1] + bias[1]) * out_scale),
+                           Mma<E>::pack2((acc[4 * a + 2] + bias[2]) * out_scale, (acc[4 * a + 3] + bias[3]) * out_scale)};
+        if (stage_row) *reinterpret_cast<u32x2_t*>(stage_row + 16 * a) = w;
+        else if (orow) *reinterpret_cast<u32x2_t*>(orow + 16 * a) = w;
+    }
+}
+
+// The wave's parked rows of one head -> memory: tile `tile` starts at token t0; chunk f of the tile is 16 bytes at
+// offset 16 f of its (contiguous) rows.
+__device__ __forceinline__ void recon_flush_tile(const char* stage, int stride_o, char* tile_dst, int rows_valid, int cpr, int lane) {
+    const int total = min(rows_valid, 32) * cpr;
+    for (int f = lane; f < total; f += 64) {
+        const int row = f / cpr, ch = f - row * cpr;
+        *reinterpret_cast<u32x4_t*>(tile_dst + (size_t)f * 16) = *reinterpret_cast<const u32x4_t*>(stage + row * stride_o + ch * 16);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // decoded rows (linear decoder)
 // ---------------------------------------------------------------------------------------------------------
 typedef const __attribute__((address_space(4))) ReconParams* RArgs;
 typedef const __attribute__((address_space(4))) ReconEntry* REntry;
 
-constexpr int kReconChunk = 256;      // tokens per workgroup: two 32-token tiles per wave
 
-// The wave's latent rows as B operands: tile `tile` (0, 1) of its 64 tokens; lane (token l32, half h) holds latent
+// The wave's latent rows as B operands: tile `tile` of its 32 TL tokens; lane (token l32, half h) holds latent
 // columns 16s + 8h .. +7 of k-step s, dequantised in registers when the rows are int8 codes; rows past n_rows are zero.
-template <typename E, int R, bool kI8>
-__device__ __forceinline__ void recon_load_rows(u32x4_t (&zb)[2][R / 16], REntry e, RArgs p, int b, int tok0, int l32, int h) {
+template <typename E, int R, bool kI8, int TL>
+__device__ __forceinline__ void recon_load_rows(u32x4_t (&zb)[TL][R / 16], REntry e, RArgs p, int b, int tok0, int l32, int h) {
     constexpr int KS = R / 16;
     const int n_rows = p->n_rows;
 #pragma unroll
-    for (int tile = 0; tile < 2; ++tile) {
+    for (int tile = 0; tile < TL; ++tile) {
         const int t = tok0 + tile * 32 + l32;
         const bool valid = t < n_rows;
         const size_t row = (size_t)b * p->max_seq + (valid ? t : 0);
@@ -121,8 +176,9 @@ __device__ __forceinline__ void recon_load_rows(u32x4_t (&zb)[2][R / 16], REntry
 // Workgroup = (256-token chunk, sequence, entry).  The wave keeps its latent rows as B operands (lane: token
 // l32, latent columns 16s + 8h .. +7 of k-step s) and walks over the KV heads of the entry; per head the
 // decoder slice [R, d_head] passes through LDS once for the four waves.
-template <typename E, int R, bool kI8>
-__global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
+template <typename E, int R, bool kI8, int TL>
+__global__ __launch_bounds__(64 * kReconChunk / (32 * TL)) void recon_mfma_kernel(ReconParams) {
+    constexpr int NT = 64 * kReconChunk / (32 * TL);      // threads
     constexpr int KS = R / 16;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     RArgs p = (RArgs)__builtin_amdgcn_kernarg_segment_ptr();
@@ -132,9 +188,11 @@ __global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
     const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
     const int dh = p->d_head, n_rows = p->n_rows;
     const int stride_w = 2 * dh + 32, cpr = dh >> 3;
+    const int stride_o = recon_stage_stride(dh);
+    char* stage = p->staged ? lds + R * stride_w + wave * 32 * TL * stride_o : nullptr;
 
-    u32x4_t zb[2][KS];
-    recon_load_rows<E, R, kI8>(zb, e, p, b, chunk0 + wave * 64, l32, h);
+    u32x4_t zb[TL][KS];
+    recon_load_rows<E, R, kI8, TL>(zb, e, p, b, chunk0 + wave * 32 * TL, l32, h);
 
     const char* wl = static_cast<const char*>(e->d.wl);
     const int in_width = e->d.in_width;
@@ -143,41 +201,37 @@ __global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
     for (int hi = 0; hi < e->n_heads; ++hi) {
         const int g = e->head[hi], col = e->col[hi];
         __syncthreads();                           // the previous slice is no longer read
-        for (int f = tid; f < R * cpr; f += 256) {
-            const int row = f / cpr, ch = f - row * cpr;
-            *reinterpret_cast<u32x4_t*>(lds + row * stride_w + ch * 16) =
-                *reinterpret_cast<const u32x4_t*>(wl + ((size_t)row * in_width + col) * 2 + ch * 16);
-        }
+        recon_stage_matrix(lds, stride_w, wl + (size_t)col * 2, (size_t)in_width * 2, R, cpr, tid, NT);
         __syncthreads();
         for (int mb = 0; mb < (dh >> 5); ++mb) {
             // A operand: row = decoder column 32 mb + l32, k-slots = latent indices 16s + 8h .. +7
             const char* wsrc = lds + (8 * h + (l16 >> 2)) * stride_w + (32 * mb + 16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
-            f32x16_t acc[2];
+            f32x16_t acc[TL];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.f;
+            for (int tile = 0; tile < TL; ++tile)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[tile][v] = 0.f;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const u32x4_t wa = tr_pair32(wsrc + 16 * s * stride_w, 4 * stride_w);
-                acc[0] = Mma32<E>::mfma(wa, zb[0][s], acc[0]);
-                acc[1] = Mma32<E>::mfma(wa, zb[1][s], acc[1]);
+#pragma unroll
+                for (int tile = 0; tile < TL; ++tile) acc[tile] = Mma32<E>::mfma(wa, zb[tile][s], acc[tile]);
             }
             // this lane: token l32, decoder columns 32 mb + 8a + 4h + j (register 4a + j)
 #pragma unroll
-            for (int tile = 0; tile < 2; ++tile) {
-                const int t = chunk0 + wave * 64 + tile * 32 + l32;
-                if (t >= n_rows) continue;
-                char* orow = dst + ((((size_t)b * p->n_kv_heads + g) * n_rows + t) * dh + 32 * mb + 4 * h) * 2;
+            for (int tile = 0; tile < TL; ++tile) {
+                const int t = chunk0 + wave * 32 * TL + tile * 32 + l32;
+                char* srow = stage ? stage + (tile * 32 + l32) * stride_o + (32 * mb + 4 * h) * 2 : nullptr;
+                char* orow = t < n_rows ? dst + ((((size_t)b * p->n_kv_heads + g) * n_rows + t) * dh + 32 * mb + 4 * h) * 2 : nullptr;
+                recon_emit_block<E>(acc[tile], e->d.bl, col + 32 * mb + 4 * h, out_scale, srow, orow);
+            }
+        }
+        if (stage) {
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    float bias[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (e->d.bl) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) bias[j] = Elem<E>::load(e->d.bl, col + 32 * mb + 8 * a + 4 * h + j);
-                    }
-                    *reinterpret_cast<u32x2_t*>(orow + 16 * a) =
-                        u32x2_t{Mma<E>::pack2((acc[tile][4 * a] + bias[0]) * out_scale, (acc[tile][4 * a + 1] + bias[1]) * out_scale),
-                                Mma<E>::pack2((acc[tile][4 * a + 2] + bias[2]) * out_scale, (acc[tile][4 * a + 3] + bias[3]) * out_scale)};
-                }
+            for (int tile = 0; tile < TL; ++tile) {
+                const int t0 = chunk0 + wave * 32 * TL + tile * 32;
+                if (t0 < n_rows)
+                    recon_flush_tile(stage + tile * 32 * stride_o, stride_o, dst + (((size_t)b * p->n_kv_heads + g) * n_rows + t0) * dh * 2, n_rows - t0, cpr, lane);
             }
         }
     }
@@ -189,8 +243,9 @@ __global__ __launch_bounds__(256) void recon_mfma_kernel(ReconParams) {
 //               of the second product with the rows of a k-step taken in register order
 //   X^^T[n, t] = Wl^T[n, c] . H^T[c, t]   per KV head and 32-column block of the head
 // W1 [R, C] stays in LDS for the whole workgroup; the slice [C, d_head] of the last layer passes through LDS per head.
-template <typename E, int R, int C, int ACT, bool kI8>
-__global__ __launch_bounds__(256) void recon_mlp_mfma_kernel(ReconParams) {
+template <typename E, int R, int C, int ACT, bool kI8, int TL>
+__global__ __launch_bounds__(64 * kReconChunk / (32 * TL)) void recon_mlp_mfma_kernel(ReconParams) {
+    constexpr int NT = 64 * kReconChunk / (32 * TL);      // threads
     constexpr int KS = R / 16;          // k-steps of the first product
     constexpr int CB = C / 32;          // 32-column blocks of the hidden width
     constexpr int STRIDE1 = 2 * C + 32; // LDS row stride of W1
@@ -204,38 +259,44 @@ __global__ __launch_bounds__(256) void recon_mlp_mfma_kernel(ReconParams) {
     const int stride_w = 2 * dh + 32, cpr = dh >> 3;
     char* w1_lds = lds;
     char* wl_lds = lds + R * STRIDE1;
+    const int stride_o = recon_stage_stride(dh);
+    char* stage = p->staged ? wl_lds + C * stride_w + wave * 32 * TL * stride_o : nullptr;
     const float slope = e->d.slope;
 
-    {
-        const char* w1 = static_cast<const char*>(e->d.w1);
-        for (int f = tid; f < R * (C / 8); f += 256) {
-            const int row = f / (C / 8), ch = f % (C / 8);
-            *reinterpret_cast<u32x4_t*>(w1_lds + row * STRIDE1 + ch * 16) = *reinterpret_cast<const u32x4_t*>(w1 + (size_t)f * 16);
-        }
-    }
-    u32x4_t zb[2][KS];
-    recon_load_rows<E, R, kI8>(zb, e, p, b, chunk0 + wave * 64, l32, h);
+    u32x4_t zb[TL][KS];
+    recon_load_rows<E, R, kI8, TL>(zb, e, p, b, chunk0 + wave * 32 * TL, l32, h);         // in flight while W1 is staged
+    recon_stage_matrix(w1_lds, STRIDE1, static_cast<const char*>(e->d.w1), (size_t)C * 2, R, C / 8, tid, NT);
+    float* b1s = reinterpret_cast<float*>(wl_lds + C * stride_w + (p->staged ? kReconChunk * stride_o : 0));      // [C] first-layer bias
+    for (int i = tid; i < C; i += NT) b1s[i] = e->d.b1 ? Elem<E>::load(e->d.b1, i) : 0.f;
     __syncthreads();
 
     // hidden rows of the wave's two tiles as B operands of the second product: [tile][block][k-step]
-    u32x4_t hb[2][CB][2];
+    u32x4_t hb[TL][CB][2];
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
         const char* wsrc = w1_lds + (8 * h + (l16 >> 2)) * STRIDE1 + (32 * cb + 16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
-        f32x16_t acc[2];
+        f32x16_t acc[TL];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.f;
+        for (int tile = 0; tile < TL; ++tile)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[tile][v] = 0.f;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const u32x4_t wa = tr_pair32(wsrc + 16 * s * STRIDE1, 4 * STRIDE1);
-            acc[0] = Mma32<E>::mfma(wa, zb[0][s], acc[0]);
-            acc[1] = Mma32<E>::mfma(wa, zb[1][s], acc[1]);
+#pragma unroll
+            for (int tile = 0; tile < TL; ++tile) acc[tile] = Mma32<E>::mfma(wa, zb[tile][s], acc[tile]);
         }
+        // bias of this lane's hidden rows 32 cb + 8a + 4h + j, from the fp32 copy in LDS (global loads here would all be
+        // hoisted to the top of the unrolled loop and hold 16 registers per block)
         float bias[16];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) bias[v] = e->d.b1 ? Elem<E>::load(e->d.b1, 32 * cb + 8 * (v >> 2) + 4 * h + (v & 3)) : 0.f;
+        for (int a = 0; a < 4; ++a) {
+            const f32x4_t b4 = *reinterpret_cast<const f32x4_t*>(b1s + 32 * cb + 8 * a + 4 * h);
 #pragma unroll
-        for (int tile = 0; tile < 2; ++tile)
+            for (int j = 0; j < 4; ++j) bias[4 * a + j] = b4[j];
+        }
+#pragma unroll
+        for (int tile = 0; tile < TL; ++tile)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 unsigned w[4];
@@ -254,43 +315,39 @@ __global__ __launch_bounds__(256) void recon_mlp_mfma_kernel(ReconParams) {
     for (int hi = 0; hi < e->n_heads; ++hi) {
         const int g = e->head[hi], col = e->col[hi];
         __syncthreads();                           // the previous slice is no longer read
-        for (int f = tid; f < C * cpr; f += 256) {
-            const int row = f / cpr, ch = f - row * cpr;
-            *reinterpret_cast<u32x4_t*>(wl_lds + row * stride_w + ch * 16) =
-                *reinterpret_cast<const u32x4_t*>(wl + ((size_t)row * in_width + col) * 2 + ch * 16);
-        }
+        recon_stage_matrix(wl_lds, stride_w, wl + (size_t)col * 2, (size_t)in_width * 2, C, cpr, tid, NT);
         __syncthreads();
         for (int mb = 0; mb < (dh >> 5); ++mb) {
             // A operand: row = decoder column 32 mb + l32; k-slots of k-step s of block cb = hidden rows
             // 32 cb + 16 s + 8(e/4) + 4h + e%4
             const char* wsrc = wl_lds + (4 * h + (l16 >> 2)) * stride_w + (32 * mb + 16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
-            f32x16_t acc[2];
+            f32x16_t acc[TL];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.f;
+            for (int tile = 0; tile < TL; ++tile)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[tile][v] = 0.f;
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
                     const u32x4_t wa = tr_pair32(wsrc + (32 * cb + 16 * s) * stride_w, 8 * stride_w);
-                    acc[0] = Mma32<E>::mfma(wa, hb[0][cb][s], acc[0]);
-                    acc[1] = Mma32<E>::mfma(wa, hb[1][cb][s], acc[1]);
+#pragma unroll
+                    for (int tile = 0; tile < TL; ++tile) acc[tile] = Mma32<E>::mfma(wa, hb[tile][cb][s], acc[tile]);
                 }
 #pragma unroll
-            for (int tile = 0; tile < 2; ++tile) {
-                const int t = chunk0 + wave * 64 + tile * 32 + l32;
-                if (t >= n_rows) continue;
-                char* orow = dst + ((((size_t)b * p->n_kv_heads + g) * n_rows + t) * dh + 32 * mb + 4 * h) * 2;
+            for (int tile = 0; tile < TL; ++tile) {
+                const int t = chunk0 + wave * 32 * TL + tile * 32 + l32;
+                char* srow = stage ? stage + (tile * 32 + l32) * stride_o + (32 * mb + 4 * h) * 2 : nullptr;
+                char* orow = t < n_rows ? dst + ((((size_t)b * p->n_kv_heads + g) * n_rows + t) * dh + 32 * mb + 4 * h) * 2 : nullptr;
+                recon_emit_block<E>(acc[tile], e->d.bl, col + 32 * mb + 4 * h, out_scale, srow, orow);
+            }
+        }
+        if (stage) {
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    float bias[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (e->d.bl) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) bias[j] = Elem<E>::load(e->d.bl, col + 32 * mb + 8 * a + 4 * h + j);
-                    }
-                    *reinterpret_cast<u32x2_t*>(orow + 16 * a) =
-                        u32x2_t{Mma<E>::pack2((acc[tile][4 * a] + bias[0]) * out_scale, (acc[tile][4 * a + 1] + bias[1]) * out_scale),
-                                Mma<E>::pack2((acc[tile][4 * a + 2] + bias[2]) * out_scale, (acc[tile][4 * a + 3] + bias[3]) * out_scale)};
-                }
+            for (int tile = 0; tile < TL; ++tile) {
+                const int t0 = chunk0 + wave * 32 * TL + tile * 32;
+                if (t0 < n_rows)
+                    recon_flush_tile(stage + tile * 32 * stride_o, stride_o, dst + (((size_t)b * p->n_kv_heads + g) * n_rows + t0) * dh * 2, n_rows - t0, cpr, lane);
             }
         }
     }
@@ -323,14 +380,18 @@ bool recon_mfma_supported(const ReconParams& p, int dtype) {
 
 template <typename E, int R, bool kI8>
 static hipError_t launch_recon_one(const ReconParams& p, hipStream_t stream) {
-    const size_t lds = (size_t)R * (2 * p.d_head + 32);
-    auto k = recon_mfma_kernel<E, R, kI8>;
+    size_t lds = (size_t)R * (2 * p.d_head + 32);
+    ReconParams q = p;
+    q.staged = lds + recon_stage_bytes(p.d_head) <= kReconLdsMax ? 1 : 0;      // else the lanes store their 8-byte pieces themselves
+    if (q.staged) lds += recon_stage_bytes(p.d_head);
+    constexpr int TL = 2;               // four waves of 64 tokens (eight of 32 measured the same)
+    auto k = recon_mfma_kernel<E, R, kI8, TL>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
     }
     dim3 grid((p.n_rows + kReconChunk - 1) / kReconChunk, p.batch, p.n_entries);
-    hipLaunchKernelGGL(k, grid, dim3(256), lds, stream, p);
+    hipLaunchKernelGGL(k, grid, dim3(64 * kReconChunk / (32 * TL)), lds, stream, q);
     return hipGetLastError();
 }
 
@@ -350,12 +411,17 @@ static hipError_t launch_recon_width(const ReconParams& p, int r, hipStream_t st
 
 template <typename E, int R, int C, int ACT, bool kI8>
 static hipError_t launch_recon_mlp_one(const ReconParams& p, hipStream_t stream) {
-    const size_t lds = (size_t)R * (2 * C + 32) + (size_t)C * (2 * p.d_head + 32);
-    auto k = recon_mlp_mfma_kernel<E, R, C, ACT, kI8>;
+    size_t lds = (size_t)R * (2 * C + 32) + (size_t)C * (2 * p.d_head + 32);
+    ReconParams q = p;
+    q.staged = lds + recon_stage_bytes(p.d_head) + C * sizeof(float) <= kReconLdsMax ? 1 : 0;
+    if (q.staged) lds += recon_stage_bytes(p.d_head);
+    lds += C * sizeof(float);                                   // the first-layer bias in fp32
+    constexpr int TL = 1;               // eight waves of 32 tokens: two waves per SIMD overlap their matrix and vector work
+    auto k = recon_mlp_mfma_kernel<E, R, C, ACT, kI8, TL>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     dim3 grid((p.n_rows + kReconChunk - 1) / kReconChunk, p.batch, p.n_entries);
-    hipLaunchKernelGGL(k, grid, dim3(256), lds, stream, p);
+    hipLaunchKernelGGL(k, grid, dim3(64 * kReconChunk / (32 * TL)), lds, stream, q);
     return hipGetLastError();
 }
 
