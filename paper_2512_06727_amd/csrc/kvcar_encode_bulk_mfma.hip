@@ -30,23 +30,28 @@ template <> struct BulkMma<BF16> {
     static __device__ __forceinline__ f32x4_t mfma(u32x4_t a, u32x4_t b, f32x4_t c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
-    static __device__ __forceinline__ uint16_t to16(float v) { return f32_to_bf16_bits(v); }
+    static __device__ __forceinline__ unsigned pack2(float lo, float hi) {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+        bf16x2_t v = {(__bf16)lo, (__bf16)hi};          // round to nearest even
+        return __builtin_bit_cast(unsigned, v);
+    }
 };
 template <> struct BulkMma<F16> {
     static __device__ __forceinline__ f32x4_t mfma(u32x4_t a, u32x4_t b, f32x4_t c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
     }
-    static __device__ __forceinline__ uint16_t to16(float v) { _Float16 h = (_Float16)v; return __builtin_bit_cast(uint16_t, h); }
+    static __device__ __forceinline__ unsigned pack2(float lo, float hi) {
+        typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+        f16x2_t v = {(_Float16)lo, (_Float16)hi};
+        return __builtin_bit_cast(unsigned, v);
+    }
 };
 
 constexpr int kBulkWaves = 8;
 constexpr int kBulkRows = 16;                          // tokens per wave tile
 constexpr int kBulkTile = kBulkWaves * kBulkRows;      // tokens per workgroup iteration
 constexpr int kBulkMaxKs = 8;                          // input width up to 256: 16-byte chunks per lane and tile
-#ifndef KVCAR_BULK_AHEAD
-#define KVCAR_BULK_AHEAD 2
-#endif
-constexpr int kBulkAhead = KVCAR_BULK_AHEAD;             // tiles in flight per wave
+constexpr int kBulkAhead = 2;                          // tiles in flight per wave (3 and 4 measured the same)
 constexpr int kBulkMinTokens = 8192;                   // below this the launch cannot fill the chip with whole workgroups
 constexpr size_t kBulkLdsMax = 160 * 1024;
 
@@ -69,28 +74,35 @@ __global__ __launch_bounds__(64 * kBulkWaves, 1) void encode_bulk_kernel(EncodeP
     char* reg = lds + (size_t)in_w * stride_w + (size_t)wave * bulk_region(in_w, r);
 
     // this lane's chunks of a tile: chunk f = i * 64 + lane is 16 bytes of row f / cpr of the gathered input
-    // (the columns of the KV heads the layer stores, 8 consecutive ones never straddling a head)
+    // (the columns of the KV heads the layer stores, 8 consecutive ones never straddling a head).  Source offsets
+    // are relative to the tile's first row, so that a tile costs one 64-bit base and no per-chunk multiply.
+    const int x_stride = p.d_kv * 2;
     int c_row[kBulkMaxKs], c_src[kBulkMaxKs], c_dst[kBulkMaxKs];
 #pragma unroll
     for (int i = 0; i < kBulkMaxKs; ++i) {
         const int f = i * 64 + lane;
         const int row = f / cpr, col = (f - row * cpr) * 8;
         c_row[i] = row;
-        c_src[i] = ((int)s.heads[col / p.d_head] * p.d_head + col % p.d_head) * 2;
+        c_src[i] = row * x_stride + ((int)s.heads[col / p.d_head] * p.d_head + col % p.d_head) * 2;
         c_dst[i] = row * stride_x + col * 2;
     }
     const char* x = static_cast<const char*>(s.x);
-    const size_t x_stride = (size_t)p.d_kv * 2;
     auto issue = [&](u32x4_t (&st)[kBulkMaxKs], int tile) {
         const int t0 = tile * kBulkTile + wave * kBulkRows;
+        const char* base = x + (size_t)t0 * x_stride;
+        if (t0 + kBulkRows <= n_tok) {
 #pragma unroll
-        for (int i = 0; i < kBulkMaxKs; ++i)
-            if (i < ks) {
-                const int tok = t0 + c_row[i];
-                u32x4_t v = {0u, 0u, 0u, 0u};
-                if (tok < n_tok) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(x + (size_t)tok * x_stride + c_src[i]));
-                st[i] = v;
-            }
+            for (int i = 0; i < kBulkMaxKs; ++i)
+                if (i < ks) st[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(base + c_src[i]));
+        } else {
+#pragma unroll
+            for (int i = 0; i < kBulkMaxKs; ++i)
+                if (i < ks) {
+                    u32x4_t v = {0u, 0u, 0u, 0u};
+                    if (t0 + c_row[i] < n_tok) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(base + c_src[i]));
+                    st[i] = v;
+                }
+        }
     };
 
     const int step = gridDim.x;
@@ -118,14 +130,29 @@ __global__ __launch_bounds__(64 * kBulkWaves, 1) void encode_bulk_kernel(EncodeP
             }
         }
     }
-    float bias[NB];
+    // the products are formed transposed, Z^T = W^T X^T (the matrix as the first operand), so that a lane holds four
+    // CONSECUTIVE latent columns 16 nb + 4 lg + v of ONE token l16: pairs convert together and leave as 8 bytes
+    f32x4_t bias[NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) bias[nb] = s.b1 ? Elem<E>::load(s.b1, 16 * nb + l16) : 0.f;
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) bias[nb][v] = s.b1 ? Elem<E>::load(s.b1, 16 * nb + 4 * lg + v) : 0.f;
     __syncthreads();
 
-    // cache row of token t: sequence b = t / t_new at position pos(b) + t % t_new
-    auto cache_row = [&](int t) -> size_t {
-        const int b = t / p.t_new, tt = t - b * p.t_new;
+    // Cache row of token t: sequence b = t / t_new at position pos(b) + t % t_new.  The division is done once per
+    // tile, for its first token (the same in every lane); the rows of a tile then step through at most two
+    // sequences when a sequence brings at least a tile's worth of tokens, else each row divides for itself.
+    const bool long_seqs = p.t_new >= kBulkRows;
+    auto cache_row = [&](int t0, int b0, int tt0, int row) -> size_t {
+        int b, tt;
+        if (long_seqs) {
+            const bool carry = tt0 + row >= p.t_new;
+            b = b0 + (carry ? 1 : 0);
+            tt = tt0 + row - (carry ? p.t_new : 0);
+        } else {
+            b = (t0 + row) / p.t_new;
+            tt = t0 + row - b * p.t_new;
+        }
         return (size_t)b * p.max_seq + (p.positions ? p.positions[b] : p.pos0) + tt;
     };
 
@@ -136,69 +163,71 @@ __global__ __launch_bounds__(64 * kBulkWaves, 1) void encode_bulk_kernel(EncodeP
             if (i < ks) *reinterpret_cast<u32x4_t*>(reg + c_dst[i]) = st[i];
         if (next < n_tiles) issue(st, next);
         if (t0 >= n_tok) return;                   // a wave tile past the end: only in the last workgroup tile
+        const int b0 = __builtin_amdgcn_readfirstlane(t0 / p.t_new);
+        const int tt0 = t0 - b0 * p.t_new;
 
         f32x4_t acc[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         for (int s2 = 0; s2 < ks; ++s2) {
-            const u32x4_t a = *reinterpret_cast<const u32x4_t*>(reg + l16 * stride_x + (32 * s2 + 8 * lg) * 2);
+            const u32x4_t xa = *reinterpret_cast<const u32x4_t*>(reg + l16 * stride_x + (32 * s2 + 8 * lg) * 2);
             const char* wrow = wbuf + (32 * s2 + 8 * lg + (l16 >> 2)) * stride_w + (l16 & 3) * 8;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(wrow + nb * 32));
                 const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(wrow + nb * 32 + 4 * stride_w));
                 const u32x2_t lo2 = __builtin_bit_cast(u32x2_t, lo), hi2 = __builtin_bit_cast(u32x2_t, hi);
-                acc[nb] = BulkMma<E>::mfma(a, u32x4_t{lo2[0], lo2[1], hi2[0], hi2[1]}, acc[nb]);
+                acc[nb] = BulkMma<E>::mfma(u32x4_t{lo2[0], lo2[1], hi2[0], hi2[1]}, xa, acc[nb]);
             }
         }
-        // result layout: this lane holds column 16 nb + l16 of tokens 4 lg + v
+        // this lane: token l16, latent columns 16 nb + 4 lg + v
         if constexpr (kI8) {
             constexpr int ostride = r + 16;
             signed char* z8 = static_cast<signed char*>(s.z);
+            float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                float mn = INFINITY, mx = -INFINITY;
+            for (int nb = 0; nb < NB; ++nb) {
+                acc[nb] += bias[nb];
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    acc[nb][v] += bias[nb];
+                for (int v = 0; v < 4; ++v) {
                     mn = fminf(mn, acc[nb][v]);
                     mx = fmaxf(mx, acc[nb][v]);
                 }
-#pragma unroll
-                for (int off = 8; off > 0; off >>= 1) {
-                    mn = fminf(mn, __shfl_xor(mn, off));
-                    mx = fmaxf(mx, __shfl_xor(mx, off));
-                }
-                const QuantParams qp = quant_params(mn, mx);
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    *reinterpret_cast<signed char*>(reg + (4 * lg + v) * ostride + 16 * nb + l16) = quant_code(acc[nb][v], qp);
-                const int t = t0 + 4 * lg + v;
-                if (l16 == 0 && t < n_tok) static_cast<RowMeta*>(s.meta)[cache_row(t)] = quant_meta(qp);
             }
+            mn = fminf(mn, __shfl_xor(mn, 16)); mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mn = fminf(mn, __shfl_xor(mn, 32)); mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const QuantParams qp = quant_params(mn, mx);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                unsigned w = 0;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) w |= (unsigned)(unsigned char)quant_code(acc[nb][v], qp) << (8 * v);
+                *reinterpret_cast<unsigned*>(reg + l16 * ostride + 16 * nb + 4 * lg) = w;
+            }
+            if (lg == 0 && t0 + l16 < n_tok) static_cast<RowMeta*>(s.meta)[cache_row(t0, b0, tt0, l16)] = quant_meta(qp);
             constexpr int total = kBulkRows * NB;              // 16-byte chunks of the tile's code rows
 #pragma unroll
             for (int i = 0; i < (total + 63) / 64; ++i) {
                 const int f = i * 64 + lane;
                 const int row = f / NB, ch = f % NB;
                 if (f < total && t0 + row < n_tok)
-                    *reinterpret_cast<u32x4_t*>(z8 + cache_row(t0 + row) * r + ch * 16) = *reinterpret_cast<const u32x4_t*>(reg + row * ostride + ch * 16);
+                    *reinterpret_cast<u32x4_t*>(z8 + cache_row(t0, b0, tt0, row) * r + ch * 16) = *reinterpret_cast<const u32x4_t*>(reg + row * ostride + ch * 16);
             }
         } else {
             constexpr int ostride = 2 * r + 16;
             char* z = static_cast<char*>(s.z);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    *reinterpret_cast<uint16_t*>(reg + (4 * lg + v) * ostride + (16 * nb + l16) * 2) = BulkMma<E>::to16(acc[nb][v] + bias[nb]);
+            for (int nb = 0; nb < NB; ++nb) {
+                const f32x4_t y = acc[nb] + bias[nb];
+                *reinterpret_cast<u32x2_t*>(reg + l16 * ostride + (16 * nb + 4 * lg) * 2) = u32x2_t{BulkMma<E>::pack2(y[0], y[1]), BulkMma<E>::pack2(y[2], y[3])};
+            }
             constexpr int ocpr = 2 * NB;                       // 16-byte chunks per latent row
 #pragma unroll
             for (int i = 0; i < NB / 2; ++i) {
                 const int f = i * 64 + lane;
                 const int row = f / ocpr, ch = f % ocpr;
                 if (t0 + row < n_tok)
-                    *reinterpret_cast<u32x4_t*>(z + (cache_row(t0 + row) * r + ch * 8) * 2) = *reinterpret_cast<const u32x4_t*>(reg + row * ostride + ch * 16);
+                    *reinterpret_cast<u32x4_t*>(z + (cache_row(t0, b0, tt0, row) * r + ch * 8) * 2) = *reinterpret_cast<const u32x4_t*>(reg + row * ostride + ch * 16);
             }
         }
     };
