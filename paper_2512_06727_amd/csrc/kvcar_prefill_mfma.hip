@@ -354,7 +354,7 @@ __global__ __launch_bounds__(64 * kReconChunk / (32 * TL)) void recon_mlp_mfma_k
 }
 
 
-static bool recon_width_ok(int r) { return r == 32 || r == 64 || r == 96 || r == 128 || r == 192 || r == 256 || r == 384; }
+static bool recon_width_ok(int r) { return r % 32 == 0 && r >= 32 && r <= 384; }      // every width a GPT-2 or TinyLlama layer can store under a reuse map
 
 // Two-layer decoders: the (latent, hidden) shapes with an instance
 static bool recon_mlp_shape_ok(const SideDesc& sd) {
@@ -402,8 +402,13 @@ static hipError_t launch_recon_width(const ReconParams& p, int r, hipStream_t st
         case 64: return launch_recon_one<E, 64, kI8>(p, stream);
         case 96: return launch_recon_one<E, 96, kI8>(p, stream);
         case 128: return launch_recon_one<E, 128, kI8>(p, stream);
+        case 160: return launch_recon_one<E, 160, kI8>(p, stream);
         case 192: return launch_recon_one<E, 192, kI8>(p, stream);
+        case 224: return launch_recon_one<E, 224, kI8>(p, stream);
         case 256: return launch_recon_one<E, 256, kI8>(p, stream);
+        case 288: return launch_recon_one<E, 288, kI8>(p, stream);
+        case 320: return launch_recon_one<E, 320, kI8>(p, stream);
+        case 352: return launch_recon_one<E, 352, kI8>(p, stream);
         case 384: return launch_recon_one<E, 384, kI8>(p, stream);
         default: return hipErrorInvalidValue;
     }

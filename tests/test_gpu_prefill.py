@@ -62,6 +62,8 @@ CASES = {
     "c4-bf16-p2": (C[4].scaled(n_layers=6, batch=2, n_cached=200, policy="P2"), 200, [(0, 200)], {}),
     # fp16, GPT-2 shape (12 KV heads, latent 384 / 288)
     "c1-f16": (C[1].scaled(n_layers=4, batch=2, n_cached=260), 260, [(0, 260)], {}),
+    # GPT-2 shape under a Bernoulli(0.3) map: layers store 6..12 of 12 heads (latent 192..384 in steps of 32)
+    "c1-f16-bernoulli": (C[1].scaled(n_layers=7, batch=2, n_cached=140, reuse="bernoulli:0.3"), 140, [(0, 140)], {}),
     # two-layer GELU / LeakyReLU decoders
     "c3-mlp": (C[3].scaled(n_layers=2, batch=2, n_cached=140), 140, [(0, 140)], {}),
     "mlp-leaky": (C[3].scaled(n_layers=3, batch=2, n_cached=100, act="leaky_relu", reuse="from2:1", policy="P2"), 100, [(0, 100)],
