@@ -5,9 +5,10 @@
 // A wave owns 32 tokens and walks the hidden width in blocks of 32 columns:
 //   H^T[hidden blk, token] = W1^T . X^T   v_mfma_f32_32x32x16 (A = a column slice of W1 read from LDS with
 //                                          the transposing load, B = the token rows, resident in registers)
-//   -> + b1, activation, split into a hi + lo pair of 16-bit values: the result layout IS the A-operand
+//   -> + b1, activation, split into a hi + lo pair of 16-bit values: the result layout IS an operand
 //      layout of the second product, so the hidden activations never leave registers
-//   Z[token, r] += H[token, hidden blk] . W2[hidden blk, :]   (B = a row slice of W2, transposing load)
+//   Z^T[r, token] += W2[hidden blk, :]^T . H^T[hidden blk, token]   (A = a row slice of W2, transposing load):
+//      formed transposed, so that a lane ends with consecutive latent columns of one token (8-byte stores)
 // The two weight slices of the next hidden block are fetched into registers while the current block
 // computes and written to the other half of a double LDS buffer: one barrier per hidden block.
 // The latent is rounded once, from the fp32 accumulator, to the cache dtype and appended.
@@ -86,13 +87,17 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
     u32x4_t xr[KX];
     {
         const char* xrow = static_cast<const char*>(s.x) + (size_t)(tok_ok ? tok : 0) * p.d_kv * 2;
+        // input column 16 ks + 8 h sits in stored head hi at offset off + 8 h (d_head is a multiple of 16 here): the
+        // pair (hi, off) steps along with ks, no division per k-step
+        int hi = 0, off = 0;
 #pragma unroll
         for (int ks = 0; ks < KX; ++ks) {
-            const int kk = 16 * ks + 8 * h;
-            const int src_col = (int)s.heads[kk / p.d_head] * p.d_head + kk % p.d_head;
+            const int src_col = (int)s.heads[hi] * p.d_head + off + 8 * h;
             u32x4_t v = *reinterpret_cast<const u32x4_t*>(xrow + src_col * 2);
             if (!tok_ok) v = u32x4_t{0u, 0u, 0u, 0u};
             xr[ks] = v;
+            off += 16;
+            if (off >= p.d_head) { off -= p.d_head; ++hi; }
         }
     }
 
@@ -142,6 +147,8 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
     // would queue behind the weight prefetch and serialise its latency into every block
     float* b1s = reinterpret_cast<float*>(lds + 2 * buf_bytes);
     for (int i = tid; i < hid; i += 256) b1s[i] = s.b1 ? Elem<E>::load(s.b1, i) : 0.f;
+    float* b2s = b1s + 1024;                     // second-layer bias [r], past the largest first-layer bias
+    for (int i = tid; i < r; i += 256) b2s[i] = s.b2 ? Elem<E>::load(s.b2, i) : 0.f;
 
     fetch(0);
     for (int mb = 0; mb < n_mb; ++mb) {
@@ -184,7 +191,8 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
             hi[s2] = u32x4_t{wh[0], wh[1], wh[2], wh[3]};
             lo[s2] = u32x4_t{wl[0], wl[1], wl[2], wl[3]};
         }
-        // ---- Z[token, :] += H[token, hidden blk] . W2[hidden blk, :] ------------------------------
+        // ---- Z^T[:, token] += W2[hidden blk, :]^T . H^T[hidden blk, token] (formed transposed: a lane then holds
+        // consecutive latent columns of ONE token and the epilogue stores 8 bytes at a time) -----------------
         // k-slots of lane half h in k-step s2 are hidden rows 16 s2 + 4h + j and 16 s2 + 8 + 4h + j
         const char* w2base = buf + w2_off + (4 * h + (l16 >> 2)) * w2_stride + (16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
 #pragma unroll
@@ -192,55 +200,58 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
 #pragma unroll
             for (int nb = 0; nb < NBZ; ++nb) {
                 const u32x4_t bw = tr_pair(w2base + 16 * s2 * w2_stride + nb * 64, 8 * w2_stride);
-                accz[nb] = EMma<E>::mfma(hi[s2], bw, accz[nb]);
-                accz[nb] = EMma<E>::mfma(lo[s2], bw, accz[nb]);
+                accz[nb] = EMma<E>::mfma(bw, hi[s2], accz[nb]);
+                accz[nb] = EMma<E>::mfma(bw, lo[s2], accz[nb]);
             }
     }
 
     // ---- latent rows: bias, one rounding to the cache dtype, append --------------------------------
-    // lane holds latent column 32nb + l32 of tokens 8a + 4h + j
-    uint16_t* z = static_cast<uint16_t*>(s.z);
-    const int tbase = blockIdx.x * kEmTokens + wave * 32;
-    float b2v[NBZ];
+    // lane holds, for token l32 of the wave's tile, latent columns 32 nb + 8a + 4h + j (register 4a + j)
+    const int t = blockIdx.x * kEmTokens + wave * 32 + l32;
+    if (t >= n_tok) return;
+    const int b = t / p.t_new, tt = t - b * p.t_new;
+    const size_t row = (size_t)b * p.max_seq + (p.positions ? p.positions[b] : p.pos0) + tt;
 #pragma unroll
-    for (int nb = 0; nb < NBZ; ++nb) b2v[nb] = s.b2 ? Elem<E>::load(s.b2, 32 * nb + l32) : 0.f;
+    for (int nb = 0; nb < NBZ; ++nb)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const f32x4_t b4 = *reinterpret_cast<const f32x4_t*>(b2s + 32 * nb + 8 * a + 4 * h);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) accz[nb][4 * a + j] += b4[j];
+        }
     if (s.meta) {
-        // ---- int8 latents: a token's row lies in the 32 lanes of its half (columns 32 nb + l32) ---------
+        // ---- int8 latents: the token's row lies in this lane and its partner in the other half ---------
         signed char* z8 = static_cast<signed char*>(s.z);
+        float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            float mn = INFINITY, mx = -INFINITY;
+        for (int nb = 0; nb < NBZ; ++nb)
 #pragma unroll
-            for (int nb = 0; nb < NBZ; ++nb) {
-                accz[nb][v] += b2v[nb];
+            for (int v = 0; v < 16; ++v) {
                 mn = fminf(mn, accz[nb][v]);
                 mx = fmaxf(mx, accz[nb][v]);
             }
+        mn = fminf(mn, __shfl_xor(mn, 32));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const QuantParams qp = quant_params(mn, mx);
 #pragma unroll
-            for (int off = 16; off > 0; off >>= 1) {
-                mn = fminf(mn, __shfl_xor(mn, off));
-                mx = fmaxf(mx, __shfl_xor(mx, off));
+        for (int nb = 0; nb < NBZ; ++nb)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                unsigned w = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w |= (unsigned)(unsigned char)quant_code(accz[nb][4 * a + j], qp) << (8 * j);
+                *reinterpret_cast<unsigned*>(z8 + row * r + 32 * nb + 8 * a + 4 * h) = w;
             }
-            const QuantParams qp = quant_params(mn, mx);
-            const int t = tbase + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (t >= n_tok) continue;
-            const int b = t / p.t_new, tt = t - b * p.t_new;
-            const size_t row = (size_t)b * p.max_seq + (p.positions ? p.positions[b] : p.pos0) + tt;
-#pragma unroll
-            for (int nb = 0; nb < NBZ; ++nb) z8[row * r + 32 * nb + l32] = quant_code(accz[nb][v], qp);
-            if (l32 == 0) static_cast<RowMeta*>(s.meta)[row] = quant_meta(qp);
-        }
+        if (h == 0) static_cast<RowMeta*>(s.meta)[row] = quant_meta(qp);
         return;
     }
+    char* z = static_cast<char*>(s.z);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int t = tbase + 8 * (v >> 2) + 4 * h + (v & 3);
-        if (t >= n_tok) continue;
-        const int b = t / p.t_new, tt = t - b * p.t_new;
-        const size_t row_off = ((size_t)b * p.max_seq + (p.positions ? p.positions[b] : p.pos0) + tt) * r;
+    for (int nb = 0; nb < NBZ; ++nb)
 #pragma unroll
-        for (int nb = 0; nb < NBZ; ++nb) z[row_off + 32 * nb + l32] = EMma<E>::to16(accz[nb][v] + b2v[nb]);
-    }
+        for (int a = 0; a < 4; ++a)
+            *reinterpret_cast<u32x2_t*>(z + (row * r + 32 * nb + 8 * a + 4 * h) * 2) =
+                u32x2_t{EMma<E>::pack2(accz[nb][4 * a], accz[nb][4 * a + 1]), EMma<E>::pack2(accz[nb][4 * a + 2], accz[nb][4 * a + 3])};
 }
 
 namespace {
@@ -260,7 +271,7 @@ template <typename E, int KX, int NBZ>
 hipError_t em_launch_shape(const EncodeParams& p, int side0, int n_sides, bool gelu, hipStream_t stream) {
     const int n_tok = p.batch * p.t_new;
     dim3 grid((n_tok + kEmTokens - 1) / kEmTokens, n_sides);
-    constexpr size_t lds = 2 * (size_t)(16 * KX * kW1Stride + 32 * (64 * NBZ + 32)) + 4 * 1024;     // + first-layer bias
+    constexpr size_t lds = 2 * (size_t)(16 * KX * kW1Stride + 32 * (64 * NBZ + 32)) + 4 * 1024 + 4 * 32 * NBZ;     // + both biases in fp32
     auto kern = gelu ? encode_mlp_mfma_kernel<E, KX, NBZ, true> : encode_mlp_mfma_kernel<E, KX, NBZ, false>;
     static bool attr[2] = {false, false};
     if (lds > 64 * 1024 && !attr[gelu]) {
@@ -289,9 +300,9 @@ hipError_t em_launch(const EncodeParams& p, int side0, int n_sides, hipStream_t 
 }  // namespace
 
 // 16-bit dtype, every stored tensor two-layer with one of the compiled (input width, latent) shapes,
-// 8-column chunks inside one head, hidden width a multiple of 32 up to 1024.
+// 16-column chunks inside one head, hidden width a multiple of 32 up to 1024.
 bool encode_mlp_mfma_supported(const EncodeParams& p, int dtype) {
-    if (dtype == KVCAR_F32 || p.d_head % 8) return false;
+    if (dtype == KVCAR_F32 || p.d_head % 16) return false;      // a 16-column k-step stays inside one head
     bool any = false;
     for (int i = 0; i < 2; ++i) {
         const EncodeSide& s = p.s[i];
