@@ -24,7 +24,7 @@
 // Measured budget of the attention kernel on 16 x 4096 tokens (per launch, with parts removed in turn):
 // matrix instructions alone would take 0.44 ms at the dense peak; LDS reads of the operands 0.40 ms, staging
 // and barriers 0.19 ms, the softmax's vector instructions 0.5-0.7 ms (on this chip a matrix instruction blocks
-// vector issue for about half its duration); they overlap only in part: 1.17 ms.  Hence the effort to keep
+// vector issue for about half its duration); they overlap only in part: 1.13 ms.  Hence the effort to keep
 // vector work per score down to exp2 + half a conversion + half a dot2 + half a max3.
 #include "kvcar_attend_mfma_body.hpp"
 
@@ -471,7 +471,7 @@ hipError_t launch_recon_mfma(const ReconParams& p, int dtype, hipStream_t stream
 constexpr int kKvTile = 64;           // decoded rows per LDS tile
 constexpr float kSlack = 8.f;         // a query's softmax reference point moves when a score exceeds it by 2^kSlack
 // Launch shape (measured on 16 x 4096 tokens, 32 heads of 64: TFLOP/s of the kernel):
-//   one 32-query block per wave, 8 waves, 2 workgroups per CU (4 waves per SIMD)   887      <- used (944 after later savings)
+//   one 32-query block per wave, 8 waves, 2 workgroups per CU (4 waves per SIMD)   887      <- used (970 after later savings)
 //   two blocks per wave, 4 waves, 2 workgroups per CU (2 waves per SIMD)            835
 //   two blocks per wave, 8 waves, 1 workgroup per CU                                779;  with 128-row tiles 808
 //   two blocks per wave, 4 waves, 1 workgroup per CU (1 wave per SIMD)              485
@@ -641,9 +641,11 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
 #pragma unroll
                     for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s[qb][v]), s[qb][v + 1]);
                     mx = fmaxf(mx, s[qb][15]);
-                    mx = fmaxf(mx, __shfl_xor(mx, 32));
-                    const bool moved = mx > kSlack || (jt == 0 && kvb == 0);
-                    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+                    // the two lanes of a query (one per half of the wave) meet only when one of them has to move
+                    const bool first = jt == 0 && kvb == 0;
+                    if (__builtin_amdgcn_ballot_w64(mx > kSlack || first) != 0) {
+                        mx = fmaxf(mx, __shfl_xor(mx, 32));
+                        const bool moved = mx > kSlack || first;
                         const float delta = moved ? mx : 0.f;
                         const float alpha = __builtin_amdgcn_exp2f(-delta);
                         l_run[qb] *= alpha;
