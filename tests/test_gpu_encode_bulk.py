@@ -20,6 +20,10 @@ CASES = {
     # Bernoulli(0.3) map: layers storing 1..4 heads; P2 keeps the latent at full width (64 h -> 128)
     "c4-bf16": (C[4].scaled(n_layers=8, batch=3, n_cached=2731, n_steps=0), {}),
     "c4-bf16-p2": (C[4].scaled(n_layers=6, batch=3, n_cached=2731, n_steps=0, policy="P2"), {"with_bias": True}),
+    # 3 x 22000 = 66000 tokens: 516 workgroup tiles over 128 workgroups per tensor, so every wave walks four or five
+    # tiles (the look-ahead slots are reused) and the last workgroup tile is ragged
+    "c2-bf16-long": (C[2].scaled(n_layers=3, batch=3, n_cached=22000, n_steps=0), {}),
+    "c2-int8-long": (C[2].scaled(n_layers=3, batch=3, n_cached=22000, n_steps=0), {"latent_format": "int8"}),
     # int8 latent rows: the quantiser runs over whole rows in the same kernel
     "c2-int8": (C[2].scaled(n_layers=3, batch=3, n_cached=2731, n_steps=0), {"latent_format": "int8"}),
     "c4-int8-bias": (C[4].scaled(n_layers=5, batch=3, n_cached=2731, n_steps=0), {"latent_format": "int8", "with_bias": True}),
