@@ -488,19 +488,27 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         for (int nb = 0; nb < NHB; ++nb) {
             float mx = fmaxf(fmaxf(fmaxf(sT[0][nb][0], sT[0][nb][1]), fmaxf(sT[0][nb][2], sT[0][nb][3])),
                              fmaxf(fmaxf(sT[1][nb][0], sT[1][nb][1]), fmaxf(sT[1][nb][2], sT[1][nb][3])));
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[nb], mx);
-            alpha[nb] = __builtin_amdgcn_exp2f(m_run[nb] - m_new);     // m_run = -inf on the first tile gives 0
-            rescale |= m_new != m_run[nb];
-            m_run[nb] = m_new;
+            // The four lanes of a head share its running maximum.  They exchange their tile maxima only when some lane
+            // of the wave holds a score above its running maximum: after the first tiles the maxima have settled and
+            // the two cross-lane steps, the exponential of the correction and the rescaling are skipped.
+            alpha[nb] = 1.f;
+            if (__builtin_amdgcn_ballot_w64(mx > m_run[nb]) != 0) {
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run[nb], mx);
+                alpha[nb] = __builtin_amdgcn_exp2f(m_run[nb] - m_new);     // m_run = -inf on the first tile gives 0
+                rescale |= m_new != m_run[nb];
+                m_run[nb] = m_new;
+                l_run[nb] *= alpha[nb];
+            }
+            const float m_new = m_run[nb];
             float e[8];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 e[v] = __builtin_amdgcn_exp2f(sT[0][nb][v] - m_new);
                 e[4 + v] = __builtin_amdgcn_exp2f(sT[1][nb][v] - m_new);
             }
-            l_run[nb] = l_run[nb] * alpha[nb] + ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+            l_run[nb] += ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
             if constexpr (kI8) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) { e[v] *= av4[0][v]; e[4 + v] *= av4[1][v]; }
