@@ -9,8 +9,8 @@
 //      layout of the second product, so the hidden activations never leave registers
 //   Z^T[r, token] += W2[hidden blk, :]^T . H^T[hidden blk, token]   (A = a row slice of W2, transposing load):
 //      formed transposed, so that a lane ends with consecutive latent columns of one token (8-byte stores)
-// The two weight slices of the next hidden block are fetched into registers while the current block
-// computes and written to the other half of a double LDS buffer: one barrier per hidden block.
+// The two weight slices of a later hidden block are fetched into registers while the current block
+// computes and written to another of the LDS buffers: one barrier per hidden block.
 // The latent is rounded once, from the fp32 accumulator, to the cache dtype and appended.
 #include "kvcar_device.hpp"
 
@@ -66,14 +66,19 @@ constexpr int kW1Stride = 64 + 32;   // LDS row stride of a [in, 32] slice of W1
 // (r == 32 NBZ exactly); GELU: the activation is GELU, else leaky ReLU with the side's slope (the identity
 // is slope 1). Exact compile-time shapes keep the whole hidden-block body one straight-line block: with
 // run-time guards every transposing load sat in a block of its own and paid its LDS latency serially.
-template <typename E, int KX, int NBZ, bool GELU>
-__global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p, int side0) {
+// kSmall (launches of a few tokens: a decode step): a workgroup takes 32 tokens and its four waves split the HIDDEN
+// blocks instead of the tokens - with 16 tokens one wave would otherwise walk all blocks alone, a chain of dependent
+// matrix and vector work (18 us for 256 -> 256 -> 128).  Four weight slices are staged per round, wave w computes
+// block 4 round + w, the waves' partial latent rows are added in wave order through LDS and wave 0 appends them.
+template <typename E, int KX, int NBZ, bool GELU, bool kSmall>
+__global__ __launch_bounds__(256, kSmall ? 1 : 2) void encode_mlp_mfma_kernel(EncodeParams p, int side0) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const EncodeSide& s = p.s[blockIdx.y + side0];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
     const int n_tok = p.batch * p.t_new;
-    const int tok = blockIdx.x * kEmTokens + wave * 32 + l32;       // the token column (B operand) of this lane
+    const int tok0 = kSmall ? blockIdx.x * 32 : blockIdx.x * kEmTokens + wave * 32;     // first token of this wave's tile
+    const int tok = tok0 + l32;                                     // the token column (B operand) of this lane
     const bool tok_ok = tok < n_tok;
     constexpr int in_w = 16 * KX, r = 32 * NBZ;
     constexpr int w2_stride = 2 * r + 32;
@@ -105,8 +110,7 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
     // (32 rows of 2r bytes); 16-byte chunk f of the pair belongs to thread f % 256
     constexpr int c1 = in_w * 4, c2 = 32 * (r >> 3), cpr = r >> 3;
     constexpr int n_pre = (c1 + c2 + 255) / 256;
-    u32x4_t pre[n_pre];
-    auto fetch = [&](int mb) {
+    auto fetch = [&](u32x4_t (&pre)[n_pre], int mb) {
 #pragma unroll
         for (int i = 0; i < n_pre; ++i) {
             const int f = i * 256 + tid;
@@ -122,7 +126,7 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
             pre[i] = v;
         }
     };
-    auto park = [&](char* buf) {
+    auto park = [&](const u32x4_t (&pre)[n_pre], char* buf) {
 #pragma unroll
         for (int i = 0; i < n_pre; ++i) {
             const int f = i * 256 + tid;
@@ -145,18 +149,14 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
 
     // first-layer bias -> LDS (fp32), read from there inside the loop: a global load in the loop body
     // would queue behind the weight prefetch and serialise its latency into every block
-    float* b1s = reinterpret_cast<float*>(lds + 2 * buf_bytes);
+    constexpr int NBUF = kSmall ? 4 : 2;
+    float* b1s = reinterpret_cast<float*>(lds + NBUF * buf_bytes);
     for (int i = tid; i < hid; i += 256) b1s[i] = s.b1 ? Elem<E>::load(s.b1, i) : 0.f;
     float* b2s = b1s + 1024;                     // second-layer bias [r], past the largest first-layer bias
     for (int i = tid; i < r; i += 256) b2s[i] = s.b2 ? Elem<E>::load(s.b2, i) : 0.f;
 
-    fetch(0);
-    for (int mb = 0; mb < n_mb; ++mb) {
-        char* buf = lds + (mb & 1) * buf_bytes;
-        park(buf);
-        if (mb + 1 < n_mb) fetch(mb + 1);
-        __syncthreads();          // slice mb visible; every wave is past block mb-1, whose buffer the next park reuses
-
+    // one hidden block: hidden rows, activation, their share of the latent rows
+    auto block = [&](int mb, const char* buf) {
         // bias of this lane's hidden rows 32mb + 8a + 4h + j: four 16-byte reads
         f32x4_t bq[4];
 #pragma unroll
@@ -203,11 +203,58 @@ __global__ __launch_bounds__(256, 2) void encode_mlp_mfma_kernel(EncodeParams p,
                 accz[nb] = EMma<E>::mfma(bw, hi[s2], accz[nb]);
                 accz[nb] = EMma<E>::mfma(bw, lo[s2], accz[nb]);
             }
+    };
+
+    if constexpr (kSmall) {
+        u32x4_t pre[4][n_pre];
+        auto fetch4 = [&](int mb0) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (mb0 + u < n_mb) fetch(pre[u], mb0 + u);
+        };
+        fetch4(0);
+        for (int mb0 = 0; mb0 < n_mb; mb0 += 4) {
+            if (mb0) __syncthreads();         // every wave is done with the previous round's slices
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (mb0 + u < n_mb) park(pre[u], lds + u * buf_bytes);
+            if (mb0 + 4 < n_mb) fetch4(mb0 + 4);
+            __syncthreads();
+            if (mb0 + wave < n_mb) block(mb0 + wave, lds + wave * buf_bytes);
+        }
+        // the waves' partial latent rows, added in wave order (a fixed order); the slices' buffers are free now
+        __syncthreads();
+        float* part = reinterpret_cast<float*>(lds);       // [wave][NBZ][16][64]
+#pragma unroll
+        for (int nb = 0; nb < NBZ; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) part[((wave * NBZ + nb) * 16 + v) * 64 + lane] = accz[nb][v];
+        __syncthreads();
+        if (wave != 0) return;
+#pragma unroll
+        for (int nb = 0; nb < NBZ; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float a = part[(nb * 16 + v) * 64 + lane];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) a += part[((w * NBZ + nb) * 16 + v) * 64 + lane];
+                accz[nb][v] = a;
+            }
+    } else {
+        u32x4_t pre[n_pre];
+        fetch(pre, 0);
+        for (int mb = 0; mb < n_mb; ++mb) {
+            char* buf = lds + (mb & 1) * buf_bytes;
+            park(pre, buf);
+            if (mb + 1 < n_mb) fetch(pre, mb + 1);
+            __syncthreads();      // slice mb visible; every wave is past block mb-1, whose buffer the next park reuses
+            block(mb, buf);
+        }
     }
 
     // ---- latent rows: bias, one rounding to the cache dtype, append --------------------------------
     // lane holds, for token l32 of the wave's tile, latent columns 32 nb + 8a + 4h + j (register 4a + j)
-    const int t = blockIdx.x * kEmTokens + wave * 32 + l32;
+    const int t = tok;
     if (t >= n_tok) return;
     const int b = t / p.t_new, tt = t - b * p.t_new;
     const size_t row = (size_t)b * p.max_seq + (p.positions ? p.positions[b] : p.pos0) + tt;
@@ -270,14 +317,18 @@ bool em_side_ok(const EncodeSide& s) {
 template <typename E, int KX, int NBZ>
 hipError_t em_launch_shape(const EncodeParams& p, int side0, int n_sides, bool gelu, hipStream_t stream) {
     const int n_tok = p.batch * p.t_new;
-    dim3 grid((n_tok + kEmTokens - 1) / kEmTokens, n_sides);
-    constexpr size_t lds = 2 * (size_t)(16 * KX * kW1Stride + 32 * (64 * NBZ + 32)) + 4 * 1024 + 4 * 32 * NBZ;     // + both biases in fp32
-    auto kern = gelu ? encode_mlp_mfma_kernel<E, KX, NBZ, true> : encode_mlp_mfma_kernel<E, KX, NBZ, false>;
-    static bool attr[2] = {false, false};
-    if (lds > 64 * 1024 && !attr[gelu]) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    constexpr size_t buf = (size_t)(16 * KX * kW1Stride + 32 * (64 * NBZ + 32)), biases = 4 * 1024 + 4 * 32 * NBZ;     // both biases in fp32
+    // a few tokens (a decode step): 32 tokens per workgroup, the waves split the hidden blocks
+    const bool small = n_tok <= kEmTokens && 4 * buf + biases <= 160 * 1024;
+    dim3 grid(small ? (n_tok + 31) / 32 : (n_tok + kEmTokens - 1) / kEmTokens, n_sides);
+    const size_t lds = (small ? 4 : 2) * buf + biases;
+    void (*kern)(EncodeParams, int) = small ? (gelu ? encode_mlp_mfma_kernel<E, KX, NBZ, true, true> : encode_mlp_mfma_kernel<E, KX, NBZ, false, true>)
+                                            : (gelu ? encode_mlp_mfma_kernel<E, KX, NBZ, true, false> : encode_mlp_mfma_kernel<E, KX, NBZ, false, false>);
+    static bool attr[2][2] = {{false, false}, {false, false}};
+    if (lds > 64 * 1024 && !attr[small][gelu]) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (err != hipSuccess) return err;
-        attr[gelu] = true;
+        attr[small][gelu] = true;
     }
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p, side0);
     return hipGetLastError();

@@ -5,7 +5,8 @@ import pytest
 import torch
 
 from paper_2512_06727_amd import synth
-from tests.helpers import (ABS_TOL, assert_cache_close, assert_outputs_close, run_gpu, run_oracle)
+from tests.helpers import (ABS_TOL, assert_cache_close, assert_outputs_close, assert_quantized_cache_close, build_oracle,
+                           oracle_prefill, run_gpu, run_oracle)
 
 pytestmark = pytest.mark.gpu
 
@@ -83,6 +84,30 @@ def test_two_layer_decoder_uses_the_mfma_kernels():
         assert ses.ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached + 1).uses_mfma == 1, name
     w, kw = CASES["leaky-bias"]            # hidden width 160: no resident-weight instance, plain-ALU kernels
     assert Session(w, with_bias=True).ctx.describe_plan(0, w.batch, w.n_cached + 1).uses_mfma == 0
+
+
+@pytest.mark.parametrize("batch,t_new", [(16, 1), (35, 2), (1, 1), (4, 32), (43, 3)])
+@pytest.mark.parametrize("variant", ["gelu-bf16", "leaky-f16-bias", "gelu-int8"])
+def test_two_layer_encoder_on_a_few_tokens(batch, t_new, variant):
+    """Encode calls of up to 128 tokens through a two-layer encoder: the kernel form whose waves split the hidden
+    blocks (1..4 workgroups of 32 tokens, ragged), and the first sizes above it (129 tokens)."""
+    from paper_2512_06727_amd.harness import Session
+    kw = {"gelu-bf16": {}, "leaky-f16-bias": {"with_bias": True}, "gelu-int8": {"latent_format": "int8"}}[variant]
+    over = {"leaky-f16-bias": dict(dtype="f16", act="leaky_relu")}.get(variant, {})
+    w = synth.CONFIGS[3].scaled(n_layers=2, batch=batch, n_cached=t_new, n_steps=1, **over)
+    from paper_2512_06727_amd import binding
+    assert Session(w, **kw).ctx.describe_encode(0, batch, t_new) == binding.ENC_MFMA_TWO_LAYER
+    fmt = kw.get("latent_format", "dtype")
+    orc = build_oracle(w, with_bias=kw.get("with_bias", False), latent_format=fmt)
+    for n in range(w.n_layers):
+        oracle_prefill(orc, w, n, 0, t_new)
+    ses = Session(w, poison=True, **kw)
+    ses.prefill(0, t_new, chunk=t_new)
+    torch.cuda.synchronize()
+    if fmt == "int8":
+        assert_quantized_cache_close(w, ses, orc, t_new)
+    else:
+        assert_cache_close(w, ses, orc, t_new)
 
 
 @pytest.mark.parametrize("name", ["c2-small", "c4-small", "c4-small-p2"])
