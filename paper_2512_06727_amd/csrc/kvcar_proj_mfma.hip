@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void qtilde_mfma_kernel(AttendParams p) {
 // ---------------------------------------------------------------------------------------------
 constexpr int kCombMaxSplits = 32;
 
-template <typename E, int NBO, int kPf>
+template <typename E, int NBO, int kPf, int kDepth = 4>
 __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int rows_per_wg) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const GroupDesc& g = p.g[blockIdx.z];
@@ -166,11 +166,11 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
     float* wts = om + (size_t)rows_per_wg * pstride;                    // [rows_per_wg][ns]
 
     // Small launches are a chain of memory round trips (decoder slice, (m, l) pairs, latent sums): when a thread
-    // has at most kPf items of phase 1b, their first four splits are requested here, before anything waits on
-    // memory, so that the three share one round trip.
+    // has at most kPf items of phase 1b, their first kDepth splits (4, or 16 for launches of a few rows) are
+    // requested here, before anything waits on memory, so that the three share one round trip.
     const int c4n = rv >> 2;
     constexpr bool prefetch = kPf > 0;                      // the launcher picks kPf >= items per thread, or 0
-    f32x4_t xp[kPf > 0 ? kPf : 1][4];
+    f32x4_t xp[kPf > 0 ? kPf : 1][kDepth];
     if constexpr (prefetch) {
 #pragma unroll
         for (int it = 0; it < kPf; ++it) {
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
             const int b = live ? row / len : 0, i = live ? row - b * len : 0;
             const float* prow = p.part + (size_t)b * ns * p.part_stride + g.part_off + (size_t)(s0 + i) * pstride + 4 + 4 * (live ? c4 : 0);
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < kDepth; ++u)
                 xp[it][u] = live && u < ns ? *reinterpret_cast<const f32x4_t*>(prow + (size_t)u * p.part_stride) : f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
     }
@@ -268,11 +268,11 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
             f32x4_t a = {0.f, 0.f, 0.f, 0.f};
             if (row < rows) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < kDepth; ++u)
                     if (u < ns) a += xp[it][u] * wts[r * ns + u];
                 const int b = row / len, i = row - b * len;
                 const float* prow = p.part + (size_t)b * ns * p.part_stride + g.part_off + (size_t)(s0 + i) * pstride + 4 + 4 * c4;
-                for (int k = 4; k < ns; k += 4) {
+                for (int k = kDepth; k < ns; k += 4) {
                     f32x4_t x[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
 #pragma unroll
     for (int nb = 0; nb < NBO; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const int nbo = dh >> 4;
-    const float* arow = om + (size_t)(row0 + l16) * pstride;
+    const float* arow = om + (size_t)min(row0 + l16, rows_per_wg - 1) * pstride;      // workgroups of fewer than 16 rows: the block's other rows are not stored
     for (int k0 = 0; k0 < rv; k0 += 32) {
         const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(arow + k0 + 8 * lg);
         const f32x4_t x1 = *reinterpret_cast<const f32x4_t*>(arow + k0 + 8 * lg + 4);
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
     for (int v = 0; v < 4; ++v) {
         const int rl = row0 + 4 * lg + v;
         const int r = wg_row0 + rl;
-        if (r >= rows) continue;
+        if (rl >= rows_per_wg || r >= rows) continue;
         const int b = r / len, i = r - b * len;
         const size_t base = ((size_t)b * p.n_q_heads + g.q_head[s0 + i]) * dh;
 #pragma unroll
@@ -403,18 +403,21 @@ hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t str
     const int segs = max_segments(p, false, max_len);
     for (int i = 0; i < p.n_groups; ++i) rmax = p.g[i].v.c > rmax ? p.g[i].v.c : rmax;
     // 64 rows per workgroup for narrow rows; 16 when the launch is small (more workgroups, and few enough items
-    // per thread for the kernel to request everything at once)
+    // per thread for the kernel to request everything at once); 4 when even that leaves most of the chip idle (a few
+    // sequences: every thread then has one or two items and requests all their splits, up to 16, in one go)
     const long long rows_all = (long long)p.batch * max_len * segs * p.n_groups;
-    const int rows_per_wg = rmax <= 128 && rows_all > 64 * 64 ? 64 : 16;
+    int rows_per_wg = rmax <= 128 && rows_all > 64 * 64 ? 64 : 16;
+    if (rows_per_wg == 16 && rows_all <= 16 * 64 && (4 * (rmax >> 2) + 255) / 256 <= 2) rows_per_wg = 4;
     const size_t lds = (size_t)rmax * (2 * p.d_head + 32) + 1024 + (size_t)rows_per_wg * (rmax + 4 + 3 * p.n_splits + 2) * sizeof(float);
     dim3 grid((p.batch * max_len + rows_per_wg - 1) / rows_per_wg, segs, p.n_groups);
     const int items = (rows_per_wg * (rmax >> 2) + 255) / 256;        // phase-1b items per thread
+    const bool deep = rows_per_wg == 4 && p.n_splits > 4;             // all splits (up to 16) of an item in flight
     const int pf = items <= 2 ? 2 : items <= 6 ? 6 : 0;
     void (*kern)(AttendParams, int);
-    if (dtype == KVCAR_BF16) kern = pf == 2 ? combine_mfma_kernel<BF16, 8, 2> : pf == 6 ? combine_mfma_kernel<BF16, 8, 6> : combine_mfma_kernel<BF16, 8, 0>;
-    else kern = pf == 2 ? combine_mfma_kernel<F16, 8, 2> : pf == 6 ? combine_mfma_kernel<F16, 8, 6> : combine_mfma_kernel<F16, 8, 0>;
-    const int slot = (dtype == KVCAR_BF16 ? 0 : 3) + (pf == 2 ? 1 : pf == 6 ? 2 : 0);
-    static bool attr[6] = {};
+    if (dtype == KVCAR_BF16) kern = deep ? combine_mfma_kernel<BF16, 8, 2, 16> : pf == 2 ? combine_mfma_kernel<BF16, 8, 2> : pf == 6 ? combine_mfma_kernel<BF16, 8, 6> : combine_mfma_kernel<BF16, 8, 0>;
+    else kern = deep ? combine_mfma_kernel<F16, 8, 2, 16> : pf == 2 ? combine_mfma_kernel<F16, 8, 2> : pf == 6 ? combine_mfma_kernel<F16, 8, 6> : combine_mfma_kernel<F16, 8, 0>;
+    const int slot = (dtype == KVCAR_BF16 ? 0 : 4) + (deep ? 3 : pf == 2 ? 1 : pf == 6 ? 2 : 0);
+    static bool attr[8] = {};
     if (!attr[slot]) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (err != hipSuccess) return err;
