@@ -22,6 +22,7 @@ namespace kvcar {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
@@ -83,7 +84,8 @@ __global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParam
 
     extern __shared__ __attribute__((aligned(16))) char lds[];
     // two buffers of a K tile + a V tile (the next tile is parked at the end of the current one), then the score exchange
-    float* sbuf = reinterpret_cast<float*>(lds + 4 * kMlpTile * STRIDE);    // [wave][64 lanes][16]
+    float* sbuf = reinterpret_cast<float*>(lds + 4 * kMlpTile * STRIDE);    // partial scores [wave][4 chunks][64 lanes][4]
+    float* stot = sbuf + NW * 64 * 16;                                      // their sums [4 chunks][64 lanes][4]
 
     const GroupDesc& g = p.g[blockIdx.z];
     const int split = blockIdx.x, b = blockIdx.y;
@@ -283,16 +285,39 @@ __global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParam
                 for (int s = 0; s < 2; ++s) sT = MMma<E>::mfma(ha[s], qb[mb][s], sT);
             }
         }
-        // ---- sum the partial scores of the waves ---------------------------------------------
+        // ---- sum the partial scores of the waves, in wave order.  Every wave needs all 16 sums of its lanes; a wave
+        // adds 16 / NW of them over the waves and the waves trade the sums (each adding all of them itself costs
+        // NW * 16 additions and LDS words per lane and tile) ---------------------------------------------------------
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            *reinterpret_cast<f32x4_t*>(sbuf + ((size_t)wave * 64 + lane) * 16 + 4 * q) = f32x4_t{sT[4 * q], sT[4 * q + 1], sT[4 * q + 2], sT[4 * q + 3]};
+            *reinterpret_cast<f32x4_t*>(sbuf + ((size_t)(wave * 4 + q) * 64 + lane) * 4) = f32x4_t{sT[4 * q], sT[4 * q + 1], sT[4 * q + 2], sT[4 * q + 3]};
+        __syncthreads();
+        {
+            constexpr int EPW = 16 / NW;                       // entries per wave: 2 (eight waves) or 4 (four)
+            const int e0 = wave * EPW;                         // entries e0 .. e0 + EPW - 1 = part of chunk e0 / 4
+            float t[EPW];
+#pragma unroll
+            for (int e = 0; e < EPW; ++e) t[e] = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float* src = sbuf + ((size_t)(w * 4 + (e0 >> 2)) * 64 + lane) * 4 + (e0 & 3);
+                if constexpr (EPW == 2) {
+                    const f32x2_t x = *reinterpret_cast<const f32x2_t*>(src);
+                    t[0] += x[0]; t[1] += x[1];
+                } else {
+                    const f32x4_t x = *reinterpret_cast<const f32x4_t*>(src);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[e] += x[e];
+                }
+            }
+            float* dst = stot + ((size_t)(e0 >> 2) * 64 + lane) * 4 + (e0 & 3);
+            if constexpr (EPW == 2) *reinterpret_cast<f32x2_t*>(dst) = f32x2_t{t[0], t[1]};
+            else *reinterpret_cast<f32x4_t*>(dst) = f32x4_t{t[0], t[1], t[2], t[3]};
+        }
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            f32x4_t s4 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int w = 0; w < NW; ++w) s4 += *reinterpret_cast<const f32x4_t*>(sbuf + ((size_t)w * 64 + lane) * 16 + 4 * q);
+            const f32x4_t s4 = *reinterpret_cast<const f32x4_t*>(stot + ((size_t)q * 64 + lane) * 4);
 #pragma unroll
             for (int e = 0; e < 4; ++e) sT[4 * q + e] = s4[e];
         }
@@ -389,7 +414,7 @@ template <int C> struct MlpWaves { static constexpr int value = C >= 256 ? 8 : 4
 template <typename E, int R, int C, bool kI8>
 static hipError_t launch_mlp(const AttendParams& p, int act, hipStream_t stream) {
     constexpr int NW = MlpWaves<C>::value;
-    const size_t loop_lds = 4 * (size_t)kMlpTile * (2 * R + 16) + (size_t)NW * 64 * 16 * sizeof(float);
+    const size_t loop_lds = 4 * (size_t)kMlpTile * (2 * R + 16) + (size_t)(NW + 1) * 64 * 16 * sizeof(float);
     const size_t stage_lds = (size_t)R * (2 * C + 32);            // first-layer weights pass through LDS at start
     const size_t lds = loop_lds > stage_lds ? loop_lds : stage_lds;
     dim3 grid(p.n_splits, p.batch, p.n_groups);
