@@ -54,14 +54,13 @@ constexpr int kMlpTile = 32;      // tokens per workgroup iteration
 // 32x32 result layout: register v of lane (l32, h) holds row 8*(v/4) + 4*h + v%4 of column l32.  As an
 // operand of the next product, k-step s (16 of the 32 rows) is registers 8s..8s+7 of the lane.
 template <typename E, int ACT>
-__device__ __forceinline__ void act_pack(const f32x16_t& t, const float (&bias)[16], float slope, u32x4_t (&out)[2]) {
+__device__ __forceinline__ void act_pack(const f32x16_t& t, float slope, u32x4_t (&out)[2]) {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         unsigned w[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            w[e] = MMma<E>::pack2(fast_act<ACT>(t[8 * s + 2 * e] + bias[8 * s + 2 * e], slope),
-                                  fast_act<ACT>(t[8 * s + 2 * e + 1] + bias[8 * s + 2 * e + 1], slope));
+            w[e] = MMma<E>::pack2(fast_act<ACT>(t[8 * s + 2 * e], slope), fast_act<ACT>(t[8 * s + 2 * e + 1], slope));
         out[s] = u32x4_t{w[0], w[1], w[2], w[3]};
     }
 }
@@ -260,10 +259,11 @@ __global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParam
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) zb[ks] = *reinterpret_cast<const u32x4_t*>(tile_k + l32 * STRIDE + (2 * ks + h) * 16);
             f32x16_t hk[MB];
+            // the products start from the first-layer bias: no addition per hidden value afterwards
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) hk[mb][v] = 0.f;
+                for (int v = 0; v < 16; ++v) hk[mb][v] = bk[mb][v];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) hk[0] = MMma<E>::mfma(wk[0][ks], zb[ks], hk[0]);
 #pragma unroll
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParam
                     for (int ks = 0; ks < KS; ++ks) hk[mb + 1] = MMma<E>::mfma(wk[mb + 1][ks], zb[ks], hk[mb + 1]);
                 }
                 u32x4_t ha[2];
-                act_pack<E, ACT>(hk[mb], bk[mb], slope, ha);       // lane: token l32, hidden rows of block mb
+                act_pack<E, ACT>(hk[mb], slope, ha);       // lane: token l32, hidden rows of block mb
                 if (mb + 1 < MB) {
 #pragma unroll
                     for (int i = 0; i < KS; ++i) {
@@ -361,7 +361,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParam
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) hv[mb][v] = 0.f;
+                for (int v = 0; v < 16; ++v) hv[mb][v] = bv[mb][v];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) hv[0] = MMma<E>::mfma(za[ks], wv[0][ks], hv[0]);
 #pragma unroll
@@ -371,7 +371,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attend_mlp_mfma_kernel(AttendParam
                     for (int ks = 0; ks < KS; ++ks) hv[mb + 1] = MMma<E>::mfma(za[ks], wv[mb + 1][ks], hv[mb + 1]);
                 }
                 u32x4_t va[2];
-                act_pack<E, ACT>(hv[mb], bv[mb], slope, va);       // lane: hidden column l32 of block mb, 16 tokens
+                act_pack<E, ACT>(hv[mb], slope, va);       // lane: hidden column l32 of block mb, 16 tokens
                 if (mb + 1 < MB) {
 #pragma unroll
                     for (int i = 0; i < KS; ++i) {

@@ -163,9 +163,9 @@ __global__ __launch_bounds__(256, kSmall ? 1 : 2) void encode_mlp_mfma_kernel(En
         for (int a = 0; a < 4; ++a) bq[a] = *reinterpret_cast<const f32x4_t*>(b1s + 32 * mb + 8 * a + 4 * h);
 
         // ---- H^T[hidden blk, token] ------------------------------------------------------------
-        f32x16_t ht;
+        f32x16_t ht;               // starts from the bias: no addition per hidden value afterwards
 #pragma unroll
-        for (int v = 0; v < 16; ++v) ht[v] = 0.f;
+        for (int v = 0; v < 16; ++v) ht[v] = bq[v >> 2][v & 3];
         const char* w1row = buf + (8 * h + (l16 >> 2)) * kW1Stride + (16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
 #pragma unroll
         for (int ks = 0; ks < KX; ++ks)
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256, kSmall ? 1 : 2) void encode_mlp_mfma_kernel(En
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
                     const int v = 8 * s2 + 2 * e + q;
-                    const float x = ht[v] + bq[v >> 2][v & 3];
+                    const float x = ht[v];
                     if constexpr (GELU) a[q] = pinned(0.5f * x * (1.f + erf_rational(x * 0.70710678118654752f)));
                     else a[q] = pinned(x >= 0.f ? x : slope * x);
                 }
