@@ -8,6 +8,8 @@
 //   sum_t p_t x^_t[C]    = (sum_t p_t h_t) W[:,C] + b[C]
 // where h is the latent row itself (linear decoder) or act(z W1 + b1) (two-layer decoder).  The
 // kernels therefore attend over rows h_t and apply W once per head before and after.
+#include <algorithm>
+
 #include "kvcar_device.hpp"
 
 namespace kvcar {
@@ -45,6 +47,7 @@ __global__ __launch_bounds__(256) void encode_generic_kernel(EncodeParams p) {
         for (int i = tid; i < nt * s.hidden; i += 256) {
             const int t = i / s.hidden, c = i % s.hidden;
             float a = s.b1 ? Elem<E>::load(s.b1, c) : 0.f;
+#pragma unroll 16
             for (int k = 0; k < s.in_width; ++k) a = fmaf(xs[t * s.in_width + k], Elem<E>::load(s.w1, (size_t)k * s.hidden + c), a);
             hs[t * s.hidden + c] = apply_act(a, s.act, s.slope);
         }
@@ -57,6 +60,7 @@ __global__ __launch_bounds__(256) void encode_generic_kernel(EncodeParams p) {
     for (int i = tid; i < nt * s.r; i += 256) {
         const int t = i / s.r, c = i % s.r;
         float a = bias ? Elem<E>::load(bias, c) : 0.f;
+#pragma unroll 16
         for (int k = 0; k < in_w; ++k) a = fmaf(in[t * in_w + k], Elem<E>::load(w, (size_t)k * s.r + c), a);
         if (s.meta) { zs[t * s.r + c] = a; continue; }
         const int tok = tok0 + t;
@@ -118,11 +122,13 @@ __global__ __launch_bounds__(256) void qtilde_kernel(AttendParams p) {
     __syncthreads();
     const int c_w = g.k.c;
     const size_t base = (size_t)b * p.qt_stride + g.qt_off;
-    for (int i = threadIdx.x; i < g.slots_pad * c_w; i += 256) {
+    // the (slot, column) items are dealt over blockIdx.z: a single sequence would otherwise leave one workgroup with all of them
+    for (int i = blockIdx.z * 256 + threadIdx.x; i < g.slots_pad * c_w; i += 256 * gridDim.z) {
         const int s = i / c_w, c = i % c_w;
         float a = 0.f;
         if (s < g.n_slots) {
             const size_t wrow = (size_t)c * g.k.in_width + g.k_col[s];
+#pragma unroll 16
             for (int k = 0; k < dh; ++k) a = fmaf(Elem<E>::load(g.k.wl, wrow + k), qs[s * dh + k], a);
             a *= p.scale_log2e;
         }
@@ -132,7 +138,10 @@ __global__ __launch_bounds__(256) void qtilde_kernel(AttendParams p) {
 }
 
 hipError_t launch_qtilde(const AttendParams& p, int dtype, bool qt_f32, hipStream_t stream) {
-    dim3 grid(p.batch, p.n_groups);
+    int items = 0;
+    for (int i = 0; i < p.n_groups; ++i) items = std::max(items, p.g[i].slots_pad * p.g[i].k.c);
+    const int nz = std::max(1, std::min(16, std::min((items + 255) / 256, 512 / std::max(1, p.batch * p.n_groups))));     // a few hundred workgroups at most
+    dim3 grid(p.batch, p.n_groups, nz);
     size_t lds = (size_t)kMaxSlots * p.d_head * sizeof(float);
     if (dtype == KVCAR_F32) hipLaunchKernelGGL((qtilde_kernel<F32, true>), grid, dim3(256), lds, stream, p);
     else if (dtype == KVCAR_F16) {
@@ -169,6 +178,7 @@ __device__ void load_rows(const SideDesc& sd, float* rows, float* zrow, int b, i
     for (int i = tid; i < kGenericTile * sd.c; i += 256) {
         const int t = i / sd.c, c = i % sd.c;
         float a = sd.b1 ? Elem<E>::load(sd.b1, c) : 0.f;
+#pragma unroll 16
         for (int k = 0; k < sd.r; ++k) a = fmaf(zrow[t * sd.r + k], Elem<E>::load(sd.w1, (size_t)k * sd.c + c), a);
         rows[t * ld + c] = t < nt ? apply_act(a, sd.act, sd.slope) : 0.f;
     }
@@ -338,6 +348,7 @@ __global__ __launch_bounds__(64) void combine_kernel(AttendParams p) {
     const int col = g.v_col[s];
     for (int k = tid; k < p.d_head; k += 64) {
         float a = g.v.bl ? Elem<E>::load(g.v.bl, col + k) : 0.f;
+#pragma unroll 16
         for (int c = 0; c < cv; ++c) a = fmaf(olat[c], Elem<E>::load(g.v.wl, (size_t)c * g.v.in_width + col + k), a);
         if (p.v_cur) a = w_cached * a + w_cur * Elem<E>::load(p.v_cur, ((size_t)b * (p.n_q_heads / p.gq) + kvh) * p.d_head + k);
         Elem<E>::store(p.out, ((size_t)b * p.n_q_heads + g.q_head[s]) * p.d_head + k, a);
