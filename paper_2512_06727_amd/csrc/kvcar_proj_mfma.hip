@@ -185,6 +185,19 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
                 xp[it][u] = live && u < ns ? *reinterpret_cast<const f32x4_t*>(prow + (size_t)u * p.part_stride) : f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
     }
+    // the (m, l) pair of (row, split) number threadIdx.x joins the same round trip
+    float pm = -INFINITY, pl = 0.f;
+    {
+        const int idx = threadIdx.x;
+        const int r = idx / ns, k = idx - r * ns;
+        const int row = wg_row0 + r;
+        if (idx < rows_per_wg * ns && row < rows) {
+            const int b = row / len, i = row - b * len;
+            const float* prow = p.part + ((size_t)b * ns + k) * p.part_stride + g.part_off + (size_t)(s0 + i) * pstride;
+            pm = prow[0];
+            pl = prow[1];
+        }
+    }
     {   // phase 0
         const int cpr = dh >> 3;
         const int total = rv * cpr;
@@ -209,7 +222,11 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
     // loop over the splits would pay one memory latency per split), then one thread per row reduces.
     float* ml = wts + (size_t)rows_per_wg * ns;                         // [rows_per_wg][ns][2]
     float* ab = ml + 2 * (size_t)rows_per_wg * ns;                      // [rows_per_wg][2]: weights of bias and of the exact current row
-    for (int idx = threadIdx.x; idx < rows_per_wg * ns; idx += 256) {
+    if (threadIdx.x < rows_per_wg * ns) {
+        ml[2 * threadIdx.x] = pm;
+        ml[2 * threadIdx.x + 1] = pl;
+    }
+    for (int idx = threadIdx.x + 256; idx < rows_per_wg * ns; idx += 256) {
         const int r = idx / ns, k = idx - r * ns;
         const int row = wg_row0 + r;
         float m_k = -INFINITY, l_k = 0.f;
@@ -308,15 +325,17 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
     }
     __syncthreads();
 
-    // phase 2
-    const int row0 = wave * 16;                       // within the workgroup
-    if (row0 >= rows_per_wg || wg_row0 + row0 >= rows) return;
+    // phase 2.  Workgroups of up to 16 rows have one row block: its k-steps are dealt over the four waves, whose
+    // partial products wave 0 adds in wave order (the decoder slice's buffer takes them once every wave has read it).
+    const int nbo = dh >> 4;
+    const bool ksplit = rows_per_wg <= 16 && rv >= 128 && (size_t)rv * stride_w >= (size_t)nbo * 4 * 1024;
+    const int row0 = ksplit ? 0 : wave * 16;          // within the workgroup
+    if (!ksplit && (row0 >= rows_per_wg || wg_row0 + row0 >= rows)) return;
     f32x4_t acc[NBO];
 #pragma unroll
     for (int nb = 0; nb < NBO; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    const int nbo = dh >> 4;
     const float* arow = om + (size_t)min(row0 + l16, rows_per_wg - 1) * pstride;      // workgroups of fewer than 16 rows: the block's other rows are not stored
-    for (int k0 = 0; k0 < rv; k0 += 32) {
+    for (int k0 = ksplit ? 32 * wave : 0; k0 < rv; k0 += ksplit ? 128 : 32) {
         const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(arow + k0 + 8 * lg);
         const f32x4_t x1 = *reinterpret_cast<const f32x4_t*>(arow + k0 + 8 * lg + 4);
         const float o[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
@@ -341,6 +360,23 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
                 acc[nb] = PMma<E>::mfma(al, bw, acc[nb]);
             }
         }
+    }
+    if (ksplit) {
+        __syncthreads();                                   // every wave is done with the decoder slice
+        f32x4_t* part2 = reinterpret_cast<f32x4_t*>(wbuf); // [wave][nbo][64]
+#pragma unroll
+        for (int nb = 0; nb < NBO; ++nb)
+            if (nb < nbo) part2[(wave * nbo + nb) * 64 + lane] = acc[nb];
+        __syncthreads();
+        if (wave != 0) return;
+#pragma unroll
+        for (int nb = 0; nb < NBO; ++nb)
+            if (nb < nbo) {
+                f32x4_t a = part2[nb * 64 + lane];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) a += part2[(w * nbo + nb) * 64 + lane];
+                acc[nb] = a;
+            }
     }
     // epilogue: bias, one rounding, store; this lane holds output column 16*nb + l16 of rows 4*lg + v
     uint16_t* out = static_cast<uint16_t*>(p.out);
