@@ -24,6 +24,10 @@ CASES = {
     # tiles (the look-ahead slots are reused) and the last workgroup tile is ragged
     "c2-bf16-long": (C[2].scaled(n_layers=3, batch=3, n_cached=22000, n_steps=0), {}),
     "c2-int8-long": (C[2].scaled(n_layers=3, batch=3, n_cached=22000, n_steps=0), {"latent_format": "int8"}),
+    # 1030 sequences of 8 tokens: fewer tokens per sequence than a wave tile has rows, so a tile's rows step through
+    # several sequences (each row finds its sequence by division)
+    "c2-bf16-many-short": (C[2].scaled(n_layers=2, batch=1030, n_cached=8, n_steps=0), {}),
+    "c2-int8-many-short": (C[2].scaled(n_layers=2, batch=1030, n_cached=8, n_steps=0), {"latent_format": "int8"}),
     # int8 latent rows: the quantiser runs over whole rows in the same kernel
     "c2-int8": (C[2].scaled(n_layers=3, batch=3, n_cached=2731, n_steps=0), {"latent_format": "int8"}),
     "c4-int8-bias": (C[4].scaled(n_layers=5, batch=3, n_cached=2731, n_steps=0), {"latent_format": "int8", "with_bias": True}),

@@ -34,6 +34,10 @@ CASES = {
                      {"with_bias": True}),
     "mlp-f16-narrow": (C[3].scaled(n_layers=2, batch=3, n_cached=70, n_steps=1, dtype="f16", latent=64, hidden=128), {}),
     "linear-bias-f32": (C[0].scaled(n_layers=2, batch=2, n_cached=50, n_steps=2, reuse="odd:5"), {"with_bias": True}),
+    # one long sequence: the token range goes to 32 splits (more than the 16 the merge kernel requests in one go),
+    # for linear and for two-layer decoders
+    "c2-one-long": (C[2].scaled(n_layers=3, batch=1, n_cached=4000, n_steps=1), {}),
+    "c3-one-long": (C[3].scaled(n_layers=2, batch=1, n_cached=1100, n_steps=1), {}),
 }
 
 
