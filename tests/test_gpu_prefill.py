@@ -72,6 +72,9 @@ CASES = {
     "dh128-bf16": (C[2].scaled(n_layers=3, batch=2, n_cached=300, n_q_heads=8, n_kv_heads=2, d_head=128), 300, [(0, 300)], {}),
     "dh128-f16": (C[2].scaled(n_layers=2, batch=2, n_cached=150, n_q_heads=8, n_kv_heads=2, d_head=128, dtype="f16", reuse="none"), 150, [(0, 100), (100, 50)],
                   {"with_bias": True}),
+    # two-layer decoder with d_head 128: the decoded-row kernel has no room for its LDS output staging and the lanes
+    # store their 8-byte pieces themselves
+    "mlp-dh128": (C[3].scaled(n_layers=2, batch=2, n_cached=120, n_q_heads=8, n_kv_heads=2, d_head=128), 120, [(0, 120)], {"with_bias": True}),
     # d_head 32: decoded rows on the matrix cores, attention on the plain-ALU kernel (no instance for this head width)
     "dh32-bf16": (C[2].scaled(n_layers=2, batch=2, n_cached=100, n_q_heads=16, n_kv_heads=8, d_head=32), 100, [(0, 100)], {}),
     # a short chunk far into a long context (7 tokens at position 1000), one sequence
