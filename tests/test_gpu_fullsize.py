@@ -153,3 +153,40 @@ def test_prefill_mlp_full_size():
     """The same prompt shape through two-layer GELU decoders (the configuration named for prefill)."""
     w = synth.CONFIGS[3].scaled(n_steps=0)
     run_prefill_fullsize(w, layers=[0, 21], seqs=[3], tokens=[0, 63, 64, 1000, 4095], gain=8.0)
+
+
+def test_long_context_full_size_exact_row_and_ragged_lengths():
+    """The benchmark's workload through kvcar_decode_attention_ex, as `bench.py --variant exact | ragged` launches it:
+    the exact current-token row merged in the fused kernel, and per-sequence context lengths in [n/2, n]; the oracle
+    recomputes sampled (layer, sequence) units."""
+    w = synth.CONFIGS[4].scaled(n_steps=1)
+    reuse = synth.reuse_map(w)
+    layers, seqs = [0, 13, w.n_layers - 1], [0, 77, 255]
+    ses = Session(w, reuse=reuse)
+    need = set()
+    for n in layers:
+        need |= {n} | set(sources(reuse, n, 0)) | set(sources(reuse, n, 1))
+    ses.prefill(0, w.n_cached, chunk=max(1, (1 << 24) // (w.batch * w.d_kv)), layers=sorted(need))
+    gen = torch.Generator().manual_seed(5)
+    lens = torch.randint(w.n_cached // 2, w.n_cached + 1, (w.batch,), generator=gen, dtype=torch.int32)
+    ulp = 2.0 ** -7
+    for n in layers:
+        q = synth.queries(w, n, 0, gain=30.0)
+        kc = synth.kv_tokens(w, n, 0, 0, w.batch, w.n_cached, w.n_cached + 1)[:, 0]
+        vc = synth.kv_tokens(w, n, 1, 0, w.batch, w.n_cached, w.n_cached + 1)[:, 0]
+        dev = lambda t: t.to(ses.dev, ses.tdt).contiguous()
+        ses.ensure_workspace(w.batch, w.n_cached)
+        out_exact, out_ragged = torch.empty_like(dev(q)), torch.empty_like(dev(q))
+        ses.ctx.decode_attention_ex(n, dev(q), out_exact, w.batch, w.n_cached, ses.workspace, k_cur=dev(kc), v_cur=dev(vc))
+        ses.ctx.decode_attention_ex(n, dev(q), out_ragged, w.batch, w.n_cached, ses.workspace, seq_lens=lens.to(ses.dev))
+        assert ses.ctx.describe_plan(n, w.batch, w.n_cached).fused == 1
+        out_exact, out_ragged = (o.float().cpu().double().numpy() for o in (out_exact, out_ragged))
+        for b in seqs:
+            _, orc = oracle_unit(w, reuse, n, b, w.n_cached - 1, q[b].double().numpy())       # caches of rows 0 .. n_cached - 1
+            qb = q[b:b + 1].double().numpy()
+            want = orc.decode_attention(n, qb, w.n_cached, k_cur=kc[b:b + 1].double().numpy(), v_cur=vc[b:b + 1].double().numpy())[0]
+            err = np.abs(out_exact[b] - want)
+            assert (err <= ABS_TOL[w.dtype] + ulp * np.abs(want)).all(), ("exact", n, b, err.max())
+            want = orc.decode_attention(n, qb, w.n_cached, seq_lens=np.array([int(lens[b])]))[0]
+            err = np.abs(out_ragged[b] - want).max()
+            assert err <= ABS_TOL[w.dtype] and err <= REL_TOL[w.dtype] * np.abs(want).max(), ("ragged", n, b, err)
