@@ -13,8 +13,9 @@
 // twice the flop rate of the 16x16x32 form, and this kernel is bound by matrix + vector issue): tokens,
 // heads and hidden columns are handled in blocks of 32.  The waves of a workgroup (eight, or four for the narrow shape) share a 32-token tile and split the
 // hidden width: each keeps its share of W1K and W1V resident in registers as MFMA operands.  Scores
-// are a contraction over the whole hidden width, so the per-wave partial scores are summed through LDS;
-// every wave then runs the same online softmax and accumulates its share of O^T.
+// are a contraction over the whole hidden width, so the per-wave partial scores are summed through LDS
+// (each wave adds a share of the entries over the waves, the waves then trade the sums); every wave then
+// runs the same online softmax and accumulates its share of O^T.
 #include "kvcar_device.hpp"
 
 namespace kvcar {

@@ -134,8 +134,8 @@ __global__ __launch_bounds__(256) void qtilde_mfma_kernel(AttendParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// split merge + output epilogue.  grid = (row blocks, segment, group); a workgroup owns 16*NW rows
-// (sequence, head) of one KV head.
+// split merge + output epilogue.  grid = (row blocks, segment, group); a workgroup owns 4, 16 or 64 rows
+// (sequence, head) of one KV head (the launcher picks: few rows per workgroup when the launch is small).
 //   phase 0  the decoder-matrix slice [r, d_head] of the KV head is staged in LDS (read later with
 //            the transposing load: a lane needs 8 consecutive c of one output column)
 //   phase 1  all threads merge the split partials of the workgroup's rows into LDS:
