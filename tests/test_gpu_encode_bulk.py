@@ -107,3 +107,27 @@ def test_prompt_sized_encode_at_per_sequence_positions(fmt):
                 ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 7)
                 assert (np.abs(got - want) <= ulp * 1.0001 + 2e-6 * np.abs(want).max()).all()
                 assert np.isnan(view[bi, :st]).all() and np.isnan(view[bi, st + 2731:]).all()
+
+
+@pytest.mark.parametrize("fmt", ["dtype", "int8"])
+def test_prompt_sized_encode_with_different_maps_for_keys_and_values(fmt):
+    """Layer 1 reuses one key head and two value heads: its K and V encoders have different widths (192 -> 96 and
+    128 -> 64) and leave in a launch each; 4 x 2048 = 8192 tokens, no ragged tile."""
+    w = C[2].scaled(n_layers=2, batch=4, n_cached=2048, n_steps=0, reuse="none")
+    reuse = np.zeros((2, 2, w.n_kv_heads), dtype=bool)
+    reuse[1, 0, 0] = True
+    reuse[1, 1, 1] = reuse[1, 1, 2] = True
+    orc = build_oracle(w, reuse=reuse, latent_format=fmt)
+    for n in range(w.n_layers):
+        oracle_prefill(orc, w, n, 0, w.n_cached)
+    from paper_2512_06727_amd import binding
+    from paper_2512_06727_amd.harness import Session
+    ses = Session(w, reuse=reuse, poison=True, latent_format=fmt)
+    assert ses.ctx.describe_encode(1, w.batch, w.n_cached) == binding.ENC_MFMA_STREAM
+    ses.prefill(0, w.n_cached, chunk=w.n_cached)
+    torch.cuda.synchronize()
+    assert ses.caches[1][0].shape[-1] != ses.caches[1][1].shape[-1] or fmt == "int8"
+    if fmt == "int8":
+        assert_quantized_cache_close(w, ses, orc, w.n_cached)
+    else:
+        assert_cache_close(w, ses, orc, w.n_cached)
