@@ -85,6 +85,20 @@ CASES = {
 }
 
 
+def _mixed_maps():
+    """Different maps for keys and values: layer 1 takes K head 0 and V heads 1, 2 from layer 0; layer 2 takes K head 0
+    (a chain through layer 1) and V head 3 from layer 1."""
+    w = C[2].scaled(n_layers=3, batch=2, n_cached=210, reuse="none")
+    reuse = np.zeros((3, 2, w.n_kv_heads), dtype=bool)
+    reuse[1, 0, 0] = reuse[1, 1, 1] = reuse[1, 1, 2] = True
+    reuse[2, 0, 0] = reuse[2, 1, 3] = True
+    return w, reuse
+
+
+CASES["c2-mixed-maps"] = (_mixed_maps()[0], 210, [(0, 210)], {"reuse": _mixed_maps()[1]})
+CASES["c2-mixed-maps-int8"] = (_mixed_maps()[0], 210, [(0, 100), (100, 110)], {"reuse": _mixed_maps()[1], "latent_format": "int8"})
+
+
 @pytest.mark.parametrize("name", list(CASES))
 @pytest.mark.parametrize("gain", [1.0, 30.0])
 def test_prefill_parity(name, gain):
