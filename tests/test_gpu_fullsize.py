@@ -190,3 +190,41 @@ def test_long_context_full_size_exact_row_and_ragged_lengths():
             want = orc.decode_attention(n, qb, w.n_cached, seq_lens=np.array([int(lens[b])]))[0]
             err = np.abs(out_ragged[b] - want).max()
             assert err <= ABS_TOL[w.dtype] and err <= REL_TOL[w.dtype] * np.abs(want).max(), ("ragged", n, b, err)
+
+
+@pytest.mark.parametrize("fmt", ["dtype", "int8"])
+def test_caches_larger_than_4_gib(fmt):
+    """36 sequences with room for 2^20 tokens each: a latent cache of 9.7 GB (int8 rows: 4.8 GB of codes), so the
+    rows of the later sequences lie beyond 32-bit byte and element offsets.  600 prompt tokens through the
+    prompt-sized encoder, one decode-step append, then decode and prefill attention over all 36 sequences against
+    the oracle (which holds the same 601 rows in arrays of their own size).  Layer 1 reads one key head and one
+    value head from layer 0's caches."""
+    from tests.helpers import build_oracle
+    big = synth.CONFIGS[2].scaled(n_layers=2, batch=36, n_cached=600, n_steps=2 ** 20 - 600)
+    small = synth.CONFIGS[2].scaled(n_layers=2, batch=36, n_cached=600, n_steps=2)
+    assert big.max_seq == 2 ** 20
+    reuse = np.zeros((2, 2, big.n_kv_heads), dtype=bool)
+    reuse[1, 0, 0] = reuse[1, 1, 1] = True
+    orc = build_oracle(small, reuse=reuse, with_bias=True, latent_format=fmt)
+    ses = Session(big, reuse=reuse, with_bias=True, latent_format=fmt)
+    assert ses.ctx.cache_bytes(0, 0) > 2 ** 32
+    for t0, t1 in ((0, 600), (600, 601)):
+        for n in range(2):
+            k = synth.kv_tokens(small, n, 0, 0, 36, t0, t1)
+            v = synth.kv_tokens(small, n, 1, 0, 36, t0, t1)
+            orc.encode_append(n, k.double().numpy(), v.double().numpy(), t0)
+            ses.encode_append(n, k.to(ses.dev, ses.tdt), v.to(ses.dev, ses.tdt), t0)
+    for n in range(2):
+        q = synth.queries(small, n, 0, gain=6.0)
+        got = ses.decode_attention(n, q.to(ses.dev, ses.tdt), 601).float().cpu().double().numpy()
+        want = orc.decode_attention(n, q.double().numpy(), 601)
+        err = np.abs(got - want).max(axis=(1, 2))
+        print(f"layer {n} decode: max abs err per sequence {err.max():.3e} (last sequence {err[-1]:.3e})", flush=True)
+        assert np.isfinite(got).all() and err.max() <= ABS_TOL[big.dtype] and err.max() <= REL_TOL[big.dtype] * np.abs(want).max()
+        qp = synth.prompt_queries(small, n, 0, 36, 0, 601, gain=6.0)
+        got = ses.prefill_attention(n, qp.to(ses.dev, ses.tdt), 0).float().cpu().double().numpy()
+        want = orc.prefill_attention(n, qp.double().numpy(), 0)
+        err = np.abs(got - want)
+        ulp = 2.0 ** -7
+        print(f"layer {n} prefill: max abs err {err.max():.3e}", flush=True)
+        assert np.isfinite(got).all() and (err <= ABS_TOL[big.dtype] + ulp * np.abs(want)).all()
