@@ -228,3 +228,18 @@ def test_caches_larger_than_4_gib(fmt):
         ulp = 2.0 ** -7
         print(f"layer {n} prefill: max abs err {err.max():.3e}", flush=True)
         assert np.isfinite(got).all() and (err <= ABS_TOL[big.dtype] + ulp * np.abs(want)).all()
+
+
+@pytest.mark.parametrize("fmt", ["dtype", "int8"])
+def test_one_sequence_of_300001_tokens(fmt):
+    """A single sequence far longer than the benchmark's: its token range goes to 64 splits of about 4700 tokens
+    (37 wave tiles each, the last one ragged); every cached row and the attention output against the oracle."""
+    from tests.helpers import assert_cache_close, assert_outputs_close, assert_quantized_cache_close, run_gpu, run_oracle
+    w = synth.CONFIGS[2].scaled(n_layers=2, batch=1, n_cached=300000, n_steps=1, reuse="odd:1")
+    orc, want = run_oracle(w, gain=30.0, latent_format=fmt)
+    ses, got = run_gpu(w, gain=30.0, latent_format=fmt)
+    if fmt == "int8":
+        assert_quantized_cache_close(w, ses, orc, w.n_cached + 1)
+    else:
+        assert_cache_close(w, ses, orc, w.n_cached + 1)
+    assert_outputs_close(w, got, want, "300001 tokens")
