@@ -28,6 +28,12 @@ CASES = {
     # several sequences (each row finds its sequence by division)
     "c2-bf16-many-short": (C[2].scaled(n_layers=2, batch=1030, n_cached=8, n_steps=0), {}),
     "c2-int8-many-short": (C[2].scaled(n_layers=2, batch=1030, n_cached=8, n_steps=0), {"latent_format": "int8"}),
+    # two KV heads of width 128 (layer 2 stores one: input 128 -> latent 64), fp16 and int8 rows
+    "dh128-f16": (C[2].scaled(n_layers=3, batch=3, n_cached=2731, n_steps=0, n_q_heads=8, n_kv_heads=2, d_head=128, dtype="f16"), {"with_bias": True}),
+    "dh128-int8": (C[2].scaled(n_layers=3, batch=3, n_cached=2731, n_steps=0, n_q_heads=8, n_kv_heads=2, d_head=128), {"latent_format": "int8"}),
+    # eight KV heads of width 32: layer 2 stores seven (input 224 -> latent 112, no multiple of 32: the plain-ALU kernel takes
+    # that layer, the prompt-sized one layers 0 and 1)
+    "dh32-bf16": (C[2].scaled(n_layers=3, batch=3, n_cached=2731, n_steps=0, n_q_heads=16, n_kv_heads=8, d_head=32), {}),
     # int8 latent rows: the quantiser runs over whole rows in the same kernel
     "c2-int8": (C[2].scaled(n_layers=3, batch=3, n_cached=2731, n_steps=0), {"latent_format": "int8"}),
     "c4-int8-bias": (C[4].scaled(n_layers=5, batch=3, n_cached=2731, n_steps=0), {"latent_format": "int8", "with_bias": True}),
