@@ -17,7 +17,8 @@
  * and, for the prompt, kvcar_prefill_attention (causal attention of a chunk over the same caches).
  *
  * Conventions
- *   - Pure C.  Every function returns a kvcar_status (0 = OK, negative = error); nothing throws.
+ *   - Pure C.  Every function returns a kvcar_status (0 = OK, negative = error); nothing throws
+ *     (a failed host allocation inside the library comes back as KVCAR_ERR_NOMEM).
  *   - "dev" pointers are device (HBM) addresses owned by the caller (e.g. PyTorch tensors); they
  *     must be 16-byte aligned and stay valid until the work enqueued on `stream` has finished.
  *     "host" pointers are read during the call and not retained.
@@ -70,7 +71,8 @@ typedef enum {
     KVCAR_ERR_UNSUPPORTED = -5,  /* no kernel for this dtype / width combination           */
     KVCAR_ERR_STATE = -6,        /* autoencoder or cache of a needed layer not set / bound */
     KVCAR_ERR_HIP = -7,          /* a HIP runtime call failed                               */
-    KVCAR_ERR_WORKSPACE = -8     /* workspace too small                                     */
+    KVCAR_ERR_WORKSPACE = -8,    /* workspace too small                                     */
+    KVCAR_ERR_NOMEM = -9         /* a host allocation inside the library failed             */
 } kvcar_status;
 
 typedef enum { KVCAR_F32 = 0, KVCAR_F16 = 1, KVCAR_BF16 = 2 } kvcar_dtype;

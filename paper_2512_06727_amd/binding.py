@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_PKG, "libkvcar.so")
 
 OK = 0
 ENC_NONE, ENC_PLAIN, ENC_MFMA, ENC_MFMA_TWO_LAYER, ENC_MFMA_STREAM = range(5)
-ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_REUSE, ERR_UNSUPPORTED, ERR_STATE, ERR_HIP, ERR_WORKSPACE = range(-1, -9, -1)
+ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_REUSE, ERR_UNSUPPORTED, ERR_STATE, ERR_HIP, ERR_WORKSPACE, ERR_NOMEM = range(-1, -10, -1)
 F32, F16, BF16 = 0, 1, 2
 ACT_NONE, ACT_LEAKY_RELU, ACT_GELU = 0, 1, 2
 K, V = 0, 1

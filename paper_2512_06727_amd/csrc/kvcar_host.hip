@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <memory>
 #include <new>
 #include <string>
 #include <utility>
@@ -275,7 +276,7 @@ int check_layer(const kvcar_ctx* ctx, int layer) {
 
 extern "C" {
 
-int kvcar_create(const kvcar_config* cfg, kvcar_ctx** out) {
+int kvcar_create(const kvcar_config* cfg, kvcar_ctx** out) try {
     if (!cfg || !out) return KVCAR_ERR_ARG;
     *out = nullptr;
     if (cfg->n_layers <= 0 || cfg->n_q_heads <= 0 || cfg->n_kv_heads <= 0 || cfg->d_head <= 0 || cfg->max_batch <= 0 ||
@@ -284,8 +285,8 @@ int kvcar_create(const kvcar_config* cfg, kvcar_ctx** out) {
     if (cfg->n_kv_heads > kMaxKvHeads) return KVCAR_ERR_UNSUPPORTED;
     if (cfg->dtype != KVCAR_F32 && cfg->dtype != KVCAR_F16 && cfg->dtype != KVCAR_BF16) return KVCAR_ERR_UNSUPPORTED;
     if (cfg->latent_format != KVCAR_LATENT_DTYPE && cfg->latent_format != KVCAR_LATENT_INT8) return KVCAR_ERR_UNSUPPORTED;
-    kvcar_ctx* ctx = new (std::nothrow) kvcar_ctx();
-    if (!ctx) return KVCAR_ERR_ARG;
+    std::unique_ptr<kvcar_ctx> ctx(new (std::nothrow) kvcar_ctx());
+    if (!ctx) return KVCAR_ERR_NOMEM;
     ctx->cfg = *cfg;
     ctx->scale = cfg->softmax_scale != 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->d_head);
     ctx->reuse.assign((size_t)cfg->n_layers * 2 * cfg->n_kv_heads, 0);
@@ -298,18 +299,18 @@ int kvcar_create(const kvcar_config* cfg, kvcar_ctx** out) {
         ctx->n_cu = prop.multiProcessorCount;
     else
         (void)hipGetLastError();   // no device here: host-side calls still work
-    *out = ctx;
+    *out = ctx.release();
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_destroy(kvcar_ctx* ctx) {
+int kvcar_destroy(kvcar_ctx* ctx) try {
     if (ctx)
         for (auto& e : ctx->ev_pool) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
     delete ctx;
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_set_reuse_map(kvcar_ctx* ctx, int layer, const uint8_t* k_reuse, const uint8_t* v_reuse) {
+int kvcar_set_reuse_map(kvcar_ctx* ctx, int layer, const uint8_t* k_reuse, const uint8_t* v_reuse) try {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     if (!k_reuse || !v_reuse) return fail(ctx, KVCAR_ERR_ARG, "null reuse mask");
@@ -329,18 +330,18 @@ int kvcar_set_reuse_map(kvcar_ctx* ctx, int layer, const uint8_t* k_reuse, const
         ctx->ae_at(layer, KVCAR_V) = AEState();
     }
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_resolve_source(const kvcar_ctx* ctx, int layer, int which, int kv_head, int* src_layer) {
+int kvcar_resolve_source(const kvcar_ctx* ctx, int layer, int which, int kv_head, int* src_layer) try {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     if (!src_layer || (which != KVCAR_K && which != KVCAR_V) || kv_head < 0 || kv_head >= ctx->cfg.n_kv_heads)
         return fail(ctx, KVCAR_ERR_ARG, "bad argument to kvcar_resolve_source");
     *src_layer = resolve(ctx, layer, which, kv_head);
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_set_autoencoder(kvcar_ctx* ctx, int layer, int which, const kvcar_ae_desc* d) {
+int kvcar_set_autoencoder(kvcar_ctx* ctx, int layer, int which, const kvcar_ae_desc* d) try {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     if (!d || (which != KVCAR_K && which != KVCAR_V)) return fail(ctx, KVCAR_ERR_ARG, "bad argument to kvcar_set_autoencoder");
@@ -387,9 +388,9 @@ int kvcar_set_autoencoder(kvcar_ctx* ctx, int layer, int which, const kvcar_ae_d
     }
     ctx->ae_at(layer, which) = st;
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_cache_bytes(const kvcar_ctx* ctx, int layer, int which, size_t* bytes) {
+int kvcar_cache_bytes(const kvcar_ctx* ctx, int layer, int which, size_t* bytes) try {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     if (!bytes || (which != KVCAR_K && which != KVCAR_V)) return fail(ctx, KVCAR_ERR_ARG, "bad argument to kvcar_cache_bytes");
@@ -397,9 +398,9 @@ int kvcar_cache_bytes(const kvcar_ctx* ctx, int layer, int which, size_t* bytes)
     if (!a.set) return fail(ctx, KVCAR_ERR_STATE, "autoencoder of layer %d not set", layer);
     *bytes = ctx->cache_need(a.d.latent_width);
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_bind_cache(kvcar_ctx* ctx, int layer, int which, void* dev, size_t bytes) {
+int kvcar_bind_cache(kvcar_ctx* ctx, int layer, int which, void* dev, size_t bytes) try {
     size_t need = 0;
     int rc = kvcar_cache_bytes(ctx, layer, which, &need);
     if (rc) return rc;
@@ -409,17 +410,17 @@ int kvcar_bind_cache(kvcar_ctx* ctx, int layer, int which, void* dev, size_t byt
     ctx->cache[(size_t)layer * 2 + which] = dev;
     ctx->cache_bytes[(size_t)layer * 2 + which] = bytes;
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_set_tuning(kvcar_ctx* ctx, const kvcar_tuning* t) {
+int kvcar_set_tuning(kvcar_ctx* ctx, const kvcar_tuning* t) try {
     if (!ctx || !t) return KVCAR_ERR_ARG;
     if (t->n_splits < 0 || t->tile_order < 0 || t->tile_order > 2 || (t->wg_waves != 0 && t->wg_waves != 4 && t->wg_waves != 8))
         return fail(ctx, KVCAR_ERR_ARG, "bad tuning value");
     ctx->tun = *t;
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_ctx, size_t* bytes) {
+int kvcar_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_ctx, size_t* bytes) try {
     if (!ctx || !bytes) return KVCAR_ERR_ARG;
     if (batch < 1 || batch > ctx->cfg.max_batch || n_ctx < 1 || n_ctx > ctx->cfg.max_seq)
         return fail(ctx, KVCAR_ERR_CAPACITY, "batch %d / n_ctx %d outside [1,%d] / [1,%d]", batch, n_ctx, ctx->cfg.max_batch, ctx->cfg.max_seq);
@@ -432,7 +433,7 @@ int kvcar_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_ctx, size_t* by
     }
     *bytes = mx;
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
 }  // extern "C"
 
@@ -660,41 +661,41 @@ int prefill_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch,
 
 extern "C" {
 
-int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, int pos0, int t_new, void* stream) {
+int kvcar_encode_append(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, int pos0, int t_new, void* stream) try {
     return encode_impl(ctx, layer, k_new, v_new, batch, pos0, nullptr, t_new, stream);
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
 int kvcar_encode_append_at(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, const int32_t* positions, int t_new,
-                           void* stream) {
+                           void* stream) try {
     if (!ctx) return KVCAR_ERR_ARG;
     if (!positions || (reinterpret_cast<uintptr_t>(positions) & 3u)) return fail(ctx, KVCAR_ERR_ARG, "positions null or misaligned");
     return encode_impl(ctx, layer, k_new, v_new, batch, 0, positions, t_new, stream);
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
 int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, void* workspace,
-                           size_t workspace_bytes, void* stream) {
+                           size_t workspace_bytes, void* stream) try {
     return decode_impl(ctx, layer, q, out, batch, n_ctx, nullptr, workspace, workspace_bytes, stream);
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
 int kvcar_decode_attention_ex(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, const kvcar_step_ext* ext,
-                              void* workspace, size_t workspace_bytes, void* stream) {
+                              void* workspace, size_t workspace_bytes, void* stream) try {
     return decode_impl(ctx, layer, q, out, batch, n_ctx, ext, workspace, workspace_bytes, stream);
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_prefill_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_rows, size_t* bytes) {
+int kvcar_prefill_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_rows, size_t* bytes) try {
     if (!ctx || !bytes) return KVCAR_ERR_ARG;
     if (batch < 1 || batch > ctx->cfg.max_batch || n_rows < 1 || n_rows > ctx->cfg.max_seq)
         return fail(ctx, KVCAR_ERR_CAPACITY, "batch %d / n_rows %d outside [1,%d] / [1,%d]", batch, n_rows, ctx->cfg.max_batch, ctx->cfg.max_seq);
     *bytes = prefill_need(ctx, batch, n_rows);
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
 int kvcar_prefill_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int pos0, int t_new, void* workspace,
-                            size_t workspace_bytes, void* stream) {
+                            size_t workspace_bytes, void* stream) try {
     return prefill_impl(ctx, layer, q, out, batch, pos0, t_new, workspace, workspace_bytes, stream);
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, kvcar_plan_info* out) {
+int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, kvcar_plan_info* out) try {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     if (!out) return fail(ctx, KVCAR_ERR_ARG, "null output");
@@ -714,9 +715,9 @@ int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, k
     out->latent_bytes = lat * ctx->row_elem_bytes() * batch * n_ctx;
     if (ctx->int8()) out->latent_bytes += plan.groups.size() * 2 * sizeof(RowMeta) * (size_t)batch * n_ctx;
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_describe_encode(const kvcar_ctx* ctx, int layer, int batch, int t_new, int* kernel) {
+int kvcar_describe_encode(const kvcar_ctx* ctx, int layer, int batch, int t_new, int* kernel) try {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     if (!kernel) return fail(ctx, KVCAR_ERR_ARG, "null output");
@@ -729,15 +730,15 @@ int kvcar_describe_encode(const kvcar_ctx* ctx, int layer, int batch, int t_new,
     if (rc) return rc;
     *kernel = any ? encode_kernel_kind(ctx, p) : KVCAR_ENC_NONE;
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_profile_enable(kvcar_ctx* ctx, int enable) {
+int kvcar_profile_enable(kvcar_ctx* ctx, int enable) try {
     if (!ctx) return KVCAR_ERR_ARG;
     ctx->profiling = enable != 0;
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_profile_read(kvcar_ctx* ctx, double* attend_ms, long* n_launches) {
+int kvcar_profile_read(kvcar_ctx* ctx, double* attend_ms, long* n_launches) try {
     if (!ctx || !attend_ms || !n_launches) return KVCAR_ERR_ARG;
     double total = 0.0;
     for (size_t i = 0; i < ctx->ev_used; ++i) {
@@ -751,7 +752,7 @@ int kvcar_profile_read(kvcar_ctx* ctx, double* attend_ms, long* n_launches) {
     *n_launches = (long)ctx->ev_used;
     ctx->ev_used = 0;
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
 static int device_cu_count() {
     int dev = 0, n_cu = 0;
@@ -762,14 +763,14 @@ static int device_cu_count() {
     return n_cu;
 }
 
-int kvcar_head_l1_workspace_bytes(size_t n_tokens, int n_kv_heads, size_t* bytes) {
+int kvcar_head_l1_workspace_bytes(size_t n_tokens, int n_kv_heads, size_t* bytes) try {
     if (!bytes || n_tokens == 0 || n_kv_heads < 1) return KVCAR_ERR_ARG;
     *bytes = (size_t)kvcar::head_l1_workgroups(n_tokens, device_cu_count()) * n_kv_heads * sizeof(float);
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
 int kvcar_head_l1_distance(const void* x_prev, const void* x_cur, int dtype, size_t n_tokens, int n_kv_heads, int d_head, int accumulate,
-                           float* dist, void* workspace, size_t workspace_bytes, void* stream) {
+                           float* dist, void* workspace, size_t workspace_bytes, void* stream) try {
     if (!x_prev || !x_cur || !dist || !workspace || n_tokens == 0 || n_kv_heads < 1 || d_head < 1) return KVCAR_ERR_ARG;
     if (!aligned16(x_prev) || !aligned16(x_cur) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(dist) & 3u)) return KVCAR_ERR_ARG;
     if (dtype != KVCAR_F32 && dtype != KVCAR_F16 && dtype != KVCAR_BF16) return KVCAR_ERR_UNSUPPORTED;
@@ -781,9 +782,9 @@ int kvcar_head_l1_distance(const void* x_prev, const void* x_cur, int dtype, siz
     hipError_t e = kvcar::launch_head_l1(x_prev, x_cur, dtype, n_tokens, n_kv_heads, d_head, accumulate, dist, static_cast<float*>(workspace), n_wg,
                                          static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KVCAR_OK : KVCAR_ERR_HIP;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
-int kvcar_probe_read_bandwidth(const void* dev_buf, size_t bytes, int repeats, void* stream, double* gb_per_s) {
+int kvcar_probe_read_bandwidth(const void* dev_buf, size_t bytes, int repeats, void* stream, double* gb_per_s) try {
     if (!dev_buf || !gb_per_s || bytes < 16 || bytes % 16 || repeats < 1 || (reinterpret_cast<uintptr_t>(dev_buf) & 15)) return KVCAR_ERR_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int dev = 0, n_cu = 0;
@@ -813,7 +814,7 @@ int kvcar_probe_read_bandwidth(const void* dev_buf, size_t bytes, int repeats, v
     if (e != hipSuccess || best <= 0.0) return KVCAR_ERR_HIP;
     *gb_per_s = best;
     return KVCAR_OK;
-}
+} catch (...) { return KVCAR_ERR_NOMEM; }
 
 const char* kvcar_status_string(int s) {
     switch (s) {
@@ -826,6 +827,7 @@ const char* kvcar_status_string(int s) {
         case KVCAR_ERR_STATE: return "KVCAR_ERR_STATE";
         case KVCAR_ERR_HIP: return "KVCAR_ERR_HIP";
         case KVCAR_ERR_WORKSPACE: return "KVCAR_ERR_WORKSPACE";
+        case KVCAR_ERR_NOMEM: return "KVCAR_ERR_NOMEM";
         default: return "KVCAR_ERR_UNKNOWN";
     }
 }

@@ -53,6 +53,7 @@ def test_create_validation():
     assert B.lib().kvcar_create(C.byref(bad), C.byref(h)) == B.ERR_UNSUPPORTED
     assert B.lib().kvcar_create(None, C.byref(h)) == B.ERR_ARG
     assert B.lib().kvcar_status_string(B.ERR_REUSE) == b"KVCAR_ERR_REUSE"
+    assert B.lib().kvcar_status_string(B.ERR_NOMEM) == b"KVCAR_ERR_NOMEM" and B.ERR_NOMEM == -9
 
 
 def test_reuse_resolution_matches_hand_table():
