@@ -662,6 +662,13 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         const int nseg = g->n_vseg;
 #pragma unroll
         for (int sg = 0; sg < kMaxSeg; ++sg) { seg_lo[sg] = g->vseg_lo[sg]; seg_hi[sg] = g->vseg_hi[sg]; seg_col[sg] = g->vseg_col[sg]; }
+        // query heads of this lane's four result rows in every head block: read now (the group tables sit in the
+        // kernel-argument segment, a memory round trip away) rather than inside the loop over the KV heads
+        int heads_of[NHB][4];
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) heads_of[nb][v] = nb * 16 + 4 * lg + v < g->n_slots ? (int)g->q_head[nb * 16 + 4 * lg + v] : 0;
         u32x4_t wreg[kMaxSeg][kCpt];
 #pragma unroll
         for (int sg = 0; sg < kMaxSeg; ++sg)
@@ -731,7 +738,11 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             for (int nb = seg_lo[sg] >> 4; nb <= (seg_hi[sg] - 1) >> 4; ++nb) {
                 int heads4[4];                          // query heads of this lane's four result rows
 #pragma unroll
-                for (int v = 0; v < 4; ++v) heads4[v] = nb * 16 + 4 * lg + v < g->n_slots ? (int)g->q_head[nb * 16 + 4 * lg + v] : 0;
+                for (int v = 0; v < 4; ++v) {
+                    heads4[v] = heads_of[0][v];
+#pragma unroll
+                    for (int n2 = 1; n2 < NHB; ++n2) heads4[v] = nb == n2 ? heads_of[n2][v] : heads4[v];
+                }
                 for (int nbo = wave; nbo < (dh >> 4); nbo += NW) {
                     f32x4_t o = {0.f, 0.f, 0.f, 0.f};
                     for (int k0 = 0; k0 < rv; k0 += 32) {
