@@ -289,3 +289,45 @@ def test_encoder_kernel_choice():
     for which in (B.K, B.V):
         assert lib.kvcar_set_autoencoder(f32._h, 0, which, C.byref(desc(256, 0, 128))) == B.OK
     assert f32.describe_encode(0, 16, 4096) == B.ENC_PLAIN
+
+
+def test_plans_for_the_shape_sweep():
+    """Host planning over the 64 shapes of the GPU shape sweep (fake device pointers, nothing launched): every shape
+    is accepted, the plan's figures are consistent, and matrix-core kernels are only picked for 16-bit dtypes."""
+    from paper_2512_06727_amd import synth
+    from tests.test_gpu_shape_sweep import CASES
+    act = {"none": B.ACT_NONE, "gelu": B.ACT_GELU, "leaky_relu": B.ACT_LEAKY_RELU}
+    n_mfma = 0
+    for w, kw in CASES:
+        ctx = B.Context(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, w.batch, w.max_seq, w.dtype, latent_format=kw["latent_format"])
+        reuse = synth.reuse_map(w)
+        for layer in range(w.n_layers):
+            ctx.set_reuse_map(layer, reuse[layer, 0], reuse[layer, 1])
+        for layer in range(w.n_layers):
+            for which in (B.K, B.V):
+                stored = int((~reuse[layer, which]).sum())
+                heads = stored if w.policy == "P1" else w.n_kv_heads
+                lat = w.latent * stored // w.n_kv_heads if w.policy == "P1" else w.latent
+                d = desc(heads * w.d_head, w.hidden if heads else 0, lat if heads else 0, act[w.act] if heads else B.ACT_NONE, ptrs=heads > 0)
+                if heads and w.hidden:
+                    d.enc_b1 = d.dec_b1 = FAKE
+                assert B.lib().kvcar_set_autoencoder(ctx._h, layer, which, C.byref(d)) == B.OK, (w, layer, which)
+                need = ctx.cache_bytes(layer, which)
+                assert (need > 0) == (heads > 0)
+                if need:
+                    assert B.lib().kvcar_bind_cache(ctx._h, layer, which, FAKE, need) == B.OK
+        n_ctx = w.n_cached + 1
+        # kvcar_workspace_bytes is the largest need of any layer
+        assert ctx.workspace_bytes(w.batch, n_ctx) == max(ctx.describe_plan(layer, w.batch, n_ctx).workspace_bytes for layer in range(w.n_layers))
+        for layer in range(w.n_layers):
+            p = ctx.describe_plan(layer, w.batch, n_ctx)
+            assert 1 <= p.n_groups <= w.n_kv_heads and 1 <= p.n_splits <= 256 and p.n_launches >= 1
+            assert p.workspace_bytes > 0
+            assert not (p.fused and p.n_splits != 1)
+            assert not (p.uses_mfma and w.dtype == "f32")
+            n_mfma += p.uses_mfma
+            kind = ctx.describe_encode(layer, w.batch, 1)
+            stores = bool((~reuse[layer]).any()) if w.policy == "P1" else True
+            assert (kind == B.ENC_NONE) == (not stores)
+            assert not (w.dtype == "f32" and kind not in (B.ENC_NONE, B.ENC_PLAIN))
+    assert n_mfma >= 40          # the sweep does reach the matrix-core kernels
