@@ -92,3 +92,42 @@ def test_prefill_graph_replays_match_eager(hidden):
         torch.cuda.synchronize()
         for n in range(w.n_layers):
             assert torch.equal(outs[n], want[n]), f"replay {replay}, layer {n}"
+
+
+def test_two_contexts_on_two_streams_at_once():
+    """Two library contexts (own caches, own workspaces) driven from two streams of default priority at the same
+    time: the library keeps no device state of its own, so each gives the bytes it gives when run alone."""
+    wa = synth.CONFIGS[4].scaled(n_layers=3, batch=8, n_cached=3000, n_steps=1)
+    wb = synth.CONFIGS[2].scaled(n_layers=3, batch=6, n_cached=2500, n_steps=1, seed=5)
+    sessions = [Session(wa), Session(wb, latent_format="int8")]
+    work = []
+    for ses in sessions:
+        w = ses.w
+        ses.prefill(0, w.n_cached, chunk=512)
+        ses.ensure_workspace(w.batch, w.max_seq)
+        qs = [synth.queries(w, n, 0, device=ses.dev, gain=10.0).to(ses.tdt) for n in range(w.n_layers)]
+        work.append((qs, [torch.empty_like(q) for q in qs]))
+
+    def run(i):
+        ses, (qs, outs) = sessions[i], work[i]
+        for rep in range(5):
+            for n in range(ses.w.n_layers):
+                ses.ctx.decode_attention(n, qs[n], outs[n], ses.w.batch, ses.w.n_cached, ses.workspace)
+
+    want = []
+    for i in range(2):                            # each alone, on the current stream
+        run(i)
+        torch.cuda.synchronize()
+        want.append([o.clone() for o in work[i][1]])
+        for o in work[i][1]:
+            o.zero_()
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):                          # interleaved submissions, both streams busy
+        for i in range(2):
+            with torch.cuda.stream(streams[i]):
+                run(i)
+    torch.cuda.synchronize()
+    for i in range(2):
+        for got, ref in zip(work[i][1], want[i]):
+            assert torch.equal(got.view(torch.int16), ref.view(torch.int16))
