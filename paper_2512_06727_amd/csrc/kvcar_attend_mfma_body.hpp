@@ -578,30 +578,52 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         l_run[nb] += __shfl_xor(l_run[nb], 16);
         l_run[nb] += __shfl_xor(l_run[nb], 32);
     }
-    __syncthreads();                                   // every wave is done with its staging region
-    float* red = reinterpret_cast<float*>(lds_raw);    // [wave][NHB*16] m, then l
-    float* accs = reinterpret_cast<float*>(lds_raw) + 2 * NW * NHB * 16;   // [wave][NHB][MB][64][4]
+    // Fused kernel: a wave parks its accumulators (unscaled) and its running (m, l) in its own staging region as soon as
+    // it leaves the loop, without waiting for the others: one barrier instead of three before the sums can be merged.
+    constexpr size_t kAccBytes = (size_t)NHB * MB * 1024;          // a wave's accumulators: [NHB][MB][64] x 16 bytes
+    static_assert(!kFused || kAccBytes + NHB * 128 <= G::kWaveLds, "accumulators and (m, l) must fit the wave's own staging region");
+    if constexpr (!kFused) __syncthreads();            // every wave is done with its staging region
+    // m of (wave w, head slot nb*16 + l): red[w * red_stride + nb*16 + l]; l of the same: red[red_l + w * red_stride + nb*16 + l]
+    float* red = kFused ? reinterpret_cast<float*>(lds_raw + kAccBytes) : reinterpret_cast<float*>(lds_raw);
+    const int red_stride = kFused ? (int)(wave_lds >> 2) : NHB * 16;
+    const int red_l = kFused ? NHB * 16 : NW * NHB * 16;
+    float* accs = reinterpret_cast<float*>(lds_raw) + 2 * NW * NHB * 16;   // not fused: [wave][NHB][MB][64][4]
     if (lane < 16) {
 #pragma unroll
         for (int nb = 0; nb < NHB; ++nb) {
-            red[wave * NHB * 16 + nb * 16 + lane] = m_run[nb];
-            red[NW * NHB * 16 + wave * NHB * 16 + nb * 16 + lane] = l_run[nb];
+            red[wave * red_stride + nb * 16 + lane] = m_run[nb];
+            red[red_l + wave * red_stride + nb * 16 + lane] = l_run[nb];
         }
+    }
+    if constexpr (kFused) {
+        float* mine = reinterpret_cast<float*>(lds_raw + wave * wave_lds);     // [NHB][MB][64][4]
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) *reinterpret_cast<f32x4_t*>(mine + ((size_t)(nb * MB + mb) * 64 + lane) * 4) = acc[nb][mb];
     }
     __syncthreads();
     float m_all[NHB], l_all[NHB], f_own[NHB];
+    float f_wave[kFused ? NW : 1][NHB];                // fused: every wave's factor 2^(m_w - M) for this lane's head slot
 #pragma unroll
     for (int nb = 0; nb < NHB; ++nb) {
         float M = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) M = fmaxf(M, red[w * NHB * 16 + nb * 16 + l16]);
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, red[w * red_stride + nb * 16 + l16]);
         float L = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
-            const float mw = red[w * NHB * 16 + nb * 16 + l16];
-            L += mw == -INFINITY ? 0.f : red[NW * NHB * 16 + w * NHB * 16 + nb * 16 + l16] * exp2f(mw - M);
+            const float mw = red[w * red_stride + nb * 16 + l16];
+            L += mw == -INFINITY ? 0.f : red[red_l + w * red_stride + nb * 16 + l16] * exp2f(mw - M);
         }
         f_own[nb] = m_run[nb] == -INFINITY ? 0.f : exp2f(m_run[nb] - M);
+        if constexpr (kFused) {
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float mw = red[w * red_stride + nb * 16 + l16];
+                f_wave[w][nb] = mw == -INFINITY ? 0.f : exp2f(mw - M);
+            }
+        }
         m_all[nb] = M;
         l_all[nb] = L;
     }
@@ -653,7 +675,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         constexpr int kCpt = 1024 / (64 * NW);                // 16-byte chunks per thread and decoder slice
         const int dh = p->d_head;
         const int ostride = rv + 4;
-        float* olat = red + 2 * NW * NHB * 16;
+        float* olat = reinterpret_cast<float*>(lds_raw) + 2 * NW * NHB * 16;
         char* wst = reinterpret_cast<char*>(olat + (size_t)NHB * 16 * ostride);
         const int stride_w = 2 * dh + 32;
         const int cpr = dh >> 3;
@@ -683,35 +705,35 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         // Merge of the waves' normalised latent sums: every wave parks its scaled accumulators, then each thread
         // adds the waves' copies of its share in wave order (a fixed order: deterministic) and writes the result
         // as olat[slot][rv + 4], which overlays the parked copies once every thread has read its inputs.
+        constexpr int kItems = NHB * MB * 64;                  // float4 items of the merged sums
+        constexpr int kPerThread = (kItems + 64 * NW - 1) / (64 * NW);
+        f32x4_t merged[kPerThread];
 #pragma unroll
-        for (int nb = 0; nb < NHB; ++nb) {
-            const float sc = f_own[nb] * inv_l[nb];
+        for (int i = 0; i < kPerThread; ++i) {
+            // item = (head block nb, column block mb, lane): its lane is this thread's lane, so the factors above apply
+            const int item = i * (64 * NW) + threadIdx.x;
+            f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+            if (item < kItems) {
+                const int nb_i = (item >> 6) / MB;
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                *reinterpret_cast<f32x4_t*>(accs + ((size_t)((wave * NHB + nb) * MB + mb) * 64 + lane) * 4) = acc[nb][mb] * sc;
+                for (int w = 0; w < NW; ++w) {
+                    float sc = f_wave[w][0] * inv_l[0];
+#pragma unroll
+                    for (int n2 = 1; n2 < NHB; ++n2) sc = nb_i == n2 ? f_wave[w][n2] * inv_l[n2] : sc;
+                    sum += *reinterpret_cast<const f32x4_t*>(lds_raw + w * wave_lds + (size_t)item * 16) * sc;
+                }
+            }
+            merged[i] = sum;
         }
         __syncthreads();
-        if (exact_row && wave == 0 && lane < 16) {             // the (m, l) exchange area is free now: per-slot weights for the store
+        red = reinterpret_cast<float*>(lds_raw);               // from here on: per-slot weights, merged sums, decoder slices
+        if (exact_row && wave == 0 && lane < 16) {             // per-slot weights for the store
 #pragma unroll
             for (int nb = 0; nb < NHB; ++nb) {
                 red[nb * 16 + lane] = w_bias[nb];
                 red[NHB * 16 + nb * 16 + lane] = w_cur[nb];
             }
         }
-        constexpr int kItems = NHB * MB * 64;                  // float4 items of the merged sums
-        constexpr int kPerThread = (kItems + 64 * NW - 1) / (64 * NW);
-        f32x4_t merged[kPerThread];
-#pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int item = i * (64 * NW) + threadIdx.x;
-            f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
-            if (item < kItems) {
-#pragma unroll
-                for (int w = 0; w < NW; ++w) sum += *reinterpret_cast<const f32x4_t*>(accs + ((size_t)w * kItems + item) * 4);
-            }
-            merged[i] = sum;
-        }
-        __syncthreads();
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {
             const int item = i * (64 * NW) + threadIdx.x;
