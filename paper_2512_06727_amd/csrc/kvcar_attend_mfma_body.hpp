@@ -691,16 +691,24 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         for (int nb = 0; nb < NHB; ++nb)
 #pragma unroll
             for (int v = 0; v < 4; ++v) heads_of[nb][v] = nb * 16 + 4 * lg + v < g->n_slots ? (int)g->q_head[nb * 16 + 4 * lg + v] : 0;
+        // chunk f of a slice is (row f / cpr, 16-byte piece f % cpr): the same for every KV head, so worked out once, and
+        // with a multiplication ((f * inv) >> 16 is exact for f < 8192 and cpr <= 16) instead of a division per chunk
+        const unsigned inv_cpr = (65536u + cpr - 1) / cpr;
+        int wrow[kCpt], wch[kCpt];
+#pragma unroll
+        for (int i = 0; i < kCpt; ++i) {
+            const unsigned f = i * (64 * NW) + threadIdx.x;
+            wrow[i] = (int)((f * inv_cpr) >> 16);
+            wch[i] = (int)f - wrow[i] * cpr;
+        }
         u32x4_t wreg[kMaxSeg][kCpt];
 #pragma unroll
         for (int sg = 0; sg < kMaxSeg; ++sg)
 #pragma unroll
             for (int i = 0; i < kCpt; ++i) {
                 const int f = i * (64 * NW) + threadIdx.x;
-                if (sg < nseg && f < rv * cpr) {
-                    const int row = f / cpr, ch = f - row * cpr;
-                    wreg[sg][i] = *reinterpret_cast<const u32x4_t*>(wlv + ((size_t)row * g->v.in_width + seg_col[sg]) * 2 + ch * 16);
-                }
+                if (sg < nseg && f < rv * cpr)
+                    wreg[sg][i] = *reinterpret_cast<const u32x4_t*>(wlv + ((size_t)wrow[i] * g->v.in_width + seg_col[sg]) * 2 + wch[i] * 16);
             }
         // Merge of the waves' normalised latent sums: every wave parks its scaled accumulators, then each thread
         // adds the waves' copies of its share in wave order (a fixed order: deterministic) and writes the result
@@ -750,10 +758,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
 #pragma unroll
             for (int i = 0; i < kCpt; ++i) {
                 const int f = i * (64 * NW) + threadIdx.x;
-                if (f < rv * cpr) {
-                    const int row = f / cpr, ch = f - row * cpr;
-                    *reinterpret_cast<u32x4_t*>(wst + row * stride_w + ch * 16) = wreg[sg][i];
-                }
+                if (f < rv * cpr) *reinterpret_cast<u32x4_t*>(wst + wrow[i] * stride_w + wch[i] * 16) = wreg[sg][i];
             }
             __syncthreads();
             const int col = seg_col[sg];

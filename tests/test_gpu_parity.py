@@ -114,7 +114,15 @@ def test_two_layer_encoder_on_a_few_tokens(batch, t_new, variant):
         assert_cache_close(w, ses, orc, t_new)
 
 
-@pytest.mark.parametrize("name", ["c2-small", "c4-small", "c4-small-p2"])
+# head widths 32, 96 and 128 in the fused kernel (its epilogue cuts the V decoder's slices into 16-byte pieces per row:
+# 4, 12 and 16 pieces), with a reused head so that a group holds more than one KV head
+CASES["dh32-fused"] = (C[2].scaled(n_layers=3, batch=3, n_cached=200, n_steps=1, n_q_heads=32, n_kv_heads=4, d_head=32, reuse="odd:1"), {"with_bias": True})
+CASES["dh96-fused"] = (C[2].scaled(n_layers=3, batch=3, n_cached=200, n_steps=1, n_q_heads=32, n_kv_heads=4, d_head=96, latent=64, policy="P2", reuse="odd:1"), {})
+CASES["dh128-fused"] = (C[2].scaled(n_layers=3, batch=3, n_cached=200, n_steps=1, n_q_heads=16, n_kv_heads=2, d_head=128, latent=64, policy="P2", reuse="odd:1",
+                                    dtype="f16"), {"with_bias": True})
+
+
+@pytest.mark.parametrize("name", ["c2-small", "c4-small", "c4-small-p2", "dh32-fused", "dh96-fused", "dh128-fused"])
 def test_fused_single_split_kernel(name):
     """With one split the absorbed queries and the output epilogue run inside the attention kernel;
     the same cases with the three separate kernels must give the same answer as the oracle."""
