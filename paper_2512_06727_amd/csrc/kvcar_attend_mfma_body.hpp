@@ -692,7 +692,8 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
 #pragma unroll
             for (int v = 0; v < 4; ++v) heads_of[nb][v] = nb * 16 + 4 * lg + v < g->n_slots ? (int)g->q_head[nb * 16 + 4 * lg + v] : 0;
         // chunk f of a slice is (row f / cpr, 16-byte piece f % cpr): the same for every KV head, so worked out once, and
-        // with a multiplication ((f * inv) >> 16 is exact for f < 8192 and cpr <= 16) instead of a division per chunk
+        // with a multiplication instead of a division per chunk ((f * inv) >> 16 is exact for f < 8192 when a row has 4, 8,
+        // 12 or 16 pieces, i.e. for every head width this kernel takes)
         const unsigned inv_cpr = (65536u + cpr - 1) / cpr;
         int wrow[kCpt], wch[kCpt];
 #pragma unroll

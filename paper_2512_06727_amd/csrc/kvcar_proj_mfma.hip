@@ -199,7 +199,8 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
         }
     }
     {   // phase 0
-        const int cpr = dh >> 3;
+        const int cpr = dh >> 3;                             // 4, 8, 12 or 16 pieces of 16 bytes per row
+        const unsigned inv_cpr = (65536u + cpr - 1) / cpr;   // f / cpr == (f * inv_cpr) >> 16 for f < 8192 at these values
         const int total = rv * cpr;
         const char* src = static_cast<const char*>(g.v.wl);
         // eight chunks per thread in flight (a load-store-load-store loop pays one round trip per chunk)
@@ -209,7 +210,7 @@ __global__ __launch_bounds__(256) void combine_mfma_kernel(AttendParams p, int r
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int f = f0 + u * 256;
-                const int row = f / cpr, ch = f - row * cpr;
+                const int row = (int)(((unsigned)f * inv_cpr) >> 16), ch = f - row * cpr;
                 dst[u] = row * stride_w + ch * 16;
                 if (f < total) t[u] = *reinterpret_cast<const u32x4_t*>(src + ((size_t)row * g.v.in_width + col) * 2 + ch * 16);
             }
