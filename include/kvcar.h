@@ -230,6 +230,25 @@ typedef struct {
 int kvcar_decode_attention_ex(kvcar_ctx *ctx, int layer, const void *q, void *out, int batch, int n_ctx,
                               const kvcar_step_ext *ext, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * kvcar_decode_attention for callers that cannot allocate device memory and have no workspace to pass: code
+ * running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result
+ * and errors as kvcar_decode_attention, without the workspace: the scratch memory of the call (absorbed queries
+ * and split partials) is a static device buffer of KVCAR_STATIC_SCRATCH_BYTES bytes inside the library, which
+ * every GPU the library runs on holds until the process ends.  The call allocates nothing on the device, creates
+ * no events (kvcar_profile_enable is ignored by it) and, like the other calls, does not synchronise.
+ * KVCAR_ERR_WORKSPACE if the call needs more scratch memory than the buffer holds
+ * (kvcar_workspace_bytes(batch, n_ctx) tells how much; the long-context single-split form needs none),
+ * KVCAR_ERR_HIP if the buffer's address cannot be obtained.  The buffer's address on a device is looked up once,
+ * in kvcar_create on that device or else in the first such call there.  All such calls on one GPU share the one
+ * buffer, whatever their context or stream: calls that may overlap on a GPU (different streams, no ordering
+ * between them) race on it and give wrong results; calls on one stream are safe.  Nothing in it needs to start
+ * from zero: every call writes what it later reads.
+ */
+#define KVCAR_STATIC_SCRATCH_BYTES (32u << 20)
+int kvcar_decode_attention_static(kvcar_ctx *ctx, int layer, const void *q, void *out, int batch, int n_ctx,
+                                  void *stream);
+
 /* kvcar_encode_append for a ragged batch: sequence b's t_new rows land at positions
  * [positions[b], positions[b] + t_new) (positions: dev int32 [batch]).  The caller guarantees
  * positions[b] + t_new <= max_seq (device data is not checked). */

@@ -17,6 +17,7 @@ OK = 0
 ENC_NONE, ENC_PLAIN, ENC_MFMA, ENC_MFMA_TWO_LAYER, ENC_MFMA_STREAM = range(5)
 ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_REUSE, ERR_UNSUPPORTED, ERR_STATE, ERR_HIP, ERR_WORKSPACE, ERR_NOMEM = range(-1, -10, -1)
 F32, F16, BF16 = 0, 1, 2
+STATIC_SCRATCH_BYTES = 32 << 20         # KVCAR_STATIC_SCRATCH_BYTES
 ACT_NONE, ACT_LEAKY_RELU, ACT_GELU = 0, 1, 2
 K, V = 0, 1
 
@@ -67,6 +68,7 @@ SYMBOLS = {
                                          C.c_size_t, C.c_void_p]),
     "kvcar_decode_attention_ex": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(StepExt), C.c_void_p,
                                             C.c_size_t, C.c_void_p]),
+    "kvcar_decode_attention_static": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
     "kvcar_encode_append_at": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]),
     "kvcar_describe_encode": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int)]),
     "kvcar_prefill_workspace_bytes": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]),
@@ -259,6 +261,10 @@ class Context:
         nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
         self._check(lib().kvcar_decode_attention(self._h, layer, _ptr(q), _ptr(out), batch, n_ctx, _ptr(workspace),
                                                  nbytes, _stream()))
+
+    def decode_attention_static(self, layer: int, q, out, batch: int, n_ctx: int):
+        """kvcar_decode_attention on the library's own static scratch buffer (no workspace, no allocation)."""
+        self._check(lib().kvcar_decode_attention_static(self._h, layer, _ptr(q), _ptr(out), batch, n_ctx, _stream()))
 
     def prefill_workspace_bytes(self, batch: int, n_rows: int) -> int:
         n = C.c_size_t(0)

@@ -6,6 +6,7 @@
 #include <cstring>
 #include <map>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <utility>
@@ -26,6 +27,37 @@ struct AEState {
 size_t dtype_size(int dt) { return dt == KVCAR_F32 ? 4 : 2; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+// Scratch memory of kvcar_decode_attention_static (absorbed queries and split partials of one call), owned by the
+// library so that the call itself allocates nothing.  Every device holds its own copy of this array; in host code
+// the name below is only a handle for hipGetSymbolAddress, never an address to hand to a kernel.
+static __device__ __align__(256) unsigned char scratch[KVCAR_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+void* scratch_ptr[kMaxDevices];      // device address of `scratch` on each device, looked up once per device
+
+// Address of the current device's copy of `scratch` (looked up on the first use on that device).
+hipError_t scratch_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return hipSuccess;
+}
 
 }  // namespace
 
@@ -299,6 +331,8 @@ int kvcar_create(const kvcar_config* cfg, kvcar_ctx** out) try {
         ctx->n_cu = prop.multiProcessorCount;
     else
         (void)hipGetLastError();   // no device here: host-side calls still work
+    void* sp = nullptr;            // the static scratch buffer's address on this device, so that the first
+    if (scratch_of_current_device(&sp) != hipSuccess) (void)hipGetLastError();   // ..._static call need not look it up
     *out = ctx.release();
     return KVCAR_OK;
 } catch (...) { return KVCAR_ERR_NOMEM; }
@@ -504,8 +538,10 @@ int encode_impl(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new,
     return KVCAR_OK;
 }
 
+// `library_scratch`: the workspace is the library's static buffer (sized by the caller of this function, not by the
+// user) and the call must not create anything: no timing events.
 int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, const kvcar_step_ext* ext, void* workspace,
-                size_t workspace_bytes, void* stream) {
+                size_t workspace_bytes, void* stream, bool library_scratch = false) {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     const kvcar_config& c = ctx->cfg;
@@ -521,7 +557,10 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
     if (rc) return rc;
     if (!workspace || !aligned16(workspace)) return fail(ctx, KVCAR_ERR_ARG, "workspace null or misaligned");
     if (workspace_bytes < plan.total_bytes)
-        return fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, plan.total_bytes);
+        return library_scratch
+                   ? fail(ctx, KVCAR_ERR_WORKSPACE, "this call needs %zu bytes of scratch memory, more than the %zu of the library's static buffer: "
+                          "use kvcar_decode_attention with a workspace", plan.total_bytes, workspace_bytes)
+                   : fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, plan.total_bytes);
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     for (size_t g0 = 0; g0 < plan.groups.size(); g0 += kMaxGroups) {
@@ -548,7 +587,7 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
         if (!plan.fused && !plan.prologue)
             e = proj && !plan.i8 ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma || plan.i8, st);
         std::pair<hipEvent_t, hipEvent_t>* ev = nullptr;
-        if (e == hipSuccess && ctx->profiling) {
+        if (e == hipSuccess && ctx->profiling && !library_scratch) {
             if (ctx->ev_used == ctx->ev_pool.size()) {
                 hipEvent_t a, b2;
                 e = hipEventCreate(&a);
@@ -680,6 +719,14 @@ int kvcar_decode_attention(kvcar_ctx* ctx, int layer, const void* q, void* out, 
 int kvcar_decode_attention_ex(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, const kvcar_step_ext* ext,
                               void* workspace, size_t workspace_bytes, void* stream) try {
     return decode_impl(ctx, layer, q, out, batch, n_ctx, ext, workspace, workspace_bytes, stream);
+} catch (...) { return KVCAR_ERR_NOMEM; }
+
+int kvcar_decode_attention_static(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, void* stream) try {
+    if (!ctx) return KVCAR_ERR_ARG;
+    void* sp = nullptr;
+    const hipError_t e = scratch_of_current_device(&sp);
+    if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "the static scratch buffer's device address is not available: %s", hipGetErrorString(e));
+    return decode_impl(ctx, layer, q, out, batch, n_ctx, nullptr, sp, KVCAR_STATIC_SCRATCH_BYTES, stream, true);
 } catch (...) { return KVCAR_ERR_NOMEM; }
 
 int kvcar_prefill_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_rows, size_t* bytes) try {
