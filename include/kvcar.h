@@ -28,7 +28,8 @@
  *   - Weight matrices are row-major [in_features, out_features]; biases may be NULL.
  *   - The library owns only its host-side context.  The context holds no sequence positions:
  *     positions are explicit arguments, so calls can be replayed.
- *   - All sequences of a batch have the same length (uniform batch).
+ *   - kvcar_encode_append / kvcar_decode_attention treat all sequences of a batch alike (same position, same
+ *     context length); kvcar_encode_append_at / kvcar_decode_attention_ex take per-sequence positions and lengths.
  *   - Layers are 0-indexed.  KVCAR_K = keys, KVCAR_V = values.
  *
  * Latent cache layout (library-defined, caller-allocated): for layer N and tensor `which`
@@ -48,7 +49,11 @@
  * r must be a multiple of 16.  Activations, weights and outputs keep the configured dtype.
  * The matrix-core attention kernel for int8 rows feeds codes, 1/scale and the zero point to fp16
  * operands: it expects |zeropoint| < 2^23 and max(x) - min(x) < 6e4 in every row (far outside what
- * latent activations reach; a row of nearly equal large values would violate the first).
+ * latent activations reach; a row of nearly equal values 1e5 times larger than their spread would
+ * violate the first).  Beyond these limits it saturates the operands: its result stays finite but is
+ * no longer the method's.  A caller whose latents can look like that sets kvcar_tuning.force_generic:
+ * the plain-ALU kernels take a key row's zero point out of the scores in fp64 and dequantise value
+ * rows in fp32, which is exact for |zeropoint| <= 2^24.
  */
 #ifndef KVCAR_H
 #define KVCAR_H
@@ -83,7 +88,11 @@ typedef enum { KVCAR_LATENT_DTYPE = 0, KVCAR_LATENT_INT8 = 1 } kvcar_latent_form
 
 /* Activation between the two fully connected layers of an encoder / decoder.  NONE = the
  * autoencoder is a single linear map each way. */
-typedef enum { KVCAR_ACT_NONE = 0, KVCAR_ACT_LEAKY_RELU = 1, KVCAR_ACT_GELU = 2 /* erf form */ } kvcar_act;
+typedef enum { KVCAR_ACT_NONE = 0, KVCAR_ACT_LEAKY_RELU = 1, KVCAR_ACT_GELU = 2 } kvcar_act;
+/* GELU is x Phi(x) with the normal distribution function Phi (the erf form, not the tanh form).  Encoders and
+ * the plain-ALU kernels evaluate erf to 1.5e-7; the matrix-core kernels that rebuild hidden rows of a two-layer
+ * decoder (decode and prefill attention) use a polynomial for Phi with |GELU error| <= 3.1e-5 |x|, below the
+ * 16-bit rounding those hidden rows receive next. */
 
 enum { KVCAR_K = 0, KVCAR_V = 1 };
 
@@ -141,7 +150,8 @@ typedef struct {
 } kvcar_tuning;
 
 /* Create / destroy a context.  ERR_ARG on null pointers, ERR_SHAPE on non-positive sizes or
- * n_q_heads % n_kv_heads != 0, ERR_UNSUPPORTED on an unknown dtype or latent format. */
+ * n_q_heads % n_kv_heads != 0, ERR_UNSUPPORTED on an unknown dtype or latent format, more than 64 KV heads,
+ * n_q_heads > 32767 or n_kv_heads * d_head > 32767. */
 int kvcar_create(const kvcar_config *cfg, kvcar_ctx **out);
 int kvcar_destroy(kvcar_ctx *ctx);
 
@@ -268,9 +278,11 @@ int kvcar_encode_append_at(kvcar_ctx *ctx, int layer, const void *k_new, const v
  * steps with n_ctx = pos0 + i + 1 up to rounding.  Unlike a decode step, a prompt chunk is bound by the
  * matrix units, not by reading the cache, so the decoder is not folded into the query (that would double
  * the products per score): the rows 0 .. pos0 + t_new - 1 of every KV head are decoded ONCE per call into
- * `workspace` (rounded to dtype, the precision the model holds its keys and values in; the keys carry the
- * softmax scale into that one rounding) and a causal
- * attention kernel runs over them.  Nothing outlives the call: the workspace may be reused at once by
+ * `workspace` and a causal attention kernel runs over them.  The decoded rows are an internal
+ * approximation, not a step of the method: they are held in fp16 for both 16-bit model dtypes (11-bit
+ * significands; bf16's 8 bits would put the rounding of every key into every prompt score), in fp32 for
+ * fp32 models, the keys carrying the softmax scale into that one rounding.  fp16's range applies: |q|,
+ * |scale * log2(e) * K^| and |V^| beyond 65504 saturate.  Nothing outlives the call: the workspace may be reused at once by
  * the next layer.  kvcar_prefill_workspace_bytes(batch, n_rows) gives its size for n_rows = pos0 + t_new
  * (2 * batch * n_rows * H_kv * d_head elements).
  * ERR_CAPACITY if batch > max_batch or pos0 + t_new > max_seq; ERR_ARG if t_new < 1, pos0 < 0 or a

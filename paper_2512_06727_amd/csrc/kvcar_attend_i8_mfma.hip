@@ -17,39 +17,24 @@ __global__ __launch_bounds__(256, 2) void attend_i8_mfma_r128_kernel(AttendParam
     const int key = g->k.r * 4 + (g->slots_pad >> 4);
     if (p->fused == 3) {                      // several splits, absorbed queries computed here
         switch (key) {
-            case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+            KVCAR_EXACT_SHAPES(X)
+#undef X
             default: return;
         }
     }
     if (p->fused) {
         switch (key) {
-            case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, true, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, true, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, true, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, true, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, true, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, true, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, true, true>(p, g, lds_raw, kI8WaveLds); return;
-            case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+            KVCAR_EXACT_SHAPES(X)
+#undef X
             default: return;
         }
     }
     switch (key) {
-        case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, false, true>(p, g, lds_raw, kI8WaveLds); return;
-        case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, false, true>(p, g, lds_raw, kI8WaveLds); return;
-        case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, false, true>(p, g, lds_raw, kI8WaveLds); return;
-        case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, false, true>(p, g, lds_raw, kI8WaveLds); return;
-        case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, false, true>(p, g, lds_raw, kI8WaveLds); return;
-        case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, false, true>(p, g, lds_raw, kI8WaveLds); return;
-        case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, false, true>(p, g, lds_raw, kI8WaveLds); return;
-        case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+        KVCAR_EXACT_SHAPES(X)
+#undef X
         default: return;
     }
 }
@@ -62,14 +47,9 @@ __global__ __launch_bounds__(512, 1) void attend_i8_mfma_r128_w8_kernel(AttendPa
     KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
     KGroup g = &p->g[blockIdx.z];
     switch (g->k.r * 4 + (g->slots_pad >> 4)) {
-        case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
-        case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
-        case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
-        case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
-        case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
-        case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
-        case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
-        case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+        KVCAR_EXACT_SHAPES(X)
+#undef X
         default: return;
     }
 }
@@ -81,13 +61,13 @@ bool attend_i8_mfma_supported(const AttendParams& p, int dtype) {
     for (int i = 0; i < p.n_groups; ++i) {
         const GroupDesc& g = p.g[i];
         if (!g.k.meta || !g.v.meta || g.k.w1 || g.v.w1) return false;
-        if (g.k.r != g.v.r || g.k.r % 32 || g.k.r < 32 || g.k.r > 128 || g.slots_pad > 32) return false;
+        if (g.k.r != g.v.r || !exact_shape(g.k.r, g.slots_pad / 16)) return false;      // every form of this kernel is compiled for the exact shapes only
     }
     return true;
 }
 
 hipError_t launch_attend_i8_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
-    static bool attr[2] = {false, false}, attr8[2] = {false, false};
+    static AttrFlag attr[2] = {false, false}, attr8[2] = {false, false};
     if (!attend_i8_mfma_supported(p, dtype)) return hipErrorNotSupported;
     if (p.fused == 2) {
         const size_t epi8 = 2048 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);

@@ -17,39 +17,24 @@ __global__ __launch_bounds__(256, 2) void attend_mfma_r128_kernel(AttendParams p
         const int key = g->k.r * 4 + nhb;
         if (p->fused == 1) {                  // the host only asks for this with exact shapes in every group
             switch (key) {
-                case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, true>(p, g, lds_raw, wl); return;
-                case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, true>(p, g, lds_raw, wl); return;
-                case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, true>(p, g, lds_raw, wl); return;
-                case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, true>(p, g, lds_raw, wl); return;
-                case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, true>(p, g, lds_raw, wl); return;
-                case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, true>(p, g, lds_raw, wl); return;
-                case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, true>(p, g, lds_raw, wl); return;
-                case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, true>(p, g, lds_raw, wl); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true>(p, g, lds_raw, wl); return;
+                KVCAR_EXACT_SHAPES(X)
+#undef X
                 default: return;
             }
         }
         if (p->fused == 3) {                  // several splits, absorbed queries computed here
             switch (key) {
-                case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
-                case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
-                case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
-                case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
-                case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
-                case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
-                case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
-                case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
+                KVCAR_EXACT_SHAPES(X)
+#undef X
                 default: return;
             }
         }
         switch (key) {
-            case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, false>(p, g, lds_raw, wl); return;
-            case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, false>(p, g, lds_raw, wl); return;
-            case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, false>(p, g, lds_raw, wl); return;
-            case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, false>(p, g, lds_raw, wl); return;
-            case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, false>(p, g, lds_raw, wl); return;
-            case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, false>(p, g, lds_raw, wl); return;
-            case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, false>(p, g, lds_raw, wl); return;
-            case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, false>(p, g, lds_raw, wl); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false>(p, g, lds_raw, wl); return;
+            KVCAR_EXACT_SHAPES(X)
+#undef X
             default: break;
         }
     }
@@ -67,14 +52,9 @@ __global__ __launch_bounds__(512, 1) void attend_mfma_r128_w8_kernel(AttendParam
     KGroup g = &p->g[blockIdx.z];
     constexpr size_t wl = Geo<128>::kWaveLds;
     switch (g->k.r * 4 + (g->slots_pad >> 4)) {
-        case 128 * 4 + 2: attend_body<E, DimsExact<128, 2>, true, false, 8>(p, g, lds_raw, wl); return;
-        case 128 * 4 + 1: attend_body<E, DimsExact<128, 1>, true, false, 8>(p, g, lds_raw, wl); return;
-        case 96 * 4 + 2: attend_body<E, DimsExact<96, 2>, true, false, 8>(p, g, lds_raw, wl); return;
-        case 96 * 4 + 1: attend_body<E, DimsExact<96, 1>, true, false, 8>(p, g, lds_raw, wl); return;
-        case 64 * 4 + 2: attend_body<E, DimsExact<64, 2>, true, false, 8>(p, g, lds_raw, wl); return;
-        case 64 * 4 + 1: attend_body<E, DimsExact<64, 1>, true, false, 8>(p, g, lds_raw, wl); return;
-        case 32 * 4 + 2: attend_body<E, DimsExact<32, 2>, true, false, 8>(p, g, lds_raw, wl); return;
-        case 32 * 4 + 1: attend_body<E, DimsExact<32, 1>, true, false, 8>(p, g, lds_raw, wl); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, false, 8>(p, g, lds_raw, wl); return;
+        KVCAR_EXACT_SHAPES(X)
+#undef X
         default: return;
     }
 }
@@ -93,7 +73,7 @@ __global__ __launch_bounds__(256, 1) void attend_mfma_r384_kernel(AttendParams p
 }
 
 template <typename K>
-static hipError_t launch_one(K kern, size_t lds, const AttendParams& p, hipStream_t stream, bool& attr_set, int threads = 256) {
+static hipError_t launch_one(K kern, size_t lds, const AttendParams& p, hipStream_t stream, AttrFlag& attr_set, int threads = 256) {
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
@@ -107,7 +87,7 @@ static hipError_t launch_one(K kern, size_t lds, const AttendParams& p, hipStrea
 bool attend_mfma_available() { return true; }
 
 hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
-    static bool set128[2] = {false, false}, set384[2] = {false, false}, set128w8[2] = {false, false};
+    static AttrFlag set128[2] = {false, false}, set384[2] = {false, false}, set128w8[2] = {false, false};
     int rmax = 0, nhb = 1;
     for (int i = 0; i < p.n_groups; ++i) {
         rmax = p.g[i].k.r > rmax ? p.g[i].k.r : rmax;
@@ -115,6 +95,10 @@ hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stre
         nhb = p.g[i].slots_pad / 16 > nhb ? p.g[i].slots_pad / 16 : nhb;
     }
     const int e = dtype == KVCAR_BF16 ? 0 : 1;
+    // the fused and prologue forms exist for the exact shapes only: a group outside them would find no instance
+    if (p.fused != 0)
+        for (int i = 0; i < p.n_groups; ++i)
+            if (p.g[i].k.r != p.g[i].v.r || !exact_shape(p.g[i].k.r, p.g[i].slots_pad / 16)) return hipErrorNotSupported;
     if (rmax <= 128 && nhb <= 2 && p.fused == 2) {
         // eight waves: staging regions + swapped query operands, or the epilogue's exchange area (m, l of
         // eight waves) + latent sums + one decoder slice

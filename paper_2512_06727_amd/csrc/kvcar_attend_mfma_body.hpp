@@ -64,6 +64,17 @@ template <> struct Mma<F16> {
     static __device__ __forceinline__ uint16_t to16(float v) { _Float16 h = (_Float16)v; return __builtin_bit_cast(uint16_t, h); }
 };
 
+// The (latent width, 16-head blocks) pairs the loop is compiled for with every size a constant.  The kernels' switches
+// and the host's test of whether a launch may use them (exact_shape) are both generated from this one list, so a
+// launch that passes the host's test always finds its instance.
+#define KVCAR_EXACT_SHAPES(X) X(128, 2) X(128, 1) X(96, 2) X(96, 1) X(64, 2) X(64, 1) X(32, 2) X(32, 1)
+inline bool exact_shape(int r, int nhb) {
+#define X(R, N) if (r == R && nhb == N) return true;
+    KVCAR_EXACT_SHAPES(X)
+#undef X
+    return false;
+}
+
 constexpr int kWaveTile = 32;     // tokens per wave per iteration
 constexpr int kWaves = 4;
 

@@ -419,7 +419,7 @@ static hipError_t launch_mlp(const AttendParams& p, int act, hipStream_t stream)
     const size_t stage_lds = (size_t)R * (2 * C + 32);            // first-layer weights pass through LDS at start
     const size_t lds = loop_lds > stage_lds ? loop_lds : stage_lds;
     dim3 grid(p.n_splits, p.batch, p.n_groups);
-    static bool attr[2] = {false, false};
+    static AttrFlag attr[2] = {false, false};
     auto kg = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_GELU, kI8, NW>;
     auto kl = attend_mlp_mfma_kernel<E, R, C, KVCAR_ACT_LEAKY_RELU, kI8, NW>;
     const int ai = act == KVCAR_ACT_GELU ? 0 : 1;

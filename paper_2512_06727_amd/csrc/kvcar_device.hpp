@@ -43,6 +43,17 @@ template <> struct Elem<BF16> {
     static __device__ __forceinline__ void store(void* p, size_t i, float v) { static_cast<uint16_t*>(p)[i] = f32_to_bf16_bits(v); }
 };
 
+// The dtype in which prefill attention holds the decoded rows K^ / V^ between its two kernels: fp32 for fp32 models,
+// fp16 for both 16-bit dtypes.  A bf16 model's decoded rows would otherwise carry bf16's 8-bit rounding into every
+// prompt score (q . dK^ grows with the query's size and the row width); fp16 keeps 11 bits at the same cost.  Its
+// range ends at 65504: decoded values (the keys after the softmax scale) and queries beyond that saturate.
+template <typename E> struct RowsOf { using type = F16; };
+template <> struct RowsOf<F32> { using type = F32; };
+constexpr float kHalfMax = 65504.f;
+__device__ __forceinline__ float sat_half(float x) { return __builtin_amdgcn_fmed3f(x, -kHalfMax, kHalfMax); }
+template <typename E> __device__ __forceinline__ float sat_rows(float x) { return sat_half(x); }
+template <> __device__ __forceinline__ float sat_rows<F32>(float x) { return x; }
+
 // Element c of latent row `row` of a cache side: as stored, or dequantised from its int8 code
 // (x^ = (code - zeropoint) / scale, Eq. "quant").
 template <typename E>

@@ -253,7 +253,7 @@ hipError_t launch_bulk_nb(const EncodeParams& p, int nb, int side0, int n_sides,
         case 8: kern = encode_bulk_kernel<E, 8, kI8>; break;
         default: return hipErrorInvalidValue;
     }
-    static bool attr_set[5] = {false, false, false, false, false};      // per instantiation of this function template
+    static AttrFlag attr_set[5] = {false, false, false, false, false};      // per instantiation of this function template
     if (!attr_set[nb / 2]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBulkLdsMax);
         if (e != hipSuccess) return e;

@@ -333,7 +333,7 @@ __global__ __launch_bounds__(256) void encode_i8_step_kernel(EncodeParams p) {
 
 
 template <typename K>
-static hipError_t launch_enc(K kern, size_t lds, const EncodeParams& p, hipStream_t stream, bool& attr_set, int col_windows = 1) {
+static hipError_t launch_enc(K kern, size_t lds, const EncodeParams& p, hipStream_t stream, AttrFlag& attr_set, int col_windows = 1) {
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
@@ -361,7 +361,7 @@ bool encode_mfma_supported(const EncodeParams& p, int dtype) {
 }
 
 hipError_t launch_encode_mfma(const EncodeParams& p, int dtype, hipStream_t stream) {
-    static bool set[8] = {false, false, false, false, false, false, false, false};
+    static AttrFlag set[8] = {false, false, false, false, false, false, false, false};
     int rmax = 0, hmax = 0;
     for (int i = 0; i < 2; ++i) { rmax = p.s[i].r > rmax ? p.s[i].r : rmax; hmax = p.s[i].hidden > hmax ? p.s[i].hidden : hmax; }
     const bool bf = dtype == KVCAR_BF16;
@@ -378,7 +378,7 @@ hipError_t launch_encode_mfma(const EncodeParams& p, int dtype, hipStream_t stre
         const size_t lds8 = kWBufBytes + 4 * 16 * 2 * sizeof(float);
         const int n_tok = p.batch * p.t_new;
         dim3 grid((n_tok + 15) / 16, 2);
-        static bool set8[4] = {false, false, false, false};
+        static AttrFlag set8[4] = {false, false, false, false};
         const int slot = (bf ? 0 : 2) + (rmax <= 128 ? 0 : 1);
         void (*k8)(EncodeParams) = bf ? (rmax <= 128 ? encode_i8_step_kernel<BF16, 2> : encode_i8_step_kernel<BF16, 6>)
                                       : (rmax <= 128 ? encode_i8_step_kernel<F16, 2> : encode_i8_step_kernel<F16, 6>);

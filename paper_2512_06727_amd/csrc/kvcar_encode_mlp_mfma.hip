@@ -324,7 +324,7 @@ hipError_t em_launch_shape(const EncodeParams& p, int side0, int n_sides, bool g
     const size_t lds = (small ? 4 : 2) * buf + biases;
     void (*kern)(EncodeParams, int) = small ? (gelu ? encode_mlp_mfma_kernel<E, KX, NBZ, true, true> : encode_mlp_mfma_kernel<E, KX, NBZ, false, true>)
                                             : (gelu ? encode_mlp_mfma_kernel<E, KX, NBZ, true, false> : encode_mlp_mfma_kernel<E, KX, NBZ, false, false>);
-    static bool attr[2][2] = {{false, false}, {false, false}};
+    static AttrFlag attr[2][2] = {{false, false}, {false, false}};
     if (lds > 64 * 1024 && !attr[small][gelu]) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (err != hipSuccess) return err;

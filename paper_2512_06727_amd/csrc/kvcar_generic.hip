@@ -158,11 +158,26 @@ hipError_t launch_qtilde(const AttendParams& p, int dtype, bool qt_f32, hipStrea
 // plain-ALU attention over rows h_t, one workgroup per (split, sequence, group).
 // Partial written per (b, split, group): for each slot  [m, l, -, -, o[0..cv)]  with scores in log2 units.
 // ---------------------------------------------------------------------------------------------
+// `codes` (keys over int8 rows through a linear decoder): the rows are left as their integer codes and the tile's
+// scales and zero points go to inv / zp; the caller applies them to the finished dot products (see there).
 template <typename E>
-__device__ void load_rows(const SideDesc& sd, float* rows, float* zrow, int b, int t0, int nt, int max_seq) {
+__device__ void load_rows(const SideDesc& sd, float* rows, float* zrow, int b, int t0, int nt, int max_seq, bool codes = false, float* inv = nullptr,
+                          int* zp = nullptr) {
     // rows [kGenericTile][c+1]; rows of tokens >= nt are zero
     const int tid = threadIdx.x;
     const int ld = sd.c + 1;
+    if (codes) {
+        for (int i = tid; i < kGenericTile * sd.c; i += 256) {
+            const int t = i / sd.c, c = i % sd.c;
+            rows[t * ld + c] = t < nt ? (float)static_cast<const signed char*>(sd.z)[((size_t)b * max_seq + t0 + t) * sd.r + c] : 0.f;
+        }
+        if (tid < kGenericTile) {
+            const RowMeta m = tid < nt ? static_cast<const RowMeta*>(sd.meta)[(size_t)b * max_seq + t0 + tid] : RowMeta{1.f, 0};
+            inv[tid] = 1.f / m.scale;
+            zp[tid] = m.zeropoint;
+        }
+        return;
+    }
     if (sd.w1 == nullptr) {
         for (int i = tid; i < kGenericTile * sd.c; i += 256) {
             const int t = i / sd.c, c = i % sd.c;
@@ -191,6 +206,7 @@ size_t attend_generic_lds_bytes(const GroupDesc& g) {
     if (g.v.w1 && (size_t)g.v.r > zr) zr = g.v.r;
     size_t f = (size_t)g.n_slots * g.k.c + (size_t)kGenericTile * (g.k.c + 1) + (size_t)kGenericTile * (g.v.c + 1) +
                (size_t)kGenericTile * zr + (size_t)g.n_slots * kGenericTile + 3 * (size_t)g.n_slots;
+    f += 2 * (size_t)g.n_slots + 2 * kGenericTile + 2;      // int8 key rows: the slots' query sums (fp64) and the tile's scales and zero points
     return f * sizeof(float);
 }
 
@@ -214,10 +230,27 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(AttendParams p) {
     float* m_s = sc + ns * kGenericTile;                // [ns]
     float* l_s = m_s + ns;
     float* a_s = l_s + ns;
+    // Keys over int8 rows through a linear decoder: score = (sum_c qt_c code_c - zeropoint sum_c qt_c) / scale.  A row far
+    // from zero has a large zero point, and the second term - the same for every token up to the rows' own offsets,
+    // so softmax only sees differences of it - is then far larger than the score: the difference is formed in fp64 from
+    // the fp32 dot product over the codes and the slot's query sum (fp64).  Dequantising the row in fp32 first would
+    // round away part of every code once |zeropoint| passes 2^20.
+    const bool k_codes = g.k.meta != nullptr && g.k.w1 == nullptr;
+    float* inv_k = a_s + ns;                            // [tile]
+    int* zp_k = reinterpret_cast<int*>(inv_k + kGenericTile);
+    double* qsum = reinterpret_cast<double*>((reinterpret_cast<uintptr_t>(zp_k + kGenericTile) + 7) & ~(uintptr_t)7);      // [ns]
 
     const float* qsrc = static_cast<const float*>(p.qt) + (size_t)b * p.qt_stride + g.qt_off;
     for (int i = tid; i < ns * ck; i += 256) qt[i] = qsrc[i];
     if (tid < ns) { m_s[tid] = -INFINITY; l_s[tid] = 0.f; }
+    if (k_codes) {
+        __syncthreads();
+        if (tid < ns) {
+            double a = 0.0;
+            for (int c = 0; c < ck; ++c) a += (double)qt[tid * ck + c];
+            qsum[tid] = a;
+        }
+    }
 
     float acc[kGenericAcc];
 #pragma unroll
@@ -234,13 +267,14 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(AttendParams p) {
     for (int tile = tile0; tile < tile1; ++tile) {
         const int t0 = tile * kGenericTile;
         const int nt = min(kGenericTile, n_ctx - t0);
-        load_rows<E>(g.k, rk, zrow, b, t0, nt, p.max_seq);
+        load_rows<E>(g.k, rk, zrow, b, t0, nt, p.max_seq, k_codes, inv_k, zp_k);
         load_rows<E>(g.v, rv, zrow, b, t0, nt, p.max_seq);
         __syncthreads();
         for (int i = tid; i < ns * kGenericTile; i += 256) {
             const int s = i / kGenericTile, t = i % kGenericTile;
             float a = 0.f;
             for (int c = 0; c < ck; ++c) a = fmaf(qt[s * ck + c], rk[t * (ck + 1) + c], a);
+            if (k_codes) a = (float)((double)a - (double)zp_k[t] * qsum[s]) * inv_k[t];
             sc[i] = t < nt ? a : -INFINITY;
         }
         __syncthreads();

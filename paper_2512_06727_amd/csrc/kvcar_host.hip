@@ -315,6 +315,8 @@ int kvcar_create(const kvcar_config* cfg, kvcar_ctx** out) try {
         cfg->max_seq <= 0 || cfg->n_q_heads % cfg->n_kv_heads != 0)
         return KVCAR_ERR_SHAPE;
     if (cfg->n_kv_heads > kMaxKvHeads) return KVCAR_ERR_UNSUPPORTED;
+    // query-head indices and decoder column offsets travel to the kernels as 16-bit numbers
+    if (cfg->n_q_heads > 32767 || (long long)cfg->n_kv_heads * cfg->d_head > 32767) return KVCAR_ERR_UNSUPPORTED;
     if (cfg->dtype != KVCAR_F32 && cfg->dtype != KVCAR_F16 && cfg->dtype != KVCAR_BF16) return KVCAR_ERR_UNSUPPORTED;
     if (cfg->latent_format != KVCAR_LATENT_DTYPE && cfg->latent_format != KVCAR_LATENT_INT8) return KVCAR_ERR_UNSUPPORTED;
     std::unique_ptr<kvcar_ctx> ctx(new (std::nothrow) kvcar_ctx());

@@ -4,9 +4,15 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "kvcar.h"
 
 namespace kvcar {
+
+// "This kernel's dynamic-LDS limit has been raised" flags of the launchers: process-wide, set once; two host threads
+// that launch at the same moment may both set the attribute, which is harmless.
+using AttrFlag = std::atomic<bool>;
 
 constexpr int kMaxSlots = 32;       // query heads served by one group
 constexpr int kMaxGroups = 8;       // groups per attention launch

@@ -4,9 +4,9 @@
 // the keys and values of all prompt tokens, which go to the cache - as latent rows here - and come back
 // through the decoder, "Network Architecture", 2nd paragraph; attention is Eq. 1 per token).  Two steps:
 //   recon    K^[b, g, t, :] / V^[b, g, t, :] = decoder(latent row t of the layer that supplies head g),
-//            the columns of head g, for t < n_rows; written once, rounded to the model dtype.  The keys are
-//            multiplied by scale * log2(e) before that one rounding, so scores come out in log2 units and
-//            the scale costs neither an operation per score nor a second rounding
+//            the columns of head g, for t < n_rows; written once, rounded to fp16 for 16-bit models (fp32 for
+//            fp32 models; see RowsOf).  The keys are multiplied by scale * log2(e) before that one rounding, so
+//            scores come out in log2 units and the scale costs neither an operation per score nor a second rounding
 //   attend   out[b, i, j, :] = sum_{t <= pos0 + i} softmax_t(scale q[b,i,j,:] . K^_g[t]) V^_g[t]
 // These kernels serve fp32 models and shapes the matrix-core kernels do not cover.
 #include "kvcar_device.hpp"
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void recon_generic_kernel(ReconParams p) {
             if (t >= nt) continue;
             float a = sd.bl ? Elem<E>::load(sd.bl, col + k) : 0.f;
             for (int c = 0; c < sd.c; ++c) a = fmaf(rows[t * sd.c + c], Elem<E>::load(sd.wl, (size_t)c * sd.in_width + col + k), a);
-            Elem<E>::store(dst, (((size_t)b * p.n_kv_heads + g) * p.n_rows + t0 + t) * dh + k, a * out_scale);
+            Elem<typename RowsOf<E>::type>::store(dst, (((size_t)b * p.n_kv_heads + g) * p.n_rows + t0 + t) * dh + k, sat_rows<E>(a * out_scale));
         }
     }
 }
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(64) void prefill_generic_kernel(PrefillParams p) {
         float s = -INFINITY;
         if (t < n) {
             s = 0.f;
-            for (int k = 0; k < dh; ++k) s = fmaf(qs[k], Elem<E>::load(p.khat, (row0 + t) * dh + k), s);
+            for (int k = 0; k < dh; ++k) s = fmaf(qs[k], Elem<typename RowsOf<E>::type>::load(p.khat, (row0 + t) * dh + k), s);
         }
         float mx = s;
 #pragma unroll
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(64) void prefill_generic_kernel(PrefillParams p) {
             const int d = lane + 64 * u;
             if (d < dh) {
                 float a = acc[u] * alpha;
-                for (int tt = 0; tt < nt; ++tt) a = fmaf(ps[tt], Elem<E>::load(p.vhat, (row0 + t0 + tt) * dh + d), a);
+                for (int tt = 0; tt < nt; ++tt) a = fmaf(ps[tt], Elem<typename RowsOf<E>::type>::load(p.vhat, (row0 + t0 + tt) * dh + d), a);
                 acc[u] = a;
             }
         }

@@ -97,9 +97,20 @@ constexpr int kReconChunk = 256;      // tokens per workgroup: TL 32-token tiles
 __host__ __device__ constexpr int recon_stage_stride(int d_head) { return 2 * d_head + 16; }
 __host__ __device__ constexpr size_t recon_stage_bytes(int d_head) { return (size_t)kReconChunk * recon_stage_stride(d_head); }
 
-template <typename E>
-__device__ __forceinline__ void recon_emit_block(const f32x16_t& acc, const void* bl, int col0, float out_scale, char* stage_row, char* orow) {
-    // this lane: one token, decoder columns col0 + 8a + j (register 4a + j), col0 already holding the lane half's 4h
+// int8 rows enter the products as their codes (exact in either 16-bit dtype), so a row's scale and zero point are
+// applied to the fp32 sums: x^ . W[:, n] = (sum_c u_c W[c, n] - (128 + zeropoint) S_n) / scale with u = code + 128 and
+// S_n the column sums of the matrix.  Rounding the dequantised row to 16 bits first would cost about as much
+// accuracy as the int8 codes themselves hold.
+struct RowQuant {
+    float inv;      // 1 / scale
+    float sub;      // 128 + zeropoint
+};
+
+template <typename E, bool kI8>
+__device__ __forceinline__ void recon_emit_block(const f32x16_t& acc, const void* bl, int col0, float out_scale, char* stage_row, char* orow,
+                                                 const float* colsum, RowQuant rq) {
+    // this lane: one token, decoder columns col0 + 8a + j (register 4a + j), col0 already holding the lane half's 4h;
+    // colsum points at the column sums of those columns (int8 rows)
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
         float bias[4] = {0.f, 0.f, 0.f, 0.f};
@@ -107,10 +118,29 @@ __device__ __forceinline__ void recon_emit_block(const f32x16_t& acc, const void
 #pragma unroll
             for (int j = 0; j < 4; ++j) bias[j] = Elem<E>::load(bl, col0 + 8 * a + j);
         }
-        const u32x2_t w = {Mma<E>::pack2((acc[4 * a] + bias[0]) * out_scale, (acc[4 * a + 1] + bias[1]) * out_scale),
-                           Mma<E>::pack2((acc[4 * a + 2] + bias[2]) * out_scale, (acc[4 * a + 3] + bias[3]) * out_scale)};
+        float v[4];
+        if constexpr (kI8) {
+            const f32x4_t cs = *reinterpret_cast<const f32x4_t*>(colsum + 8 * a);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = fmaf(fmaf(-rq.sub, cs[j], acc[4 * a + j]), rq.inv, bias[j]) * out_scale;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (acc[4 * a + j] + bias[j]) * out_scale;
+        }
+        // decoded rows are held in fp16 whatever the 16-bit model dtype (RowsOf), saturating at its range
+        const u32x2_t w = {Mma<F16>::pack2(sat_half(v[0]), sat_half(v[1])), Mma<F16>::pack2(sat_half(v[2]), sat_half(v[3]))};
         if (stage_row) *reinterpret_cast<u32x2_t*>(stage_row + 16 * a) = w;
         else if (orow) *reinterpret_cast<u32x2_t*>(orow + 16 * a) = w;
+    }
+}
+
+// Column sums of an [n_rows, n_cols] matrix of 16-bit elements staged in LDS (row stride in bytes), in fp32.
+template <typename E>
+__device__ __forceinline__ void lds_column_sums(float* out, const char* mat, int stride, int n_rows, int n_cols, int tid, int n_threads) {
+    for (int n = tid; n < n_cols; n += n_threads) {
+        float acc = 0.f;
+        for (int c = 0; c < n_rows; ++c) acc += Elem<E>::load(mat + (size_t)c * stride, n);
+        out[n] = acc;
     }
 }
 
@@ -134,7 +164,7 @@ typedef const __attribute__((address_space(4))) ReconEntry* REntry;
 // The wave's latent rows as B operands: tile `tile` of its 32 TL tokens; lane (token l32, half h) holds latent
 // columns 16s + 8h .. +7 of k-step s, dequantised in registers when the rows are int8 codes; rows past n_rows are zero.
 template <typename E, int R, bool kI8, int TL>
-__device__ __forceinline__ void recon_load_rows(u32x4_t (&zb)[TL][R / 16], REntry e, RArgs p, int b, int tok0, int l32, int h) {
+__device__ __forceinline__ void recon_load_rows(u32x4_t (&zb)[TL][R / 16], RowQuant (&rq)[TL], REntry e, RArgs p, int b, int tok0, int l32, int h) {
     constexpr int KS = R / 16;
     const int n_rows = p->n_rows;
 #pragma unroll
@@ -142,10 +172,11 @@ __device__ __forceinline__ void recon_load_rows(u32x4_t (&zb)[TL][R / 16], REntr
         const int t = tok0 + tile * 32 + l32;
         const bool valid = t < n_rows;
         const size_t row = (size_t)b * p->max_seq + (valid ? t : 0);
+        rq[tile] = RowQuant{1.f, 0.f};
         if constexpr (kI8) {
             const RowMeta m = static_cast<const RowMeta*>(e->d.meta)[row];
-            const float inv = 1.f / m.scale;
-            const float sub = (128.f + (float)m.zeropoint) * inv;          // codes are read as unsigned bytes code + 128
+            rq[tile].inv = 1.f / m.scale;
+            rq[tile].sub = 128.f + (float)m.zeropoint;                     // codes are read as unsigned bytes u = code + 128
             const char* zr = static_cast<const char*>(e->d.z) + row * R + 8 * h;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
@@ -154,10 +185,8 @@ __device__ __forceinline__ void recon_load_rows(u32x4_t (&zb)[TL][R / 16], REntr
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     const unsigned x = c[i] ^ 0x80808080u;
-                    const float f0 = fmaf((float)(x & 0xffu), inv, -sub), f1 = fmaf((float)((x >> 8) & 0xffu), inv, -sub);
-                    const float f2 = fmaf((float)((x >> 16) & 0xffu), inv, -sub), f3 = fmaf((float)(x >> 24), inv, -sub);
-                    w[2 * i] = Mma<E>::pack2(f0, f1);
-                    w[2 * i + 1] = Mma<E>::pack2(f2, f3);
+                    w[2 * i] = Mma<E>::pack2((float)(x & 0xffu), (float)((x >> 8) & 0xffu));          // 0 .. 255: exact in 8 significant bits
+                    w[2 * i + 1] = Mma<E>::pack2((float)((x >> 16) & 0xffu), (float)(x >> 24));
                 }
                 zb[tile][s] = valid ? u32x4_t{w[0], w[1], w[2], w[3]} : u32x4_t{0u, 0u, 0u, 0u};
             }
@@ -190,9 +219,11 @@ __global__ __launch_bounds__(64 * kReconChunk / (32 * TL)) void recon_mfma_kerne
     const int stride_w = 2 * dh + 32, cpr = dh >> 3;
     const int stride_o = recon_stage_stride(dh);
     char* stage = p->staged ? lds + R * stride_w + wave * 32 * TL * stride_o : nullptr;
+    float* colsum = reinterpret_cast<float*>(lds + R * stride_w + (p->staged ? kReconChunk * stride_o : 0));      // [d_head], int8 rows only
 
     u32x4_t zb[TL][KS];
-    recon_load_rows<E, R, kI8, TL>(zb, e, p, b, chunk0 + wave * 32 * TL, l32, h);
+    RowQuant rq[TL];
+    recon_load_rows<E, R, kI8, TL>(zb, rq, e, p, b, chunk0 + wave * 32 * TL, l32, h);
 
     const char* wl = static_cast<const char*>(e->d.wl);
     const int in_width = e->d.in_width;
@@ -203,6 +234,10 @@ __global__ __launch_bounds__(64 * kReconChunk / (32 * TL)) void recon_mfma_kerne
         __syncthreads();                           // the previous slice is no longer read
         recon_stage_matrix(lds, stride_w, wl + (size_t)col * 2, (size_t)in_width * 2, R, cpr, tid, NT);
         __syncthreads();
+        if constexpr (kI8) {
+            lds_column_sums<E>(colsum, lds, stride_w, R, dh, tid, NT);
+            __syncthreads();
+        }
         for (int mb = 0; mb < (dh >> 5); ++mb) {
             // A operand: row = decoder column 32 mb + l32, k-slots = latent indices 16s + 8h .. +7
             const char* wsrc = lds + (8 * h + (l16 >> 2)) * stride_w + (32 * mb + 16 * (l32 >> 4) + 4 * (l16 & 3)) * 2;
@@ -223,7 +258,7 @@ __global__ __launch_bounds__(64 * kReconChunk / (32 * TL)) void recon_mfma_kerne
                 const int t = chunk0 + wave * 32 * TL + tile * 32 + l32;
                 char* srow = stage ? stage + (tile * 32 + l32) * stride_o + (32 * mb + 4 * h) * 2 : nullptr;
                 char* orow = t < n_rows ? dst + ((((size_t)b * p->n_kv_heads + g) * n_rows + t) * dh + 32 * mb + 4 * h) * 2 : nullptr;
-                recon_emit_block<E>(acc[tile], e->d.bl, col + 32 * mb + 4 * h, out_scale, srow, orow);
+                recon_emit_block<E, kI8>(acc[tile], e->d.bl, col + 32 * mb + 4 * h, out_scale, srow, orow, colsum + 32 * mb + 4 * h, rq[tile]);
             }
         }
         if (stage) {
@@ -264,11 +299,17 @@ __global__ __launch_bounds__(64 * kReconChunk / (32 * TL)) void recon_mlp_mfma_k
     const float slope = e->d.slope;
 
     u32x4_t zb[TL][KS];
-    recon_load_rows<E, R, kI8, TL>(zb, e, p, b, chunk0 + wave * 32 * TL, l32, h);         // in flight while W1 is staged
+    RowQuant rq[TL];
+    recon_load_rows<E, R, kI8, TL>(zb, rq, e, p, b, chunk0 + wave * 32 * TL, l32, h);         // in flight while W1 is staged
     recon_stage_matrix(w1_lds, STRIDE1, static_cast<const char*>(e->d.w1), (size_t)C * 2, R, C / 8, tid, NT);
     float* b1s = reinterpret_cast<float*>(wl_lds + C * stride_w + (p->staged ? kReconChunk * stride_o : 0));      // [C] first-layer bias
+    float* cs1 = b1s + C;                                                                                           // [C] column sums of W1 (int8 rows)
     for (int i = tid; i < C; i += NT) b1s[i] = e->d.b1 ? Elem<E>::load(e->d.b1, i) : 0.f;
     __syncthreads();
+    if constexpr (kI8) {
+        lds_column_sums<E>(cs1, w1_lds, STRIDE1, R, C, tid, NT);
+        __syncthreads();
+    }
 
     // hidden rows of the wave's two tiles as B operands of the second product: [tile][block][k-step]
     u32x4_t hb[TL][CB][2];
@@ -296,16 +337,29 @@ __global__ __launch_bounds__(64 * kReconChunk / (32 * TL)) void recon_mlp_mfma_k
             for (int j = 0; j < 4; ++j) bias[4 * a + j] = b4[j];
         }
 #pragma unroll
-        for (int tile = 0; tile < TL; ++tile)
+        for (int tile = 0; tile < TL; ++tile) {
+            // pre-activations; int8 rows: the row's scale and zero point applied to the sums over its codes
+            float pre[16];
+            if constexpr (kI8) {
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const f32x4_t c4 = *reinterpret_cast<const f32x4_t*>(cs1 + 32 * cb + 8 * a + 4 * h);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) pre[4 * a + j] = fmaf(fmaf(-rq[tile].sub, c4[j], acc[tile][4 * a + j]), rq[tile].inv, bias[4 * a + j]);
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) pre[v] = acc[tile][v] + bias[v];
+            }
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 unsigned w[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    w[q] = Mma<E>::pack2(fast_act<ACT>(acc[tile][8 * s + 2 * q] + bias[8 * s + 2 * q], slope),
-                                         fast_act<ACT>(acc[tile][8 * s + 2 * q + 1] + bias[8 * s + 2 * q + 1], slope));
+                    w[q] = Mma<E>::pack2(fast_act<ACT>(pre[8 * s + 2 * q], slope), fast_act<ACT>(pre[8 * s + 2 * q + 1], slope));
                 hb[tile][cb][s] = u32x4_t{w[0], w[1], w[2], w[3]};
             }
+        }
     }
 
     const char* wl = static_cast<const char*>(e->d.wl);
@@ -339,7 +393,7 @@ __global__ __launch_bounds__(64 * kReconChunk / (32 * TL)) void recon_mlp_mfma_k
                 const int t = chunk0 + wave * 32 * TL + tile * 32 + l32;
                 char* srow = stage ? stage + (tile * 32 + l32) * stride_o + (32 * mb + 4 * h) * 2 : nullptr;
                 char* orow = t < n_rows ? dst + ((((size_t)b * p->n_kv_heads + g) * n_rows + t) * dh + 32 * mb + 4 * h) * 2 : nullptr;
-                recon_emit_block<E>(acc[tile], e->d.bl, col + 32 * mb + 4 * h, out_scale, srow, orow);
+                recon_emit_block<E, false>(acc[tile], e->d.bl, col + 32 * mb + 4 * h, out_scale, srow, orow, nullptr, RowQuant{1.f, 0.f});
             }
         }
         if (stage) {
@@ -381,9 +435,11 @@ bool recon_mfma_supported(const ReconParams& p, int dtype) {
 template <typename E, int R, bool kI8>
 static hipError_t launch_recon_one(const ReconParams& p, hipStream_t stream) {
     size_t lds = (size_t)R * (2 * p.d_head + 32);
+    const size_t sums = kI8 ? (size_t)p.d_head * sizeof(float) : 0;            // column sums of the decoder slice (int8 rows)
     ReconParams q = p;
-    q.staged = lds + recon_stage_bytes(p.d_head) <= kReconLdsMax ? 1 : 0;      // else the lanes store their 8-byte pieces themselves
+    q.staged = lds + recon_stage_bytes(p.d_head) + sums <= kReconLdsMax ? 1 : 0;      // else the lanes store their 8-byte pieces themselves
     if (q.staged) lds += recon_stage_bytes(p.d_head);
+    lds += sums;
     constexpr int TL = 2;               // four waves of 64 tokens (eight of 32 measured the same)
     auto k = recon_mfma_kernel<E, R, kI8, TL>;
     if (lds > 64 * 1024) {
@@ -418,9 +474,9 @@ template <typename E, int R, int C, int ACT, bool kI8>
 static hipError_t launch_recon_mlp_one(const ReconParams& p, hipStream_t stream) {
     size_t lds = (size_t)R * (2 * C + 32) + (size_t)C * (2 * p.d_head + 32);
     ReconParams q = p;
-    q.staged = lds + recon_stage_bytes(p.d_head) + C * sizeof(float) <= kReconLdsMax ? 1 : 0;
+    q.staged = lds + recon_stage_bytes(p.d_head) + 2 * C * sizeof(float) <= kReconLdsMax ? 1 : 0;
     if (q.staged) lds += recon_stage_bytes(p.d_head);
-    lds += C * sizeof(float);                                   // the first-layer bias in fp32
+    lds += 2 * C * sizeof(float);                               // the first-layer bias and the column sums of W1 in fp32
     constexpr int TL = 1;               // eight waves of 32 tokens: two waves per SIMD overlap their matrix and vector work
     auto k = recon_mlp_mfma_kernel<E, R, C, ACT, kI8, TL>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -531,7 +587,10 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
     const int i0 = qblk * TQ + wave * 32 * QB;  // first query token of this wave
 
     // queries as B operands: lane (token l32 of block qb, half h) holds components 16s + 8h .. +7 (the decoded keys
-    // carry scale * log2(e), so the score product comes out in log2 units)
+    // carry scale * log2(e), so the score product comes out in log2 units).  Decoded rows are fp16 (RowsOf), so both
+    // products run on the fp16 matrix instruction: a bf16 model's queries are converted here (saturating) and its
+    // probabilities are packed to fp16; only the output is rounded to the model dtype.
+    using W = F16;
     u32x4_t qB[QB][KS];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -541,6 +600,10 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
         for (int s = 0; s < KS; ++s) {
             u32x4_t v = {0u, 0u, 0u, 0u};
             if (i < p.t_new) v = *reinterpret_cast<const u32x4_t*>(qrow + 32 * s);
+            if constexpr (std::is_same<E, BF16>::value) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = Mma<F16>::pack2(sat_half(Mma<BF16>::unpack_lo(v[e])), sat_half(Mma<BF16>::unpack_hi(v[e])));
+            }
             qB[qb][s] = v;
         }
     }
@@ -616,7 +679,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
                 for (int ks = 0; ks < KS; ++ks) {
                     const u32x4_t ka = *reinterpret_cast<const u32x4_t*>(krow + 32 * kvb * G::kStrideK + ks * 32);
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) s[qb] = Mma32<E>::mfma(ka, qB[qb][ks], ks == 0 ? negm[qb] : s[qb]);
+                    for (int qb = 0; qb < QB; ++qb) s[qb] = Mma32<W>::mfma(ka, qB[qb][ks], ks == 0 ? negm[qb] : s[qb]);
                 }
 
                 u32x4_t pb[QB][2];
@@ -660,12 +723,12 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
                     // k-step s2 of the half: rows 16 s2 + 8(e/4) + 4h + e%4 = registers 8 s2 .. 8 s2 + 7
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2)
-                        pb[qb][s2] = u32x4_t{Mma<E>::pack2(e[8 * s2], e[8 * s2 + 1]), Mma<E>::pack2(e[8 * s2 + 2], e[8 * s2 + 3]),
-                                             Mma<E>::pack2(e[8 * s2 + 4], e[8 * s2 + 5]), Mma<E>::pack2(e[8 * s2 + 6], e[8 * s2 + 7])};
+                        pb[qb][s2] = u32x4_t{Mma<W>::pack2(e[8 * s2], e[8 * s2 + 1]), Mma<W>::pack2(e[8 * s2 + 2], e[8 * s2 + 3]),
+                                             Mma<W>::pack2(e[8 * s2 + 4], e[8 * s2 + 5]), Mma<W>::pack2(e[8 * s2 + 6], e[8 * s2 + 7])};
                     // the denominator sums the probabilities as rounded for the product (two chains of four pairs)
                     float la = 0.f, lb = 0.f;
 #pragma unroll
-                    for (int w = 0; w < 4; ++w) { la = PairSum<E>::add(la, pb[qb][0][w]); lb = PairSum<E>::add(lb, pb[qb][1][w]); }
+                    for (int w = 0; w < 4; ++w) { la = PairSum<W>::add(la, pb[qb][0][w]); lb = PairSum<W>::add(lb, pb[qb][1][w]); }
                     l_run[qb] += la + lb;
                 }
 
@@ -676,7 +739,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void prefill_mfma_kernel(PrefillParam
                     for (int db = 0; db < DB; ++db) {
                         const u32x4_t va = tr_pair32(vrow + (32 * kvb + 16 * s2) * G::kStrideV + db * 64, 8 * G::kStrideV);
 #pragma unroll
-                        for (int qb = 0; qb < QB; ++qb) acc[qb][db] = Mma32<E>::mfma(va, pb[qb][s2], acc[qb][db]);
+                        for (int qb = 0; qb < QB; ++qb) acc[qb][db] = Mma32<W>::mfma(va, pb[qb][s2], acc[qb][db]);
                     }
             }
         }

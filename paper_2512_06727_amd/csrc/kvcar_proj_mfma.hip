@@ -454,7 +454,7 @@ hipError_t launch_combine_mfma(const AttendParams& p, int dtype, hipStream_t str
     if (dtype == KVCAR_BF16) kern = deep ? combine_mfma_kernel<BF16, 8, 2, 16> : pf == 2 ? combine_mfma_kernel<BF16, 8, 2> : pf == 6 ? combine_mfma_kernel<BF16, 8, 6> : combine_mfma_kernel<BF16, 8, 0>;
     else kern = deep ? combine_mfma_kernel<F16, 8, 2, 16> : pf == 2 ? combine_mfma_kernel<F16, 8, 2> : pf == 6 ? combine_mfma_kernel<F16, 8, 6> : combine_mfma_kernel<F16, 8, 0>;
     const int slot = (dtype == KVCAR_BF16 ? 0 : 4) + (deep ? 3 : pf == 2 ? 1 : pf == 6 ? 2 : 0);
-    static bool attr[8] = {};
+    static AttrFlag attr[8] = {};
     if (!attr[slot]) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (err != hipSuccess) return err;

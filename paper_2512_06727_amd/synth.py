@@ -113,6 +113,11 @@ class Workload:
     policy: str = "P1"       # P1: latent shrinks with the stored heads; P2: full-width latent
     weight_std: float = 0.02
     seed: int = 0
+    # test knobs (inputs only): multipliers on the decoder's first- and last-layer weights (to drive a two-layer
+    # decoder's pre-activations over a chosen range), and a constant added to every latent column by the encoder's
+    # last bias, for keys and for values (latent rows with a large common offset)
+    dec_gain: Tuple[float, float] = (1.0, 1.0)
+    latent_offset: Optional[Tuple[float, float]] = None
 
     @property
     def d_kv(self) -> int:
@@ -220,6 +225,12 @@ def autoencoder(w: Workload, layer: int, which: int, reuse: Optional[np.ndarray]
                (mat(2, h, w.latent)[:, :latent].contiguous(), None if not with_bias else bias(2, w.latent)[:latent].contiguous())]
         dec = [(mat(3, w.latent, h)[:latent].contiguous(), bias(3, h)),
                (mat(1, h, d)[:, cols].contiguous(), None if not with_bias else bias(1, d)[cols].contiguous())]
+    if w.dec_gain != (1.0, 1.0):
+        dec[0] = (_round(dec[0][0] * w.dec_gain[0], w.dtype), dec[0][1])
+        dec[-1] = (_round(dec[-1][0] * w.dec_gain[1], w.dtype), dec[-1][1])
+    if w.latent_offset is not None and latent > 0:
+        b_last = enc[-1][1] if enc[-1][1] is not None else torch.zeros(latent)
+        enc[-1] = (enc[-1][0], _round(b_last + float(w.latent_offset[which]), w.dtype))
     return AEWeights(heads=heads, latent=latent, hidden=w.hidden, act=w.act, slope=0.01, enc=enc, dec=dec)
 
 

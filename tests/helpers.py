@@ -37,6 +37,21 @@ ABS_TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}       # max |gpu - oracle|
 REL_TOL = {"f32": 1e-4, "f16": 4e-3, "bf16": 2e-2}       # max |gpu - oracle| / max |oracle|
 
 
+MANTISSA_BITS = {"f32": 23, "f16": 10, "bf16": 7}
+
+
+def half_ulp(x, dtype):
+    """Half a unit in the last place of `dtype` at the magnitude of x: what the single rounding of an exact result
+    to the output dtype can move it by."""
+    return 0.5 * 2.0 ** (np.floor(np.log2(np.maximum(np.abs(x), 1e-300))) - MANTISSA_BITS[dtype])
+
+
+def elementwise_bound(want, dtype):
+    """Bound on |gpu - oracle| per element where outputs can be O(1) (the exact current-token row, a prompt token
+    that sees a handful of rows): the absolute tolerance plus the rounding of the result to the output dtype."""
+    return ABS_TOL[dtype] + half_ulp(want, dtype)
+
+
 def run_oracle(w, reuse=None, with_bias=False, gain=1.0, layers=None, latent_format="dtype"):
     """Prefill n_cached tokens, then n_steps decode steps (append at pos, attend over
     pos+1 tokens).  Returns (oracle, outputs[step][layer] as fp64 arrays)."""

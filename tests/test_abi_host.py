@@ -56,6 +56,15 @@ def test_create_validation():
     assert B.lib().kvcar_status_string(B.ERR_NOMEM) == b"KVCAR_ERR_NOMEM" and B.ERR_NOMEM == -9
 
 
+def test_create_rejects_shapes_whose_offsets_do_not_fit_16_bits():
+    """Query-head indices and decoder column offsets reach the kernels as 16-bit numbers."""
+    h = C.c_void_p()
+    for cfg in (B.Config(1, 64, 64, 512, 1, 8, B.BF16, 0.0), B.Config(1, 32768, 1, 16, 1, 8, B.BF16, 0.0)):   # 64 x 512 = 32768 columns; 32768 heads
+        assert B.lib().kvcar_create(C.byref(cfg), C.byref(h)) == B.ERR_UNSUPPORTED
+    assert B.lib().kvcar_create(C.byref(B.Config(1, 63, 63, 520, 1, 8, B.BF16, 0.0)), C.byref(h)) == B.OK   # 63 * 520 = 32760 columns
+    B.lib().kvcar_destroy(h)
+
+
 def test_reuse_resolution_matches_hand_table():
     ctx = make(n_layers=4)
     with pytest.raises(B.KVCARError) as e:

@@ -8,7 +8,7 @@ import torch
 from oracle import kvcar_oracle as O
 from paper_2512_06727_amd import synth
 from paper_2512_06727_amd.harness import Session
-from tests.helpers import ABS_TOL, REL_TOL, oracle_ae
+from tests.helpers import ABS_TOL, REL_TOL, elementwise_bound, oracle_ae
 
 pytestmark = pytest.mark.gpu
 
@@ -137,8 +137,7 @@ def run_prefill_fullsize(w, layers, seqs, tokens, gain):
             for i in tokens:
                 want = orc.decode_attention(n, q[b, i].double().numpy()[None], i + 1)[0]
                 err = np.abs(out[b, i] - want)
-                ulp = 2.0 ** -7 if w.dtype == "bf16" else 2.0 ** -10
-                assert (err <= ABS_TOL[w.dtype] + ulp * np.abs(want)).all(), (n, b, i, err.max())
+                assert (err <= elementwise_bound(want, w.dtype)).all(), (n, b, i, err.max())
                 assert err.max() <= REL_TOL[w.dtype] * np.abs(want).max(), (n, b, i, err.max(), np.abs(want).max())
 
 
@@ -169,7 +168,6 @@ def test_long_context_full_size_exact_row_and_ragged_lengths():
     ses.prefill(0, w.n_cached, chunk=max(1, (1 << 24) // (w.batch * w.d_kv)), layers=sorted(need))
     gen = torch.Generator().manual_seed(5)
     lens = torch.randint(w.n_cached // 2, w.n_cached + 1, (w.batch,), generator=gen, dtype=torch.int32)
-    ulp = 2.0 ** -7
     for n in layers:
         q = synth.queries(w, n, 0, gain=30.0)
         kc = synth.kv_tokens(w, n, 0, 0, w.batch, w.n_cached, w.n_cached + 1)[:, 0]
@@ -186,7 +184,7 @@ def test_long_context_full_size_exact_row_and_ragged_lengths():
             qb = q[b:b + 1].double().numpy()
             want = orc.decode_attention(n, qb, w.n_cached, k_cur=kc[b:b + 1].double().numpy(), v_cur=vc[b:b + 1].double().numpy())[0]
             err = np.abs(out_exact[b] - want)
-            assert (err <= ABS_TOL[w.dtype] + ulp * np.abs(want)).all(), ("exact", n, b, err.max())
+            assert (err <= elementwise_bound(want, w.dtype)).all(), ("exact", n, b, err.max())
             want = orc.decode_attention(n, qb, w.n_cached, seq_lens=np.array([int(lens[b])]))[0]
             err = np.abs(out_ragged[b] - want).max()
             assert err <= ABS_TOL[w.dtype] and err <= REL_TOL[w.dtype] * np.abs(want).max(), ("ragged", n, b, err)
@@ -225,9 +223,8 @@ def test_caches_larger_than_4_gib(fmt):
         got = ses.prefill_attention(n, qp.to(ses.dev, ses.tdt), 0).float().cpu().double().numpy()
         want = orc.prefill_attention(n, qp.double().numpy(), 0)
         err = np.abs(got - want)
-        ulp = 2.0 ** -7
         print(f"layer {n} prefill: max abs err {err.max():.3e}", flush=True)
-        assert np.isfinite(got).all() and (err <= ABS_TOL[big.dtype] + ulp * np.abs(want)).all()
+        assert np.isfinite(got).all() and (err <= elementwise_bound(want, big.dtype)).all()
 
 
 @pytest.mark.parametrize("fmt", ["dtype", "int8"])

@@ -135,3 +135,90 @@ def test_int8_bit_exact_on_exact_inputs(dtype):
     # constant rows dequantise to themselves up to the rounding of the scale, zero rows exactly
     np.testing.assert_allclose(orc.Z[(0, 0)][:, 5], 7.0, rtol=1e-7)
     np.testing.assert_array_equal(orc.Z[(0, 0)][:, 6], 0.0)
+
+
+def offset_rows_case(offsets, gain, session_kw_list, n_cached=300):
+    """TinyLlama-shaped bf16 model whose encoders add a constant to every latent column (keys: offsets[0], values:
+    offsets[1]), so that latent rows sit far from zero and their zero points are large; every seventh token is all
+    zeros, which makes its latent row constant (or zero, without an offset).  The oracle encodes and quantises; its
+    codes, scales and zero points are written into the library's caches (the documented layout), so that both sides
+    attend over identical int8 rows and the test isolates the attention kernels.  (Through the library's own encoder
+    the rows differ slightly: fp32 sums that start from a large bias lose the low bits the oracle's fp64 sums keep.)
+    Returns the workload, the oracle, its outputs and one GPU result per session setting."""
+    from paper_2512_06727_amd.harness import Session
+    from tests.helpers import build_oracle
+    w = C[2].scaled(n_layers=2, batch=2, n_cached=n_cached, n_steps=1, reuse="odd:1", latent_offset=offsets)
+    n = w.n_cached + 1
+    orc = build_oracle(w, latent_format="int8")
+    for layer in range(w.n_layers):
+        k, v = synth.kv_tokens(w, layer, 0, 0, w.batch, 0, n), synth.kv_tokens(w, layer, 1, 0, w.batch, 0, n)
+        k[:, 3::7], v[:, 3::7] = 0.0, 0.0
+        orc.encode_append(layer, k.double().numpy(), v.double().numpy(), 0)
+    q = [synth.queries(w, layer, 0, gain=gain) for layer in range(w.n_layers)]
+    want = {layer: orc.decode_attention(layer, q[layer].double().numpy(), n) for layer in range(w.n_layers)}
+    results = []
+    for skw in session_kw_list:
+        ses = Session(w, latent_format="int8", poison=True, **skw)
+        for layer in range(w.n_layers):
+            for which in (0, 1):
+                view = ses.quantized_view(layer, which)
+                if view is None:
+                    continue
+                codes, scale, zp = view
+                codes[:, :n].copy_(torch.from_numpy(orc.Q[(layer, which)][:, :n]))
+                scale[:, :n].copy_(torch.from_numpy(orc.Qscale[(layer, which)][:, :n]))
+                zp[:, :n].copy_(torch.from_numpy(orc.Qzero[(layer, which)][:, :n]))
+        got = {layer: ses.decode_attention(layer, q[layer].to(ses.dev, ses.tdt), n).float().cpu().double().numpy() for layer in range(w.n_layers)}
+        torch.cuda.synchronize()
+        results.append((ses, got))
+    return w, orc, want, results
+
+
+def assert_within(got, want, dtype, label):
+    """Outputs here reach the thousands (value rows with a common offset).  Per element: the absolute tolerance, the
+    rounding of the output to its dtype, and 2^-12 of the value for what precedes that rounding - the softmax weights
+    enter the matrix product as fp16 numbers (relative rounding 2^-12 each), which a weighted sum of equal-signed
+    rows inherits and which decides the direction of the final rounding near a midpoint."""
+    from tests.helpers import REL_TOL, elementwise_bound
+    assert np.isfinite(got).all(), label
+    err = np.abs(got - want)
+    excess = err - (elementwise_bound(want, dtype) + 2.0 ** -12 * np.abs(want))
+    i = np.unravel_index(np.argmax(excess), excess.shape)
+    assert excess[i] <= 0, f"{label}: |{got[i]:.6g} - {want[i]:.6g}| = {err[i]:.3e} exceeds the bound by {excess[i]:.3e}"
+    assert err.max() <= REL_TOL[dtype] * np.abs(want).max(), f"{label}: max err {err.max():.3e} vs max |ref| {np.abs(want).max():.3e}"
+
+
+MFMA_FORMS = [{"n_splits": 1, "wg_waves": 4}, {"n_splits": 1, "wg_waves": 8}, {"n_splits": 3}]
+
+
+@pytest.mark.parametrize("offsets,zp_decade", [((0.0, 0.0), 1e2), ((8.0, 0.0), 1e3), ((96.0, 2.0), 1e4), ((0.0, 1024.0), 1e5),
+                                               ((4096.0, 4096.0), 1e6), ((24576.0, 0.0), 4e6)])
+def test_int8_rows_far_from_zero_through_the_mfma_kernel(offsets, zp_decade):
+    """The matrix-core kernel over int8 rows feeds codes, 1/scale and the zero point to fp16 operands and states
+    |zeropoint| < 2^23: rows with zero points from 1e2 to 6e6, constant rows and zero rows, in its fused (four and
+    eight waves) and split forms and on the plain-ALU kernels, against the oracle.  Value rows with a large common
+    offset give outputs of that size: the bound is the tolerance plus the rounding of the output to its dtype."""
+    forms = MFMA_FORMS + [{"force_generic": True}]
+    w, orc, want, results = offset_rows_case(offsets, 8.0, forms)
+    zmax = max(int(np.abs(orc.Qzero[(0, which)][:, :w.n_cached + 1]).max()) for which in (0, 1))
+    assert zp_decade / 4 < zmax < 4 * zp_decade and zmax < 2 ** 23, zmax          # the inputs are what the case claims
+    const_rows = orc.Z[(0, 0)][:, 3:w.n_cached + 1:7]
+    assert (const_rows.max(axis=-1) == const_rows.min(axis=-1)).all()             # constant (or zero) latent rows are present
+    for (ses, got), skw in zip(results, forms):
+        assert ses.ctx.describe_plan(1, w.batch, w.n_cached + 1).uses_mfma == (0 if "force_generic" in skw else 1)
+        for layer in want:
+            assert_within(got[layer], want[layer], w.dtype, f"{offsets} {skw} layer {layer}")
+
+
+def test_int8_rows_beyond_the_mfma_kernels_limits_take_the_plain_alu_kernels():
+    """Zero points beyond 2^23 (a latent row 65536 away from zero with a range of about 2) are outside what the
+    matrix-core kernel's fp16 operands hold: it saturates them, so its result is finite but not the method's.
+    Callers whose latents can look like this set kvcar_tuning.force_generic: the plain-ALU kernels dequantise in fp32
+    (exact up to |zeropoint| = 2^24)."""
+    w, orc, want, results = offset_rows_case((65536.0, 0.0), 4.0, [{"force_generic": True}, {"n_splits": 1}], n_cached=120)
+    zmax = int(np.abs(orc.Qzero[(0, 0)][:, :w.n_cached + 1]).max())
+    assert 2 ** 23 < zmax < 2 ** 24, zmax
+    (_, got_alu), (_, got_mfma) = results
+    for layer in want:
+        assert_within(got_alu[layer], want[layer], w.dtype, f"plain-ALU kernels, layer {layer}")
+        assert np.isfinite(got_mfma[layer]).all()

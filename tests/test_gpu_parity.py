@@ -45,8 +45,6 @@ CASES = {
 @pytest.mark.parametrize("gain", [1.0, 50.0])
 def test_parity(name, gain):
     w, kw = CASES[name]
-    if gain != 1.0 and w.dtype == "f32" and name != "c0-exact":
-        pytest.skip("sharp case covered by c0")
     print(f"case {name} gain {gain} {w}", flush=True)
     orc, want = run_oracle(w, gain=gain, **kw)
     ses, got = run_gpu(w, gain=gain, **kw)
@@ -150,3 +148,34 @@ def test_many_source_layers_need_several_launches(force_generic):
     assert plan.n_groups == 12 and plan.n_launches == 2
     assert [ses.ctx.resolve_source(11, 0, g) for g in range(12)] == list(range(12))
     assert_outputs_close(w, got, want, label=f"12 sources, force_generic={force_generic}")
+
+
+@pytest.mark.parametrize("gain", [1.0, 8.0])
+@pytest.mark.parametrize("variant", ["gelu-bf16", "gelu-f16-narrow", "gelu-bf16-int8"])
+def test_gelu_decoder_over_its_whole_range(variant, gain):
+    """Two-layer GELU decoders whose pre-activations reach |x| = 8, far into both tails (the benchmark weights keep
+    them below 0.1, where GELU is almost linear): first-layer weights 200 times larger, last-layer weights smaller so
+    that decoded rows keep their usual size.  Decode step (the matrix-core kernel that rebuilds hidden rows per tile)
+    and prefill attention (the kernel that decodes rows once) against the oracle's erf form."""
+    from paper_2512_06727_amd.harness import Session
+    from tests.helpers import REL_TOL, elementwise_bound
+    over = {"gelu-bf16": {}, "gelu-f16-narrow": dict(dtype="f16", latent=64, hidden=128, dec_gain=(380.0, 0.35)), "gelu-bf16-int8": {}}[variant]
+    fmt = "int8" if variant.endswith("int8") else "dtype"
+    w = C[3].scaled(n_layers=2, batch=2, n_cached=150, n_steps=1, **{**dict(dec_gain=(200.0, 0.25), reuse="odd:1", policy="P2"), **over})
+    print(f"case {variant} gain {gain} {w}", flush=True)
+    orc, want = run_oracle(w, gain=gain, with_bias=True, latent_format=fmt)
+    # the inputs really span the range: decoder pre-activations of the cached rows, from the oracle's latents
+    for which in (0, 1):
+        w1, b1 = orc.ae[(0, which)].dec[0]
+        pre = orc.Z[(0, which)][:, :w.n_cached + 1] @ w1 + b1
+        assert 6.0 < np.abs(pre).max() < 16.0 and (np.abs(pre) > 4.0).mean() > 0.02 and (np.abs(pre) < 1.0).mean() > 0.1, (np.abs(pre).max(), pre.std())
+    ses, got = run_gpu(w, gain=gain, with_bias=True, latent_format=fmt)
+    assert ses.ctx.describe_plan(1, w.batch, w.n_cached + 1).uses_mfma == 1
+    assert_outputs_close(w, got, want, f"{variant} decode")
+    n_rows = w.n_cached + 1
+    q = synth.prompt_queries(w, 1, 0, w.batch, 0, n_rows, gain=gain)
+    want_p = orc.prefill_attention(1, q.double().numpy(), 0)
+    got_p = ses.prefill_attention(1, q.to(ses.dev, ses.tdt), 0).float().cpu().double().numpy()
+    err = np.abs(got_p - want_p)
+    assert np.isfinite(got_p).all() and (err <= elementwise_bound(want_p, w.dtype)).all(), f"{variant} prefill: max abs err {err.max():.3e}"
+    assert err.max() <= REL_TOL[w.dtype] * np.abs(want_p).max()

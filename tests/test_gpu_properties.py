@@ -80,3 +80,39 @@ def test_plain_alu_and_mfma_kernels_agree():
         q = synth.queries(w, 4, 0, gain=25.0).to(ses.dev, ses.tdt)
         outs.append(ses.decode_attention(4, q, 700).float().cpu().double().numpy())
     assert np.abs(outs[0] - outs[1]).max() <= REL_TOL[w.dtype] * np.abs(outs[1]).max()
+
+
+def test_two_host_threads_with_their_own_contexts_and_streams():
+    """Two host threads, each with its own context and stream, run decode steps at the same time (the launchers'
+    once-per-process kernel attributes are set from whichever thread comes first): both must match the oracle."""
+    import threading
+    from paper_2512_06727_amd import synth
+    from paper_2512_06727_amd.harness import Session
+    from tests.helpers import assert_outputs_close, run_oracle
+    ws = [synth.CONFIGS[2].scaled(n_layers=3, batch=2, n_cached=150, n_steps=1, seed=11),
+          synth.CONFIGS[1].scaled(n_layers=2, batch=2, n_cached=120, n_steps=1, seed=12)]
+    wants = [run_oracle(w, gain=8.0)[1] for w in ws]
+    got, errors = [None, None], []
+
+    def work(i):
+        try:
+            w = ws[i]
+            with torch.cuda.stream(torch.cuda.Stream()):
+                ses = Session(w)
+                ses.prefill(0, w.n_cached + 1, chunk=64)
+                row = {}
+                for n in range(w.n_layers):
+                    q = synth.queries(w, n, 0, gain=8.0).to(ses.dev, ses.tdt)
+                    row[n] = ses.decode_attention(n, q, w.n_cached + 1).float().cpu().double().numpy()
+                got[i] = [row]
+        except Exception as e:          # surfaced below: an exception in a thread would otherwise be lost
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for w, g, want in zip(ws, got, wants):
+        assert_outputs_close(w, g, want, w.name)

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from paper_2512_06727_amd import synth
-from tests.helpers import (ABS_TOL, REL_TOL, assert_cache_close, assert_outputs_close, assert_quantized_cache_close, build_oracle, oracle_prefill,
+from tests.helpers import (ABS_TOL, REL_TOL, elementwise_bound, assert_cache_close, assert_outputs_close, assert_quantized_cache_close, build_oracle, oracle_prefill,
                            run_gpu, run_oracle)
 
 pytestmark = pytest.mark.gpu
@@ -33,10 +33,7 @@ def draw_cases(n, seed=20251206, matrix_core=False):
         w = synth.Workload(f"sweep{i}{'m' if matrix_core else ''}", n_layers=int(rng.integers(2, 4)), n_q_heads=n_kv * group, n_kv_heads=n_kv, d_head=d_head,
                            batch=int(rng.integers(1, 4)), n_cached=int(rng.integers(0, 261)), n_steps=int(rng.integers(1, 3)),
                            dtype=dtype, latent=latent, hidden=hidden, act=act,
-                           reuse=pick(["none", "odd:1", "bernoulli:0.3", "bernoulli:0.6"]), policy=pick(["P1", "P1", "P2"]), seed=100 + i,
-                           # the absolute tolerance is meant for latents and decoded rows of the size the benchmark shapes
-                           # give (weights N(0, 0.02^2) at D_kv = 256): wider layers draw proportionally smaller weights
-                           weight_std=0.02 * min(1.0, (256.0 / (n_kv * d_head)) ** 0.5))
+                           reuse=pick(["none", "odd:1", "bernoulli:0.3", "bernoulli:0.6"]), policy=pick(["P1", "P1", "P2"]), seed=100 + i)
         kw = {"with_bias": bool(rng.integers(2)), "latent_format": fmt, "gain": pick([1.0, 8.0, 40.0])}
         cases.append((w, kw))
     return cases
@@ -59,16 +56,13 @@ def test_shape_sweep(i):
     assert_outputs_close(w, got, want, f"sweep {i}")
 
 
-ULP_REL = {"f32": 2.0 ** -23, "f16": 2.0 ** -10, "bf16": 2.0 ** -7}
-
-
 def check(w, got, want, label):
-    """Absolute tolerance plus one unit in the last place of the reference (outputs of O(1) where the exact current
+    """Absolute tolerance plus half a unit in the last place of the reference (outputs of O(1) where the exact current
     row or a single value row dominates carry the rounding of the result to the dtype)."""
     assert got.shape == want.shape and np.isfinite(got).all(), label
     err = np.abs(got - want)
-    worst = (err - (ABS_TOL[w.dtype] + ULP_REL[w.dtype] * np.abs(want))).max()
-    assert worst <= 0, f"{label}: error exceeds abs tol + 1 ulp by {worst:.3e}"
+    worst = (err - elementwise_bound(want, w.dtype)).max()
+    assert worst <= 0, f"{label}: error exceeds abs tol + half an ulp by {worst:.3e}"
     assert err.max() <= REL_TOL[w.dtype] * np.abs(want).max(), f"{label}: err {err.max():.3e} vs max |ref| {np.abs(want).max():.3e}"
 
 
