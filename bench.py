@@ -9,7 +9,10 @@ Bernoulli(0.3) head-reuse map).  Inputs are synthetic and resident in HBM before
 
 Prints ONE JSON line: tokens/s of the whole job, the HBM roofline of the dominant kernel (the
 MFMA attention kernel, timed live with HIP events recorded around it on its stream in a second
-pass over the same steps) and the CPU oracle timed on a bounded sample of the same workload.
+pass over the same steps), the CPU oracle timed on a bounded sample of the same workload, and -
+in the default run - a `workloads` block with the other four configurations at their full sizes
+(ms per step, tokens/s, the attention kernel against the HBM peak; the two-layer configuration
+also against the MFMA peak).
 """
 from __future__ import annotations
 
@@ -24,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+MFMA_PEAK_TFLOPS = 2500.0    # MI355X published dense bf16 / fp16 matrix rate
 
 
 def sources(reuse, layer, which):
@@ -50,9 +54,11 @@ def algorithmic_latent_bytes(w, reuse, widths, batch, n_ctx, elem, row_meta=0):
     return per_layer
 
 
-def cpu_baseline(w, reuse, budget_s: float):
-    """The CPU oracle timed on (layer, sequence) units of the same workload: full-length
-    context, one sequence at a time.  Returns tokens/s extrapolated to the whole job."""
+def cpu_baseline(w, reuse, budget_s: float, n_steps: int = 1):
+    """The CPU oracle timed on (layer, sequence, step) units of the same workload: full-length context, one
+    sequence at a time.  Units are taken in an order that covers, first, the first and the last layer and one
+    layer of every reuse-chain depth at the first and at the last decode step, then further (layer, sequence)
+    pairs up to 96 units or the time budget.  Returns tokens/s extrapolated to the whole job."""
     import numpy as np
     import torch
     from threadpoolctl import threadpool_info
@@ -60,41 +66,62 @@ def cpu_baseline(w, reuse, budget_s: float):
     from paper_2512_06727_amd import synth
 
     wo = w.scaled(batch=1)
-    orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, 1, w.max_seq, w.dtype)
-    for layer in range(w.n_layers):
-        orc.set_reuse_map(layer, reuse[layer, 0], reuse[layer, 1])
     cv = lambda pairs: [(a.double().numpy(), None if b is None else b.double().numpy()) for a, b in pairs]
-    for layer in range(w.n_layers):
-        for which in (0, 1):
-            ae = synth.autoencoder(w, layer, which, reuse)
+    aes = {(layer, which): synth.autoencoder(w, layer, which, reuse) for layer in range(w.n_layers) for which in (0, 1)}
+
+    def new_oracle():
+        orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, 1, w.max_seq, w.dtype)
+        for layer in range(w.n_layers):
+            orc.set_reuse_map(layer, reuse[layer, 0], reuse[layer, 1])
+        for (layer, which), ae in aes.items():
             orc.set_autoencoder(layer, which, O.Autoencoder(ae.heads, cv(ae.enc), cv(ae.dec), act=ae.act, slope=ae.slope))
-    # untimed: fill the sequence's caches (prefill is not part of the timed decode step)
-    n_ctx = w.n_cached + 1
-    order = [0, w.n_layers - 1] + list(range(1, w.n_layers - 1))
-    filled = set()
-    t_used, units = 0.0, 0
-    for layer in order:
+        return orc
+
+    # chain depth of a layer: how far back its farthest source lies
+    depth = [max(layer - m for which in (0, 1) for m in sources(reuse, layer, which)) for layer in range(w.n_layers)]
+    by_depth = {}
+    for layer, d in enumerate(depth):
+        by_depth.setdefault(d, layer)
+    first_layers = list(dict.fromkeys([0, w.n_layers - 1] + list(by_depth.values())))
+    last_step = max(0, n_steps - 1)
+    seqs = list(dict.fromkeys([0, w.batch - 1, w.batch // 2, w.batch // 3]))
+    units = [(layer, seqs[0], st) for layer in first_layers for st in dict.fromkeys([0, last_step])]
+    for b in seqs:
+        units += [(layer, b, 0 if (layer + b) % 2 == 0 else last_step) for layer in range(w.n_layers)]
+    units = list(dict.fromkeys(units))[:96]
+
+    t_used, done, covered = 0.0, 0, set()
+    orc, orc_b, filled = None, None, {}
+    for layer, b, st in units:
+        if orc_b != b:
+            orc, orc_b, filled = new_oracle(), b, {}
+        n_ctx = w.n_cached + st + 1
         need = {layer} | set(sources(reuse, layer, 0)) | set(sources(reuse, layer, 1))
-        for m in sorted(need - filled):
-            k = synth.kv_tokens(wo, m, 0, 0, 1, 0, w.n_cached).double().numpy()
-            v = synth.kv_tokens(wo, m, 1, 0, 1, 0, w.n_cached).double().numpy()
-            orc.encode_append(m, k, v, 0)
-            filled.add(m)
-        k1 = synth.kv_tokens(wo, layer, 0, 0, 1, w.n_cached, n_ctx).double().numpy()
-        v1 = synth.kv_tokens(wo, layer, 1, 0, 1, w.n_cached, n_ctx).double().numpy()
-        q = synth.queries(wo, layer, 0).double().numpy()
+        for m in sorted(need):                       # untimed: the sequence's cached rows up to this step (prefill is not part of the step)
+            have = filled.get(m, 0)
+            upto = n_ctx if m != layer else n_ctx - 1
+            if have < upto:
+                orc.encode_append(m, synth.kv_tokens(wo, m, 0, b, b + 1, have, upto).double().numpy(),
+                                  synth.kv_tokens(wo, m, 1, b, b + 1, have, upto).double().numpy(), have)
+                filled[m] = upto
+        k1 = synth.kv_tokens(wo, layer, 0, b, b + 1, n_ctx - 1, n_ctx).double().numpy()
+        v1 = synth.kv_tokens(wo, layer, 1, b, b + 1, n_ctx - 1, n_ctx).double().numpy()
+        q = synth.queries(w, layer, st)[b:b + 1].double().numpy()
         t0 = time.perf_counter()
-        orc.encode_append(layer, k1, v1, w.n_cached)          # timed: one decode step of one (layer, sequence)
+        orc.encode_append(layer, k1, v1, n_ctx - 1)           # timed: one decode step of one (layer, sequence)
         orc.decode_attention(layer, q, n_ctx)
         t_used += time.perf_counter() - t0
-        units += 1
+        filled[layer] = max(filled.get(layer, 0), n_ctx)
+        done += 1
+        covered.add((depth[layer], st))
         if t_used > budget_s:
             break
-    per_unit = t_used / units
+    per_unit = t_used / done
     step_s = per_unit * w.n_layers * w.batch                  # extrapolated to all layers and sequences
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [torch.get_num_threads(), 1])
     return {"value": w.batch / step_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{units} (layer, sequence) units of one decode step at n_ctx={n_ctx}, "
+            "sample": f"{done} (layer, sequence, step) units of one decode step at n_ctx={w.n_cached + 1}..{w.n_cached + last_step + 1} "
+                      f"(first and last layer, reuse-chain depths {sorted({d for d, _ in covered})}, decode steps {sorted({t for _, t in covered})}), "
                       f"{per_unit * 1e3:.1f} ms each, extrapolated to {w.n_layers} layers x {w.batch} sequences"}
 
 
@@ -158,7 +185,6 @@ def bench_l1_distance(args):
     }))
 
 
-MFMA_PEAK_TFLOPS = 2500.0    # MI355X published dense bf16 / fp16 matrix rate
 
 
 def bench_prefill(args):
@@ -406,6 +432,171 @@ def capacity_check(args):
     }))
 
 
+def kernel_source_hash() -> str:
+    """sha256 over the library's sources (csrc/ and the public header): what a committed profile was taken with."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2512_06727_amd", "csrc")
+    for name in sorted(os.listdir(csrc)) + ["../../include/kvcar.h"]:
+        if name.endswith((".hip", ".hpp", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def attention_flops_per_token(w) -> int:
+    """Algorithmic flops of the attention kernel per cached token and layer: scores and weighted sums over the
+    contraction width (the latent, or the hidden width of a two-layer decoder), plus, for a two-layer decoder, the
+    rebuild of the K and V hidden rows."""
+    c = w.hidden if w.hidden else w.latent
+    return 2 * 2 * w.n_q_heads * c + (2 * 2 * w.latent * w.hidden if w.hidden else 0)
+
+
+def roofline_entry(w, m, latent_format):
+    """Roofline object of the attention kernel of one measured workload: achieved = algorithmic latent bytes per
+    launch / average launch time (HIP events around the kernel on its stream) against the HBM peak; two-layer
+    decoders (matrix work per byte near the ridge) also against the dense 16-bit MFMA peak."""
+    plan = m["plan"]
+    achieved = m["alg_bytes"] / (m["attend_ms"] * 1e-3) / 1e9
+    kernel = "attend_generic_kernel"
+    if plan.uses_mfma:
+        kernel = "attend_mlp_mfma_kernel" if w.hidden else "attend_i8_mfma_r128_kernel" if latent_format == "int8" else "attend_mfma_kernel"
+    r = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+         "traffic": None, "algorithmic_bytes_per_launch": m["alg_bytes"] / max(1, m["n_launch"]),
+         "avg_launch_ms": m["attend_ms"] / max(1, m["n_launch"]), "launches": m["n_launch"],
+         "whole_step_GBs": m["alg_bytes"] / m["steps"] / (m["ms_per_step"] * 1e-3) / 1e9}
+    if w.hidden and plan.uses_mfma:
+        tf = m["alg_flops"] / (m["attend_ms"] * 1e-3) / 1e12
+        r["mfma"] = {"achieved": tf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS,
+                     "algorithmic_flops_per_launch": m["alg_flops"] / max(1, m["n_launch"])}
+    return r
+
+
+def measure_decode(w, args, steps, warmup, graph=True, plain=False):
+    """Times `steps` decode steps of workload `w` (after `warmup`), then the same steps again with HIP events around
+    the attention kernel.  `plain`: library defaults, model-dtype latents and the cache-only variant whatever the
+    command line says (the extra workloads of the default run)."""
+    import torch
+    from paper_2512_06727_amd import synth
+    from paper_2512_06727_amd.harness import Session
+
+    total_steps = steps + warmup
+    latent = "dtype" if plain else args.latent
+    variant = "cache" if plain else args.variant
+    fill = "encode" if plain else args.fill
+    reuse = synth.reuse_map(w)
+    elem = synth.DTYPE_BYTES[w.dtype]
+    kw = {} if plain else dict(n_splits=args.splits, tile_order=args.tile_order, wg_waves=args.wg_waves, no_fuse=args.no_fuse)
+    ses = Session(w, reuse=reuse, latent_format=latent, **kw)
+    lat_elem, row_meta = (1, 8) if latent == "int8" else (elem, 0)
+    dev, tdt = ses.dev, ses.tdt
+    widths = [[ses.ae[n][which].latent for which in (0, 1)] for n in range(w.n_layers)]
+    t_fill = time.perf_counter()
+    if fill == "encode":
+        ses.prefill(0, w.n_cached, chunk=max(1, (1 << 25) // (w.batch * w.d_kv)))
+    else:
+        torch.manual_seed(w.seed)
+        for n, row in enumerate(ses.caches):
+            for which, c in enumerate(row):
+                if c is None:
+                    continue
+                if latent == "int8":
+                    codes, scale, zp = ses.quantized_view(n, which)
+                    codes.view(torch.uint8).random_(0, 256)
+                    scale.fill_(127.5)
+                    zp.random_(-8, 9)
+                else:
+                    c.normal_(0.0, 0.32)
+    torch.cuda.synchronize()
+    t_fill = time.perf_counter() - t_fill
+
+    # inputs of every step, resident in HBM before timing
+    qs, ks, vs = [], [], []
+    for step in range(total_steps):
+        pos = w.n_cached + step
+        if fill == "encode":
+            qs.append([synth.queries(w, n, step, device=dev).to(tdt) for n in range(w.n_layers)])
+            ks.append([synth.kv_tokens(w, n, 0, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)])
+            vs.append([synth.kv_tokens(w, n, 1, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)])
+        else:
+            qs.append([torch.randn(w.batch, w.n_q_heads, w.d_head, device=dev).to(tdt) for n in range(w.n_layers)])
+            ks.append([torch.randn(w.batch, 1, w.d_kv, device=dev).to(tdt) for n in range(w.n_layers)])
+            vs.append([torch.randn(w.batch, 1, w.d_kv, device=dev).to(tdt) for n in range(w.n_layers)])
+    outs = [torch.empty_like(qs[0][n]) for n in range(w.n_layers)]
+    ses.ensure_workspace(w.batch, w.max_seq)
+    ctx, ws = ses.ctx, ses.workspace
+
+    seq_lens = None
+    if variant == "ragged":
+        gen = torch.Generator(device="cpu").manual_seed(w.seed)
+        seq_lens = torch.randint(w.n_cached // 2, w.n_cached + 1, (w.batch,), generator=gen, dtype=torch.int32).to(dev)
+
+    def step_fn(step):
+        pos = w.n_cached + step
+        for n in range(w.n_layers):
+            if variant == "exact":
+                kc, vc = ks[step][n].view(w.batch, w.d_kv), vs[step][n].view(w.batch, w.d_kv)
+                ctx.decode_attention_ex(n, qs[step][n], outs[n], w.batch, pos, ws, k_cur=kc, v_cur=vc)
+                ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
+            elif variant == "ragged":
+                ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
+                ctx.decode_attention_ex(n, qs[step][n], outs[n], w.batch, pos + 1, ws, seq_lens=seq_lens)
+            else:
+                ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
+                ctx.decode_attention(n, qs[step][n], outs[n], w.batch, pos + 1, ws)
+
+    for step in range(warmup):
+        step_fn(step)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for step in range(warmup, total_steps):
+        step_fn(step)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / steps * 1e3
+    tokens_per_s = w.batch * steps / elapsed
+
+    # the same step as a HIP graph: captured once at the last step's positions, replayed `steps` times
+    graph_ms = None
+    if graph:
+        last = total_steps - 1
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step_fn(last)                                  # every kernel has run once on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step_fn(last)
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / steps * 1e3
+        del g
+
+    # second pass over the same steps with HIP events around the attention kernel
+    ctx.profile_enable(True)
+    for step in range(warmup, total_steps):
+        step_fn(step)
+    attend_ms, n_launch = ctx.profile_read()
+    ctx.profile_enable(False)
+    alg, flops = 0, 0
+    for step in range(warmup, total_steps):
+        n_rows = w.n_cached + step + (0 if variant == "exact" else 1)
+        if seq_lens is not None:                      # ragged: bytes of the rows each sequence really reads
+            alg += sum(algorithmic_latent_bytes(w, reuse, widths, 1, int(seq_lens.sum().item()), lat_elem, row_meta))
+        else:
+            alg += sum(algorithmic_latent_bytes(w, reuse, widths, w.batch, n_rows, lat_elem, row_meta))
+        flops += attention_flops_per_token(w) * w.batch * n_rows * w.n_layers
+    return {"reuse": reuse, "widths": widths, "ms_per_step": ms_per_step, "tokens_per_s": tokens_per_s, "graph_ms": graph_ms,
+            "attend_ms": attend_ms, "n_launch": n_launch, "alg_bytes": alg, "alg_flops": flops, "steps": steps, "prefill_s": t_fill,
+            "plan": ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -419,7 +610,8 @@ def main():
     ap.add_argument("--policy", default="", help="P1 (latent shrinks with stored heads) or P2 (full width)")
     ap.add_argument("--no-reuse", action="store_true")
     ap.add_argument("--act", default="", help="override the activation of a two-layer autoencoder (gelu | leaky_relu)")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle leg; 0 skips it")
+    ap.add_argument("--cpu-seconds", type=float, default=30.0, help="time budget of the CPU-oracle leg (up to 96 units); 0 skips it")
+    ap.add_argument("--no-workloads", action="store_true", help="default run only: skip the block with the other four configurations")
     ap.add_argument("--fill", default="encode", choices=["encode", "random"],
                     help="encode: caches filled by kvcar_encode_append of seeded K/V (default); random: torch.randn latents and "
                          "inputs (profiling runs only: same traffic, far fewer helper kernels)")
@@ -462,8 +654,7 @@ def main():
     if args.per_head:
         return bench_per_head(args)
     base = synth.CONFIGS[args.workload]
-    total_steps = args.steps + args.warmup
-    w = base.scaled(n_steps=total_steps)
+    w = base.scaled(n_steps=args.steps + args.warmup)
     if args.batch:
         w = w.scaled(batch=args.batch)
     if args.cached:
@@ -474,122 +665,24 @@ def main():
         w = w.scaled(reuse="none")
     if args.act:
         w = w.scaled(act=args.act)
-    reuse = synth.reuse_map(w)
-    elem = synth.DTYPE_BYTES[w.dtype]
-
-    ses = Session(w, reuse=reuse, n_splits=args.splits, tile_order=args.tile_order, latent_format=args.latent, wg_waves=args.wg_waves, no_fuse=args.no_fuse)
+    m = measure_decode(w, args, args.steps, args.warmup, graph=not args.no_graph)
+    reuse, elem = m["reuse"], synth.DTYPE_BYTES[w.dtype]
     lat_elem, row_meta = (1, 8) if args.latent == "int8" else (elem, 0)
-    dev, tdt = ses.dev, ses.tdt
-    widths = [[ses.ae[n][which].latent for which in (0, 1)] for n in range(w.n_layers)]
-    t_fill = time.perf_counter()
-    if args.fill == "encode":
-        ses.prefill(0, w.n_cached, chunk=max(1, (1 << 25) // (w.batch * w.d_kv)))
-    else:
-        torch.manual_seed(w.seed)
-        for n, row in enumerate(ses.caches):
-            for which, c in enumerate(row):
-                if c is None:
-                    continue
-                if args.latent == "int8":
-                    codes, scale, zp = ses.quantized_view(n, which)
-                    codes.view(torch.uint8).random_(0, 256)
-                    scale.fill_(127.5)
-                    zp.random_(-8, 9)
-                else:
-                    c.normal_(0.0, 0.32)
-    torch.cuda.synchronize()
-    t_fill = time.perf_counter() - t_fill
+    dev = torch.device("cuda:0")
 
-    # inputs of every step, resident in HBM before timing
-    qs, ks, vs = [], [], []
-    for step in range(total_steps):
-        pos = w.n_cached + step
-        if args.fill == "encode":
-            qs.append([synth.queries(w, n, step, device=dev).to(tdt) for n in range(w.n_layers)])
-            ks.append([synth.kv_tokens(w, n, 0, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)])
-            vs.append([synth.kv_tokens(w, n, 1, 0, w.batch, pos, pos + 1, device=dev).to(tdt) for n in range(w.n_layers)])
-        else:
-            qs.append([torch.randn(w.batch, w.n_q_heads, w.d_head, device=dev).to(tdt) for n in range(w.n_layers)])
-            ks.append([torch.randn(w.batch, 1, w.d_kv, device=dev).to(tdt) for n in range(w.n_layers)])
-            vs.append([torch.randn(w.batch, 1, w.d_kv, device=dev).to(tdt) for n in range(w.n_layers)])
-    outs = [torch.empty_like(qs[0][n]) for n in range(w.n_layers)]
-    ses.ensure_workspace(w.batch, w.max_seq)
-    ctx, ws = ses.ctx, ses.workspace
-
-    seq_lens = None
-    if args.variant == "ragged":
-        gen = torch.Generator(device="cpu").manual_seed(w.seed)
-        seq_lens = torch.randint(w.n_cached // 2, w.n_cached + 1, (w.batch,), generator=gen, dtype=torch.int32).to(dev)
-
-    def step_fn(step):
-        pos = w.n_cached + step
-        for n in range(w.n_layers):
-            if args.variant == "exact":
-                kc, vc = ks[step][n].view(w.batch, w.d_kv), vs[step][n].view(w.batch, w.d_kv)
-                ctx.decode_attention_ex(n, qs[step][n], outs[n], w.batch, pos, ws, k_cur=kc, v_cur=vc)
-                ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
-            elif args.variant == "ragged":
-                ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
-                ctx.decode_attention_ex(n, qs[step][n], outs[n], w.batch, pos + 1, ws, seq_lens=seq_lens)
-            else:
-                ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
-                ctx.decode_attention(n, qs[step][n], outs[n], w.batch, pos + 1, ws)
-
-    for step in range(args.warmup):
-        step_fn(step)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for step in range(args.warmup, total_steps):
-        step_fn(step)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-    tokens_per_s = w.batch * args.steps / elapsed
-
-    # the same step as a HIP graph: captured once at the last step's positions, replayed `steps` times
-    graph_ms = None
-    if not args.no_graph:
-        last = total_steps - 1
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            step_fn(last)                                  # every kernel has run once on the capture stream
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=side):
-            step_fn(last)
-        graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
-        del graph
-
-    # second pass over the same steps with HIP events around the attention kernel
-    ctx.profile_enable(True)
-    for step in range(args.warmup, total_steps):
-        step_fn(step)
-    attend_ms, n_launch = ctx.profile_read()
-    ctx.profile_enable(False)
-    alg = 0
-    for step in range(args.warmup, total_steps):
-        n_rows = w.n_cached + step + (0 if args.variant == "exact" else 1)
-        if seq_lens is not None:                      # ragged: bytes of the rows each sequence really reads
-            alg += sum(algorithmic_latent_bytes(w, reuse, widths, 1, int(seq_lens.sum().item()), lat_elem, row_meta))
-        else:
-            alg += sum(algorithmic_latent_bytes(w, reuse, widths, w.batch, n_rows, lat_elem, row_meta))
-    achieved = alg / (attend_ms * 1e-3) / 1e9
-    plan = ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq)
-    traffic = None
-    # HBM bytes per launch from the committed rocprofv3 counter summary of this same workload
+    # HBM bytes per launch from the committed rocprofv3 counter summary of this same workload - only if that summary was
+    # taken with the kernels that are running now (it records a hash of the kernel sources)
+    traffic, traffic_note = None, "no counter summary for this workload"
     tpath = os.path.join(ROOT, "profiles", "attend_i8_mfma_long_context_pmc.md" if args.latent == "int8" else "attend_mfma_long_context_pmc.md")
     if os.path.exists(tpath) and args.workload == 4 and args.variant == "cache" and not (args.batch or args.cached or args.no_reuse or args.policy):
         import re
-        m = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tpath).read())
-        traffic = float(m.group(1)) if m else None
+        text = open(tpath).read()
+        mt = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", text)
+        mh = re.search(r"kernel_source_sha256\s*=\s*([0-9a-f]+)", text)
+        if mt and mh and mh.group(1) == kernel_source_hash():
+            traffic, traffic_note = float(mt.group(1)), f"rocprofv3 FETCH_SIZE + WRITE_SIZE, {os.path.relpath(tpath, ROOT)}"
+        else:
+            traffic_note = f"{os.path.relpath(tpath, ROOT)} was taken with other kernel sources than the ones running: not quoted"
 
     # what a kernel that only reads reaches on this GPU: sweeps over a 4 GiB buffer (long enough that the
     # ramp-up and tail of a launch do not count)
@@ -608,16 +701,21 @@ def main():
 
     # capacity: how many cached tokens (batch x context) fit in 288 GB, compressed vs not
     hbm = 288e9
+    widths = m["widths"]
     full_tok = 2 * elem * w.n_layers * w.d_kv
     lat_tok = sum(r * lat_elem + (row_meta if r else 0) for pair in widths for r in pair)
+    plan = m["plan"]
+    roof = roofline_entry(w, m, args.latent)
+    roof.update({"traffic": traffic, "traffic_source": traffic_note, "read_ceiling_GBs": read_ceiling,
+                 "frac_of_read_ceiling": roof["achieved"] / read_ceiling, "read_ceiling_bytes": n_probe})
     result = {
         "metric": "decode-attn tokens/s over latent KV cache",
-        "value": tokens_per_s,
+        "value": m["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": m["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -626,21 +724,31 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "cached_tokens": w.n_cached, "layers": w.n_layers,
                    "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_head": w.d_head, "latent": w.latent, "latent_format": args.latent, "variant": args.variant,
                    "reuse": w.reuse, "policy": w.policy, "reused_head_fraction": float(reuse[1:].mean()) if w.n_layers > 1 else 0.0,
-                   "splits": plan.n_splits, "mfma": bool(plan.uses_mfma), "prefill_s": t_fill},
-        "roofline": {"bound": "hbm", "kernel": ("attend_i8_mfma_r128_kernel" if args.latent == "int8" else "attend_mfma_kernel") if plan.uses_mfma else "attend_generic_kernel",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "algorithmic_bytes_per_launch": alg / max(1, n_launch),
-                     "avg_launch_ms": attend_ms / max(1, n_launch), "launches": n_launch,
-                     "whole_step_GBs": alg / args.steps / (ms_per_step * 1e-3) / 1e9,
-                     "read_ceiling_GBs": read_ceiling, "frac_of_read_ceiling": achieved / read_ceiling,
-                     "read_ceiling_bytes": n_probe},
-        "graph_replay": None if graph_ms is None else {"ms_per_step": graph_ms, "tokens_per_s": w.batch / (graph_ms * 1e-3),
-                                                       "note": "one captured step (all layers) replayed at fixed positions"},
+                   "splits": plan.n_splits, "mfma": bool(plan.uses_mfma), "prefill_s": m["prefill_s"]},
+        "roofline": roof,
+        "graph_replay": None if m["graph_ms"] is None else {"ms_per_step": m["graph_ms"], "tokens_per_s": w.batch / (m["graph_ms"] * 1e-3),
+                                                             "note": "one captured step (all layers) replayed at fixed positions"},
         "capacity_tokens_288GB": {"uncompressed": int(hbm // full_tok), "latent": int(hbm // lat_tok),
                                   "bytes_per_token_uncompressed": full_tok, "bytes_per_token_latent": lat_tok},
     }
+    del m
+    torch.cuda.empty_cache()
+    if args.workload == 4 and not args.no_workloads and not (args.batch or args.cached):
+        # the other four configurations, each at its full size, in the same run (no graph leg, no CPU leg)
+        block = {}
+        for i in range(4):
+            wi = synth.CONFIGS[i].scaled(n_steps=args.steps + args.warmup)
+            mi = measure_decode(wi, args, args.steps, args.warmup, graph=False, plain=True)
+            ri = roofline_entry(wi, mi, "dtype")
+            block[wi.name] = {"config": {"batch": wi.batch, "cached_tokens": wi.n_cached, "layers": wi.n_layers, "dtype": wi.dtype, "latent": wi.latent,
+                                         "hidden": wi.hidden, "act": wi.act, "reuse": wi.reuse, "splits": mi["plan"].n_splits,
+                                         "mfma": bool(mi["plan"].uses_mfma)},
+                              "ms_per_step": mi["ms_per_step"], "tokens_per_s": mi["tokens_per_s"], "steps": args.steps, "roofline": ri}
+            del mi
+            torch.cuda.empty_cache()
+        result["workloads"] = block
     if args.cpu_seconds > 0:
-        result["cpu_baseline"] = cpu_baseline(w, reuse, args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(w, reuse, args.cpu_seconds, n_steps=base.n_steps)
     print(json.dumps(result))
 
 
