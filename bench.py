@@ -486,7 +486,7 @@ def measure_decode(w, args, steps, warmup, graph=True, plain=False):
     fill = "encode" if plain else args.fill
     reuse = synth.reuse_map(w)
     elem = synth.DTYPE_BYTES[w.dtype]
-    kw = {} if plain else dict(n_splits=args.splits, tile_order=args.tile_order, wg_waves=args.wg_waves, no_fuse=args.no_fuse)
+    kw = {} if plain else dict(n_splits=args.splits, tile_order=args.tile_order, wg_waves=args.wg_waves, no_fuse=args.no_fuse, no_arrive=args.no_arrive)
     ses = Session(w, reuse=reuse, latent_format=latent, **kw)
     lat_elem, row_meta = (1, 8) if latent == "int8" else (elem, 0)
     dev, tdt = ses.dev, ses.tdt
@@ -627,6 +627,7 @@ def main():
     ap.add_argument("--per-head", action="store_true",
                     help="the per-head (block-diagonal) autoencoder variant: one context per KV head, reuse adds no cache traffic")
     ap.add_argument("--no-fuse", action="store_true", help="run prologue / attention / merge as separate kernels")
+    ap.add_argument("--no-arrive", action="store_true", help="several splits: partials to the separate merge kernel instead of the one-launch form")
     ap.add_argument("--capacity-check", action="store_true",
                     help="allocate latent caches for as many tokens as fit in free HBM, run one decode step over them, report")
     ap.add_argument("--capacity-fraction", type=float, default=0.92, help="share of the free device memory the capacity check may take")

@@ -146,7 +146,9 @@ typedef struct {
                            launch has no more workgroups than compute units, else four), 4 or 8      */
     int no_bulk_encode; /* 1 = prompt-sized encode calls take the general encoder kernel, not the
                            streaming one (linear encoders, 8192 tokens or more)                      */
-    int reserved[2];
+    int no_arrive;      /* 1 = with several splits the partials always go to a separate merge kernel; default: where the
+                           shapes allow, one launch whose last workgroup per (sequence, group) merges and decodes */
+    int reserved[1];    /* must be 0 */
 } kvcar_tuning;
 
 /* Create / destroy a context.  ERR_ARG on null pointers, ERR_SHAPE on non-positive sizes or
@@ -303,7 +305,10 @@ typedef struct {
     int n_groups;
     int n_splits;           /* token-range splits per sequence                                  */
     int n_launches;         /* attention-kernel launches (groups are batched 8 per launch)      */
-    int fused;              /* 1 = prologue and epilogue run inside the attention kernel        */
+    int fused;              /* 1 = one split and prologue and epilogue run inside the attention kernel; 2 = several
+                               splits in one launch: the last workgroup of a (sequence, group) merges and decodes
+                               (a call falls back to separate kernels if the library has no arrival counters left
+                               for its workspace: more than 64 workspaces in use); 0 = separate kernels          */
     size_t workspace_bytes;
     size_t latent_bytes;    /* bytes of latent rows the attention kernel reads for this call    */
 } kvcar_plan_info;

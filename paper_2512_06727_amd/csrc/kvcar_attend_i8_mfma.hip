@@ -15,6 +15,14 @@ __global__ __launch_bounds__(256, 2) void attend_i8_mfma_r128_kernel(AttendParam
     KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
     KGroup g = &p->g[blockIdx.z];
     const int key = g->k.r * 4 + (g->slots_pad >> 4);
+    if (p->fused == 4) {                      // several splits in one launch: the last workgroup to arrive merges and decodes
+        switch (key) {
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true, kWaves, true, true>(p, g, lds_raw, kI8WaveLds); return;
+            KVCAR_EXACT_SHAPES(X)
+#undef X
+            default: return;
+        }
+    }
     if (p->fused == 3) {                      // several splits, absorbed queries computed here
         switch (key) {
 #define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;

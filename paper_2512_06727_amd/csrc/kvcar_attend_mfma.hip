@@ -23,6 +23,14 @@ __global__ __launch_bounds__(256, 2) void attend_mfma_r128_kernel(AttendParams p
                 default: return;
             }
         }
+        if (p->fused == 4) {                  // several splits in one launch: the last workgroup to arrive merges and decodes
+            switch (key) {
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, false, kWaves, true, true>(p, g, lds_raw, wl); return;
+                KVCAR_EXACT_SHAPES(X)
+#undef X
+                default: return;
+            }
+        }
         if (p->fused == 3) {                  // several splits, absorbed queries computed here
             switch (key) {
 #define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, false, kWaves, true>(p, g, lds_raw, wl); return;

@@ -205,13 +205,53 @@ __device__ __forceinline__ void park_tile_i8(const u32x4_t (&st)[NL], char* regi
         }
 }
 
+// Two floats to / from global memory as one 8-byte access at agent scope: such accesses go past the per-XCD L2 caches,
+// so that workgroups on different XCDs can exchange them inside one launch (ordinary stores would sit in the writer's
+// L2, ordinary loads could hit a stale line in the reader's).  p must be 8-byte aligned.
+__device__ __forceinline__ void st_agent2(float* p, float a, float b) {
+    const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The same for 8 and 16 bytes through buffer accesses whose cache policy carries the agent-scope bit (the bit the
+// compiler puts on agent-scope atomic loads and stores).  `base` must be 16-byte aligned; offsets are in bytes from
+// it; accesses at or beyond `bytes` touch nothing and loads there return zeros.
+struct AgentBuf {
+    __amdgpu_buffer_rsrc_t rsrc;
+    __device__ __forceinline__ AgentBuf(const void* base, unsigned bytes)
+        : rsrc(__builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000)) {}      // raw buffer, 32-bit elements
+    static constexpr int kAgentScope = 16;          // cache-policy bit sc1
+    static constexpr unsigned kNowhere = 0xffffff00u;      // an offset beyond any buffer
+    __device__ __forceinline__ void store(unsigned byte_off, f32x4_t v) const {
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), rsrc, (int)byte_off, 0, kAgentScope);
+    }
+    __device__ __forceinline__ f32x4_t load(unsigned byte_off) const {
+        return __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_off, 0, kAgentScope));
+    }
+    __device__ __forceinline__ u32x2_t load8(unsigned byte_off) const {
+        return __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)byte_off, 0, kAgentScope);
+    }
+};
+
 // kFused (single split, exact shapes only): the absorbed queries are computed in the prologue and the
 // last decoder layer of V is applied in the epilogue, so the whole decode attention of a layer is this
 // one kernel and neither the absorbed queries nor the partials travel through memory.
 // kPrologue without kFused (several splits): every split's workgroup computes the absorbed queries itself
 // (a few microseconds, in parallel) instead of a prologue kernel running first; partials go to memory.
-template <typename E, typename D, bool kFused, bool kI8 = false, int NW = kWaves, bool kPrologue = kFused>
+// kArrive (several splits, one launch; with kPrologue, without kFused): every workgroup writes its partial past the
+// per-XCD L2 caches (agent-scope stores), waits for those stores and counts itself in at the (sequence, group)'s
+// arrival counter; the workgroup that finds all others already counted reads the partials back (agent-scope
+// loads), merges them and runs the same epilogue as the fused form.  Nobody waits for anybody: every workgroup exits
+// after its own work, so the grid drains whatever the scheduling order.
+// The counter lives in the caller's workspace, whose contents are arbitrary: it is a {tag, count} pair that means
+// something only while its tag equals the launch's epoch.  Every workgroup looks at it when it starts and, if the tag
+// is another, tries once to replace what it saw by {epoch, 0} (compare-and-swap: if that fails, somebody else has set it
+// up, or has even counted itself in already); a workgroup arrives only after its own attempt, so the counter is set up
+// by then and arriving is one atomic add.  The last workgroup leaves {0, 0}, so a replay of a captured launch (same
+// epoch) starts over.
+template <typename E, typename D, bool kFused, bool kI8 = false, int NW = kWaves, bool kPrologue = kFused, bool kArrive = false>
 __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, size_t wave_lds) {
+    static_assert(!kArrive || (kPrologue && !kFused && D::kExact && NW == kWaves), "the arrival form is a split form of the exact shapes");
     constexpr int RMAX = D::RMAX, NHB = D::NHB;
     using G = Geo<RMAX>;
     using ML = typename std::conditional<kI8, F16, E>::type;    // element type of the products in the loop
@@ -287,6 +327,14 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
 #pragma unroll
         for (int pf = 0; pf < PF; ++pf)
             if (j0 + pf * jstep < j1) issue(stage[pf], j0 + pf * jstep);
+    }
+
+    // arrival form: what the (sequence, group)'s counter holds now (used after the prologue, so the load flies meanwhile)
+    unsigned long long* counter = nullptr;
+    unsigned long long seen = 0;
+    if constexpr (kArrive) {
+        counter = p->arrive + ((size_t)b * p->arrive_stride + blockIdx.z) * kArrivePitch;
+        if (threadIdx.x == 0) seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // absorbed queries of this sequence and group, resident as MFMA B operands
@@ -379,6 +427,11 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
                 if (nb < nhb && s < ksteps) v = *reinterpret_cast<const u32x4_t*>(qt + ((size_t)(nb * 16 + l16) * rk + 8 * (4 * s + lg)) * 2);
                 qb[nb][s] = v;
             }
+    }
+    if constexpr (kArrive) {
+        const unsigned long long fresh = (unsigned long long)p->epoch << 32;
+        if (threadIdx.x == 0 && (unsigned)(seen >> 32) != p->epoch)
+            __hip_atomic_compare_exchange_strong(counter, &seen, fresh, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // int8: Qsum[nb] = sum over the latent index of this lane's head's absorbed query, as rounded to fp16
     float qsum[NHB];
@@ -638,7 +691,89 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         m_all[nb] = M;
         l_all[nb] = L;
     }
-    if constexpr (kFused) {
+    // arrival form, last workgroup: a batch of four splits' (m, l) pairs and latent sums of this thread's share
+    u32x2_t batch_ml[kArrive ? 4 : 1][NHB];
+    f32x4_t batch_x[kArrive ? 4 : 1][NHB][2];
+    auto arrive_issue = [&](const AgentBuf& buf, int s0, int n_sp, unsigned split_bytes, int pstride, int c0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int nb = 0; nb < NHB; ++nb) {
+                const bool on = s0 + u < n_sp;
+                const unsigned row = (unsigned)(s0 + u) * split_bytes + (unsigned)((nb * 16 + l16) * pstride * 4);
+                batch_ml[kArrive ? u : 0][nb] = buf.load8(on ? row : AgentBuf::kNowhere);
+                batch_x[kArrive ? u : 0][nb][0] = buf.load(on && c0 >= 0 ? row + (unsigned)((4 + c0) * 4) : AgentBuf::kNowhere);
+                batch_x[kArrive ? u : 0][nb][1] = buf.load(on && c0 >= 0 ? row + (unsigned)((8 + c0) * 4) : AgentBuf::kNowhere);
+            }
+    };
+    if constexpr (!kFused) {
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            if (mb < mblocks && nb < nhb)
+                *reinterpret_cast<f32x4_t*>(accs + ((size_t)((wave * NHB + nb) * MB + mb) * 64 + lane) * 4) = acc[nb][mb] * f_own[nb];
+    __syncthreads();
+    float* part = p->part + ((size_t)b * p->n_splits + split) * p->part_stride + g->part_off;
+    const int pstride = rv + 4;
+#pragma unroll
+    for (int nb = 0; nb < NHB; ++nb) {
+        if (nb >= nhb) continue;
+        const int slot = nb * 16 + l16;
+        if (wave == 0 && lane < 16) {
+            if constexpr (kArrive) st_agent2(part + (size_t)slot * pstride, m_all[nb], l_all[nb]);
+            else { part[(size_t)slot * pstride] = m_all[nb]; part[(size_t)slot * pstride + 1] = l_all[nb]; }
+        }
+        // 16-column blocks are shared out over the four waves
+        for (int mb = wave; mb < mblocks; mb += NW) {
+            f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < NW; ++w) s += *reinterpret_cast<const f32x4_t*>(accs + ((size_t)((w * NHB + nb) * MB + mb) * 64 + lane) * 4);
+            if constexpr (kArrive) AgentBuf(part, (unsigned)(NHB * 16 * pstride * 4)).store((unsigned)((slot * pstride + 4 + 16 * mb + 4 * lg) * 4), s);
+            else *reinterpret_cast<f32x4_t*>(part + (size_t)slot * pstride + 4 + 16 * mb + 4 * lg) = s;
+        }
+    }
+    }
+    if constexpr (kArrive) {
+        // this workgroup's partial has left the chip's caches before it counts itself in
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        unsigned* flag = reinterpret_cast<unsigned*>(lds_raw);
+        if (threadIdx.x == 0) *flag = (unsigned)__hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*flag + 1u != (unsigned)p->n_splits) return;          // the same for every thread of the workgroup
+        if (threadIdx.x == 0) __hip_atomic_store(counter, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // Last to arrive: every split's partial is complete in memory.  All loads of a batch of splits are issued before
+        // anything waits (a loop that loads, waits and adds per split pays a memory round trip per split).  The first
+        // batch of latent sums (four splits) is requested here already, ahead of the (m, l) pairs that scale them.
+        const float* pall = p->part + (size_t)b * p->n_splits * p->part_stride + g->part_off;
+        const int pstride = rv + 4;
+        const int n_sp = p->n_splits;
+        const unsigned split_bytes = (unsigned)p->part_stride * 4u;
+        const AgentBuf pbuf(pall, (unsigned)(n_sp - 1) * split_bytes + (unsigned)(NHB * 16 * pstride * 4));
+        const int c0 = 8 * (4 * wave + lg);               // this thread's latent columns c0 .. c0 + 7 of head slots nb * 16 + l16
+        arrive_issue(pbuf, 0, n_sp, split_bytes, pstride, c0 < rv ? c0 : -1);
+#pragma unroll
+        for (int nb = 0; nb < NHB; ++nb) { m_all[nb] = -INFINITY; l_all[nb] = 0.f; }
+        for (int s0 = 0; s0 < n_sp; s0 += 8) {
+            u32x2_t ml[8][NHB];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int nb = 0; nb < NHB; ++nb)
+                    ml[u][nb] = pbuf.load8(s0 + u < n_sp ? (unsigned)(s0 + u) * split_bytes + (unsigned)((nb * 16 + l16) * pstride * 4) : AgentBuf::kNowhere);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int nb = 0; nb < NHB; ++nb) {
+                    const float ms = s0 + u < n_sp ? __uint_as_float(ml[u][nb][0]) : -INFINITY, ls = __uint_as_float(ml[u][nb][1]);
+                    const float Mn = fmaxf(m_all[nb], ms);
+                    l_all[nb] = (m_all[nb] == -INFINITY ? 0.f : l_all[nb] * exp2f(m_all[nb] - Mn)) + (ms == -INFINITY ? 0.f : ls * exp2f(ms - Mn));
+                    m_all[nb] = Mn;
+                }
+        }
+    }
+    if constexpr (kFused || kArrive) {
         // ---- the current token's exact row, if given ("Network Architecture", 2nd paragraph: the decoded cache
         // rows are concatenated with the exact key / value of the current token): one more softmax term per head,
         // s = scale q . (k_cur - b_K) (the cached scores were formed without the K decoder's bias, which cancels
@@ -727,7 +862,31 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         // as olat[slot][rv + 4], which overlays the parked copies once every thread has read its inputs.
         constexpr int kItems = NHB * MB * 64;                  // float4 items of the merged sums
         constexpr int kPerThread = (kItems + 64 * NW - 1) / (64 * NW);
-        f32x4_t merged[kPerThread];
+        f32x4_t merged[kArrive ? 1 : kPerThread];
+        f32x4_t mrow[kArrive ? NHB : 1][2];                    // arrival form: this thread's eight columns of its head slots
+        if constexpr (kArrive) {
+            // Merge of the splits' partials, in split order (deterministic): this thread takes head slots nb * 16 + l16
+            // (the slots its factors were computed for) and latent columns c0 .. c0 + 7, four splits per round trip.
+            const float* pall = p->part + (size_t)b * p->n_splits * p->part_stride + g->part_off;
+            const int n_sp = p->n_splits;
+            const unsigned split_bytes = (unsigned)p->part_stride * 4u;
+            const AgentBuf pbuf(pall, (unsigned)(n_sp - 1) * split_bytes + (unsigned)(NHB * 16 * ostride * 4));
+            const int c0 = 8 * (4 * wave + lg);
+#pragma unroll
+            for (int nb = 0; nb < NHB; ++nb) mrow[nb][0] = mrow[nb][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            for (int s0 = 0; s0 < n_sp; s0 += 4) {
+                if (s0 > 0) arrive_issue(pbuf, s0, n_sp, split_bytes, ostride, c0 < rv ? c0 : -1);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int nb = 0; nb < NHB; ++nb) {
+                        const float ms = s0 + u < n_sp ? __uint_as_float(batch_ml[kArrive ? u : 0][nb][0]) : -INFINITY;
+                        const float f = ms == -INFINITY ? 0.f : exp2f(ms - m_all[nb]) * inv_l[nb];
+                        mrow[kArrive ? nb : 0][0] += batch_x[kArrive ? u : 0][nb][0] * f;
+                        mrow[kArrive ? nb : 0][1] += batch_x[kArrive ? u : 0][nb][1] * f;
+                    }
+            }
+        } else {
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {
             // item = (head block nb, column block mb, lane): its lane is this thread's lane, so the factors above apply
@@ -745,6 +904,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             }
             merged[i] = sum;
         }
+        }
         __syncthreads();
         red = reinterpret_cast<float*>(lds_raw);               // from here on: per-slot weights, merged sums, decoder slices
         if (exact_row && wave == 0 && lane < 16) {             // per-slot weights for the store
@@ -754,6 +914,16 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
                 red[NHB * 16 + nb * 16 + lane] = w_cur[nb];
             }
         }
+        if constexpr (kArrive) {
+            const int c0 = 8 * (4 * wave + lg);
+            if (c0 < rv) {
+#pragma unroll
+                for (int nb = 0; nb < NHB; ++nb) {
+                    *reinterpret_cast<f32x4_t*>(olat + (size_t)(nb * 16 + l16) * ostride + c0) = mrow[kArrive ? nb : 0][0];
+                    *reinterpret_cast<f32x4_t*>(olat + (size_t)(nb * 16 + l16) * ostride + c0 + 4) = mrow[kArrive ? nb : 0][1];
+                }
+            }
+        } else {
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {
             const int item = i * (64 * NW) + threadIdx.x;
@@ -761,6 +931,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
                 const int ln = item & 63, blk = item >> 6, mb = blk % MB, nb = blk / MB;
                 *reinterpret_cast<f32x4_t*>(olat + (size_t)(nb * 16 + (ln & 15)) * ostride + 16 * mb + 4 * (ln >> 4)) = merged[i];
             }
+        }
         }
         __syncthreads();
         uint16_t* out = static_cast<uint16_t*>(p->out);
@@ -820,29 +991,6 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             }
             __syncthreads();                             // the slice buffer is rewritten for the next KV head
         }
-    } else {
-#pragma unroll
-    for (int nb = 0; nb < NHB; ++nb)
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-            if (mb < mblocks && nb < nhb)
-                *reinterpret_cast<f32x4_t*>(accs + ((size_t)((wave * NHB + nb) * MB + mb) * 64 + lane) * 4) = acc[nb][mb] * f_own[nb];
-    __syncthreads();
-    float* part = p->part + ((size_t)b * p->n_splits + split) * p->part_stride + g->part_off;
-    const int pstride = rv + 4;
-#pragma unroll
-    for (int nb = 0; nb < NHB; ++nb) {
-        if (nb >= nhb) continue;
-        const int slot = nb * 16 + l16;
-        if (wave == 0 && lane < 16) { part[(size_t)slot * pstride] = m_all[nb]; part[(size_t)slot * pstride + 1] = l_all[nb]; }
-        // 16-column blocks are shared out over the four waves
-        for (int mb = wave; mb < mblocks; mb += NW) {
-            f32x4_t s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int w = 0; w < NW; ++w) s += *reinterpret_cast<const f32x4_t*>(accs + ((size_t)((w * NHB + nb) * MB + mb) * 64 + lane) * 4);
-            *reinterpret_cast<f32x4_t*>(part + (size_t)slot * pstride + 4 + 16 * mb + 4 * lg) = s;
-        }
-    }
     }
 }
 

@@ -41,6 +41,14 @@ constexpr int kMaxDevices = 64;
 std::mutex scratch_mu;
 void* scratch_ptr[kMaxDevices];      // device address of `scratch` on each device, looked up once per device
 
+// Tag of one launch of the one-launch split attention: its arrival counters are valid only under this tag, so the
+// counters need no initial state (see attend_body).  Never 0: that is the tag of a counter at rest.
+unsigned next_epoch() {
+    static std::atomic<unsigned> epoch{0x9e3779b9u};
+    unsigned e = epoch.fetch_add(1u, std::memory_order_relaxed) + 1u;
+    return e ? e : epoch.fetch_add(1u, std::memory_order_relaxed) + 1u;
+}
+
 // Address of the current device's copy of `scratch` (looked up on the first use on that device).
 hipError_t scratch_of_current_device(void** out) {
     int dev = -1;
@@ -120,10 +128,11 @@ struct Plan {
     bool i8 = false;          // ... the one over int8 latent rows (absorbed queries travel in fp32)
     bool fused = false;       // one kernel does prologue, attention and epilogue (single split, exact shapes)
     bool prologue = false;    // several splits: the attention kernel computes the absorbed queries itself
+    bool arrive = false;      // ... and its last workgroup per (sequence, group) merges the splits and decodes: one launch
     int n_splits = 1;
     int qt_stride = 0;        // elements per sequence
     int part_stride = 0;      // floats per (sequence, split)
-    size_t qt_bytes = 0, part_bytes = 0, total_bytes = 0;
+    size_t qt_bytes = 0, part_bytes = 0, arrive_bytes = 0, total_bytes = 0;
 };
 
 int fill_side(const kvcar_ctx* ctx, int layer, int src, int which, SideDesc& sd) {
@@ -271,8 +280,9 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     plan.n_splits = splits;
     plan.fused = false;
     plan.prologue = false;
+    plan.arrive = false;
     if (plan.mfma && !plan.mlp && !ctx->tun.no_fuse && r_all <= 128 && c.d_head % 32 == 0 && c.d_head <= 128) {
-        plan.fused = splits == 1;
+        plan.fused = true;                                  // whether the epilogue can run inside: decided over the groups below
         plan.prologue = true;                               // the query side alone: also with several splits
         for (auto& gd : plan.groups) {
             if (gd.k.r != gd.v.r || gd.k.r % 32 || gd.k.r < 32 || gd.slots_pad > 32 || gd.n_kseg == 0) plan.fused = plan.prologue = false;
@@ -291,10 +301,15 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
                 if (kinds > 2) plan.fused = plan.prologue = false;
             }
         }
+        // with several splits the same prologue and epilogue run in the one-launch form whose last workgroup merges
+        plan.arrive = plan.fused && plan.prologue && splits > 1 && splits <= kArriveMaxSplits && !ctx->tun.no_arrive;
+        plan.fused = plan.fused && splits == 1;
     }
     plan.qt_bytes = align_up((size_t)batch * qt * (plan.mfma && !plan.i8 ? 2 : 4), 256);
     plan.part_bytes = align_up((size_t)batch * splits * part * sizeof(float), 256);
-    plan.total_bytes = plan.qt_bytes + plan.part_bytes;
+    // one-launch split form: an 8-byte arrival counter per (sequence, group) after the partials
+    plan.arrive_bytes = plan.arrive ? (size_t)batch * plan.groups.size() * kArrivePitch * sizeof(unsigned long long) : 0;
+    plan.total_bytes = plan.qt_bytes + plan.part_bytes + plan.arrive_bytes;
     return KVCAR_OK;
 }
 
@@ -450,7 +465,7 @@ int kvcar_bind_cache(kvcar_ctx* ctx, int layer, int which, void* dev, size_t byt
 
 int kvcar_set_tuning(kvcar_ctx* ctx, const kvcar_tuning* t) try {
     if (!ctx || !t) return KVCAR_ERR_ARG;
-    if (t->n_splits < 0 || t->tile_order < 0 || t->tile_order > 2 || (t->wg_waves != 0 && t->wg_waves != 4 && t->wg_waves != 8))
+    if (t->n_splits < 0 || t->tile_order < 0 || t->tile_order > 2 || (t->wg_waves != 0 && t->wg_waves != 4 && t->wg_waves != 8) || t->reserved[0] != 0)
         return fail(ctx, KVCAR_ERR_ARG, "bad tuning value");
     ctx->tun = *t;
     return KVCAR_OK;
@@ -583,7 +598,13 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
         p.tile_order = ctx->tun.tile_order == 2 ? 1 : 0;
         // fused: 1 = four waves per workgroup; 2 = eight, when the launch has no more workgroups than compute units
         const bool w8 = ctx->tun.wg_waves == 8 || (ctx->tun.wg_waves == 0 && batch * p.n_groups <= ctx->n_cu);
-        p.fused = plan.fused ? (w8 ? 2 : 1) : plan.prologue ? 3 : 0;
+        if (plan.arrive) {
+            p.arrive = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + plan.qt_bytes + plan.part_bytes) + g0 * kArrivePitch;
+            p.arrive_stride = (int)plan.groups.size();
+            p.epoch = next_epoch();
+        }
+        const bool one_launch = plan.fused || plan.arrive;
+        p.fused = plan.fused ? (w8 ? 2 : 1) : plan.arrive ? 4 : plan.prologue ? 3 : 0;
         const bool proj = plan.mfma && proj_mfma_supported(p, c.dtype);
         hipError_t e = hipSuccess;
         if (!plan.fused && !plan.prologue)
@@ -603,7 +624,7 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
                          : plan.i8 ? launch_attend_i8_mfma(p, c.dtype, st)
                          : plan.mfma ? launch_attend_mfma(p, c.dtype, st) : launch_attend_generic(p, c.dtype, st);
         if (e == hipSuccess && ev) e = hipEventRecord(ev->second, st);
-        if (e == hipSuccess && !plan.fused) e = proj ? launch_combine_mfma(p, c.dtype, st) : launch_combine(p, c.dtype, st);
+        if (e == hipSuccess && !one_launch) e = proj ? launch_combine_mfma(p, c.dtype, st) : launch_combine(p, c.dtype, st);
         if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "attention launch failed: %s", hipGetErrorString(e));
     }
     return KVCAR_OK;
@@ -757,7 +778,7 @@ int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, k
     out->n_groups = (int)plan.groups.size();
     out->n_splits = plan.n_splits;
     out->n_launches = (int)((plan.groups.size() + kMaxGroups - 1) / kMaxGroups);
-    out->fused = plan.fused ? 1 : 0;
+    out->fused = plan.fused ? 1 : plan.arrive ? 2 : 0;
     out->workspace_bytes = plan.total_bytes;
     size_t lat = 0;
     for (auto& g : plan.groups) lat += (size_t)(g.k.r + g.v.r);

@@ -20,6 +20,9 @@ constexpr int kMaxKvHeads = 64;     // bound on n_kv_heads (head lists live in k
 constexpr int kGenericTile = 16;    // tokens per tile of the plain-ALU attention kernel
 constexpr int kGenericAcc = 48;     // accumulators per thread of the plain-ALU attention kernel
 constexpr int kMaxRow = 384;        // widest latent / hidden row any kernel handles
+constexpr int kArriveMaxSplits = 64;   // most splits the one-launch form's last workgroup merges
+constexpr int kArrivePitch = 32;       // 8-byte words between two arrival counters: 256 bytes apart, so that the atomic
+                                       // operations of different (sequence, group) pairs spread over the memory channels
 constexpr float kLog2e = 1.4426950408889634f;
 
 // Scale and zero point of one int8 latent row.
@@ -76,8 +79,12 @@ struct AttendParams {
     int part_stride;      // partial floats per (sequence, split) (all groups)
     float scale_log2e;    // softmax scale * log2(e)
     int tile_order;       // MFMA kernel: 0 = contiguous token range per split, 1 = tiles dealt round-robin
-    int fused;            // MFMA kernel: absorbed queries and output epilogue computed inside (single split);
-                          // 2 = the eight-wave variant of that kernel
+    int fused;            // MFMA kernel: 1 = absorbed queries and output epilogue computed inside (single split); 2 = the
+                          // eight-wave variant of that; 3 = several splits, absorbed queries computed inside, partials to the
+                          // merge kernel; 4 = several splits, the last workgroup to arrive merges and decodes (one launch)
+    unsigned long long* arrive;   // fused == 4: arrival counter of (sequence b, group z of this launch) at [(b * arrive_stride + z) * kArrivePitch]:
+    int arrive_stride;            //   {tag : 32, count : 32}; valid only while the tag equals `epoch`
+    unsigned epoch;               //   tag of this launch (never 0)
     int gq;               // query heads per KV head
     const int* seq_lens;  // per-sequence context length [batch] (ragged batch), or null: n_ctx for all
     const void* k_cur;    // exact key / value row of the current token [batch, H_kv * d_head], attended as one

@@ -14,17 +14,18 @@ from . import binding, synth
 class Session:
     def __init__(self, w: synth.Workload, reuse: Optional[np.ndarray] = None, with_bias: bool = False,
                  device: str = "cuda:0", n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, no_fuse: bool = False, poison: bool = False,
-                 max_batch: Optional[int] = None, latent_format: str = "dtype", wg_waves: int = 0, no_bulk_encode: bool = False):
+                 max_batch: Optional[int] = None, latent_format: str = "dtype", wg_waves: int = 0, no_bulk_encode: bool = False, no_arrive: bool = False):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: libkvcar has no CPU path")
         self.w = w
+        self.poison = poison
         self.dev = torch.device(device)
         self.tdt = synth.TORCH_DTYPE[w.dtype]
         self.reuse = synth.reuse_map(w) if reuse is None else reuse
         self.latent_format = latent_format
         self.ctx = binding.Context(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, max_batch or w.batch, w.max_seq, w.dtype,
                                    latent_format=latent_format)
-        self.ctx.set_tuning(n_splits=n_splits, force_generic=force_generic, tile_order=tile_order, no_fuse=no_fuse, wg_waves=wg_waves, no_bulk_encode=no_bulk_encode)
+        self.ctx.set_tuning(n_splits=n_splits, force_generic=force_generic, tile_order=tile_order, no_fuse=no_fuse, wg_waves=wg_waves, no_bulk_encode=no_bulk_encode, no_arrive=no_arrive)
         self.ae: List[List[synth.AEWeights]] = []
         self.caches: List[List[Optional[torch.Tensor]]] = []
         for layer in range(w.n_layers):
@@ -85,6 +86,8 @@ class Session:
         need = self.ctx.workspace_bytes(batch, n_ctx)
         if self.workspace is None or self.workspace.numel() < need:
             self.workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=self.dev)
+            if self.poison:                      # the library must not rely on anything a workspace holds
+                self.workspace.random_(0, 256)
 
     def encode_append(self, layer: int, k_new: torch.Tensor, v_new: torch.Tensor, pos0: int):
         b, t, _ = k_new.shape

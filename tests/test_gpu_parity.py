@@ -179,3 +179,51 @@ def test_gelu_decoder_over_its_whole_range(variant, gain):
     err = np.abs(got_p - want_p)
     assert np.isfinite(got_p).all() and (err <= elementwise_bound(want_p, w.dtype)).all(), f"{variant} prefill: max abs err {err.max():.3e}"
     assert err.max() <= REL_TOL[w.dtype] * np.abs(want_p).max()
+
+
+# ---- several splits in one launch: the last workgroup of a (sequence, group) merges the partials and decodes --------
+ONE_LAUNCH = {
+    # TinyLlama shape, reuse chain: two groups per layer, 34 workgroup tiles per sequence
+    "tinyllama": (C[2].scaled(n_layers=3, batch=2, n_cached=4300, n_steps=1), {}),
+    # Bernoulli map, full-width policy, biases: groups of unequal size
+    "bernoulli-p2-bias": (C[4].scaled(n_layers=5, batch=3, n_cached=1000, n_steps=1, policy="P2"), {"with_bias": True}),
+    # head width 128, fp16
+    "dh128-f16": (C[2].scaled(n_layers=3, batch=2, n_cached=1100, n_steps=1, n_q_heads=16, n_kv_heads=2, d_head=128, latent=64, policy="P2", reuse="odd:1",
+                              dtype="f16"), {"with_bias": True}),
+    "tinyllama-int8": (C[2].scaled(n_layers=3, batch=2, n_cached=4300, n_steps=1), {"latent_format": "int8"}),
+}
+
+
+@pytest.mark.parametrize("n_splits", [2, 7, 32])
+@pytest.mark.parametrize("name", list(ONE_LAUNCH))
+def test_one_launch_split_kernel(name, n_splits):
+    """With several splits the attention kernel's last workgroup per (sequence, group) merges and decodes (plan.fused == 2);
+    the workspace starts out as random bytes (arrival counters included).  Against the oracle, and the same with the
+    partials going to the separate merge kernel (no_arrive)."""
+    from paper_2512_06727_amd.harness import Session
+    w, kw = ONE_LAUNCH[name]
+    print(f"case {name} splits {n_splits} {w} {kw}", flush=True)
+    _, want = run_oracle(w, gain=20.0, **kw)
+    for no_arrive in (False, True):
+        ses, got = run_gpu(w, gain=20.0, n_splits=n_splits, no_arrive=no_arrive, **kw)
+        plan = ses.ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached + 1)
+        assert plan.n_splits == min(n_splits, (w.n_cached + 1 + 127) // 128) and plan.fused == (0 if no_arrive else 2)
+        assert_outputs_close(w, got, want, f"{name} splits={n_splits} no_arrive={no_arrive}")
+
+
+def test_one_launch_split_kernel_repeated_on_one_workspace():
+    """The same workspace serves every layer and step, with different split counts and batch sizes in turn: each
+    launch must find its arrival counters at rest whatever ran before."""
+    from paper_2512_06727_amd.harness import Session
+    w, kw = ONE_LAUNCH["tinyllama"]
+    _, want = run_oracle(w, gain=20.0)
+    ses = Session(w, poison=True)
+    ses.prefill(0, w.n_cached + 1, chunk=256)
+    ses.ensure_workspace(w.batch, w.n_cached + 1)
+    for rep, splits in enumerate([0, 5, 2, 32, 3, 0]):
+        ses.ctx.set_tuning(n_splits=splits)
+        ses.ensure_workspace(w.batch, w.n_cached + 1)
+        for n in range(w.n_layers):
+            q = synth.queries(w, n, 0, gain=20.0).to(ses.dev, ses.tdt)
+            got = ses.decode_attention(n, q, w.n_cached + 1).float().cpu().double().numpy()
+            assert_outputs_close(w, [{n: got}], [{n: want[0][n]}], f"repeat {rep} splits {splits} layer {n}")

@@ -54,6 +54,29 @@ def check(w, got, want, label):
     assert err.max() <= REL_TOL[w.dtype] * np.abs(want).max(), f"{label}: err {err.max():.3e} vs max |ref| {np.abs(want).max():.3e}"
 
 
+def test_ragged_and_exact_row_in_the_one_launch_split_kernel():
+    """Several splits in one launch (the last workgroup merges): ragged context lengths - one sequence empty, one shorter
+    than a split's share, so that some splits see no token at all - together with the exact current-token row."""
+    w = synth.CONFIGS[2].scaled(n_layers=3, batch=4, n_cached=1500, n_steps=1)
+    for fmt in ("dtype", "int8"):
+        orc = build_oracle(w, latent_format=fmt)
+        for n in range(w.n_layers):
+            oracle_prefill(orc, w, n, 0, w.n_cached)
+        ses = Session(w, poison=True, latent_format=fmt, n_splits=6)
+        ses.prefill(0, w.n_cached, chunk=256)
+        assert ses.ctx.describe_plan(2, w.batch, w.n_cached).fused == 2
+        lens = np.array([w.n_cached, 0, 100, 777])
+        tl = torch.tensor(lens, dtype=torch.int32, device=ses.dev)
+        for layer in range(w.n_layers):
+            q = synth.queries(w, layer, 0, gain=20.0)
+            kc = synth.kv_tokens(w, layer, 0, 0, w.batch, w.n_cached, w.n_cached + 1)[:, 0]
+            vc = synth.kv_tokens(w, layer, 1, 0, w.batch, w.n_cached, w.n_cached + 1)[:, 0]
+            want = orc.decode_attention(layer, q.double().numpy(), w.n_cached, seq_lens=lens, k_cur=kc.double().numpy(), v_cur=vc.double().numpy())
+            dev = lambda t: t.to(ses.dev, ses.tdt).contiguous()
+            got = run_ex(ses, w, layer, dev(q), w.n_cached, seq_lens=tl, k_cur=dev(kc), v_cur=dev(vc))
+            check(w, got, want, f"{fmt} layer {layer}")
+
+
 def run_ex(ses, w, layer, q, n_ctx, **ext):
     out = torch.empty_like(q)
     ses.ensure_workspace(w.batch, max(1, n_ctx))
