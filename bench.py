@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the KV-CAR decode hot path on one MI355X.
 
-A "step" is one decode step of the whole path over one batch: for every layer,
-kvcar_encode_append of the new token's K/V followed by kvcar_decode_attention over the latent
-cache (reuse map applied).  The default workload is the TinyLlama-shaped long-context
+A "step" is one decode step of the whole path over one batch: for every layer, the encoder and
+append of the new token's K/V followed by decode attention over the latent cache (reuse map
+applied) - kvcar_append_attend, which is the two calls kvcar_encode_append + kvcar_decode_attention
+in one (and, where the shapes allow, in one kernel); --separate-encode makes the two calls.  The default workload is the TinyLlama-shaped long-context
 configuration (batch 256, 8192 cached tokens, 22 layers, bf16, linear autoencoder r=128,
 Bernoulli(0.3) head-reuse map).  Inputs are synthetic and resident in HBM before timing starts.
 
@@ -486,6 +487,7 @@ def measure_decode(w, args, steps, warmup, graph=True, plain=False):
     fill = "encode" if plain else args.fill
     reuse = synth.reuse_map(w)
     elem = synth.DTYPE_BYTES[w.dtype]
+    separate = False if plain else args.separate_encode
     kw = {} if plain else dict(n_splits=args.splits, tile_order=args.tile_order, wg_waves=args.wg_waves, no_fuse=args.no_fuse, no_arrive=args.no_arrive)
     ses = Session(w, reuse=reuse, latent_format=latent, **kw)
     lat_elem, row_meta = (1, 8) if latent == "int8" else (elem, 0)
@@ -541,9 +543,11 @@ def measure_decode(w, args, steps, warmup, graph=True, plain=False):
             elif variant == "ragged":
                 ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
                 ctx.decode_attention_ex(n, qs[step][n], outs[n], w.batch, pos + 1, ws, seq_lens=seq_lens)
-            else:
+            elif separate:
                 ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
                 ctx.decode_attention(n, qs[step][n], outs[n], w.batch, pos + 1, ws)
+            else:
+                ctx.append_attend(n, ks[step][n], vs[step][n], qs[step][n], outs[n], w.batch, pos, ws)
 
     for step in range(warmup):
         step_fn(step)
@@ -594,7 +598,7 @@ def measure_decode(w, args, steps, warmup, graph=True, plain=False):
         flops += attention_flops_per_token(w) * w.batch * n_rows * w.n_layers
     return {"reuse": reuse, "widths": widths, "ms_per_step": ms_per_step, "tokens_per_s": tokens_per_s, "graph_ms": graph_ms,
             "attend_ms": attend_ms, "n_launch": n_launch, "alg_bytes": alg, "alg_flops": flops, "steps": steps, "prefill_s": t_fill,
-            "plan": ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq)}
+            "plan": ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq), "one_call": not separate and variant == "cache"}
 
 
 def main():
@@ -627,6 +631,8 @@ def main():
     ap.add_argument("--per-head", action="store_true",
                     help="the per-head (block-diagonal) autoencoder variant: one context per KV head, reuse adds no cache traffic")
     ap.add_argument("--no-fuse", action="store_true", help="run prologue / attention / merge as separate kernels")
+    ap.add_argument("--separate-encode", action="store_true",
+                    help="a layer's step as kvcar_encode_append + kvcar_decode_attention (two calls) instead of kvcar_append_attend")
     ap.add_argument("--no-arrive", action="store_true", help="several splits: partials to the separate merge kernel instead of the one-launch form")
     ap.add_argument("--capacity-check", action="store_true",
                     help="allocate latent caches for as many tokens as fit in free HBM, run one decode step over them, report")
@@ -725,7 +731,9 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "cached_tokens": w.n_cached, "layers": w.n_layers,
                    "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_head": w.d_head, "latent": w.latent, "latent_format": args.latent, "variant": args.variant,
                    "reuse": w.reuse, "policy": w.policy, "reused_head_fraction": float(reuse[1:].mean()) if w.n_layers > 1 else 0.0,
-                   "splits": plan.n_splits, "mfma": bool(plan.uses_mfma), "prefill_s": m["prefill_s"]},
+                   "splits": plan.n_splits, "mfma": bool(plan.uses_mfma), "prefill_s": m["prefill_s"],
+                   "step_call": "kvcar_append_attend" if m["one_call"] else "kvcar_encode_append + kvcar_decode_attention",
+                   "encoder_in_attention_kernel": bool(plan.append_in_kernel) and m["one_call"]},
         "roofline": roof,
         "graph_replay": None if m["graph_ms"] is None else {"ms_per_step": m["graph_ms"], "tokens_per_s": w.batch / (m["graph_ms"] * 1e-3),
                                                              "note": "one captured step (all layers) replayed at fixed positions"},
@@ -743,7 +751,8 @@ def main():
             ri = roofline_entry(wi, mi, "dtype")
             block[wi.name] = {"config": {"batch": wi.batch, "cached_tokens": wi.n_cached, "layers": wi.n_layers, "dtype": wi.dtype, "latent": wi.latent,
                                          "hidden": wi.hidden, "act": wi.act, "reuse": wi.reuse, "splits": mi["plan"].n_splits,
-                                         "mfma": bool(mi["plan"].uses_mfma)},
+                                         "mfma": bool(mi["plan"].uses_mfma), "launches_per_layer_fused": mi["plan"].fused,
+                                         "encoder_in_attention_kernel": bool(mi["plan"].append_in_kernel)},
                               "ms_per_step": mi["ms_per_step"], "tokens_per_s": mi["tokens_per_s"], "steps": args.steps, "roofline": ri}
             del mi
             torch.cuda.empty_cache()

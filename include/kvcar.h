@@ -261,6 +261,23 @@ int kvcar_decode_attention_ex(kvcar_ctx *ctx, int layer, const void *q, void *ou
 int kvcar_decode_attention_static(kvcar_ctx *ctx, int layer, const void *q, void *out, int batch, int n_ctx,
                                   void *stream);
 
+/*
+ * One decode step of a layer in one call: kvcar_encode_append(layer, k_new, v_new, batch, pos, 1) followed by
+ * kvcar_decode_attention(layer, q, out, batch, pos + 1, ..) - the encoder after K/V generation, the append, and
+ * attention over the cache including the row just appended ("Network Architecture", 1st and 2nd paragraphs; Eq. 1).
+ *   k_new, v_new  dev [batch, D_kv]: the new token's key and value vectors of every sequence
+ *   pos           position the rows are written at; attention then runs over rows 0 .. pos
+ * Where the launch planned for the attention can take the encoder in (matrix-core kernels with rows in the model
+ * dtype, linear encoders with in_width <= 256 and latent_width <= 128, at most 16 KV heads, tuning without no_fuse /
+ * tile_order 2) the whole step of the layer is ONE kernel: the workgroup that reaches the end of a sequence's context
+ * encodes that sequence's new rows, writes them to the caches and attends to them; otherwise the call enqueues what the
+ * two separate calls would.  Results equal those of the two calls up to the order of the encoder's fp32 sums (the row
+ * written may differ in the last place of the cache dtype on a small fraction of elements).
+ * Arguments, workspace (kvcar_workspace_bytes(batch, pos + 1)) and errors as for the two calls.
+ */
+int kvcar_append_attend(kvcar_ctx *ctx, int layer, const void *k_new, const void *v_new, const void *q, void *out,
+                        int batch, int pos, void *workspace, size_t workspace_bytes, void *stream);
+
 /* kvcar_encode_append for a ragged batch: sequence b's t_new rows land at positions
  * [positions[b], positions[b] + t_new) (positions: dev int32 [batch]).  The caller guarantees
  * positions[b] + t_new <= max_seq (device data is not checked). */
@@ -311,6 +328,8 @@ typedef struct {
                                for its workspace: more than 64 workspaces in use); 0 = separate kernels          */
     size_t workspace_bytes;
     size_t latent_bytes;    /* bytes of latent rows the attention kernel reads for this call    */
+    int append_in_kernel;   /* 1 = kvcar_append_attend at this size encodes the new token inside the
+                               attention kernel (one launch for the layer's whole step)         */
 } kvcar_plan_info;
 int kvcar_describe_plan(const kvcar_ctx *ctx, int layer, int batch, int n_ctx, kvcar_plan_info *out);
 

@@ -49,7 +49,7 @@ class StepExt(C.Structure):
 
 class PlanInfo(C.Structure):
     _fields_ = [("uses_mfma", C.c_int), ("n_groups", C.c_int), ("n_splits", C.c_int), ("n_launches", C.c_int), ("fused", C.c_int),
-                ("workspace_bytes", C.c_size_t), ("latent_bytes", C.c_size_t)]
+                ("workspace_bytes", C.c_size_t), ("latent_bytes", C.c_size_t), ("append_in_kernel", C.c_int)]
 
 
 # every symbol include/kvcar.h declares: name -> (restype, argtypes)
@@ -69,6 +69,8 @@ SYMBOLS = {
     "kvcar_decode_attention_ex": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(StepExt), C.c_void_p,
                                             C.c_size_t, C.c_void_p]),
     "kvcar_decode_attention_static": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
+    "kvcar_append_attend": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t,
+                                      C.c_void_p]),
     "kvcar_encode_append_at": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]),
     "kvcar_describe_encode": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int)]),
     "kvcar_prefill_workspace_bytes": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]),
@@ -261,6 +263,12 @@ class Context:
         nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
         self._check(lib().kvcar_decode_attention(self._h, layer, _ptr(q), _ptr(out), batch, n_ctx, _ptr(workspace),
                                                  nbytes, _stream()))
+
+    def append_attend(self, layer: int, k_new, v_new, q, out, batch: int, pos: int, workspace):
+        """kvcar_append_attend: encode + append the new token at `pos`, then attend over rows 0 .. pos."""
+        nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self._check(lib().kvcar_append_attend(self._h, layer, _ptr(k_new), _ptr(v_new), _ptr(q), _ptr(out), batch, pos, _ptr(workspace), nbytes,
+                                              _stream()))
 
     def decode_attention_static(self, layer: int, q, out, batch: int, n_ctx: int):
         """kvcar_decode_attention on the library's own static scratch buffer (no workspace, no allocation)."""

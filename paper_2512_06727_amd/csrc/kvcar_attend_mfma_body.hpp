@@ -433,6 +433,83 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         if (threadIdx.x == 0 && (unsigned)(seen >> 32) != p->epoch)
             __hip_atomic_compare_exchange_strong(counter, &seen, fresh, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    // ---- append-and-attend: the new token's latent rows ("Network Architecture", 1st paragraph: the encoder after K/V
+    // generation), computed here by the workgroup that holds the context's last tile instead of by an encoder launch
+    // before this one.  z = x[columns of the stored heads] . W_enc + b in fp32, rounded once to the cache dtype; the
+    // row is written to the layer's cache (by one group per side) and kept in LDS, from where it replaces the last row
+    // of the tile as parked - the copy of that row loaded from memory may predate the write.
+    const char* znew = nullptr;
+    bool patch_k = false, patch_v = false;
+    if constexpr (kPrologue && !kI8) {
+        if (p->append && (g->append & 3) && j0 < j1 && j1 == wg_tiles) {     // the same for the whole workgroup
+            char* app = lds_raw + NW * wave_lds;                // the query-operand exchange area, free from here on
+            float* xs = reinterpret_cast<float*>(app);          // [in_width <= 256]
+            float* ps = xs + 256;                               // [4 waves][128]
+            uint16_t* zn = reinterpret_cast<uint16_t*>(ps + 512);      // [2 sides][128]
+            const int tid = threadIdx.x, dh = p->d_head, d_kv = (p->n_q_heads / p->gq) * dh;
+            __syncthreads();                                    // every wave has taken its query operands out of the area
+#pragma unroll
+            for (int side = 0; side < 2; ++side) {
+                if (!((g->append >> side) & 1)) continue;
+                const int inw = p->enc[side].in_width, r = p->enc[side].r;
+                if (tid < inw) {
+                    // column tid of the encoder input = component tid % dh of the (tid / dh)-th stored head
+                    const int k = tid / dh;
+                    int head = 0;
+#pragma unroll
+                    for (int i = 0; i < kAppendMaxHeads; ++i) head = i == k ? (int)p->enc[side].heads[i] : head;
+                    xs[tid] = Elem<E>::load(p->enc[side].x, (size_t)b * d_kv + head * dh + (tid - k * dh));
+                }
+                __syncthreads();
+                if (tid < 256) {
+                    // thread = (row group rg of 16, column group cg of 16): rows rg * in_width / 16 .., columns 8 cg .. 8 cg + 7;
+                    // its 16-byte loads of the matrix are all in flight together
+                    const int rg = tid >> 4, c = 8 * (tid & 15), rows = inw >> 4;
+                    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    if (c < r) {
+                        const char* w = static_cast<const char*>(p->enc[side].w) + ((size_t)rg * rows * r + c) * 2;
+                        for (int i0 = 0; i0 < rows; i0 += 8) {
+                            u32x4_t wv[8];
+#pragma unroll
+                            for (int u = 0; u < 8; ++u)
+                                wv[u] = i0 + u < rows ? *reinterpret_cast<const u32x4_t*>(w + (size_t)(i0 + u) * r * 2) : u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+                            for (int u = 0; u < 8; ++u) {
+                                const float x = i0 + u < rows ? xs[rg * rows + i0 + u] : 0.f;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    a[2 * e] = fmaf(x, Mma<E>::unpack_lo(wv[u][e]), a[2 * e]);
+                                    a[2 * e + 1] = fmaf(x, Mma<E>::unpack_hi(wv[u][e]), a[2 * e + 1]);
+                                }
+                            }
+                        }
+                    }
+                    // the four row groups of a wave (lane / 16) meet by two cross-lane steps, the four waves through LDS
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        a[e] += __shfl_xor(a[e], 16);
+                        a[e] += __shfl_xor(a[e], 32);
+                    }
+                    if (lane < 16 && c < r) {
+                        *reinterpret_cast<f32x4_t*>(ps + wave * 128 + c) = f32x4_t{a[0], a[1], a[2], a[3]};
+                        *reinterpret_cast<f32x4_t*>(ps + wave * 128 + c + 4) = f32x4_t{a[4], a[5], a[6], a[7]};
+                    }
+                }
+                __syncthreads();
+                if (tid < r) {
+                    const float z = ((ps[tid] + ps[128 + tid]) + (ps[256 + tid] + ps[384 + tid])) + (p->enc[side].b ? Elem<E>::load(p->enc[side].b, tid) : 0.f);
+                    const uint16_t z16 = Mma<E>::to16(z);
+                    zn[side * 128 + tid] = z16;
+                    if ((g->append >> (2 + side)) & 1)
+                        static_cast<uint16_t*>(p->enc[side].z)[((size_t)b * p->max_seq + (n_ctx - 1)) * r + tid] = z16;
+                }
+                __syncthreads();
+            }
+            znew = reinterpret_cast<const char*>(zn);
+            patch_k = (g->append & 1) != 0;
+            patch_v = (g->append & 2) != 0;
+        }
+    }
     // int8: Qsum[nb] = sum over the latent index of this lane's head's absorbed query, as rounded to fp16
     float qsum[NHB];
 #pragma unroll
@@ -493,6 +570,11 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         if constexpr (G::kPrefetch) {
             park_tile<NL>(sg.v, lds_v, nlv, cprv, stride_v, lane);
             if (j + PF * jstep < j1) issue(sg, j + PF * jstep);
+            if (znew != nullptr && n_ctx - 1 >= t0 && n_ctx - 1 < t0 + kWaveTile) {      // append-and-attend: the row encoded above
+                const int rown = n_ctx - 1 - t0;
+                if (patch_k && lane < cprk) *reinterpret_cast<u32x4_t*>(lds_k + rown * stride_k + lane * 16) = *reinterpret_cast<const u32x4_t*>(znew + lane * 16);
+                if (patch_v && lane < cprv) *reinterpret_cast<u32x4_t*>(lds_v + rown * stride_v + lane * 16) = *reinterpret_cast<const u32x4_t*>(znew + 256 + lane * 16);
+            }
         }
         }
 

@@ -557,8 +557,30 @@ int encode_impl(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new,
 
 // `library_scratch`: the workspace is the library's static buffer (sized by the caller of this function, not by the
 // user) and the call must not create anything: no timing events.
+// The new token of an append-and-attend call.
+struct NewToken {
+    const void* k_new;
+    const void* v_new;
+};
+
+// Whether the attention launch planned for (layer, batch, n_ctx) can encode the new token itself: a matrix-core form with
+// its prologue inside (single split, or the one-launch split form), rows in the model dtype, linear encoders of the sizes
+// the in-kernel encoder handles, contiguous token ranges per split.
+bool can_append_in_kernel(const kvcar_ctx* ctx, int layer, const Plan& plan) {
+    if (!(plan.fused || plan.arrive) || plan.mlp || plan.i8 || ctx->int8() || ctx->tun.tile_order == 2) return false;
+    if (ctx->cfg.n_kv_heads > kAppendMaxHeads) return false;
+    for (int which = 0; which < 2; ++which) {
+        const AEState& a = ctx->ae_at(layer, which);
+        if (!a.set) return false;
+        if (a.d.latent_width == 0) continue;
+        if (a.d.hidden_width != 0 || a.d.in_width > 256 || a.d.in_width % 16 || a.d.latent_width > 128) return false;
+        if (ctx->cache[(size_t)layer * 2 + which] == nullptr) return false;
+    }
+    return true;
+}
+
 int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, const kvcar_step_ext* ext, void* workspace,
-                size_t workspace_bytes, void* stream, bool library_scratch = false) {
+                size_t workspace_bytes, void* stream, bool library_scratch = false, const NewToken* fresh = nullptr) {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     const kvcar_config& c = ctx->cfg;
@@ -579,6 +601,8 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
                           "use kvcar_decode_attention with a workspace", plan.total_bytes, workspace_bytes)
                    : fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, plan.total_bytes);
 
+    if (fresh && !can_append_in_kernel(ctx, layer, plan)) return fail(ctx, KVCAR_ERR_STATE, "internal: this plan cannot encode in the attention kernel");
+    bool writer_given[2] = {false, false};
     hipStream_t st = static_cast<hipStream_t>(stream);
     for (size_t g0 = 0; g0 < plan.groups.size(); g0 += kMaxGroups) {
         AttendParams p{};
@@ -596,6 +620,26 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
         p.k_cur = exact ? ext->k_cur : nullptr;
         p.v_cur = exact ? ext->v_cur : nullptr;
         p.tile_order = ctx->tun.tile_order == 2 ? 1 : 0;
+        if (fresh) {
+            p.append = 1;
+            const void* xs[2] = {fresh->k_new, fresh->v_new};
+            for (int which = 0; which < 2; ++which) {
+                const AEState& a = ctx->ae_at(layer, which);
+                AppendSide& e = p.enc[which];
+                e.x = xs[which];
+                e.z = ctx->cache[(size_t)layer * 2 + which];
+                e.w = a.d.enc_w1; e.b = a.d.enc_b1;
+                e.in_width = a.d.in_width; e.r = a.d.latent_width;
+                for (size_t i = 0; i < a.heads.size() && i < (size_t)kAppendMaxHeads; ++i) e.heads[i] = (unsigned char)a.heads[i];
+                if (e.r == 0) continue;
+                for (int i = 0; i < p.n_groups; ++i) {
+                    const SideDesc& sd = which == 0 ? p.g[i].k : p.g[i].v;
+                    if (sd.z != e.z) continue;                       // rows of another layer
+                    p.g[i].append |= (short)(1 << which);
+                    if (!writer_given[which]) { p.g[i].append |= (short)(4 << which); writer_given[which] = true; }
+                }
+            }
+        }
         // fused: 1 = four waves per workgroup; 2 = eight, when the launch has no more workgroups than compute units
         const bool w8 = ctx->tun.wg_waves == 8 || (ctx->tun.wg_waves == 0 && batch * p.n_groups <= ctx->n_cu);
         if (plan.arrive) {
@@ -752,6 +796,28 @@ int kvcar_decode_attention_static(kvcar_ctx* ctx, int layer, const void* q, void
     return decode_impl(ctx, layer, q, out, batch, n_ctx, nullptr, sp, KVCAR_STATIC_SCRATCH_BYTES, stream, true);
 } catch (...) { return KVCAR_ERR_NOMEM; }
 
+int kvcar_append_attend(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, const void* q, void* out, int batch, int pos,
+                        void* workspace, size_t workspace_bytes, void* stream) try {
+    int rc = check_layer(ctx, layer);
+    if (rc) return rc;
+    const kvcar_config& c = ctx->cfg;
+    if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return fail(ctx, KVCAR_ERR_ARG, "k_new / v_new null or misaligned");
+    if (batch < 1 || pos < 0) return fail(ctx, KVCAR_ERR_ARG, "batch must be >= 1 and pos >= 0");
+    if (batch > c.max_batch || (long long)pos + 1 > c.max_seq)
+        return fail(ctx, KVCAR_ERR_CAPACITY, "append at %d for batch %d exceeds max_seq %d / max_batch %d", pos, batch, c.max_seq, c.max_batch);
+    Plan plan;
+    rc = build_plan(ctx, layer, batch, pos + 1, plan);
+    if (rc) return rc;
+    if (can_append_in_kernel(ctx, layer, plan)) {
+        // every stored side of the layer must be read by the layer itself (its own heads are), or nobody would write the row
+        const NewToken fresh{k_new, v_new};
+        return decode_impl(ctx, layer, q, out, batch, pos + 1, nullptr, workspace, workspace_bytes, stream, false, &fresh);
+    }
+    rc = encode_impl(ctx, layer, k_new, v_new, batch, pos, nullptr, 1, stream);
+    if (rc) return rc;
+    return decode_impl(ctx, layer, q, out, batch, pos + 1, nullptr, workspace, workspace_bytes, stream);
+} catch (...) { return KVCAR_ERR_NOMEM; }
+
 int kvcar_prefill_workspace_bytes(const kvcar_ctx* ctx, int batch, int n_rows, size_t* bytes) try {
     if (!ctx || !bytes) return KVCAR_ERR_ARG;
     if (batch < 1 || batch > ctx->cfg.max_batch || n_rows < 1 || n_rows > ctx->cfg.max_seq)
@@ -784,6 +850,7 @@ int kvcar_describe_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, k
     for (auto& g : plan.groups) lat += (size_t)(g.k.r + g.v.r);
     out->latent_bytes = lat * ctx->row_elem_bytes() * batch * n_ctx;
     if (ctx->int8()) out->latent_bytes += plan.groups.size() * 2 * sizeof(RowMeta) * (size_t)batch * n_ctx;
+    out->append_in_kernel = can_append_in_kernel(ctx, layer, plan) ? 1 : 0;
     return KVCAR_OK;
 } catch (...) { return KVCAR_ERR_NOMEM; }
 

@@ -62,8 +62,24 @@ struct GroupDesc {
     short n_kseg, n_vseg;
     short kseg_lo[4], kseg_hi[4], kseg_col[4];
     short vseg_lo[4], vseg_hi[4], vseg_col[4];
+    // Append-and-attend: bit 0 / 1 = this group's key / value rows come from the layer whose new token the launch
+    // encodes (so its last row is the one being appended); bit 2 / 3 = this group's workgroup also writes that row to
+    // the cache (one group per side does).
+    short append;
 };
 constexpr int kMaxSeg = 4;
+
+constexpr int kAppendMaxHeads = 16;  // KV heads a layer may have for the in-kernel encoder of append-and-attend
+
+// One side (keys or values) of the token that append-and-attend encodes inside the attention kernel: a linear encoder.
+struct AppendSide {
+    const void* x;        // [batch, d_kv]: the new token's vectors
+    void* z;              // the layer's own cache [max_batch, max_seq, r]
+    const void* w;        // encoder matrix [in_width, r]
+    const void* b;        // its bias or null
+    int in_width, r;      // r = 0: the layer stores nothing on this side
+    unsigned char heads[kAppendMaxHeads];   // KV heads whose columns form the encoder input, in order
+};
 
 struct AttendParams {
     GroupDesc g[kMaxGroups];
@@ -85,6 +101,8 @@ struct AttendParams {
     unsigned long long* arrive;   // fused == 4: arrival counter of (sequence b, group z of this launch) at [(b * arrive_stride + z) * kArrivePitch]:
     int arrive_stride;            //   {tag : 32, count : 32}; valid only while the tag equals `epoch`
     unsigned epoch;               //   tag of this launch (never 0)
+    int append;                   // 1 = append-and-attend: the new token (position n_ctx - 1 of every sequence) is encoded in
+    AppendSide enc[2];            //   this kernel, written to the cache and attended to as the context's last row
     int gq;               // query heads per KV head
     const int* seq_lens;  // per-sequence context length [batch] (ragged batch), or null: n_ctx for all
     const void* k_cur;    // exact key / value row of the current token [batch, H_kv * d_head], attended as one

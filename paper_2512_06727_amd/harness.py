@@ -111,6 +111,16 @@ class Session:
         self.ctx.decode_attention(layer, q, out, b, n_ctx, self.workspace)
         return out
 
+    def append_attend(self, layer: int, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor, pos: int,
+                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """One decode step of a layer: k_new, v_new [batch, 1, D_kv] are encoded and appended at `pos`, q attends over rows 0 .. pos."""
+        b = q.shape[0]
+        self.ensure_workspace(b, pos + 1)
+        if out is None:
+            out = torch.empty_like(q)
+        self.ctx.append_attend(layer, k_new, v_new, q, out, b, pos, self.workspace)
+        return out
+
     def prefill_attention(self, layer: int, q: torch.Tensor, pos0: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         """q [batch, t_new, H_q, d_head]: causal attention of the chunk at positions pos0.. over the caches."""
         b, t = q.shape[0], q.shape[1]
