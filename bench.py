@@ -613,6 +613,7 @@ def main():
     ap.add_argument("--tile-order", type=int, default=0, help="0 library default, 1 contiguous token range per split, 2 tiles dealt round-robin")
     ap.add_argument("--policy", default="", help="P1 (latent shrinks with stored heads) or P2 (full width)")
     ap.add_argument("--no-reuse", action="store_true")
+    ap.add_argument("--reuse", default="", help="override the reuse map, e.g. kvbernoulli:0.3 (keys and values drawn independently)")
     ap.add_argument("--act", default="", help="override the activation of a two-layer autoencoder (gelu | leaky_relu)")
     ap.add_argument("--cpu-seconds", type=float, default=30.0, help="time budget of the CPU-oracle leg (up to 96 units); 0 skips it")
     ap.add_argument("--no-workloads", action="store_true", help="default run only: skip the block with the other four configurations")
@@ -670,6 +671,8 @@ def main():
         w = w.scaled(policy=args.policy)
     if args.no_reuse:
         w = w.scaled(reuse="none")
+    if args.reuse:
+        w = w.scaled(reuse=args.reuse)
     if args.act:
         w = w.scaled(act=args.act)
     m = measure_decode(w, args, args.steps, args.warmup, graph=not args.no_graph)
@@ -681,7 +684,7 @@ def main():
     # taken with the kernels that are running now (it records a hash of the kernel sources)
     traffic, traffic_note = None, "no counter summary for this workload"
     tpath = os.path.join(ROOT, "profiles", "attend_i8_mfma_long_context_pmc.md" if args.latent == "int8" else "attend_mfma_long_context_pmc.md")
-    if os.path.exists(tpath) and args.workload == 4 and args.variant == "cache" and not (args.batch or args.cached or args.no_reuse or args.policy):
+    if os.path.exists(tpath) and args.workload == 4 and args.variant == "cache" and not (args.batch or args.cached or args.no_reuse or args.policy or args.reuse):
         import re
         text = open(tpath).read()
         mt = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", text)

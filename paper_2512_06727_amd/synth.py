@@ -109,7 +109,7 @@ class Workload:
     latent: int              # r of a layer that stores all its heads
     hidden: int = 0          # 0: linear autoencoder; else width of the FC before/after the latent
     act: str = "none"        # 'none' | 'gelu' | 'leaky_relu'
-    reuse: str = "none"      # 'none' | 'odd:3' | 'from2:1' | 'bernoulli:0.3'
+    reuse: str = "none"      # 'none' | 'odd:3' | 'from2:1' | 'bernoulli:0.3' | 'kvbernoulli:0.3'
     policy: str = "P1"       # P1: latent shrinks with the stored heads; P2: full-width latent
     weight_std: float = 0.02
     seed: int = 0
@@ -160,6 +160,8 @@ def reuse_map(w: Workload) -> np.ndarray:
             m[layer, :, rng.choice(w.n_kv_heads, size=int(arg), replace=False)] = True
         elif kind == "bernoulli":
             m[layer, :, :] = rng.random(w.n_kv_heads) < float(arg)
+        elif kind == "kvbernoulli":                       # keys and values drawn independently
+            m[layer] = rng.random((2, w.n_kv_heads)) < float(arg)
         elif kind == "all" and layer >= 1:
             m[layer, :, :] = True
     return m
