@@ -466,6 +466,11 @@ def roofline_entry(w, m, latent_format):
          "traffic": None, "algorithmic_bytes_per_launch": m["alg_bytes"] / max(1, m["n_launch"]),
          "avg_launch_ms": m["attend_ms"] / max(1, m["n_launch"]), "launches": m["n_launch"],
          "whole_step_GBs": m["alg_bytes"] / m["steps"] / (m["ms_per_step"] * 1e-3) / 1e9}
+    if m.get("sep_attend_ms"):
+        a2 = m["alg_bytes"] / (m["sep_attend_ms"] * 1e-3) / 1e9
+        r["attention_launch_without_encoder"] = {"avg_launch_ms": m["sep_attend_ms"] / max(1, m["n_launch"]), "achieved": a2, "frac": a2 / HBM_PEAK_GBS,
+                                                 "note": "same steps as kvcar_encode_append + kvcar_decode_attention: the attention kernel alone; the figures above "
+                                                         "are for the one kernel per layer that also encodes and appends the new token"}
     if w.hidden and plan.uses_mfma:
         tf = m["alg_flops"] / (m["attend_ms"] * 1e-3) / 1e12
         r["mfma"] = {"achieved": tf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS,
@@ -588,6 +593,16 @@ def measure_decode(w, args, steps, warmup, graph=True, plain=False):
         step_fn(step)
     attend_ms, n_launch = ctx.profile_read()
     ctx.profile_enable(False)
+    # the same steps once more as two calls per layer (encoder launch + attention launch), for the attention kernel alone
+    sep_ms = None
+    if not separate and variant == "cache" and not plain and ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq).append_in_kernel:
+        separate = True
+        ctx.profile_enable(True)
+        for step in range(warmup, total_steps):
+            step_fn(step)
+        sep_ms, _ = ctx.profile_read()
+        ctx.profile_enable(False)
+        separate = False
     alg, flops = 0, 0
     for step in range(warmup, total_steps):
         n_rows = w.n_cached + step + (0 if variant == "exact" else 1)
@@ -597,7 +612,7 @@ def measure_decode(w, args, steps, warmup, graph=True, plain=False):
             alg += sum(algorithmic_latent_bytes(w, reuse, widths, w.batch, n_rows, lat_elem, row_meta))
         flops += attention_flops_per_token(w) * w.batch * n_rows * w.n_layers
     return {"reuse": reuse, "widths": widths, "ms_per_step": ms_per_step, "tokens_per_s": tokens_per_s, "graph_ms": graph_ms,
-            "attend_ms": attend_ms, "n_launch": n_launch, "alg_bytes": alg, "alg_flops": flops, "steps": steps, "prefill_s": t_fill,
+            "attend_ms": attend_ms, "sep_attend_ms": sep_ms, "n_launch": n_launch, "alg_bytes": alg, "alg_flops": flops, "steps": steps, "prefill_s": t_fill,
             "plan": ctx.describe_plan(w.n_layers - 1, w.batch, w.max_seq), "one_call": not separate and variant == "cache"}
 
 

@@ -111,7 +111,7 @@ hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stre
         // eight waves: staging regions + swapped query operands, or the epilogue's exchange area (m, l of
         // eight waves) + latent sums + one decoder slice
         const size_t epi = 2048 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);
-        const size_t stage = 8 * Geo<128>::kWaveLds + 2 * 4 * 64 * 16;
+        const size_t stage = 8 * Geo<128>::kWaveLds + 2 * 4 * 64 * 16 + 512;      // + the new token's rows (append-and-attend)
         const size_t lds = epi > stage ? epi : stage;
         return e == 0 ? launch_one(attend_mfma_r128_w8_kernel<BF16>, lds, p, stream, set128w8[0], 512)
                       : launch_one(attend_mfma_r128_w8_kernel<F16>, lds, p, stream, set128w8[1], 512);
@@ -120,7 +120,7 @@ hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stre
         // fused: + normalised latent sums [32][132] fp32 + one decoder-matrix slice [128][2*d_head+32]
         // fused epilogue: exchange area + latent sums [32][132] fp32 + one decoder slice [128][2*d_head+32]
         const size_t epi = 1024 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);
-        const size_t stage = mfma_lds_bytes(128, 2) + (p.fused ? 2 * 4 * 64 * 16 : 0);   // + swapped query operands
+        const size_t stage = mfma_lds_bytes(128, 2) + (p.fused ? 2 * 4 * 64 * 16 + 512 : 0);   // + swapped query operands + the new token's rows (append-and-attend)
         const size_t lds = epi > stage ? epi : stage;
         return e == 0 ? launch_one(attend_mfma_r128_kernel<BF16>, lds, p, stream, set128[0])
                       : launch_one(attend_mfma_r128_kernel<F16>, lds, p, stream, set128[1]);

@@ -78,6 +78,10 @@ inline bool exact_shape(int r, int nhb) {
 constexpr int kWaveTile = 32;     // tokens per wave per iteration
 constexpr int kWaves = 4;
 
+#ifndef KVCAR_APPEND_IN_KERNEL
+#define KVCAR_APPEND_IN_KERNEL 1
+#endif
+
 #ifndef KVCAR_NT_LOADS
 #define KVCAR_NT_LOADS 1
 #endif
@@ -337,6 +341,96 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         if (threadIdx.x == 0) seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
+    // ---- append-and-attend: the new token's latent rows ("Network Architecture", 1st paragraph: the encoder after K/V
+    // generation), computed by the workgroup that holds the context's last tile instead of by an encoder launch
+    // before this one.  z = x[columns of the stored heads] . W_enc + b in fp32, rounded once to the cache dtype; the
+    // row is written to the layer's cache (by one group per side) and kept in LDS, from where it replaces the last row
+    // of the tile as parked - the copy of that row loaded from memory may predate the write.
+    const char* znew = nullptr;
+    bool patch_k = false, patch_v = false;
+    auto encode_new_token = [&]() {
+        // runs between the prologue's exchange barrier and the reads of the query operands: few registers are live then,
+        // and the waves' staging regions (the first tiles are still in flight, in registers) serve as scratch
+        // eight waves: the first four take the keys, the other four the values, at the same time; four waves: one side after the other
+        constexpr int kPasses = NW >= 8 ? 1 : 2;
+        float* xs_all = reinterpret_cast<float*>(lds_raw);   // [2 sides][in_width <= 256]
+        float* ps_all = xs_all + 512;                        // [2 sides][4 waves][128]
+        uint16_t* zn = reinterpret_cast<uint16_t*>(lds_raw + NW * wave_lds + 2 * 4 * 64 * 16);      // [2 sides][128], past the exchange area: kept through the loop
+        const int dh = p->d_head, d_kv = (p->n_q_heads / p->gq) * dh;
+        const int tid = threadIdx.x & 255, w4 = wave & 3;
+#pragma unroll
+        for (int pass = 0; pass < kPasses; ++pass) {
+            const int side = kPasses == 1 ? (int)(threadIdx.x >> 8) : pass;
+            // this side's encoder (read with constant indices: the argument block must not be indexed by a run-time value)
+            const bool v_side = side == 1;
+            const bool on = ((g->append >> side) & 1) != 0 && (kPasses == 1 || threadIdx.x < 256);
+            const int inw = v_side ? p->enc[1].in_width : p->enc[0].in_width, r = v_side ? p->enc[1].r : p->enc[0].r;
+            const void* ex = v_side ? p->enc[1].x : p->enc[0].x;
+            const void* ew = v_side ? p->enc[1].w : p->enc[0].w;
+            const void* eb = v_side ? p->enc[1].b : p->enc[0].b;
+            void* ez = v_side ? p->enc[1].z : p->enc[0].z;
+            float* xs = xs_all + side * 256;
+            float* ps = ps_all + side * 512;
+            if (on && tid < inw) {
+                // column tid of the encoder input = component tid % dh of the (tid / dh)-th stored head
+                const int k = tid / dh;
+                int head = 0;
+#pragma unroll
+                for (int i = 0; i < kAppendMaxHeads; ++i) head = i == k ? (int)(v_side ? p->enc[1].heads[i] : p->enc[0].heads[i]) : head;
+                xs[tid] = Elem<E>::load(ex, (size_t)b * d_kv + head * dh + (tid - k * dh));
+            }
+            __syncthreads();
+            if (on) {
+                // thread = (row group rg of 16, column group cg of 16): rows rg * in_width / 16 .., columns 8 cg .. 8 cg + 7;
+                // its 16-byte loads of the matrix are in flight eight at a time
+                const int rg = tid >> 4, c = 8 * (tid & 15), rows = inw >> 4;
+                float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                if (c < r) {
+                    const char* w = static_cast<const char*>(ew) + ((size_t)rg * rows * r + c) * 2;
+                    for (int i0 = 0; i0 < rows; i0 += 8) {
+                        u32x4_t wv[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            wv[u] = i0 + u < rows ? *reinterpret_cast<const u32x4_t*>(w + (size_t)(i0 + u) * r * 2) : u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const float x = i0 + u < rows ? xs[rg * rows + i0 + u] : 0.f;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                a[2 * e] = fmaf(x, Mma<E>::unpack_lo(wv[u][e]), a[2 * e]);
+                                a[2 * e + 1] = fmaf(x, Mma<E>::unpack_hi(wv[u][e]), a[2 * e + 1]);
+                            }
+                        }
+                    }
+                }
+                // the four row groups of a wave (lane / 16) meet by two cross-lane steps, the four waves through LDS
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    a[e] += __shfl_xor(a[e], 16);
+                    a[e] += __shfl_xor(a[e], 32);
+                }
+                if (lane < 16 && c < r) {
+                    *reinterpret_cast<f32x4_t*>(ps + w4 * 128 + c) = f32x4_t{a[0], a[1], a[2], a[3]};
+                    *reinterpret_cast<f32x4_t*>(ps + w4 * 128 + c + 4) = f32x4_t{a[4], a[5], a[6], a[7]};
+                }
+            }
+            __syncthreads();
+            if (on && tid < r) {
+                const float z = ((ps[tid] + ps[128 + tid]) + (ps[256 + tid] + ps[384 + tid])) + (eb ? Elem<E>::load(eb, tid) : 0.f);
+                const uint16_t z16 = Mma<E>::to16(z);
+                zn[side * 128 + tid] = z16;
+                if ((g->append >> (2 + side)) & 1)
+                    static_cast<uint16_t*>(ez)[((size_t)b * p->max_seq + (n_ctx - 1)) * r + tid] = z16;
+            }
+            __syncthreads();
+        }
+        znew = reinterpret_cast<const char*>(zn);
+        patch_k = (g->append & 1) != 0;
+        patch_v = (g->append & 2) != 0;
+    };
+    bool encode_here = false;
+    if constexpr (kPrologue && !kI8 && KVCAR_APPEND_IN_KERNEL) encode_here = p->append && (g->append & 3) && j0 < j1 && j1 == wg_tiles;     // the same for the whole workgroup
+
     // absorbed queries of this sequence and group, resident as MFMA B operands
     u32x4_t qb[NHB][KS];
     if constexpr (kPrologue) {
@@ -402,6 +496,9 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             }
         }
         __syncthreads();
+        if constexpr (!kI8 && KVCAR_APPEND_IN_KERNEL) {
+            if (encode_here) encode_new_token();
+        }
 #pragma unroll
         for (int nb = 0; nb < NHB; ++nb)
 #pragma unroll
@@ -432,83 +529,6 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         const unsigned long long fresh = (unsigned long long)p->epoch << 32;
         if (threadIdx.x == 0 && (unsigned)(seen >> 32) != p->epoch)
             __hip_atomic_compare_exchange_strong(counter, &seen, fresh, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    // ---- append-and-attend: the new token's latent rows ("Network Architecture", 1st paragraph: the encoder after K/V
-    // generation), computed here by the workgroup that holds the context's last tile instead of by an encoder launch
-    // before this one.  z = x[columns of the stored heads] . W_enc + b in fp32, rounded once to the cache dtype; the
-    // row is written to the layer's cache (by one group per side) and kept in LDS, from where it replaces the last row
-    // of the tile as parked - the copy of that row loaded from memory may predate the write.
-    const char* znew = nullptr;
-    bool patch_k = false, patch_v = false;
-    if constexpr (kPrologue && !kI8) {
-        if (p->append && (g->append & 3) && j0 < j1 && j1 == wg_tiles) {     // the same for the whole workgroup
-            char* app = lds_raw + NW * wave_lds;                // the query-operand exchange area, free from here on
-            float* xs = reinterpret_cast<float*>(app);          // [in_width <= 256]
-            float* ps = xs + 256;                               // [4 waves][128]
-            uint16_t* zn = reinterpret_cast<uint16_t*>(ps + 512);      // [2 sides][128]
-            const int tid = threadIdx.x, dh = p->d_head, d_kv = (p->n_q_heads / p->gq) * dh;
-            __syncthreads();                                    // every wave has taken its query operands out of the area
-#pragma unroll
-            for (int side = 0; side < 2; ++side) {
-                if (!((g->append >> side) & 1)) continue;
-                const int inw = p->enc[side].in_width, r = p->enc[side].r;
-                if (tid < inw) {
-                    // column tid of the encoder input = component tid % dh of the (tid / dh)-th stored head
-                    const int k = tid / dh;
-                    int head = 0;
-#pragma unroll
-                    for (int i = 0; i < kAppendMaxHeads; ++i) head = i == k ? (int)p->enc[side].heads[i] : head;
-                    xs[tid] = Elem<E>::load(p->enc[side].x, (size_t)b * d_kv + head * dh + (tid - k * dh));
-                }
-                __syncthreads();
-                if (tid < 256) {
-                    // thread = (row group rg of 16, column group cg of 16): rows rg * in_width / 16 .., columns 8 cg .. 8 cg + 7;
-                    // its 16-byte loads of the matrix are all in flight together
-                    const int rg = tid >> 4, c = 8 * (tid & 15), rows = inw >> 4;
-                    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                    if (c < r) {
-                        const char* w = static_cast<const char*>(p->enc[side].w) + ((size_t)rg * rows * r + c) * 2;
-                        for (int i0 = 0; i0 < rows; i0 += 8) {
-                            u32x4_t wv[8];
-#pragma unroll
-                            for (int u = 0; u < 8; ++u)
-                                wv[u] = i0 + u < rows ? *reinterpret_cast<const u32x4_t*>(w + (size_t)(i0 + u) * r * 2) : u32x4_t{0u, 0u, 0u, 0u};
-#pragma unroll
-                            for (int u = 0; u < 8; ++u) {
-                                const float x = i0 + u < rows ? xs[rg * rows + i0 + u] : 0.f;
-#pragma unroll
-                                for (int e = 0; e < 4; ++e) {
-                                    a[2 * e] = fmaf(x, Mma<E>::unpack_lo(wv[u][e]), a[2 * e]);
-                                    a[2 * e + 1] = fmaf(x, Mma<E>::unpack_hi(wv[u][e]), a[2 * e + 1]);
-                                }
-                            }
-                        }
-                    }
-                    // the four row groups of a wave (lane / 16) meet by two cross-lane steps, the four waves through LDS
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        a[e] += __shfl_xor(a[e], 16);
-                        a[e] += __shfl_xor(a[e], 32);
-                    }
-                    if (lane < 16 && c < r) {
-                        *reinterpret_cast<f32x4_t*>(ps + wave * 128 + c) = f32x4_t{a[0], a[1], a[2], a[3]};
-                        *reinterpret_cast<f32x4_t*>(ps + wave * 128 + c + 4) = f32x4_t{a[4], a[5], a[6], a[7]};
-                    }
-                }
-                __syncthreads();
-                if (tid < r) {
-                    const float z = ((ps[tid] + ps[128 + tid]) + (ps[256 + tid] + ps[384 + tid])) + (p->enc[side].b ? Elem<E>::load(p->enc[side].b, tid) : 0.f);
-                    const uint16_t z16 = Mma<E>::to16(z);
-                    zn[side * 128 + tid] = z16;
-                    if ((g->append >> (2 + side)) & 1)
-                        static_cast<uint16_t*>(p->enc[side].z)[((size_t)b * p->max_seq + (n_ctx - 1)) * r + tid] = z16;
-                }
-                __syncthreads();
-            }
-            znew = reinterpret_cast<const char*>(zn);
-            patch_k = (g->append & 1) != 0;
-            patch_v = (g->append & 2) != 0;
-        }
     }
     // int8: Qsum[nb] = sum over the latent index of this lane's head's absorbed query, as rounded to fp16
     float qsum[NHB];
