@@ -227,3 +227,34 @@ def test_one_launch_split_kernel_repeated_on_one_workspace():
             q = synth.queries(w, n, 0, gain=20.0).to(ses.dev, ses.tdt)
             got = ses.decode_attention(n, q, w.n_cached + 1).float().cpu().double().numpy()
             assert_outputs_close(w, [{n: got}], [{n: want[0][n]}], f"repeat {rep} splits {splits} layer {n}")
+
+
+def test_one_launch_split_kernel_gives_the_same_bits_every_time():
+    """The splits' partials cross from one workgroup to another inside the launch (agent-scope stores and loads, an
+    arrival counter): 300 launches in a row on a workspace whose contents are scrambled in between must reproduce the
+    first result bit for bit (the merge order is fixed), and that result must match the oracle.  A partial read before
+    it was complete, or out of a stale cache line, would show up as a differing output."""
+    from paper_2512_06727_amd.harness import Session
+    w = C[2].scaled(n_layers=3, batch=24, n_cached=2300, n_steps=1)
+    ses = Session(w, poison=True)
+    ses.prefill(0, w.n_cached + 1, chunk=512)
+    n_ctx = w.n_cached + 1
+    plan = ses.ctx.describe_plan(2, w.batch, n_ctx)
+    assert plan.fused == 2 and plan.n_splits >= 4
+    ses.ensure_workspace(w.batch, n_ctx)
+    q = synth.queries(w, 2, 0, gain=20.0).to(ses.dev, ses.tdt)
+    first = ses.decode_attention(2, q, n_ctx).clone()
+    orc = build_oracle(w)
+    for n in range(w.n_layers):
+        oracle_prefill(orc, w, n, 0, n_ctx)
+    want = orc.decode_attention(2, synth.queries(w, 2, 0, gain=20.0).double().numpy(), n_ctx)
+    assert_outputs_close(w, [{2: first.float().cpu().double().numpy()}], [{2: want}], "first launch")
+    out = torch.empty_like(first)
+    for rep in range(300):
+        if rep % 10 == 0:
+            ses.workspace.random_(0, 256)           # also scrambles the arrival counters: every launch must cope with any content
+        ses.ctx.decode_attention(2, q, out, w.batch, n_ctx, ses.workspace)
+        if rep % 25 == 24:
+            assert torch.equal(out, first), f"launch {rep} differs"
+    torch.cuda.synchronize()
+    assert torch.equal(out, first)
