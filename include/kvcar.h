@@ -324,8 +324,8 @@ typedef struct {
     int n_launches;         /* attention-kernel launches (groups are batched 8 per launch)      */
     int fused;              /* 1 = one split and prologue and epilogue run inside the attention kernel; 2 = several
                                splits in one launch: the last workgroup of a (sequence, group) merges and decodes
-                               (a call falls back to separate kernels if the library has no arrival counters left
-                               for its workspace: more than 64 workspaces in use); 0 = separate kernels          */
+                               (its arrival counters lie in the workspace and need no initial state);
+                               0 = separate kernels                                             */
     size_t workspace_bytes;
     size_t latent_bytes;    /* bytes of latent rows the attention kernel reads for this call    */
     int append_in_kernel;   /* 1 = kvcar_append_attend at this size encodes the new token inside the
