@@ -281,13 +281,15 @@ def bench_prefill(args):
 
 
 def bench_per_head(args):
-    """Secondary measurement: the per-head (block-diagonal) autoencoder variant of the workload - one library
-    context per KV head, latent / H_kv columns each (harness.PerHeadSessions).  A reused head then reads only its
+    """Secondary measurement: the per-head (block-diagonal) autoencoder variant of the workload - the autoencoder
+    descriptor's per_head flag: every KV head has a d_head -> latent / H_kv -> d_head autoencoder and a block of the
+    cache of its own, a layer's attention is one launch with a group per KV head.  A reused head then reads only its
     own rows of the source layer, so the step moves the bytes of the map-free workload while storing what the map
-    leaves.  A step = for every layer and KV head, kvcar_encode_append + kvcar_decode_attention."""
+    leaves.  A step = kvcar_append_attend for every layer (--separate-encode: kvcar_encode_append +
+    kvcar_decode_attention)."""
     import torch
-    from paper_2512_06727_amd import binding, synth
-    from paper_2512_06727_amd.harness import PerHeadSessions
+    from paper_2512_06727_amd import synth
+    from paper_2512_06727_amd.harness import Session
 
     total_steps = args.steps + args.warmup
     w = synth.CONFIGS[args.workload].scaled(n_steps=total_steps)
@@ -295,30 +297,31 @@ def bench_per_head(args):
         w = w.scaled(batch=args.batch)
     if args.cached:
         w = w.scaled(n_cached=args.cached)
+    if args.reuse:
+        w = w.scaled(reuse=args.reuse)
     reuse = synth.reuse_map(w)
     elem = synth.DTYPE_BYTES[w.dtype]
-    ph = PerHeadSessions(w, reuse)
+    ses = Session(w, reuse, per_head=True, n_splits=args.splits, wg_waves=args.wg_waves, no_arrive=args.no_arrive)
     t0 = time.perf_counter()
-    ph.prefill(0, w.n_cached, chunk=max(1, (1 << 25) // (w.batch * w.d_head)))
+    ses.prefill(0, w.n_cached, chunk=max(1, (1 << 25) // (w.batch * w.d_kv)))
     torch.cuda.synchronize()
     t_fill = time.perf_counter() - t0
     H = w.n_kv_heads
-    qs, ks, vs = [], [], []
-    for step in range(total_steps):
-        pos = w.n_cached + step
-        qs.append([[synth.queries(wg, n, step, device=s.dev).to(s.tdt) for n in range(w.n_layers)] for (wg, _), s in zip(ph.parts, ph.sessions)])
-        ks.append([[synth.kv_tokens(wg, n, 0, 0, w.batch, pos, pos + 1, device=s.dev).to(s.tdt) for n in range(w.n_layers)] for (wg, _), s in zip(ph.parts, ph.sessions)])
-        vs.append([[synth.kv_tokens(wg, n, 1, 0, w.batch, pos, pos + 1, device=s.dev).to(s.tdt) for n in range(w.n_layers)] for (wg, _), s in zip(ph.parts, ph.sessions)])
-    outs = [[torch.empty_like(qs[0][g][n]) for n in range(w.n_layers)] for g in range(H)]
-    for s in ph.sessions:
-        s.ensure_workspace(w.batch, w.max_seq)
+    qs = [[ses.queries(n, step) for n in range(w.n_layers)] for step in range(total_steps)]
+    ks = [[ses.kv(n, 0, w.n_cached + step, w.n_cached + step + 1) for n in range(w.n_layers)] for step in range(total_steps)]
+    vs = [[ses.kv(n, 1, w.n_cached + step, w.n_cached + step + 1) for n in range(w.n_layers)] for step in range(total_steps)]
+    outs = [torch.empty_like(qs[0][n]) for n in range(w.n_layers)]
+    ses.ensure_workspace(w.batch, w.max_seq)
+    ctx, ws = ses.ctx, ses.workspace
 
     def step_fn(step):
         pos = w.n_cached + step
         for n in range(w.n_layers):
-            for g, s in enumerate(ph.sessions):
-                s.ctx.encode_append(n, ks[step][g][n], vs[step][g][n], w.batch, pos, 1)
-                s.ctx.decode_attention(n, qs[step][g][n], outs[g][n], w.batch, pos + 1, s.workspace)
+            if args.separate_encode:
+                ctx.encode_append(n, ks[step][n], vs[step][n], w.batch, pos, 1)
+                ctx.decode_attention(n, qs[step][n], outs[n], w.batch, pos + 1, ws)
+            else:
+                ctx.append_attend(n, ks[step][n], vs[step][n], qs[step][n], outs[n], w.batch, pos, ws)
 
     for step in range(args.warmup):
         step_fn(step)
@@ -328,16 +331,12 @@ def bench_per_head(args):
         step_fn(step)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    for s in ph.sessions:
-        s.ctx.profile_enable(True)
+    ctx.profile_enable(True)
     for step in range(args.warmup, total_steps):
         step_fn(step)
-    attend_ms, n_launch = 0.0, 0
-    for s in ph.sessions:
-        ms, n = s.ctx.profile_read()
-        s.ctx.profile_enable(False)
-        attend_ms += ms
-        n_launch += n
+    attend_ms, n_launch = ctx.profile_read()
+    ctx.profile_enable(False)
+    plan = ctx.describe_plan(w.n_layers - 1, w.batch, w.n_cached + 1)
     r_h = w.latent // H
     alg = sum(2 * r_h * elem * H * w.batch * (w.n_cached + step + 1) * w.n_layers for step in range(args.warmup, total_steps))
     achieved = alg / (attend_ms * 1e-3) / 1e9
@@ -346,10 +345,12 @@ def bench_per_head(args):
         "metric": "decode-attn tokens/s over latent KV cache, per-head autoencoders", "value": w.batch * args.steps / elapsed, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "variant": "per-head autoencoders (one context per KV head)", "batch": w.batch, "cached_tokens": w.n_cached,
+        "config": {"workload": w.name, "variant": "per-head autoencoders (descriptor flag, one context)", "batch": w.batch, "cached_tokens": w.n_cached,
                    "layers": w.n_layers, "kv_heads": H, "latent_per_head": r_h, "reuse": w.reuse, "reused_head_fraction": float(reuse[1:].mean()),
+                   "groups": plan.n_groups, "splits": plan.n_splits, "fused": plan.fused, "append_in_kernel": plan.append_in_kernel and not args.separate_encode,
                    "prefill_s": t_fill},
-        "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel (latent width 32)", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "roofline": {"bound": "hbm", "kernel": "attend_mfma_r128_kernel (latent width 32 per head" + (", new token encoded inside)" if plan.append_in_kernel and not args.separate_encode else ")"),
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": alg / max(1, n_launch),
                      "avg_launch_ms": attend_ms / max(1, n_launch), "launches": n_launch},
         "bytes_per_token_stored": stored, "bytes_per_token_read_per_step": 2 * r_h * elem * H * w.n_layers,
@@ -645,7 +646,7 @@ def main():
                     help="decode: the decode step (default, the headline); l1dist: the reuse-map selection statistic over the workload's tokens; "
                          "prefill: encode + causal attention of a whole prompt (default batch 16 x 4096 tokens of the chosen workload's shape)")
     ap.add_argument("--per-head", action="store_true",
-                    help="the per-head (block-diagonal) autoencoder variant: one context per KV head, reuse adds no cache traffic")
+                    help="the per-head (block-diagonal) autoencoder variant (the descriptor's per_head flag): reuse adds no cache traffic")
     ap.add_argument("--no-fuse", action="store_true", help="run prologue / attention / merge as separate kernels")
     ap.add_argument("--separate-encode", action="store_true",
                     help="a layer's step as kvcar_encode_append + kvcar_decode_attention (two calls) instead of kvcar_append_attend")

@@ -124,6 +124,17 @@ typedef struct {
  *   enc_w1 [in_width, hidden or latent], enc_b1; enc_w2 [hidden, latent], enc_b2 (hidden > 0)
  *   dec_w1 [latent, hidden or in_width], dec_b1; dec_w2 [hidden, in_width], dec_b2 (hidden > 0)
  *   All weight pointers are dev pointers that must outlive every call using the context.
+ *
+ *   per_head      0: one autoencoder over the whole vector, as in the paper (every head's keys depend on the
+ *                 whole latent row).  1: a block-diagonal autoencoder, one d_head -> r_h -> d_head pair per
+ *                 covered head, r_h = latent_width / n_covered (an extension: the paper's autoencoder is dense).
+ *                 A head that reuses an earlier layer's keys or values then reads only that head's latent
+ *                 rows of the source layer.  Linear autoencoders and latent rows in `dtype` only; r_h rows must
+ *                 be a multiple of 16 bytes.  Layouts, with i the position of the head among the covered heads:
+ *                   enc_w1 [n_covered][d_head][r_h], enc_b1 [n_covered][r_h]
+ *                   dec_w1 [n_covered][r_h][d_head], dec_b1 [n_covered][d_head]
+ *                 and the cache of this layer-tensor is head-major, Z[i][b][t][r_h] (b < max_batch,
+ *                 t < max_seq): a head's rows of one sequence are contiguous.  kvcar_cache_bytes is unchanged.
  */
 typedef struct {
     int in_width;
@@ -133,6 +144,7 @@ typedef struct {
     float leaky_slope;
     const void *enc_w1, *enc_b1, *enc_w2, *enc_b2;
     const void *dec_w1, *dec_b1, *dec_w2, *dec_b2;
+    int per_head;       /* 0 or 1, see above */
 } kvcar_ae_desc;
 
 /* Launch tuning; all zero = library defaults. */
@@ -171,7 +183,9 @@ int kvcar_set_reuse_map(kvcar_ctx *ctx, int layer, const uint8_t *k_reuse, const
 int kvcar_resolve_source(const kvcar_ctx *ctx, int layer, int which, int kv_head, int *src_layer);
 
 /* Set the autoencoder of (layer, which).  ERR_SHAPE if in_width matches neither form above or
- * widths are inconsistent; ERR_ARG on null / misaligned required pointers. */
+ * widths are inconsistent (per_head: latent_width not a multiple of the covered heads); ERR_ARG on null /
+ * misaligned required pointers or per_head outside {0, 1}; ERR_UNSUPPORTED for per_head with a hidden layer,
+ * with int8 latents, or with head rows that are not a multiple of 16 bytes. */
 int kvcar_set_autoencoder(kvcar_ctx *ctx, int layer, int which, const kvcar_ae_desc *desc);
 
 /* Bytes of the latent cache of (layer, which): max_batch * max_seq * latent_width * sizeof(dtype)

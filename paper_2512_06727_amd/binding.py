@@ -36,7 +36,8 @@ class AEDesc(C.Structure):
     _fields_ = [("in_width", C.c_int), ("hidden_width", C.c_int), ("latent_width", C.c_int), ("act", C.c_int),
                 ("leaky_slope", C.c_float),
                 ("enc_w1", C.c_void_p), ("enc_b1", C.c_void_p), ("enc_w2", C.c_void_p), ("enc_b2", C.c_void_p),
-                ("dec_w1", C.c_void_p), ("dec_b1", C.c_void_p), ("dec_w2", C.c_void_p), ("dec_b2", C.c_void_p)]
+                ("dec_w1", C.c_void_p), ("dec_b1", C.c_void_p), ("dec_w2", C.c_void_p), ("dec_b2", C.c_void_p),
+                ("per_head", C.c_int)]
 
 
 class Tuning(C.Structure):
@@ -191,9 +192,10 @@ class Context:
         return out.value
 
     def set_autoencoder(self, layer: int, which: int, in_width: int, hidden_width: int, latent_width: int, act: str,
-                        enc, dec, leaky_slope: float = 0.01):
+                        enc, dec, leaky_slope: float = 0.01, per_head: bool = False):
         """enc / dec: lists of (weight tensor, bias tensor or None) on the device."""
         d = AEDesc()
+        d.per_head = 1 if per_head else 0
         d.in_width, d.hidden_width, d.latent_width, d.act, d.leaky_slope = in_width, hidden_width, latent_width, ACTS[act], leaky_slope
         names = [("enc_w1", "enc_b1"), ("enc_w2", "enc_b2")]
         for (wn, bn), (w, b) in zip(names, enc):

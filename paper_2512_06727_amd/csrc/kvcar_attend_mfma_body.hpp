@@ -351,79 +351,130 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     auto encode_new_token = [&]() {
         // runs between the prologue's exchange barrier and the reads of the query operands: few registers are live then,
         // and the waves' staging regions (the first tiles are still in flight, in registers) serve as scratch
-        // eight waves: the first four take the keys, the other four the values, at the same time; four waves: one side after the other
-        constexpr int kPasses = NW >= 8 ? 1 : 2;
+        // eight waves: the first four take the keys, the other four the values; four waves: every thread works on both
+        // sides, phase by phase, so that the two sides' memory round trips overlap (three barriers either way)
+        constexpr int S = NW >= 8 ? 1 : 2;
         float* xs_all = reinterpret_cast<float*>(lds_raw);   // [2 sides][in_width <= 256]
         float* ps_all = xs_all + 512;                        // [2 sides][4 waves][128]
         uint16_t* zn = reinterpret_cast<uint16_t*>(lds_raw + NW * wave_lds + 2 * 4 * 64 * 16);      // [2 sides][128], past the exchange area: kept through the loop
         const int dh = p->d_head, d_kv = (p->n_q_heads / p->gq) * dh;
         const int tid = threadIdx.x & 255, w4 = wave & 3;
+        // one side's encoder (read with constant indices: the argument block must not be indexed by a run-time value)
+        struct Side {
+            bool on, v_side;
+            int inw, r, b_off;
+            long long head_block;
+            const void* ex;
+            const char* ew;
+            const void* eb;
+            char* ez;
+        };
+        auto side_of = [&](int side) {
+            Side e;
+            e.v_side = side == 1;
+            e.on = ((g->append >> side) & 1) != 0;
+            e.inw = e.v_side ? p->enc[1].in_width : p->enc[0].in_width;
+            e.r = e.v_side ? p->enc[1].r : p->enc[0].r;
+            e.ex = e.v_side ? p->enc[1].x : p->enc[0].x;
+            e.ew = static_cast<const char*>(e.v_side ? p->enc[1].w : p->enc[0].w);
+            e.eb = e.v_side ? p->enc[1].b : p->enc[0].b;
+            e.ez = static_cast<char*>(e.v_side ? p->enc[1].z : p->enc[0].z);
+            // per-head autoencoders: this group's head has an encoder, a bias and a block of the cache of its own
+            e.head_block = e.v_side ? p->enc[1].head_block : p->enc[0].head_block;
+            const int slice = e.head_block ? (int)(e.v_side ? g->app_slice[1] : g->app_slice[0]) : 0;
+            e.ew += (size_t)slice * e.inw * e.r * 2;
+            e.ez += (size_t)slice * e.head_block;
+            e.b_off = slice * e.r;
+            return e;
+        };
+        Side sd[S];
 #pragma unroll
-        for (int pass = 0; pass < kPasses; ++pass) {
-            const int side = kPasses == 1 ? (int)(threadIdx.x >> 8) : pass;
-            // this side's encoder (read with constant indices: the argument block must not be indexed by a run-time value)
-            const bool v_side = side == 1;
-            const bool on = ((g->append >> side) & 1) != 0 && (kPasses == 1 || threadIdx.x < 256);
-            const int inw = v_side ? p->enc[1].in_width : p->enc[0].in_width, r = v_side ? p->enc[1].r : p->enc[0].r;
-            const void* ex = v_side ? p->enc[1].x : p->enc[0].x;
-            const void* ew = v_side ? p->enc[1].w : p->enc[0].w;
-            const void* eb = v_side ? p->enc[1].b : p->enc[0].b;
-            void* ez = v_side ? p->enc[1].z : p->enc[0].z;
-            float* xs = xs_all + side * 256;
-            float* ps = ps_all + side * 512;
-            if (on && tid < inw) {
+        for (int si = 0; si < S; ++si) sd[si] = side_of(S == 1 ? (int)(threadIdx.x >> 8) : si);
+        // ---- the token's vectors into LDS, as fp32
+#pragma unroll
+        for (int si = 0; si < S; ++si) {
+            const Side& e = sd[si];
+            if (e.on && tid < e.inw) {
                 // column tid of the encoder input = component tid % dh of the (tid / dh)-th stored head
                 const int k = tid / dh;
                 int head = 0;
 #pragma unroll
-                for (int i = 0; i < kAppendMaxHeads; ++i) head = i == k ? (int)(v_side ? p->enc[1].heads[i] : p->enc[0].heads[i]) : head;
-                xs[tid] = Elem<E>::load(ex, (size_t)b * d_kv + head * dh + (tid - k * dh));
+                for (int i = 0; i < kAppendMaxHeads; ++i) head = i == k ? (int)(e.v_side ? p->enc[1].heads[i] : p->enc[0].heads[i]) : head;
+                if (e.head_block) head = g->app_head;
+                xs_all[(e.v_side ? 256 : 0) + tid] = Elem<E>::load(e.ex, (size_t)b * d_kv + head * dh + (tid - k * dh));
             }
-            __syncthreads();
-            if (on) {
-                // thread = (row group rg of 16, column group cg of 16): rows rg * in_width / 16 .., columns 8 cg .. 8 cg + 7;
-                // its 16-byte loads of the matrix are in flight eight at a time
-                const int rg = tid >> 4, c = 8 * (tid & 15), rows = inw >> 4;
-                float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                if (c < r) {
-                    const char* w = static_cast<const char*>(ew) + ((size_t)rg * rows * r + c) * 2;
-                    for (int i0 = 0; i0 < rows; i0 += 8) {
-                        u32x4_t wv[8];
+        }
+        __syncthreads();
+        // ---- thread = (row group rg of 16, column group cg of 16): rows rg * in_width / 16 .., columns 8 cg .. 8 cg + 7;
+        // its 16-byte loads of the matrix (of both sides, with four waves) are in flight eight rows at a time
+        {
+            const int rg = tid >> 4, c = 8 * (tid & 15);
+            float a[S][8];
+            int rows[S];
+            bool live[S];
+            const char* w[S];
+            int rows_max = 0;
 #pragma unroll
-                        for (int u = 0; u < 8; ++u)
-                            wv[u] = i0 + u < rows ? *reinterpret_cast<const u32x4_t*>(w + (size_t)(i0 + u) * r * 2) : u32x4_t{0u, 0u, 0u, 0u};
+            for (int si = 0; si < S; ++si) {
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            const float x = i0 + u < rows ? xs[rg * rows + i0 + u] : 0.f;
+                for (int e = 0; e < 8; ++e) a[si][e] = 0.f;
+                rows[si] = sd[si].inw >> 4;
+                live[si] = sd[si].on && c < sd[si].r;
+                w[si] = sd[si].ew + ((size_t)rg * rows[si] * sd[si].r + c) * 2;
+                rows_max = live[si] && rows[si] > rows_max ? rows[si] : rows_max;
+            }
+            for (int i0 = 0; i0 < rows_max; i0 += 8) {
+                u32x4_t wv[S][8];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                a[2 * e] = fmaf(x, Mma<E>::unpack_lo(wv[u][e]), a[2 * e]);
-                                a[2 * e + 1] = fmaf(x, Mma<E>::unpack_hi(wv[u][e]), a[2 * e + 1]);
-                            }
+                for (int si = 0; si < S; ++si)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        wv[si][u] = live[si] && i0 + u < rows[si] ? *reinterpret_cast<const u32x4_t*>(w[si] + (size_t)(i0 + u) * sd[si].r * 2) : u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int si = 0; si < S; ++si) {
+                    const float* xs = xs_all + (sd[si].v_side ? 256 : 0);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const float x = live[si] && i0 + u < rows[si] ? xs[rg * rows[si] + i0 + u] : 0.f;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            a[si][2 * e] = fmaf(x, Mma<E>::unpack_lo(wv[si][u][e]), a[si][2 * e]);
+                            a[si][2 * e + 1] = fmaf(x, Mma<E>::unpack_hi(wv[si][u][e]), a[si][2 * e + 1]);
                         }
                     }
                 }
-                // the four row groups of a wave (lane / 16) meet by two cross-lane steps, the four waves through LDS
+            }
+            // the four row groups of a wave (lane / 16) meet by two cross-lane steps, the four waves through LDS
+#pragma unroll
+            for (int si = 0; si < S; ++si) {
+                if (!sd[si].on) continue;                    // the same for the whole workgroup
+                float* ps = ps_all + (sd[si].v_side ? 512 : 0);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    a[e] += __shfl_xor(a[e], 16);
-                    a[e] += __shfl_xor(a[e], 32);
+                    a[si][e] += __shfl_xor(a[si][e], 16);
+                    a[si][e] += __shfl_xor(a[si][e], 32);
                 }
-                if (lane < 16 && c < r) {
-                    *reinterpret_cast<f32x4_t*>(ps + w4 * 128 + c) = f32x4_t{a[0], a[1], a[2], a[3]};
-                    *reinterpret_cast<f32x4_t*>(ps + w4 * 128 + c + 4) = f32x4_t{a[4], a[5], a[6], a[7]};
+                if (lane < 16 && live[si]) {
+                    *reinterpret_cast<f32x4_t*>(ps + w4 * 128 + c) = f32x4_t{a[si][0], a[si][1], a[si][2], a[si][3]};
+                    *reinterpret_cast<f32x4_t*>(ps + w4 * 128 + c + 4) = f32x4_t{a[si][4], a[si][5], a[si][6], a[si][7]};
                 }
             }
-            __syncthreads();
-            if (on && tid < r) {
-                const float z = ((ps[tid] + ps[128 + tid]) + (ps[256 + tid] + ps[384 + tid])) + (eb ? Elem<E>::load(eb, tid) : 0.f);
-                const uint16_t z16 = Mma<E>::to16(z);
-                zn[side * 128 + tid] = z16;
-                if ((g->append >> (2 + side)) & 1)
-                    static_cast<uint16_t*>(ez)[((size_t)b * p->max_seq + (n_ctx - 1)) * r + tid] = z16;
-            }
-            __syncthreads();
         }
+        __syncthreads();
+        // ---- the waves' sums in wave order, the bias, one rounding to the cache dtype; into LDS and (one group) to the cache
+#pragma unroll
+        for (int si = 0; si < S; ++si) {
+            const Side& e = sd[si];
+            if (e.on && tid < e.r) {
+                const float* ps = ps_all + (e.v_side ? 512 : 0);
+                const float z = ((ps[tid] + ps[128 + tid]) + (ps[256 + tid] + ps[384 + tid])) + (e.eb ? Elem<E>::load(e.eb, e.b_off + tid) : 0.f);
+                const uint16_t z16 = Mma<E>::to16(z);
+                zn[(e.v_side ? 128 : 0) + tid] = z16;
+                if ((g->append >> (e.v_side ? 3 : 2)) & 1)
+                    reinterpret_cast<uint16_t*>(e.ez)[((size_t)b * p->max_seq + (n_ctx - 1)) * e.r + tid] = z16;
+            }
+        }
+        __syncthreads();
         znew = reinterpret_cast<const char*>(zn);
         patch_k = (g->append & 1) != 0;
         patch_v = (g->append & 2) != 0;

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <array>
 #include <map>
 #include <memory>
 #include <mutex>
@@ -123,6 +124,7 @@ int resolve(const kvcar_ctx* ctx, int layer, int which, int g) {
 
 struct Plan {
     std::vector<GroupDesc> groups;
+    std::vector<std::array<int, 2>> src;   // per group: the layers that supply its keys and its values
     bool mfma = false;        // an MFMA attention kernel (linear or two-layer decoder) is used
     bool mlp = false;         // ... the two-layer one
     bool i8 = false;          // ... the one over int8 latent rows (absorbed queries travel in fp32)
@@ -135,18 +137,51 @@ struct Plan {
     size_t qt_bytes = 0, part_bytes = 0, arrive_bytes = 0, total_bytes = 0;
 };
 
-int fill_side(const kvcar_ctx* ctx, int layer, int src, int which, SideDesc& sd) {
+// Position of KV head g among the heads the autoencoder of (src, which) covers, or -1.
+int head_slot(const kvcar_ctx* ctx, int src, int which, int g) {
+    const AEState& a = ctx->ae_at(src, which);
+    for (size_t i = 0; i < a.heads.size(); ++i)
+        if (a.heads[i] == g) return (int)i;
+    return -1;
+}
+
+// Width of one head's latent rows under a per-head autoencoder.
+int head_latent(const AEState& a) { return a.heads.empty() ? 0 : a.d.latent_width / (int)a.heads.size(); }
+
+// Bytes between the blocks of two consecutive heads in a head-major cache (per-head autoencoders).
+size_t head_block_bytes(const kvcar_ctx* ctx, const AEState& a) {
+    return (size_t)ctx->cfg.max_batch * ctx->cfg.max_seq * head_latent(a) * dtype_size(ctx->cfg.dtype);
+}
+
+// What the attention kernels need to know of the layer `src` that supplies tensor `which` to KV head g of `layer`.
+// With a per-head autoencoder that is head g's own block of the cache and its own d_head-wide decoder (the kernels
+// then see a single-head autoencoder whose columns start at 0); with a dense one g plays no part.
+int fill_side(const kvcar_ctx* ctx, int layer, int src, int which, int g, SideDesc& sd) {
     const AEState& a = ctx->ae_at(src, which);
     if (!a.set) return fail(ctx, KVCAR_ERR_STATE, "layer %d needs the %s autoencoder of layer %d, which is not set", layer, which ? "V" : "K", src);
     void* z = ctx->cache[(size_t)src * 2 + which];
     if (a.d.latent_width > 0 && z == nullptr)
         return fail(ctx, KVCAR_ERR_STATE, "layer %d needs the %s cache of layer %d, which is not bound", layer, which ? "V" : "K", src);
+    sd.act = a.d.act;
+    sd.slope = a.d.leaky_slope;
+    if (a.d.per_head) {
+        const int i = head_slot(ctx, src, which, g);
+        if (i < 0) return fail(ctx, KVCAR_ERR_REUSE, "layer %d takes head %d from a layer whose autoencoder does not cover it", layer, g);
+        const int rh = head_latent(a), dh = ctx->cfg.d_head;
+        const size_t es = dtype_size(ctx->cfg.dtype);
+        sd.z = static_cast<const char*>(z) + (size_t)i * head_block_bytes(ctx, a);
+        sd.meta = nullptr;
+        sd.r = sd.c = rh;
+        sd.in_width = dh;
+        sd.w1 = nullptr; sd.b1 = nullptr;
+        sd.wl = static_cast<const char*>(a.d.dec_w1) + (size_t)i * rh * dh * es;
+        sd.bl = a.d.dec_b1 ? static_cast<const char*>(a.d.dec_b1) + (size_t)i * dh * es : nullptr;
+        return KVCAR_OK;
+    }
     sd.z = z;
     sd.meta = (ctx->int8() && z) ? static_cast<const char*>(z) + ctx->meta_offset(a.d.latent_width) : nullptr;
     sd.r = a.d.latent_width;
     sd.in_width = a.d.in_width;
-    sd.act = a.d.act;
-    sd.slope = a.d.leaky_slope;
     if (a.d.hidden_width > 0) {
         sd.w1 = a.d.dec_w1; sd.b1 = a.d.dec_b1; sd.wl = a.d.dec_w2; sd.bl = a.d.dec_b2; sd.c = a.d.hidden_width;
     } else {
@@ -155,11 +190,11 @@ int fill_side(const kvcar_ctx* ctx, int layer, int src, int which, SideDesc& sd)
     return KVCAR_OK;
 }
 
+// First column of KV head g in the last decoder layer that fill_side hands to the kernels, or -1.
 int head_column(const kvcar_ctx* ctx, int src, int which, int g) {
-    const AEState& a = ctx->ae_at(src, which);
-    for (size_t i = 0; i < a.heads.size(); ++i)
-        if (a.heads[i] == g) return (int)i * ctx->cfg.d_head;
-    return -1;
+    const int i = head_slot(ctx, src, which, g);
+    if (i < 0) return -1;
+    return ctx->ae_at(src, which).d.per_head ? 0 : i * ctx->cfg.d_head;
 }
 
 constexpr size_t kLdsBudget = 150 * 1024;
@@ -167,10 +202,17 @@ constexpr size_t kLdsBudget = 150 * 1024;
 int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan) {
     const kvcar_config& c = ctx->cfg;
     const int gq = c.n_q_heads / c.n_kv_heads;
-    std::map<std::pair<int, int>, std::vector<int>> by_src;     // (K source, V source) -> KV heads
-    for (int g = 0; g < c.n_kv_heads; ++g) by_src[{resolve(ctx, layer, KVCAR_K, g), resolve(ctx, layer, KVCAR_V, g)}].push_back(g);
+    // (K source, V source, head) -> KV heads; the head is part of the key only where a source has a per-head
+    // autoencoder (then every KV head reads rows of its own), else -1
+    std::map<std::array<int, 3>, std::vector<int>> by_src;
+    for (int g = 0; g < c.n_kv_heads; ++g) {
+        const int sk = resolve(ctx, layer, KVCAR_K, g), sv = resolve(ctx, layer, KVCAR_V, g);
+        const bool own_rows = ctx->ae_at(sk, KVCAR_K).d.per_head || ctx->ae_at(sv, KVCAR_V).d.per_head;
+        by_src[{sk, sv, own_rows ? g : -1}].push_back(g);
+    }
 
     plan.groups.clear();
+    plan.src.clear();
     // MFMA kernels: 16-bit dtype, linear decoders, latent widths that are multiples of 32
     bool mfma_ok = c.dtype != KVCAR_F32 && !ctx->tun.force_generic && attend_mfma_available() && c.d_head % 8 == 0;
     // ... or two-layer decoders of one of the shapes with a resident-weight kernel, the same for K and V
@@ -182,10 +224,15 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     std::vector<Base> bases;
     for (auto& kv : by_src) {
         GroupDesc base{};
-        int rc = fill_side(ctx, layer, kv.first.first, KVCAR_K, base.k);
+        const int src_k = kv.first[0], src_v = kv.first[1], g_first = kv.second.front();
+        int rc = fill_side(ctx, layer, src_k, KVCAR_K, g_first, base.k);
         if (rc) return rc;
-        rc = fill_side(ctx, layer, kv.first.second, KVCAR_V, base.v);
+        rc = fill_side(ctx, layer, src_v, KVCAR_V, g_first, base.v);
         if (rc) return rc;
+        // append-and-attend: the head's block of the layer's own per-head caches, and the head itself
+        base.app_slice[0] = (short)(ctx->ae_at(src_k, KVCAR_K).d.per_head ? head_slot(ctx, src_k, KVCAR_K, g_first) : -1);
+        base.app_slice[1] = (short)(ctx->ae_at(src_v, KVCAR_V).d.per_head ? head_slot(ctx, src_v, KVCAR_V, g_first) : -1);
+        base.app_head = (short)g_first;
         if (base.k.c > kMaxRow || base.v.c > kMaxRow || base.k.r > kMaxRow || base.v.r > kMaxRow)
             return fail(ctx, KVCAR_ERR_UNSUPPORTED, "row width above %d", kMaxRow);
         if (base.k.w1 || base.v.w1 || base.k.r % 32 || base.v.r % 32 || base.k.r > 384 || base.v.r > 384) mfma_ok = false;
@@ -203,10 +250,10 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
             for (int i = 0; i < gq; ++i) heads.push_back(g * gq + i);
         for (int j : heads) {
             const int g = j / gq;
-            if (head_column(ctx, kv.first.first, KVCAR_K, g) < 0 || head_column(ctx, kv.first.second, KVCAR_V, g) < 0)
+            if (head_column(ctx, src_k, KVCAR_K, g) < 0 || head_column(ctx, src_v, KVCAR_V, g) < 0)
                 return fail(ctx, KVCAR_ERR_REUSE, "layer %d takes head %d from a layer whose autoencoder does not cover it", layer, g);
         }
-        bases.push_back(Base{base, heads, kv.first.first, kv.first.second});
+        bases.push_back(Base{base, heads, src_k, src_v});
     }
     if (mlp_ok) mlp_ok = ((mlp_r == 128 && mlp_c == 256) || (mlp_r == 64 && mlp_c == 128)) &&
                          (mlp_act == KVCAR_ACT_GELU || mlp_act == KVCAR_ACT_LEAKY_RELU);
@@ -252,6 +299,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
             runs(gd.k_col, gd.n_kseg, gd.kseg_lo, gd.kseg_hi, gd.kseg_col);
             runs(gd.v_col, gd.n_vseg, gd.vseg_lo, gd.vseg_hi, gd.vseg_col);
             plan.groups.push_back(gd);
+            plan.src.push_back({bh.src_k, bh.src_v});
         }
     }
     plan.mfma = mfma_ok;
@@ -412,6 +460,7 @@ int kvcar_set_autoencoder(kvcar_ctx* ctx, int layer, int which, const kvcar_ae_d
     }
     if (d->in_width == 0) {
         if (d->latent_width != 0) return fail(ctx, KVCAR_ERR_SHAPE, "latent_width must be 0 when in_width is 0");
+        st.d.per_head = 0;
     } else {
         if (d->latent_width <= 0 || d->hidden_width < 0) return fail(ctx, KVCAR_ERR_SHAPE, "non-positive widths");
         if ((d->hidden_width > 0) != (d->act != KVCAR_ACT_NONE))
@@ -422,6 +471,15 @@ int kvcar_set_autoencoder(kvcar_ctx* ctx, int layer, int which, const kvcar_ae_d
             return fail(ctx, KVCAR_ERR_UNSUPPORTED, "widths above %d are not supported", kMaxRow);
         if ((size_t)d->latent_width * ctx->row_elem_bytes() % 16 != 0)
             return fail(ctx, KVCAR_ERR_UNSUPPORTED, "latent rows must be a multiple of 16 bytes");
+        if (d->per_head != 0 && d->per_head != 1) return fail(ctx, KVCAR_ERR_ARG, "per_head must be 0 or 1");
+        if (d->per_head) {
+            const int n = (int)st.heads.size();
+            if (d->hidden_width > 0 || ctx->int8())
+                return fail(ctx, KVCAR_ERR_UNSUPPORTED, "per-head autoencoders are linear and keep latent rows in the model dtype");
+            if (d->latent_width % n != 0) return fail(ctx, KVCAR_ERR_SHAPE, "latent_width %d is not a multiple of the %d covered heads", d->latent_width, n);
+            if ((size_t)(d->latent_width / n) * ctx->row_elem_bytes() % 16 != 0 || (size_t)c.d_head * dtype_size(c.dtype) % 16 != 0)
+                return fail(ctx, KVCAR_ERR_UNSUPPORTED, "a head's latent rows and its decoder rows must be multiples of 16 bytes");
+        }
         const void* req[4] = {d->enc_w1, d->dec_w1, d->hidden_width ? d->enc_w2 : d->enc_w1, d->hidden_width ? d->dec_w2 : d->dec_w1};
         for (const void* p : req)
             if (!p) return fail(ctx, KVCAR_ERR_ARG, "null weight pointer");
@@ -492,8 +550,11 @@ namespace {
 
 // The encoder side of a call: shapes, weights and (when `bound`) the input and cache pointers.  `any` tells
 // whether the layer stores anything.
+// `piece`: with per-head autoencoders a call is one launch per covered head (the piece-th covered head of K beside the
+// piece-th of V: each is a d_head -> r_h encoder of its own writing its own block of the cache); a side with a dense
+// autoencoder belongs to piece 0.  `any` = the piece has something to encode.
 int fill_encode_params(const kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new, int batch, int pos0, const int32_t* positions,
-                       int t_new, bool bound, EncodeParams& p, bool& any) {
+                       int t_new, bool bound, EncodeParams& p, bool& any, int piece = 0) {
     const kvcar_config& c = ctx->cfg;
     p = EncodeParams{};
     p.batch = batch; p.t_new = t_new; p.pos0 = pos0; p.max_seq = c.max_seq; p.d_kv = c.n_kv_heads * c.d_head; p.d_head = c.d_head;
@@ -509,6 +570,24 @@ int fill_encode_params(const kvcar_ctx* ctx, int layer, const void* k_new, const
         if (s.r == 0) continue;
         s.z = ctx->cache[(size_t)layer * 2 + which];
         if (bound && !s.z) return fail(ctx, KVCAR_ERR_STATE, "cache of layer %d (%s) not bound", layer, which ? "V" : "K");
+        if (a.d.per_head) {
+            s.r = 0;
+            if (piece >= (int)a.heads.size()) continue;
+            const int rh = head_latent(a), dh = c.d_head;
+            const size_t es = dtype_size(c.dtype);
+            s.r = rh;
+            if (s.z) s.z = static_cast<char*>(s.z) + (size_t)piece * head_block_bytes(ctx, a);
+            s.meta = nullptr;
+            s.w1 = static_cast<const char*>(a.d.enc_w1) + (size_t)piece * dh * rh * es;
+            s.b1 = a.d.enc_b1 ? static_cast<const char*>(a.d.enc_b1) + (size_t)piece * rh * es : nullptr;
+            s.w2 = nullptr; s.b2 = nullptr;
+            s.in_width = dh; s.hidden = 0; s.act = KVCAR_ACT_NONE; s.slope = 0.f;
+            s.n_heads = 1;
+            s.heads[0] = (unsigned char)a.heads[piece];
+            any = true;
+            continue;
+        }
+        if (piece > 0) { s.r = 0; continue; }
         s.meta = ctx->int8() && s.z ? static_cast<char*>(s.z) + ctx->meta_offset(s.r) : nullptr;
         s.w1 = a.d.enc_w1; s.b1 = a.d.enc_b1; s.w2 = a.d.enc_w2; s.b2 = a.d.enc_b2;
         s.in_width = a.d.in_width; s.hidden = a.d.hidden_width; s.act = a.d.act; s.slope = a.d.leaky_slope;
@@ -517,6 +596,16 @@ int fill_encode_params(const kvcar_ctx* ctx, int layer, const void* k_new, const
         any = true;
     }
     return KVCAR_OK;
+}
+
+// Launches an encode call of `layer` takes: one, or with per-head autoencoders one per covered head.
+int encode_pieces(const kvcar_ctx* ctx, int layer) {
+    int n = 1;
+    for (int which = 0; which < 2; ++which) {
+        const AEState& a = ctx->ae_at(layer, which);
+        if (a.set && a.d.per_head) n = std::max(n, (int)a.heads.size());
+    }
+    return n;
 }
 
 // Which encoder kernel a call takes (the KVCAR_ENC_* values).
@@ -538,20 +627,22 @@ int encode_impl(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new,
     if (batch < 1 || t_new < 1 || pos0 < 0) return fail(ctx, KVCAR_ERR_ARG, "batch, t_new must be >= 1 and pos0 >= 0");
     if (batch > c.max_batch || (long long)pos0 + t_new > c.max_seq)
         return fail(ctx, KVCAR_ERR_CAPACITY, "append of %d tokens at %d for batch %d exceeds max_seq %d / max_batch %d", t_new, pos0, batch, c.max_seq, c.max_batch);
-    EncodeParams p;
-    bool any = false;
-    rc = fill_encode_params(ctx, layer, k_new, v_new, batch, pos0, positions, t_new, true, p, any);
-    if (rc) return rc;
-    if (!any) return KVCAR_OK;   // the layer stores nothing
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e;
-    switch (encode_kernel_kind(ctx, p)) {
-        case KVCAR_ENC_MFMA_TWO_LAYER: e = launch_encode_mlp_mfma(p, c.dtype, st); break;
-        case KVCAR_ENC_MFMA_STREAM: e = launch_encode_bulk(p, c.dtype, ctx->n_cu, st); break;
-        case KVCAR_ENC_MFMA: e = launch_encode_mfma(p, c.dtype, st); break;
-        default: e = launch_encode_generic(p, c.dtype, st); break;
+    for (int piece = 0; piece < encode_pieces(ctx, layer); ++piece) {
+        EncodeParams p;
+        bool any = false;
+        rc = fill_encode_params(ctx, layer, k_new, v_new, batch, pos0, positions, t_new, true, p, any, piece);
+        if (rc) return rc;
+        if (!any) continue;          // nothing stored on either side
+        hipError_t e;
+        switch (encode_kernel_kind(ctx, p)) {
+            case KVCAR_ENC_MFMA_TWO_LAYER: e = launch_encode_mlp_mfma(p, c.dtype, st); break;
+            case KVCAR_ENC_MFMA_STREAM: e = launch_encode_bulk(p, c.dtype, ctx->n_cu, st); break;
+            case KVCAR_ENC_MFMA: e = launch_encode_mfma(p, c.dtype, st); break;
+            default: e = launch_encode_generic(p, c.dtype, st); break;
+        }
+        if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "encode launch failed: %s", hipGetErrorString(e));
     }
-    if (e != hipSuccess) return fail(ctx, KVCAR_ERR_HIP, "encode launch failed: %s", hipGetErrorString(e));
     return KVCAR_OK;
 }
 
@@ -573,7 +664,8 @@ bool can_append_in_kernel(const kvcar_ctx* ctx, int layer, const Plan& plan) {
         const AEState& a = ctx->ae_at(layer, which);
         if (!a.set) return false;
         if (a.d.latent_width == 0) continue;
-        if (a.d.hidden_width != 0 || a.d.in_width > 256 || a.d.in_width % 16 || a.d.latent_width > 128) return false;
+        const int in_w = a.d.per_head ? ctx->cfg.d_head : a.d.in_width, lat = a.d.per_head ? head_latent(a) : a.d.latent_width;
+        if (a.d.hidden_width != 0 || in_w > 256 || in_w % 16 || lat > 128) return false;
         if (ctx->cache[(size_t)layer * 2 + which] == nullptr) return false;
     }
     return true;
@@ -602,7 +694,7 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
                    : fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, plan.total_bytes);
 
     if (fresh && !can_append_in_kernel(ctx, layer, plan)) return fail(ctx, KVCAR_ERR_STATE, "internal: this plan cannot encode in the attention kernel");
-    bool writer_given[2] = {false, false};
+    unsigned long long writer_given[2] = {0ull, 0ull};    // per side: the heads' blocks (bit 0: the dense row) that have their writer
     hipStream_t st = static_cast<hipStream_t>(stream);
     for (size_t g0 = 0; g0 < plan.groups.size(); g0 += kMaxGroups) {
         AttendParams p{};
@@ -630,13 +722,19 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
                 e.z = ctx->cache[(size_t)layer * 2 + which];
                 e.w = a.d.enc_w1; e.b = a.d.enc_b1;
                 e.in_width = a.d.in_width; e.r = a.d.latent_width;
+                e.head_block = 0;
+                if (a.d.per_head && e.r > 0) {       // every group encodes its own head: d_head -> r_h, into the head's block
+                    e.in_width = c.d_head; e.r = head_latent(a);
+                    e.head_block = (long long)head_block_bytes(ctx, a);
+                }
                 for (size_t i = 0; i < a.heads.size() && i < (size_t)kAppendMaxHeads; ++i) e.heads[i] = (unsigned char)a.heads[i];
                 if (e.r == 0) continue;
                 for (int i = 0; i < p.n_groups; ++i) {
-                    const SideDesc& sd = which == 0 ? p.g[i].k : p.g[i].v;
-                    if (sd.z != e.z) continue;                       // rows of another layer
+                    if (plan.src[g0 + i][which] != layer) continue;  // rows of another layer
                     p.g[i].append |= (short)(1 << which);
-                    if (!writer_given[which]) { p.g[i].append |= (short)(4 << which); writer_given[which] = true; }
+                    // one group writes the row to the cache: per side, or per head's block
+                    const int unit = a.d.per_head ? p.g[i].app_slice[which] : 0;
+                    if (!(writer_given[which] >> unit & 1ull)) { p.g[i].append |= (short)(4 << which); writer_given[which] |= 1ull << unit; }
                 }
             }
         }
@@ -679,11 +777,15 @@ int build_recon(const kvcar_ctx* ctx, int layer, std::vector<ReconEntry>& entrie
     const kvcar_config& c = ctx->cfg;
     entries.clear();
     for (int which = 0; which < 2; ++which) {
-        std::map<int, std::vector<int>> by_src;
-        for (int g = 0; g < c.n_kv_heads; ++g) by_src[resolve(ctx, layer, which, g)].push_back(g);
-        for (auto& kv : by_src) {
+        std::map<std::pair<int, int>, std::vector<int>> by_src;     // (source, head where the source's autoencoder is per-head, else -1)
+        for (int g = 0; g < c.n_kv_heads; ++g) {
+            const int src = resolve(ctx, layer, which, g);
+            by_src[{src, ctx->ae_at(src, which).d.per_head ? g : -1}].push_back(g);
+        }
+        for (auto& kvp : by_src) {
+            const std::pair<const int, std::vector<int>> kv{kvp.first.first, kvp.second};
             SideDesc sd{};
-            int rc = fill_side(ctx, layer, kv.first, which, sd);
+            int rc = fill_side(ctx, layer, kv.first, which, kv.second.front(), sd);
             if (rc) return rc;
             if (sd.c > kMaxRow || sd.r > kMaxRow) return fail(ctx, KVCAR_ERR_UNSUPPORTED, "row width above %d", kMaxRow);
             for (size_t h0 = 0; h0 < kv.second.size(); h0 += kMaxReconHeads) {

@@ -66,6 +66,10 @@ struct GroupDesc {
     // encodes (so its last row is the one being appended); bit 2 / 3 = this group's workgroup also writes that row to
     // the cache (one group per side does).
     short append;
+    // Per-head autoencoders: the block of the source's head-major cache this group reads on the key / value side (the
+    // position of its KV head among the covered heads), else -1; and the group's first KV head.
+    short app_slice[2];
+    short app_head;
 };
 constexpr int kMaxSeg = 4;
 
@@ -79,6 +83,10 @@ struct AppendSide {
     const void* b;        // its bias or null
     int in_width, r;      // r = 0: the layer stores nothing on this side
     unsigned char heads[kAppendMaxHeads];   // KV heads whose columns form the encoder input, in order
+    // Per-head autoencoders: bytes between two heads' blocks of the cache, and in_width = d_head, r = one head's latent
+    // width; a group then encodes its own head (GroupDesc::app_head) with the app_slice-th [in_width, r] matrix of w,
+    // the app_slice-th r entries of b, into the app_slice-th block of z.  0 = one dense autoencoder.
+    long long head_block;
 };
 
 struct AttendParams {

@@ -14,10 +14,14 @@ from . import binding, synth
 class Session:
     def __init__(self, w: synth.Workload, reuse: Optional[np.ndarray] = None, with_bias: bool = False,
                  device: str = "cuda:0", n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, no_fuse: bool = False, poison: bool = False,
-                 max_batch: Optional[int] = None, latent_format: str = "dtype", wg_waves: int = 0, no_bulk_encode: bool = False, no_arrive: bool = False):
+                 max_batch: Optional[int] = None, latent_format: str = "dtype", wg_waves: int = 0, no_bulk_encode: bool = False, no_arrive: bool = False,
+                 per_head: bool = False):
+        """per_head: every KV head has an autoencoder d_head -> latent / H_kv -> d_head of its own (the library's
+        per_head descriptor flag); head g's weights and activations are those of per_head_workloads(w)[g]."""
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: libkvcar has no CPU path")
         self.w = w
+        self.per_head = per_head
         self.poison = poison
         self.dev = torch.device(device)
         self.tdt = synth.TORCH_DTYPE[w.dtype]
@@ -30,15 +34,16 @@ class Session:
         self.caches: List[List[Optional[torch.Tensor]]] = []
         for layer in range(w.n_layers):
             self.ctx.set_reuse_map(layer, self.reuse[layer, 0], self.reuse[layer, 1])
+        self.parts = per_head_workloads(w, self.reuse) if per_head else None
         for layer in range(w.n_layers):
             row, crow = [], []
             for which in (0, 1):
-                ae = synth.autoencoder(w, layer, which, self.reuse, with_bias)
+                ae = self.stacked_autoencoder(layer, which, with_bias) if per_head else synth.autoencoder(w, layer, which, self.reuse, with_bias)
                 up = lambda pairs: [(wt.to(self.dev, self.tdt).contiguous(), None if b is None else b.to(self.dev, self.tdt).contiguous())
                                     for wt, b in pairs]
                 enc, dec = up(ae.enc), up(ae.dec)
-                self.ctx.set_autoencoder(layer, which, ae.width, ae.hidden if ae.width else 0, ae.latent,
-                                         ae.act if ae.width else "none", enc, dec, ae.slope)
+                self.ctx.set_autoencoder(layer, which, len(ae.heads) * w.d_head if per_head else ae.width, ae.hidden if ae.heads else 0, ae.latent,
+                                         ae.act if ae.heads else "none", enc, dec, ae.slope, per_head=per_head and bool(ae.heads))
                 nbytes = self.ctx.cache_bytes(layer, which)
                 cache = None
                 if nbytes and latent_format == "int8":
@@ -60,14 +65,46 @@ class Session:
         self._ws_key = None
 
     # ------------------------------------------------------------------
+    def stacked_autoencoder(self, layer: int, which: int, with_bias: bool) -> synth.AEWeights:
+        """Per-head autoencoders of one layer-tensor in the library's layout: the stored heads' matrices one after the
+        other, enc [n][d_head][r_h], dec [n][r_h][d_head], biases concatenated (pure data movement)."""
+        stored = [g for g in range(self.w.n_kv_heads) if not self.reuse[layer, which, g]]
+        aes = [synth.autoencoder(self.parts[g][0], layer, which, self.parts[g][1], with_bias) for g in stored]
+        if not stored:
+            empty = torch.zeros(0, 0)
+            return synth.AEWeights([], 0, 0, "none", 0.01, [(empty, None)], [(empty, None)])
+        cat = lambda vs: torch.cat(list(vs)) if with_bias else None
+        enc = [(torch.stack([a.enc[0][0] for a in aes]), cat(a.enc[0][1] for a in aes))]
+        dec = [(torch.stack([a.dec[0][0] for a in aes]), cat(a.dec[0][1] for a in aes))]
+        return synth.AEWeights(stored, sum(a.latent for a in aes), 0, "none", 0.01, enc, dec)
+
+    def kv(self, layer: int, which: int, t0: int, t1: int) -> torch.Tensor:
+        """Synthetic keys (which = 0) or values [batch, t1 - t0, D_kv] of positions [t0, t1); per-head sessions: head g's
+        columns are the stream of per_head_workloads(w)[g]."""
+        w = self.w
+        if not self.per_head:
+            return synth.kv_tokens(w, layer, which, 0, w.batch, t0, t1, device=self.dev).to(self.tdt)
+        return torch.cat([synth.kv_tokens(wg, layer, which, 0, w.batch, t0, t1, device=self.dev) for wg, _ in self.parts], dim=2).to(self.tdt)
+
+    def queries(self, layer: int, step: int, gain: float = 1.0) -> torch.Tensor:
+        """Synthetic decode queries [batch, H_q, d_head] (per-head sessions: head g's query heads from its own stream)."""
+        if not self.per_head:
+            return synth.queries(self.w, layer, step, device=self.dev, gain=gain).to(self.tdt)
+        return torch.cat([synth.queries(wg, layer, step, device=self.dev, gain=gain) for wg, _ in self.parts], dim=1).to(self.tdt)
+
     def cache_view(self, layer: int, which: int) -> Optional[torch.Tensor]:
-        """[max_batch, max_seq, r] view of a latent cache (the documented layout)."""
+        """[max_batch, max_seq, r] view of a latent cache (the documented layout); per-head autoencoders: the heads'
+        blocks [n_stored_heads][max_batch][max_seq][r_h] gathered side by side into rows of the same shape (a copy)."""
         c = self.caches[layer][which]
         if c is None:
             return None
         if self.latent_format == "int8":
             raise RuntimeError("int8 latents: use quantized_view")
-        return c.view(self.ctx.cfg.max_batch, self.w.max_seq, self.ae[layer][which].latent)
+        ae = self.ae[layer][which]
+        if self.per_head:
+            n, mb, ms = len(ae.heads), self.ctx.cfg.max_batch, self.w.max_seq
+            return c.view(n, mb, ms, ae.latent // n).permute(1, 2, 0, 3).reshape(mb, ms, ae.latent)
+        return c.view(self.ctx.cfg.max_batch, self.w.max_seq, ae.latent)
 
     def quantized_view(self, layer: int, which: int):
         """int8 latents: (codes int8 [max_batch, max_seq, r], scale fp32 [max_batch, max_seq],
@@ -99,9 +136,7 @@ class Session:
         for layer in (range(w.n_layers) if layers is None else layers):
             for c0 in range(t0, t1, chunk):
                 c1 = min(t1, c0 + chunk)
-                k = synth.kv_tokens(w, layer, 0, 0, w.batch, c0, c1, device=self.dev).to(self.tdt)
-                v = synth.kv_tokens(w, layer, 1, 0, w.batch, c0, c1, device=self.dev).to(self.tdt)
-                self.encode_append(layer, k, v, c0)
+                self.encode_append(layer, self.kv(layer, 0, c0, c1), self.kv(layer, 1, c0, c1), c0)
 
     def decode_attention(self, layer: int, q: torch.Tensor, n_ctx: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         b = q.shape[0]

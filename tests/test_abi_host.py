@@ -340,3 +340,46 @@ def test_plans_for_the_shape_sweep():
             assert (kind == B.ENC_NONE) == (not stores)
             assert not (w.dtype == "f32" and kind not in (B.ENC_NONE, B.ENC_PLAIN))
     assert n_mfma >= 40          # the sweep does reach the matrix-core kernels
+
+
+def test_per_head_descriptor_rules_and_plan():
+    """The per_head flag of the autoencoder descriptor (block-diagonal autoencoders; fake device pointers, nothing
+    launched): what it accepts, that the cache keeps its size, that a layer is planned as one group per KV head, and that
+    a head reused from an earlier layer costs that head's rows only."""
+    lib = B.lib()
+    ctx = make(n_layers=3, hq=32, hkv=4, dh=64, mb=8, ms=512)
+
+    def ph(in_w, hid, lat, act=B.ACT_NONE, flag=1):
+        d = desc(in_w, hid, lat, act)
+        d.per_head = flag
+        return d
+
+    assert lib.kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(ph(256, 0, 16))) == B.ERR_UNSUPPORTED    # 8-byte head rows
+    assert lib.kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(ph(256, 64, 128, B.ACT_GELU))) == B.ERR_UNSUPPORTED
+    assert lib.kvcar_set_autoencoder(ctx._h, 0, B.K, C.byref(ph(256, 0, 128, flag=2))) == B.ERR_ARG
+    ctx.set_reuse_map(1, [0, 1, 0, 0], [0, 0, 0, 1])
+    ctx.set_reuse_map(2, [0, 1, 1, 0], [0, 0, 0, 0])
+    assert lib.kvcar_set_autoencoder(ctx._h, 1, B.K, C.byref(ph(192, 0, 128))) == B.ERR_SHAPE         # three heads do not divide 128
+    widths = {0: (4, 4), 1: (3, 3), 2: (2, 4)}            # stored heads of (K, V) per layer
+    for layer, (nk, nv) in widths.items():
+        for which, n in ((B.K, nk), (B.V, nv)):
+            assert lib.kvcar_set_autoencoder(ctx._h, layer, which, C.byref(ph(64 * n, 0, 32 * n))) == B.OK
+            need = ctx.cache_bytes(layer, which)
+            assert need == 8 * 512 * 32 * n * 2            # the head blocks together are as large as the dense rows
+            assert lib.kvcar_bind_cache(ctx._h, layer, which, FAKE, need) == B.OK
+    for layer in range(3):
+        p = ctx.describe_plan(layer, 8, 300)
+        assert p.n_groups == 4 and p.uses_mfma == 1 and p.n_launches == 1
+        assert p.latent_bytes == 4 * 2 * 32 * 2 * 8 * 300  # 4 heads x (K + V) x 32 columns x 2 bytes, per cached token and sequence
+        assert p.fused == 2 and p.append_in_kernel == 1    # 8 sequences x 4 groups: several splits, one launch
+    assert ctx.describe_plan(2, 8, 300).n_splits == 3          # 300 tokens are three 128-token workgroup tiles
+    # int8 latents do not combine with the flag
+    c8 = B.Context(2, 32, 4, 64, 2, 64, "bf16", latent_format="int8")
+    assert lib.kvcar_set_autoencoder(c8._h, 0, B.K, C.byref(ph(256, 0, 128))) == B.ERR_UNSUPPORTED
+    # fp32: 32-column head rows are fine, the plan takes the plain-ALU kernels
+    f32 = make(n_layers=1, hq=8, hkv=4, dh=64, mb=2, ms=64, dtype="f32")
+    for which in (B.K, B.V):
+        assert lib.kvcar_set_autoencoder(f32._h, 0, which, C.byref(ph(256, 0, 128))) == B.OK
+        assert lib.kvcar_bind_cache(f32._h, 0, which, FAKE, f32.cache_bytes(0, which)) == B.OK
+    p = f32.describe_plan(0, 2, 40)
+    assert p.n_groups == 4 and p.uses_mfma == 0
