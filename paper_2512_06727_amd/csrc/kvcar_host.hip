@@ -915,6 +915,10 @@ int kvcar_append_attend(kvcar_ctx* ctx, int layer, const void* k_new, const void
         const NewToken fresh{k_new, v_new};
         return decode_impl(ctx, layer, q, out, batch, pos + 1, nullptr, workspace, workspace_bytes, stream, false, &fresh);
     }
+    // two launches: what the second would refuse is refused before the first appends anything
+    if (!q || !out || !aligned16(q) || !aligned16(out)) return fail(ctx, KVCAR_ERR_ARG, "q / out null or misaligned");
+    if (!workspace || !aligned16(workspace)) return fail(ctx, KVCAR_ERR_ARG, "workspace null or misaligned");
+    if (workspace_bytes < plan.total_bytes) return fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, plan.total_bytes);
     rc = encode_impl(ctx, layer, k_new, v_new, batch, pos, nullptr, 1, stream);
     if (rc) return rc;
     return decode_impl(ctx, layer, q, out, batch, pos + 1, nullptr, workspace, workspace_bytes, stream);
