@@ -193,7 +193,12 @@ __device__ __forceinline__ void i8_chunk_to_f16(const u32x4_t c, u32x4_t& lo, u3
     hi = u32x4_t{h[4], h[5], h[6], h[7]};
 }
 
-// Park an int8 tile: 16-byte chunk f holds 16 codes of row f / cpr8 -> 32 bytes of fp16 in the padded row
+// Park an int8 tile: 16-byte chunk f holds 16 codes of row f / cpr8 -> 32 bytes of fp16 in the padded row.
+// A lane's two 16-byte stores lie 32 bytes from its neighbours': eight consecutive lanes, which share the 128 bytes of
+// LDS banks, would cover only every other 16-byte bank group, twice.  So in the upper half of a 256-byte row (fp16
+// chunks 8 and up) the two chunks of a pair swap places: lanes 0-3 of a row then write bank groups 0, 2, 4, 6 and lanes
+// 4-7 write 1, 3, 5, 7 in the same instruction.  Readers undo the swap (kI8SwapFrom).
+constexpr int kI8SwapFrom = 8;       // first 16-byte chunk of a parked int8 row that sits in its pair's other slot
 template <int NL>
 __device__ __forceinline__ void park_tile_i8(const u32x4_t (&st)[NL], char* region, int n_loads, int cpr8, int stride, int lane) {
 #pragma unroll
@@ -202,10 +207,11 @@ __device__ __forceinline__ void park_tile_i8(const u32x4_t (&st)[NL], char* regi
             const unsigned f = i * 64 + lane;
             const unsigned row = f / (unsigned)cpr8;
             const unsigned ch = f - row * cpr8;
+            const unsigned sw = 2 * ch >= (unsigned)kI8SwapFrom ? 16u : 0u;
             u32x4_t lo, hi;
             i8_chunk_to_f16(st[i], lo, hi);
-            *reinterpret_cast<u32x4_t*>(region + row * stride + ch * 32) = lo;
-            *reinterpret_cast<u32x4_t*>(region + row * stride + ch * 32 + 16) = hi;
+            *reinterpret_cast<u32x4_t*>(region + row * stride + ch * 32 + sw) = lo;
+            *reinterpret_cast<u32x4_t*>(region + row * stride + ch * 32 + (16u ^ sw)) = hi;
         }
 }
 
@@ -656,12 +662,14 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
 #pragma unroll
             for (int nb = 0; nb < NHB; ++nb) sT[a][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         const char* krow = lds_k + l16 * stride_k + lg * 16;
+        const char* krow_sw = lds_k + l16 * stride_k + (lg ^ 1) * 16;       // int8 rows: chunks whose pair is swapped
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             if (s < ksteps) {
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
-                    const u32x4_t ka = *reinterpret_cast<const u32x4_t*>(krow + a * 16 * stride_k + s * 64);
+                    const char* kr = kI8 && 4 * s >= kI8SwapFrom ? krow_sw : krow;
+                    const u32x4_t ka = *reinterpret_cast<const u32x4_t*>(kr + a * 16 * stride_k + s * 64);
 #pragma unroll
                     for (int nb = 0; nb < NHB; ++nb)
                         if (nb < nhb) sT[a][nb] = Mma<ML>::mfma(ka, qb[nb][s], sT[a][nb]);
@@ -749,11 +757,13 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         // 16 lanes of a block supply the addresses of a 4-token x 16-column patch; the transposing
         // load hands lane i its column i for the 4 tokens
         const char* vrow = lds_v + (4 * lg + (l16 >> 2)) * stride_v + (l16 & 3) * 8;
+        const char* vrow_sw = lds_v + (4 * lg + (l16 >> 2)) * stride_v + (((l16 & 3) * 8) ^ 16);      // int8 rows: the other slot of the pair
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             if (mb < mblocks) {
-                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(vrow + mb * 32));
-                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(vrow + mb * 32 + 16 * stride_v));
+                const char* vr = kI8 && 2 * mb >= kI8SwapFrom ? vrow_sw : vrow;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(vr + mb * 32));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(vr + mb * 32 + 16 * stride_v));
                 const u32x2_t lo2 = __builtin_bit_cast(u32x2_t, lo), hi2 = __builtin_bit_cast(u32x2_t, hi);
                 const u32x4_t va = {lo2[0], lo2[1], hi2[0], hi2[1]};
 #pragma unroll
