@@ -79,7 +79,7 @@ hipError_t launch_attend_i8_mfma(const AttendParams& p, int dtype, hipStream_t s
     if (!attend_i8_mfma_supported(p, dtype)) return hipErrorNotSupported;
     if (p.fused == 2) {
         const size_t epi8 = 2048 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);
-        size_t lds8 = 8 * kI8WaveLds + 2 * 4 * 64 * 16;
+        size_t lds8 = 8 * kI8WaveLds + 2 * 4 * 64 * 16;              // + swapped query operands (the new token's codes of append-and-attend sit in the waves' spare bytes)
         lds8 = lds8 > epi8 ? lds8 : epi8;
         const int e8 = dtype == KVCAR_BF16 ? 0 : 1;
         auto kern8 = e8 == 0 ? attend_i8_mfma_r128_w8_kernel<BF16> : attend_i8_mfma_r128_w8_kernel<F16>;
@@ -93,7 +93,7 @@ hipError_t launch_attend_i8_mfma(const AttendParams& p, int dtype, hipStream_t s
     }
     const size_t epi = 1024 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);
     const size_t merge = mfma_lds_bytes(128, 2);
-    size_t lds = kWaves * kI8WaveLds + (p.fused ? 2 * 4 * 64 * 16 : 0);
+    size_t lds = kWaves * kI8WaveLds + (p.fused ? 2 * 4 * 64 * 16 : 0);       // two workgroups of 81920 bytes fill a compute unit's LDS exactly
     lds = lds > merge ? lds : merge;
     lds = lds > epi ? lds : epi;
     const int e = dtype == KVCAR_BF16 ? 0 : 1;

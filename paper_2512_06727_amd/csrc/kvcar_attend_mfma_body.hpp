@@ -363,6 +363,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         float* xs_all = reinterpret_cast<float*>(lds_raw);   // [2 sides][in_width <= 256]
         float* ps_all = xs_all + 512;                        // [2 sides][4 waves][128]
         uint16_t* zn = reinterpret_cast<uint16_t*>(lds_raw + NW * wave_lds + 2 * 4 * 64 * 16);      // [2 sides][128], past the exchange area: kept through the loop
+        char* zi8 = lds_raw + kWaveTile * (stride_k + stride_v) + 384;                              // int8 rows: see below
         const int dh = p->d_head, d_kv = (p->n_q_heads / p->gq) * dh;
         const int tid = threadIdx.x & 255, w4 = wave & 3;
         // one side's encoder (read with constant indices: the argument block must not be indexed by a run-time value)
@@ -468,25 +469,70 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         }
         __syncthreads();
         // ---- the waves' sums in wave order, the bias, one rounding to the cache dtype; into LDS and (one group) to the cache
+        if constexpr (!kI8) {
 #pragma unroll
-        for (int si = 0; si < S; ++si) {
-            const Side& e = sd[si];
-            if (e.on && tid < e.r) {
-                const float* ps = ps_all + (e.v_side ? 512 : 0);
-                const float z = ((ps[tid] + ps[128 + tid]) + (ps[256 + tid] + ps[384 + tid])) + (e.eb ? Elem<E>::load(e.eb, e.b_off + tid) : 0.f);
-                const uint16_t z16 = Mma<E>::to16(z);
-                zn[(e.v_side ? 128 : 0) + tid] = z16;
-                if ((g->append >> (e.v_side ? 3 : 2)) & 1)
-                    reinterpret_cast<uint16_t*>(e.ez)[((size_t)b * p->max_seq + (n_ctx - 1)) * e.r + tid] = z16;
+            for (int si = 0; si < S; ++si) {
+                const Side& e = sd[si];
+                if (e.on && tid < e.r) {
+                    const float* ps = ps_all + (e.v_side ? 512 : 0);
+                    const float z = ((ps[tid] + ps[128 + tid]) + (ps[256 + tid] + ps[384 + tid])) + (e.eb ? Elem<E>::load(e.eb, e.b_off + tid) : 0.f);
+                    const uint16_t z16 = Mma<E>::to16(z);
+                    zn[(e.v_side ? 128 : 0) + tid] = z16;
+                    if ((g->append >> (e.v_side ? 3 : 2)) & 1)
+                        reinterpret_cast<uint16_t*>(e.ez)[((size_t)b * p->max_seq + (n_ctx - 1)) * e.r + tid] = z16;
+                }
             }
+            __syncthreads();
+        } else {
+            // int8 rows ("Quantization", Eq. "quant"): the row's minimum and maximum first (the first two waves of a side
+            // hold its r <= 128 entries: butterfly inside a wave, the two waves meet in LDS), then scale, zero point and
+            // codes with the encoders' arithmetic; codes and {scale, zero point} go to LDS and (one group) to the cache
+            float* mm = ps_all + 1024;                        // [2 sides][2 waves][min, max]
+            float zf[S];
+#pragma unroll
+            for (int si = 0; si < S; ++si) {
+                const Side& e = sd[si];
+                const float* ps = ps_all + (e.v_side ? 512 : 0);
+                const bool mine = e.on && tid < e.r;
+                zf[si] = mine ? ((ps[tid] + ps[128 + tid]) + (ps[256 + tid] + ps[384 + tid])) + (e.eb ? Elem<E>::load(e.eb, e.b_off + tid) : 0.f) : 0.f;
+                float mn = mine ? zf[si] : INFINITY, mx = mine ? zf[si] : -INFINITY;
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    mn = fminf(mn, __shfl_xor(mn, off));
+                    mx = fmaxf(mx, __shfl_xor(mx, off));
+                }
+                if (e.on && w4 < 2 && lane == 0) { mm[(e.v_side ? 4 : 0) + 2 * w4] = mn; mm[(e.v_side ? 4 : 0) + 2 * w4 + 1] = mx; }
+            }
+            __syncthreads();
+            // kept through the loop in the 128 spare bytes after each wave's per-row terms (its last 512 bytes hold 96
+            // floats): the key codes with wave 0, the value codes with wave 1, the two {scale, zero point} with wave 2
+            signed char* zn8 = reinterpret_cast<signed char*>(zi8);              // side s: [128] codes at s * wave_lds
+            u32x2_t* znm = reinterpret_cast<u32x2_t*>(zi8 + 2 * wave_lds);        // [2 sides] {scale, zero point}
+#pragma unroll
+            for (int si = 0; si < S; ++si) {
+                const Side& e = sd[si];
+                if (e.on && tid < e.r) {
+                    const float* m4 = mm + (e.v_side ? 4 : 0);
+                    const QuantParams qp = quant_params(fminf(m4[0], m4[2]), fmaxf(m4[1], m4[3]));
+                    const signed char code = quant_code(zf[si], qp);
+                    const RowMeta meta = quant_meta(qp);
+                    zn8[(e.v_side ? wave_lds : 0) + tid] = code;
+                    if (tid == 0) znm[e.v_side ? 1 : 0] = u32x2_t{__float_as_uint(meta.scale), (unsigned)meta.zeropoint};
+                    if ((g->append >> (e.v_side ? 3 : 2)) & 1) {
+                        const size_t row = (size_t)b * p->max_seq + (n_ctx - 1);
+                        reinterpret_cast<signed char*>(e.ez)[row * e.r + tid] = code;
+                        if (tid == 0) static_cast<RowMeta*>(e.v_side ? p->enc[1].meta : p->enc[0].meta)[row] = meta;
+                    }
+                }
+            }
+            __syncthreads();
         }
-        __syncthreads();
-        znew = reinterpret_cast<const char*>(zn);
+        znew = kI8 ? zi8 : reinterpret_cast<const char*>(zn);
         patch_k = (g->append & 1) != 0;
         patch_v = (g->append & 2) != 0;
     };
     bool encode_here = false;
-    if constexpr (kPrologue && !kI8 && KVCAR_APPEND_IN_KERNEL) encode_here = p->append && (g->append & 3) && j0 < j1 && j1 == wg_tiles;     // the same for the whole workgroup
+    if constexpr (kPrologue && KVCAR_APPEND_IN_KERNEL) encode_here = p->append && (g->append & 3) && j0 < j1 && j1 == wg_tiles;     // the same for the whole workgroup
 
     // absorbed queries of this sequence and group, resident as MFMA B operands
     u32x4_t qb[NHB][KS];
@@ -553,7 +599,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
             }
         }
         __syncthreads();
-        if constexpr (!kI8 && KVCAR_APPEND_IN_KERNEL) {
+        if constexpr (KVCAR_APPEND_IN_KERNEL) {
             if (encode_here) encode_new_token();
         }
 #pragma unroll
@@ -627,6 +673,26 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
         if constexpr (kI8) {
             park_tile_i8<NL>(sg.k, lds_k, nlk, cprk, stride_k, lane);
             park_tile_i8<NL>(sg.v, lds_v, nlv, cprv, stride_v, lane);
+            if constexpr (KVCAR_APPEND_IN_KERNEL) {
+                if (znew != nullptr && n_ctx - 1 >= t0 && n_ctx - 1 < t0 + kWaveTile) {      // append-and-attend: the row encoded above
+                    const int rown = n_ctx - 1 - t0;
+                    const u32x2_t* znm = reinterpret_cast<const u32x2_t*>(znew + 2 * wave_lds);
+#pragma unroll
+                    for (int side = 0; side < 2; ++side) {
+                        if (!(side == 0 ? patch_k : patch_v)) continue;
+                        char* region = side == 0 ? lds_k : lds_v;
+                        const int stride = side == 0 ? stride_k : stride_v, cpr8 = side == 0 ? cprk : cprv;
+                        if (lane < cpr8) {                       // 16 codes per lane, parked as park_tile_i8 parks them
+                            u32x4_t lo, hi;
+                            i8_chunk_to_f16(*reinterpret_cast<const u32x4_t*>(znew + side * wave_lds + lane * 16), lo, hi);
+                            const unsigned sw = 2 * lane >= kI8SwapFrom ? 16u : 0u;
+                            *reinterpret_cast<u32x4_t*>(region + rown * stride + lane * 32 + sw) = lo;
+                            *reinterpret_cast<u32x4_t*>(region + rown * stride + lane * 32 + (16u ^ sw)) = hi;
+                        }
+                        if (lane == side * 32 + rown) sg.m = znm[side];       // the lane that holds this row's scale and zero point
+                    }
+                }
+            }
             const float inv = __builtin_amdgcn_rcpf(__uint_as_float(sg.m[0]));
             const float off = kI8Offset + (float)(int)sg.m[1];
             if (lane < 32) {

@@ -655,10 +655,10 @@ struct NewToken {
 };
 
 // Whether the attention launch planned for (layer, batch, n_ctx) can encode the new token itself: a matrix-core form with
-// its prologue inside (single split, or the one-launch split form), rows in the model dtype, linear encoders of the sizes
-// the in-kernel encoder handles, contiguous token ranges per split.
+// its prologue inside (single split, or the one-launch split form; rows in the model dtype or int8 codes), linear encoders
+// of the sizes the in-kernel encoder handles, contiguous token ranges per split.
 bool can_append_in_kernel(const kvcar_ctx* ctx, int layer, const Plan& plan) {
-    if (!(plan.fused || plan.arrive) || plan.mlp || plan.i8 || ctx->int8() || ctx->tun.tile_order == 2) return false;
+    if (!(plan.fused || plan.arrive) || plan.mlp || (ctx->int8() && !plan.i8) || ctx->tun.tile_order == 2) return false;
     if (ctx->cfg.n_kv_heads > kAppendMaxHeads) return false;
     for (int which = 0; which < 2; ++which) {
         const AEState& a = ctx->ae_at(layer, which);
@@ -720,6 +720,7 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
                 AppendSide& e = p.enc[which];
                 e.x = xs[which];
                 e.z = ctx->cache[(size_t)layer * 2 + which];
+                e.meta = ctx->int8() && e.z ? static_cast<char*>(e.z) + ctx->meta_offset(a.d.latent_width) : nullptr;
                 e.w = a.d.enc_w1; e.b = a.d.enc_b1;
                 e.in_width = a.d.in_width; e.r = a.d.latent_width;
                 e.head_block = 0;

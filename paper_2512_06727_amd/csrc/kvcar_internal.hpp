@@ -79,6 +79,7 @@ constexpr int kAppendMaxHeads = 16;  // KV heads a layer may have for the in-ker
 struct AppendSide {
     const void* x;        // [batch, d_kv]: the new token's vectors
     void* z;              // the layer's own cache [max_batch, max_seq, r]
+    void* meta;           // int8 latents: {float scale; int zeropoint} per row of that cache; else null
     const void* w;        // encoder matrix [in_width, r]
     const void* b;        // its bias or null
     int in_width, r;      // r = 0: the layer stores nothing on this side

@@ -31,7 +31,15 @@ CASES = {
     # shapes the in-kernel encoder does not take: the call falls back to the two launches
     "gpt2-f16": (C[1].scaled(n_layers=3, batch=2, n_cached=150, n_steps=2), {}, {}, False),
     "two-layer": (C[3].scaled(n_layers=2, batch=2, n_cached=90, n_steps=2), {}, {}, False),
-    "int8": (C[2].scaled(n_layers=3, batch=2, n_cached=200, n_steps=2), {"latent_format": "int8"}, {}, False),
+    # int8 rows: the workgroup quantises the row it encodes (several splits; one split with four and eight waves; biases
+    # and the Bernoulli map with layers that store nothing); plain-ALU plans keep the two launches
+    "int8": (C[2].scaled(n_layers=3, batch=2, n_cached=200, n_steps=2), {"latent_format": "int8"}, {}, True),
+    "int8-tile-boundary": (C[2].scaled(n_layers=3, batch=3, n_cached=255, n_steps=3), {"latent_format": "int8"}, {}, True),
+    "int8-one-split-w4": (C[4].scaled(n_layers=6, batch=2, n_cached=200, n_steps=2), {"latent_format": "int8", "with_bias": True},
+                          {"n_splits": 1, "wg_waves": 4}, True),
+    "int8-one-split-w8": (C[4].scaled(n_layers=6, batch=2, n_cached=200, n_steps=2), {"latent_format": "int8"}, {"n_splits": 1, "wg_waves": 8}, True),
+    "int8-bernoulli-splits": (C[4].scaled(n_layers=8, batch=2, n_cached=333, n_steps=2), {"latent_format": "int8", "with_bias": True}, {}, True),
+    "int8-plain-alu": (C[2].scaled(n_layers=3, batch=2, n_cached=100, n_steps=2), {"latent_format": "int8"}, {"force_generic": True}, False),
     "f32": (C[0].scaled(n_layers=2, batch=2, n_cached=60, n_steps=2, reuse="odd:5"), {"with_bias": True}, {}, False),
     "separate-kernels": (C[2].scaled(n_layers=3, batch=2, n_cached=200, n_steps=2), {}, {"no_fuse": True}, False),
 }
