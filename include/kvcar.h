@@ -281,12 +281,13 @@ int kvcar_decode_attention_static(kvcar_ctx *ctx, int layer, const void *q, void
  * attention over the cache including the row just appended ("Network Architecture", 1st and 2nd paragraphs; Eq. 1).
  *   k_new, v_new  dev [batch, D_kv]: the new token's key and value vectors of every sequence
  *   pos           position the rows are written at; attention then runs over rows 0 .. pos
- * Where the launch planned for the attention can take the encoder in (matrix-core kernels with rows in the model
- * dtype, linear encoders with in_width <= 256 and latent_width <= 128, at most 16 KV heads, tuning without no_fuse /
- * tile_order 2) the whole step of the layer is ONE kernel: the workgroup that reaches the end of a sequence's context
- * encodes that sequence's new rows, writes them to the caches and attends to them; otherwise the call enqueues what the
- * two separate calls would.  Results equal those of the two calls up to the order of the encoder's fp32 sums (the row
- * written may differ in the last place of the cache dtype on a small fraction of elements).
+ * Where the launch planned for the attention can take the encoder in (matrix-core kernels over rows in the model
+ * dtype or int8 codes, linear encoders with in_width <= 256 and latent_width <= 128 - per head with per_head
+ * autoencoders -, at most 16 KV heads, tuning without no_fuse / tile_order 2) the whole step of the layer is ONE kernel:
+ * the workgroup that reaches the end of a sequence's context encodes that sequence's new rows (and quantises them, with
+ * int8 latents), writes them to the caches and attends to them; otherwise the call enqueues what the two separate calls
+ * would.  Results equal those of the two calls up to the order of the encoder's fp32 sums (the row written may differ in
+ * the last place of the cache dtype - by one in an int8 code - on a small fraction of elements).
  * Arguments, workspace (kvcar_workspace_bytes(batch, pos + 1)) and errors as for the two calls.
  */
 int kvcar_append_attend(kvcar_ctx *ctx, int layer, const void *k_new, const void *v_new, const void *q, void *out,
@@ -329,7 +330,8 @@ int kvcar_prefill_attention(kvcar_ctx *ctx, int layer, const void *q, void *out,
 /*
  * What kvcar_decode_attention would launch for (layer, batch, n_ctx) under the current maps,
  * autoencoders and tuning.  A "group" is the set of query heads of the layer that read the same
- * (K source layer, V source layer); each distinct source's latent rows are streamed once per group.
+ * (K source layer, V source layer) - with per_head autoencoders, the query heads of one KV head; each
+ * distinct source's latent rows are streamed once per group.
  */
 typedef struct {
     int uses_mfma;          /* 1 = MFMA kernels, 0 = plain-ALU kernels                          */
