@@ -137,6 +137,41 @@ def test_per_head_prefill_attention(name):
         assert (err <= elementwise_bound(want, w.dtype)).all() and err.max() <= REL_TOL[w.dtype] * np.abs(want).max(), (n, err.max())
 
 
+@pytest.mark.parametrize("name", ["tinyllama-bernoulli-bias", "one-split-w4", "one-split-w8", "separate-kernels", "plain-alu", "gpt2-f16", "f32"])
+def test_per_head_ragged_lengths_and_exact_current_row(name):
+    """The extended step on per-head autoencoders: per-sequence context lengths (one sequence empty) together with the
+    exact current-token row, and the same step through the entry point that uses the library's static scratch buffer."""
+    w, with_bias, skw, _ = CASES[name]
+    reuse = synth.reuse_map(w)
+    parts = per_head_workloads(w, reuse)
+    orc = full_model_oracle(w, reuse, parts, with_bias)
+    ses = Session(w, reuse, with_bias=with_bias, poison=True, per_head=True, **skw)
+    n = w.n_cached
+    for layer in range(w.n_layers):
+        orc.encode_append(layer, kv_full(parts, w, layer, 0, 0, n), kv_full(parts, w, layer, 1, 0, n), 0)
+    ses.prefill(0, n, chunk=77)
+    lens = np.array(([n, 0, max(1, n // 3)] * w.batch)[:w.batch])
+    tl = torch.tensor(lens, dtype=torch.int32, device=ses.dev)
+    ses.ensure_workspace(w.batch, n)
+    for layer in range(w.n_layers):
+        q = queries_full(parts, layer, 0, 20.0)
+        kc, vc = kv_full(parts, w, layer, 0, n, n + 1)[:, 0], kv_full(parts, w, layer, 1, n, n + 1)[:, 0]
+        want = orc.decode_attention(layer, q, n, seq_lens=lens, k_cur=kc, v_cur=vc)
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(ses.dev, ses.tdt)
+        out = torch.empty_like(dev(q))
+        ses.ctx.decode_attention_ex(layer, dev(q), out, w.batch, n, ses.workspace, seq_lens=tl, k_cur=dev(kc), v_cur=dev(vc))
+        got = out.float().cpu().double().numpy()
+        err = np.abs(got - want)
+        assert np.isfinite(got).all() and (err <= elementwise_bound(want, w.dtype)).all(), (layer, err.max())
+        assert err.max() <= REL_TOL[w.dtype] * np.abs(want).max(), (layer, err.max())
+        # the plain step on the library's static scratch buffer against the same step on the workspace: the same kernels
+        a, b2 = torch.empty_like(out), torch.empty_like(out)
+        ses.ctx.decode_attention(layer, dev(q), a, w.batch, n, ses.workspace)
+        ses.ctx.decode_attention_static(layer, dev(q), b2, w.batch, n)
+        assert torch.equal(a, b2), layer
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("with_bias", [False, True])
 def test_block_diagonal_model_equals_per_head_contexts(with_bias):
     """The composition: one single-head library context per KV head."""
