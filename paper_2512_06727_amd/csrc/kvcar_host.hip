@@ -667,6 +667,15 @@ bool can_append_in_kernel(const kvcar_ctx* ctx, int layer, const Plan& plan) {
         const int in_w = a.d.per_head ? ctx->cfg.d_head : a.d.in_width, lat = a.d.per_head ? head_latent(a) : a.d.latent_width;
         if (a.d.hidden_width != 0 || in_w > 256 || in_w % 16 || lat > 128) return false;
         if (ctx->cache[(size_t)layer * 2 + which] == nullptr) return false;
+        // the row is written by a workgroup that reads it: a layer-tensor that stores rows none of the layer's own heads
+        // take (a full-width autoencoder in a layer whose heads are all reused) keeps the separate encoder launch
+        bool read_here = false;
+        for (const auto& src : plan.src) read_here |= src[which] == layer;
+        if (!read_here) return false;
+        // per-head autoencoders: every covered head's block needs its writer
+        if (a.d.per_head)
+            for (int g : a.heads)
+                if (ctx->reuse_at(layer, which, g)) return false;
     }
     return true;
 }

@@ -12,6 +12,9 @@ from tests.helpers import assert_cache_close, assert_outputs_close, assert_quant
 pytestmark = pytest.mark.gpu
 
 C = synth.CONFIGS
+ALL_K_REUSED = np.zeros((3, 2, 4), dtype=bool)
+ALL_K_REUSED[1, 0, 1] = ALL_K_REUSED[1, 1, 2] = True
+ALL_K_REUSED[2, 0, :] = True
 CASES = {
     # name: (workload, oracle / session keywords, session-only keywords, in-kernel encoder expected)
     # TinyLlama shape with a reuse chain: several splits, the last workgroup to arrive merges
@@ -42,6 +45,9 @@ CASES = {
     "int8-plain-alu": (C[2].scaled(n_layers=3, batch=2, n_cached=100, n_steps=2), {"latent_format": "int8"}, {"force_generic": True}, False),
     "f32": (C[0].scaled(n_layers=2, batch=2, n_cached=60, n_steps=2, reuse="odd:5"), {"with_bias": True}, {}, False),
     "separate-kernels": (C[2].scaled(n_layers=3, batch=2, n_cached=200, n_steps=2), {}, {"no_fuse": True}, False),
+    # full-width autoencoders, and a last layer whose key heads are ALL reused: it still stores key rows (nobody reads
+    # them), which no workgroup of the attention launch would write: that layer keeps the encoder launch
+    "p2-all-key-heads-reused": (C[2].scaled(n_layers=3, batch=2, n_cached=140, n_steps=2, policy="P2"), {"reuse": ALL_K_REUSED}, {}, False),
 }
 
 
