@@ -40,12 +40,20 @@ def run_fullsize(w, layers, seqs, gain, check_cache=True, latent_format="dtype")
         need |= {n} | set(sources(reuse, n, 0)) | set(sources(reuse, n, 1))
     need = sorted(need)
     ses.prefill(0, w.n_cached, chunk=max(1, (1 << 24) // (w.batch * w.d_kv)), layers=need)
-    ses.prefill(w.n_cached, w.n_cached + 1, layers=need)            # the decode step's own token
-    for n in layers:
+    # the decode step as bench.py runs it: kvcar_append_attend per layer (encode the step's token, append, attend); layers
+    # that only supply rows to a checked layer get their token through kvcar_encode_append; sources come before their users
+    outs = {}
+    pos = w.n_cached
+    for n in need:
+        if n not in layers:
+            ses.prefill(pos, pos + 1, layers=[n])
+            continue
         q = synth.queries(w, n, 0, gain=gain)
-        out = ses.decode_attention(n, q.to(ses.dev, ses.tdt), w.n_cached + 1).float().cpu().double().numpy()
+        outs[n] = (q, ses.append_attend(n, ses.kv(n, 0, pos, pos + 1), ses.kv(n, 1, pos, pos + 1), q.to(ses.dev, ses.tdt), pos).float().cpu().double().numpy())
+    for n in layers:
+        q, out = outs[n]
         plan = ses.ctx.describe_plan(n, w.batch, w.n_cached + 1)
-        print(f"layer {n}: mfma={plan.uses_mfma} groups={plan.n_groups} splits={plan.n_splits}", flush=True)
+        print(f"layer {n}: mfma={plan.uses_mfma} groups={plan.n_groups} splits={plan.n_splits} fused={plan.fused} append_in_kernel={plan.append_in_kernel}", flush=True)
         for b in seqs:
             want, orc = oracle_unit(w, reuse, n, b, w.n_cached, q[b].double().numpy(), latent_format)
             err = np.abs(out[b] - want).max()
@@ -240,3 +248,66 @@ def test_one_sequence_of_300001_tokens(fmt):
     else:
         assert_cache_close(w, ses, orc, w.n_cached + 1)
     assert_outputs_close(w, got, want, "300001 tokens")
+
+
+def test_long_context_per_head_full_size():
+    """`bench.py --per-head` at full size: per-head (block-diagonal) autoencoders through the descriptor flag, one
+    kvcar_append_attend per layer; the oracle recomputes sampled (layer, sequence) units with dense block-diagonal
+    matrices."""
+    from paper_2512_06727_amd.harness import per_head_workloads
+    from tests.test_gpu_per_head import block_diag
+    w = synth.CONFIGS[4].scaled(n_steps=1)
+    reuse = synth.reuse_map(w)
+    parts = per_head_workloads(w, reuse)
+    deepest = int(np.argmax([n - min(sources(reuse, n, 0)) for n in range(w.n_layers)]))
+    layers = sorted({0, w.n_layers - 1, deepest})
+    need = set()
+    for n in layers:
+        need |= {n} | set(sources(reuse, n, 0)) | set(sources(reuse, n, 1))
+    need = sorted(need)
+    ses = Session(w, reuse=reuse, per_head=True)
+    ses.prefill(0, w.n_cached, chunk=max(1, (1 << 24) // (w.batch * w.d_kv)), layers=need)
+    pos, outs = w.n_cached, {}
+    for n in need:
+        if n not in layers:
+            ses.prefill(pos, pos + 1, layers=[n])
+            continue
+        q = ses.queries(n, 0, gain=30.0)
+        outs[n] = (q.float().cpu().double().numpy(), ses.append_attend(n, ses.kv(n, 0, pos, pos + 1), ses.kv(n, 1, pos, pos + 1), q, pos).float().cpu().double().numpy())
+    plan = ses.ctx.describe_plan(w.n_layers - 1, w.batch, pos + 1)
+    assert plan.n_groups == w.n_kv_heads and plan.fused == 1 and plan.append_in_kernel == 1 and plan.n_launches == 1
+
+    def oracle_unit_per_head(layer, b):
+        orc = O.KVCAROracle(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, 1, w.max_seq, w.dtype)
+        for n in range(w.n_layers):
+            orc.set_reuse_map(n, reuse[n, 0], reuse[n, 1])
+        mine = {layer} | set(sources(reuse, layer, 0)) | set(sources(reuse, layer, 1))
+        for n in sorted(mine):
+            for which in (0, 1):
+                stored = [g for g in range(w.n_kv_heads) if not reuse[n, which, g]]
+                aes = [synth.autoencoder(parts[g][0], n, which, parts[g][1]) for g in stored]
+                if stored:
+                    enc = [(block_diag([a.enc[0][0].double().numpy() for a in aes]), None)]
+                    dec = [(block_diag([a.dec[0][0].double().numpy() for a in aes]), None)]
+                else:
+                    enc, dec = [(np.zeros((0, 0)), None)], [(np.zeros((0, 0)), None)]
+                orc.set_autoencoder(n, which, O.Autoencoder(stored, enc, dec))
+            kv = lambda which: np.concatenate([synth.kv_tokens(wg, n, which, b, b + 1, 0, pos + 1).double().numpy() for wg, _ in parts], axis=2)
+            orc.encode_append(n, kv(0), kv(1), 0)
+        return orc
+
+    for n in layers:
+        q, out = outs[n]
+        for b in (0, 131, 255):
+            orc = oracle_unit_per_head(n, b)
+            want = orc.decode_attention(n, q[b][None], pos + 1)[0]
+            err, ref = np.abs(out[b] - want).max(), np.abs(want).max()
+            assert err <= ABS_TOL[w.dtype] and err <= REL_TOL[w.dtype] * ref, (n, b, err, ref)
+            for which in (0, 1):
+                view = ses.cache_view(n, which)
+                if view is None:
+                    continue
+                zg = view[b, : pos + 1].float().cpu().double().numpy()
+                zo = orc.Z[(n, which)][0, : pos + 1]
+                ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(zo), 1e-30))) - 7)
+                assert (np.abs(zg - zo) <= 1.0001 * ulp + 2e-6 * np.abs(zo).max()).all(), (n, b, which)
