@@ -160,7 +160,11 @@ typedef struct {
                            streaming one (linear encoders, 8192 tokens or more)                      */
     int no_arrive;      /* 1 = with several splits the partials always go to a separate merge kernel; default: where the
                            shapes allow, one launch whose last workgroup per (sequence, group) merges and decodes */
-    int reserved[1];    /* must be 0 */
+    int group_slots;    /* matrix-core attention over rows up to 128 wide: most query heads one workgroup serves: 8, 16 or
+                           32; 0 = automatic (launches that would then still read no more than about 320 MB - bound by latency, not
+                           by bandwidth - give every KV head a group of its own where that keeps the layer one launch: less
+                           prologue, partial and epilogue per workgroup, at the price of reading a source's rows once per
+                           group; larger launches keep up to 32 heads per workgroup) */
 } kvcar_tuning;
 
 /* Create / destroy a context.  ERR_ARG on null pointers, ERR_SHAPE on non-positive sizes or

@@ -198,6 +198,7 @@ int head_column(const kvcar_ctx* ctx, int src, int which, int g) {
 }
 
 constexpr size_t kLdsBudget = 150 * 1024;
+constexpr size_t kFineGroupBytes = 320u << 20;     // bytes a launch may read with groups made as small as the maps allow
 
 int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan) {
     const kvcar_config& c = ctx->cfg;
@@ -258,12 +259,36 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     if (mlp_ok) mlp_ok = ((mlp_r == 128 && mlp_c == 256) || (mlp_r == 64 && mlp_c == 128)) &&
                          (mlp_act == KVCAR_ACT_GELU || mlp_act == KVCAR_ACT_LEAKY_RELU);
     if (mlp_ok) mfma_ok = true;
+    // Query heads per group on the matrix-core kernels for rows up to 128 wide.  A workgroup's fixed work - absorbed
+    // queries, its partial, the merge and the V decoder - grows with the heads it serves, its share of the streaming does
+    // not.  A launch that moves little (a few dozen sequences) is a chain of such fixed pieces: there every KV head gets
+    // a group of its own (as few heads per workgroup as the maps allow while the layer stays one launch), although each
+    // group then reads its sources' rows for itself - the copies meet in the caches.  A launch that moves a lot is bound by
+    // those bytes and keeps up to 32 heads per workgroup.  Measured crossover: between 300 and 440 MB read per launch
+    // (TinyLlama shape, 2048 cached tokens: 64 sequences gain a fifth with a group per KV head, 96 sequences lose a fifth).
+    int fine_cap = 0;                                       // 0: the kernels' capacity
+    if (mfma_ok && !mlp_ok && r_all <= 128) {
+        if (ctx->tun.group_slots > 0) {
+            fine_cap = ctx->tun.group_slots;
+        } else {
+            for (int cap_try : {gq, 16}) {                  // one KV head per group, else one head block
+                size_t n_groups = 0, bytes = 0;             // ... and what the launch then reads
+                for (auto& bh : bases) {
+                    const size_t chunks = (bh.heads.size() + cap_try - 1) / cap_try;
+                    n_groups += chunks;
+                    bytes += chunks * (size_t)(bh.gd.k.r + bh.gd.v.r) * ctx->row_elem_bytes() * batch * n_ctx;
+                }
+                if (cap_try <= 32 && n_groups <= (size_t)kMaxGroups && bytes <= kFineGroupBytes) { fine_cap = cap_try; break; }
+            }
+        }
+    }
     for (auto& bh : bases) {
         const GroupDesc& base = bh.gd;
         const std::vector<int>& heads = bh.heads;
         int cap;
         if (mfma_ok) {
             cap = (mlp_ok || r_all <= 128) ? 32 : 16;      // head blocks one wave can keep accumulators for
+            if (fine_cap > 0) cap = std::min(cap, fine_cap);
         } else {
             // slot capacity of one plain-ALU workgroup: accumulators and LDS
             cap = std::min(kMaxSlots, kGenericAcc * 256 / std::max(1, base.v.c));
@@ -523,7 +548,7 @@ int kvcar_bind_cache(kvcar_ctx* ctx, int layer, int which, void* dev, size_t byt
 
 int kvcar_set_tuning(kvcar_ctx* ctx, const kvcar_tuning* t) try {
     if (!ctx || !t) return KVCAR_ERR_ARG;
-    if (t->n_splits < 0 || t->tile_order < 0 || t->tile_order > 2 || (t->wg_waves != 0 && t->wg_waves != 4 && t->wg_waves != 8) || t->reserved[0] != 0)
+    if (t->n_splits < 0 || t->tile_order < 0 || t->tile_order > 2 || (t->wg_waves != 0 && t->wg_waves != 4 && t->wg_waves != 8) || (t->group_slots != 0 && t->group_slots != 8 && t->group_slots != 16 && t->group_slots != 32))
         return fail(ctx, KVCAR_ERR_ARG, "bad tuning value");
     ctx->tun = *t;
     return KVCAR_OK;

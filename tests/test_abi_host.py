@@ -383,3 +383,40 @@ def test_per_head_descriptor_rules_and_plan():
         assert lib.kvcar_bind_cache(f32._h, 0, which, FAKE, f32.cache_bytes(0, which)) == B.OK
     p = f32.describe_plan(0, 2, 40)
     assert p.n_groups == 4 and p.uses_mfma == 0
+
+
+def test_small_launches_get_a_group_per_kv_head():
+    """Host planning of the query heads per attention workgroup (fake device pointers, nothing launched): a launch that
+    reads little is planned with a group per KV head - more, smaller workgroups - as long as the layer stays one launch;
+    a launch that reads a lot keeps up to 32 heads per workgroup; kvcar_tuning.group_slots overrides either."""
+    lib = B.lib()
+
+    def model(hq, hkv, mb, ms, rh=32):
+        ctx = make(n_layers=2, hq=hq, hkv=hkv, dh=64, mb=mb, ms=ms)
+        ctx.set_reuse_map(1, [1] + [0] * (hkv - 1), [1] + [0] * (hkv - 1))
+        for layer, n in ((0, hkv), (1, hkv - 1)):
+            for which in (B.K, B.V):
+                assert lib.kvcar_set_autoencoder(ctx._h, layer, which, C.byref(desc(64 * n, 0, rh * n))) == B.OK
+                assert lib.kvcar_bind_cache(ctx._h, layer, which, FAKE, ctx.cache_bytes(layer, which)) == B.OK
+        return ctx
+
+    ctx = model(32, 4, 256, 8300)
+    small, big = ctx.describe_plan(0, 32, 2049), ctx.describe_plan(0, 256, 8193)
+    assert (small.n_groups, small.n_launches, small.fused) == (4, 1, 2) and small.n_splits == 2       # 4 x 32 workgroup units: two splits fill the chip
+    assert (big.n_groups, big.n_splits, big.fused) == (1, 1, 1)
+    assert small.latent_bytes == 4 * 2 * 128 * 2 * 32 * 2049                 # every group reads the whole rows
+    assert ctx.describe_plan(1, 32, 2049).n_groups == 4                      # head 0 from layer 0, three heads of its own: 1 + 3 groups
+    assert ctx.describe_plan(1, 256, 8193).n_groups == 2
+    ctx.set_tuning(group_slots=32)
+    assert ctx.describe_plan(0, 32, 2049).n_groups == 1
+    ctx.set_tuning(group_slots=8)
+    assert ctx.describe_plan(0, 256, 8193).n_groups == 4
+    ctx.set_tuning(group_slots=16)
+    assert ctx.describe_plan(0, 32, 2049).n_groups == 2
+    t = B.Tuning()
+    t.group_slots = 12
+    assert lib.kvcar_set_tuning(ctx._h, C.byref(t)) == B.ERR_ARG
+    # sixteen KV heads of two query heads each: a group per KV head would need two launches, so 16 heads per group
+    wide = model(32, 16, 8, 600, rh=8)
+    p = wide.describe_plan(0, 8, 512)
+    assert p.n_groups == 2 and p.n_launches == 1

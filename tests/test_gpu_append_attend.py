@@ -9,7 +9,7 @@ from paper_2512_06727_amd import synth
 from paper_2512_06727_amd.harness import Session
 from tests.helpers import assert_cache_close, assert_outputs_close, assert_quantized_cache_close, run_oracle
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("both_groupings")]
 
 C = synth.CONFIGS
 ALL_K_REUSED = np.zeros((3, 2, 4), dtype=bool)

@@ -7,7 +7,7 @@ import torch
 from paper_2512_06727_amd import synth
 from paper_2512_06727_amd.harness import Session
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("both_groupings")]
 
 
 @pytest.mark.parametrize("fmt,splits", [("dtype", 1), ("dtype", 3), ("int8", 1)])

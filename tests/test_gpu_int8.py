@@ -10,7 +10,7 @@ from oracle import kvcar_oracle as O
 from paper_2512_06727_amd import binding, synth
 from helpers import assert_outputs_close, assert_quantized_cache_close, run_gpu, run_oracle
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("both_groupings")]
 
 C = synth.CONFIGS
 CASES = {

@@ -8,7 +8,7 @@ from paper_2512_06727_amd import synth
 from tests.helpers import (ABS_TOL, assert_cache_close, assert_outputs_close, assert_quantized_cache_close, build_oracle,
                            oracle_prefill, run_gpu, run_oracle)
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("both_groupings")]
 
 C = synth.CONFIGS
 
@@ -236,11 +236,11 @@ def test_one_launch_split_kernel_gives_the_same_bits_every_time():
     it was complete, or out of a stale cache line, would show up as a differing output."""
     from paper_2512_06727_amd.harness import Session
     w = C[2].scaled(n_layers=3, batch=24, n_cached=2300, n_steps=1)
-    ses = Session(w, poison=True)
+    ses = Session(w, poison=True, n_splits=6)
     ses.prefill(0, w.n_cached + 1, chunk=512)
     n_ctx = w.n_cached + 1
     plan = ses.ctx.describe_plan(2, w.batch, n_ctx)
-    assert plan.fused == 2 and plan.n_splits >= 4
+    assert plan.fused == 2 and plan.n_splits == 6
     ses.ensure_workspace(w.batch, n_ctx)
     q = synth.queries(w, 2, 0, gain=20.0).to(ses.dev, ses.tdt)
     first = ses.decode_attention(2, q, n_ctx).clone()

@@ -9,7 +9,7 @@ from paper_2512_06727_amd import synth
 from tests.helpers import (ABS_TOL, REL_TOL, elementwise_bound, assert_cache_close, assert_outputs_close, assert_quantized_cache_close, build_oracle, oracle_prefill,
                            run_gpu, run_oracle)
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("both_groupings")]
 
 
 def draw_cases(n, seed=20251206, matrix_core=False):

@@ -9,7 +9,7 @@ from paper_2512_06727_amd import synth
 from paper_2512_06727_amd.harness import Session
 from tests.helpers import ABS_TOL, REL_TOL, build_oracle, elementwise_bound, oracle_prefill
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("both_groupings")]
 
 C = synth.CONFIGS
 CASES = {
