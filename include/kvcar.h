@@ -205,7 +205,10 @@ int kvcar_bind_cache(kvcar_ctx *ctx, int layer, int which, void *dev, size_t byt
 int kvcar_set_tuning(kvcar_ctx *ctx, const kvcar_tuning *tuning);
 
 /* Workspace (device bytes) that kvcar_decode_attention needs for `batch` sequences of `n_ctx`
- * cached tokens, maximised over layers under the current maps, autoencoders and tuning. */
+ * cached tokens, maximised over layers under the current maps, autoencoders and tuning.  The launch plan (splits per
+ * sequence, query heads per workgroup) follows the sizes of the call, so the need is not monotonic in batch or n_ctx:
+ * ask for the sizes of the call, or take the largest answer over the sizes to come; a workspace that is too small is
+ * refused with KVCAR_ERR_WORKSPACE before anything is enqueued. */
 int kvcar_workspace_bytes(const kvcar_ctx *ctx, int batch, int n_ctx, size_t *bytes);
 
 /*
