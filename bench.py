@@ -464,7 +464,9 @@ def roofline_entry(w, m, latent_format):
     achieved = m["alg_bytes"] / (m["attend_ms"] * 1e-3) / 1e9
     kernel = "attend_generic_kernel"
     if plan.uses_mfma:
-        kernel = "attend_mlp_mfma_kernel" if w.hidden else "attend_i8_mfma_r128_kernel" if latent_format == "int8" else "attend_mfma_kernel"
+        # the attention kernel's forms by row width and waves per workgroup: all launches of a step are averaged
+        kernel = ("attend_mlp_mfma_kernel" if w.hidden else "attend_i8_mfma_r128_kernel / attend_i8_mfma_r128_w8_kernel" if latent_format == "int8"
+                  else "attend_mfma_r384_kernel" if w.latent > 128 else "attend_mfma_r128_kernel / attend_mfma_r128_w8_kernel")
     r = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
          "traffic": None, "algorithmic_bytes_per_launch": m["alg_bytes"] / max(1, m["n_launch"]),
          "avg_launch_ms": m["attend_ms"] / max(1, m["n_launch"]), "launches": m["n_launch"],
