@@ -118,6 +118,9 @@ struct AttendParams {
     const void* v_cur;    //   more row after the cached ones; or both null
 };
 
+// Kernel arguments travel in the kernel-argument segment, which holds at most 4 KB.
+static_assert(sizeof(AttendParams) <= 4096, "AttendParams must fit the kernel-argument segment");
+
 struct EncodeSide {
     const void* x;        // [batch, t_new, d_kv]
     void* z;              // cache [max_batch, max_seq, r]
