@@ -13,11 +13,12 @@ __global__ __launch_bounds__(256, 2) void attend_i8_mfma_r128_kernel(AttendParam
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     (void)p_by_value;
     KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
-    KGroup g = &p->g[blockIdx.z];
+    const WgCoords wc = wg_coords(p);
+    KGroup g = &p->g[wc.z];
     const int key = g->k.r * 4 + (g->slots_pad >> 4);
     if (p->fused == 4) {                      // several splits in one launch: the last workgroup to arrive merges and decodes
         switch (key) {
-#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true, kWaves, true, true>(p, g, lds_raw, kI8WaveLds); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true, kWaves, true, true>(p, g, wc, lds_raw, kI8WaveLds); return;
             KVCAR_EXACT_SHAPES(X)
 #undef X
             default: return;
@@ -25,7 +26,7 @@ __global__ __launch_bounds__(256, 2) void attend_i8_mfma_r128_kernel(AttendParam
     }
     if (p->fused == 3) {                      // several splits, absorbed queries computed here
         switch (key) {
-#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true, kWaves, true>(p, g, lds_raw, kI8WaveLds); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true, kWaves, true>(p, g, wc, lds_raw, kI8WaveLds); return;
             KVCAR_EXACT_SHAPES(X)
 #undef X
             default: return;
@@ -33,14 +34,14 @@ __global__ __launch_bounds__(256, 2) void attend_i8_mfma_r128_kernel(AttendParam
     }
     if (p->fused) {
         switch (key) {
-#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, true>(p, g, lds_raw, kI8WaveLds); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, true>(p, g, wc, lds_raw, kI8WaveLds); return;
             KVCAR_EXACT_SHAPES(X)
 #undef X
             default: return;
         }
     }
     switch (key) {
-#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true>(p, g, lds_raw, kI8WaveLds); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true>(p, g, wc, lds_raw, kI8WaveLds); return;
         KVCAR_EXACT_SHAPES(X)
 #undef X
         default: return;
@@ -53,9 +54,10 @@ __global__ __launch_bounds__(512, 1) void attend_i8_mfma_r128_w8_kernel(AttendPa
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     (void)p_by_value;
     KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
-    KGroup g = &p->g[blockIdx.z];
+    const WgCoords wc = wg_coords(p);
+    KGroup g = &p->g[wc.z];
     switch (g->k.r * 4 + (g->slots_pad >> 4)) {
-#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, true, 8>(p, g, lds_raw, kI8WaveLds); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, true, 8>(p, g, wc, lds_raw, kI8WaveLds); return;
         KVCAR_EXACT_SHAPES(X)
 #undef X
         default: return;

@@ -10,14 +10,15 @@ __global__ __launch_bounds__(256, 2) void attend_mfma_r128_kernel(AttendParams p
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     (void)p_by_value;
     KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
-    KGroup g = &p->g[blockIdx.z];
+    const WgCoords wc = wg_coords(p);
+    KGroup g = &p->g[wc.z];
     constexpr size_t wl = Geo<128>::kWaveLds;
     const int nhb = g->slots_pad >> 4;
     if (g->k.r == g->v.r) {
         const int key = g->k.r * 4 + nhb;
         if (p->fused == 1) {                  // the host only asks for this with exact shapes in every group
             switch (key) {
-#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true>(p, g, lds_raw, wl); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true>(p, g, wc, lds_raw, wl); return;
                 KVCAR_EXACT_SHAPES(X)
 #undef X
                 default: return;
@@ -25,7 +26,7 @@ __global__ __launch_bounds__(256, 2) void attend_mfma_r128_kernel(AttendParams p
         }
         if (p->fused == 4) {                  // several splits in one launch: the last workgroup to arrive merges and decodes
             switch (key) {
-#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, false, kWaves, true, true>(p, g, lds_raw, wl); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, false, kWaves, true, true>(p, g, wc, lds_raw, wl); return;
                 KVCAR_EXACT_SHAPES(X)
 #undef X
                 default: return;
@@ -33,20 +34,20 @@ __global__ __launch_bounds__(256, 2) void attend_mfma_r128_kernel(AttendParams p
         }
         if (p->fused == 3) {                  // several splits, absorbed queries computed here
             switch (key) {
-#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, false, kWaves, true>(p, g, lds_raw, wl); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, false, kWaves, true>(p, g, wc, lds_raw, wl); return;
                 KVCAR_EXACT_SHAPES(X)
 #undef X
                 default: return;
             }
         }
         switch (key) {
-#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false>(p, g, lds_raw, wl); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false>(p, g, wc, lds_raw, wl); return;
             KVCAR_EXACT_SHAPES(X)
 #undef X
             default: break;
         }
     }
-    attend_body<E, DimsAny<128, 2>, false>(p, g, lds_raw, wl);
+    attend_body<E, DimsAny<128, 2>, false>(p, g, wc, lds_raw, wl);
 }
 
 // Fused single-split variant with eight waves per workgroup, for launches with no more workgroups
@@ -57,10 +58,11 @@ __global__ __launch_bounds__(512, 1) void attend_mfma_r128_w8_kernel(AttendParam
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     (void)p_by_value;
     KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
-    KGroup g = &p->g[blockIdx.z];
+    const WgCoords wc = wg_coords(p);
+    KGroup g = &p->g[wc.z];
     constexpr size_t wl = Geo<128>::kWaveLds;
     switch (g->k.r * 4 + (g->slots_pad >> 4)) {
-#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, false, 8>(p, g, lds_raw, wl); return;
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, false, 8>(p, g, wc, lds_raw, wl); return;
         KVCAR_EXACT_SHAPES(X)
 #undef X
         default: return;
@@ -73,11 +75,12 @@ __global__ __launch_bounds__(256, 1) void attend_mfma_r384_kernel(AttendParams p
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     (void)p_by_value;
     KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
-    KGroup g = &p->g[blockIdx.z];
+    const WgCoords wc = wg_coords(p);
+    KGroup g = &p->g[wc.z];
     constexpr size_t wl = Geo<384>::kWaveLds;
-    if (g->k.r == g->v.r && g->k.r == 384) { attend_body<E, DimsExact<384, 1>, false>(p, g, lds_raw, wl); return; }
-    if (g->k.r == g->v.r && g->k.r == 288) { attend_body<E, DimsExact<288, 1>, false>(p, g, lds_raw, wl); return; }
-    attend_body<E, DimsAny<384, 1>, false>(p, g, lds_raw, wl);
+    if (g->k.r == g->v.r && g->k.r == 384) { attend_body<E, DimsExact<384, 1>, false>(p, g, wc, lds_raw, wl); return; }
+    if (g->k.r == g->v.r && g->k.r == 288) { attend_body<E, DimsExact<288, 1>, false>(p, g, wc, lds_raw, wl); return; }
+    attend_body<E, DimsAny<384, 1>, false>(p, g, wc, lds_raw, wl);
 }
 
 template <typename K>

@@ -259,8 +259,36 @@ struct AgentBuf {
 // up, or has even counted itself in already); a workgroup arrives only after its own attempt, so the counter is set up
 // by then and arriving is one atomic add.  The last workgroup leaves {0, 0}, so a replay of a captured launch (same
 // epoch) starts over.
+// Which (split, sequence, group) a workgroup takes: (blockIdx.x, blockIdx.y, blockIdx.z), unless groups of the launch
+// read the same latent rows (small launches give every KV head a group of its own).  Workgroups are dealt round-robin
+// over the chip's eight XCDs in launch order (x fastest, z slowest), which would scatter the groups of one (split,
+// sequence) over the XCDs whenever splits x batch is not a multiple of eight; each XCD has an L2 of its own, so the
+// repeated reads would then miss.  With `colocate` the workgroup whose place in the launch order is L takes unit
+// ((L / 8) / G) * 8 + L % 8 (units = (split, sequence) pairs, split fastest) and group (L / 8) % G: all G groups of a unit
+// sit on XCD L % 8.  The last units, which do not fill a round of eight, keep an order of their own.
+struct WgCoords {
+    int split, b, z;
+};
+__device__ __forceinline__ WgCoords wg_coords(KArgs p) {
+    if (!p->colocate) return WgCoords{(int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z};
+    const unsigned n_sp = (unsigned)p->n_splits, G = (unsigned)p->n_groups;
+    const unsigned L = blockIdx.x + n_sp * (blockIdx.y + (unsigned)p->batch * blockIdx.z);
+    const unsigned U = n_sp * (unsigned)p->batch, U8 = U & ~7u, N8 = U8 * G;
+    unsigned u, z;
+    if (L < N8) {
+        const unsigned k = L >> 3;
+        z = k % G;
+        u = (k / G) * 8 + (L & 7u);
+    } else {
+        const unsigned i = L - N8, rest = U - U8;
+        z = i / rest;
+        u = U8 + i % rest;
+    }
+    return WgCoords{(int)(u % n_sp), (int)(u / n_sp), (int)z};
+}
+
 template <typename E, typename D, bool kFused, bool kI8 = false, int NW = kWaves, bool kPrologue = kFused, bool kArrive = false>
-__device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, size_t wave_lds) {
+__device__ __forceinline__ void attend_body(KArgs p, KGroup g, const WgCoords& wc, char* lds_raw, size_t wave_lds) {
     static_assert(!kArrive || (kPrologue && !kFused && D::kExact && NW == kWaves), "the arrival form is a split form of the exact shapes");
     constexpr int RMAX = D::RMAX, NHB = D::NHB;
     using G = Geo<RMAX>;
@@ -272,7 +300,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     constexpr int EB = kI8 ? 1 : 2;    // bytes per cached latent element
 
     const D d(g->k.r, g->v.r, g->slots_pad >> 4);
-    const int split = blockIdx.x, b = blockIdx.y;
+    const int split = wc.split, b = wc.b;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, lg = lane >> 4;
 
@@ -343,7 +371,7 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, char* lds_raw, si
     unsigned long long* counter = nullptr;
     unsigned long long seen = 0;
     if constexpr (kArrive) {
-        counter = p->arrive + ((size_t)b * p->arrive_stride + blockIdx.z) * kArrivePitch;
+        counter = p->arrive + ((size_t)b * p->arrive_stride + wc.z) * kArrivePitch;
         if (threadIdx.x == 0) seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 

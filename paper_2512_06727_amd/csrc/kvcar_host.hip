@@ -343,9 +343,11 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     const int n_groups = (int)plan.groups.size();
     int splits = ctx->tun.n_splits;
     if (splits <= 0) {
-        // the MFMA kernel runs best with about one long-lived workgroup per compute unit
-        const int target = plan.mfma ? ctx->n_cu : ctx->n_cu * 2;
-        splits = (target + batch * n_groups - 1) / (batch * n_groups);
+        // the MFMA kernel runs best with about one long-lived workgroup per compute unit, and rather with fewer workgroups
+        // than units than with a second split (more than half a chip of (sequence, group) pairs: one split each; measured
+        // at 36 to 63 sequences of four groups, one split against two: 0.62-0.72 ms per step against 0.70-0.82)
+        const int units = batch * n_groups;
+        splits = plan.mfma ? std::max(1, ctx->n_cu / units) : (ctx->n_cu * 2 + units - 1) / units;
     }
     const int tile = plan.mlp ? 32 : plan.mfma ? 128 : kGenericTile;   // tokens per workgroup iteration
     const int max_splits = std::max(1, (n_ctx + tile - 1) / tile);
@@ -746,6 +748,9 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
         p.k_cur = exact ? ext->k_cur : nullptr;
         p.v_cur = exact ? ext->v_cur : nullptr;
         p.tile_order = ctx->tun.tile_order == 2 ? 1 : 0;
+        for (int i = 0; i < p.n_groups && !p.colocate; ++i)          // groups that stream the same rows: keep them on one XCD
+            for (int k = 0; k < i; ++k)
+                if (p.g[i].k.z == p.g[k].k.z || p.g[i].v.z == p.g[k].v.z) p.colocate = 1;
         if (fresh) {
             p.append = 1;
             const void* xs[2] = {fresh->k_new, fresh->v_new};

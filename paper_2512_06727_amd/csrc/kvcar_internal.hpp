@@ -113,6 +113,7 @@ struct AttendParams {
     int append;                   // 1 = append-and-attend: the new token (position n_ctx - 1 of every sequence) is encoded in
     AppendSide enc[2];            //   this kernel, written to the cache and attended to as the context's last row
     int gq;               // query heads per KV head
+    int colocate;         // 1 = groups of this launch read the same rows: the groups of a (split, sequence) share an XCD
     const int* seq_lens;  // per-sequence context length [batch] (ragged batch), or null: n_ctx for all
     const void* k_cur;    // exact key / value row of the current token [batch, H_kv * d_head], attended as one
     const void* v_cur;    //   more row after the cached ones; or both null
