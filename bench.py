@@ -498,7 +498,7 @@ def measure_decode(w, args, steps, warmup, graph=True, plain=False):
     reuse = synth.reuse_map(w)
     elem = synth.DTYPE_BYTES[w.dtype]
     separate = False if plain else args.separate_encode
-    kw = {} if plain else dict(n_splits=args.splits, tile_order=args.tile_order, wg_waves=args.wg_waves, no_fuse=args.no_fuse, no_arrive=args.no_arrive, group_slots=args.group_slots)
+    kw = {} if plain else dict(n_splits=args.splits, tile_order=args.tile_order, wg_waves=args.wg_waves, no_fuse=args.no_fuse, no_arrive=args.no_arrive, group_slots=args.group_slots, no_colocate=args.no_colocate)
     ses = Session(w, reuse=reuse, latent_format=latent, **kw)
     lat_elem, row_meta = (1, 8) if latent == "int8" else (elem, 0)
     dev, tdt = ses.dev, ses.tdt
@@ -654,6 +654,7 @@ def main():
     ap.add_argument("--no-fuse", action="store_true", help="run prologue / attention / merge as separate kernels")
     ap.add_argument("--separate-encode", action="store_true",
                     help="a layer's step as kvcar_encode_append + kvcar_decode_attention (two calls) instead of kvcar_append_attend")
+    ap.add_argument("--no-colocate", action="store_true", help="workgroups in launch order even where groups read the same rows")
     ap.add_argument("--group-slots", type=int, default=0, help="most query heads per attention workgroup: 0 automatic, 16 or 32")
     ap.add_argument("--no-arrive", action="store_true", help="several splits: partials to the separate merge kernel instead of the one-launch form")
     ap.add_argument("--capacity-check", action="store_true",

@@ -160,6 +160,9 @@ typedef struct {
                            streaming one (linear encoders, 8192 tokens or more)                      */
     int no_arrive;      /* 1 = with several splits the partials always go to a separate merge kernel; default: where the
                            shapes allow, one launch whose last workgroup per (sequence, group) merges and decodes */
+    int no_colocate;    /* 1 = workgroups take (split, sequence, group) in launch order even where groups of the launch
+                           read the same rows; default: such launches, if they read no more than about 320 MB, place the
+                           groups of a (split, sequence) on one XCD, whose L2 then serves the repeated reads */
     int group_slots;    /* matrix-core attention over rows up to 128 wide: most query heads one workgroup serves: 8, 16 or
                            32; 0 = automatic (launches that would then still read no more than about 320 MB - bound by latency, not
                            by bandwidth - give every KV head a group of its own where that keeps the layer one launch: less

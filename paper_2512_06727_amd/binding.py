@@ -41,7 +41,7 @@ class AEDesc(C.Structure):
 
 
 class Tuning(C.Structure):
-    _fields_ = [("n_splits", C.c_int), ("force_generic", C.c_int), ("tile_order", C.c_int), ("no_fuse", C.c_int), ("wg_waves", C.c_int), ("no_bulk_encode", C.c_int), ("no_arrive", C.c_int), ("group_slots", C.c_int)]
+    _fields_ = [("n_splits", C.c_int), ("force_generic", C.c_int), ("tile_order", C.c_int), ("no_fuse", C.c_int), ("wg_waves", C.c_int), ("no_bulk_encode", C.c_int), ("no_arrive", C.c_int), ("no_colocate", C.c_int), ("group_slots", C.c_int)]
 
 
 class StepExt(C.Structure):
@@ -217,8 +217,10 @@ class Context:
         self._check(lib().kvcar_bind_cache(self._h, layer, which, _ptr(tensor), nbytes))
 
     def set_tuning(self, n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, no_fuse: bool = False,
-                   wg_waves: int = 0, no_bulk_encode: bool = False, no_arrive: bool = False, group_slots: int = 0):
-        t = Tuning(n_splits, 1 if force_generic else 0, tile_order, 1 if no_fuse else 0, wg_waves, 1 if no_bulk_encode else 0, 1 if no_arrive else 0, group_slots)
+                   wg_waves: int = 0, no_bulk_encode: bool = False, no_arrive: bool = False, group_slots: int = 0,
+                   no_colocate: bool = False):
+        t = Tuning(n_splits, 1 if force_generic else 0, tile_order, 1 if no_fuse else 0, wg_waves, 1 if no_bulk_encode else 0, 1 if no_arrive else 0,
+                   1 if no_colocate else 0, group_slots)
         self._check(lib().kvcar_set_tuning(self._h, C.byref(t)))
 
     def describe_encode(self, layer: int, batch: int, t_new: int) -> int:

@@ -748,7 +748,13 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
         p.k_cur = exact ? ext->k_cur : nullptr;
         p.v_cur = exact ? ext->v_cur : nullptr;
         p.tile_order = ctx->tun.tile_order == 2 ? 1 : 0;
-        for (int i = 0; i < p.n_groups && !p.colocate; ++i)          // groups that stream the same rows: keep them on one XCD
+        // groups that stream the same rows: keep the groups of a (split, sequence) on one XCD - where the launch is small
+        // enough for an L2 to hold what they share for as long as it takes them to get there; large launches are faster in
+        // launch order (long context, independent key and value maps: 463 us against 538 per launch)
+        size_t launch_bytes = 0;
+        for (int i = 0; i < p.n_groups; ++i) launch_bytes += (size_t)(p.g[i].k.r + p.g[i].v.r) * ctx->row_elem_bytes() * batch * std::max(1, n_ctx);
+        const bool may_colocate = !ctx->tun.no_colocate && launch_bytes <= kFineGroupBytes;
+        for (int i = 0; i < p.n_groups && may_colocate && !p.colocate; ++i)
             for (int k = 0; k < i; ++k)
                 if (p.g[i].k.z == p.g[k].k.z || p.g[i].v.z == p.g[k].v.z) p.colocate = 1;
         if (fresh) {

@@ -20,7 +20,7 @@ class Session:
     def __init__(self, w: synth.Workload, reuse: Optional[np.ndarray] = None, with_bias: bool = False,
                  device: str = "cuda:0", n_splits: int = 0, force_generic: bool = False, tile_order: int = 0, no_fuse: bool = False, poison: bool = False,
                  max_batch: Optional[int] = None, latent_format: str = "dtype", wg_waves: int = 0, no_bulk_encode: bool = False, no_arrive: bool = False,
-                 per_head: bool = False, group_slots: Optional[int] = None):
+                 per_head: bool = False, group_slots: Optional[int] = None, no_colocate: bool = False):
         """per_head: every KV head has an autoencoder d_head -> latent / H_kv -> d_head of its own (the library's
         per_head descriptor flag); head g's weights and activations are those of per_head_workloads(w)[g]."""
         if not torch.cuda.is_available():
@@ -35,7 +35,7 @@ class Session:
         self.ctx = binding.Context(w.n_layers, w.n_q_heads, w.n_kv_heads, w.d_head, max_batch or w.batch, w.max_seq, w.dtype,
                                    latent_format=latent_format)
         self.ctx.set_tuning(n_splits=n_splits, force_generic=force_generic, tile_order=tile_order, no_fuse=no_fuse, wg_waves=wg_waves, no_bulk_encode=no_bulk_encode, no_arrive=no_arrive,
-                            group_slots=default_group_slots if group_slots is None else group_slots)
+                            group_slots=default_group_slots if group_slots is None else group_slots, no_colocate=no_colocate)
         self.ae: List[List[synth.AEWeights]] = []
         self.caches: List[List[Optional[torch.Tensor]]] = []
         for layer in range(w.n_layers):

@@ -88,7 +88,7 @@ static void plan_model(int dtype, int latent_format, int hq, int hkv, int dh, in
     /* tuning: every documented value, then a bad one */
     kvcar_tuning t;
     memset(&t, 0, sizeof t);
-    t.n_splits = 5; t.no_fuse = 1; t.no_arrive = 1; t.tile_order = 2; t.wg_waves = 8; t.no_bulk_encode = 1;
+    t.n_splits = 5; t.no_fuse = 1; t.no_arrive = 1; t.tile_order = 2; t.wg_waves = 8; t.no_bulk_encode = 1; t.no_colocate = 1; t.group_slots = 16;
     CHECK(kvcar_set_tuning(ctx, &t) == KVCAR_OK);
     kvcar_plan_info info;
     CHECK(kvcar_describe_plan(ctx, 1, 7, 2049, &info) == KVCAR_OK && info.n_splits == 5 && info.fused == 0);
