@@ -116,3 +116,31 @@ def test_two_host_threads_with_their_own_contexts_and_streams():
     assert not errors, errors
     for w, g, want in zip(ws, got, wants):
         assert_outputs_close(w, g, want, w.name)
+
+
+@pytest.mark.parametrize("batch,n_rows,n_splits", [(11, 700, 3), (5, 300, 0), (37, 260, 1), (16, 1000, 0), (3, 2100, 7)])
+@pytest.mark.parametrize("fmt", ["dtype", "int8"])
+def test_where_a_workgroup_runs_does_not_change_what_it_computes(batch, n_rows, n_splits, fmt):
+    """Small launches give every KV head a group and place the groups of a (split, sequence) on one XCD by renumbering the
+    workgroups; the renumbering is a permutation of (split, sequence, group), so the outputs must equal, bit for bit,
+    those of the same launch in launch order (kvcar_tuning.no_colocate) - for unit counts that are and are not multiples
+    of eight - and match the oracle."""
+    w = synth.CONFIGS[4].scaled(n_layers=6, batch=batch, n_cached=n_rows - 1, n_steps=1)
+    orc = build_oracle(w, latent_format=fmt)
+    outs = []
+    for no_colocate in (False, True):
+        ses = Session(w, poison=True, latent_format=fmt, n_splits=n_splits, no_colocate=no_colocate, group_slots=0)
+        ses.prefill(0, n_rows, chunk=256)
+        plan = ses.ctx.describe_plan(w.n_layers - 1, batch, n_rows)
+        assert plan.n_groups == w.n_kv_heads and plan.n_launches == 1
+        outs.append([ses.decode_attention(n, synth.queries(w, n, 0, gain=20.0).to(ses.dev, ses.tdt), n_rows) for n in range(w.n_layers)])
+    for n in range(w.n_layers):
+        assert torch.equal(outs[0][n], outs[1][n]), n
+    for n in range(w.n_layers):
+        k = synth.kv_tokens(w, n, 0, 0, batch, 0, n_rows).double().numpy()
+        v = synth.kv_tokens(w, n, 1, 0, batch, 0, n_rows).double().numpy()
+        orc.encode_append(n, k, v, 0)
+    for n in range(w.n_layers):
+        want = orc.decode_attention(n, synth.queries(w, n, 0, gain=20.0).double().numpy(), n_rows)
+        err = np.abs(outs[0][n].float().cpu().double().numpy() - want).max()
+        assert err <= ABS_TOL[w.dtype] and err <= REL_TOL[w.dtype] * np.abs(want).max(), (n, err)
