@@ -12,7 +12,7 @@
 // transposing load ds_read_b64_tr_b16 (a lane needs 8 consecutive k of one column).  Hidden
 // activations are kept as a bf16/fp16 pair hi + lo so that the second layer sees them to ~2^-17
 // relative precision; the latent is rounded once, from the fp32 accumulator, to the cache dtype.
-#include "kvcar_device.hpp"
+#include "kvcar_qtilde_mfma.hpp"
 
 namespace kvcar {
 
@@ -88,8 +88,7 @@ __device__ __forceinline__ void mma_kstep(f32x4_t (&acc)[NB], u32x4_t a, const c
 // 16 * NB1, each workgroup reading only its window of the weight matrix.  A decode step encodes a handful of
 // tokens: without the split one workgroup per tensor streams the whole matrix (590 KB for 768 -> 384) alone.
 template <typename E, int NB1, int NB2, bool kTwoLayer, bool kSplit = false>
-__global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+__device__ __forceinline__ void encode_mfma_body(const EncodeParams& p, char* lds) {
     const EncodeSide& s = p.s[blockIdx.y];
     if (s.r == 0) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -238,6 +237,28 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
                 if (row_ok[v]) z[row_off[v] + col] = EncMma<E>::to16(out_acc[nb][v] + bias);
         }
     }
+}
+
+template <typename E, int NB1, int NB2, bool kTwoLayer, bool kSplit = false>
+__global__ __launch_bounds__(256) void encode_mfma_kernel(EncodeParams p) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    encode_mfma_body<E, NB1, NB2, kTwoLayer, kSplit>(p, lds);
+}
+
+// A decode step's two small independent pieces in one launch: the new token's latent rows (the column-window form of
+// the encoder above: workgroups blockIdx.x < enc_x) and the absorbed queries of the attention launch that follows
+// (qtilde_mfma_block: the workgroups beyond, with blockIdx.y = blockIdx.z = 0, numbered (x, y, z) over a qx x qy x .. grid).
+// Two launches of about 6 us each become one.
+template <typename E>
+__global__ __launch_bounds__(256) void encode_step_qtilde_kernel(EncodeParams p, AttendParams q, int enc_x, int qx, int qy) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    if ((int)blockIdx.x < enc_x) {
+        encode_mfma_body<E, 2, 1, false, true>(p, lds);
+        return;
+    }
+    if (blockIdx.y != 0 || blockIdx.z != 0) return;
+    const int id = (int)blockIdx.x - enc_x;
+    qtilde_mfma_block<E>(&q, id % qx, (id / qx) % qy, id / (qx * qy), qx);
 }
 
 // Decode steps with int8 latents (linear encoder, few tokens): a row's minimum and maximum need the whole row, so
@@ -398,6 +419,34 @@ hipError_t launch_encode_mfma(const EncodeParams& p, int dtype, hipStream_t stre
                   : launch_enc(encode_mfma_kernel<F16, 8, 1, false>, lds, p, stream, set[3]);
     return bf ? launch_enc(encode_mfma_kernel<BF16, 24, 1, false>, lds, p, stream, set[4])
               : launch_enc(encode_mfma_kernel<F16, 24, 1, false>, lds, p, stream, set[5]);
+}
+
+// The decode-step encoder (linear, rows in the model dtype, at most 2048 tokens) and the absorbed-query projection of `q`
+// in one launch.  The caller has checked that both pieces have these forms (encode_step_qtilde_supported).
+bool encode_step_qtilde_supported(const EncodeParams& p, int dtype) {
+    if (!encode_mfma_supported(p, dtype) || (long long)p.batch * p.t_new > 2048) return false;
+    for (int i = 0; i < 2; ++i)
+        if (p.s[i].r > 0 && (p.s[i].hidden > 0 || p.s[i].meta != nullptr)) return false;
+    return true;
+}
+
+hipError_t launch_encode_step_qtilde(const EncodeParams& p, const AttendParams& q, int qx, int qy, int qz, int dtype, hipStream_t stream) {
+    static_assert(sizeof(EncodeParams) + sizeof(AttendParams) + 16 <= 4096, "both argument blocks must fit the kernel-argument segment");
+    static AttrFlag set[2] = {false, false};
+    const bool bf = dtype == KVCAR_BF16;
+    auto kern = bf ? encode_step_qtilde_kernel<BF16> : encode_step_qtilde_kernel<F16>;
+    if (!set[bf ? 0 : 1]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        set[bf ? 0 : 1] = true;
+    }
+    int rmax = 0;
+    for (int i = 0; i < 2; ++i) rmax = p.s[i].r > rmax ? p.s[i].r : rmax;
+    const int n_tok = p.batch * p.t_new;
+    const int enc_x = (n_tok + kEncTokens - 1) / kEncTokens;
+    dim3 grid(enc_x + qx * qy * qz, 2, (rmax + 31) / 32);
+    hipLaunchKernelGGL(kern, grid, dim3(256), kWBufBytes, stream, p, q, enc_x, qx, qy);
+    return hipGetLastError();
 }
 
 }  // namespace kvcar

@@ -708,7 +708,8 @@ bool can_append_in_kernel(const kvcar_ctx* ctx, int layer, const Plan& plan) {
 }
 
 int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, const kvcar_step_ext* ext, void* workspace,
-                size_t workspace_bytes, void* stream, bool library_scratch = false, const NewToken* fresh = nullptr) {
+                size_t workspace_bytes, void* stream, bool library_scratch = false, const NewToken* fresh = nullptr,
+                const EncodeParams* with_encode = nullptr) {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     const kvcar_config& c = ctx->cfg;
@@ -795,8 +796,20 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
         p.fused = plan.fused ? (w8 ? 2 : 1) : plan.arrive ? 4 : plan.prologue ? 3 : 0;
         const bool proj = plan.mfma && proj_mfma_supported(p, c.dtype);
         hipError_t e = hipSuccess;
-        if (!plan.fused && !plan.prologue)
+        // append-and-attend (with_encode): the step's encoder launch and the projection of the absorbed queries are
+        // independent: where both are the matrix-core forms they share one launch, else the encoder goes first
+        const bool own_qtilde = !plan.fused && !plan.prologue;
+        const bool together = with_encode && g0 == 0 && own_qtilde && proj && !plan.i8;
+        if (with_encode && g0 == 0) {
+            if (!together) e = launch_encode_mfma(*with_encode, c.dtype, st);
+        }
+        if (e == hipSuccess && together) {
+            int qx, qy, qz;
+            qtilde_mfma_grid(p, qx, qy, qz);
+            e = launch_encode_step_qtilde(*with_encode, p, qx, qy, qz, c.dtype, st);
+        } else if (e == hipSuccess && own_qtilde) {
             e = proj && !plan.i8 ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma || plan.i8, st);
+        }
         std::pair<hipEvent_t, hipEvent_t>* ev = nullptr;
         if (e == hipSuccess && ctx->profiling && !library_scratch) {
             if (ctx->ev_used == ctx->ev_pool.size()) {
@@ -965,6 +978,17 @@ int kvcar_append_attend(kvcar_ctx* ctx, int layer, const void* k_new, const void
     if (!q || !out || !aligned16(q) || !aligned16(out)) return fail(ctx, KVCAR_ERR_ARG, "q / out null or misaligned");
     if (!workspace || !aligned16(workspace)) return fail(ctx, KVCAR_ERR_ARG, "workspace null or misaligned");
     if (workspace_bytes < plan.total_bytes) return fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, plan.total_bytes);
+    // where the attention needs a projection launch of its own for the absorbed queries and the encoder is the decode-step
+    // form of the linear matrix-core encoder, the two share a launch; decode_impl reports whether it took the encoder in
+    if (plan.mfma && !plan.i8 && !plan.mlp && !plan.fused && !plan.prologue && encode_pieces(ctx, layer) == 1) {
+        EncodeParams ep;
+        bool any = false;
+        rc = fill_encode_params(ctx, layer, k_new, v_new, batch, pos, nullptr, 1, true, ep, any);
+        if (rc) return rc;
+        if (any && !ctx->tun.force_generic && encode_step_qtilde_supported(ep, c.dtype)) {
+            return decode_impl(ctx, layer, q, out, batch, pos + 1, nullptr, workspace, workspace_bytes, stream, false, nullptr, &ep);
+        }
+    }
     rc = encode_impl(ctx, layer, k_new, v_new, batch, pos, nullptr, 1, stream);
     if (rc) return rc;
     return decode_impl(ctx, layer, q, out, batch, pos + 1, nullptr, workspace, workspace_bytes, stream);
