@@ -12,7 +12,7 @@
 // The two weight slices of a later hidden block are fetched into registers while the current block
 // computes and written to another of the LDS buffers: one barrier per hidden block.
 // The latent is rounded once, from the fp32 accumulator, to the cache dtype and appended.
-#include "kvcar_device.hpp"
+#include "kvcar_qtilde_mfma.hpp"
 
 namespace kvcar {
 
@@ -71,8 +71,7 @@ constexpr int kW1Stride = 64 + 32;   // LDS row stride of a [in, 32] slice of W1
 // matrix and vector work (18 us for 256 -> 256 -> 128).  Four weight slices are staged per round, wave w computes
 // block 4 round + w, the waves' partial latent rows are added in wave order through LDS and wave 0 appends them.
 template <typename E, int KX, int NBZ, bool GELU, bool kSmall>
-__global__ __launch_bounds__(256, kSmall ? 1 : 2) void encode_mlp_mfma_kernel(EncodeParams p, int side0) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+__device__ __forceinline__ void encode_mlp_mfma_body(const EncodeParams& p, int side0, char* lds) {
     const EncodeSide& s = p.s[blockIdx.y + side0];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5, l16 = lane & 15;
@@ -301,6 +300,27 @@ __global__ __launch_bounds__(256, kSmall ? 1 : 2) void encode_mlp_mfma_kernel(En
                 u32x2_t{EMma<E>::pack2(accz[nb][4 * a], accz[nb][4 * a + 1]), EMma<E>::pack2(accz[nb][4 * a + 2], accz[nb][4 * a + 3])};
 }
 
+template <typename E, int KX, int NBZ, bool GELU, bool kSmall>
+__global__ __launch_bounds__(256, kSmall ? 1 : 2) void encode_mlp_mfma_kernel(EncodeParams p, int side0) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    encode_mlp_mfma_body<E, KX, NBZ, GELU, kSmall>(p, side0, lds);
+}
+
+// A decode step's two small independent pieces in one launch: the new token's latent rows (the few-token form above, both
+// tensors: workgroups blockIdx.x < enc_x) and the absorbed queries of the attention launch that follows
+// (qtilde_mfma_block: the workgroups beyond, with blockIdx.y = 0, numbered (x, y, z) over a qx x qy x .. grid).
+template <typename E, int KX, int NBZ, bool GELU>
+__global__ __launch_bounds__(256, 1) void encode_mlp_step_qtilde_kernel(EncodeParams p, AttendParams q, int enc_x, int qx, int qy) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    if ((int)blockIdx.x < enc_x) {
+        encode_mlp_mfma_body<E, KX, NBZ, GELU, true>(p, 0, lds);
+        return;
+    }
+    if (blockIdx.y != 0) return;
+    const int id = (int)blockIdx.x - enc_x;
+    qtilde_mfma_block<E>(&q, id % qx, (id / qx) % qy, id / (qx * qy), qx);
+}
+
 namespace {
 
 struct EmShape { int kx, nbz; };
@@ -348,7 +368,67 @@ hipError_t em_launch(const EncodeParams& p, int side0, int n_sides, hipStream_t 
     return hipErrorInvalidValue;
 }
 
+template <typename E, int KX, int NBZ>
+hipError_t em_step_qtilde_shape(const EncodeParams& p, const AttendParams& q, int qx, int qy, int qz, bool gelu, hipStream_t stream) {
+    const int n_tok = p.batch * p.t_new;
+    constexpr size_t buf = (size_t)(16 * KX * kW1Stride + 32 * (64 * NBZ + 32)), biases = 4 * 1024 + 4 * 32 * NBZ;
+    const size_t lds = 4 * buf + biases;
+    void (*kern)(EncodeParams, AttendParams, int, int, int) = gelu ? encode_mlp_step_qtilde_kernel<E, KX, NBZ, true> : encode_mlp_step_qtilde_kernel<E, KX, NBZ, false>;
+    static AttrFlag attr[2] = {false, false};
+    if (lds > 64 * 1024 && !attr[gelu]) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (err != hipSuccess) return err;
+        attr[gelu] = true;
+    }
+    const int enc_x = (n_tok + 31) / 32;
+    dim3 grid(enc_x + qx * qy * qz, 2);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p, q, enc_x, qx, qy);
+    return hipGetLastError();
+}
+
+// Whether a shape's few-token form applies (its four weight slices and biases fit the LDS).
+template <int KX, int NBZ>
+constexpr bool em_small_fits() { return 4 * (size_t)(16 * KX * kW1Stride + 32 * (64 * NBZ + 32)) + 4 * 1024 + 4 * 32 * NBZ <= 160 * 1024; }
+
+template <typename E>
+hipError_t em_step_qtilde(const EncodeParams& p, const AttendParams& q, int qx, int qy, int qz, hipStream_t stream) {
+    const EncodeSide& s = p.s[0];
+    const bool gelu = s.act == KVCAR_ACT_GELU;
+    const int kx = s.in_width / 16, nbz = s.r / 32;
+    if (kx == 4 && nbz == 1) return em_step_qtilde_shape<E, 4, 1>(p, q, qx, qy, qz, gelu, stream);
+    if (kx == 8 && nbz == 2) return em_step_qtilde_shape<E, 8, 2>(p, q, qx, qy, qz, gelu, stream);
+    if (kx == 12 && nbz == 3) return em_step_qtilde_shape<E, 12, 3>(p, q, qx, qy, qz, gelu, stream);
+    if (kx == 16 && nbz == 4) return em_step_qtilde_shape<E, 16, 4>(p, q, qx, qy, qz, gelu, stream);
+    if (kx == 16 && nbz == 2) return em_step_qtilde_shape<E, 16, 2>(p, q, qx, qy, qz, gelu, stream);
+    if (kx == 8 && nbz == 1) return em_step_qtilde_shape<E, 8, 1>(p, q, qx, qy, qz, gelu, stream);
+    return hipErrorInvalidValue;
+}
+
+bool em_small_shape_fits(int kx, int nbz) {
+    if (kx == 4 && nbz == 1) return em_small_fits<4, 1>();
+    if (kx == 8 && nbz == 2) return em_small_fits<8, 2>();
+    if (kx == 12 && nbz == 3) return em_small_fits<12, 3>();
+    if (kx == 16 && nbz == 4) return em_small_fits<16, 4>();
+    if (kx == 16 && nbz == 2) return em_small_fits<16, 2>();
+    if (kx == 8 && nbz == 1) return em_small_fits<8, 1>();
+    return false;
+}
+
 }  // namespace
+
+// The few-token form for both tensors at once (same shape and activation, at most 128 tokens) can share its launch with the
+// absorbed-query projection.
+bool encode_mlp_step_qtilde_supported(const EncodeParams& p, int dtype) {
+    if (!encode_mlp_mfma_supported(p, dtype)) return false;
+    const EncodeSide &k = p.s[0], &v = p.s[1];
+    if (!(k.r && v.r && k.in_width == v.in_width && k.r == v.r && (k.act == KVCAR_ACT_GELU) == (v.act == KVCAR_ACT_GELU))) return false;
+    return p.batch * p.t_new <= kEmTokens && em_small_shape_fits(k.in_width / 16, k.r / 32);
+}
+
+hipError_t launch_encode_mlp_step_qtilde(const EncodeParams& p, const AttendParams& q, int qx, int qy, int qz, int dtype, hipStream_t stream) {
+    static_assert(sizeof(EncodeParams) + sizeof(AttendParams) + 16 <= 4096, "both argument blocks must fit the kernel-argument segment");
+    return dtype == KVCAR_BF16 ? em_step_qtilde<BF16>(p, q, qx, qy, qz, stream) : em_step_qtilde<F16>(p, q, qx, qy, qz, stream);
+}
 
 // 16-bit dtype, every stored tensor two-layer with one of the compiled (input width, latent) shapes,
 // 16-column chunks inside one head, hidden width a multiple of 32 up to 1024.

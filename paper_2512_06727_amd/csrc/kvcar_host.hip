@@ -676,6 +676,13 @@ int encode_impl(kvcar_ctx* ctx, int layer, const void* k_new, const void* v_new,
 // `library_scratch`: the workspace is the library's static buffer (sized by the caller of this function, not by the
 // user) and the call must not create anything: no timing events.
 // The new token of an append-and-attend call.
+// The encoder launch of an append-and-attend call whose attention has a projection launch of its own: decode_impl
+// enqueues it, together with that projection where both have their matrix-core forms.
+struct StepEncoder {
+    const EncodeParams* p;
+    bool two_layer;       // the few-token form of the two-layer encoder, else the decode-step form of the linear one
+};
+
 struct NewToken {
     const void* k_new;
     const void* v_new;
@@ -709,7 +716,7 @@ bool can_append_in_kernel(const kvcar_ctx* ctx, int layer, const Plan& plan) {
 
 int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, int n_ctx, const kvcar_step_ext* ext, void* workspace,
                 size_t workspace_bytes, void* stream, bool library_scratch = false, const NewToken* fresh = nullptr,
-                const EncodeParams* with_encode = nullptr) {
+                const StepEncoder* with_encode = nullptr) {
     int rc = check_layer(ctx, layer);
     if (rc) return rc;
     const kvcar_config& c = ctx->cfg;
@@ -800,13 +807,13 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
         // independent: where both are the matrix-core forms they share one launch, else the encoder goes first
         const bool own_qtilde = !plan.fused && !plan.prologue;
         const bool together = with_encode && g0 == 0 && own_qtilde && proj && !plan.i8;
-        if (with_encode && g0 == 0) {
-            if (!together) e = launch_encode_mfma(*with_encode, c.dtype, st);
-        }
+        if (with_encode && g0 == 0 && !together)
+            e = with_encode->two_layer ? launch_encode_mlp_mfma(*with_encode->p, c.dtype, st) : launch_encode_mfma(*with_encode->p, c.dtype, st);
         if (e == hipSuccess && together) {
             int qx, qy, qz;
             qtilde_mfma_grid(p, qx, qy, qz);
-            e = launch_encode_step_qtilde(*with_encode, p, qx, qy, qz, c.dtype, st);
+            e = with_encode->two_layer ? launch_encode_mlp_step_qtilde(*with_encode->p, p, qx, qy, qz, c.dtype, st)
+                                       : launch_encode_step_qtilde(*with_encode->p, p, qx, qy, qz, c.dtype, st);
         } else if (e == hipSuccess && own_qtilde) {
             e = proj && !plan.i8 ? launch_qtilde_mfma(p, c.dtype, st) : launch_qtilde(p, c.dtype, !plan.mfma || plan.i8, st);
         }
@@ -980,13 +987,17 @@ int kvcar_append_attend(kvcar_ctx* ctx, int layer, const void* k_new, const void
     if (workspace_bytes < plan.total_bytes) return fail(ctx, KVCAR_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, plan.total_bytes);
     // where the attention needs a projection launch of its own for the absorbed queries and the encoder is the decode-step
     // form of the linear matrix-core encoder, the two share a launch; decode_impl reports whether it took the encoder in
-    if (plan.mfma && !plan.i8 && !plan.mlp && !plan.fused && !plan.prologue && encode_pieces(ctx, layer) == 1) {
+    if (plan.mfma && !plan.i8 && !plan.fused && !plan.prologue && encode_pieces(ctx, layer) == 1 && !ctx->int8()) {
         EncodeParams ep;
         bool any = false;
         rc = fill_encode_params(ctx, layer, k_new, v_new, batch, pos, nullptr, 1, true, ep, any);
         if (rc) return rc;
-        if (any && !ctx->tun.force_generic && encode_step_qtilde_supported(ep, c.dtype)) {
-            return decode_impl(ctx, layer, q, out, batch, pos + 1, nullptr, workspace, workspace_bytes, stream, false, nullptr, &ep);
+        const int kind = any ? encode_kernel_kind(ctx, ep) : KVCAR_ENC_NONE;
+        const bool linear = kind == KVCAR_ENC_MFMA && encode_step_qtilde_supported(ep, c.dtype);
+        const bool two_layer = kind == KVCAR_ENC_MFMA_TWO_LAYER && encode_mlp_step_qtilde_supported(ep, c.dtype);
+        if (linear || two_layer) {
+            const StepEncoder enc{&ep, two_layer};
+            return decode_impl(ctx, layer, q, out, batch, pos + 1, nullptr, workspace, workspace_bytes, stream, false, nullptr, &enc);
         }
     }
     rc = encode_impl(ctx, layer, k_new, v_new, batch, pos, nullptr, 1, stream);

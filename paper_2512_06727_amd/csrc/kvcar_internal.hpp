@@ -164,6 +164,9 @@ void qtilde_mfma_grid(const AttendParams& p, int& qx, int& qy, int& qz);
 // The decode-step encoder (linear, rows in the model dtype) and the absorbed-query projection in one launch.
 bool encode_step_qtilde_supported(const EncodeParams& p, int dtype);
 hipError_t launch_encode_step_qtilde(const EncodeParams& p, const AttendParams& q, int qx, int qy, int qz, int dtype, hipStream_t stream);
+// The same for the few-token form of the two-layer encoder.
+bool encode_mlp_step_qtilde_supported(const EncodeParams& p, int dtype);
+hipError_t launch_encode_mlp_step_qtilde(const EncodeParams& p, const AttendParams& q, int qx, int qy, int qz, int dtype, hipStream_t stream);
 
 // MFMA attention for two-layer decoders (resident first-layer weights).
 bool attend_mlp_mfma_supported(const AttendParams& p, int dtype);
