@@ -296,7 +296,8 @@ int kvcar_decode_attention_static(kvcar_ctx *ctx, int layer, const void *q, void
  * autoencoders -, at most 16 KV heads, tuning without no_fuse / tile_order 2) the whole step of the layer is ONE kernel:
  * the workgroup that reaches the end of a sequence's context encodes that sequence's new rows (and quantises them, with
  * int8 latents), writes them to the caches and attends to them; otherwise the call enqueues what the two separate calls
- * would.  Results equal those of the two calls up to the order of the encoder's fp32 sums (the row written may differ in
+ * would - except that the encoder of a few tokens and the projection of the absorbed queries, two small independent
+ * launches, become one where both have their matrix-core forms (GPT-2-shaped and two-layer configurations).  Results equal those of the two calls up to the order of the encoder's fp32 sums (the row written may differ in
  * the last place of the cache dtype - by one in an int8 code - on a small fraction of elements).
  * Arguments, workspace (kvcar_workspace_bytes(batch, pos + 1)) and errors as for the two calls.
  */
