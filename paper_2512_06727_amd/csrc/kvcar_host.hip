@@ -339,25 +339,14 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     plan.qt_stride = qt;
     plan.part_stride = part;
 
-    // token-range splits: enough workgroups to fill the chip, never less than one tile per split
-    const int n_groups = (int)plan.groups.size();
-    int splits = ctx->tun.n_splits;
-    if (splits <= 0) {
-        // the MFMA kernel runs best with about one long-lived workgroup per compute unit, and rather with fewer workgroups
-        // than units than with a second split (more than half a chip of (sequence, group) pairs: one split each; measured
-        // at 36 to 63 sequences of four groups, one split against two: 0.62-0.72 ms per step against 0.70-0.82)
-        const int units = batch * n_groups;
-        splits = plan.mfma ? std::max(1, ctx->n_cu / units) : (ctx->n_cu * 2 + units - 1) / units;
-    }
-    const int tile = plan.mlp ? 32 : plan.mfma ? 128 : kGenericTile;   // tokens per workgroup iteration
-    const int max_splits = std::max(1, (n_ctx + tile - 1) / tile);
-    splits = std::max(1, std::min(splits, std::min(max_splits, 256)));
-    plan.n_splits = splits;
+    // whether the absorbed queries (prologue) and the output epilogue (fused) can run inside the matrix-core kernel:
+    // decided over the groups, before the number of splits, which depends on it
     plan.fused = false;
     plan.prologue = false;
     plan.arrive = false;
-    if (plan.mfma && !plan.mlp && !ctx->tun.no_fuse && r_all <= 128 && c.d_head % 32 == 0 && c.d_head <= 128) {
-        plan.fused = true;                                  // whether the epilogue can run inside: decided over the groups below
+    const bool one_launch_family = plan.mfma && !plan.mlp && !ctx->tun.no_fuse && r_all <= 128 && c.d_head % 32 == 0 && c.d_head <= 128;
+    if (one_launch_family) {
+        plan.fused = true;                                  // whether the epilogue can run inside
         plan.prologue = true;                               // the query side alone: also with several splits
         for (auto& gd : plan.groups) {
             if (gd.k.r != gd.v.r || gd.k.r % 32 || gd.k.r < 32 || gd.slots_pad > 32 || gd.n_kseg == 0) plan.fused = plan.prologue = false;
@@ -376,10 +365,37 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
                 if (kinds > 2) plan.fused = plan.prologue = false;
             }
         }
-        // with several splits the same prologue and epilogue run in the one-launch form whose last workgroup merges
-        plan.arrive = plan.fused && plan.prologue && splits > 1 && splits <= kArriveMaxSplits && !ctx->tun.no_arrive;
-        plan.fused = plan.fused && splits == 1;
     }
+    const bool arrive_ok = plan.fused && plan.prologue && !ctx->tun.no_arrive;      // several splits can finish in the same launch
+
+    // token-range splits: enough workgroups to fill the chip, never less than one tile per split
+    const int n_groups = (int)plan.groups.size();
+    const int tile = plan.mlp ? 32 : plan.mfma ? 128 : kGenericTile;   // tokens per workgroup iteration
+    const int wg_tiles = std::max(1, (n_ctx + tile - 1) / tile);
+    int splits = ctx->tun.n_splits;
+    if (splits <= 0) {
+        const int units = batch * n_groups;
+        if (arrive_ok) {
+            // The one-launch forms.  More than half a chip of (sequence, group) pairs: one long-lived workgroup each (a second
+            // split costs the whole arrival tail: 36 to 63 sequences of four groups, 0.62-0.72 ms per step against 0.70-0.82).
+            // Fewer: splits fill the chip - one workgroup per compute unit up to a quarter chip of pairs, two beyond; never
+            // more workgroups than are resident at once (512: beyond, launches take half as long again) - but a split keeps
+            // about four workgroup tiles: with less the loop is shorter than the merge of one more partial (TinyLlama at 2048
+            // tokens, 4 sequences: 16 splits 0.49 ms per step, 5 splits 0.41; 32 sequences: 2 splits 0.61, 4 splits 0.58).
+            const int by_tiles = (wg_tiles + 3) / 4;
+            if (2 * units > ctx->n_cu) splits = 1;
+            else if (4 * units > ctx->n_cu) splits = std::min(2 * ctx->n_cu / units, by_tiles);
+            else splits = std::min(ctx->n_cu / units, by_tiles);
+        } else {
+            // separate kernels: about one workgroup per compute unit for the matrix-core kernels, two for the plain ones
+            splits = plan.mfma ? std::max(1, ctx->n_cu / units) : (ctx->n_cu * 2 + units - 1) / units;
+        }
+    }
+    splits = std::max(1, std::min(splits, std::min(wg_tiles, 256)));
+    plan.n_splits = splits;
+    // with several splits the same prologue and epilogue run in the one-launch form whose last workgroup merges
+    plan.arrive = arrive_ok && splits > 1 && splits <= kArriveMaxSplits;
+    plan.fused = plan.fused && splits == 1;
     plan.qt_bytes = align_up((size_t)batch * qt * (plan.mfma && !plan.i8 ? 2 : 4), 256);
     plan.part_bytes = align_up((size_t)batch * splits * part * sizeof(float), 256);
     // one-launch split form: an 8-byte arrival counter per (sequence, group) after the partials

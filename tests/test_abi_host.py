@@ -347,7 +347,7 @@ def test_per_head_descriptor_rules_and_plan():
     launched): what it accepts, that the cache keeps its size, that a layer is planned as one group per KV head, and that
     a head reused from an earlier layer costs that head's rows only."""
     lib = B.lib()
-    ctx = make(n_layers=3, hq=32, hkv=4, dh=64, mb=8, ms=512)
+    ctx = make(n_layers=3, hq=32, hkv=4, dh=64, mb=8, ms=2048)
 
     def ph(in_w, hid, lat, act=B.ACT_NONE, flag=1):
         d = desc(in_w, hid, lat, act)
@@ -365,14 +365,15 @@ def test_per_head_descriptor_rules_and_plan():
         for which, n in ((B.K, nk), (B.V, nv)):
             assert lib.kvcar_set_autoencoder(ctx._h, layer, which, C.byref(ph(64 * n, 0, 32 * n))) == B.OK
             need = ctx.cache_bytes(layer, which)
-            assert need == 8 * 512 * 32 * n * 2            # the head blocks together are as large as the dense rows
+            assert need == 8 * 2048 * 32 * n * 2            # the head blocks together are as large as the dense rows
             assert lib.kvcar_bind_cache(ctx._h, layer, which, FAKE, need) == B.OK
     for layer in range(3):
-        p = ctx.describe_plan(layer, 8, 300)
+        p = ctx.describe_plan(layer, 8, 2000)
         assert p.n_groups == 4 and p.uses_mfma == 1 and p.n_launches == 1
-        assert p.latent_bytes == 4 * 2 * 32 * 2 * 8 * 300  # 4 heads x (K + V) x 32 columns x 2 bytes, per cached token and sequence
+        assert p.latent_bytes == 4 * 2 * 32 * 2 * 8 * 2000  # 4 heads x (K + V) x 32 columns x 2 bytes, per cached token and sequence
         assert p.fused == 2 and p.append_in_kernel == 1    # 8 sequences x 4 groups: several splits, one launch
-    assert ctx.describe_plan(2, 8, 300).n_splits == 3          # 300 tokens are three 128-token workgroup tiles
+    assert ctx.describe_plan(2, 8, 2000).n_splits == 4         # 16 workgroup tiles: four per split
+    assert ctx.describe_plan(2, 8, 300).n_splits == 1          # three tiles: not worth a second partial
     # int8 latents do not combine with the flag
     c8 = B.Context(2, 32, 4, 64, 2, 64, "bf16", latent_format="int8")
     assert lib.kvcar_set_autoencoder(c8._h, 0, B.K, C.byref(ph(256, 0, 128))) == B.ERR_UNSUPPORTED
@@ -402,7 +403,7 @@ def test_small_launches_get_a_group_per_kv_head():
 
     ctx = model(32, 4, 256, 8300)
     small, big = ctx.describe_plan(0, 32, 2049), ctx.describe_plan(0, 256, 8193)
-    assert (small.n_groups, small.n_launches, small.fused) == (4, 1, 2) and small.n_splits == 2       # 4 x 32 workgroup units: two splits fill the chip
+    assert (small.n_groups, small.n_launches, small.fused) == (4, 1, 2) and small.n_splits == 4       # 4 x 32 (sequence, group) pairs: two workgroups per compute unit
     assert (big.n_groups, big.n_splits, big.fused) == (1, 1, 1)
     assert small.latent_bytes == 4 * 2 * 128 * 2 * 32 * 2049                 # every group reads the whole rows
     assert ctx.describe_plan(1, 32, 2049).n_groups == 4                      # head 0 from layer 0, three heads of its own: 1 + 3 groups
