@@ -77,9 +77,18 @@ def test_append_attend_steps(name):
         assert_cache_close(w, ses, orc, w.n_cached + w.n_steps)
 
 
-def test_append_attend_in_a_replayed_graph():
-    """The one-kernel step captured as a HIP graph: replays rewrite the same cache row and give the eager result."""
-    w = C[4].scaled(n_layers=4, batch=4, n_cached=600, n_steps=2)
+GRAPH_CASES = {
+    # the one-kernel step; the step whose encoder shares a launch with the absorbed-query projection (linear, two-layer)
+    "one-kernel": (C[4].scaled(n_layers=4, batch=4, n_cached=600, n_steps=2), 1),
+    "gpt2-folded": (C[1].scaled(n_layers=3, batch=3, n_cached=300, n_steps=2), 0),
+    "two-layer-folded": (C[3].scaled(n_layers=2, batch=3, n_cached=200, n_steps=2), 0),
+}
+
+
+@pytest.mark.parametrize("name", list(GRAPH_CASES))
+def test_append_attend_in_a_replayed_graph(name):
+    """The step captured as a HIP graph: replays rewrite the same cache row and give the eager result."""
+    w, in_kernel = GRAPH_CASES[name]
     ses = Session(w, poison=True)
     ses.prefill(0, w.n_cached, chunk=256)
     dev, tdt, pos = ses.dev, ses.tdt, w.n_cached
@@ -88,7 +97,7 @@ def test_append_attend_in_a_replayed_graph():
     qs = [synth.queries(w, n, 0, device=dev, gain=10.0).to(tdt) for n in range(w.n_layers)]
     outs = [torch.empty_like(q) for q in qs]
     ses.ensure_workspace(w.batch, w.max_seq)
-    assert ses.ctx.describe_plan(3, w.batch, pos + 1).append_in_kernel == 1
+    assert ses.ctx.describe_plan(w.n_layers - 1, w.batch, pos + 1).append_in_kernel == in_kernel
 
     def step():
         for n in range(w.n_layers):
