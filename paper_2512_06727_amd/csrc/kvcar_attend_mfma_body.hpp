@@ -78,6 +78,14 @@ inline bool exact_shape(int r, int nhb) {
 constexpr int kWaveTile = 32;     // tokens per wave per iteration
 constexpr int kWaves = 4;
 
+// One-launch split form, last workgroup: where in LDS the table of the splits' (m, l) pairs [split][slot] and the table
+// of the splits' scaling factors [split][slot] live while the partials are merged - past the first kilobyte (the
+// arrival flag, the per-slot weights), inside what every launch of these kernels is given (the staging regions of a
+// 128-wide latent, 71680 bytes); the merged sums and the decoder slices overwrite them afterwards.
+constexpr int kArriveMlTab = 1024;
+constexpr int kArriveFTab = kArriveMlTab + kArriveMaxSplits * 32 * 8;
+static_assert(kArriveFTab + kArriveMaxSplits * 32 * 4 <= 71680, "the merge tables must fit the staging regions");
+
 #ifndef KVCAR_APPEND_IN_KERNEL
 #define KVCAR_APPEND_IN_KERNEL 1
 #endif
@@ -948,20 +956,30 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, const WgCoords& w
         m_all[nb] = M;
         l_all[nb] = L;
     }
-    // arrival form, last workgroup: a batch of four splits' (m, l) pairs and latent sums of this thread's share
-    u32x2_t batch_ml[kArrive ? 4 : 1][NHB];
-    f32x4_t batch_x[kArrive ? 4 : 1][NHB][2];
-    auto arrive_issue = [&](const AgentBuf& buf, int s0, int n_sp, unsigned split_bytes, int pstride, int c0) {
+    // Arrival form, last workgroup.  The splits' partials are read as what they are in memory, runs of consecutive bytes:
+    // 16-byte chunk i of a partial's latent sums (i = t, t + 256, ..: head slot i / (rv / 4), columns 4 (i % (rv / 4)) ..)
+    // goes to thread t, so a wave's load covers whole cache lines (loads that leave the chip's caches are paid per line
+    // touched: a layout that follows the accumulator's lanes takes three times as long).  kAB splits per memory round trip.
+    constexpr int NS = NHB * 16;                          // head slots of a partial
+    constexpr int kRowChunks = kArrive ? RMAX / 4 : 1;    // 16-byte chunks of a slot's latent sums (exact shapes: rv = RMAX)
+    constexpr int kJ = kArrive ? (NS * kRowChunks + 64 * NW - 1) / (64 * NW) : 1;      // chunks per thread
+    constexpr int kAB = kArrive ? (16 / kJ < 4 ? 4 : 16 / kJ) : 1;      // as many as registers allow without spilling
+    f32x4_t batch_x[kAB][kJ];
+    int mslot[kJ], mcol[kJ];
+    unsigned moff[kJ];                                    // byte offset of the chunk in a partial, kNowhere: none
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+    for (int j = 0; j < kJ; ++j) {
+        const int i = j * (64 * NW) + (int)threadIdx.x;
+        mslot[j] = i / kRowChunks;
+        mcol[j] = 4 * (i % kRowChunks);
+        moff[j] = mslot[j] < g->n_slots ? (unsigned)((mslot[j] * (rv + 4) + 4 + mcol[j]) * 4) : AgentBuf::kNowhere;
+    }
+    auto arrive_issue = [&](const AgentBuf& buf, int s0, int n_sp, unsigned split_bytes) {
 #pragma unroll
-            for (int nb = 0; nb < NHB; ++nb) {
-                const bool on = s0 + u < n_sp;
-                const unsigned row = (unsigned)(s0 + u) * split_bytes + (unsigned)((nb * 16 + l16) * pstride * 4);
-                batch_ml[kArrive ? u : 0][nb] = buf.load8(on ? row : AgentBuf::kNowhere);
-                batch_x[kArrive ? u : 0][nb][0] = buf.load(on && c0 >= 0 ? row + (unsigned)((4 + c0) * 4) : AgentBuf::kNowhere);
-                batch_x[kArrive ? u : 0][nb][1] = buf.load(on && c0 >= 0 ? row + (unsigned)((8 + c0) * 4) : AgentBuf::kNowhere);
-            }
+        for (int u = 0; u < kAB; ++u)
+#pragma unroll
+            for (int j = 0; j < kJ; ++j)
+                batch_x[u][j] = buf.load(s0 + u < n_sp && moff[j] != AgentBuf::kNowhere ? (unsigned)(s0 + u) * split_bytes + moff[j] : AgentBuf::kNowhere);
     };
     if constexpr (!kFused) {
 #pragma unroll
@@ -1000,35 +1018,41 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, const WgCoords& w
         __syncthreads();
         if (*flag + 1u != (unsigned)p->n_splits) return;          // the same for every thread of the workgroup
         if (threadIdx.x == 0) __hip_atomic_store(counter, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // Last to arrive: every split's partial is complete in memory.  All loads of a batch of splits are issued before
-        // anything waits (a loop that loads, waits and adds per split pays a memory round trip per split).  The first
-        // batch of latent sums (four splits) is requested here already, ahead of the (m, l) pairs that scale them.
+        // Last to arrive: every split's partial is complete in memory.  All loads of a batch are issued before anything
+        // waits (a loop that loads, waits and adds per split pays a memory round trip per split).  The first batch of
+        // latent sums is requested here already, ahead of the (m, l) pairs that scale them.
         const float* pall = p->part + (size_t)b * p->n_splits * p->part_stride + g->part_off;
         const int pstride = rv + 4;
         const int n_sp = p->n_splits;
         const unsigned split_bytes = (unsigned)p->part_stride * 4u;
-        const AgentBuf pbuf(pall, (unsigned)(n_sp - 1) * split_bytes + (unsigned)(NHB * 16 * pstride * 4));
-        const int c0 = 8 * (4 * wave + lg);               // this thread's latent columns c0 .. c0 + 7 of head slots nb * 16 + l16
-        arrive_issue(pbuf, 0, n_sp, split_bytes, pstride, c0 < rv ? c0 : -1);
+        const AgentBuf pbuf(pall, (unsigned)(n_sp - 1) * split_bytes + (unsigned)(NS * pstride * 4));
+        arrive_issue(pbuf, 0, n_sp, split_bytes);
+        // the (m, l) pairs of every split and head slot: one load each, shared out over the workgroup, into a table in LDS
+        constexpr int kMl = kArriveMaxSplits * NS / (64 * NW);
+        u32x2_t ml[kMl];
+#pragma unroll
+        for (int k = 0; k < kMl; ++k) {
+            const int e = k * (64 * NW) + (int)threadIdx.x, sp = e / NS, slot = e % NS;
+            ml[k] = pbuf.load8(sp < n_sp && slot < g->n_slots ? (unsigned)sp * split_bytes + (unsigned)(slot * pstride * 4) : AgentBuf::kNowhere);
+        }
+        u32x2_t* ml_tab = reinterpret_cast<u32x2_t*>(lds_raw + kArriveMlTab);          // [split][slot]
+#pragma unroll
+        for (int k = 0; k < kMl; ++k) {
+            const int e = k * (64 * NW) + (int)threadIdx.x, sp = e / NS, slot = e % NS;
+            if (sp < n_sp) ml_tab[e] = slot < g->n_slots ? ml[k] : u32x2_t{__float_as_uint(-INFINITY), 0u};
+        }
+        __syncthreads();
 #pragma unroll
         for (int nb = 0; nb < NHB; ++nb) { m_all[nb] = -INFINITY; l_all[nb] = 0.f; }
-        for (int s0 = 0; s0 < n_sp; s0 += 8) {
-            u32x2_t ml[8][NHB];
+        for (int sp = 0; sp < n_sp; ++sp)
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-#pragma unroll
-                for (int nb = 0; nb < NHB; ++nb)
-                    ml[u][nb] = pbuf.load8(s0 + u < n_sp ? (unsigned)(s0 + u) * split_bytes + (unsigned)((nb * 16 + l16) * pstride * 4) : AgentBuf::kNowhere);
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-#pragma unroll
-                for (int nb = 0; nb < NHB; ++nb) {
-                    const float ms = s0 + u < n_sp ? __uint_as_float(ml[u][nb][0]) : -INFINITY, ls = __uint_as_float(ml[u][nb][1]);
-                    const float Mn = fmaxf(m_all[nb], ms);
-                    l_all[nb] = (m_all[nb] == -INFINITY ? 0.f : l_all[nb] * exp2f(m_all[nb] - Mn)) + (ms == -INFINITY ? 0.f : ls * exp2f(ms - Mn));
-                    m_all[nb] = Mn;
-                }
-        }
+            for (int nb = 0; nb < NHB; ++nb) {
+                const u32x2_t e = ml_tab[sp * NS + nb * 16 + l16];
+                const float ms = __uint_as_float(e[0]), ls = __uint_as_float(e[1]);
+                const float Mn = fmaxf(m_all[nb], ms);
+                l_all[nb] = (m_all[nb] == -INFINITY ? 0.f : l_all[nb] * exp2f(m_all[nb] - Mn)) + (ms == -INFINITY ? 0.f : ls * exp2f(ms - Mn));
+                m_all[nb] = Mn;
+            }
     }
     if constexpr (kFused || kArrive) {
         // ---- the current token's exact row, if given ("Network Architecture", 2nd paragraph: the decoded cache
@@ -1120,27 +1144,34 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, const WgCoords& w
         constexpr int kItems = NHB * MB * 64;                  // float4 items of the merged sums
         constexpr int kPerThread = (kItems + 64 * NW - 1) / (64 * NW);
         f32x4_t merged[kArrive ? 1 : kPerThread];
-        f32x4_t mrow[kArrive ? NHB : 1][2];                    // arrival form: this thread's eight columns of its head slots
+        f32x4_t msum[kJ];                                      // arrival form: the merged sums of this thread's chunks
         if constexpr (kArrive) {
-            // Merge of the splits' partials, in split order (deterministic): this thread takes head slots nb * 16 + l16
-            // (the slots its factors were computed for) and latent columns c0 .. c0 + 7, four splits per round trip.
-            const float* pall = p->part + (size_t)b * p->n_splits * p->part_stride + g->part_off;
+            // Merge of the splits' partials, in split order (deterministic).  What a split's sums are scaled by,
+            // 2^(m_split - M) / L per head slot, goes through a second table in LDS: the thread that holds a chunk is not
+            // the thread whose lanes hold that slot's M and L.
             const int n_sp = p->n_splits;
+            const u32x2_t* ml_tab = reinterpret_cast<const u32x2_t*>(lds_raw + kArriveMlTab);
+            float* f_tab = reinterpret_cast<float*>(lds_raw + kArriveFTab);            // [split][slot]
+            for (int sp = 4 * wave + lg; sp < n_sp; sp += 4 * NW)
+#pragma unroll
+                for (int nb = 0; nb < NHB; ++nb) {
+                    const float ms = __uint_as_float(ml_tab[sp * NS + nb * 16 + l16][0]);
+                    f_tab[sp * NS + nb * 16 + l16] = ms == -INFINITY ? 0.f : exp2f(ms - m_all[nb]) * inv_l[nb];
+                }
+            __syncthreads();
+            const float* pall = p->part + (size_t)b * p->n_splits * p->part_stride + g->part_off;
             const unsigned split_bytes = (unsigned)p->part_stride * 4u;
-            const AgentBuf pbuf(pall, (unsigned)(n_sp - 1) * split_bytes + (unsigned)(NHB * 16 * ostride * 4));
-            const int c0 = 8 * (4 * wave + lg);
+            const AgentBuf pbuf(pall, (unsigned)(n_sp - 1) * split_bytes + (unsigned)(NS * ostride * 4));
 #pragma unroll
-            for (int nb = 0; nb < NHB; ++nb) mrow[nb][0] = mrow[nb][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            for (int s0 = 0; s0 < n_sp; s0 += 4) {
-                if (s0 > 0) arrive_issue(pbuf, s0, n_sp, split_bytes, ostride, c0 < rv ? c0 : -1);
+            for (int j = 0; j < kJ; ++j) msum[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            for (int s0 = 0; s0 < n_sp; s0 += kAB) {
+                if (s0 > 0) arrive_issue(pbuf, s0, n_sp, split_bytes);
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < kAB; ++u)
 #pragma unroll
-                    for (int nb = 0; nb < NHB; ++nb) {
-                        const float ms = s0 + u < n_sp ? __uint_as_float(batch_ml[kArrive ? u : 0][nb][0]) : -INFINITY;
-                        const float f = ms == -INFINITY ? 0.f : exp2f(ms - m_all[nb]) * inv_l[nb];
-                        mrow[kArrive ? nb : 0][0] += batch_x[kArrive ? u : 0][nb][0] * f;
-                        mrow[kArrive ? nb : 0][1] += batch_x[kArrive ? u : 0][nb][1] * f;
+                    for (int j = 0; j < kJ; ++j) {
+                        const float f = s0 + u < n_sp && mslot[j] < NS ? f_tab[(s0 + u) * NS + mslot[j]] : 0.f;
+                        msum[j] += batch_x[u][j] * f;
                     }
             }
         } else {
@@ -1172,14 +1203,9 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, const WgCoords& w
             }
         }
         if constexpr (kArrive) {
-            const int c0 = 8 * (4 * wave + lg);
-            if (c0 < rv) {
 #pragma unroll
-                for (int nb = 0; nb < NHB; ++nb) {
-                    *reinterpret_cast<f32x4_t*>(olat + (size_t)(nb * 16 + l16) * ostride + c0) = mrow[kArrive ? nb : 0][0];
-                    *reinterpret_cast<f32x4_t*>(olat + (size_t)(nb * 16 + l16) * ostride + c0 + 4) = mrow[kArrive ? nb : 0][1];
-                }
-            }
+            for (int j = 0; j < kJ; ++j)
+                if (mslot[j] < NS) *reinterpret_cast<f32x4_t*>(olat + (size_t)mslot[j] * ostride + mcol[j]) = msum[j];
         } else {
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {

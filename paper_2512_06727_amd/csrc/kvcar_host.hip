@@ -266,6 +266,9 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     // group then reads its sources' rows for itself - the copies meet in the caches.  A launch that moves a lot is bound by
     // those bytes and keeps up to 32 heads per workgroup.  Measured crossover: between 300 and 440 MB read per launch
     // (TinyLlama shape, 2048 cached tokens: 64 sequences gain a fifth with a group per KV head, 96 sequences lose a fifth).
+    // Many short sequences are the other limit: once there are more (sequence, group) pairs than compute units the
+    // finer groups only queue behind each other (256 sequences of 512 tokens lose a quarter), so the finer form is
+    // taken only while the pairs fit the chip at one workgroup each.
     int fine_cap = 0;                                       // 0: the kernels' capacity
     if (mfma_ok && !mlp_ok && r_all <= 128) {
         if (ctx->tun.group_slots > 0) {
@@ -278,7 +281,8 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
                     n_groups += chunks;
                     bytes += chunks * (size_t)(bh.gd.k.r + bh.gd.v.r) * ctx->row_elem_bytes() * batch * n_ctx;
                 }
-                if (cap_try <= 32 && n_groups <= (size_t)kMaxGroups && bytes <= kFineGroupBytes) { fine_cap = cap_try; break; }
+                if (cap_try <= 32 && n_groups <= (size_t)kMaxGroups && bytes <= kFineGroupBytes &&
+                    n_groups * (size_t)batch <= (size_t)ctx->n_cu) { fine_cap = cap_try; break; }
             }
         }
     }
@@ -378,14 +382,21 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
         if (arrive_ok) {
             // The one-launch forms.  More than half a chip of (sequence, group) pairs: one long-lived workgroup each (a second
             // split costs the whole arrival tail: 36 to 63 sequences of four groups, 0.62-0.72 ms per step against 0.70-0.82).
-            // Fewer: splits fill the chip - one workgroup per compute unit up to a quarter chip of pairs, two beyond; never
-            // more workgroups than are resident at once (512: beyond, launches take half as long again) - but a split keeps
-            // about four workgroup tiles: with less the loop is shorter than the merge of one more partial (TinyLlama at 2048
-            // tokens, 4 sequences: 16 splits 0.49 ms per step, 5 splits 0.41; 32 sequences: 2 splits 0.61, 4 splits 0.58).
+            // Fewer: splits fill the chip, never with more workgroups than are resident at once (512: beyond, launches take
+            // half as long again), and a split keeps about four workgroup tiles: with less the loop is shorter than the merge
+            // of one more partial (TinyLlama at 2048 tokens, 4 sequences: 16 splits 0.49 ms per step, 5 splits 0.41; 32
+            // sequences: 2 splits 0.61, 4 splits 0.58).  One workgroup per compute unit or two: above a quarter chip of pairs
+            // two; below, whichever the measured costs favour - a workgroup alone on its compute unit streams a tile in
+            // about 1.4 us, one of two in about 2.2 us, and the last workgroup spends about 0.17 us per partial it merges
+            // (one sequence of 131072 tokens: 64 splits 48 us per launch, 128 splits 55; 8 sequences of 16384: 8 splits
+            // 39.5 us, 16 splits 37.7).
             const int by_tiles = (wg_tiles + 3) / 4;
+            const int one = std::max(1, std::min({ctx->n_cu / units, by_tiles, kArriveMaxSplits}));
+            const int two = std::max(1, std::min({2 * ctx->n_cu / units, by_tiles, kArriveMaxSplits}));
+            auto cost_us = [&](int n, double tile_us) { return (wg_tiles + n - 1) / n * tile_us + 0.17 * n; };
             if (2 * units > ctx->n_cu) splits = 1;
-            else if (4 * units > ctx->n_cu) splits = std::min(2 * ctx->n_cu / units, by_tiles);
-            else splits = std::min(ctx->n_cu / units, by_tiles);
+            else if (4 * units > ctx->n_cu) splits = two;
+            else splits = cost_us(two, 2.2) < cost_us(one, 1.4) ? two : one;
         } else {
             // separate kernels: about one workgroup per compute unit for the matrix-core kernels, two for the plain ones
             splits = plan.mfma ? std::max(1, ctx->n_cu / units) : (ctx->n_cu * 2 + units - 1) / units;

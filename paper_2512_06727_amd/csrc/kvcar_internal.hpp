@@ -20,7 +20,7 @@ constexpr int kMaxKvHeads = 64;     // bound on n_kv_heads (head lists live in k
 constexpr int kGenericTile = 16;    // tokens per tile of the plain-ALU attention kernel
 constexpr int kGenericAcc = 48;     // accumulators per thread of the plain-ALU attention kernel
 constexpr int kMaxRow = 384;        // widest latent / hidden row any kernel handles
-constexpr int kArriveMaxSplits = 64;   // most splits the one-launch form's last workgroup merges
+constexpr int kArriveMaxSplits = 128;  // most splits the one-launch form's last workgroup merges
 constexpr int kArrivePitch = 32;       // 8-byte words between two arrival counters: 256 bytes apart, so that the atomic
                                        // operations of different (sequence, group) pairs spread over the memory channels
 constexpr float kLog2e = 1.4426950408889634f;
