@@ -959,7 +959,8 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, const WgCoords& w
     // Arrival form, last workgroup.  The splits' partials are read as what they are in memory, runs of consecutive bytes:
     // 16-byte chunk i of a partial's latent sums (i = t, t + 256, ..: head slot i / (rv / 4), columns 4 (i % (rv / 4)) ..)
     // goes to thread t, so a wave's load covers whole cache lines (loads that leave the chip's caches are paid per line
-    // touched: a layout that follows the accumulator's lanes takes three times as long).  kAB splits per memory round trip.
+    // touched: a layout that follows the accumulator's lanes takes three times as long).  kAB splits per memory round trip:
+    // more do not help, the merge then runs at what one compute unit reads (about 50 GB/s).
     constexpr int NS = NHB * 16;                          // head slots of a partial
     constexpr int kRowChunks = kArrive ? RMAX / 4 : 1;    // 16-byte chunks of a slot's latent sums (exact shapes: rv = RMAX)
     constexpr int kJ = kArrive ? (NS * kRowChunks + 64 * NW - 1) / (64 * NW) : 1;      // chunks per thread
@@ -1042,16 +1043,21 @@ __device__ __forceinline__ void attend_body(KArgs p, KGroup g, const WgCoords& w
             if (sp < n_sp) ml_tab[e] = slot < g->n_slots ? ml[k] : u32x2_t{__float_as_uint(-INFINITY), 0u};
         }
         __syncthreads();
+        // two passes over the table, the maximum and then the sum: neither carries more than one operation from a split to
+        // the next (the running form, which rescales the sum at every split, takes 80 ns per split)
 #pragma unroll
         for (int nb = 0; nb < NHB; ++nb) { m_all[nb] = -INFINITY; l_all[nb] = 0.f; }
+#pragma unroll 8
+        for (int sp = 0; sp < n_sp; ++sp)
+#pragma unroll
+            for (int nb = 0; nb < NHB; ++nb) m_all[nb] = fmaxf(m_all[nb], __uint_as_float(ml_tab[sp * NS + nb * 16 + l16][0]));
+#pragma unroll 8
         for (int sp = 0; sp < n_sp; ++sp)
 #pragma unroll
             for (int nb = 0; nb < NHB; ++nb) {
                 const u32x2_t e = ml_tab[sp * NS + nb * 16 + l16];
                 const float ms = __uint_as_float(e[0]), ls = __uint_as_float(e[1]);
-                const float Mn = fmaxf(m_all[nb], ms);
-                l_all[nb] = (m_all[nb] == -INFINITY ? 0.f : l_all[nb] * exp2f(m_all[nb] - Mn)) + (ms == -INFINITY ? 0.f : ls * exp2f(ms - Mn));
-                m_all[nb] = Mn;
+                l_all[nb] += ms == -INFINITY ? 0.f : ls * exp2f(ms - m_all[nb]);
             }
     }
     if constexpr (kFused || kArrive) {
