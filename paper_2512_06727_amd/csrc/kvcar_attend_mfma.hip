@@ -61,6 +61,14 @@ __global__ __launch_bounds__(512, 1) void attend_mfma_r128_w8_kernel(AttendParam
     const WgCoords wc = wg_coords(p);
     KGroup g = &p->g[wc.z];
     constexpr size_t wl = Geo<128>::kWaveLds;
+    if (p->fused == 5) {                      // several splits in one launch (the last workgroup merges), eight waves
+        switch (g->k.r * 4 + (g->slots_pad >> 4)) {
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, false, 8, true, true>(p, g, wc, lds_raw, wl); return;
+            KVCAR_EXACT_SHAPES(X)
+#undef X
+            default: return;
+        }
+    }
     switch (g->k.r * 4 + (g->slots_pad >> 4)) {
 #define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, false, 8>(p, g, wc, lds_raw, wl); return;
         KVCAR_EXACT_SHAPES(X)
@@ -110,7 +118,7 @@ hipError_t launch_attend_mfma(const AttendParams& p, int dtype, hipStream_t stre
     if (p.fused != 0)
         for (int i = 0; i < p.n_groups; ++i)
             if (p.g[i].k.r != p.g[i].v.r || !exact_shape(p.g[i].k.r, p.g[i].slots_pad / 16)) return hipErrorNotSupported;
-    if (rmax <= 128 && nhb <= 2 && p.fused == 2) {
+    if (rmax <= 128 && nhb <= 2 && (p.fused == 2 || p.fused == 5)) {
         // eight waves: staging regions + swapped query operands, or the epilogue's exchange area (m, l of
         // eight waves) + latent sums + one decoder slice
         const size_t epi = 2048 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);

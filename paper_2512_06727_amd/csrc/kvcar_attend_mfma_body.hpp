@@ -297,7 +297,7 @@ __device__ __forceinline__ WgCoords wg_coords(KArgs p) {
 
 template <typename E, typename D, bool kFused, bool kI8 = false, int NW = kWaves, bool kPrologue = kFused, bool kArrive = false>
 __device__ __forceinline__ void attend_body(KArgs p, KGroup g, const WgCoords& wc, char* lds_raw, size_t wave_lds) {
-    static_assert(!kArrive || (kPrologue && !kFused && D::kExact && NW == kWaves), "the arrival form is a split form of the exact shapes");
+    static_assert(!kArrive || (kPrologue && !kFused && D::kExact && (NW == kWaves || NW == 2 * kWaves)), "the arrival form is a split form of the exact shapes");
     constexpr int RMAX = D::RMAX, NHB = D::NHB;
     using G = Geo<RMAX>;
     using ML = typename std::conditional<kI8, F16, E>::type;    // element type of the products in the loop

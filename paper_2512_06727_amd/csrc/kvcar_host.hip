@@ -131,6 +131,7 @@ struct Plan {
     bool fused = false;       // one kernel does prologue, attention and epilogue (single split, exact shapes)
     bool prologue = false;    // several splits: the attention kernel computes the absorbed queries itself
     bool arrive = false;      // ... and its last workgroup per (sequence, group) merges the splits and decodes: one launch
+    bool arrive_w8 = false;   // ... with eight waves per workgroup
     int n_splits = 1;
     int qt_stride = 0;        // elements per sequence
     int part_stride = 0;      // floats per (sequence, split)
@@ -199,6 +200,16 @@ int head_column(const kvcar_ctx* ctx, int src, int which, int g) {
 
 constexpr size_t kLdsBudget = 150 * 1024;
 constexpr size_t kFineGroupBytes = 320u << 20;     // bytes a launch may read with groups made as small as the maps allow
+
+// One-launch split form: whether its workgroups run with eight waves - 16-bit rows, every workgroup with a compute unit to
+// itself, and the eight waves' 256-token tiles make the longest split at most an eighth longer than 128-token tiles would
+// (2049 tokens in 4 splits: 3 tiles of 256 against 5 of 128 - 16 sequences, 0.51 ms per step against 0.48).
+bool eight_waves_fit(const kvcar_ctx* ctx, const Plan& plan, int batch, int n_groups, int n_ctx, int splits) {
+    if (plan.i8 || ctx->tun.wg_waves == 4) return false;
+    if (ctx->tun.wg_waves == 8) return true;
+    const auto longest_split = [&](int tile_tokens) { return ((n_ctx + tile_tokens - 1) / tile_tokens + splits - 1) / splits * tile_tokens; };
+    return (long long)batch * n_groups * splits <= ctx->n_cu && 8 * longest_split(256) <= 9 * longest_split(128);
+}
 
 int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan) {
     const kvcar_config& c = ctx->cfg;
@@ -385,18 +396,23 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
             // Fewer: splits fill the chip, never with more workgroups than are resident at once (512: beyond, launches take
             // half as long again), and a split keeps about four workgroup tiles: with less the loop is shorter than the merge
             // of one more partial (TinyLlama at 2048 tokens, 4 sequences: 16 splits 0.49 ms per step, 5 splits 0.41; 32
-            // sequences: 2 splits 0.61, 4 splits 0.58).  One workgroup per compute unit or two: above a quarter chip of pairs
-            // two; below, whichever the measured costs favour - a workgroup alone on its compute unit streams a tile in
-            // about 1.4 us, one of two in about 2.2 us, and the last workgroup spends about 0.17 us per partial it merges
-            // (one sequence of 131072 tokens: 64 splits 48 us per launch, 128 splits 55; 8 sequences of 16384: 8 splits
-            // 39.5 us, 16 splits 37.7).
+            // sequences: 2 splits 0.61, 4 splits 0.58).  One workgroup per compute unit or two: whichever the measured costs
+            // favour - a four-wave workgroup alone on its compute unit streams a 128-token tile in about 1.4 us, one of two
+            // in about 2.2 us, and the last workgroup spends about 0.17 us per partial it merges (one sequence of 131072
+            // tokens: 64 splits 48 us per launch, 128 splits 55).  Where the launch is small enough to be bound by latency
+            // (the same limit as for the finer groups; measured: 270 MB yes, 335 MB no), a workgroup alone on its compute
+            // unit runs with eight waves and takes about 1.1 us per 128 tokens: then half as many splits as two four-wave
+            // workgroups per compute unit would take win by 3-9 % (32 sequences of 2048 tokens: 2 splits 26.0 us, 4 splits
+            // of four waves 26.9; 4 of 32768: 35.9 against 39.4; 4 of 131072, 335 MB: 97 against 90).
             const int by_tiles = (wg_tiles + 3) / 4;
             const int one = std::max(1, std::min({ctx->n_cu / units, by_tiles, kArriveMaxSplits}));
             const int two = std::max(1, std::min({2 * ctx->n_cu / units, by_tiles, kArriveMaxSplits}));
+            size_t launch_bytes = 0;
+            for (const GroupDesc& gd : plan.groups) launch_bytes += (size_t)(gd.k.r + gd.v.r) * ctx->row_elem_bytes() * batch * n_ctx;
+            const bool one_w8 = eight_waves_fit(ctx, plan, batch, n_groups, n_ctx, one) && launch_bytes <= kFineGroupBytes;
             auto cost_us = [&](int n, double tile_us) { return (wg_tiles + n - 1) / n * tile_us + 0.17 * n; };
             if (2 * units > ctx->n_cu) splits = 1;
-            else if (4 * units > ctx->n_cu) splits = two;
-            else splits = cost_us(two, 2.2) < cost_us(one, 1.4) ? two : one;
+            else splits = cost_us(two, 2.2) < cost_us(one, one_w8 ? 1.1 : 1.4) ? two : one;
         } else {
             // separate kernels: about one workgroup per compute unit for the matrix-core kernels, two for the plain ones
             splits = plan.mfma ? std::max(1, ctx->n_cu / units) : (ctx->n_cu * 2 + units - 1) / units;
@@ -406,6 +422,7 @@ int build_plan(const kvcar_ctx* ctx, int layer, int batch, int n_ctx, Plan& plan
     plan.n_splits = splits;
     // with several splits the same prologue and epilogue run in the one-launch form whose last workgroup merges
     plan.arrive = arrive_ok && splits > 1 && splits <= kArriveMaxSplits;
+    plan.arrive_w8 = plan.arrive && eight_waves_fit(ctx, plan, batch, n_groups, n_ctx, splits);
     plan.fused = plan.fused && splits == 1;
     plan.qt_bytes = align_up((size_t)batch * qt * (plan.mfma && !plan.i8 ? 2 : 4), 256);
     plan.part_bytes = align_up((size_t)batch * splits * part * sizeof(float), 256);
@@ -827,7 +844,8 @@ int decode_impl(kvcar_ctx* ctx, int layer, const void* q, void* out, int batch, 
             p.epoch = next_epoch();
         }
         const bool one_launch = plan.fused || plan.arrive;
-        p.fused = plan.fused ? (w8 ? 2 : 1) : plan.arrive ? 4 : plan.prologue ? 3 : 0;
+        // the one-launch split form likewise: 4 = four waves, 5 = eight
+        p.fused = plan.fused ? (w8 ? 2 : 1) : plan.arrive ? (plan.arrive_w8 ? 5 : 4) : plan.prologue ? 3 : 0;
         const bool proj = plan.mfma && proj_mfma_supported(p, c.dtype);
         hipError_t e = hipSuccess;
         // append-and-attend (with_encode): the step's encoder launch and the projection of the absorbed queries are

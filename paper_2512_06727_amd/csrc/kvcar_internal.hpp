@@ -106,8 +106,9 @@ struct AttendParams {
     int tile_order;       // MFMA kernel: 0 = contiguous token range per split, 1 = tiles dealt round-robin
     int fused;            // MFMA kernel: 1 = absorbed queries and output epilogue computed inside (single split); 2 = the
                           // eight-wave variant of that; 3 = several splits, absorbed queries computed inside, partials to the
-                          // merge kernel; 4 = several splits, the last workgroup to arrive merges and decodes (one launch)
-    unsigned long long* arrive;   // fused == 4: arrival counter of (sequence b, group z of this launch) at [(b * arrive_stride + z) * kArrivePitch]:
+                          // merge kernel; 4 = several splits, the last workgroup to arrive merges and decodes (one launch);
+                          // 5 = the eight-wave variant of that
+    unsigned long long* arrive;   // fused == 4, 5: arrival counter of (sequence b, group z of this launch) at [(b * arrive_stride + z) * kArrivePitch]:
     int arrive_stride;            //   {tag : 32, count : 32}; valid only while the tag equals `epoch`
     unsigned epoch;               //   tag of this launch (never 0)
     int append;                   // 1 = append-and-attend: the new token (position n_ctx - 1 of every sequence) is encoded in

@@ -403,7 +403,7 @@ def test_small_launches_get_a_group_per_kv_head():
 
     ctx = model(32, 4, 256, 8300)
     small, big = ctx.describe_plan(0, 32, 2049), ctx.describe_plan(0, 256, 8193)
-    assert (small.n_groups, small.n_launches, small.fused) == (4, 1, 2) and small.n_splits == 4       # 4 x 32 (sequence, group) pairs: two workgroups per compute unit
+    assert (small.n_groups, small.n_launches, small.fused) == (4, 1, 2) and small.n_splits == 2       # 4 x 32 (sequence, group) pairs: one eight-wave workgroup per compute unit
     assert (big.n_groups, big.n_splits, big.fused) == (1, 1, 1)
     assert small.latent_bytes == 4 * 2 * 128 * 2 * 32 * 2049                 # every group reads the whole rows
     assert ctx.describe_plan(1, 32, 2049).n_groups == 4                      # head 0 from layer 0, three heads of its own: 1 + 3 groups

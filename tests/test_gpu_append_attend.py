@@ -28,6 +28,11 @@ CASES = {
     # one split: the fused kernel, four and eight waves
     "one-split-w4": (C[4].scaled(n_layers=6, batch=2, n_cached=200, n_steps=2), {}, {"n_splits": 1, "wg_waves": 4}, True),
     "one-split-w8": (C[4].scaled(n_layers=6, batch=2, n_cached=200, n_steps=2), {}, {"n_splits": 1, "wg_waves": 8}, True),
+    # several splits in one launch with eight waves per workgroup, against the same with four; five splits of 602 tokens
+    # leave two eight-wave splits without a tile
+    "splits-w8": (C[4].scaled(n_layers=6, batch=2, n_cached=700, n_steps=2), {"with_bias": True}, {"n_splits": 3, "wg_waves": 8}, True),
+    "splits-w4": (C[4].scaled(n_layers=6, batch=2, n_cached=700, n_steps=2), {"with_bias": True}, {"n_splits": 3, "wg_waves": 4}, True),
+    "tinyllama-empty-splits-w8": (C[2].scaled(n_layers=5, batch=3, n_cached=601, n_steps=3), {}, {"n_splits": 5, "wg_waves": 8}, True),
     # head width 128, fp16
     "dh128-f16": (C[2].scaled(n_layers=3, batch=2, n_cached=300, n_steps=2, n_q_heads=16, n_kv_heads=2, d_head=128, latent=64, policy="P2",
                               reuse="odd:1", dtype="f16"), {"with_bias": True}, {}, True),
