@@ -660,7 +660,7 @@ def main():
     ap.add_argument("--capacity-check", action="store_true",
                     help="allocate latent caches for as many tokens as fit in free HBM, run one decode step over them, report")
     ap.add_argument("--capacity-fraction", type=float, default=0.92, help="share of the free device memory the capacity check may take")
-    ap.add_argument("--wg-waves", type=int, default=0, help="fused attention kernel: 0 automatic, 4 or 8 waves per workgroup")
+    ap.add_argument("--wg-waves", type=int, default=0, help="one-launch attention kernels: 0 automatic, 4 or 8 waves per workgroup")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (counter calibration under rocprofv3 --pmc)")
