@@ -154,9 +154,9 @@ typedef struct {
     int tile_order;     /* MFMA attention: 0 = library default, 1 = each split owns a contiguous
                            token range, 2 = 128-token tiles dealt round-robin over the splits    */
     int no_fuse;        /* 1 = always run prologue / attention / epilogue as separate kernels     */
-    int wg_waves;       /* one-launch attention kernels (one split, or several with the last workgroup merging;
-                           16-bit rows for the latter): 0 = automatic (eight waves per workgroup when the
-                           launch has no more workgroups than compute units, else four), 4 or 8      */
+    int wg_waves;       /* one-launch attention kernels (one split, or several with the last workgroup merging):
+                           0 = automatic (eight waves per workgroup when the launch has no more workgroups
+                           than compute units, else four), 4 or 8                                    */
     int no_bulk_encode; /* 1 = prompt-sized encode calls take the general encoder kernel, not the
                            streaming one (linear encoders, 8192 tokens or more)                      */
     int no_arrive;      /* 1 = with several splits the partials always go to a separate merge kernel; default: where the

@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256, 2) void attend_i8_mfma_r128_kernel(AttendParam
     }
 }
 
-// Eight waves per workgroup (fused, single split): for launches with no more workgroups than compute units.
+// Eight waves per workgroup (the one-launch forms): for launches with no more workgroups than compute units.
 template <typename E>
 __global__ __launch_bounds__(512, 1) void attend_i8_mfma_r128_w8_kernel(AttendParams p_by_value) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
@@ -56,6 +56,14 @@ __global__ __launch_bounds__(512, 1) void attend_i8_mfma_r128_w8_kernel(AttendPa
     KArgs p = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
     const WgCoords wc = wg_coords(p);
     KGroup g = &p->g[wc.z];
+    if (p->fused == 5) {                      // several splits in one launch (the last workgroup merges), eight waves
+        switch (g->k.r * 4 + (g->slots_pad >> 4)) {
+#define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, false, true, 8, true, true>(p, g, wc, lds_raw, kI8WaveLds); return;
+            KVCAR_EXACT_SHAPES(X)
+#undef X
+            default: return;
+        }
+    }
     switch (g->k.r * 4 + (g->slots_pad >> 4)) {
 #define X(R, N) case R * 4 + N: attend_body<E, DimsExact<R, N>, true, true, 8>(p, g, wc, lds_raw, kI8WaveLds); return;
         KVCAR_EXACT_SHAPES(X)
@@ -79,7 +87,7 @@ bool attend_i8_mfma_supported(const AttendParams& p, int dtype) {
 hipError_t launch_attend_i8_mfma(const AttendParams& p, int dtype, hipStream_t stream) {
     static AttrFlag attr[2] = {false, false}, attr8[2] = {false, false};
     if (!attend_i8_mfma_supported(p, dtype)) return hipErrorNotSupported;
-    if (p.fused == 2) {
+    if (p.fused == 2 || p.fused == 5) {
         const size_t epi8 = 2048 + 32 * 132 * 4 + 128 * (2 * (size_t)p.d_head + 32);
         size_t lds8 = 8 * kI8WaveLds + 2 * 4 * 64 * 16;              // + swapped query operands (the new token's codes of append-and-attend sit in the waves' spare bytes)
         lds8 = lds8 > epi8 ? lds8 : epi8;

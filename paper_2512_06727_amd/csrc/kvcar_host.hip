@@ -201,11 +201,11 @@ int head_column(const kvcar_ctx* ctx, int src, int which, int g) {
 constexpr size_t kLdsBudget = 150 * 1024;
 constexpr size_t kFineGroupBytes = 320u << 20;     // bytes a launch may read with groups made as small as the maps allow
 
-// One-launch split form: whether its workgroups run with eight waves - 16-bit rows, every workgroup with a compute unit to
+// One-launch split form: whether its workgroups run with eight waves - every workgroup with a compute unit to
 // itself, and the eight waves' 256-token tiles make the longest split at most an eighth longer than 128-token tiles would
 // (2049 tokens in 4 splits: 3 tiles of 256 against 5 of 128 - 16 sequences, 0.51 ms per step against 0.48).
 bool eight_waves_fit(const kvcar_ctx* ctx, const Plan& plan, int batch, int n_groups, int n_ctx, int splits) {
-    if (plan.i8 || ctx->tun.wg_waves == 4) return false;
+    if (ctx->tun.wg_waves == 4) return false;
     if (ctx->tun.wg_waves == 8) return true;
     const auto longest_split = [&](int tile_tokens) { return ((n_ctx + tile_tokens - 1) / tile_tokens + splits - 1) / splits * tile_tokens; };
     return (long long)batch * n_groups * splits <= ctx->n_cu && 8 * longest_split(256) <= 9 * longest_split(128);

@@ -46,6 +46,8 @@ CASES = {
     "int8-one-split-w4": (C[4].scaled(n_layers=6, batch=2, n_cached=200, n_steps=2), {"latent_format": "int8", "with_bias": True},
                           {"n_splits": 1, "wg_waves": 4}, True),
     "int8-one-split-w8": (C[4].scaled(n_layers=6, batch=2, n_cached=200, n_steps=2), {"latent_format": "int8"}, {"n_splits": 1, "wg_waves": 8}, True),
+    "int8-splits-w8": (C[4].scaled(n_layers=6, batch=2, n_cached=700, n_steps=2), {"latent_format": "int8", "with_bias": True},
+                       {"n_splits": 3, "wg_waves": 8}, True),
     "int8-bernoulli-splits": (C[4].scaled(n_layers=8, batch=2, n_cached=333, n_steps=2), {"latent_format": "int8", "with_bias": True}, {}, True),
     "int8-plain-alu": (C[2].scaled(n_layers=3, batch=2, n_cached=100, n_steps=2), {"latent_format": "int8"}, {"force_generic": True}, False),
     "f32": (C[0].scaled(n_layers=2, batch=2, n_cached=60, n_steps=2, reuse="odd:5"), {"with_bias": True}, {}, False),

@@ -188,7 +188,7 @@ def assert_within(got, want, dtype, label):
     assert err.max() <= REL_TOL[dtype] * np.abs(want).max(), f"{label}: max err {err.max():.3e} vs max |ref| {np.abs(want).max():.3e}"
 
 
-MFMA_FORMS = [{"n_splits": 1, "wg_waves": 4}, {"n_splits": 1, "wg_waves": 8}, {"n_splits": 3}]
+MFMA_FORMS = [{"n_splits": 1, "wg_waves": 4}, {"n_splits": 1, "wg_waves": 8}, {"n_splits": 3}, {"n_splits": 3, "wg_waves": 8}]
 
 
 @pytest.mark.parametrize("offsets,zp_decade", [((0.0, 0.0), 1e2), ((8.0, 0.0), 1e3), ((96.0, 2.0), 1e4), ((0.0, 1024.0), 1e5),

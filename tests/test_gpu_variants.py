@@ -25,6 +25,7 @@ CASES = {
     # leave two of them without a tile
     "c4-small-bf16-3splits-w8": (C[4].scaled(n_layers=5, batch=2, n_cached=700, n_steps=1), {"with_bias": True}, {"n_splits": 3, "wg_waves": 8}),
     "c2-small-bf16-5splits-w8": (C[2].scaled(n_layers=4, batch=3, n_cached=600, n_steps=1), {}, {"n_splits": 5, "wg_waves": 8}),
+    "c2-small-int8-3splits-w8": (C[2].scaled(n_layers=4, batch=3, n_cached=600, n_steps=1), {"latent_format": "int8"}, {"n_splits": 3, "wg_waves": 8}),
     "c2-small-int8-1split": (C[2].scaled(n_layers=4, batch=3, n_cached=200, n_steps=1), {"latent_format": "int8"}, {"n_splits": 1}),
     "c3-small-mlp": (C[3].scaled(n_layers=2, batch=3, n_cached=90, n_steps=1), {}, {}),
     "c2-small-int8": (C[2].scaled(n_layers=4, batch=5, n_cached=300, n_steps=1), {"latent_format": "int8"}, {}),
